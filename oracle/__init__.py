@@ -1,0 +1,169 @@
+"""Python face of the CPU oracle (oracle/dgnn_oracle.c).
+
+TEST INFRASTRUCTURE ONLY.  Importers are the tests, the smoke check and the CPU-baseline leg
+of the benchmark; the product package never imports this and this never imports the product.
+Arrays go in and out as numpy; real numbers are float64 throughout.
+
+Passages followed: reconstruction from a graph difference -- Section "Graph-difference Based
+Input Transfer"; normalised adjacency -- Eqn (1); GCN operation -- Eqn (2); M-transform and
+its matrix M -- Section "TM-GCN".
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "dgnn_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain C, OpenMP over independent rows only)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+                               "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = None
+_i32p = ctypes.POINTER(ctypes.c_int32)
+_i64p = ctypes.POINTER(ctypes.c_int64)
+_f64p = ctypes.POINTER(ctypes.c_double)
+_i64 = ctypes.c_int64
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        lib.oracle_csr_from_edges.restype = _i64
+        lib.oracle_csr_from_edges.argtypes = [_i64, _i32p, _i32p, _i64, _i32p, _i32p, _i64]
+        lib.oracle_delta_apply.restype = _i64
+        lib.oracle_delta_apply.argtypes = [_i64, _i32p, _i32p, _i32p, _i32p, _i64, _i32p, _i32p, _i64,
+                                           _i32p, _i32p, _i64]
+        lib.oracle_gcn_values.restype = None
+        lib.oracle_gcn_values.argtypes = [_i64, _i32p, _i32p, _f64p]
+        lib.oracle_xw.restype = None
+        lib.oracle_xw.argtypes = [_i64, _i64, _i64, _f64p, _f64p, _f64p]
+        lib.oracle_spmm.restype = None
+        lib.oracle_spmm.argtypes = [_i64, _i32p, _i32p, _f64p, _f64p, _i64, ctypes.c_int, _i64p, _i64, _f64p]
+        lib.oracle_m_matrix.restype = None
+        lib.oracle_m_matrix.argtypes = [_i64, _i64, _f64p]
+        lib.oracle_mproduct.restype = None
+        lib.oracle_mproduct.argtypes = [_i64, _i64, _f64p, _f64p, _f64p]
+        lib.oracle_num_threads.restype = ctypes.c_int
+        lib.oracle_set_threads.argtypes = [ctypes.c_int]
+        _lib = lib
+    return _lib
+
+
+def _a(x, dt):
+    return np.ascontiguousarray(np.asarray(x), dtype=dt)
+
+
+def _p(a, ptype):
+    return a.ctypes.data_as(ptype)
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def set_threads(t: int) -> None:
+    _load().oracle_set_threads(int(t))
+
+
+def csr_from_edges(n: int, row, col) -> Tuple[np.ndarray, np.ndarray]:
+    """Edge list (any order, repeats allowed) -> canonical CSR (rowptr int32[n+1], colidx int32)."""
+    row, col = _a(row, np.int32), _a(col, np.int32)
+    m = row.size
+    rowptr = np.zeros(n + 1, np.int32)
+    colidx = np.zeros(max(m, 1), np.int32)
+    rc = _load().oracle_csr_from_edges(n, _p(row, _i32p), _p(col, _i32p), m, _p(rowptr, _i32p),
+                                       _p(colidx, _i32p), colidx.size)
+    if rc < 0:
+        raise ValueError(f"oracle_csr_from_edges failed: {rc}")
+    return rowptr, colidx[:rc].copy()
+
+
+def delta_apply(n: int, rowptr, colidx, add_row, add_col, del_row, del_col) -> Tuple[np.ndarray, np.ndarray]:
+    """E_{i+1} = (E_i minus deleted edges) union added edges, returned as canonical CSR."""
+    rowptr, colidx = _a(rowptr, np.int32), _a(colidx, np.int32)
+    ar, ac, dr, dc = (_a(x, np.int32) for x in (add_row, add_col, del_row, del_col))
+    cap = int(rowptr[n]) + ar.size + 1
+    rp = np.zeros(n + 1, np.int32)
+    ci = np.zeros(cap, np.int32)
+    rc = _load().oracle_delta_apply(n, _p(rowptr, _i32p), _p(colidx, _i32p), _p(ar, _i32p), _p(ac, _i32p),
+                                    ar.size, _p(dr, _i32p), _p(dc, _i32p), dr.size, _p(rp, _i32p),
+                                    _p(ci, _i32p), cap)
+    if rc < 0:
+        raise ValueError(f"oracle_delta_apply failed: {rc}")
+    return rp, ci[:rc].copy()
+
+
+def gcn_values(rowptr, colidx) -> np.ndarray:
+    """Per stored entry (u,v) of A+I: 1/sqrt((1+deg_u)(1+deg_v)), Eqn (1)."""
+    rowptr, colidx = _a(rowptr, np.int32), _a(colidx, np.int32)
+    n = rowptr.size - 1
+    val = np.zeros(max(colidx.size, 1), np.float64)
+    _load().oracle_gcn_values(n, _p(rowptr, _i32p), _p(colidx, _i32p), _p(val, _f64p))
+    return val[:colidx.size]
+
+
+def xw(x, w) -> np.ndarray:
+    x, w = _a(x, np.float64), _a(w, np.float64)
+    n, fi = x.shape
+    fo = w.shape[1]
+    assert w.shape[0] == fi
+    h = np.zeros((n, fo), np.float64)
+    _load().oracle_xw(n, fi, fo, _p(x, _f64p), _p(w, _f64p), _p(h, _f64p))
+    return h
+
+
+def spmm(rowptr, colidx, h, relu: bool = False, rows=None, val: Optional[np.ndarray] = None) -> np.ndarray:
+    """sigma?(A~ H).  `rows` (int64 indices) restricts the output to those rows, in that order."""
+    rowptr, colidx, h = _a(rowptr, np.int32), _a(colidx, np.int32), _a(h, np.float64)
+    n = rowptr.size - 1
+    f = h.shape[1]
+    assert h.shape[0] == n
+    if val is None:
+        val = gcn_values(rowptr, colidx)
+    val = _a(val, np.float64)
+    if rows is None:
+        z = np.zeros((n, f), np.float64)
+        rp, nr = None, 0
+    else:
+        rows = _a(rows, np.int64)
+        z = np.zeros((rows.size, f), np.float64)
+        rp, nr = _p(rows, _i64p), rows.size
+    _load().oracle_spmm(n, _p(rowptr, _i32p), _p(colidx, _i32p), _p(val, _f64p), _p(h, _f64p), f,
+                        int(bool(relu)), rp, nr, _p(z, _f64p))
+    return z
+
+
+def m_matrix(T: int, w: int) -> np.ndarray:
+    """Dense T x T matrix of the M-transform: M[t][k] = 1/min(w,t) on max(1,t-w+1) <= k <= t (1-based)."""
+    M = np.zeros((T, T), np.float64)
+    _load().oracle_m_matrix(T, w, _p(M, _f64p))
+    return M
+
+
+def mproduct(z, M) -> np.ndarray:
+    """Y = Z x_1 M for Z of shape [T, ...]; M is a dense T x T matrix."""
+    z, M = _a(z, np.float64), _a(M, np.float64)
+    T = z.shape[0]
+    assert M.shape == (T, T)
+    frame = int(np.prod(z.shape[1:]))
+    y = np.zeros_like(z)
+    _load().oracle_mproduct(T, frame, _p(M, _f64p), _p(z, _f64p), _p(y, _f64p))
+    return y
+
+
+def gcn_layer(rowptr, colidx, x, w, relu: bool = False, rows=None) -> np.ndarray:
+    """sigma?(A~ (X W)), Eqn (2)."""
+    return spmm(rowptr, colidx, xw(x, w), relu=relu, rows=rows)
