@@ -1,0 +1,167 @@
+/*
+ * dgnn.h -- C boundary of the MI355X (gfx950) dynamic-GNN hot path.
+ *
+ * The path, for one GPU's block of timesteps of a discrete-time dynamic graph G_1..G_T over N
+ * vertices (Section "Discrete Time Dynamic Graphs"):
+ *
+ *   A_1 arrives whole; for t > 1 only the graph difference arrives and A_t is rebuilt on the
+ *   GPU from A_{t-1}                                   dgnn_delta_h2d, dgnn_delta_rebuild
+ *   H_t = X_t W                                        dgnn_feature_transform
+ *   Z_t = sigma(A~_t H_t)                              dgnn_spmm
+ *   Y   = Z x_1 M  (TM-GCN's temporal mixing)          dgnn_mproduct
+ *
+ * Conventions shared by every call
+ *   - A snapshot is stored as CSR of A_t + I: int32 rowptr[n+1], int32 colidx[nnz], columns
+ *     strictly ascending inside a row, the diagonal entry present in every row.  With the
+ *     diagonal stored, the 1 + deg_u of Eqn (1) is the length of row u, and
+ *     dinv[u] = (1 + deg_u)^(-1/2) is all that is needed for the values of A~ (the snapshots
+ *     are unweighted, so no value array exists).
+ *   - Dense matrices are row-major with leading dimension equal to the feature width; tensors
+ *     over time are [T][n][f] contiguous.  Feature widths must be one of 16, 32, 64, 128.
+ *   - Unless a parameter is marked HOST, every pointer is a DEVICE pointer, 16-byte aligned for
+ *     feature matrices, owned by the caller, and must stay valid until the work enqueued on
+ *     `stream` has run.  `stream` is a hipStream_t passed as void* (NULL = the default
+ *     stream).  Calls only enqueue work and return; nothing is allocated, nothing is kept
+ *     between calls, nothing is printed.
+ *   - Return value: DGNN_OK (0) or a negative dgnn_status.  Argument errors are detected on
+ *     the host before anything is enqueued.
+ *   - All indices and counts that live in device arrays are int32; n and nnz must be below 2^31.
+ */
+#ifndef DGNN_H
+#define DGNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DGNN_OK = 0,
+    DGNN_ERR_NULL = -1,      /* a required pointer is NULL                                   */
+    DGNN_ERR_SHAPE = -2,     /* non-positive size, unsupported feature width / window / dtype */
+    DGNN_ERR_CAPACITY = -3,  /* output buffer or workspace too small                          */
+    DGNN_ERR_OVERFLOW = -4,  /* n or nnz does not fit in int32                                */
+    DGNN_ERR_ALIAS = -5,     /* output aliases an input where that is not allowed             */
+    DGNN_ERR_HIP = -6,       /* the HIP runtime refused a launch or copy                      */
+    DGNN_ERR_ALIGN = -7      /* a feature pointer is not 16-byte aligned                      */
+} dgnn_status;
+
+/* Storage type of feature matrices; accumulation is always fp32.  bf16 stores round to nearest even. */
+typedef enum { DGNN_F32 = 0, DGNN_BF16 = 1 } dgnn_dtype;
+
+/* Flags of dgnn_delta_rebuild. */
+#define DGNN_VALIDATE 1u     /* check the difference lists against A_prev on the device */
+
+/* Codes written to *d_status by dgnn_delta_rebuild (0 = nothing found; the smallest code found wins). */
+#define DGNN_BAD_INDEX_RANGE 1   /* a row or column index outside [0, n)                         */
+#define DGNN_BAD_DELTA_ORDER 2   /* a list is not strictly ascending by (row, col)               */
+#define DGNN_BAD_DIAGONAL 3      /* a list names a diagonal entry                                */
+#define DGNN_BAD_DEL_ABSENT 4    /* a deleted edge is not in A_prev                              */
+#define DGNN_BAD_ADD_PRESENT 5   /* an added edge is already in A_prev                           */
+#define DGNN_BAD_EMPTY_ROW 6     /* A_prev has a row without entries (the diagonal is missing)   */
+
+/* Flags of dgnn_spmm. */
+#define DGNN_RELU 1u             /* apply sigma = ReLU to the aggregated rows (Eqn (2)) */
+
+/* Text for a dgnn_status value; never NULL; static storage. */
+const char *dgnn_strerror(int code);
+
+/*
+ * dinv[u] = (rowptr[u+1] - rowptr[u])^(-1/2), u in [0, n): the diagonal of D^(-1/2) in Eqn (1)
+ * for a snapshot that did not come out of dgnn_delta_rebuild (the first one of a block).
+ */
+int dgnn_csr_dinv(int64_t n, const int32_t *rowptr, float *dinv, void *stream);
+
+/*
+ * Graph-difference transfer (Section "Graph-difference Based Input Transfer"): instead of the
+ * whole snapshot, only the indices of the edges that disappear and of the edges that appear
+ * are shipped from the host.  Copies the four index lists from PINNED HOST memory (h_*) to
+ * device staging buffers (d_*), n_add resp. n_del int32 each, asynchronously on `stream`.
+ * Zero-length lists are allowed (their pointers may then be NULL).
+ * Bytes moved: 8 * (n_add + n_del), against 4 * (nnz + n + 1) for a whole CSR snapshot.
+ */
+int dgnn_delta_h2d(const int32_t *h_add_row, const int32_t *h_add_col, int64_t n_add,
+                   const int32_t *h_del_row, const int32_t *h_del_col, int64_t n_del,
+                   int32_t *d_add_row, int32_t *d_add_col, int32_t *d_del_row, int32_t *d_del_col,
+                   void *stream);
+
+/* Workspace size of dgnn_delta_rebuild in bytes (HOST out-parameter). */
+int dgnn_delta_rebuild_workspace(int64_t n, int64_t nnz_prev, int64_t n_add, int64_t n_del, size_t *bytes);
+
+/*
+ * On-GPU reconstruction of a snapshot (same section): with A_prev on the device,
+ *     common = A_prev minus the deleted edges,   A_next = common plus the added edges,
+ * both as CSR of A + I in the canonical form above.  Also emits dinv_next (may be NULL).
+ *
+ *   n                       vertices
+ *   rowptr_prev, colidx_prev, nnz_prev    A_{t-1}; nnz_prev == rowptr_prev[n] (known to the host)
+ *   add_row/add_col, n_add  edges of A_t not in A_{t-1}, sorted by (row, col), no repeats
+ *   del_row/del_col, n_del  edges of A_{t-1} not in A_t, sorted by (row, col), no repeats
+ *                           (the two lists are disjoint from each other by construction and
+ *                           never name the diagonal)
+ *   rowptr_next [n+1], colidx_next [cap_next]   output; cap_next >= nnz_prev + n_add - n_del
+ *   nnz_next                HOST out-parameter (may be NULL): nnz_prev + n_add - n_del
+ *   ws, ws_bytes            scratch of at least dgnn_delta_rebuild_workspace() bytes
+ *   flags                   0 or DGNN_VALIDATE
+ *   d_status                device int32 (may be NULL).  Always reset to 0 by the call; under
+ *                           DGNN_VALIDATE receives the smallest DGNN_BAD_* code found.
+ *
+ * Lists that break the preconditions give an unspecified A_next (never an out-of-bounds
+ * access); use DGNN_VALIDATE to find out.  Outputs must not overlap inputs (DGNN_ERR_ALIAS
+ * when the base pointers coincide).  The result is bit-for-bit unique.
+ */
+int dgnn_delta_rebuild(int64_t n,
+                       const int32_t *rowptr_prev, const int32_t *colidx_prev, int64_t nnz_prev,
+                       const int32_t *add_row, const int32_t *add_col, int64_t n_add,
+                       const int32_t *del_row, const int32_t *del_col, int64_t n_del,
+                       int32_t *rowptr_next, int32_t *colidx_next, int64_t cap_next, int64_t *nnz_next,
+                       float *dinv_next,
+                       void *ws, size_t ws_bytes, uint32_t flags, int32_t *d_status, void *stream);
+
+/*
+ * Dense factor of the GCN operation, Eqn (2): H = X W.
+ *   x [n][f_in], w [f_in][f_out], h [n][f_out], all of storage type dt, fp32 accumulation on
+ *   the matrix cores.  W is a per-call argument, so a model that keeps one weight per
+ *   timestep (Section "EvolveGCN") passes W_t.  h must not alias x.
+ */
+int dgnn_feature_transform(const void *x, int64_t n, int32_t f_in, const void *w, int32_t f_out,
+                           void *h, dgnn_dtype dt, void *stream);
+
+/* Workspace size of dgnn_spmm in bytes (HOST out-parameter); depends on n, nnz and f only. */
+int dgnn_spmm_workspace(int64_t n, int64_t nnz, int32_t f, size_t *bytes);
+
+/*
+ * Sparse factor of the GCN operation, Eqn (1) and Eqn (2): Z = sigma?(A~ H),
+ *     Z[u] = dinv[u] * sum over stored (u,v) of dinv[v] * H[v],
+ * i.e. every stored entry of A + I weighs 1/sqrt((1+deg_u)(1+deg_v)).
+ *   rowptr, colidx, nnz     the snapshot (CSR of A + I)
+ *   dinv [n]                from dgnn_delta_rebuild or dgnn_csr_dinv; NULL means all ones
+ *                           (plain A + I, no normalisation)
+ *   h [n][f], z [n][f]      storage type dt; z must not alias h
+ *   flags                   0 or DGNN_RELU
+ *   ws, ws_bytes            scratch of at least dgnn_spmm_workspace() bytes
+ * The result does not depend on scheduling: no floating-point atomics are used.
+ */
+int dgnn_spmm(int64_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *dinv,
+              const void *h, int32_t f, void *z, dgnn_dtype dt, uint32_t flags,
+              void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * M-transform (Section "TM-GCN"): Y = Z x_1 M for the banded lower-triangular M,
+ *     Y_t = sum_{j=0}^{min(w,t)-1} m(t,j) Z_{t-j},   t = 1..T (1-based),
+ *   z, y [T][n][f]          storage type dt; y may be the same pointer as z (in place), and
+ *                           must not overlap it in any other way
+ *   w                       window, 1 <= min(w, T) <= 32
+ *   m_band                  DEVICE float [T][w] with m_band[(t-1)*w + j] = m(t,j), or NULL for
+ *                           the paper's weights m(t,j) = 1/min(w,t); entries with j >= t are
+ *                           ignored
+ */
+int dgnn_mproduct(const void *z, void *y, int64_t T, int64_t n, int32_t f, int32_t w,
+                  const float *m_band, dgnn_dtype dt, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DGNN_H */

@@ -1,0 +1,13 @@
+"""MI355X-native hot path of discrete-time dynamic-GNN training: on-GPU snapshot reconstruction
+from a graph difference, the GCN step A~ (X W), and TM-GCN's M-transform.
+
+Everything is computed by hand-written HIP kernels behind the C boundary declared in
+include/dgnn.h; this package only marshals torch tensors (used for device memory and streams)
+into those calls.  There is no CPU fallback: without the built library the calls raise.
+"""
+from .binding import (  # noqa: F401
+    DgnnError, build_library, library_path, load_library,
+    csr_dinv, delta_h2d, delta_rebuild, delta_rebuild_workspace, feature_transform,
+    spmm, spmm_workspace, mproduct, strerror,
+    DGNN_VALIDATE, DGNN_RELU, DGNN_F32, DGNN_BF16,
+)

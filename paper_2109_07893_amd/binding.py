@@ -1,0 +1,210 @@
+"""ctypes binding of libdgnn (include/dgnn.h).  Same names as the C entry points, argument
+marshalling only: tensors become device pointers, the current torch stream becomes the
+hipStream_t, and a non-zero status becomes a DgnnError."""
+from __future__ import annotations
+
+import ctypes
+import glob
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_ROOT = os.path.dirname(_HERE)
+_CSRC = os.path.join(_HERE, "csrc")
+_LIB_PATH = os.path.join(_CSRC, "libdgnn.so")
+
+DGNN_F32, DGNN_BF16 = 0, 1
+DGNN_VALIDATE = 1
+DGNN_RELU = 1
+
+EXPORTS = (
+    "dgnn_strerror", "dgnn_csr_dinv", "dgnn_delta_h2d", "dgnn_delta_rebuild_workspace",
+    "dgnn_delta_rebuild", "dgnn_feature_transform", "dgnn_spmm_workspace", "dgnn_spmm", "dgnn_mproduct",
+)
+
+
+class DgnnError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} ({code})")
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def build_library(verbose: bool = False) -> str:
+    """Compile csrc/*.hip for gfx950 into csrc/libdgnn.so with hipcc (cross-compiles without a GPU)."""
+    srcs = sorted(glob.glob(os.path.join(_CSRC, "*.hip")))
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-I", os.path.join(_ROOT, "include"), "-I", _CSRC, "-o", _LIB_PATH] + srcs
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if verbose or res.returncode != 0:
+        print(res.stdout)
+        print(res.stderr)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed building libdgnn.so")
+    return _LIB_PATH
+
+
+_lib = None
+_vp, _i64, _i32, _u32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_uint32
+_sz = ctypes.c_size_t
+
+
+def load_library():
+    """Load the built library; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                           "(or paper_2109_07893_amd.build_library()) first; there is no CPU fallback")
+    lib = ctypes.CDLL(_LIB_PATH)
+    lib.dgnn_strerror.restype = ctypes.c_char_p
+    lib.dgnn_strerror.argtypes = [ctypes.c_int]
+    lib.dgnn_csr_dinv.argtypes = [_i64, _vp, _vp, _vp]
+    lib.dgnn_delta_h2d.argtypes = [_vp, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp, _vp, _vp]
+    lib.dgnn_delta_rebuild_workspace.argtypes = [_i64, _i64, _i64, _i64, ctypes.POINTER(_sz)]
+    lib.dgnn_delta_rebuild.argtypes = [_i64, _vp, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _i64,
+                                       _vp, _vp, _i64, ctypes.POINTER(_i64), _vp, _vp, _sz, _u32, _vp, _vp]
+    lib.dgnn_feature_transform.argtypes = [_vp, _i64, _i32, _vp, _i32, _vp, ctypes.c_int, _vp]
+    lib.dgnn_spmm_workspace.argtypes = [_i64, _i64, _i32, ctypes.POINTER(_sz)]
+    lib.dgnn_spmm.argtypes = [_i64, _i64, _vp, _vp, _vp, _vp, _i32, _vp, ctypes.c_int, _u32, _vp, _sz, _vp]
+    lib.dgnn_mproduct.argtypes = [_vp, _vp, _i64, _i64, _i32, _i32, _vp, ctypes.c_int, _vp]
+    for name in EXPORTS:
+        if name != "dgnn_strerror":
+            getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def strerror(code: int) -> str:
+    return load_library().dgnn_strerror(int(code)).decode()
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != 0:
+        raise DgnnError(rc, where)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    assert t.is_contiguous(), "dgnn takes contiguous tensors"
+    return t.data_ptr() if t.numel() > 0 else None
+
+
+def _stream(t: torch.Tensor) -> Optional[int]:
+    return torch.cuda.current_stream(t.device).cuda_stream if t.is_cuda else None
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return DGNN_F32
+    if t.dtype == torch.bfloat16:
+        return DGNN_BF16
+    raise TypeError(f"dgnn feature tensors are float32 or bfloat16, not {t.dtype}")
+
+
+def _need(t: torch.Tensor, dtype, name: str) -> None:
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+
+
+def csr_dinv(rowptr: torch.Tensor, dinv: torch.Tensor) -> None:
+    _need(rowptr, torch.int32, "rowptr"); _need(dinv, torch.float32, "dinv")
+    n = rowptr.numel() - 1
+    _check(load_library().dgnn_csr_dinv(n, _ptr(rowptr), _ptr(dinv), _stream(rowptr)), "dgnn_csr_dinv")
+
+
+def delta_h2d(h_add_row, h_add_col, h_del_row, h_del_col, d_add_row, d_add_col, d_del_row, d_del_col) -> None:
+    """Pinned-host index lists -> device staging, asynchronously on the current stream."""
+    for t in (h_add_row, h_add_col, h_del_row, h_del_col):
+        _need(t, torch.int32, "difference list")
+        if t.numel() and not t.is_pinned():
+            raise ValueError("host difference lists must live in pinned memory")
+    n_add, n_del = h_add_row.numel(), h_del_row.numel()
+    assert d_add_row.numel() >= n_add and d_add_col.numel() >= n_add
+    assert d_del_row.numel() >= n_del and d_del_col.numel() >= n_del
+    _check(load_library().dgnn_delta_h2d(_ptr(h_add_row), _ptr(h_add_col), n_add, _ptr(h_del_row), _ptr(h_del_col),
+                                         n_del, _ptr(d_add_row), _ptr(d_add_col), _ptr(d_del_row), _ptr(d_del_col),
+                                         _stream(d_add_row)), "dgnn_delta_h2d")
+
+
+def delta_rebuild_workspace(n: int, nnz_prev: int, n_add: int, n_del: int) -> int:
+    out = _sz(0)
+    _check(load_library().dgnn_delta_rebuild_workspace(n, nnz_prev, n_add, n_del, ctypes.byref(out)),
+           "dgnn_delta_rebuild_workspace")
+    return int(out.value)
+
+
+def delta_rebuild(rowptr_prev, colidx_prev, nnz_prev: int, add_row, add_col, n_add: int, del_row, del_col, n_del: int,
+                  rowptr_next, colidx_next, dinv_next, ws, flags: int = 0, d_status=None) -> int:
+    """A_next = (A_prev minus deleted) plus added; returns nnz of A_next."""
+    for t, name in ((rowptr_prev, "rowptr_prev"), (colidx_prev, "colidx_prev"), (rowptr_next, "rowptr_next"),
+                    (colidx_next, "colidx_next")):
+        _need(t, torch.int32, name)
+    n = rowptr_prev.numel() - 1
+    if rowptr_next.numel() < n + 1:
+        raise DgnnError(-3, "dgnn_delta_rebuild (rowptr_next)")
+    nnz_next = _i64(0)
+    rc = load_library().dgnn_delta_rebuild(
+        n, _ptr(rowptr_prev), _ptr(colidx_prev), nnz_prev, _ptr(add_row), _ptr(add_col), n_add,
+        _ptr(del_row), _ptr(del_col), n_del, _ptr(rowptr_next), _ptr(colidx_next), colidx_next.numel(),
+        ctypes.byref(nnz_next), _ptr(dinv_next), _ptr(ws), ws.numel() * ws.element_size(), flags,
+        _ptr(d_status), _stream(rowptr_prev))
+    _check(rc, "dgnn_delta_rebuild")
+    return int(nnz_next.value)
+
+
+def feature_transform(x: torch.Tensor, w: torch.Tensor, h: torch.Tensor) -> None:
+    """H = X W."""
+    dt = _dtype_code(x)
+    if w.dtype != x.dtype or h.dtype != x.dtype:
+        raise TypeError("x, w, h must share one dtype")
+    n, f_in = x.shape
+    f_out = w.shape[1]
+    if w.shape[0] != f_in or tuple(h.shape) != (n, f_out):
+        raise ValueError("shape mismatch in feature_transform")
+    _check(load_library().dgnn_feature_transform(_ptr(x), n, f_in, _ptr(w), f_out, _ptr(h), dt, _stream(x)),
+           "dgnn_feature_transform")
+
+
+def spmm_workspace(n: int, nnz: int, f: int) -> int:
+    out = _sz(0)
+    _check(load_library().dgnn_spmm_workspace(n, nnz, f, ctypes.byref(out)), "dgnn_spmm_workspace")
+    return int(out.value)
+
+
+def spmm(rowptr, colidx, nnz: int, dinv, h: torch.Tensor, z: torch.Tensor, ws, flags: int = 0) -> None:
+    """Z = sigma?(A~ H)."""
+    _need(rowptr, torch.int32, "rowptr"); _need(colidx, torch.int32, "colidx")
+    dt = _dtype_code(h)
+    n, f = h.shape
+    if rowptr.numel() != n + 1 or tuple(z.shape) != (n, f) or z.dtype != h.dtype or colidx.numel() < nnz:
+        raise ValueError("shape mismatch in spmm")
+    _check(load_library().dgnn_spmm(n, nnz, _ptr(rowptr), _ptr(colidx), _ptr(dinv), _ptr(h), f, _ptr(z), dt, flags,
+                                    _ptr(ws), ws.numel() * ws.element_size(), _stream(h)), "dgnn_spmm")
+
+
+def mproduct(z: torch.Tensor, y: torch.Tensor, w: int, m_band: Optional[torch.Tensor] = None) -> None:
+    """Y = Z x_1 M over tensors [T, n, f]; y may be z itself."""
+    dt = _dtype_code(z)
+    T, n, f = z.shape
+    if tuple(y.shape) != (T, n, f) or y.dtype != z.dtype:
+        raise ValueError("shape mismatch in mproduct")
+    if m_band is not None:
+        _need(m_band, torch.float32, "m_band")
+        if m_band.numel() != T * w:
+            raise ValueError("m_band must be [T, w]")
+    _check(load_library().dgnn_mproduct(_ptr(z), _ptr(y), T, n, f, w, _ptr(m_band), dt, _stream(z)), "dgnn_mproduct")
+
+
+# codes a device-side validation can leave in d_status (include/dgnn.h)
+DGNN_BAD_INDEX_RANGE, DGNN_BAD_DELTA_ORDER, DGNN_BAD_DIAGONAL = 1, 2, 3
+DGNN_BAD_DEL_ABSENT, DGNN_BAD_ADD_PRESENT, DGNN_BAD_EMPTY_ROW = 4, 5, 6

@@ -1,0 +1,59 @@
+// Internal helpers shared by the HIP sources of libdgnn (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dgnn.h"
+
+#define DGNN_RETURN_IF_LAUNCH_FAILED()                       \
+    do {                                                     \
+        if (hipGetLastError() != hipSuccess) return DGNN_ERR_HIP; \
+    } while (0)
+
+namespace dgnn {
+
+constexpr int kWave = 64;   // wavefront width on CDNA4
+
+inline bool fits_i32(int64_t v) { return v >= 0 && v <= 2147483647LL; }
+inline bool supported_width(int32_t f) { return f == 16 || f == 32 || f == 64 || f == 128; }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// First index in [lo, hi) whose element is >= key (array ascending).
+__device__ __forceinline__ int lower_bound(const int32_t *__restrict__ a, int lo, int hi, int32_t key) {
+    while (lo < hi) {
+        int mid = lo + ((hi - lo) >> 1);
+        if (a[mid] < key) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+// Inclusive wavefront scans over 64 lanes.
+__device__ __forceinline__ int wave_scan_add(int v, int lane) {
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        int o = __shfl_up(v, d, kWave);
+        if (lane >= d) v += o;
+    }
+    return v;
+}
+__device__ __forceinline__ int wave_scan_max(int v, int lane) {
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        int o = __shfl_up(v, d, kWave);
+        if (lane >= d) v = max(v, o);
+    }
+    return v;
+}
+
+// bfloat16 <-> float, round to nearest even on the way down.
+__device__ __forceinline__ float bf16_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+__device__ __forceinline__ uint32_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;   // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+}  // namespace dgnn

@@ -1,0 +1,134 @@
+// M-transform of TM-GCN (Section "TM-GCN"): Y = Z x_1 M with the banded lower-triangular M,
+//     Y_t = sum_{j=0}^{min(w,t)-1} m(t,j) Z_{t-j},   m(t,j) = 1/min(w,t) unless given.
+//
+// Each lane owns one 16-byte piece of the N x F frame and walks the time axis once, keeping the
+// last w frames of its piece in a register ring, so every frame is read once and written once
+// (2 s N F bytes per timestep) whatever the window, and the transform can run in place.
+// The time loop is unrolled by the ring size so that ring slots are compile-time registers.
+#include "common.hpp"
+
+namespace {
+
+using namespace dgnn;
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 256;
+
+template <bool BF16> struct Vec;
+template <> struct Vec<false> {
+    static constexpr int kVals = 4;
+    static __device__ __forceinline__ void load(float (&v)[4], const char *p) {
+        floatx4 t = *reinterpret_cast<const floatx4 *>(p);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = t[e];
+    }
+    static __device__ __forceinline__ void store(char *p, const float (&v)[4]) {
+        *reinterpret_cast<floatx4 *>(p) = floatx4{v[0], v[1], v[2], v[3]};
+    }
+};
+template <> struct Vec<true> {
+    static constexpr int kVals = 8;
+    static __device__ __forceinline__ void load(float (&v)[8], const char *p) {
+        uintx4 t = *reinterpret_cast<const uintx4 *>(p);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            v[2 * e] = __uint_as_float(t[e] << 16);
+            v[2 * e + 1] = __uint_as_float(t[e] & 0xffff0000u);
+        }
+    }
+    static __device__ __forceinline__ void store(char *p, const float (&v)[8]) {
+        uintx4 t;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) t[e] = f32_to_bf16(v[2 * e]) | (f32_to_bf16(v[2 * e + 1]) << 16);
+        *reinterpret_cast<uintx4 *>(p) = t;
+    }
+};
+
+// RING >= w.  frame_bytes = n * f * s; pieces = frame_bytes / 16.
+template <int RING, bool BF16>
+__global__ __launch_bounds__(kThreads) void mproduct_kernel(const char *z, char *y, int T, int64_t pieces,
+                                                            int64_t frame_bytes, int w, const float *__restrict__ m_band) {
+    constexpr int NV = Vec<BF16>::kVals;
+    const int64_t piece = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (piece >= pieces) return;
+    const char *src = z + piece * 16;
+    char *dst = y + piece * 16;
+
+    float ring[RING][NV];
+#pragma unroll
+    for (int r = 0; r < RING; ++r)
+#pragma unroll
+        for (int e = 0; e < NV; ++e) ring[r][e] = 0.0f;
+
+    float next[NV];
+    Vec<BF16>::load(next, src);
+    for (int tb = 0; tb < T; tb += RING) {
+#pragma unroll
+        for (int jj = 0; jj < RING; ++jj) {
+            const int t = tb + jj;             // 0-based timestep
+            if (t < T) {
+#pragma unroll
+                for (int e = 0; e < NV; ++e) ring[jj][e] = next[e];
+                if (t + 1 < T) Vec<BF16>::load(next, src + (int64_t)(t + 1) * frame_bytes);   // before the store: y may be z
+                const int terms = min(w, t + 1);
+                const float uniform = 1.0f / (float)terms;
+                float out[NV];
+#pragma unroll
+                for (int e = 0; e < NV; ++e) out[e] = 0.0f;
+#pragma unroll
+                for (int j = 0; j < RING; ++j) {
+                    if (j < terms) {
+                        const float c = m_band ? m_band[(int64_t)t * w + j] : uniform;
+#pragma unroll
+                        for (int e = 0; e < NV; ++e) out[e] = fmaf(c, ring[(jj - j + RING) % RING][e], out[e]);
+                    }
+                }
+                Vec<BF16>::store(dst + (int64_t)t * frame_bytes, out);
+            }
+        }
+    }
+}
+
+template <int RING>
+int launch(const void *z, void *y, int64_t T, int64_t n, int32_t f, int32_t w, const float *m_band, dgnn_dtype dt,
+           hipStream_t s) {
+    const int64_t frame_bytes = n * f * (dt == DGNN_F32 ? 4 : 2);
+    const int64_t pieces = frame_bytes / 16;
+    const unsigned blocks = (unsigned)((pieces + kThreads - 1) / kThreads);
+    if (dt == DGNN_F32)
+        hipLaunchKernelGGL((mproduct_kernel<RING, false>), dim3(blocks), dim3(kThreads), 0, s,
+                           static_cast<const char *>(z), static_cast<char *>(y), (int)T, pieces, frame_bytes, (int)w, m_band);
+    else
+        hipLaunchKernelGGL((mproduct_kernel<RING, true>), dim3(blocks), dim3(kThreads), 0, s,
+                           static_cast<const char *>(z), static_cast<char *>(y), (int)T, pieces, frame_bytes, (int)w, m_band);
+    DGNN_RETURN_IF_LAUNCH_FAILED();
+    return DGNN_OK;
+}
+
+}  // namespace
+
+extern "C" int dgnn_mproduct(const void *z, void *y, int64_t T, int64_t n, int32_t f, int32_t w,
+                             const float *m_band, dgnn_dtype dt, void *stream) {
+    if (!z || !y) return DGNN_ERR_NULL;
+    if (T <= 0 || n <= 0 || w <= 0 || !supported_width(f)) return DGNN_ERR_SHAPE;
+    if (dt != DGNN_F32 && dt != DGNN_BF16) return DGNN_ERR_SHAPE;
+    if (!fits_i32(n) || !fits_i32(T)) return DGNN_ERR_OVERFLOW;
+    if (!aligned16(z) || !aligned16(y)) return DGNN_ERR_ALIGN;
+    const int64_t bytes = T * n * f * (dt == DGNN_F32 ? 4 : 2);
+    if (y != z) {   // partial overlap is not allowed
+        const char *a = static_cast<const char *>(z), *b = static_cast<const char *>(y);
+        if (a < b + bytes && b < a + bytes) return DGNN_ERR_ALIAS;
+    }
+    // A window longer than the series acts like the series length; with explicit coefficients the
+    // band layout keeps the caller's w as its row stride, so w itself must fit the ring.
+    const int64_t eff = m_band ? (int64_t)w : (w < T ? (int64_t)w : T);
+    if (eff > 32) return DGNN_ERR_SHAPE;
+    const int32_t wk = m_band ? w : (int32_t)eff;
+    hipStream_t s = (hipStream_t)stream;
+    if (eff <= 4) return launch<4>(z, y, T, n, f, wk, m_band, dt, s);
+    if (eff <= 8) return launch<8>(z, y, T, n, f, wk, m_band, dt, s);
+    if (eff <= 16) return launch<16>(z, y, T, n, f, wk, m_band, dt, s);
+    return launch<32>(z, y, T, n, f, wk, m_band, dt, s);
+}

@@ -1,0 +1,186 @@
+"""Caller-side plumbing for one GPU's block of timesteps: owns the device buffers (torch, used
+for memory and streams only) and issues the library calls in the order of the forward pass,
+
+    t = 1:      A_1 resident (sent whole, Section "Graph-difference Based Input Transfer")
+    t = 2..T:   [difference lists host -> device]  ->  dgnn_delta_rebuild  ->  A_t
+    every t:    per GCN layer  H = X W (dgnn_feature_transform),  Z = relu(A~_t H) (dgnn_spmm)
+    at the end: Y = Z x_1 M (dgnn_mproduct) when the workload has a window.
+
+No arithmetic of the method lives here; every step runs in the HIP kernels behind the C boundary.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Optional, Tuple
+
+import torch
+
+from . import binding as B
+
+
+@dataclass
+class BlockInputs:
+    """Inputs of one block of T snapshots, resident on `device`."""
+    n: int
+    T: int
+    f: int
+    layers: int
+    window: int
+    rowptr1: torch.Tensor                  # int32 [n+1]   first snapshot, sent whole
+    colidx1: torch.Tensor                  # int32 [nnz_1]
+    deltas: List[Tuple[torch.Tensor, ...]]  # per t = 2..T: (add_row, add_col, del_row, del_col), int32, device
+    x: List[torch.Tensor]                  # T frames [n, f]
+    w: List[torch.Tensor]                  # one weight [f, f] per layer
+    pinned: Optional[List[Tuple[torch.Tensor, ...]]] = None   # the same lists in pinned host memory
+    nnz: List[int] = field(default_factory=list)              # nnz_t, t = 1..T (host arithmetic on list lengths)
+
+    def __post_init__(self):
+        if not self.nnz:
+            cur = int(self.colidx1.numel())
+            self.nnz = [cur]
+            for ar, _, dr, _ in self.deltas:
+                cur += int(ar.numel()) - int(dr.numel())
+                self.nnz.append(cur)
+
+
+def make_block(wl, device, gen_device=None, pinned: bool = False, T: Optional[int] = None) -> BlockInputs:
+    """Generate a workload's block with the seeded generator and place it on `device`."""
+    from dtdg_synth import DynamicGraph, features, glorot_weight
+    gen_device = torch.device(gen_device if gen_device is not None else device)
+    T = T or wl.T
+    g = DynamicGraph(wl, device=gen_device)
+    rowptr1, colidx1 = (t.to(device) for t in g.csr())
+    deltas, pins = [], []
+    for _ in range(2, T + 1):
+        d = g.advance()
+        deltas.append(tuple(t.to(device) for t in d))
+        if pinned:
+            pins.append(tuple(torch.empty(t.shape, dtype=t.dtype, pin_memory=True).copy_(t) for t in d))
+    x = [features(wl, t, device=gen_device).to(device) for t in range(1, T + 1)]
+    w = [glorot_weight(wl, layer, device=gen_device).to(device) for layer in range(wl.layers)]
+    return BlockInputs(n=wl.n, T=T, f=wl.f, layers=wl.layers, window=wl.window, rowptr1=rowptr1,
+                       colidx1=colidx1, deltas=deltas, x=x, w=w, pinned=pins if pinned else None)
+
+
+class BlockRunner:
+    """Buffers and call sequence for the forward pass over one block."""
+
+    def __init__(self, blk: BlockInputs, keep_all_z: Optional[bool] = None):
+        self.blk = blk
+        dev = blk.rowptr1.device
+        self.dev = dev
+        n, f = blk.n, blk.f
+        dt = blk.x[0].dtype
+        cap = max(blk.nnz)
+        self.cap = cap
+        # two CSR slots used alternately: A_{t-1} is read while A_t is written
+        self.rowptr = [torch.empty(n + 1, dtype=torch.int32, device=dev) for _ in range(2)]
+        self.colidx = [torch.empty(cap, dtype=torch.int32, device=dev) for _ in range(2)]
+        self.dinv = [torch.empty(n, dtype=torch.float32, device=dev) for _ in range(2)]
+        self.h = torch.empty((n, f), dtype=dt, device=dev)
+        self.z_mid = torch.empty((n, f), dtype=dt, device=dev) if blk.layers > 1 else None
+        self.keep_all_z = bool(blk.window) if keep_all_z is None else keep_all_z
+        zt = blk.T if self.keep_all_z else 1
+        self.z = torch.empty((zt, n, f), dtype=dt, device=dev)
+        max_add = max([int(d[0].numel()) for d in blk.deltas] + [1])
+        max_del = max([int(d[2].numel()) for d in blk.deltas] + [1])
+        ws_r = B.delta_rebuild_workspace(n, cap, max_add, max_del)
+        ws_s = B.spmm_workspace(n, cap, f)
+        self.ws_rebuild = torch.empty(ws_r, dtype=torch.uint8, device=dev)
+        self.ws_spmm = torch.empty(ws_s, dtype=torch.uint8, device=dev)
+        self.status = torch.zeros(blk.T + 1, dtype=torch.int32, device=dev)
+        # staging for difference lists that arrive from pinned host memory (two sets, used alternately)
+        self.stage = None
+        if blk.pinned is not None:
+            self.stage = [tuple(torch.empty(m, dtype=torch.int32, device=dev) for m in (max_add, max_add, max_del, max_del))
+                          for _ in range(2)]
+            self.copy_stream = torch.cuda.Stream(device=dev)
+            self.copied = [torch.cuda.Event() for _ in range(2)]
+            self.consumed = [torch.cuda.Event() for _ in range(2)]
+
+    # ------------------------------------------------------------------ pieces
+    def load_first(self) -> None:
+        """Place A_1 in slot 0 and derive its dinv (outside any timed region: A_1 is sent whole)."""
+        blk = self.blk
+        self.rowptr[0].copy_(blk.rowptr1)
+        self.colidx[0][: blk.nnz[0]].copy_(blk.colidx1)
+        B.csr_dinv(self.rowptr[0], self.dinv[0])
+
+    def rebuild(self, t: int, lists, validate: bool = False) -> None:
+        """A_t (slot (t-1) % 2) from A_{t-1} (the other slot) and the difference lists of step t (t >= 2)."""
+        blk = self.blk
+        src, dst = (t - 2) % 2, (t - 1) % 2
+        ar, ac, dr, dc = lists
+        n_add, n_del = int(blk.deltas[t - 2][0].numel()), int(blk.deltas[t - 2][2].numel())
+        nnz = B.delta_rebuild(self.rowptr[src], self.colidx[src], blk.nnz[t - 2], ar, ac, n_add, dr, dc, n_del,
+                              self.rowptr[dst], self.colidx[dst], self.dinv[dst], self.ws_rebuild,
+                              flags=B.DGNN_VALIDATE if validate else 0, d_status=self.status[t:t + 1])
+        assert nnz == blk.nnz[t - 1]
+
+    def gcn(self, t: int) -> torch.Tensor:
+        """All GCN layers on snapshot t; returns the frame Z_t."""
+        blk = self.blk
+        slot = (t - 1) % 2
+        out = self.z[t - 1] if self.keep_all_z else self.z[0]
+        cur = blk.x[t - 1]
+        for layer in range(blk.layers):
+            B.feature_transform(cur, blk.w[layer], self.h)
+            dst = out if layer == blk.layers - 1 else self.z_mid
+            B.spmm(self.rowptr[slot], self.colidx[slot], blk.nnz[t - 1], self.dinv[slot], self.h, dst,
+                   self.ws_spmm, flags=B.DGNN_RELU)
+            cur = dst
+        return out
+
+    def mix(self) -> None:
+        """In-place M-transform over the stored frames."""
+        if self.blk.window:
+            B.mproduct(self.z, self.z, self.blk.window)
+
+    # ------------------------------------------------------------------ whole passes
+    def run_resident(self, first: int = 1, validate: bool = False, on_snapshot=None) -> None:
+        """Forward pass with the difference lists already on the device.  `first` = 2 skips the GCN
+        on A_1 (timed regions that count only rebuilt snapshots).  on_snapshot(t, slot) is called
+        after the work of timestep t has been enqueued."""
+        blk = self.blk
+        for t in range(1, blk.T + 1):
+            if t >= 2:
+                self.rebuild(t, blk.deltas[t - 2], validate)
+            if t >= first:
+                self.gcn(t)
+            if on_snapshot is not None:
+                on_snapshot(t, (t - 1) % 2)
+        self.mix()
+
+    def run_from_pinned(self, first: int = 1) -> None:
+        """Same pass with the difference lists of step t+1 copied from pinned host memory on a second
+        stream while step t computes (two staging sets, events both ways)."""
+        blk = self.blk
+        assert self.stage is not None
+        main = torch.cuda.current_stream(self.dev)
+
+        def issue_copy(t):
+            k = t % 2
+            with torch.cuda.stream(self.copy_stream):
+                self.copy_stream.wait_event(self.consumed[k])
+                B.delta_h2d(*blk.pinned[t - 2], *self.stage[k])
+                self.copied[k].record(self.copy_stream)
+
+        for k in range(2):
+            self.consumed[k].record(main)
+        if blk.T >= 2:
+            issue_copy(2)
+        for t in range(1, blk.T + 1):
+            if t >= 2:
+                k = t % 2
+                main.wait_event(self.copied[k])
+                if t + 1 <= blk.T:
+                    issue_copy(t + 1)
+                self.rebuild(t, self.stage[k])
+                self.consumed[k].record(main)
+            if t >= first:
+                self.gcn(t)
+        self.mix()
+
+    def snapshot_to_host(self, t: int):
+        slot = (t - 1) % 2
+        return self.rowptr[slot].cpu().numpy(), self.colidx[slot][: self.blk.nnz[t - 1]].cpu().numpy()

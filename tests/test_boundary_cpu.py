@@ -1,0 +1,130 @@
+"""Host-side checks of the C boundary that need no GPU: the library loads, exports every entry
+point that include/dgnn.h declares, and turns bad arguments into error codes before anything is
+enqueued."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2109_07893_amd as dg
+from paper_2109_07893_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(dg.library_path()):
+        dg.build_library()
+    return dg.load_library()
+
+
+def declared_entry_points():
+    text = open(os.path.join(ROOT, "include", "dgnn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dgnn_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_and_library_agree(lib):
+    names = declared_entry_points()
+    assert set(names) == set(binding.EXPORTS)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_strerror(lib):
+    assert dg.strerror(0) == "ok"
+    for code in range(-7, 0):
+        assert dg.strerror(code) != "unknown dgnn status"
+    assert dg.strerror(-99) == "unknown dgnn status"
+
+
+P = ctypes.c_void_p
+FAKE = 0x1000  # never dereferenced: every call below must fail on the host first
+
+
+def test_workspace_queries(lib):
+    out = ctypes.c_size_t(0)
+    assert lib.dgnn_delta_rebuild_workspace(1000, 11000, 500, 500, ctypes.byref(out)) == 0
+    assert out.value >= 4 * 1001
+    assert lib.dgnn_delta_rebuild_workspace(1000, 11000, 500, 500, None) == -1
+    assert lib.dgnn_delta_rebuild_workspace(0, 1, 0, 0, ctypes.byref(out)) == -2
+    assert lib.dgnn_delta_rebuild_workspace(1 << 31, 1, 0, 0, ctypes.byref(out)) == -4
+    assert lib.dgnn_delta_rebuild_workspace(10, (1 << 31) - 2, 5, 0, ctypes.byref(out)) == -4
+    assert lib.dgnn_spmm_workspace(1000, 11000, 32, ctypes.byref(out)) == 0 and out.value > 0
+    assert lib.dgnn_spmm_workspace(1000, 11000, 24, ctypes.byref(out)) == -2
+    assert lib.dgnn_spmm_workspace(1000, 1 << 31, 32, ctypes.byref(out)) == -4
+
+
+def test_delta_rebuild_argument_errors(lib):
+    nn = ctypes.c_int64(0)
+
+    def call(n=10, rp=FAKE, ci=FAKE, nnz=20, ar=FAKE, ac=FAKE, na=2, dr=FAKE, dc=FAKE, nd=1, rpn=FAKE + 64,
+             cin=FAKE + 128, cap=64, dinv=None, ws=FAKE + 256, wsb=1 << 20, flags=0):
+        return lib.dgnn_delta_rebuild(n, rp, ci, nnz, ar, ac, na, dr, dc, nd, rpn, cin, cap, ctypes.byref(nn), dinv,
+                                      ws, wsb, flags, None, None)
+
+    assert call(rp=None) == -1 and call(cin=None) == -1 and call(ws=None) == -1
+    assert call(ar=None) == -1 and call(dc=None) == -1
+    assert call(n=0) == -2 and call(na=-1) == -2 and call(flags=8) == -2
+    assert call(cap=20) == -3            # needs 21
+    assert call(wsb=8) == -3
+    assert call(n=1 << 31) == -4
+    assert call(rpn=FAKE) == -5 and call(cin=FAKE) == -5
+
+
+def test_feature_transform_argument_errors(lib):
+    f = lib.dgnn_feature_transform
+    assert f(None, 10, 32, FAKE, 32, FAKE + 4096, 0, None) == -1
+    assert f(FAKE, 0, 32, FAKE, 32, FAKE + 4096, 0, None) == -2
+    assert f(FAKE, 10, 24, FAKE, 32, FAKE + 4096, 0, None) == -2
+    assert f(FAKE, 10, 32, FAKE, 32, FAKE + 4096, 7, None) == -2
+    assert f(FAKE + 4, 10, 32, FAKE, 32, FAKE + 4096, 0, None) == -7
+    assert f(FAKE, 10, 32, FAKE + 64, 32, FAKE, 0, None) == -5
+
+
+def test_spmm_argument_errors(lib):
+    f = lib.dgnn_spmm
+    ok = dict(n=10, nnz=20, rp=FAKE, ci=FAKE, dinv=None, h=FAKE, f=32, z=FAKE + 4096, dt=0, flags=0, ws=FAKE + 8192,
+              wsb=1 << 24)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return f(a["n"], a["nnz"], a["rp"], a["ci"], a["dinv"], a["h"], a["f"], a["z"], a["dt"], a["flags"], a["ws"],
+                 a["wsb"], None)
+
+    assert call(rp=None) == -1 and call(z=None) == -1 and call(ws=None) == -1
+    assert call(f=20) == -2 and call(flags=4) == -2 and call(n=-1) == -2
+    assert call(wsb=16) == -3
+    assert call(h=FAKE + 8) == -7
+    assert call(z=FAKE) == -5
+    assert call(nnz=1 << 31) == -4
+
+
+def test_mproduct_argument_errors(lib):
+    f = lib.dgnn_mproduct
+    assert f(None, FAKE, 8, 10, 16, 3, None, 0, None) == -1
+    assert f(FAKE, FAKE, 0, 10, 16, 3, None, 0, None) == -2
+    assert f(FAKE, FAKE, 8, 10, 16, 0, None, 0, None) == -2
+    assert f(FAKE, FAKE, 64, 10, 16, 33, None, 0, None) == -2           # window beyond the register ring
+    assert f(FAKE, FAKE + 16, 8, 10, 16, 3, None, 0, None) == -5        # partial overlap
+    assert f(FAKE, FAKE + 4, 8, 10, 16, 3, None, 0, None) == -7
+
+
+def test_misc_argument_errors(lib):
+    assert lib.dgnn_csr_dinv(10, None, FAKE, None) == -1
+    assert lib.dgnn_csr_dinv(0, FAKE, FAKE, None) == -2
+    assert lib.dgnn_delta_h2d(None, None, 3, None, None, 0, None, None, None, None, None) == -1
+    assert lib.dgnn_delta_h2d(None, None, 0, None, None, 0, None, None, None, None, None) == 0
+    assert lib.dgnn_delta_h2d(None, None, -1, None, None, 0, None, None, None, None, None) == -2
+
+
+def test_python_binding_rejects_wrong_dtypes():
+    import torch
+    x = torch.zeros((4, 16), dtype=torch.float64)
+    with pytest.raises(TypeError):
+        dg.feature_transform(x, x, x)
+    rp = torch.zeros(5, dtype=torch.int64)
+    with pytest.raises(TypeError):
+        dg.csr_dinv(rp, torch.zeros(4))

@@ -1,0 +1,282 @@
+"""GPU parity, kernel by kernel: every entry point of the C boundary against the CPU oracle on the
+same seeded inputs, element by element, at sizes that span several tiles and a ragged tail."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2109_07893_amd as dg
+from dtdg_synth import WORKLOADS, DynamicGraph
+from helpers import assert_close, to_f64
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def dev_i32(a):
+    return torch.as_tensor(np.ascontiguousarray(a), dtype=torch.int32).to(DEV)
+
+
+def gpu_rebuild(n, rp, ci, ar, ac, dr, dc, validate=True, slack=0):
+    rp_d, ci_d = dev_i32(rp), dev_i32(ci)
+    lists = [dev_i32(x) for x in (ar, ac, dr, dc)]
+    nnz_prev, n_add, n_del = int(ci.size), int(ar.size), int(dr.size)
+    cap = nnz_prev + n_add - n_del + slack
+    rpn = torch.full((n + 1,), -7, dtype=torch.int32, device=DEV)
+    cin = torch.full((max(cap, 1),), -7, dtype=torch.int32, device=DEV)
+    dinv = torch.zeros(n, dtype=torch.float32, device=DEV)
+    ws = torch.empty(dg.delta_rebuild_workspace(n, nnz_prev, n_add, n_del), dtype=torch.uint8, device=DEV)
+    status = torch.full((1,), 99, dtype=torch.int32, device=DEV)
+    nnz = dg.delta_rebuild(rp_d, ci_d, nnz_prev, lists[0], lists[1], n_add, lists[2], lists[3], n_del, rpn, cin, dinv,
+                           ws, flags=dg.DGNN_VALIDATE if validate else 0, d_status=status)
+    torch.cuda.synchronize()
+    return rpn.cpu().numpy(), cin.cpu().numpy()[:nnz], dinv.cpu().numpy(), int(status.item()), cin.cpu().numpy()[nnz:]
+
+
+def coo(pairs):
+    pairs = sorted(set(pairs))
+    return (np.array([p[0] for p in pairs], np.int32), np.array([p[1] for p in pairs], np.int32))
+
+
+EMPTY = (np.zeros(0, np.int32), np.zeros(0, np.int32))
+
+
+# ------------------------------------------------------------------------------- delta rebuild
+def test_rebuild_adversarial_tiny_cases():
+    n = 6
+    base = [(u, u) for u in range(n)] + [(0, 1), (0, 5), (1, 0), (2, 3), (2, 4), (2, 5), (5, 0), (5, 4)]
+    rp, ci = oracle.csr_from_edges(n, *coo(base))
+    cases = {
+        "empty": ([], []),
+        "first_row_only": ([(0, 2), (0, 3)], [(0, 1)]),
+        "last_row_only": ([(5, 1)], [(5, 4), (5, 0)]),
+        "row_emptied_to_diagonal": ([], [(2, 3), (2, 4), (2, 5)]),
+        "delete_next_to_insert": ([(2, 1), (0, 4)], [(2, 3), (0, 5)]),
+        "first_and_last_column": ([(3, 0), (3, 5), (4, 0), (1, 5)], [(5, 0), (0, 5)]),
+        "every_row": ([(0, 2), (1, 2), (2, 0), (3, 1), (4, 1), (5, 3)], [(0, 1), (1, 0), (2, 3), (5, 4)]),
+        "only_adds": ([(1, 3), (1, 4), (1, 5), (4, 2)], []),
+        "only_dels": ([], [(0, 1), (5, 4)]),
+    }
+    for name, (adds, dels) in cases.items():
+        a = coo(adds) if adds else EMPTY
+        d = coo(dels) if dels else EMPTY
+        erp, eci = oracle.delta_apply(n, rp, ci, *a, *d)
+        grp, gci, dinv, status, tail = gpu_rebuild(n, rp, ci, *a, *d, slack=3)
+        assert status == 0, name
+        assert np.array_equal(grp, erp) and np.array_equal(gci, eci), name
+        assert np.all(tail == -7), name                                   # nothing written past nnz
+        assert np.allclose(dinv, 1.0 / np.sqrt(np.diff(erp)), rtol=3e-7, atol=0), name
+
+
+@pytest.mark.parametrize("name,n,steps", [("c1", 1000, 7), ("c2", 50_000, 3), ("c3", 1 << 16, 3), ("c5", 1 << 15, 3),
+                                          ("c4", 30_000, 3)])
+def test_rebuild_matches_oracle_and_from_scratch(name, n, steps):
+    wl = WORKLOADS[name] if WORKLOADS[name].n == n else WORKLOADS[name].scaled(n)
+    g = DynamicGraph(wl)
+    rp, ci = (x.numpy() for x in g.csr())
+    for _ in range(steps):
+        lists = [x.numpy() for x in g.advance()]
+        erp, eci = oracle.delta_apply(wl.n, rp, ci, *lists)
+        grp, gci, dinv, status, _ = gpu_rebuild(wl.n, rp, ci, *lists)
+        assert status == 0
+        assert np.array_equal(grp, erp) and np.array_equal(gci, eci)
+        srp, sci = (x.numpy() for x in g.csr())                         # the generator's own E_t, from scratch
+        assert np.array_equal(grp, srp) and np.array_equal(gci, sci)
+        assert np.allclose(dinv, 1.0 / np.sqrt(np.diff(erp)), rtol=3e-7, atol=0)
+        rp, ci = erp, eci
+
+
+def test_rebuild_heavy_rows_and_many_adds_between_neighbours():
+    """A hub row spanning several tiles that loses and gains thousands of entries, a row that grows from
+    its diagonal alone, and rows of length one around them."""
+    n = 20000
+    rng = np.random.default_rng(3)
+    hub, lone = 7, 11
+    hub_cols = np.setdiff1d(rng.choice(n, 9000, replace=False), [hub])
+    pairs_r = [np.full(hub_cols.size, hub), np.arange(n)]
+    pairs_c = [hub_cols, np.arange(n)]
+    other_r = rng.integers(100, n, 30000)
+    other_c = rng.integers(0, n, 30000)
+    rp, ci = oracle.csr_from_edges(n, np.concatenate(pairs_r + [other_r]).astype(np.int32),
+                                   np.concatenate(pairs_c + [other_c]).astype(np.int32))
+    present = set(zip(np.repeat(np.arange(n), np.diff(rp)).tolist(), ci.tolist()))
+    dels = [(hub, int(c)) for c in hub_cols[::3]]
+    adds = [(hub, int(c)) for c in rng.choice(n, 6000, replace=False) if (hub, int(c)) not in present]
+    adds += [(lone, int(c)) for c in rng.choice(n, 5000, replace=False) if (lone, int(c)) not in present]
+    a, d = coo(adds), coo(dels)
+    erp, eci = oracle.delta_apply(n, rp, ci, *a, *d)
+    grp, gci, _, status, _ = gpu_rebuild(n, rp, ci, *a, *d)
+    assert status == 0
+    assert np.array_equal(grp, erp) and np.array_equal(gci, eci)
+
+
+def test_rebuild_validation_codes():
+    n = 6
+    base = [(u, u) for u in range(n)] + [(0, 1), (1, 0), (2, 3), (3, 2)]
+    rp, ci = oracle.csr_from_edges(n, *coo(base))
+
+    def status(adds, dels, raw=False):
+        a = adds if raw else (coo(adds) if adds else EMPTY)
+        d = coo(dels) if dels else EMPTY
+        return gpu_rebuild(n, rp, ci, *a, *d, slack=4)[3]
+
+    assert status([(0, 2)], [(0, 1)]) == 0
+    assert status([(0, 1)], []) == 5                                    # added edge present
+    assert status([], [(0, 2)]) == 4                                              # deleted edge absent
+    assert status([(4, 4)], []) == 3                                              # diagonal named
+    assert status((np.array([0, 0], np.int32), np.array([3, 2], np.int32)), [], raw=True) == 2   # unsorted
+    assert status((np.array([0, 0], np.int32), np.array([2, 2], np.int32)), [], raw=True) == 2   # repeated
+    assert status((np.array([0], np.int32), np.array([6], np.int32)), [], raw=True) == 1         # out of range
+
+
+def test_rebuild_is_deterministic():
+    wl = WORKLOADS["c3"].scaled(1 << 14)
+    g = DynamicGraph(wl)
+    rp, ci = (x.numpy() for x in g.csr())
+    lists = [x.numpy() for x in g.advance()]
+    a = gpu_rebuild(wl.n, rp, ci, *lists)
+    b = gpu_rebuild(wl.n, rp, ci, *lists)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2])
+
+
+def test_csr_dinv():
+    wl = WORKLOADS["c3"].scaled(1 << 12)
+    rp, _ = DynamicGraph(wl).csr()
+    dinv = torch.zeros(wl.n, dtype=torch.float32, device=DEV)
+    dg.csr_dinv(rp.to(DEV), dinv)
+    assert np.allclose(dinv.cpu().numpy(), 1.0 / np.sqrt(np.diff(rp.numpy())), rtol=3e-7, atol=0)
+
+
+# ------------------------------------------------------------------------------- X W
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("f_in", [16, 32, 64, 128])
+@pytest.mark.parametrize("f_out", [16, 32, 64, 128])
+def test_feature_transform(dtype, f_in, f_out):
+    gen = torch.Generator().manual_seed(f_in * 1000 + f_out)
+    for n in (1, 33, 1000, 20497):
+        x = torch.randn((n, f_in), generator=gen).to(dtype)
+        w = (torch.rand((f_in, f_out), generator=gen) - 0.5).to(dtype)
+        h = torch.full((n, f_out), float("nan"), dtype=dtype, device=DEV)
+        dg.feature_transform(x.to(DEV), w.to(DEV), h)
+        torch.cuda.synchronize()
+        assert_close(to_f64(h), oracle.xw(to_f64(x), to_f64(w)), dtype, f"xw n={n} {f_in}x{f_out}")
+
+
+@pytest.mark.parametrize("dtype,f", [(torch.float32, 32), (torch.bfloat16, 128)])
+def test_feature_transform_more_rows_than_one_grid_pass(dtype, f):
+    n = 600_001                                             # the launch caps its grid and loops over row tiles
+    gen = torch.Generator().manual_seed(f)
+    x = torch.randn((n, f), generator=gen).to(dtype)
+    w = (torch.rand((f, f), generator=gen) - 0.5).to(dtype)
+    h = torch.full((n, f), float("nan"), dtype=dtype, device=DEV)
+    dg.feature_transform(x.to(DEV), w.to(DEV), h)
+    assert_close(to_f64(h), oracle.xw(to_f64(x), to_f64(w)), dtype, f"xw n={n} f={f}")
+
+
+def test_feature_transform_identity_is_exact():
+    x = torch.randn((777, 64))
+    h = torch.empty((777, 64), device=DEV)
+    dg.feature_transform(x.to(DEV), torch.eye(64, device=DEV), h)
+    assert torch.equal(h.cpu(), x)
+
+
+# ------------------------------------------------------------------------------- A~ H
+def gpu_spmm(rp, ci, h, relu, use_dinv=True):
+    n, f = h.shape
+    rp_d, ci_d = dev_i32(rp), dev_i32(ci)
+    dinv = None
+    if use_dinv:
+        dinv = torch.empty(n, dtype=torch.float32, device=DEV)
+        dg.csr_dinv(rp_d, dinv)
+    z = torch.full((n, f), float("nan"), dtype=h.dtype, device=DEV)
+    ws = torch.empty(dg.spmm_workspace(n, int(ci.size), f), dtype=torch.uint8, device=DEV)
+    dg.spmm(rp_d, ci_d, int(ci.size), dinv, h.to(DEV), z, ws, flags=dg.DGNN_RELU if relu else 0)
+    torch.cuda.synchronize()
+    return z
+
+
+def graph_with_long_rows(n, seed):
+    """Power-law snapshot plus planted rows of 513, 1024, 1025 and 5000 entries (the bin edges of the
+    row-length split and of the long-row chunks)."""
+    wl = WORKLOADS["c3"].scaled(n)
+    g = DynamicGraph(wl)
+    keys = g.keys.numpy()
+    rng = np.random.default_rng(seed)
+    extra_r, extra_c = [], []
+    for row, length in ((3, 513), (n // 2, 1024), (n - 1, 1025), (17, 5000), (18, 512)):
+        cols = rng.choice(n, length, replace=False)
+        extra_r.append(np.full(length, row))
+        extra_c.append(cols)
+    r = np.concatenate([keys >> 32] + extra_r).astype(np.int32)
+    c = np.concatenate([keys & 0xFFFFFFFF] + extra_c).astype(np.int32)
+    return oracle.csr_from_edges(n, r, c)
+
+
+@pytest.mark.parametrize("dtype,f", [(torch.float32, 16), (torch.float32, 32), (torch.float32, 64), (torch.float32, 128),
+                                     (torch.bfloat16, 16), (torch.bfloat16, 32), (torch.bfloat16, 64), (torch.bfloat16, 128)])
+@pytest.mark.parametrize("relu", [False, True])
+def test_spmm_power_law_with_long_rows(dtype, f, relu):
+    n = 1 << 13
+    rp, ci = graph_with_long_rows(n, f)
+    assert np.diff(rp).max() > 5000
+    h = torch.randn((n, f), generator=torch.Generator().manual_seed(f)).to(dtype)
+    z = gpu_spmm(rp, ci, h, relu)
+    assert_close(to_f64(z), oracle.spmm(rp, ci, to_f64(h), relu=relu), dtype, f"spmm f={f}")
+
+
+def test_spmm_uniform_graph_ragged_tail_and_closed_form():
+    wl = WORKLOADS["c2"].scaled(10_007)
+    rp, ci = (x.numpy() for x in DynamicGraph(wl).csr())
+    h = torch.randn((wl.n, 32), generator=torch.Generator().manual_seed(1))
+    z = gpu_spmm(rp, ci, h, False)
+    assert_close(to_f64(z), oracle.spmm(rp, ci, to_f64(h)), torch.float32, "uniform")
+    # sqrt(1 + deg) is a fixed vector of the normalised adjacency
+    d = np.sqrt(np.diff(rp).astype(np.float64))
+    x = torch.tensor(np.repeat(d[:, None], 16, axis=1), dtype=torch.float32)
+    assert_close(to_f64(gpu_spmm(rp, ci, x, False)), to_f64(x), torch.float32, "fixed vector")
+
+
+def test_spmm_without_normalisation_counts_neighbours():
+    wl = WORKLOADS["c1"]
+    rp, ci = (x.numpy() for x in DynamicGraph(wl).csr())
+    z = gpu_spmm(rp, ci, torch.ones((wl.n, 16)), False, use_dinv=False)
+    assert np.array_equal(to_f64(z), np.repeat(np.diff(rp).astype(np.float64)[:, None], 16, axis=1))
+
+
+def test_spmm_is_deterministic():
+    n = 1 << 13
+    rp, ci = graph_with_long_rows(n, 5)
+    h = torch.randn((n, 32), generator=torch.Generator().manual_seed(9))
+    a, b = gpu_spmm(rp, ci, h, True), gpu_spmm(rp, ci, h, True)
+    assert torch.equal(a, b)
+
+
+# ------------------------------------------------------------------------------- M-transform
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("T,w", [(8, 3), (32, 8), (40, 16), (5, 1), (6, 9), (70, 32), (3, 2), (1, 4)])
+def test_mproduct_paper_weights(dtype, T, w):
+    n, f = 333, 32
+    z = torch.randn((T, n, f), generator=torch.Generator().manual_seed(T * 100 + w)).to(dtype)
+    expect = oracle.mproduct(to_f64(z), oracle.m_matrix(T, w))
+    zd = z.to(DEV)
+    y = torch.full_like(zd, float("nan"))
+    dg.mproduct(zd, y, w)
+    assert_close(to_f64(y), expect, dtype, f"mproduct T={T} w={w}")
+    assert torch.equal(zd.cpu(), z)                                       # input untouched out of place
+    dg.mproduct(zd, zd, w)                                               # in place
+    torch.cuda.synchronize()
+    assert torch.equal(zd, y)
+
+
+def test_mproduct_explicit_band():
+    T, w, n, f = 12, 4, 100, 16
+    gen = torch.Generator().manual_seed(4)
+    z = torch.randn((T, n, f), generator=gen)
+    band = torch.randn((T, w), generator=gen)
+    M = np.zeros((T, T))
+    for t in range(T):
+        for j in range(min(w, t + 1)):
+            M[t, t - j] = float(band[t, j])
+    y = torch.empty((T, n, f), device=DEV)
+    dg.mproduct(z.to(DEV), y, w, m_band=band.to(DEV))
+    assert_close(to_f64(y), oracle.mproduct(to_f64(z), M), torch.float32, "explicit band")
