@@ -1,0 +1,215 @@
+#!/usr/bin/env python3
+"""Benchmark of the dynamic-GNN hot path on one MI355X.
+
+A step is one forward pass over one GPU's block of snapshots of a seeded synthetic dynamic graph:
+for every snapshot after the first, rebuild its CSR on the GPU from the previous snapshot and the
+graph difference (lists already resident in HBM), then H = X W and Z = relu(A~ H) per GCN layer;
+workloads with a window finish with the M-transform over the block.  Throughput is the paper's
+definition (Section "Scaling Study", weak scaling): edges summed over the processed snapshots
+divided by time.
+
+Prints ONE JSON line.  Besides the throughput it carries
+  roofline      for the stage that takes the most time: algorithmic bytes per call / its average
+                duration, measured here with event pairs on the launch stream, against 8 TB/s;
+  cpu_baseline  the CPU oracle (oracle/) timed on the host cores on a bounded sample.
+"""
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c5", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--n", type=int, default=0, help="run the workload's recipe at another vertex count (debugging)")
+    ap.add_argument("--T", type=int, default=0, help="override the number of snapshots (debugging)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0, help="stop the oracle sample after this much work")
+    ap.add_argument("--pinned", action="store_true", help="also time the pass with difference lists in pinned host memory")
+    return ap.parse_args()
+
+
+def algorithmic_bytes(blk, stage, t=None):
+    """Bytes the method itself must move per call of a stage (index = 4 B, no value array)."""
+    s = blk.x[0].element_size()
+    n, f = blk.n, blk.f
+    if stage == "delta_rebuild":
+        n_delta = blk.deltas[t - 2][0].numel() + blk.deltas[t - 2][2].numel()
+        return 4 * blk.nnz[t - 2] + 4 * blk.nnz[t - 1] + 16 * n + 16 * n_delta
+    if stage == "feature_transform":
+        return 2 * s * n * f + s * f * f
+    if stage == "spmm":            # lower bound: every row of H fetched once
+        return 4 * blk.nnz[t - 1] + 8 * n + 2 * s * n * f
+    if stage == "mproduct":
+        return 2 * s * n * f * blk.T
+    raise KeyError(stage)
+
+
+def committed_traffic(workload, stage):
+    """HBM bytes per call from the committed rocprofv3 counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", f"{stage}_{workload}_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"^traffic_bytes_per_call:\s*([0-9.eE+]+)", open(path).read(), flags=re.M)
+    return float(m.group(1)) if m else None
+
+
+def cpu_baseline(wl, blk, first, budget_s):
+    """The oracle as it stands, on the host cores, over the first timesteps of the same block."""
+    import numpy as np
+    import oracle
+    n = blk.n
+    rp = blk.rowptr1.cpu().numpy()
+    ci = blk.colidx1.cpu().numpy()
+    ws = [w.detach().cpu().double().numpy() for w in blk.w]
+    edges, spent, done = 0, 0.0, []
+    for t in range(1, blk.T + 1):
+        lists = [x.cpu().numpy() for x in blk.deltas[t - 2]] if t >= 2 else None
+        x = blk.x[t - 1].detach().cpu().double().numpy()
+        t0 = time.perf_counter()
+        if t >= 2:
+            rp, ci = oracle.delta_apply(n, rp, ci, *lists)
+        if t >= first:
+            val = oracle.gcn_values(rp, ci)
+            cur = x
+            for w in ws:
+                cur = oracle.spmm(rp, ci, oracle.xw(cur, w), relu=True, val=val)
+        dt = time.perf_counter() - t0
+        if t >= first:
+            spent += dt
+            edges += int(ci.size)
+            done.append(t)
+        if spent >= budget_s:
+            break
+    return {"value": edges / spent if spent > 0 else None, "unit": "edges/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds": round(spent, 3),
+            "sample": f"timesteps t={done[0]}..{done[-1]} of the same block (rebuild + {len(ws)} GCN layer(s), "
+                      f"no M-transform), full graph, {edges} edges"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on one GPU only (one GPU's block of timesteps, no collectives); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2109_07893_amd as dg
+    from dtdg_synth import WORKLOADS
+    from paper_2109_07893_amd.pipeline import BlockRunner, StageTimer, make_block
+
+    dg.load_library()
+    wl = WORKLOADS[args.workload]
+    if args.n:
+        wl = wl.scaled(args.n)
+    T = args.T or wl.T
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    t_gen = time.perf_counter()
+    blk = make_block(wl, dev, gen_device=dev, pinned=args.pinned, T=T)
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t_gen
+
+    runner = BlockRunner(blk)
+    runner.load_first()
+    # Workloads without a window count only the snapshots that were rebuilt from a difference (t >= 2, A_1 is
+    # sent whole outside the timed region); workloads with a window need every frame for the M-transform.
+    first = 1 if blk.window else 2
+    edges_per_step = sum(blk.nnz[first - 1:])
+
+    def one_step():
+        runner.run_resident(first=first)
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    value = edges_per_step / (elapsed / args.steps)
+
+    # per-stage durations: the same steps again with an event pair around every library call
+    runner.timer = StageTimer(dev)
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    totals = runner.timer.totals()
+    runner.timer = None
+    stages = {}
+    for name, (calls, ms) in totals.items():
+        per_step_calls = calls // args.steps
+        if name == "mproduct":
+            byts = algorithmic_bytes(blk, name)
+        else:
+            ts = range(2, T + 1) if name == "delta_rebuild" else range(first, T + 1)
+            reps = blk.layers if name in ("feature_transform", "spmm") else 1
+            byts = sum(algorithmic_bytes(blk, name, t) for t in ts) * reps / max(per_step_calls, 1)
+        avg_ms = ms / calls
+        stages[name] = {"calls_per_step": per_step_calls, "avg_ms": round(avg_ms, 4),
+                        "ms_per_step": round(ms / args.steps, 4), "algorithmic_bytes_per_call": int(byts),
+                        "algorithmic_GBps": round(byts / (avg_ms * 1e-3) / 1e9, 1)}
+    dominant = max(stages, key=lambda k: stages[k]["ms_per_step"])
+    achieved = stages[dominant]["algorithmic_GBps"]
+    kernels = {"spmm": "dgnn_spmm (spmm_short_kernel + spmm_long_kernel + spmm_long_reduce_kernel)",
+               "delta_rebuild": "dgnn_delta_rebuild (rowptr_kernel + merge_kernel)",
+               "feature_transform": "dgnn_feature_transform (xw kernel)", "mproduct": "dgnn_mproduct (mproduct_kernel)"}
+    roofline = {"bound": "hbm", "kernel": kernels[dominant], "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": committed_traffic(args.workload, dominant),
+                "avg_ms": stages[dominant]["avg_ms"],
+                "algorithmic_bytes_per_call": stages[dominant]["algorithmic_bytes_per_call"]}
+    all_bytes = sum(v["algorithmic_bytes_per_call"] * v["calls_per_step"] for v in stages.values())
+
+    out = {
+        "metric": "snapshot-edges/sec (delta rebuild + SpMM)", "value": value, "unit": "edges/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32" if wl.dtype == "f32" else "bf16 storage, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: N={blk.n}, T={T}, {wl.graph}, F={blk.f}, {wl.dtype}, layers={blk.layers}, "
+                               f"window={blk.window}, churn del {wl.del_frac:g} + add {wl.add_frac:g} per step",
+                   "snapshots_per_step": T - first + 1, "edges_per_step": edges_per_step,
+                   "nnz_first": blk.nnz[0], "nnz_last": blk.nnz[-1], "difference_lists": "resident in HBM",
+                   "timed": f"t={first}..{T}: " + ("delta rebuild (t>=2) + " if first == 1 else "delta rebuild + ")
+                            + f"{blk.layers}x(X W + SpMM)" + (" + M-transform" if blk.window else "")},
+        "roofline": roofline,
+        "stages": stages,
+        "hbm_frac_algorithmic_whole_step": round(all_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "generate_s": round(t_gen, 2),
+    }
+
+    if args.pinned:
+        for _ in range(args.warmup):
+            runner.run_from_pinned(first=first)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            runner.run_from_pinned(first=first)
+        torch.cuda.synchronize()
+        el = time.perf_counter() - t0
+        h2d = sum(8 * (d[0].numel() + d[2].numel()) for d in blk.deltas)
+        out["pinned_host_lists"] = {"value": edges_per_step / (el / args.steps), "unit": "edges/s",
+                                    "ms_per_step": el / args.steps * 1e3, "h2d_bytes_per_step": h2d,
+                                    "whole_snapshot_bytes_per_step": sum(4 * (z + blk.n + 1) for z in blk.nnz[1:])}
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, blk, first, args.cpu_seconds)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -10,6 +10,7 @@ No arithmetic of the method lives here; every step runs in the HIP kernels behin
 """
 from __future__ import annotations
 
+import contextlib
 from dataclasses import dataclass, field
 from typing import List, Optional, Tuple
 
@@ -62,6 +63,34 @@ def make_block(wl, device, gen_device=None, pinned: bool = False, T: Optional[in
                        colidx1=colidx1, deltas=deltas, x=x, w=w, pinned=pins if pinned else None)
 
 
+class StageTimer:
+    """Per-stage GPU time from event pairs recorded on the stream the kernels are launched on."""
+
+    def __init__(self, device):
+        self.device = device
+        self.pairs = []          # (stage, start, end)
+
+    @contextlib.contextmanager
+    def stage(self, name: str):
+        s = torch.cuda.Event(enable_timing=True)
+        e = torch.cuda.Event(enable_timing=True)
+        stream = torch.cuda.current_stream(self.device)
+        s.record(stream)
+        try:
+            yield
+        finally:
+            e.record(stream)
+            self.pairs.append((name, s, e))
+
+    def totals(self):
+        """{stage: (calls, total milliseconds)} -- call after a synchronize."""
+        out = {}
+        for name, s, e in self.pairs:
+            c, ms = out.get(name, (0, 0.0))
+            out[name] = (c + 1, ms + s.elapsed_time(e))
+        return out
+
+
 class BlockRunner:
     """Buffers and call sequence for the forward pass over one block."""
 
@@ -73,10 +102,11 @@ class BlockRunner:
         dt = blk.x[0].dtype
         cap = max(blk.nnz)
         self.cap = cap
-        # two CSR slots used alternately: A_{t-1} is read while A_t is written
-        self.rowptr = [torch.empty(n + 1, dtype=torch.int32, device=dev) for _ in range(2)]
-        self.colidx = [torch.empty(cap, dtype=torch.int32, device=dev) for _ in range(2)]
-        self.dinv = [torch.empty(n, dtype=torch.float32, device=dev) for _ in range(2)]
+        # CSR slots: slot 2 keeps A_1 for the whole life of the block (so a pass can be repeated), slots
+        # 0 and 1 are used alternately by A_2, A_3, ...: A_{t-1} is read while A_t is written
+        self.rowptr = [torch.empty(n + 1, dtype=torch.int32, device=dev) for _ in range(3)]
+        self.colidx = [torch.empty(cap, dtype=torch.int32, device=dev) for _ in range(3)]
+        self.dinv = [torch.empty(n, dtype=torch.float32, device=dev) for _ in range(3)]
         self.h = torch.empty((n, f), dtype=dt, device=dev)
         self.z_mid = torch.empty((n, f), dtype=dt, device=dev) if blk.layers > 1 else None
         self.keep_all_z = bool(blk.window) if keep_all_z is None else keep_all_z
@@ -89,6 +119,7 @@ class BlockRunner:
         self.ws_rebuild = torch.empty(ws_r, dtype=torch.uint8, device=dev)
         self.ws_spmm = torch.empty(ws_s, dtype=torch.uint8, device=dev)
         self.status = torch.zeros(blk.T + 1, dtype=torch.int32, device=dev)
+        self.timer: Optional[StageTimer] = None
         # staging for difference lists that arrive from pinned host memory (two sets, used alternately)
         self.stage = None
         if blk.pinned is not None:
@@ -99,42 +130,53 @@ class BlockRunner:
             self.consumed = [torch.cuda.Event() for _ in range(2)]
 
     # ------------------------------------------------------------------ pieces
+    def _stage(self, name: str):
+        return self.timer.stage(name) if self.timer is not None else contextlib.nullcontext()
+
+    @staticmethod
+    def slot_of(t: int) -> int:
+        return 2 if t == 1 else t % 2
+
     def load_first(self) -> None:
-        """Place A_1 in slot 0 and derive its dinv (outside any timed region: A_1 is sent whole)."""
+        """Place A_1 in its slot and derive its dinv (outside any timed region: A_1 is sent whole)."""
         blk = self.blk
-        self.rowptr[0].copy_(blk.rowptr1)
-        self.colidx[0][: blk.nnz[0]].copy_(blk.colidx1)
-        B.csr_dinv(self.rowptr[0], self.dinv[0])
+        self.rowptr[2].copy_(blk.rowptr1)
+        self.colidx[2][: blk.nnz[0]].copy_(blk.colidx1)
+        B.csr_dinv(self.rowptr[2], self.dinv[2])
 
     def rebuild(self, t: int, lists, validate: bool = False) -> None:
-        """A_t (slot (t-1) % 2) from A_{t-1} (the other slot) and the difference lists of step t (t >= 2)."""
+        """A_t from A_{t-1} and the difference lists of step t (t >= 2)."""
         blk = self.blk
-        src, dst = (t - 2) % 2, (t - 1) % 2
+        src, dst = self.slot_of(t - 1), self.slot_of(t)
         ar, ac, dr, dc = lists
         n_add, n_del = int(blk.deltas[t - 2][0].numel()), int(blk.deltas[t - 2][2].numel())
-        nnz = B.delta_rebuild(self.rowptr[src], self.colidx[src], blk.nnz[t - 2], ar, ac, n_add, dr, dc, n_del,
-                              self.rowptr[dst], self.colidx[dst], self.dinv[dst], self.ws_rebuild,
-                              flags=B.DGNN_VALIDATE if validate else 0, d_status=self.status[t:t + 1])
+        with self._stage("delta_rebuild"):
+            nnz = B.delta_rebuild(self.rowptr[src], self.colidx[src], blk.nnz[t - 2], ar, ac, n_add, dr, dc, n_del,
+                                  self.rowptr[dst], self.colidx[dst], self.dinv[dst], self.ws_rebuild,
+                                  flags=B.DGNN_VALIDATE if validate else 0, d_status=self.status[t:t + 1])
         assert nnz == blk.nnz[t - 1]
 
     def gcn(self, t: int) -> torch.Tensor:
         """All GCN layers on snapshot t; returns the frame Z_t."""
         blk = self.blk
-        slot = (t - 1) % 2
+        slot = self.slot_of(t)
         out = self.z[t - 1] if self.keep_all_z else self.z[0]
         cur = blk.x[t - 1]
         for layer in range(blk.layers):
-            B.feature_transform(cur, blk.w[layer], self.h)
+            with self._stage("feature_transform"):
+                B.feature_transform(cur, blk.w[layer], self.h)
             dst = out if layer == blk.layers - 1 else self.z_mid
-            B.spmm(self.rowptr[slot], self.colidx[slot], blk.nnz[t - 1], self.dinv[slot], self.h, dst,
-                   self.ws_spmm, flags=B.DGNN_RELU)
+            with self._stage("spmm"):
+                B.spmm(self.rowptr[slot], self.colidx[slot], blk.nnz[t - 1], self.dinv[slot], self.h, dst,
+                       self.ws_spmm, flags=B.DGNN_RELU)
             cur = dst
         return out
 
     def mix(self) -> None:
         """In-place M-transform over the stored frames."""
         if self.blk.window:
-            B.mproduct(self.z, self.z, self.blk.window)
+            with self._stage("mproduct"):
+                B.mproduct(self.z, self.z, self.blk.window)
 
     # ------------------------------------------------------------------ whole passes
     def run_resident(self, first: int = 1, validate: bool = False, on_snapshot=None) -> None:
@@ -148,7 +190,7 @@ class BlockRunner:
             if t >= first:
                 self.gcn(t)
             if on_snapshot is not None:
-                on_snapshot(t, (t - 1) % 2)
+                on_snapshot(t, self.slot_of(t))
         self.mix()
 
     def run_from_pinned(self, first: int = 1) -> None:
@@ -182,5 +224,5 @@ class BlockRunner:
         self.mix()
 
     def snapshot_to_host(self, t: int):
-        slot = (t - 1) % 2
+        slot = self.slot_of(t)
         return self.rowptr[slot].cpu().numpy(), self.colidx[slot][: self.blk.nnz[t - 1]].cpu().numpy()

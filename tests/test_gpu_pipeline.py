@@ -50,7 +50,7 @@ def test_pinned_host_pipeline_equals_resident():
     assert torch.equal(a.z, b.z)
     T = a.blk.T
     for t in (T - 1, T):
-        slot, nnz = (t - 1) % 2, a.blk.nnz[t - 1]
+        slot, nnz = a.slot_of(t), a.blk.nnz[t - 1]
         assert torch.equal(a.rowptr[slot], b.rowptr[slot])
         assert torch.equal(a.colidx[slot][:nnz], b.colidx[slot][:nnz])
 
