@@ -64,6 +64,7 @@ typedef enum { DGNN_F32 = 0, DGNN_BF16 = 1 } dgnn_dtype;
 
 /* Flags of dgnn_spmm. */
 #define DGNN_RELU 1u             /* apply sigma = ReLU to the aggregated rows (Eqn (2)) */
+#define DGNN_H_PRESCALED 2u      /* h already holds dinv[v] * H[v] (see dgnn_feature_transform) */
 
 /* Text for a dgnn_status value; never NULL; static storage. */
 const char *dgnn_strerror(int code);
@@ -121,13 +122,16 @@ int dgnn_delta_rebuild(int64_t n,
                        void *ws, size_t ws_bytes, uint32_t flags, int32_t *d_status, void *stream);
 
 /*
- * Dense factor of the GCN operation, Eqn (2): H = X W.
+ * Dense factor of the GCN operation, Eqn (2): H = X W, or H = diag(row_scale) X W.
  *   x [n][f_in], w [f_in][f_out], h [n][f_out], all of storage type dt, fp32 accumulation on
  *   the matrix cores.  W is a per-call argument, so a model that keeps one weight per
  *   timestep (Section "EvolveGCN") passes W_t.  h must not alias x.
+ *   row_scale [n] fp32, or NULL.  Passing the snapshot's dinv folds the right-hand D^(-1/2) of
+ *   Eqn (1) into the rows of H while they are still in registers, so that the aggregation
+ *   (dgnn_spmm with DGNN_H_PRESCALED) gathers rows of H only and no per-neighbour dinv.
  */
 int dgnn_feature_transform(const void *x, int64_t n, int32_t f_in, const void *w, int32_t f_out,
-                           void *h, dgnn_dtype dt, void *stream);
+                           const float *row_scale, void *h, dgnn_dtype dt, void *stream);
 
 /* Workspace size of dgnn_spmm in bytes (HOST out-parameter); depends on n, nnz and f only. */
 int dgnn_spmm_workspace(int64_t n, int64_t nnz, int32_t f, size_t *bytes);
@@ -140,7 +144,9 @@ int dgnn_spmm_workspace(int64_t n, int64_t nnz, int32_t f, size_t *bytes);
  *   dinv [n]                from dgnn_delta_rebuild or dgnn_csr_dinv; NULL means all ones
  *                           (plain A + I, no normalisation)
  *   h [n][f], z [n][f]      storage type dt; z must not alias h
- *   flags                   0 or DGNN_RELU
+ *   flags                   any of DGNN_RELU, DGNN_H_PRESCALED.  With DGNN_H_PRESCALED the rows of h
+ *                           are taken to be dinv[v] * H[v] already and only dinv[u] is applied:
+ *                           Z[u] = dinv[u] * sum over stored (u,v) of h[v]
  *   ws, ws_bytes            scratch of at least dgnn_spmm_workspace() bytes
  * The result does not depend on scheduling: no floating-point atomics are used.
  */

@@ -9,5 +9,5 @@ from .binding import (  # noqa: F401
     DgnnError, build_library, library_path, load_library,
     csr_dinv, delta_h2d, delta_rebuild, delta_rebuild_workspace, feature_transform,
     spmm, spmm_workspace, mproduct, strerror,
-    DGNN_VALIDATE, DGNN_RELU, DGNN_F32, DGNN_BF16,
+    DGNN_VALIDATE, DGNN_RELU, DGNN_H_PRESCALED, DGNN_F32, DGNN_BF16,
 )

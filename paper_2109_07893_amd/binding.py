@@ -19,6 +19,7 @@ _LIB_PATH = os.path.join(_CSRC, "libdgnn.so")
 DGNN_F32, DGNN_BF16 = 0, 1
 DGNN_VALIDATE = 1
 DGNN_RELU = 1
+DGNN_H_PRESCALED = 2
 
 EXPORTS = (
     "dgnn_strerror", "dgnn_csr_dinv", "dgnn_delta_h2d", "dgnn_delta_rebuild_workspace",
@@ -72,7 +73,7 @@ def load_library():
     lib.dgnn_delta_rebuild_workspace.argtypes = [_i64, _i64, _i64, _i64, ctypes.POINTER(_sz)]
     lib.dgnn_delta_rebuild.argtypes = [_i64, _vp, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _i64,
                                        _vp, _vp, _i64, ctypes.POINTER(_i64), _vp, _vp, _sz, _u32, _vp, _vp]
-    lib.dgnn_feature_transform.argtypes = [_vp, _i64, _i32, _vp, _i32, _vp, ctypes.c_int, _vp]
+    lib.dgnn_feature_transform.argtypes = [_vp, _i64, _i32, _vp, _i32, _vp, _vp, ctypes.c_int, _vp]
     lib.dgnn_spmm_workspace.argtypes = [_i64, _i64, _i32, ctypes.POINTER(_sz)]
     lib.dgnn_spmm.argtypes = [_i64, _i64, _vp, _vp, _vp, _vp, _i32, _vp, ctypes.c_int, _u32, _vp, _sz, _vp]
     lib.dgnn_mproduct.argtypes = [_vp, _vp, _i64, _i64, _i32, _i32, _vp, ctypes.c_int, _vp]
@@ -162,8 +163,8 @@ def delta_rebuild(rowptr_prev, colidx_prev, nnz_prev: int, add_row, add_col, n_a
     return int(nnz_next.value)
 
 
-def feature_transform(x: torch.Tensor, w: torch.Tensor, h: torch.Tensor) -> None:
-    """H = X W."""
+def feature_transform(x: torch.Tensor, w: torch.Tensor, h: torch.Tensor, row_scale: Optional[torch.Tensor] = None) -> None:
+    """H = X W, or diag(row_scale) X W."""
     dt = _dtype_code(x)
     if w.dtype != x.dtype or h.dtype != x.dtype:
         raise TypeError("x, w, h must share one dtype")
@@ -171,8 +172,12 @@ def feature_transform(x: torch.Tensor, w: torch.Tensor, h: torch.Tensor) -> None
     f_out = w.shape[1]
     if w.shape[0] != f_in or tuple(h.shape) != (n, f_out):
         raise ValueError("shape mismatch in feature_transform")
-    _check(load_library().dgnn_feature_transform(_ptr(x), n, f_in, _ptr(w), f_out, _ptr(h), dt, _stream(x)),
-           "dgnn_feature_transform")
+    if row_scale is not None:
+        _need(row_scale, torch.float32, "row_scale")
+        if row_scale.numel() != n:
+            raise ValueError("row_scale must have one entry per row")
+    _check(load_library().dgnn_feature_transform(_ptr(x), n, f_in, _ptr(w), f_out, _ptr(row_scale), _ptr(h), dt,
+                                                 _stream(x)), "dgnn_feature_transform")
 
 
 def spmm_workspace(n: int, nnz: int, f: int) -> int:

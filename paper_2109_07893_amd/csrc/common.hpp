@@ -29,6 +29,25 @@ __device__ __forceinline__ int lower_bound(const int32_t *__restrict__ a, int lo
     return lo;
 }
 
+// Largest r in [0, n) with rowptr[r] <= key (-1 if there is none), for a non-decreasing rowptr.
+// A 64-ary search done by one whole wavefront: every lane of the wavefront must call it with the
+// same arguments; each round probes 64 evenly spaced entries at once, so 2^24 rows take four
+// dependent loads instead of twenty-four.
+__device__ __forceinline__ int wave_find_row(const int32_t *__restrict__ rowptr, int n, int key, int lane) {
+    int lo = 0, hi = n;   // the first index whose entry exceeds key lies in [lo, hi]
+    while (hi > lo) {
+        const int step = (hi - lo + kWave - 1) / kWave;
+        const int idx = lo + lane * step;
+        const bool le = idx < hi && rowptr[idx] <= key;
+        const int m = __popcll(__ballot(le));   // monotone: exactly lanes 0 .. m-1 hold entries <= key
+        if (m == 0) { hi = lo; break; }
+        const int nlo = lo + (m - 1) * step + 1;
+        hi = min(lo + m * step, hi);
+        lo = nlo;
+    }
+    return lo - 1;
+}
+
 // Inclusive wavefront scans over 64 lanes.
 __device__ __forceinline__ int wave_scan_add(int v, int lane) {
 #pragma unroll

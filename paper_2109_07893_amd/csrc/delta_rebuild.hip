@@ -135,14 +135,9 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(
     const int i1 = (int)min((int64_t)i0 + kMergeTile, (int64_t)nnz_prev);
     const int cnt = i1 - i0;
 
-    if (tid < 2) {   // the rows that hold the first and the last entry of the tile
-        int key = tid == 0 ? i0 : i1 - 1;
-        int lo = 0, hi = n;
-        while (lo < hi) {
-            int mid = lo + ((hi - lo) >> 1);
-            if (rowptr_prev[mid] <= key) lo = mid + 1; else hi = mid;
-        }
-        s_rows[tid] = max(lo - 1, 0);
+    if (wave < 2) {   // the rows that hold the first and the last entry of the tile, one wavefront each
+        int r = wave_find_row(rowptr_prev, n, wave == 0 ? i0 : i1 - 1, lane);
+        if (lane == 0) s_rows[wave] = max(r, 0);
     }
     for (int p = tid; p < kMergeTile; p += kMergeThreads) s_rowid[p] = 0;
     __syncthreads();

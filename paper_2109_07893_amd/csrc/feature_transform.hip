@@ -26,7 +26,8 @@ constexpr int kWavesPerBlock = kThreads / kWave;
 
 template <int FIN, int FOUT>
 __global__ __launch_bounds__(kThreads) void xw_f32_kernel(const float *__restrict__ x, const float *__restrict__ w,
-                                                          float *__restrict__ h, int64_t n, int64_t n_tiles) {
+                                                          const float *__restrict__ row_scale, float *__restrict__ h,
+                                                          int64_t n, int64_t n_tiles) {
     constexpr int NT = (FOUT + 31) / 32;   // 32-wide column tiles (FOUT = 16 is zero-padded)
     constexpr int LD = NT * 32;
     constexpr int KH = FIN / 2;            // k values owned by one lane
@@ -67,13 +68,19 @@ __global__ __launch_bounds__(kThreads) void xw_f32_kernel(const float *__restric
                 acc[jt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[jt], 0, 0, 0);
             }
         }
+        float scale[16];   // row_scale of the 16 rows this lane stores
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int64_t r = tile * 32 + 8 * (v / 4) + 4 * hh + (v % 4);
+            scale[v] = (row_scale && r < n) ? row_scale[r] : 1.0f;
+        }
 #pragma unroll
         for (int jt = 0; jt < NT; ++jt) {
             const int col = jt * 32 + i;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int64_t r = tile * 32 + 8 * (v / 4) + 4 * hh + (v % 4);
-                if (r < n && col < FOUT) h[r * FOUT + col] = acc[jt][v];
+                if (r < n && col < FOUT) h[r * FOUT + col] = acc[jt][v] * scale[v];
             }
         }
     }
@@ -81,7 +88,8 @@ __global__ __launch_bounds__(kThreads) void xw_f32_kernel(const float *__restric
 
 template <int FIN, int FOUT>
 __global__ __launch_bounds__(kThreads) void xw_bf16_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ w,
-                                                           uint16_t *__restrict__ h, int64_t n, int64_t n_tiles) {
+                                                           const float *__restrict__ row_scale, uint16_t *__restrict__ h,
+                                                           int64_t n, int64_t n_tiles) {
     constexpr int NT = (FOUT + 31) / 32;
     constexpr int KH = FIN / 2;            // bf16 values owned by one lane
     constexpr int KS = KH / 8;             // MFMA steps of depth 16 (8 per lane half)
@@ -124,29 +132,35 @@ __global__ __launch_bounds__(kThreads) void xw_bf16_kernel(const uint16_t *__res
                 acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s], bv, acc[jt], 0, 0, 0);
             }
         }
+        float scale[16];   // row_scale of the 16 rows this lane stores
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int64_t r = tile * 32 + 8 * (v / 4) + 4 * hh + (v % 4);
+            scale[v] = (row_scale && r < n) ? row_scale[r] : 1.0f;
+        }
 #pragma unroll
         for (int jt = 0; jt < NT; ++jt) {
             const int col = jt * 32 + i;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int64_t r = tile * 32 + 8 * (v / 4) + 4 * hh + (v % 4);
-                if (r < n && col < FOUT) h[r * FOUT + col] = (uint16_t)f32_to_bf16(acc[jt][v]);
+                if (r < n && col < FOUT) h[r * FOUT + col] = (uint16_t)f32_to_bf16(acc[jt][v] * scale[v]);
             }
         }
     }
 }
 
 template <int FIN, int FOUT>
-int launch(const void *x, const void *w, void *h, int64_t n, dgnn_dtype dt, hipStream_t s) {
+int launch(const void *x, const void *w, const float *row_scale, void *h, int64_t n, dgnn_dtype dt, hipStream_t s) {
     const int64_t n_tiles = (n + 31) / 32;
     int64_t blocks = (n_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
     if (blocks > 4096) blocks = 4096;
     if (dt == DGNN_F32) {
         hipLaunchKernelGGL((xw_f32_kernel<FIN, FOUT>), dim3((unsigned)blocks), dim3(kThreads), 0, s,
-                           static_cast<const float *>(x), static_cast<const float *>(w), static_cast<float *>(h), n, n_tiles);
+                           static_cast<const float *>(x), static_cast<const float *>(w), row_scale, static_cast<float *>(h), n, n_tiles);
     } else {
         hipLaunchKernelGGL((xw_bf16_kernel<FIN, FOUT>), dim3((unsigned)blocks), dim3(kThreads), 0, s,
-                           static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(w),
+                           static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(w), row_scale,
                            static_cast<uint16_t *>(h), n, n_tiles);
     }
     DGNN_RETURN_IF_LAUNCH_FAILED();
@@ -154,12 +168,13 @@ int launch(const void *x, const void *w, void *h, int64_t n, dgnn_dtype dt, hipS
 }
 
 template <int FIN>
-int launch_out(int32_t f_out, const void *x, const void *w, void *h, int64_t n, dgnn_dtype dt, hipStream_t s) {
+int launch_out(int32_t f_out, const void *x, const void *w, const float *row_scale, void *h, int64_t n, dgnn_dtype dt,
+               hipStream_t s) {
     switch (f_out) {
-        case 16: return launch<FIN, 16>(x, w, h, n, dt, s);
-        case 32: return launch<FIN, 32>(x, w, h, n, dt, s);
-        case 64: return launch<FIN, 64>(x, w, h, n, dt, s);
-        case 128: return launch<FIN, 128>(x, w, h, n, dt, s);
+        case 16: return launch<FIN, 16>(x, w, row_scale, h, n, dt, s);
+        case 32: return launch<FIN, 32>(x, w, row_scale, h, n, dt, s);
+        case 64: return launch<FIN, 64>(x, w, row_scale, h, n, dt, s);
+        case 128: return launch<FIN, 128>(x, w, row_scale, h, n, dt, s);
         default: return DGNN_ERR_SHAPE;
     }
 }
@@ -167,7 +182,7 @@ int launch_out(int32_t f_out, const void *x, const void *w, void *h, int64_t n, 
 }  // namespace
 
 extern "C" int dgnn_feature_transform(const void *x, int64_t n, int32_t f_in, const void *w, int32_t f_out,
-                                      void *h, dgnn_dtype dt, void *stream) {
+                                      const float *row_scale, void *h, dgnn_dtype dt, void *stream) {
     if (!x || !w || !h) return DGNN_ERR_NULL;
     if (n <= 0 || !supported_width(f_in) || !supported_width(f_out)) return DGNN_ERR_SHAPE;
     if (dt != DGNN_F32 && dt != DGNN_BF16) return DGNN_ERR_SHAPE;
@@ -176,10 +191,10 @@ extern "C" int dgnn_feature_transform(const void *x, int64_t n, int32_t f_in, co
     if (x == h) return DGNN_ERR_ALIAS;
     hipStream_t s = (hipStream_t)stream;
     switch (f_in) {
-        case 16: return launch_out<16>(f_out, x, w, h, n, dt, s);
-        case 32: return launch_out<32>(f_out, x, w, h, n, dt, s);
-        case 64: return launch_out<64>(f_out, x, w, h, n, dt, s);
-        case 128: return launch_out<128>(f_out, x, w, h, n, dt, s);
+        case 16: return launch_out<16>(f_out, x, w, row_scale, h, n, dt, s);
+        case 32: return launch_out<32>(f_out, x, w, row_scale, h, n, dt, s);
+        case 64: return launch_out<64>(f_out, x, w, row_scale, h, n, dt, s);
+        case 128: return launch_out<128>(f_out, x, w, row_scale, h, n, dt, s);
         default: return DGNN_ERR_SHAPE;
     }
 }

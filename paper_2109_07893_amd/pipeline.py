@@ -163,12 +163,13 @@ class BlockRunner:
         out = self.z[t - 1] if self.keep_all_z else self.z[0]
         cur = blk.x[t - 1]
         for layer in range(blk.layers):
+            # the right-hand D^(-1/2) of the normalised adjacency is folded into the rows of H
             with self._stage("feature_transform"):
-                B.feature_transform(cur, blk.w[layer], self.h)
+                B.feature_transform(cur, blk.w[layer], self.h, row_scale=self.dinv[slot])
             dst = out if layer == blk.layers - 1 else self.z_mid
             with self._stage("spmm"):
                 B.spmm(self.rowptr[slot], self.colidx[slot], blk.nnz[t - 1], self.dinv[slot], self.h, dst,
-                       self.ws_spmm, flags=B.DGNN_RELU)
+                       self.ws_spmm, flags=B.DGNN_RELU | B.DGNN_H_PRESCALED)
             cur = dst
         return out
 

@@ -76,12 +76,12 @@ def test_delta_rebuild_argument_errors(lib):
 
 def test_feature_transform_argument_errors(lib):
     f = lib.dgnn_feature_transform
-    assert f(None, 10, 32, FAKE, 32, FAKE + 4096, 0, None) == -1
-    assert f(FAKE, 0, 32, FAKE, 32, FAKE + 4096, 0, None) == -2
-    assert f(FAKE, 10, 24, FAKE, 32, FAKE + 4096, 0, None) == -2
-    assert f(FAKE, 10, 32, FAKE, 32, FAKE + 4096, 7, None) == -2
-    assert f(FAKE + 4, 10, 32, FAKE, 32, FAKE + 4096, 0, None) == -7
-    assert f(FAKE, 10, 32, FAKE + 64, 32, FAKE, 0, None) == -5
+    assert f(None, 10, 32, FAKE, 32, None, FAKE + 4096, 0, None) == -1
+    assert f(FAKE, 0, 32, FAKE, 32, None, FAKE + 4096, 0, None) == -2
+    assert f(FAKE, 10, 24, FAKE, 32, None, FAKE + 4096, 0, None) == -2
+    assert f(FAKE, 10, 32, FAKE, 32, None, FAKE + 4096, 7, None) == -2
+    assert f(FAKE + 4, 10, 32, FAKE, 32, None, FAKE + 4096, 0, None) == -7
+    assert f(FAKE, 10, 32, FAKE + 64, 32, None, FAKE, 0, None) == -5
 
 
 def test_spmm_argument_errors(lib):
@@ -95,7 +95,7 @@ def test_spmm_argument_errors(lib):
                  a["wsb"], None)
 
     assert call(rp=None) == -1 and call(z=None) == -1 and call(ws=None) == -1
-    assert call(f=20) == -2 and call(flags=4) == -2 and call(n=-1) == -2
+    assert call(f=20) == -2 and call(flags=4) == -2 and call(n=-1) == -2 and call(nnz=0) == -2
     assert call(wsb=16) == -3
     assert call(h=FAKE + 8) == -7
     assert call(z=FAKE) == -5

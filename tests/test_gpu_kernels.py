@@ -173,6 +173,19 @@ def test_feature_transform_more_rows_than_one_grid_pass(dtype, f):
     assert_close(to_f64(h), oracle.xw(to_f64(x), to_f64(w)), dtype, f"xw n={n} f={f}")
 
 
+@pytest.mark.parametrize("dtype,f", [(torch.float32, 32), (torch.float32, 64), (torch.bfloat16, 128), (torch.bfloat16, 16)])
+def test_feature_transform_with_row_scale(dtype, f):
+    n = 4099
+    gen = torch.Generator().manual_seed(f + 1)
+    x = torch.randn((n, f), generator=gen).to(dtype)
+    w = (torch.rand((f, f), generator=gen) - 0.5).to(dtype)
+    scale = torch.rand(n, generator=gen) + 0.1
+    h = torch.full((n, f), float("nan"), dtype=dtype, device=DEV)
+    dg.feature_transform(x.to(DEV), w.to(DEV), h, row_scale=scale.to(DEV))
+    expect = oracle.xw(to_f64(x), to_f64(w)) * to_f64(scale)[:, None]      # diag(scale) (X W)
+    assert_close(to_f64(h), expect, dtype, f"scaled xw f={f}")
+
+
 def test_feature_transform_identity_is_exact():
     x = torch.randn((777, 64))
     h = torch.empty((777, 64), device=DEV)
@@ -181,7 +194,7 @@ def test_feature_transform_identity_is_exact():
 
 
 # ------------------------------------------------------------------------------- A~ H
-def gpu_spmm(rp, ci, h, relu, use_dinv=True):
+def gpu_spmm(rp, ci, h, relu, use_dinv=True, prescaled=False):
     n, f = h.shape
     rp_d, ci_d = dev_i32(rp), dev_i32(ci)
     dinv = None
@@ -190,7 +203,8 @@ def gpu_spmm(rp, ci, h, relu, use_dinv=True):
         dg.csr_dinv(rp_d, dinv)
     z = torch.full((n, f), float("nan"), dtype=h.dtype, device=DEV)
     ws = torch.empty(dg.spmm_workspace(n, int(ci.size), f), dtype=torch.uint8, device=DEV)
-    dg.spmm(rp_d, ci_d, int(ci.size), dinv, h.to(DEV), z, ws, flags=dg.DGNN_RELU if relu else 0)
+    flags = (dg.DGNN_RELU if relu else 0) | (dg.DGNN_H_PRESCALED if prescaled else 0)
+    dg.spmm(rp_d, ci_d, int(ci.size), dinv, h.to(DEV), z, ws, flags=flags)
     torch.cuda.synchronize()
     return z
 
@@ -222,6 +236,54 @@ def test_spmm_power_law_with_long_rows(dtype, f, relu):
     h = torch.randn((n, f), generator=torch.Generator().manual_seed(f)).to(dtype)
     z = gpu_spmm(rp, ci, h, relu)
     assert_close(to_f64(z), oracle.spmm(rp, ci, to_f64(h), relu=relu), dtype, f"spmm f={f}")
+
+
+@pytest.mark.parametrize("dtype,f", [(torch.float32, 32), (torch.bfloat16, 128)])
+def test_spmm_prescaled_rows(dtype, f):
+    """With DGNN_H_PRESCALED the rows handed over are dinv[v] H[v]; the result is the same A~ H."""
+    n = 1 << 13
+    rp, ci = graph_with_long_rows(n, 2)
+    h = torch.randn((n, f), generator=torch.Generator().manual_seed(3)).to(dtype)
+    dinv = 1.0 / np.sqrt(np.diff(rp).astype(np.float64))
+    pre = torch.tensor(to_f64(h) * dinv[:, None]).to(dtype)
+    z = gpu_spmm(rp, ci, pre, True, prescaled=True)
+    expect = np.maximum(dinv[:, None] * oracle.spmm(rp, ci, to_f64(pre), val=np.ones(ci.size)), 0.0)
+    assert_close(to_f64(z), expect, dtype, "prescaled")
+    assert_close(to_f64(z), oracle.spmm(rp, ci, to_f64(h), relu=True), dtype, "prescaled vs definition")
+
+
+def test_spmm_rows_without_entries_give_zero():
+    """Plain A H (no dinv) on a CSR with empty rows at the start, inside, at tile edges and at the end."""
+    n, f = 5000, 32
+    rng = np.random.default_rng(8)
+    lens = rng.integers(0, 6, n)
+    lens[:3] = 0
+    lens[-4:] = 0
+    lens[100:140] = 0
+    lens[2000] = 3000                                                    # a row over several tiles, then empties
+    lens[2001:2010] = 0
+    rp = np.zeros(n + 1, np.int32)
+    rp[1:] = np.cumsum(lens)
+    ci = np.concatenate([np.sort(rng.choice(n, l, replace=False)) for l in lens if l]).astype(np.int32)
+    h = torch.randn((n, f), generator=torch.Generator().manual_seed(6))
+    z = gpu_spmm(rp, ci, h, False, use_dinv=False)
+    expect = oracle.spmm(rp, ci, to_f64(h), val=np.ones(ci.size))
+    assert_close(to_f64(z), expect, torch.float32, "empty rows")
+    assert np.all(to_f64(z)[lens == 0] == 0.0)
+
+
+def test_spmm_rows_ending_exactly_on_tile_edges():
+    """fp32 F=32 uses tiles of 1024 entries: rows of 1024, 2048, 1 and 1023 entries laid end to end."""
+    n, f = 4096, 32
+    rng = np.random.default_rng(10)
+    lens = np.ones(n, np.int64)
+    lens[:8] = [1024, 2048, 1, 1023, 1024, 1, 1, 3070]
+    rp = np.zeros(n + 1, np.int32)
+    rp[1:] = np.cumsum(lens)
+    ci = np.concatenate([np.sort(rng.choice(n, l, replace=False)) for l in lens]).astype(np.int32)
+    h = torch.randn((n, f), generator=torch.Generator().manual_seed(7))
+    z = gpu_spmm(rp, ci, h, True)
+    assert_close(to_f64(z), oracle.spmm(rp, ci, to_f64(h), relu=True), torch.float32, "tile edges")
 
 
 def test_spmm_uniform_graph_ragged_tail_and_closed_form():
