@@ -7,13 +7,10 @@
 // and "#entries with row < r" is a lower bound in a sorted list.  Every tile is independent:
 //   1. rowptr_kernel  (tiles of rows)         new row pointers, dinv = (row length)^(-1/2),
 //                                             and add_ptr[r] = #added with row < r (workspace);
-//   2. merge_kernel   (tiles of old entries)  every old entry finds its new position
-//        pos = rowptr_next[r] + (i - rowptr_prev[r]) - #deleted in row with col < c
-//                                                    + #added   in row with col < c
-//      and writes itself there unless deleted; the added entries that fall between an old entry
-//      and its predecessor in the row are written by that old entry's lane.  Tiles hold equal
-//      numbers of old entries, so hub rows of power-law graphs are spread over many workgroups,
-//      and untouched rows cost one coalesced read and one coalesced write per entry.
+//   2. merge_kernel   (ranges of old entries) streams A_prev's column indices once: deleted entries
+//      are struck out, added entries slotted in, a prefix sum per sub-tile gives the positions.
+//      Ranges hold equal numbers of old entries, so hub rows of power-law graphs are spread over
+//      many wavefronts, and an old entry costs one coalesced read and one coalesced write.
 #include "common.hpp"
 
 namespace {
@@ -24,9 +21,10 @@ constexpr int kRowThreads = 256;
 constexpr int kRowsPerThread = 4;
 constexpr int kRowTile = kRowThreads * kRowsPerThread;
 
-constexpr int kMergeThreads = 256;
-constexpr int kMergeItems = 4;
-constexpr int kMergeTile = kMergeThreads * kMergeItems;
+constexpr int kPerLane = 8;                  // old entries per lane and sub-tile of the merge
+constexpr int kSub = kWave * kPerLane;       // old entries per sub-tile, at most
+constexpr int kRange = kSub * 16;            // old entries streamed by one wavefront
+constexpr int kRowCap = 2 * kWave;           // consecutive rows staged per sub-tile
 
 __device__ __forceinline__ void report(int32_t *status, int code) {
     if (!status) return;
@@ -116,121 +114,219 @@ __global__ __launch_bounds__(kRowThreads) void rowptr_kernel(
     }
 }
 
-__global__ __launch_bounds__(kMergeThreads) void merge_kernel(
+// First position in the ascending LDS array a[lo, hi) whose value is >= key (STRICT = false) or > key.
+template <bool STRICT>
+__device__ __forceinline__ int lds_bound(const int *a, int lo, int hi, int key) {
+    while (lo < hi) {
+        const int mid = lo + ((hi - lo) >> 1);
+        const bool left = STRICT ? a[mid] <= key : a[mid] < key;
+        if (left) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+// One wavefront streams a contiguous range of old entries in sub-tiles of up to kSub entries.
+// The work per OLD entry is a load, a position from a prefix sum, and a store; everything that
+// needs a search is done per DIFFERENCE entry, of which there are few:
+//   - kRowCap consecutive rows (rowptr_prev, rowptr_next, add_ptr) are staged in LDS; the row that
+//     holds the range's first entry is searched once, afterwards the rows simply follow on;
+//   - the sub-tile's column indices are staged in LDS; each deleted entry that falls into the
+//     sub-tile finds its old entry there by binary search and marks it dead, each added entry
+//     finds the old entry it goes in front of (its slot) and counts itself there; both lists
+//     are consumed in order through two cursors, so no search of the lists is ever needed;
+//   - one prefix sum over (alive, added-before) gives every old entry and every slot its place
+//     relative to the sub-tile's first output position, which follows from rowptr_next.
+// Lane l owns entries l, l + 64, ... of the sub-tile, so loads and stores coalesce; the column
+// indices of the next sub-tile are fetched while this one is placed.
+__global__ __launch_bounds__(kWave) void merge_kernel(
     int n, const int32_t *__restrict__ rowptr_prev, const int32_t *__restrict__ colidx_prev, int nnz_prev,
-    const int32_t *__restrict__ add_col, int n_add, const int32_t *__restrict__ del_col, int n_del,
+    const int32_t *__restrict__ add_row, const int32_t *__restrict__ add_col, int n_add,
+    const int32_t *__restrict__ del_row, const int32_t *__restrict__ del_col, int n_del,
     const int32_t *__restrict__ rowptr_next, const int32_t *__restrict__ add_ptr,
-    int32_t *__restrict__ colidx_next, int cap_next, int32_t *status) {
-    __shared__ int s_rowid[kMergeTile];
-    __shared__ int s_la[kMergeTile];
-    __shared__ int s_rp[kMergeTile + 2];
-    __shared__ int s_rn[kMergeTile + 2];
-    __shared__ int s_ap[kMergeTile + 2];
-    __shared__ int s_rows[2];
-    __shared__ int s_wmax[kMergeThreads / kWave];
+    int32_t *__restrict__ colidx_next, int cap_next) {
+    __shared__ int s_col[kSub];
+    __shared__ int s_mark[kSub + kWave];    // bit 0: deleted; bits 1..: added entries that go right before this slot
+    __shared__ int s_start[kSub + kWave];   // outputs (kept + added) that precede the slot's block
+    __shared__ int s_rp[kRowCap];
+    __shared__ int s_rn[kRowCap];
+    __shared__ int s_ap[kRowCap];
 
-    const int tid = threadIdx.x;
-    const int lane = tid & (kWave - 1), wave = tid / kWave;
-    const int i0 = (int)((int64_t)blockIdx.x * kMergeTile);
-    const int i1 = (int)min((int64_t)i0 + kMergeTile, (int64_t)nnz_prev);
-    const int cnt = i1 - i0;
+    const int lane = threadIdx.x;
+    const int e_begin = (int)((int64_t)blockIdx.x * kRange);
+    const int e_end = (int)min((int64_t)e_begin + kRange, (int64_t)nnz_prev);
+    int k_cur = max(wave_find_row(rowptr_prev, n, e_begin, lane), 0);   // a row with rowptr <= e_begin
 
-    if (wave < 2) {   // the rows that hold the first and the last entry of the tile, one wavefront each
-        int r = wave_find_row(rowptr_prev, n, wave == 0 ? i0 : i1 - 1, lane);
-        if (lane == 0) s_rows[wave] = max(r, 0);
-    }
-    for (int p = tid; p < kMergeTile; p += kMergeThreads) s_rowid[p] = 0;
-    __syncthreads();
-    const int r_first = s_rows[0];
-    const int nr = s_rows[1] - r_first + 1;
-    if (nr > kMergeTile || nr < 1) {   // only possible when A_prev has empty rows
-        if (tid == 0) report(status, DGNN_BAD_EMPTY_ROW);
-        return;
-    }
-    for (int k = tid; k <= nr; k += kMergeThreads) {
-        int r = r_first + k;
-        s_rp[k] = rowptr_prev[r];
-        s_rn[k] = rowptr_next[r];
-        s_ap[k] = add_ptr[r];
-    }
-    __syncthreads();
-    for (int k = tid + 1; k < nr; k += kMergeThreads) {   // rows that start inside the tile
-        unsigned p = (unsigned)(s_rp[k] - i0);
-        if (p < (unsigned)cnt) atomicMax(&s_rowid[p], k);
-    }
-    __syncthreads();
-    {   // inclusive max-scan turns the row heads into a row id per entry
-        int v[kMergeItems];
-        int m = 0;
+    int c_next[kPerLane];
 #pragma unroll
-        for (int k = 0; k < kMergeItems; ++k) {
-            m = max(m, s_rowid[tid * kMergeItems + k]);
-            v[k] = m;
+    for (int j = 0; j < kPerLane; ++j) {
+        const int i = e_begin + lane + j * kWave;
+        c_next[j] = i < e_end ? colidx_prev[i] : 0;
+    }
+    int a_cur = 0, d_cur = 0;   // first added / deleted entry not yet placed
+    int e = e_begin;
+    while (e < e_end) {
+        // ---- stage rows k_cur .. k_cur + kRowCap - 1
+        int le_e = 0;             // staged rows that begin at or before e
+        int v_[kRowCap / kWave];
+#pragma unroll
+        for (int round = 0; round < kRowCap / kWave; ++round) {
+            const int t = lane + round * kWave;
+            const int k = k_cur + t;
+            const bool ok = k <= n;
+            const int v = ok ? rowptr_prev[k] : 0x7fffffff;
+            v_[round] = v;
+            s_rp[t] = v;
+            s_rn[t] = ok ? rowptr_next[k] : 0;
+            s_ap[t] = ok ? add_ptr[k] : 0;
+            le_e += __popcll(__ballot(v <= e));
         }
-        int inc = wave_scan_max(m, lane);
-        if (lane == kWave - 1) s_wmax[wave] = inc;
-        int before = __shfl_up(inc, 1, kWave);
-        if (lane == 0) before = 0;
+        const int t0 = max(le_e - 1, 0);                 // the staged row that holds entry e
+        if (t0 >= kRowCap - 1) {                         // only rows without entries were staged: move on
+            k_cur += kRowCap - 1;
+            __syncthreads();
+            continue;
+        }
+        const int v_last = __shfl(v_[kRowCap / kWave - 1], kWave - 1, kWave);   // start of the last staged row (> e)
+        const int e_stop = min(min(e + kSub, e_end), v_last);
+        const int cnt = e_stop - e;
+        int le_stop = 0, lt_stop = 0;
+#pragma unroll
+        for (int round = 0; round < kRowCap / kWave; ++round) {
+            le_stop += __popcll(__ballot(v_[round] <= e_stop));
+            lt_stop += __popcll(__ballot(v_[round] < e_stop));
+        }
+        const int t_last = lt_stop - 1;                  // last staged row with entries in this sub-tile
+        int c_[kPerLane];
+#pragma unroll
+        for (int j = 0; j < kPerLane; ++j) {
+            c_[j] = c_next[j];
+            s_col[lane + j * kWave] = c_[j];
+            s_mark[lane + j * kWave] = 0;
+        }
+        s_mark[kSub + lane] = 0;
+        // the column indices that follow e_stop are fetched while this sub-tile is placed
+#pragma unroll
+        for (int j = 0; j < kPerLane; ++j) {
+            const int i = e_stop + lane + j * kWave;
+            c_next[j] = i < e_end ? colidx_prev[i] : 0;
+        }
         __syncthreads();
-        for (int w = 0; w < wave; ++w) before = max(before, s_wmax[w]);
-#pragma unroll
-        for (int k = 0; k < kMergeItems; ++k) s_rowid[tid * kMergeItems + k] = max(v[k], before);
-    }
-    __syncthreads();
 
-    int c_[kMergeItems], ld_[kMergeItems], la_[kMergeItems];
-    bool dead_[kMergeItems];
-#pragma unroll
-    for (int k = 0; k < kMergeItems; ++k) {
-        const int p = tid + k * kMergeThreads;
-        c_[k] = 0; ld_[k] = 0; la_[k] = 0; dead_[k] = false;
-        if (p < cnt) {
-            const int rr = s_rowid[p];
-            const int as = s_ap[rr], ae = s_ap[rr + 1];
-            const int ds = s_rp[rr] + as - s_rn[rr];
-            const int de = s_rp[rr + 1] + ae - s_rn[rr + 1];
-            const int c = colidx_prev[i0 + p];
-            c_[k] = c;
-            if (as >= 0 && as < ae && ae <= n_add) la_[k] = lower_bound(add_col, as, ae, c) - as;
-            if (ds >= 0 && ds < de && de <= n_del) {
-                int q = lower_bound(del_col, ds, de, c);
-                ld_[k] = q - ds;
-                dead_[k] = q < de && del_col[q] == c;
+        const int as0 = s_ap[t0], ds0 = s_rp[t0] + s_ap[t0] - s_rn[t0];
+        if (e == e_begin) {       // cursors of a range that starts inside a row: one search each
+            a_cur = as0;
+            d_cur = ds0;
+            if (s_rp[t0] < e) {
+                const int ae0 = s_ap[t0 + 1], de0 = s_rp[t0 + 1] + ae0 - s_rn[t0 + 1];
+                if (as0 >= 0 && as0 < ae0 && ae0 <= n_add) a_cur = lower_bound(add_col, as0, ae0, colidx_prev[e - 1]);
+                if (ds0 >= 0 && ds0 < de0 && de0 <= n_del) d_cur = lower_bound(del_col, ds0, de0, s_col[0]);
             }
-            s_la[p] = la_[k];
         }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < kMergeItems; ++k) {
-        const int p = tid + k * kMergeThreads;
-        if (p >= cnt) continue;
-        const int i = i0 + p;
-        const int rr = s_rowid[p];
-        const int rp = s_rp[rr];
-        const int as = s_ap[rr], ae = s_ap[rr + 1];
-        const int base = s_rn[rr] + (i - rp) - ld_[k];
-        if (as >= 0 && as < ae && ae <= n_add) {
-            int j = 0;                                   // adds of the row that precede this entry's predecessor
-            if (i > rp) j = p > 0 ? s_la[p - 1] : lower_bound(add_col, as, ae, colidx_prev[i - 1]) - as;
-            for (; j < la_[k]; ++j) {
-                unsigned pos = (unsigned)(base + j);
-                if (pos < (unsigned)cap_next) colidx_next[pos] = add_col[as + j];
-            }
-            if (i == s_rp[rr + 1] - 1) {                 // last old entry of the row: the adds beyond it
-                int jj = la_[k];
-                if (as + jj < ae && add_col[as + jj] == c_[k]) ++jj;   // an "added" edge that already exists
-                const int tail = base + (dead_[k] ? 0 : 1);
-                for (; jj < ae - as; ++jj) {
-                    unsigned pos = (unsigned)(tail + jj);
-                    if (pos < (unsigned)cap_next) colidx_next[pos] = add_col[as + jj];
+        // first output position of this sub-tile: row start, plus what its row kept and gained so far
+        const int base = s_rn[t0] + (e - s_rp[t0]) - (d_cur - ds0) + (a_cur - as0);
+        const int a_tile = a_cur;
+        const int a_lim = min(s_ap[t_last + 1], n_add);
+        const int d_lim = min(s_rp[t_last + 1] + s_ap[t_last + 1] - s_rn[t_last + 1], n_del);
+
+        // ---- deleted entries: mark the old entry dead
+        for (int j0 = max(d_cur, 0); j0 < d_lim; j0 += kWave) {
+            const int j = j0 + lane;
+            bool owned = false;
+            if (j < d_lim) {
+                const int t = del_row[j] - k_cur;
+                const int c = del_col[j];
+                if (t >= t0 && t <= t_last) {
+                    const int lo = max(s_rp[t] - e, 0), hi = min(s_rp[t + 1] - e, cnt);
+                    const int p = lds_bound<false>(s_col, lo, hi, c);
+                    owned = p < hi && s_col[p] == c;
+                    if (owned) atomicOr(&s_mark[p], 1);
                 }
             }
+            const int got = __popcll(__ballot(owned));
+            d_cur = j0 + got;
+            if (got < kWave) break;
         }
-        if (!dead_[k]) {
-            unsigned pos = (unsigned)(base + la_[k]);
-            if (pos < (unsigned)cap_next) colidx_next[pos] = c_[k];
+        // ---- added entries: count at the slot (old entry they precede; a row's end if none)
+        for (int j0 = max(a_cur, 0); j0 < a_lim; j0 += kWave) {
+            const int j = j0 + lane;
+            bool owned = false;
+            if (j < a_lim) {
+                const int t = add_row[j] - k_cur;
+                const int c = add_col[j];
+                if (t >= t0 && t <= t_last) {
+                    const int lo = max(s_rp[t] - e, 0), hi = min(s_rp[t + 1] - e, cnt);
+                    const int q = lds_bound<true>(s_col, lo, hi, c);
+                    owned = q < hi || s_rp[t + 1] <= e_stop;      // beyond the sub-tile's part of an unfinished row: later
+                    if (owned) atomicAdd(&s_mark[q], 2);
+                }
+            }
+            const int got = __popcll(__ballot(owned));
+            a_cur = j0 + got;
+            if (got < kWave) break;
         }
+        __syncthreads();
+
+        // ---- prefix sums: s_start[p] = kept entries before p + added entries of slots before p
+        {
+            int mk[kPerLane];
+            int alive = 0, ins = 0;
+#pragma unroll
+            for (int j = 0; j < kPerLane; ++j) {
+                const int p = lane * kPerLane + j;
+                mk[j] = s_mark[p];
+                alive += (p < cnt && !(mk[j] & 1)) ? 1 : 0;
+                ins += mk[j] >> 1;
+            }
+            const int inc_alive = wave_scan_add(alive, lane), inc_ins = wave_scan_add(ins, lane);
+            int run = (inc_alive - alive) + (inc_ins - ins);
+#pragma unroll
+            for (int j = 0; j < kPerLane; ++j) {
+                const int p = lane * kPerLane + j;
+                s_start[p] = run;
+                run += ((p < cnt && !(mk[j] & 1)) ? 1 : 0) + (mk[j] >> 1);
+            }
+            if (lane == kWave - 1) s_start[kSub] = run;   // slot "after the last entry" of a full sub-tile
+        }
+        __syncthreads();
+
+        // ---- old entries
+#pragma unroll
+        for (int j = 0; j < kPerLane; ++j) {
+            const int p = lane + j * kWave;
+            if (p < cnt) {
+                const int mk = s_mark[p];
+                const unsigned pos = (unsigned)(base + s_start[p] + (mk >> 1));
+                if (!(mk & 1) && pos < (unsigned)cap_next) colidx_next[pos] = c_[j];
+            }
+        }
+        // ---- added entries: slot again, then the rank among the adds of the same slot (they are consecutive)
+        int q_carry = -1, rank_carry = 0;
+        for (int j0 = max(a_tile, 0); j0 < a_cur; j0 += kWave) {
+            const int j = j0 + lane;
+            int q = -2 - lane, c = 0;                     // distinct dummies for idle lanes
+            if (j < a_cur) {
+                const int t = add_row[j] - k_cur;
+                c = add_col[j];
+                const int lo = max(s_rp[t] - e, 0), hi = min(s_rp[t + 1] - e, cnt);
+                q = lds_bound<true>(s_col, lo, hi, c);
+            }
+            const int q_left = __shfl_up(q, 1, kWave);
+            const bool head = lane == 0 ? q != q_carry : q != q_left;
+            const unsigned long long heads = __ballot(head) | 1ull;
+            const unsigned long long upto = heads & (~0ull >> (kWave - 1 - lane));
+            const int run_start = 63 - __clzll(upto);
+            int rank = lane - run_start;
+            if (run_start == 0 && !(__ballot(head) & 1ull)) rank += rank_carry;   // run continues from the previous 64
+            if (j < a_cur) {
+                const unsigned pos = (unsigned)(base + s_start[q] + rank);
+                if (pos < (unsigned)cap_next) colidx_next[pos] = c;
+            }
+            q_carry = __shfl(q, kWave - 1, kWave);
+            rank_carry = __shfl(rank, kWave - 1, kWave) + 1;
+        }
+        k_cur += le_stop - 1;      // a row with rowptr <= e_stop, the last such one among the staged rows
+        e = e_stop;
+        __syncthreads();           // LDS is rewritten by the next sub-tile
     }
 }
 
@@ -361,9 +457,9 @@ extern "C" int dgnn_delta_rebuild(int64_t n,
                            (int)n_del, d_status);
         DGNN_RETURN_IF_LAUNCH_FAILED();
     }
-    hipLaunchKernelGGL(merge_kernel, dim3((unsigned)((nnz_prev + kMergeTile - 1) / kMergeTile)), dim3(kMergeThreads), 0, s,
-                       (int)n, rowptr_prev, colidx_prev, (int)nnz_prev, add_col, (int)n_add, del_col, (int)n_del,
-                       rowptr_next, add_ptr, colidx_next, cap, d_status);
+    hipLaunchKernelGGL(merge_kernel, dim3((unsigned)((nnz_prev + kRange - 1) / kRange)), dim3(kWave), 0, s,
+                       (int)n, rowptr_prev, colidx_prev, (int)nnz_prev, add_row, add_col, (int)n_add, del_row, del_col,
+                       (int)n_del, rowptr_next, add_ptr, colidx_next, cap);
     DGNN_RETURN_IF_LAUNCH_FAILED();
     return DGNN_OK;
 }

@@ -68,11 +68,11 @@ __global__ __launch_bounds__(kThreads) void xw_f32_kernel(const float *__restric
                 acc[jt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[jt], 0, 0, 0);
             }
         }
-        float scale[16];   // row_scale of the 16 rows this lane stores
+        float scale[16];   // row_scale of the 16 rows this lane stores: one coalesced load, then lane exchange
+        {
+            const float mine = (row_scale && row < n) ? row_scale[row] : 1.0f;   // lane (i, hh) holds row i
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int64_t r = tile * 32 + 8 * (v / 4) + 4 * hh + (v % 4);
-            scale[v] = (row_scale && r < n) ? row_scale[r] : 1.0f;
+            for (int v = 0; v < 16; ++v) scale[v] = __shfl(mine, 8 * (v / 4) + 4 * hh + (v % 4), kWave);
         }
 #pragma unroll
         for (int jt = 0; jt < NT; ++jt) {
@@ -132,11 +132,11 @@ __global__ __launch_bounds__(kThreads) void xw_bf16_kernel(const uint16_t *__res
                 acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s], bv, acc[jt], 0, 0, 0);
             }
         }
-        float scale[16];   // row_scale of the 16 rows this lane stores
+        float scale[16];   // row_scale of the 16 rows this lane stores: one coalesced load, then lane exchange
+        {
+            const float mine = (row_scale && row < n) ? row_scale[row] : 1.0f;   // lane (i, hh) holds row i
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int64_t r = tile * 32 + 8 * (v / 4) + 4 * hh + (v % 4);
-            scale[v] = (row_scale && r < n) ? row_scale[r] : 1.0f;
+            for (int v = 0; v < 16; ++v) scale[v] = __shfl(mine, 8 * (v / 4) + 4 * hh + (v % 4), kWave);
         }
 #pragma unroll
         for (int jt = 0; jt < NT; ++jt) {
