@@ -163,6 +163,10 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
         c_next[j] = i < e_end ? colidx_prev[i] : 0;
     }
     int a_cur = 0, d_cur = 0;   // first added / deleted entry not yet placed
+    // fetched ahead of use: the next sub-tile's rows, and the 64 difference entries at each cursor
+    int m_v[kRowCap / kWave], m_rn[kRowCap / kWave], m_ap[kRowCap / kWave];
+    bool have_rows = false;
+    int pa_row = 0, pa_col = 0, pd_row = 0, pd_col = 0;
     int e = e_begin;
     while (e < e_end) {
         // ---- stage rows k_cur .. k_cur + kRowCap - 1
@@ -173,13 +177,18 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
             const int t = lane + round * kWave;
             const int k = k_cur + t;
             const bool ok = k <= n;
-            const int v = ok ? rowptr_prev[k] : 0x7fffffff;
-            v_[round] = v;
-            s_rp[t] = v;
-            s_rn[t] = ok ? rowptr_next[k] : 0;
-            s_ap[t] = ok ? add_ptr[k] : 0;
-            le_e += __popcll(__ballot(v <= e));
+            if (!have_rows) {
+                m_v[round] = ok ? rowptr_prev[k] : 0x7fffffff;
+                m_rn[round] = ok ? rowptr_next[k] : 0;
+                m_ap[round] = ok ? add_ptr[k] : 0;
+            }
+            v_[round] = m_v[round];
+            s_rp[t] = m_v[round];
+            s_rn[t] = m_rn[round];
+            s_ap[t] = m_ap[round];
+            le_e += __popcll(__ballot(v_[round] <= e));
         }
+        have_rows = false;
         const int t0 = max(le_e - 1, 0);                 // the staged row that holds entry e
         if (t0 >= kRowCap - 1) {                         // only rows without entries were staged: move on
             k_cur += kRowCap - 1;
@@ -196,6 +205,7 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
             lt_stop += __popcll(__ballot(v_[round] < e_stop));
         }
         const int t_last = lt_stop - 1;                  // last staged row with entries in this sub-tile
+        const int k_next = k_cur + le_stop - 1;          // a row with rowptr <= e_stop: first row of the next sub-tile
         int c_[kPerLane];
 #pragma unroll
         for (int j = 0; j < kPerLane; ++j) {
@@ -204,11 +214,22 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
             s_mark[lane + j * kWave] = 0;
         }
         s_mark[kSub + lane] = 0;
-        // the column indices that follow e_stop are fetched while this sub-tile is placed
+        // what follows e_stop is fetched while this sub-tile is placed: column indices and rows
+        if (e_stop < e_end) {
 #pragma unroll
-        for (int j = 0; j < kPerLane; ++j) {
-            const int i = e_stop + lane + j * kWave;
-            c_next[j] = i < e_end ? colidx_prev[i] : 0;
+            for (int j = 0; j < kPerLane; ++j) {
+                const int i = e_stop + lane + j * kWave;
+                c_next[j] = i < e_end ? colidx_prev[i] : 0;
+            }
+#pragma unroll
+            for (int round = 0; round < kRowCap / kWave; ++round) {
+                const int k = k_next + lane + round * kWave;
+                const bool ok = k <= n;
+                m_v[round] = ok ? rowptr_prev[k] : 0x7fffffff;
+                m_rn[round] = ok ? rowptr_next[k] : 0;
+                m_ap[round] = ok ? add_ptr[k] : 0;
+            }
+            have_rows = true;
         }
         __syncthreads();
 
@@ -221,6 +242,10 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
                 if (as0 >= 0 && as0 < ae0 && ae0 <= n_add) a_cur = lower_bound(add_col, as0, ae0, colidx_prev[e - 1]);
                 if (ds0 >= 0 && ds0 < de0 && de0 <= n_del) d_cur = lower_bound(del_col, ds0, de0, s_col[0]);
             }
+            a_cur = max(a_cur, 0);
+            d_cur = max(d_cur, 0);
+            if (a_cur + lane < n_add) { pa_row = add_row[a_cur + lane]; pa_col = add_col[a_cur + lane]; }
+            if (d_cur + lane < n_del) { pd_row = del_row[d_cur + lane]; pd_col = del_col[d_cur + lane]; }
         }
         // first output position of this sub-tile: row start, plus what its row kept and gained so far
         const int base = s_rn[t0] + (e - s_rp[t0]) - (d_cur - ds0) + (a_cur - as0);
@@ -229,41 +254,50 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
         const int d_lim = min(s_rp[t_last + 1] + s_ap[t_last + 1] - s_rn[t_last + 1], n_del);
 
         // ---- deleted entries: mark the old entry dead
-        for (int j0 = max(d_cur, 0); j0 < d_lim; j0 += kWave) {
-            const int j = j0 + lane;
-            bool owned = false;
-            if (j < d_lim) {
-                const int t = del_row[j] - k_cur;
-                const int c = del_col[j];
-                if (t >= t0 && t <= t_last) {
+        {
+            int row = pd_row, c = pd_col;
+            for (int j0 = d_cur; j0 < d_lim; j0 += kWave) {
+                const int j = j0 + lane;
+                if (j0 != d_cur && j < d_lim) { row = del_row[j]; c = del_col[j]; }
+                bool owned = false;
+                const int t = row - k_cur;
+                if (j < d_lim && t >= t0 && t <= t_last) {
                     const int lo = max(s_rp[t] - e, 0), hi = min(s_rp[t + 1] - e, cnt);
                     const int p = lds_bound<false>(s_col, lo, hi, c);
                     owned = p < hi && s_col[p] == c;
                     if (owned) atomicOr(&s_mark[p], 1);
                 }
+                const int got = __popcll(__ballot(owned));
+                if (got < kWave) { d_cur = j0 + got; break; }
+                if (j0 + kWave >= d_lim) d_cur = j0 + kWave;
             }
-            const int got = __popcll(__ballot(owned));
-            d_cur = j0 + got;
-            if (got < kWave) break;
         }
         // ---- added entries: count at the slot (old entry they precede; a row's end if none)
-        for (int j0 = max(a_cur, 0); j0 < a_lim; j0 += kWave) {
-            const int j = j0 + lane;
-            bool owned = false;
-            if (j < a_lim) {
-                const int t = add_row[j] - k_cur;
-                const int c = add_col[j];
-                if (t >= t0 && t <= t_last) {
+        int q_first = -2 - lane, c_first = 0;     // slot and column of the first 64, kept for the write below
+        {
+            int row = pa_row, c = pa_col;
+            const int start = a_cur;
+            for (int j0 = start; j0 < a_lim; j0 += kWave) {
+                const int j = j0 + lane;
+                if (j0 != start && j < a_lim) { row = add_row[j]; c = add_col[j]; }
+                bool owned = false;
+                const int t = row - k_cur;
+                int q = -2 - lane;
+                if (j < a_lim && t >= t0 && t <= t_last) {
                     const int lo = max(s_rp[t] - e, 0), hi = min(s_rp[t + 1] - e, cnt);
-                    const int q = lds_bound<true>(s_col, lo, hi, c);
+                    q = lds_bound<true>(s_col, lo, hi, c);
                     owned = q < hi || s_rp[t + 1] <= e_stop;      // beyond the sub-tile's part of an unfinished row: later
                     if (owned) atomicAdd(&s_mark[q], 2);
                 }
+                if (j0 == start) { q_first = owned ? q : -2 - lane; c_first = c; }
+                const int got = __popcll(__ballot(owned));
+                if (got < kWave) { a_cur = j0 + got; break; }
+                if (j0 + kWave >= a_lim) a_cur = j0 + kWave;
             }
-            const int got = __popcll(__ballot(owned));
-            a_cur = j0 + got;
-            if (got < kWave) break;
         }
+        // the difference entries at the new cursors, for the next sub-tile
+        if (a_cur + lane < n_add) { pa_row = add_row[a_cur + lane]; pa_col = add_col[a_cur + lane]; }
+        if (d_cur + lane < n_del) { pd_row = del_row[d_cur + lane]; pd_col = del_col[d_cur + lane]; }
         __syncthreads();
 
         // ---- prefix sums: s_start[p] = kept entries before p + added entries of slots before p
@@ -299,24 +333,27 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
                 if (!(mk & 1) && pos < (unsigned)cap_next) colidx_next[pos] = c_[j];
             }
         }
-        // ---- added entries: slot again, then the rank among the adds of the same slot (they are consecutive)
+        // ---- added entries: their slot, then the rank among the adds of the same slot (they are consecutive)
         int q_carry = -1, rank_carry = 0;
-        for (int j0 = max(a_tile, 0); j0 < a_cur; j0 += kWave) {
+        for (int j0 = a_tile; j0 < a_cur; j0 += kWave) {
             const int j = j0 + lane;
-            int q = -2 - lane, c = 0;                     // distinct dummies for idle lanes
-            if (j < a_cur) {
-                const int t = add_row[j] - k_cur;
-                c = add_col[j];
-                const int lo = max(s_rp[t] - e, 0), hi = min(s_rp[t + 1] - e, cnt);
-                q = lds_bound<true>(s_col, lo, hi, c);
+            int q = q_first, c = c_first;
+            if (j0 != a_tile) {
+                q = -2 - lane;
+                if (j < a_cur) {
+                    const int t = add_row[j] - k_cur;
+                    c = add_col[j];
+                    const int lo = max(s_rp[t] - e, 0), hi = min(s_rp[t + 1] - e, cnt);
+                    q = lds_bound<true>(s_col, lo, hi, c);
+                }
             }
             const int q_left = __shfl_up(q, 1, kWave);
             const bool head = lane == 0 ? q != q_carry : q != q_left;
-            const unsigned long long heads = __ballot(head) | 1ull;
-            const unsigned long long upto = heads & (~0ull >> (kWave - 1 - lane));
+            const unsigned long long true_heads = __ballot(head);
+            const unsigned long long upto = (true_heads | 1ull) & (~0ull >> (kWave - 1 - lane));
             const int run_start = 63 - __clzll(upto);
             int rank = lane - run_start;
-            if (run_start == 0 && !(__ballot(head) & 1ull)) rank += rank_carry;   // run continues from the previous 64
+            if (run_start == 0 && !(true_heads & 1ull)) rank += rank_carry;   // run continues from the previous 64
             if (j < a_cur) {
                 const unsigned pos = (unsigned)(base + s_start[q] + rank);
                 if (pos < (unsigned)cap_next) colidx_next[pos] = c;
@@ -324,7 +361,7 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
             q_carry = __shfl(q, kWave - 1, kWave);
             rank_carry = __shfl(rank, kWave - 1, kWave) + 1;
         }
-        k_cur += le_stop - 1;      // a row with rowptr <= e_stop, the last such one among the staged rows
+        k_cur = k_next;
         e = e_stop;
         __syncthreads();           // LDS is rewritten by the next sub-tile
     }

@@ -5,20 +5,24 @@
 //
 // The work is a gather of whole H rows (one 16-byte piece per lane, a lane group per row of H),
 // bound by how many independent row fetches are in flight, so it is split by ENTRIES, not by
-// rows: a workgroup owns a tile of consecutive stored entries, whatever rows they belong to.
-//   1. Two wavefronts find the rows that hold the first and the last entry of the tile (64-ary
-//      search), the others stage the tile's column indices (and dinv of the columns) in LDS.
-//   2. Row starts inside the tile are scattered into LDS and max-scanned into a row id per entry.
-//   3. Every lane group walks the same number of consecutive entries, eight gathers in flight at
-//      a time, and flushes its running sum whenever the row id changes: a row segment that
-//      begins and ends inside the group's range is a finished row and is stored at once; a
-//      segment cut by the range is parked in LDS.
-//   4. One lane group adds the parked pieces up in entry order.  Rows cut by the tile itself
-//      leave a "left" and/or "right" carry in the workspace; a second small kernel adds the
-//      carries of consecutive tiles, again in entry order.
-// Hub rows of power-law graphs are thereby spread over as many workgroups as they have tiles,
+// rows, and every wavefront is an independent stream:
+//   - a wavefront owns a contiguous range of stored entries and walks it in sub-tiles; the row
+//     that holds the range's first entry is found once (64-ary search), afterwards rows simply
+//     follow on: a window of consecutive row pointers is staged in LDS and the row starts that
+//     fall into the sub-tile become a bit mask (one 32-bit word per lane group);
+//   - every lane group takes 32 consecutive entries, keeps eight gathers in flight while it adds
+//     up the previous eight, and closes its running sum wherever the mask has a bit: a row that
+//     begins and ends inside the group's 32 entries is finished and stored at once, a piece cut
+//     at either end is parked in LDS;
+//   - one lane group adds the parked pieces in entry order and carries a row that is still open
+//     into the next sub-tile in registers; only rows cut by the range itself leave a "left" or
+//     "right" carry in the workspace, which a second small kernel adds up, again in entry order;
+//   - column indices and row pointers of the next sub-tile are fetched while this one is summed.
+// Hub rows of power-law graphs are thereby spread over as many wavefronts as they have ranges,
 // short rows share a wavefront, and every sum has a fixed order: no floating-point atomics,
 // results repeat bit for bit.
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace {
@@ -28,19 +32,13 @@ using namespace dgnn;
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
 
-constexpr int kThreads = 256;
-constexpr int kBatch = 8;          // gathers issued together by a lane group
-constexpr int kMaxTile = 2048;     // entries per tile, upper limit (LDS)
+constexpr int kBatch = 8;            // gathers issued together by a lane group
+constexpr int kPer = 32;             // entries a lane group walks per sub-tile (one mask word)
+constexpr int kRange = 8192;         // entries streamed by one wavefront
+constexpr int kRowCap = 2 * kWave;   // consecutive row pointers staged per sub-tile
 
 enum : int32_t { kLeft = 1, kLeftClosed = 2, kRight = 4 };
-struct TileRec { int32_t flags, row_first, row_last, pad; };
-
-template <int LPR> struct Shape {
-    static constexpr int kGroups = kThreads / LPR;
-    static constexpr int kTile = kGroups * 32 > kMaxTile ? kMaxTile : kGroups * 32;
-    static constexpr int kPerGroup = kTile / kGroups;      // entries walked by one lane group
-    static constexpr int kItems = kTile / kThreads;        // entries per thread in the scan
-};
+struct RangeRec { int32_t flags, row_last, pad0, pad1; };
 
 // ---- 16-byte feature pieces: 4 fp32 or 8 bf16, accumulated in fp32 -------------------------
 template <bool BF16> struct Piece;
@@ -87,236 +85,356 @@ __device__ __forceinline__ void finish_row(char *z, int64_t row, int row_bytes, 
     Piece<BF16>::store(z + row * row_bytes + sub * 16, out);
 }
 
-// SCALE_V: multiply every gathered row by dinv of its column (otherwise H already carries it).
+template <bool BF16, int LPR>
+__device__ __forceinline__ void zero_row(char *z, int64_t row) {
+    constexpr int NV = Piece<BF16>::kVals;
+    float zero[NV];
+#pragma unroll
+    for (int q = 0; q < NV; ++q) zero[q] = 0.0f;
+    for (int s = 0; s < LPR; ++s) Piece<BF16>::store(z + row * (LPR * 16) + s * 16, zero);
+}
+
+// LPR: lanes per feature row.  SCALE_V: multiply every gathered row by dinv of its column
+// (otherwise H already carries it).
 template <int LPR, bool BF16, bool SCALE_V>
-__global__ __launch_bounds__(kThreads) void spmm_tile_kernel(
+__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) void spmm_stream_kernel(
     int n, int nnz, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const float *__restrict__ dinv, const char *__restrict__ h, char *__restrict__ z, int relu,
-    TileRec *__restrict__ recs, float *__restrict__ carry) {
-    typedef Shape<LPR> S;
+    RangeRec *__restrict__ recs, float *__restrict__ carry) {
     typedef typename Piece<BF16>::Raw Raw;
     constexpr int NV = Piece<BF16>::kVals;
     constexpr int F = LPR * NV;
-    constexpr int G = S::kGroups, TILE = S::kTile, PER = S::kPerGroup, ITEMS = S::kItems;
+    constexpr int G = kWave / LPR;          // lane groups per wavefront
+    constexpr int SUB = G * kPer;           // entries per sub-tile
+    constexpr int CPL = kPer / LPR;         // column indices held by one lane
     constexpr int kRowBytes = LPR * 16;
+    constexpr int ROUNDS = kRowCap / kWave;
 
-    __shared__ int s_col[TILE];
-    __shared__ int s_rid[TILE];
-    __shared__ float s_dv[SCALE_V ? TILE : 1];
-    __shared__ float s_part[G][2][F];
-    __shared__ int s_flag[G];
-    __shared__ int s_prow[G][2];
-    __shared__ int s_rows[2];
-    __shared__ int s_wmax[kThreads / kWave];
+    __shared__ int s_rp[kRowCap];           // row pointers of the staged rows
+    __shared__ float s_du[kRowCap];         // their dinv
+    __shared__ unsigned s_heads[G + 1];     // bit p of the mask: a row begins at entry e + p
+    __shared__ float s_part[G][2][F];       // [0]: a group's first piece when cut on the left, [1]: its last piece when cut on the right only
 
-    const int tid = threadIdx.x;
-    const int lane = tid & (kWave - 1), wave = tid / kWave;
-    const int i0 = (int)((int64_t)blockIdx.x * TILE);
-    const int i1 = (int)min((int64_t)i0 + TILE, (int64_t)nnz);
-    const int cnt = i1 - i0;
+    const int lane = threadIdx.x;
+    const int sub = lane % LPR, g = lane / LPR, gbase = lane - sub;
+    const int e_begin = (int)((int64_t)blockIdx.x * kRange);
+    const int e_end = (int)min((int64_t)e_begin + kRange, (int64_t)nnz);
+    int k_cur = max(wave_find_row(rowptr, n, e_begin, lane), 0);   // a row with rowptr <= e_begin
+    if (blockIdx.x == 0)                     // rows without entries ahead of the first stored entry
+        for (int k = lane; k < k_cur; k += kWave) zero_row<BF16, LPR>(z, k);
 
-    // ---- 1. stage the tile; meanwhile two wavefronts look up the bounding rows
-    int myc[ITEMS];
+    // the row that is still open at the end of a sub-tile is carried on in the lanes of group 0
+    float run[NV];
 #pragma unroll
-    for (int k = 0; k < ITEMS; ++k) {
-        const int p = tid + k * kThreads;
-        myc[k] = p < cnt ? colidx[i0 + p] : 0;
-    }
-    if (wave < 2) {
-        int r = wave_find_row(rowptr, n, wave == 0 ? i0 : i1 - 1, lane);
-        if (lane == 0) s_rows[wave] = max(r, 0);
-    }
-#pragma unroll
-    for (int k = 0; k < ITEMS; ++k) {
-        const int p = tid + k * kThreads;
-        s_rid[p] = 0;
-        s_col[p] = myc[k];
-        if (SCALE_V) s_dv[p] = p < cnt ? dinv[myc[k]] : 0.0f;
-    }
-    __syncthreads();
-    const int r_first = s_rows[0], r_last = s_rows[1];
-    const bool first_open = rowptr[r_first] < i0;        // the tile's first row began in an earlier tile
-    const bool last_open = rowptr[r_last + 1] > i1;      // its last row goes on in a later tile
+    for (int q = 0; q < NV; ++q) run[q] = 0.0f;
+    bool running = false;       // such a row exists
+    bool began_here = false;    // ... and it began inside this range
+    int run_row = 0;
+    int range_flags = 0;
+    float *my_carry = carry + (int64_t)blockIdx.x * 2 * F;
 
-    // ---- 2. row id (relative to r_first) of every entry
-    for (int k = r_first + 1 + tid; k <= r_last; k += kThreads) {
-        const int a = rowptr[k], b = rowptr[k + 1];
-        const unsigned p = (unsigned)(a - i0);
-        if (a == b) {                                    // a row without entries: its output is zero
-            float zero[NV];
+    // column indices (and their dinv) of the coming sub-tile: lane holds entries e + 32 g + sub CPL + i
+    int c_next[CPL];
+    float d_next[SCALE_V ? CPL : 1];
+    auto fetch_cols = [&](int e0) {
 #pragma unroll
-            for (int q = 0; q < NV; ++q) zero[q] = 0.0f;
-            for (int sub = 0; sub < LPR; ++sub) Piece<BF16>::store(z + (int64_t)k * kRowBytes + sub * 16, zero);
-        } else if (p < (unsigned)cnt) {
-            atomicMax(&s_rid[p], k - r_first);
+        for (int i = 0; i < CPL; ++i) {
+            const int idx = e0 + g * kPer + sub * CPL + i;
+            c_next[i] = idx < e_end ? colidx[idx] : 0;
         }
-    }
-    __syncthreads();
-    {
-        int v[ITEMS];
-        int m = 0;
+        if (SCALE_V) {
 #pragma unroll
-        for (int k = 0; k < ITEMS; ++k) {
-            m = max(m, s_rid[tid * ITEMS + k]);
-            v[k] = m;
+            for (int i = 0; i < CPL; ++i) {
+                const int idx = e0 + g * kPer + sub * CPL + i;
+                d_next[i] = idx < e_end ? dinv[c_next[i]] : 0.0f;
+            }
         }
-        const int inc = wave_scan_max(m, lane);
-        if (lane == kWave - 1) s_wmax[wave] = inc;
-        int before = __shfl_up(inc, 1, kWave);
-        if (lane == 0) before = 0;
+    };
+    int m_v[ROUNDS];
+    float m_du[ROUNDS];
+    auto fetch_rows = [&](int k0) {
+#pragma unroll
+        for (int round = 0; round < ROUNDS; ++round) {
+            const int k = k0 + lane + round * kWave;
+            m_v[round] = k <= n ? rowptr[k] : 0x7fffffff;
+            m_du[round] = (dinv && k < n) ? dinv[k] : 1.0f;
+        }
+    };
+    fetch_cols(e_begin);
+    fetch_rows(k_cur);
+    int k_win = k_cur;
+    int e = e_begin;
+    while (e < e_end) {
+        // ---- stage rows k_cur .. k_cur + kRowCap - 1
+        int le_e = 0;
+        int v_[ROUNDS];
+#pragma unroll
+        for (int round = 0; round < ROUNDS; ++round) {
+            const int t = lane + round * kWave;
+            v_[round] = m_v[round];
+            s_rp[t] = m_v[round];
+            s_du[t] = m_du[round];
+            le_e += __popcll(__ballot(v_[round] <= e));
+        }
+        k_win = k_cur;
+        const int t0 = max(le_e - 1, 0);                 // the staged row that holds entry e
         __syncthreads();
-        for (int w = 0; w < wave; ++w) before = max(before, s_wmax[w]);
+        // rows without entries give zero output (none exist when every row holds its diagonal)
 #pragma unroll
-        for (int k = 0; k < ITEMS; ++k) s_rid[tid * ITEMS + k] = max(v[k], before);
-    }
-    __syncthreads();
+        for (int round = 0; round < ROUNDS; ++round) {
+            const int t = lane + round * kWave;
+            if (t + 1 < kRowCap && k_cur + t + 1 <= n && s_rp[t] == s_rp[t + 1]) zero_row<BF16, LPR>(z, k_cur + t);
+        }
+        if (t0 > 0) {                                    // rows without entries were stepped over: restage from the row of e
+            k_cur += t0;
+            fetch_rows(k_cur);
+            __syncthreads();
+            continue;
+        }
+        const int v_last = __shfl(v_[ROUNDS - 1], kWave - 1, kWave);   // start of the last staged row (> e)
+        const int e_stop = min(min(e + SUB, e_end), v_last);
+        const int cnt = e_stop - e;
+        int le_stop = 0, lt_stop = 0;
+#pragma unroll
+        for (int round = 0; round < ROUNDS; ++round) {
+            le_stop += __popcll(__ballot(v_[round] <= e_stop));
+            lt_stop += __popcll(__ballot(v_[round] < e_stop));
+        }
+        const int t_last = lt_stop - 1;                  // last staged row with entries in this sub-tile
+        const int k_next = k_cur + le_stop - 1;          // a row with rowptr <= e_stop
 
-    // ---- 3. every lane group walks PER consecutive entries
-    const int g = tid / LPR, sub = tid % LPR;
-    const int c0 = g * PER;
-    const int c1 = min(c0 + PER, cnt);
-    int flags = 0;
-    if (c0 < c1) {
-        int cur = s_rid[c0];
-        // is the first segment of this range the beginning of its row?
-        bool left_closed = c0 == 0 ? !first_open : s_rid[c0 - 1] != cur;
-        float acc[NV];
+        int cc[CPL];
+        float dd[SCALE_V ? CPL : 1];
 #pragma unroll
-        for (int q = 0; q < NV; ++q) acc[q] = 0.0f;
-
-        auto flush = [&](bool right_closed) {
-            if (left_closed && right_closed) {
-                finish_row<BF16, NV>(z, (int64_t)r_first + cur, kRowBytes, sub, dinv, relu, acc);
-            } else {
-                const int slot = left_closed ? 1 : 0;    // 0: cut on the left, 1: cut on the right only
+        for (int i = 0; i < CPL; ++i) {
+            cc[i] = c_next[i];
+            if (SCALE_V) dd[i] = d_next[i];
+        }
+        if (lane <= G) s_heads[lane] = 0u;
+        if (e_stop < e_end) {                            // fetched while this sub-tile is summed
+            fetch_cols(e_stop);
+            fetch_rows(k_next);
+        }
+        __syncthreads();
+        // ---- row starts inside the sub-tile -> mask bits
 #pragma unroll
-                for (int q = 0; q < NV; ++q) s_part[g][slot][sub * NV + q] = acc[q];
-                if (sub == 0) s_prow[g][slot] = cur;
-                flags |= left_closed ? kRight : (kLeft | (right_closed ? kLeftClosed : 0));
-            }
-        };
-
-#pragma unroll
-        for (int b = 0; b < PER / kBatch; ++b) {
-            const int p0 = c0 + b * kBatch;
-            Raw raw[kBatch];
-            int rid[kBatch];
-            float dv[kBatch];
-#pragma unroll
-            for (int k = 0; k < kBatch; ++k) {
-                const int p = p0 + k;
-                if (p < c1) {
-                    rid[k] = s_rid[p];
-                    dv[k] = SCALE_V ? s_dv[p] : 1.0f;
-                    raw[k] = *reinterpret_cast<const Raw *>(h + (int64_t)s_col[p] * kRowBytes + sub * 16);
-                }
-            }
-#pragma unroll
-            for (int k = 0; k < kBatch; ++k) {
-                if (p0 + k < c1) {
-                    if (rid[k] != cur) {
-                        flush(true);
-                        left_closed = true;
-                        cur = rid[k];
-#pragma unroll
-                        for (int q = 0; q < NV; ++q) acc[q] = 0.0f;
-                    }
-                    Piece<BF16>::fma(acc, dv[k], raw[k]);
-                }
+        for (int round = 0; round < ROUNDS; ++round) {
+            const int t = lane + round * kWave;
+            if (t > 0 && v_[round] < e_stop) {
+                const int p = v_[round] - e;
+                atomicOr(&s_heads[p >> 5], 1u << (p & 31));
             }
         }
-        flush(c1 == cnt ? !last_open : s_rid[c1] != cur);
-    }
-    if (sub == 0) s_flag[g] = flags;
-    __syncthreads();
+        if (lane == 0 && v_[0] == e) atomicOr(&s_heads[0], 1u);
+        __syncthreads();
 
-    // ---- 4. one lane group adds the parked pieces in entry order
-    if (tid < LPR) {
-        float acc[NV];
+        // ---- every lane group walks its 32 entries
+        const int p0 = g * kPer;
+        const int c1 = min(p0 + kPer, cnt);
+        if (p0 < c1) {
+            const unsigned w = s_heads[g];
+            int cur;                                     // staged row that holds entry p0: last one that begins at or before it
+            {
+                int lo = 0, hi = t_last + 1;
+                while (lo < hi) {
+                    const int mid = lo + ((hi - lo) >> 1);
+                    if (s_rp[mid] <= e + p0) lo = mid + 1; else hi = mid;
+                }
+                cur = lo - 1;
+            }
+            bool left_closed = (w & 1u) != 0;            // entry p0 begins its row
+            float acc[NV];
 #pragma unroll
-        for (int q = 0; q < NV; ++q) acc[q] = 0.0f;
-        bool running = false;      // a row is being accumulated
-        bool began_here = false;   // ... and it began inside this tile
-        int run_row = 0;
-        int tile_flags = 0;
-        float *my_carry = carry + (int64_t)blockIdx.x * 2 * F;
-        for (int gg = 0; gg < G; ++gg) {
-            const int fl = s_flag[gg];
-            if (fl & kLeft) {
+            for (int q = 0; q < NV; ++q) acc[q] = 0.0f;
+
+            // a piece that is a whole row is finished and stored; a cut piece is parked for the step below
+            auto flush = [&](bool right_closed) {
+                if (left_closed && right_closed) {
+                    float out[NV];
+                    const float du = s_du[cur];
 #pragma unroll
-                for (int q = 0; q < NV; ++q) acc[q] += s_part[gg][0][tid * NV + q];
-                if (!running) { running = true; began_here = false; run_row = s_prow[gg][0]; }
-                if (fl & kLeftClosed) {
+                    for (int q = 0; q < NV; ++q) {
+                        out[q] = acc[q] * du;
+                        if (relu) out[q] = fmaxf(out[q], 0.0f);
+                    }
+                    Piece<BF16>::store(z + (int64_t)(k_cur + cur) * kRowBytes + sub * 16, out);
+                } else {
+                    float *dst = &s_part[g][left_closed ? 1 : 0][sub * NV];
+#pragma unroll
+                    for (int q = 0; q < NV; ++q) dst[q] = acc[q];
+                }
+            };
+            // batch b covers entries 8 b .. 8 b + 7 of the group; ODD (the parity of b) makes the register
+            // slot q % CPL a compile-time constant while b itself stays a run-time loop counter
+            auto batch = [&](int b, auto odd) {
+                constexpr int ODD = decltype(odd)::value;
+                constexpr int slot_odd = (ODD * kBatch) % CPL;
+                Raw buf[kBatch];
+#pragma unroll
+                for (int k = 0; k < kBatch; ++k) {
+                    const int q = b * kBatch + k;
+                    if (p0 + q < c1) {
+                        const int c = __shfl(cc[(slot_odd + k) % CPL], gbase + q / CPL, kWave);
+                        buf[k] = *reinterpret_cast<const Raw *>(h + (int64_t)c * kRowBytes + sub * 16);
+                    }
+                }
+                const unsigned wb = w >> (b * kBatch);
+#pragma unroll
+                for (int k = 0; k < kBatch; ++k) {
+                    const int q = b * kBatch + k;
+                    if (p0 + q < c1) {
+                        if (q > 0 && ((wb >> k) & 1u)) {
+                            flush(true);
+                            left_closed = true;
+                            do ++cur; while (s_rp[cur + 1] <= e + p0 + q);   // rows without entries are stepped over
+#pragma unroll
+                            for (int x = 0; x < NV; ++x) acc[x] = 0.0f;
+                        }
+                        const float s = SCALE_V ? __shfl(dd[(slot_odd + k) % CPL], gbase + q / CPL, kWave) : 1.0f;
+                        Piece<BF16>::fma(acc, s, buf[k]);
+                    }
+                }
+            };
+#pragma unroll 1
+            for (int b = 0; b < kPer / kBatch; b += 2) {
+                batch(b, std::integral_constant<int, 0>{});
+                batch(b + 1, std::integral_constant<int, 1>{});
+            }
+            // does the row of the last entry end with it?
+            flush(c1 == cnt ? s_rp[t_last + 1] == e_stop : (s_heads[g + 1] & 1u) != 0);
+        }
+        __syncthreads();
+
+        // ---- rows cut between lane groups or by the sub-tile: their pieces are added in entry order.
+        // Where a row's pieces lie follows from the row pointers alone.
+        auto pieces = [&](int t, float (&sum)[NV]) {
+            const int ps = s_rp[t] - e;
+            const int pe = min(s_rp[t + 1] - e, cnt);
+            const int ga = max(ps, 0) >> 5, gb = (pe - 1) >> 5;
+            int first = ga;
+#pragma unroll
+            for (int q = 0; q < NV; ++q) sum[q] = 0.0f;
+            if (ps >= 0) {                               // begins here: its first piece is the last one of group ga
+#pragma unroll
+                for (int q = 0; q < NV; ++q) sum[q] = s_part[ga][1][sub * NV + q];
+                first = ga + 1;
+            }
+            for (int gg = first; gg <= gb; ++gg)
+#pragma unroll
+                for (int q = 0; q < NV; ++q) sum[q] += s_part[gg][0][sub * NV + q];
+        };
+        for (int t = 1 + g; t < t_last; t += G) {        // rows strictly inside the sub-tile
+            const int ps = s_rp[t] - e, pe = s_rp[t + 1] - e;
+            if (pe > ps && (ps >> 5) != ((pe - 1) >> 5)) {
+                float sum[NV];
+                pieces(t, sum);
+                float out[NV];
+#pragma unroll
+                for (int q = 0; q < NV; ++q) {
+                    out[q] = sum[q] * s_du[t];
+                    if (relu) out[q] = fmaxf(out[q], 0.0f);
+                }
+                Piece<BF16>::store(z + (int64_t)(k_cur + t) * kRowBytes + sub * 16, out);
+            }
+        }
+        if (lane < LPR) {                                // the first and the last row of the sub-tile
+            const bool first_starts = s_rp[0] == e, first_ends = s_rp[1] <= e_stop;
+            const bool first_whole_in_group = first_starts && first_ends && ((s_rp[1] - e - 1) >> 5) == 0;
+            if (!first_whole_in_group) {
+                float sum[NV];
+                pieces(0, sum);
+                if (first_starts) {                      // nothing is being carried: this row begins the carry
+#pragma unroll
+                    for (int q = 0; q < NV; ++q) run[q] = sum[q];
+                    running = true;
+                    began_here = true;
+                    run_row = k_cur;
+                } else {
+#pragma unroll
+                    for (int q = 0; q < NV; ++q) run[q] += sum[q];
+                    if (!running) { running = true; began_here = false; run_row = k_cur; }
+                }
+                if (first_ends) {
                     if (began_here) {
-                        finish_row<BF16, NV>(z, (int64_t)r_first + run_row, kRowBytes, tid, dinv, relu, acc);
-                    } else {                         // end of the row inherited from the previous tile
+                        finish_row<BF16, NV>(z, (int64_t)run_row, kRowBytes, lane, dinv, relu, run);
+                    } else {                             // end of the row inherited from the previous range
 #pragma unroll
-                        for (int q = 0; q < NV; ++q) my_carry[tid * NV + q] = acc[q];
-                        tile_flags |= kLeft | kLeftClosed;
+                        for (int q = 0; q < NV; ++q) my_carry[lane * NV + q] = run[q];
+                        range_flags |= kLeft | kLeftClosed;
                     }
                     running = false;
 #pragma unroll
-                    for (int q = 0; q < NV; ++q) acc[q] = 0.0f;
+                    for (int q = 0; q < NV; ++q) run[q] = 0.0f;
                 }
             }
-            if (fl & kRight) {
+            if (t_last > 0) {
+                const bool last_ends = s_rp[t_last + 1] <= e_stop;
+                const int ps = s_rp[t_last] - e;
+                const bool last_whole_in_group = last_ends && (ps >> 5) == ((e_stop - e - 1) >> 5);
+                if (!last_whole_in_group) {
+                    float sum[NV];
+                    pieces(t_last, sum);
+                    if (last_ends) {
+                        float out[NV];
 #pragma unroll
-                for (int q = 0; q < NV; ++q) acc[q] = s_part[gg][1][tid * NV + q];
-                running = true;
-                began_here = true;
-                run_row = s_prow[gg][1];
+                        for (int q = 0; q < NV; ++q) {
+                            out[q] = sum[q] * s_du[t_last];
+                            if (relu) out[q] = fmaxf(out[q], 0.0f);
+                        }
+                        Piece<BF16>::store(z + (int64_t)(k_cur + t_last) * kRowBytes + lane * 16, out);
+                    } else {                             // goes on in the next sub-tile
+#pragma unroll
+                        for (int q = 0; q < NV; ++q) run[q] = sum[q];
+                        running = true;
+                        began_here = true;
+                        run_row = k_cur + t_last;
+                    }
+                }
             }
         }
-        if (running) {
-            if (began_here) {                        // goes on in the next tile
-#pragma unroll
-                for (int q = 0; q < NV; ++q) my_carry[F + tid * NV + q] = acc[q];
-                tile_flags |= kRight;
-            } else {                                 // the whole tile lies inside one row
-#pragma unroll
-                for (int q = 0; q < NV; ++q) my_carry[tid * NV + q] = acc[q];
-                tile_flags |= kLeft;
-            }
-        }
-        if (tid == 0) recs[blockIdx.x] = TileRec{tile_flags, r_first, r_last, 0};
+        k_cur = k_next;
+        e = e_stop;
+        __syncthreads();
     }
 
-    // rows without entries just before this tile's first row and after the last stored entry (there are
-    // none when every row holds its diagonal); rows without entries inside the tile were zeroed above
-    {
-        float zero[NV];
+    if (lane < LPR) {
+        if (running) {
+            if (began_here) {                            // goes on in the next range
 #pragma unroll
-        for (int q = 0; q < NV; ++q) zero[q] = 0.0f;
-        if (!first_open)
-            for (int k = r_first - 1 - tid; k >= 0; k -= kThreads) {
-                if (rowptr[k] != i0) break;
-                for (int q = 0; q < LPR; ++q) Piece<BF16>::store(z + (int64_t)k * kRowBytes + q * 16, zero);
+                for (int q = 0; q < NV; ++q) my_carry[F + lane * NV + q] = run[q];
+                range_flags |= kRight;
+            } else {                                     // the whole range lies inside one row
+#pragma unroll
+                for (int q = 0; q < NV; ++q) my_carry[lane * NV + q] = run[q];
+                range_flags |= kLeft;
             }
-        if (i1 == nnz)
-            for (int k = r_last + 1 + tid; k < n; k += kThreads)
-                for (int q = 0; q < LPR; ++q) Piece<BF16>::store(z + (int64_t)k * kRowBytes + q * 16, zero);
+        }
+        if (lane == 0) recs[blockIdx.x] = RangeRec{range_flags, run_row, 0, 0};
     }
+    if (e_end == nnz)                                    // rows without entries beyond the last staged window
+        for (int k = k_win + kRowCap - 1 + lane; k < n; k += kWave)
+            if (rowptr[k] == rowptr[k + 1]) zero_row<BF16, LPR>(z, k);
 }
 
-// Rows cut by tile boundaries: the tile where such a row begins owns it and adds the left carries
-// of the following tiles until the one that closes the row.
+// Rows cut by range boundaries: the range where such a row begins owns it and adds the left carries
+// of the following ranges until the one that closes the row.
 template <int LPR, bool BF16>
-__global__ __launch_bounds__(kThreads) void spmm_carry_kernel(int tiles, const TileRec *__restrict__ recs,
-                                                              const float *__restrict__ carry,
-                                                              const float *__restrict__ dinv, char *__restrict__ z, int relu) {
+__global__ __launch_bounds__(256) void spmm_carry_kernel(int ranges, const RangeRec *__restrict__ recs,
+                                                         const float *__restrict__ carry,
+                                                         const float *__restrict__ dinv, char *__restrict__ z, int relu) {
     constexpr int NV = Piece<BF16>::kVals;
     constexpr int F = LPR * NV;
-    constexpr int G = kThreads / LPR;
+    constexpr int G = 256 / LPR;
     const int tid = threadIdx.x;
     const int sub = tid % LPR;
     const int t = blockIdx.x * G + tid / LPR;
-    if (t >= tiles) return;
-    const TileRec rec = recs[t];
+    if (t >= ranges) return;
+    const RangeRec rec = recs[t];
     if (!(rec.flags & kRight)) return;
     float acc[NV];
 #pragma unroll
     for (int q = 0; q < NV; ++q) acc[q] = carry[((int64_t)t * 2 + 1) * F + sub * NV + q];
-    for (int j = t + 1; j < tiles; ++j) {
+    for (int j = t + 1; j < ranges; ++j) {
         const int fj = recs[j].flags;
         if (!(fj & kLeft)) break;
 #pragma unroll
@@ -327,22 +445,17 @@ __global__ __launch_bounds__(kThreads) void spmm_carry_kernel(int tiles, const T
 }
 
 struct Workspace {
-    TileRec *recs;
+    RangeRec *recs;
     float *carry;
 };
 
-// Sized for the smallest tile a width can get (fp32 storage), so one query serves both dtypes.
 size_t workspace_layout(int64_t nnz, int32_t f, Workspace *ws, void *base) {
-    const int lpr = f / 4;
-    const int groups = kThreads / lpr;
-    const int tile = groups * 32 > kMaxTile ? kMaxTile : groups * 32;
-    const int64_t tiles = (nnz + tile - 1) / tile + 1;
-    const size_t o_recs = 0;
-    const size_t o_carry = round_up((size_t)tiles * sizeof(TileRec), 256);
-    const size_t total = o_carry + round_up((size_t)tiles * 2 * f * sizeof(float), 256);
+    const int64_t ranges = (nnz + kRange - 1) / kRange + 1;
+    const size_t o_carry = round_up((size_t)ranges * sizeof(RangeRec), 256);
+    const size_t total = o_carry + round_up((size_t)ranges * 2 * f * sizeof(float), 256);
     if (ws) {
         char *b = static_cast<char *>(base);
-        ws->recs = reinterpret_cast<TileRec *>(b + o_recs);
+        ws->recs = reinterpret_cast<RangeRec *>(b);
         ws->carry = reinterpret_cast<float *>(b + o_carry);
     }
     return total;
@@ -351,18 +464,16 @@ size_t workspace_layout(int64_t nnz, int32_t f, Workspace *ws, void *base) {
 template <int LPR, bool BF16>
 int launch(int64_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *dinv, bool scale_v,
            const void *h, void *z, int relu, const Workspace &ws, hipStream_t s) {
-    constexpr int TILE = Shape<LPR>::kTile;
-    constexpr int G = kThreads / LPR;
-    const int tiles = (int)((nnz + TILE - 1) / TILE);
-    if (tiles == 0) return DGNN_ERR_SHAPE;
+    constexpr int G = 256 / LPR;
+    const int ranges = (int)((nnz + kRange - 1) / kRange);
     if (scale_v)
-        hipLaunchKernelGGL((spmm_tile_kernel<LPR, BF16, true>), dim3(tiles), dim3(kThreads), 0, s, (int)n, (int)nnz, rowptr,
+        hipLaunchKernelGGL((spmm_stream_kernel<LPR, BF16, true>), dim3(ranges), dim3(kWave), 0, s, (int)n, (int)nnz, rowptr,
                            colidx, dinv, static_cast<const char *>(h), static_cast<char *>(z), relu, ws.recs, ws.carry);
     else
-        hipLaunchKernelGGL((spmm_tile_kernel<LPR, BF16, false>), dim3(tiles), dim3(kThreads), 0, s, (int)n, (int)nnz, rowptr,
+        hipLaunchKernelGGL((spmm_stream_kernel<LPR, BF16, false>), dim3(ranges), dim3(kWave), 0, s, (int)n, (int)nnz, rowptr,
                            colidx, dinv, static_cast<const char *>(h), static_cast<char *>(z), relu, ws.recs, ws.carry);
     DGNN_RETURN_IF_LAUNCH_FAILED();
-    hipLaunchKernelGGL((spmm_carry_kernel<LPR, BF16>), dim3((tiles + G - 1) / G), dim3(kThreads), 0, s, tiles, ws.recs,
+    hipLaunchKernelGGL((spmm_carry_kernel<LPR, BF16>), dim3((ranges + G - 1) / G), dim3(256), 0, s, ranges, ws.recs,
                        ws.carry, dinv, static_cast<char *>(z), relu);
     DGNN_RETURN_IF_LAUNCH_FAILED();
     return DGNN_OK;
