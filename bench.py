@@ -166,7 +166,7 @@ def main():
                         "algorithmic_GBps": round(byts / (avg_ms * 1e-3) / 1e9, 1)}
     dominant = max(stages, key=lambda k: stages[k]["ms_per_step"])
     achieved = stages[dominant]["algorithmic_GBps"]
-    kernels = {"spmm": "dgnn_spmm (spmm_short_kernel + spmm_long_kernel + spmm_long_reduce_kernel)",
+    kernels = {"spmm": "dgnn_spmm (spmm_stream_kernel + spmm_carry_kernel)",
                "delta_rebuild": "dgnn_delta_rebuild (rowptr_kernel + merge_kernel)",
                "feature_transform": "dgnn_feature_transform (xw kernel)", "mproduct": "dgnn_mproduct (mproduct_kernel)"}
     roofline = {"bound": "hbm", "kernel": kernels[dominant], "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

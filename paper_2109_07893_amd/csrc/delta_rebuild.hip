@@ -24,7 +24,7 @@ constexpr int kRowTile = kRowThreads * kRowsPerThread;
 constexpr int kPerLane = 8;                  // old entries per lane and sub-tile of the merge
 constexpr int kSub = kWave * kPerLane;       // old entries per sub-tile, at most
 constexpr int kRange = kSub * 16;            // old entries streamed by one wavefront
-constexpr int kRowCap = 2 * kWave;           // consecutive rows staged per sub-tile
+constexpr int kRowCap = kWave;               // consecutive rows staged per sub-tile
 
 __device__ __forceinline__ void report(int32_t *status, int code) {
     if (!status) return;
@@ -69,10 +69,11 @@ __global__ __launch_bounds__(kRowThreads) void rowptr_kernel(
     const int nr = r1 - r0;
 
     if (blockIdx.x == 0 && tid == 0 && status) *status = 0;
-    if (tid < 4) {
-        const int32_t *list = tid < 2 ? add_row : del_row;
-        int len = tid < 2 ? n_add : n_del;
-        s_bound[tid] = lower_bound(list, 0, len, (tid & 1) ? r1 : r0);
+    {   // how many list entries have a row below r0 / below r1: one 64-ary search per wavefront
+        const int32_t *list = wave < 2 ? add_row : del_row;
+        const int len = wave < 2 ? n_add : n_del;
+        const int below = wave_find_row(list, len, ((wave & 1) ? r1 : r0) - 1, lane) + 1;
+        if (lane == 0) s_bound[wave] = below;
     }
     for (int i = tid; i < kRowTile; i += kRowThreads) { s_add[i] = 0; s_del[i] = 0; }
     __syncthreads();

@@ -35,7 +35,7 @@ typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
 constexpr int kBatch = 8;            // gathers issued together by a lane group
 constexpr int kPer = 32;             // entries a lane group walks per sub-tile (one mask word)
 constexpr int kRange = 8192;         // entries streamed by one wavefront
-constexpr int kRowCap = 2 * kWave;   // consecutive row pointers staged per sub-tile
+constexpr int kXcds = 8;             // accelerator dies of an MI355X, each with its own L2
 
 enum : int32_t { kLeft = 1, kLeftClosed = 2, kRight = 4 };
 struct RangeRec { int32_t flags, row_last, pad0, pad1; };
@@ -98,7 +98,7 @@ __device__ __forceinline__ void zero_row(char *z, int64_t row) {
 // (otherwise H already carries it).
 template <int LPR, bool BF16, bool SCALE_V>
 __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) void spmm_stream_kernel(
-    int n, int nnz, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+    int n, int nnz, int n_ranges, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const float *__restrict__ dinv, const char *__restrict__ h, char *__restrict__ z, int relu,
     RangeRec *__restrict__ recs, float *__restrict__ carry) {
     typedef typename Piece<BF16>::Raw Raw;
@@ -108,6 +108,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) v
     constexpr int SUB = G * kPer;           // entries per sub-tile
     constexpr int CPL = kPer / LPR;         // column indices held by one lane
     constexpr int kRowBytes = LPR * 16;
+    constexpr int kRowCap = SUB / 8 > kWave ? SUB / 8 : kWave;   // consecutive rows staged per sub-tile
     constexpr int ROUNDS = kRowCap / kWave;
 
     __shared__ int s_rp[kRowCap];           // row pointers of the staged rows
@@ -117,10 +118,16 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) v
 
     const int lane = threadIdx.x;
     const int sub = lane % LPR, g = lane / LPR, gbase = lane - sub;
-    const int e_begin = (int)((int64_t)blockIdx.x * kRange);
+    // Workgroups are dealt to the eight XCDs in turn, and each XCD has an L2 of its own: give XCD x the
+    // x-th contiguous eighth of the ranges, so that rows which lie close together (and in a graph with
+    // locality gather the same rows of H) meet in one L2.
+    const int per_xcd = (gridDim.x + kXcds - 1) / kXcds;
+    const int range = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+    if (range >= n_ranges) return;
+    const int e_begin = (int)((int64_t)range * kRange);
     const int e_end = (int)min((int64_t)e_begin + kRange, (int64_t)nnz);
     int k_cur = max(wave_find_row(rowptr, n, e_begin, lane), 0);   // a row with rowptr <= e_begin
-    if (blockIdx.x == 0)                     // rows without entries ahead of the first stored entry
+    if (range == 0)                          // rows without entries ahead of the first stored entry
         for (int k = lane; k < k_cur; k += kWave) zero_row<BF16, LPR>(z, k);
 
     // the row that is still open at the end of a sub-tile is carried on in the lanes of group 0
@@ -131,7 +138,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) v
     bool began_here = false;    // ... and it began inside this range
     int run_row = 0;
     int range_flags = 0;
-    float *my_carry = carry + (int64_t)blockIdx.x * 2 * F;
+    float *my_carry = carry + (int64_t)range * 2 * F;
 
     // column indices (and their dinv) of the coming sub-tile: lane holds entries e + 32 g + sub CPL + i
     int c_next[CPL];
@@ -409,7 +416,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) v
                 range_flags |= kLeft;
             }
         }
-        if (lane == 0) recs[blockIdx.x] = RangeRec{range_flags, run_row, 0, 0};
+        if (lane == 0) recs[range] = RangeRec{range_flags, run_row, 0, 0};
     }
     if (e_end == nnz)                                    // rows without entries beyond the last staged window
         for (int k = k_win + kRowCap - 1 + lane; k < n; k += kWave)
@@ -466,12 +473,13 @@ int launch(int64_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx,
            const void *h, void *z, int relu, const Workspace &ws, hipStream_t s) {
     constexpr int G = 256 / LPR;
     const int ranges = (int)((nnz + kRange - 1) / kRange);
+    const int grid = (ranges + kXcds - 1) / kXcds * kXcds;   // a whole number of rounds over the XCDs
     if (scale_v)
-        hipLaunchKernelGGL((spmm_stream_kernel<LPR, BF16, true>), dim3(ranges), dim3(kWave), 0, s, (int)n, (int)nnz, rowptr,
-                           colidx, dinv, static_cast<const char *>(h), static_cast<char *>(z), relu, ws.recs, ws.carry);
+        hipLaunchKernelGGL((spmm_stream_kernel<LPR, BF16, true>), dim3(grid), dim3(kWave), 0, s, (int)n, (int)nnz, ranges,
+                           rowptr, colidx, dinv, static_cast<const char *>(h), static_cast<char *>(z), relu, ws.recs, ws.carry);
     else
-        hipLaunchKernelGGL((spmm_stream_kernel<LPR, BF16, false>), dim3(ranges), dim3(kWave), 0, s, (int)n, (int)nnz, rowptr,
-                           colidx, dinv, static_cast<const char *>(h), static_cast<char *>(z), relu, ws.recs, ws.carry);
+        hipLaunchKernelGGL((spmm_stream_kernel<LPR, BF16, false>), dim3(grid), dim3(kWave), 0, s, (int)n, (int)nnz, ranges,
+                           rowptr, colidx, dinv, static_cast<const char *>(h), static_cast<char *>(z), relu, ws.recs, ws.carry);
     DGNN_RETURN_IF_LAUNCH_FAILED();
     hipLaunchKernelGGL((spmm_carry_kernel<LPR, BF16>), dim3((ranges + G - 1) / G), dim3(256), 0, s, ranges, ws.recs,
                        ws.carry, dinv, static_cast<char *>(z), relu);
