@@ -23,7 +23,8 @@ constexpr int kRowTile = kRowThreads * kRowsPerThread;
 
 constexpr int kPerLane = 8;                  // old entries per lane and sub-tile of the merge
 constexpr int kSub = kWave * kPerLane;       // old entries per sub-tile, at most
-constexpr int kRange = kSub * 16;            // old entries streamed by one wavefront
+constexpr int kMaxRange = kSub * 16;         // old entries streamed by one wavefront, at most
+constexpr int kTargetWaves = 16384;          // ranges shrink on small inputs so that about this many wavefronts exist
 constexpr int kRowCap = kWave;               // consecutive rows staged per sub-tile
 
 __device__ __forceinline__ void report(int32_t *status, int code) {
@@ -140,7 +141,7 @@ __device__ __forceinline__ int lds_bound(const int *a, int lo, int hi, int key) 
 // Lane l owns entries l, l + 64, ... of the sub-tile, so loads and stores coalesce; the column
 // indices of the next sub-tile are fetched while this one is placed.
 __global__ __launch_bounds__(kWave) void merge_kernel(
-    int n, const int32_t *__restrict__ rowptr_prev, const int32_t *__restrict__ colidx_prev, int nnz_prev,
+    int n, const int32_t *__restrict__ rowptr_prev, const int32_t *__restrict__ colidx_prev, int nnz_prev, int range_len,
     const int32_t *__restrict__ add_row, const int32_t *__restrict__ add_col, int n_add,
     const int32_t *__restrict__ del_row, const int32_t *__restrict__ del_col, int n_del,
     const int32_t *__restrict__ rowptr_next, const int32_t *__restrict__ add_ptr,
@@ -153,8 +154,8 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
     __shared__ int s_ap[kRowCap];
 
     const int lane = threadIdx.x;
-    const int e_begin = (int)((int64_t)blockIdx.x * kRange);
-    const int e_end = (int)min((int64_t)e_begin + kRange, (int64_t)nnz_prev);
+    const int e_begin = (int)((int64_t)blockIdx.x * range_len);
+    const int e_end = (int)min((int64_t)e_begin + range_len, (int64_t)nnz_prev);
     int k_cur = max(wave_find_row(rowptr_prev, n, e_begin, lane), 0);   // a row with rowptr <= e_begin
 
     int c_next[kPerLane];
@@ -495,8 +496,11 @@ extern "C" int dgnn_delta_rebuild(int64_t n,
                            (int)n_del, d_status);
         DGNN_RETURN_IF_LAUNCH_FAILED();
     }
-    hipLaunchKernelGGL(merge_kernel, dim3((unsigned)((nnz_prev + kRange - 1) / kRange)), dim3(kWave), 0, s,
-                       (int)n, rowptr_prev, colidx_prev, (int)nnz_prev, add_row, add_col, (int)n_add, del_row, del_col,
+    int64_t range_len = (nnz_prev + kTargetWaves - 1) / kTargetWaves;
+    range_len = (range_len + kSub - 1) / kSub * kSub;
+    if (range_len > kMaxRange) range_len = kMaxRange;
+    hipLaunchKernelGGL(merge_kernel, dim3((unsigned)((nnz_prev + range_len - 1) / range_len)), dim3(kWave), 0, s,
+                       (int)n, rowptr_prev, colidx_prev, (int)nnz_prev, (int)range_len, add_row, add_col, (int)n_add, del_row, del_col,
                        (int)n_del, rowptr_next, add_ptr, colidx_next, cap);
     DGNN_RETURN_IF_LAUNCH_FAILED();
     return DGNN_OK;

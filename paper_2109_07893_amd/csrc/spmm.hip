@@ -34,7 +34,8 @@ typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBatch = 8;            // gathers issued together by a lane group
 constexpr int kPer = 32;             // entries a lane group walks per sub-tile (one mask word)
-constexpr int kRange = 8192;         // entries streamed by one wavefront
+constexpr int kMaxRange = 8192;      // entries streamed by one wavefront, at most
+constexpr int kTargetWaves = 16384;  // ranges shrink on small inputs so that about this many wavefronts exist
 constexpr int kXcds = 8;             // accelerator dies of an MI355X, each with its own L2
 
 enum : int32_t { kLeft = 1, kLeftClosed = 2, kRight = 4 };
@@ -98,7 +99,7 @@ __device__ __forceinline__ void zero_row(char *z, int64_t row) {
 // (otherwise H already carries it).
 template <int LPR, bool BF16, bool SCALE_V>
 __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) void spmm_stream_kernel(
-    int n, int nnz, int n_ranges, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+    int n, int nnz, int range_len, int n_ranges, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const float *__restrict__ dinv, const char *__restrict__ h, char *__restrict__ z, int relu,
     RangeRec *__restrict__ recs, float *__restrict__ carry) {
     typedef typename Piece<BF16>::Raw Raw;
@@ -124,8 +125,8 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) v
     const int per_xcd = (gridDim.x + kXcds - 1) / kXcds;
     const int range = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
     if (range >= n_ranges) return;
-    const int e_begin = (int)((int64_t)range * kRange);
-    const int e_end = (int)min((int64_t)e_begin + kRange, (int64_t)nnz);
+    const int e_begin = (int)((int64_t)range * range_len);
+    const int e_end = (int)min((int64_t)e_begin + range_len, (int64_t)nnz);
     int k_cur = max(wave_find_row(rowptr, n, e_begin, lane), 0);   // a row with rowptr <= e_begin
     if (range == 0)                          // rows without entries ahead of the first stored entry
         for (int k = lane; k < k_cur; k += kWave) zero_row<BF16, LPR>(z, k);
@@ -456,8 +457,18 @@ struct Workspace {
     float *carry;
 };
 
+// Entries per wavefront: a multiple of the sub-tile, at most kMaxRange, smaller when the input is small.
+int range_length(int64_t nnz, int sub_tile) {
+    int64_t len = (nnz + kTargetWaves - 1) / kTargetWaves;
+    len = (len + sub_tile - 1) / sub_tile * sub_tile;
+    if (len > kMaxRange) len = kMaxRange;
+    return (int)len;
+}
+
+// Sized for the shortest range a width can get (sub-tile of 64 entries), so one query serves both dtypes.
 size_t workspace_layout(int64_t nnz, int32_t f, Workspace *ws, void *base) {
-    const int64_t ranges = (nnz + kRange - 1) / kRange + 1;
+    const int shortest = range_length(nnz, kWave);
+    const int64_t ranges = (nnz + shortest - 1) / shortest + 1;
     const size_t o_carry = round_up((size_t)ranges * sizeof(RangeRec), 256);
     const size_t total = o_carry + round_up((size_t)ranges * 2 * f * sizeof(float), 256);
     if (ws) {
@@ -472,13 +483,14 @@ template <int LPR, bool BF16>
 int launch(int64_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *dinv, bool scale_v,
            const void *h, void *z, int relu, const Workspace &ws, hipStream_t s) {
     constexpr int G = 256 / LPR;
-    const int ranges = (int)((nnz + kRange - 1) / kRange);
+    const int range_len = range_length(nnz, (kWave / LPR) * kPer);
+    const int ranges = (int)((nnz + range_len - 1) / range_len);
     const int grid = (ranges + kXcds - 1) / kXcds * kXcds;   // a whole number of rounds over the XCDs
     if (scale_v)
-        hipLaunchKernelGGL((spmm_stream_kernel<LPR, BF16, true>), dim3(grid), dim3(kWave), 0, s, (int)n, (int)nnz, ranges,
+        hipLaunchKernelGGL((spmm_stream_kernel<LPR, BF16, true>), dim3(grid), dim3(kWave), 0, s, (int)n, (int)nnz, range_len, ranges,
                            rowptr, colidx, dinv, static_cast<const char *>(h), static_cast<char *>(z), relu, ws.recs, ws.carry);
     else
-        hipLaunchKernelGGL((spmm_stream_kernel<LPR, BF16, false>), dim3(grid), dim3(kWave), 0, s, (int)n, (int)nnz, ranges,
+        hipLaunchKernelGGL((spmm_stream_kernel<LPR, BF16, false>), dim3(grid), dim3(kWave), 0, s, (int)n, (int)nnz, range_len, ranges,
                            rowptr, colidx, dinv, static_cast<const char *>(h), static_cast<char *>(z), relu, ws.recs, ws.carry);
     DGNN_RETURN_IF_LAUNCH_FAILED();
     hipLaunchKernelGGL((spmm_carry_kernel<LPR, BF16>), dim3((ranges + G - 1) / G), dim3(256), 0, s, ranges, ws.recs,
