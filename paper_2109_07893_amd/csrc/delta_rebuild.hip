@@ -25,7 +25,6 @@ constexpr int kPerLane = 8;                  // old entries per lane and sub-til
 constexpr int kSub = kWave * kPerLane;       // old entries per sub-tile, at most
 constexpr int kMaxRange = kSub * 16;         // old entries streamed by one wavefront, at most
 constexpr int kTargetWaves = 16384;          // ranges shrink on small inputs so that about this many wavefronts exist
-constexpr int kRowCap = kWave;               // consecutive rows staged per sub-tile
 
 __device__ __forceinline__ void report(int32_t *status, int code) {
     if (!status) return;
@@ -127,17 +126,19 @@ __device__ __forceinline__ int lds_bound(const int *a, int lo, int hi, int key) 
     return lo;
 }
 
-// One wavefront streams a contiguous range of old entries in sub-tiles of up to kSub entries.
+// One wavefront streams a contiguous range of old entries in sub-tiles of kSub entries.
 // The work per OLD entry is a load, a position from a prefix sum, and a store; everything that
 // needs a search is done per DIFFERENCE entry, of which there are few:
-//   - kRowCap consecutive rows (rowptr_prev, rowptr_next, add_ptr) are staged in LDS; the row that
-//     holds the range's first entry is searched once, afterwards the rows simply follow on;
 //   - the sub-tile's column indices are staged in LDS; each deleted entry that falls into the
 //     sub-tile finds its old entry there by binary search and marks it dead, each added entry
-//     finds the old entry it goes in front of (its slot) and counts itself there; both lists
-//     are consumed in order through two cursors, so no search of the lists is ever needed;
+//     finds the old entry it goes in front of (its slot) and counts itself there.  Where the row
+//     of a difference entry lies inside the sub-tile follows from two row pointers of A_prev,
+//     fetched together with the entry itself one sub-tile ahead;
+//   - both lists are consumed in order through two cursors, so the lists are never searched
+//     (except once, where a range begins in the middle of a row);
 //   - one prefix sum over (alive, added-before) gives every old entry and every slot its place
-//     relative to the sub-tile's first output position, which follows from rowptr_next.
+//     relative to the sub-tile's first output position; that position follows from rowptr_next
+//     at the start of the range and simply advances by what each sub-tile wrote.
 // Lane l owns entries l, l + 64, ... of the sub-tile, so loads and stores coalesce; the column
 // indices of the next sub-tile are fetched while this one is placed.
 __global__ __launch_bounds__(kWave) void merge_kernel(
@@ -149,14 +150,10 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
     __shared__ int s_col[kSub];
     __shared__ int s_mark[kSub + kWave];    // bit 0: deleted; bits 1..: added entries that go right before this slot
     __shared__ int s_start[kSub + kWave];   // outputs (kept + added) that precede the slot's block
-    __shared__ int s_rp[kRowCap];
-    __shared__ int s_rn[kRowCap];
-    __shared__ int s_ap[kRowCap];
 
     const int lane = threadIdx.x;
     const int e_begin = (int)((int64_t)blockIdx.x * range_len);
     const int e_end = (int)min((int64_t)e_begin + range_len, (int64_t)nnz_prev);
-    int k_cur = max(wave_find_row(rowptr_prev, n, e_begin, lane), 0);   // a row with rowptr <= e_begin
 
     int c_next[kPerLane];
 #pragma unroll
@@ -164,50 +161,47 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
         const int i = e_begin + lane + j * kWave;
         c_next[j] = i < e_end ? colidx_prev[i] : 0;
     }
-    int a_cur = 0, d_cur = 0;   // first added / deleted entry not yet placed
-    // fetched ahead of use: the next sub-tile's rows, and the 64 difference entries at each cursor
-    int m_v[kRowCap / kWave], m_rn[kRowCap / kWave], m_ap[kRowCap / kWave];
-    bool have_rows = false;
-    int pa_row = 0, pa_col = 0, pd_row = 0, pd_col = 0;
-    int e = e_begin;
-    while (e < e_end) {
-        // ---- stage rows k_cur .. k_cur + kRowCap - 1
-        int le_e = 0;             // staged rows that begin at or before e
-        int v_[kRowCap / kWave];
-#pragma unroll
-        for (int round = 0; round < kRowCap / kWave; ++round) {
-            const int t = lane + round * kWave;
-            const int k = k_cur + t;
-            const bool ok = k <= n;
-            if (!have_rows) {
-                m_v[round] = ok ? rowptr_prev[k] : 0x7fffffff;
-                m_rn[round] = ok ? rowptr_next[k] : 0;
-                m_ap[round] = ok ? add_ptr[k] : 0;
-            }
-            v_[round] = m_v[round];
-            s_rp[t] = m_v[round];
-            s_rn[t] = m_rn[round];
-            s_ap[t] = m_ap[round];
-            le_e += __popcll(__ballot(v_[round] <= e));
+
+    // ---- start of the range: its row, the list cursors, the first output position
+    const int k0 = max(wave_find_row(rowptr_prev, n, e_begin, lane), 0);   // row that holds entry e_begin
+    int a_cur, d_cur;   // first added / deleted entry not yet placed
+    int base;           // output position of the next entry to be written
+    {
+        const int rp = rowptr_prev[k0], rp1 = rowptr_prev[k0 + 1];
+        const int rn = rowptr_next[k0], rn1 = rowptr_next[k0 + 1];
+        const int as = add_ptr[k0], ae = add_ptr[k0 + 1];
+        const int ds = rp + as - rn, de = rp1 + ae - rn1;
+        a_cur = as;
+        d_cur = ds;
+        if (rp < e_begin) {   // the range begins inside row k0: skip what earlier ranges place
+            if (as >= 0 && as < ae && ae <= n_add) a_cur = lower_bound(add_col, as, ae, colidx_prev[e_begin - 1]);
+            if (ds >= 0 && ds < de && de <= n_del) d_cur = lower_bound(del_col, ds, de, colidx_prev[e_begin]);
         }
-        have_rows = false;
-        const int t0 = max(le_e - 1, 0);                 // the staged row that holds entry e
-        if (t0 >= kRowCap - 1) {                         // only rows without entries were staged: move on
-            k_cur += kRowCap - 1;
-            __syncthreads();
-            continue;
+        a_cur = min(max(a_cur, 0), n_add);
+        d_cur = min(max(d_cur, 0), n_del);
+        base = rn + (e_begin - rp) - (d_cur - ds) + (a_cur - as);
+    }
+    // the 64 list entries at each cursor, with the extent of their rows in A_prev, are fetched ahead of use
+    int pa_col = 0, pa_lo = 0, pa_hi = 0, pd_col = 0, pd_lo = 0, pd_hi = 0;
+    auto fetch_lists = [&]() {
+        pa_lo = pd_lo = 0x7fffffff;      // "row begins beyond everything": not owned
+        pa_hi = pd_hi = 0x7fffffff;
+        if (a_cur + lane < n_add) {
+            const int r = add_row[a_cur + lane];
+            pa_col = add_col[a_cur + lane];
+            if ((unsigned)r < (unsigned)n) { pa_lo = rowptr_prev[r]; pa_hi = rowptr_prev[r + 1]; }
         }
-        const int v_last = __shfl(v_[kRowCap / kWave - 1], kWave - 1, kWave);   // start of the last staged row (> e)
-        const int e_stop = min(min(e + kSub, e_end), v_last);
+        if (d_cur + lane < n_del) {
+            const int r = del_row[d_cur + lane];
+            pd_col = del_col[d_cur + lane];
+            if ((unsigned)r < (unsigned)n) { pd_lo = rowptr_prev[r]; pd_hi = rowptr_prev[r + 1]; }
+        }
+    };
+    fetch_lists();
+
+    for (int e = e_begin; e < e_end; e += kSub) {
+        const int e_stop = min(e + kSub, e_end);
         const int cnt = e_stop - e;
-        int le_stop = 0, lt_stop = 0;
-#pragma unroll
-        for (int round = 0; round < kRowCap / kWave; ++round) {
-            le_stop += __popcll(__ballot(v_[round] <= e_stop));
-            lt_stop += __popcll(__ballot(v_[round] < e_stop));
-        }
-        const int t_last = lt_stop - 1;                  // last staged row with entries in this sub-tile
-        const int k_next = k_cur + le_stop - 1;          // a row with rowptr <= e_stop: first row of the next sub-tile
         int c_[kPerLane];
 #pragma unroll
         for (int j = 0; j < kPerLane; ++j) {
@@ -216,93 +210,70 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
             s_mark[lane + j * kWave] = 0;
         }
         s_mark[kSub + lane] = 0;
-        // what follows e_stop is fetched while this sub-tile is placed: column indices and rows
-        if (e_stop < e_end) {
 #pragma unroll
-            for (int j = 0; j < kPerLane; ++j) {
-                const int i = e_stop + lane + j * kWave;
-                c_next[j] = i < e_end ? colidx_prev[i] : 0;
-            }
-#pragma unroll
-            for (int round = 0; round < kRowCap / kWave; ++round) {
-                const int k = k_next + lane + round * kWave;
-                const bool ok = k <= n;
-                m_v[round] = ok ? rowptr_prev[k] : 0x7fffffff;
-                m_rn[round] = ok ? rowptr_next[k] : 0;
-                m_ap[round] = ok ? add_ptr[k] : 0;
-            }
-            have_rows = true;
+        for (int j = 0; j < kPerLane; ++j) {      // fetched while this sub-tile is placed
+            const int i = e_stop + lane + j * kWave;
+            c_next[j] = i < e_end ? colidx_prev[i] : 0;
         }
         __syncthreads();
 
-        const int as0 = s_ap[t0], ds0 = s_rp[t0] + s_ap[t0] - s_rn[t0];
-        if (e == e_begin) {       // cursors of a range that starts inside a row: one search each
-            a_cur = as0;
-            d_cur = ds0;
-            if (s_rp[t0] < e) {
-                const int ae0 = s_ap[t0 + 1], de0 = s_rp[t0 + 1] + ae0 - s_rn[t0 + 1];
-                if (as0 >= 0 && as0 < ae0 && ae0 <= n_add) a_cur = lower_bound(add_col, as0, ae0, colidx_prev[e - 1]);
-                if (ds0 >= 0 && ds0 < de0 && de0 <= n_del) d_cur = lower_bound(del_col, ds0, de0, s_col[0]);
-            }
-            a_cur = max(a_cur, 0);
-            d_cur = max(d_cur, 0);
-            if (a_cur + lane < n_add) { pa_row = add_row[a_cur + lane]; pa_col = add_col[a_cur + lane]; }
-            if (d_cur + lane < n_del) { pd_row = del_row[d_cur + lane]; pd_col = del_col[d_cur + lane]; }
-        }
-        // first output position of this sub-tile: row start, plus what its row kept and gained so far
-        const int base = s_rn[t0] + (e - s_rp[t0]) - (d_cur - ds0) + (a_cur - as0);
-        const int a_tile = a_cur;
-        const int a_lim = min(s_ap[t_last + 1], n_add);
-        const int d_lim = min(s_rp[t_last + 1] + s_ap[t_last + 1] - s_rn[t_last + 1], n_del);
-
         // ---- deleted entries: mark the old entry dead
         {
-            int row = pd_row, c = pd_col;
-            for (int j0 = d_cur; j0 < d_lim; j0 += kWave) {
+            int c = pd_col, lo_g = pd_lo, hi_g = pd_hi;
+            for (int j0 = d_cur;; j0 += kWave) {
                 const int j = j0 + lane;
-                if (j0 != d_cur && j < d_lim) { row = del_row[j]; c = del_col[j]; }
+                if (j0 != d_cur) {
+                    lo_g = hi_g = 0x7fffffff;
+                    if (j < n_del) {
+                        const int r = del_row[j];
+                        c = del_col[j];
+                        if ((unsigned)r < (unsigned)n) { lo_g = rowptr_prev[r]; hi_g = rowptr_prev[r + 1]; }
+                    }
+                }
                 bool owned = false;
-                const int t = row - k_cur;
-                if (j < d_lim && t >= t0 && t <= t_last) {
-                    const int lo = max(s_rp[t] - e, 0), hi = min(s_rp[t + 1] - e, cnt);
+                if (j < n_del && lo_g < e_stop && hi_g > e) {        // its row has entries in this sub-tile
+                    const int lo = max(lo_g - e, 0), hi = min(hi_g - e, cnt);
                     const int p = lds_bound<false>(s_col, lo, hi, c);
                     owned = p < hi && s_col[p] == c;
                     if (owned) atomicOr(&s_mark[p], 1);
                 }
                 const int got = __popcll(__ballot(owned));
                 if (got < kWave) { d_cur = j0 + got; break; }
-                if (j0 + kWave >= d_lim) d_cur = j0 + kWave;
             }
         }
         // ---- added entries: count at the slot (old entry they precede; a row's end if none)
+        const int a_tile = a_cur;
         int q_first = -2 - lane, c_first = 0;     // slot and column of the first 64, kept for the write below
         {
-            int row = pa_row, c = pa_col;
-            const int start = a_cur;
-            for (int j0 = start; j0 < a_lim; j0 += kWave) {
+            int c = pa_col, lo_g = pa_lo, hi_g = pa_hi;
+            for (int j0 = a_tile;; j0 += kWave) {
                 const int j = j0 + lane;
-                if (j0 != start && j < a_lim) { row = add_row[j]; c = add_col[j]; }
+                if (j0 != a_tile) {
+                    lo_g = hi_g = 0x7fffffff;
+                    if (j < n_add) {
+                        const int r = add_row[j];
+                        c = add_col[j];
+                        if ((unsigned)r < (unsigned)n) { lo_g = rowptr_prev[r]; hi_g = rowptr_prev[r + 1]; }
+                    }
+                }
                 bool owned = false;
-                const int t = row - k_cur;
                 int q = -2 - lane;
-                if (j < a_lim && t >= t0 && t <= t_last) {
-                    const int lo = max(s_rp[t] - e, 0), hi = min(s_rp[t + 1] - e, cnt);
+                if (j < n_add && lo_g < e_stop && hi_g > e) {
+                    const int lo = max(lo_g - e, 0), hi = min(hi_g - e, cnt);
                     q = lds_bound<true>(s_col, lo, hi, c);
-                    owned = q < hi || s_rp[t + 1] <= e_stop;      // beyond the sub-tile's part of an unfinished row: later
+                    owned = q < hi || hi_g <= e_stop;      // beyond the sub-tile's part of an unfinished row: later
                     if (owned) atomicAdd(&s_mark[q], 2);
                 }
-                if (j0 == start) { q_first = owned ? q : -2 - lane; c_first = c; }
+                if (j0 == a_tile) { q_first = owned ? q : -2 - lane; c_first = c; }
                 const int got = __popcll(__ballot(owned));
                 if (got < kWave) { a_cur = j0 + got; break; }
-                if (j0 + kWave >= a_lim) a_cur = j0 + kWave;
             }
         }
-        // the difference entries at the new cursors, for the next sub-tile
-        if (a_cur + lane < n_add) { pa_row = add_row[a_cur + lane]; pa_col = add_col[a_cur + lane]; }
-        if (d_cur + lane < n_del) { pd_row = del_row[d_cur + lane]; pd_col = del_col[d_cur + lane]; }
+        fetch_lists();            // the list entries at the new cursors, for the next sub-tile
         __syncthreads();
 
         // ---- prefix sums: s_start[p] = kept entries before p + added entries of slots before p
+        int written;
         {
             int mk[kPerLane];
             int alive = 0, ins = 0;
@@ -322,6 +293,7 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
                 run += ((p < cnt && !(mk[j] & 1)) ? 1 : 0) + (mk[j] >> 1);
             }
             if (lane == kWave - 1) s_start[kSub] = run;   // slot "after the last entry" of a full sub-tile
+            written = __shfl(run, kWave - 1, kWave) + (s_mark[kSub] >> 1);
         }
         __syncthreads();
 
@@ -343,9 +315,9 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
             if (j0 != a_tile) {
                 q = -2 - lane;
                 if (j < a_cur) {
-                    const int t = add_row[j] - k_cur;
+                    const int r = add_row[j];
                     c = add_col[j];
-                    const int lo = max(s_rp[t] - e, 0), hi = min(s_rp[t + 1] - e, cnt);
+                    const int lo = max(rowptr_prev[r] - e, 0), hi = min(rowptr_prev[r + 1] - e, cnt);
                     q = lds_bound<true>(s_col, lo, hi, c);
                 }
             }
@@ -363,8 +335,7 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
             q_carry = __shfl(q, kWave - 1, kWave);
             rank_carry = __shfl(rank, kWave - 1, kWave) + 1;
         }
-        k_cur = k_next;
-        e = e_stop;
+        base += written;
         __syncthreads();           // LDS is rewritten by the next sub-tile
     }
 }
