@@ -21,6 +21,7 @@
 // Hub rows of power-law graphs are thereby spread over as many wavefronts as they have ranges,
 // short rows share a wavefront, and every sum has a fixed order: no floating-point atomics,
 // results repeat bit for bit.
+#include <algorithm>
 #include <type_traits>
 
 #include "common.hpp"
@@ -465,10 +466,11 @@ int range_length(int64_t nnz, int sub_tile) {
     return (int)len;
 }
 
-// Sized for the shortest range a width can get (sub-tile of 64 entries), so one query serves both dtypes.
+// Sized for the largest number of ranges any call with at most nnz entries can have (a smaller snapshot gets
+// shorter ranges, never more than kTargetWaves + 1 of them), so a buffer queried for the largest snapshot of a
+// block serves every snapshot of it, and both dtypes.
 size_t workspace_layout(int64_t nnz, int32_t f, Workspace *ws, void *base) {
-    const int shortest = range_length(nnz, kWave);
-    const int64_t ranges = (nnz + shortest - 1) / shortest + 1;
+    const int64_t ranges = std::max<int64_t>(kTargetWaves + 1, (nnz + kMaxRange - 1) / kMaxRange) + 1;
     const size_t o_carry = round_up((size_t)ranges * sizeof(RangeRec), 256);
     const size_t total = o_carry + round_up((size_t)ranges * 2 * f * sizeof(float), 256);
     if (ws) {
