@@ -8,9 +8,14 @@
 // Operand mapping.  In a 32x32xK MFMA, lane l supplies row (l % 32) of A and column (l % 32)
 // of B for the k-slice selected by h = l / 32.  The order in which k is consumed is free as
 // long as A and B agree, so lane (i, h) owns the contiguous k range [h F/2, (h+1) F/2) of its
-// row: step s of the fp32 kernel multiplies k = h F/2 + s, step s of the bf16 kernel the eight
-// values k = h F/2 + 8 s .. + 7.  The accumulator of a 32x32 tile holds, in register v of lane
-// l, the element (row 8 (v / 4) + 4 (l / 32) + v % 4, column l % 32).
+// row of X: step s of the fp32 kernel multiplies k = h F/2 + s, step s of the bf16 kernel the
+// eight values k = h F/2 + 8 s .. + 7.  The accumulator of a 32x32 tile holds, in register v of
+// lane l, the element (row 8 (v / 4) + 4 (l / 32) + v % 4, column l % 32).  The fp32 kernel
+// stores that layout as it is: per register the two lane halves write two whole 128-byte lines.
+// The bf16 kernel computes the TRANSPOSED tile, (X W)^T = W^T X^T, with W^T as the A operand and
+// the rows of X as the B operand: lane (i, h) then holds row i of the result and, in every four
+// consecutive accumulator registers, four consecutive columns of it, which turns sixty-four
+// 2-byte stores per lane into sixteen 8-byte ones and makes row_scale one value per lane.
 #include "common.hpp"
 
 namespace {
@@ -42,18 +47,30 @@ __global__ __launch_bounds__(kThreads) void xw_f32_kernel(const float *__restric
 
     const int lane = tid & (kWave - 1), wave = tid / kWave;
     const int i = lane & 31, hh = lane >> 5;
-    for (int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wave; tile < n_tiles;
-         tile += (int64_t)gridDim.x * kWavesPerBlock) {
-        const int64_t row = tile * 32 + i;
-        floatx4 a[KH / 4];
-        if (row < n) {
+    const int64_t stride = (int64_t)gridDim.x * kWavesPerBlock;
+    int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wave;
+
+    floatx4 a_next[KH / 4];
+    float sc_next = 1.0f;
+    auto fetch = [&](int64_t t) {
+        const int64_t row = t * 32 + i;
+        if (t < n_tiles && row < n) {
             const floatx4 *src = reinterpret_cast<const floatx4 *>(x + row * FIN + hh * KH);
 #pragma unroll
-            for (int q = 0; q < KH / 4; ++q) a[q] = src[q];
+            for (int q = 0; q < KH / 4; ++q) a_next[q] = src[q];
+            sc_next = row_scale ? row_scale[row] : 1.0f;
         } else {
 #pragma unroll
-            for (int q = 0; q < KH / 4; ++q) a[q] = floatx4{0.f, 0.f, 0.f, 0.f};
+            for (int q = 0; q < KH / 4; ++q) a_next[q] = floatx4{0.f, 0.f, 0.f, 0.f};
         }
+    };
+    fetch(tile);
+    for (; tile < n_tiles; tile += stride) {
+        floatx4 a[KH / 4];
+#pragma unroll
+        for (int q = 0; q < KH / 4; ++q) a[q] = a_next[q];
+        const float scale = sc_next;
+        fetch(tile + stride);              // the next tile's rows travel while this one is multiplied
         floatx16 acc[NT];
 #pragma unroll
         for (int jt = 0; jt < NT; ++jt)
@@ -61,26 +78,25 @@ __global__ __launch_bounds__(kThreads) void xw_f32_kernel(const float *__restric
             for (int v = 0; v < 16; ++v) acc[jt][v] = 0.0f;
 #pragma unroll
         for (int s = 0; s < KH; ++s) {
-            const float av = a[s / 4][s % 4];
+            const float xv = a[s / 4][s % 4];
 #pragma unroll
             for (int jt = 0; jt < NT; ++jt) {
-                const float bv = s_w[(hh * KH + s) * LD + jt * 32 + i];
-                acc[jt] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[jt], 0, 0, 0);
+                const float wv = s_w[(hh * KH + s) * LD + jt * 32 + i];
+                acc[jt] = __builtin_amdgcn_mfma_f32_32x32x2f32(xv, wv, acc[jt], 0, 0, 0);
             }
         }
-        float scale[16];   // row_scale of the 16 rows this lane stores: one coalesced load, then lane exchange
-        {
-            const float mine = (row_scale && row < n) ? row_scale[row] : 1.0f;   // lane (i, hh) holds row i
+        // register v of lane (i, hh) holds row 8 (v / 4) + 4 hh + v % 4, column i of the tile: per register the
+        // two lane halves write two whole 128-byte rows
+        float sc[16];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) scale[v] = __shfl(mine, 8 * (v / 4) + 4 * hh + (v % 4), kWave);
-        }
+        for (int v = 0; v < 16; ++v) sc[v] = __shfl(scale, 8 * (v / 4) + 4 * hh + (v % 4), kWave);
 #pragma unroll
         for (int jt = 0; jt < NT; ++jt) {
             const int col = jt * 32 + i;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int64_t r = tile * 32 + 8 * (v / 4) + 4 * hh + (v % 4);
-                if (r < n && col < FOUT) h[r * FOUT + col] = acc[jt][v] * scale[v];
+                if (r < n && col < FOUT) h[r * FOUT + col] = acc[jt][v] * sc[v];
             }
         }
     }
@@ -105,20 +121,32 @@ __global__ __launch_bounds__(kThreads) void xw_bf16_kernel(const uint16_t *__res
 
     const int lane = tid & (kWave - 1), wave = tid / kWave;
     const int i = lane & 31, hh = lane >> 5;
-    for (int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wave; tile < n_tiles;
-         tile += (int64_t)gridDim.x * kWavesPerBlock) {
-        const int64_t row = tile * 32 + i;
-        bf16x8 a[KS];
-        if (row < n) {
+    const int64_t stride = (int64_t)gridDim.x * kWavesPerBlock;
+    int64_t tile = (int64_t)blockIdx.x * kWavesPerBlock + wave;
+
+    bf16x8 a_next[KS];
+    float sc_next = 1.0f;
+    auto fetch = [&](int64_t t) {
+        const int64_t row = t * 32 + i;
+        if (t < n_tiles && row < n) {
             const bf16x8 *src = reinterpret_cast<const bf16x8 *>(x + row * FIN + hh * KH);
 #pragma unroll
-            for (int s = 0; s < KS; ++s) a[s] = src[s];
+            for (int s = 0; s < KS; ++s) a_next[s] = src[s];
+            sc_next = row_scale ? row_scale[row] : 1.0f;
         } else {
 #pragma unroll
             for (int s = 0; s < KS; ++s)
 #pragma unroll
-                for (int e = 0; e < 8; ++e) a[s][e] = (__bf16)0.0f;
+                for (int e = 0; e < 8; ++e) a_next[s][e] = (__bf16)0.0f;
         }
+    };
+    fetch(tile);
+    for (; tile < n_tiles; tile += stride) {
+        bf16x8 a[KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) a[s] = a_next[s];
+        const float scale = sc_next;
+        fetch(tile + stride);
         floatx16 acc[NT];
 #pragma unroll
         for (int jt = 0; jt < NT; ++jt)
@@ -128,24 +156,23 @@ __global__ __launch_bounds__(kThreads) void xw_bf16_kernel(const uint16_t *__res
         for (int s = 0; s < KS; ++s) {
 #pragma unroll
             for (int jt = 0; jt < NT; ++jt) {
-                const bf16x8 bv = *reinterpret_cast<const bf16x8 *>(&s_wt[(jt * 32 + i) * LDW + hh * KH + s * 8]);
-                acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s], bv, acc[jt], 0, 0, 0);
+                const bf16x8 wv = *reinterpret_cast<const bf16x8 *>(&s_wt[(jt * 32 + i) * LDW + hh * KH + s * 8]);
+                acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, a[s], acc[jt], 0, 0, 0);   // (X W)^T tile
             }
         }
-        float scale[16];   // row_scale of the 16 rows this lane stores: one coalesced load, then lane exchange
-        {
-            const float mine = (row_scale && row < n) ? row_scale[row] : 1.0f;   // lane (i, hh) holds row i
+        const int64_t row = tile * 32 + i;
+        if (row < n) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) scale[v] = __shfl(mine, 8 * (v / 4) + 4 * hh + (v % 4), kWave);
-        }
+            for (int jt = 0; jt < NT; ++jt)
 #pragma unroll
-        for (int jt = 0; jt < NT; ++jt) {
-            const int col = jt * 32 + i;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int64_t r = tile * 32 + 8 * (v / 4) + 4 * hh + (v % 4);
-                if (r < n && col < FOUT) h[r * FOUT + col] = (uint16_t)f32_to_bf16(acc[jt][v] * scale[v]);
-            }
+                for (int g = 0; g < 4; ++g) {
+                    const int col = jt * 32 + 8 * g + 4 * hh;
+                    if (col < FOUT) {
+                        const uint32_t lo = f32_to_bf16(acc[jt][4 * g] * scale) | (f32_to_bf16(acc[jt][4 * g + 1] * scale) << 16);
+                        const uint32_t hi = f32_to_bf16(acc[jt][4 * g + 2] * scale) | (f32_to_bf16(acc[jt][4 * g + 3] * scale) << 16);
+                        *reinterpret_cast<uint2 *>(h + row * FOUT + col) = make_uint2(lo, hi);
+                    }
+                }
         }
     }
 }

@@ -5,6 +5,9 @@
 // last w frames of its piece in a register ring, so every frame is read once and written once
 // (2 s N F bytes per timestep) whatever the window, and the transform can run in place.
 // The time loop is unrolled by the ring size so that ring slots are compile-time registers.
+// With the paper's weights (every term 1/min(w,t)) the window sum is kept as a running sum,
+// S_t = S_{t-1} + Z_t - Z_{t-w}, with a ring of exactly w slots (the slot about to be overwritten
+// holds Z_{t-w}); explicit coefficients take the general kernel, w multiply-adds per element.
 #include "common.hpp"
 
 namespace {
@@ -27,6 +30,10 @@ template <> struct Vec<false> {
     static __device__ __forceinline__ void store(char *p, const float (&v)[4]) {
         *reinterpret_cast<floatx4 *>(p) = floatx4{v[0], v[1], v[2], v[3]};
     }
+    static __device__ __forceinline__ void unpack(float (&v)[4], uintx4 t) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = __uint_as_float(t[e]);
+    }
 };
 template <> struct Vec<true> {
     static constexpr int kVals = 8;
@@ -43,6 +50,13 @@ template <> struct Vec<true> {
 #pragma unroll
         for (int e = 0; e < 4; ++e) t[e] = f32_to_bf16(v[2 * e]) | (f32_to_bf16(v[2 * e + 1]) << 16);
         *reinterpret_cast<uintx4 *>(p) = t;
+    }
+    static __device__ __forceinline__ void unpack(float (&v)[8], uintx4 t) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            v[2 * e] = __uint_as_float(t[e] << 16);
+            v[2 * e + 1] = __uint_as_float(t[e] & 0xffff0000u);
+        }
     }
 };
 
@@ -91,6 +105,69 @@ __global__ __launch_bounds__(kThreads) void mproduct_kernel(const char *z, char 
     }
 }
 
+// The paper's weights: ring of exactly W raw 16-byte pieces, running window sum in fp32.
+template <int W, bool BF16>
+__global__ __launch_bounds__(kThreads) void mproduct_uniform_kernel(const char *z, char *y, int T, int64_t pieces,
+                                                                    int64_t frame_bytes) {
+    constexpr int NV = Vec<BF16>::kVals;
+    const int64_t piece = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (piece >= pieces) return;
+    const char *src = z + piece * 16;
+    char *dst = y + piece * 16;
+
+    uintx4 ring[W];
+#pragma unroll
+    for (int r = 0; r < W; ++r) ring[r] = uintx4{0u, 0u, 0u, 0u};   // the bit pattern of zeros in either type
+    float sum[NV];
+#pragma unroll
+    for (int e = 0; e < NV; ++e) sum[e] = 0.0f;
+
+    uintx4 next = *reinterpret_cast<const uintx4 *>(src);
+    for (int tb = 0; tb < T; tb += W) {
+#pragma unroll
+        for (int jj = 0; jj < W; ++jj) {
+            const int t = tb + jj;             // 0-based timestep; slot jj holds frame t - W
+            if (t < T) {
+                const uintx4 cur = next;
+                if (t + 1 < T) next = *reinterpret_cast<const uintx4 *>(src + (int64_t)(t + 1) * frame_bytes);   // before the store: y may be z
+                float in[NV], old[NV], out[NV];
+                Vec<BF16>::unpack(in, cur);
+                Vec<BF16>::unpack(old, ring[jj]);
+                ring[jj] = cur;
+                const float scale = 1.0f / (float)min(W, t + 1);
+#pragma unroll
+                for (int e = 0; e < NV; ++e) {
+                    sum[e] += in[e] - old[e];
+                    out[e] = sum[e] * scale;
+                }
+                Vec<BF16>::store(dst + (int64_t)t * frame_bytes, out);
+            }
+        }
+    }
+}
+
+template <int W>
+int launch_uniform(const void *z, void *y, int64_t T, int64_t n, int32_t f, dgnn_dtype dt, hipStream_t s) {
+    const int64_t frame_bytes = n * f * (dt == DGNN_F32 ? 4 : 2);
+    const int64_t pieces = frame_bytes / 16;
+    const unsigned blocks = (unsigned)((pieces + kThreads - 1) / kThreads);
+    if (dt == DGNN_F32)
+        hipLaunchKernelGGL((mproduct_uniform_kernel<W, false>), dim3(blocks), dim3(kThreads), 0, s,
+                           static_cast<const char *>(z), static_cast<char *>(y), (int)T, pieces, frame_bytes);
+    else
+        hipLaunchKernelGGL((mproduct_uniform_kernel<W, true>), dim3(blocks), dim3(kThreads), 0, s,
+                           static_cast<const char *>(z), static_cast<char *>(y), (int)T, pieces, frame_bytes);
+    DGNN_RETURN_IF_LAUNCH_FAILED();
+    return DGNN_OK;
+}
+
+template <int W>
+int dispatch_uniform(int w, const void *z, void *y, int64_t T, int64_t n, int32_t f, dgnn_dtype dt, hipStream_t s) {
+    if (w == W) return launch_uniform<W>(z, y, T, n, f, dt, s);
+    if constexpr (W > 1) return dispatch_uniform<W - 1>(w, z, y, T, n, f, dt, s);
+    return DGNN_ERR_SHAPE;
+}
+
 template <int RING>
 int launch(const void *z, void *y, int64_t T, int64_t n, int32_t f, int32_t w, const float *m_band, dgnn_dtype dt,
            hipStream_t s) {
@@ -127,6 +204,7 @@ extern "C" int dgnn_mproduct(const void *z, void *y, int64_t T, int64_t n, int32
     if (eff > 32) return DGNN_ERR_SHAPE;
     const int32_t wk = m_band ? w : (int32_t)eff;
     hipStream_t s = (hipStream_t)stream;
+    if (!m_band) return dispatch_uniform<32>((int)eff, z, y, T, n, f, dt, s);
     if (eff <= 4) return launch<4>(z, y, T, n, f, wk, m_band, dt, s);
     if (eff <= 8) return launch<8>(z, y, T, n, f, wk, m_band, dt, s);
     if (eff <= 16) return launch<16>(z, y, T, n, f, wk, m_band, dt, s);
