@@ -38,6 +38,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="stop the oracle sample after this much work")
     ap.add_argument("--pinned", action="store_true", help="also time the pass with difference lists in pinned host memory")
+    ap.add_argument("--natural-labels", action="store_true",
+                    help="R-MAT workloads: keep the generator's vertex labels (locality) instead of scrambling them")
     return ap.parse_args()
 
 
@@ -114,6 +116,9 @@ def main():
     wl = WORKLOADS[args.workload]
     if args.n:
         wl = wl.scaled(args.n)
+    if args.natural_labels:
+        from dataclasses import replace
+        wl = replace(wl, scramble=False, name=wl.name + "-natural")
     T = args.T or wl.T
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -169,10 +174,14 @@ def main():
     kernels = {"spmm": "dgnn_spmm (spmm_stream_kernel + spmm_carry_kernel)",
                "delta_rebuild": "dgnn_delta_rebuild (rowptr_kernel + merge_kernel)",
                "feature_transform": "dgnn_feature_transform (xw kernel)", "mproduct": "dgnn_mproduct (mproduct_kernel)"}
+    traffic = committed_traffic(args.workload, dominant)
     roofline = {"bound": "hbm", "kernel": kernels[dominant], "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": committed_traffic(args.workload, dominant),
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "avg_ms": stages[dominant]["avg_ms"],
                 "algorithmic_bytes_per_call": stages[dominant]["algorithmic_bytes_per_call"]}
+    if traffic:   # counter bytes of the committed profile over the duration measured now
+        roofline["traffic_GBps"] = round(traffic / (stages[dominant]["avg_ms"] * 1e-3) / 1e9, 1)
+        roofline["traffic_frac"] = round(roofline["traffic_GBps"] / HBM_PEAK_GBS, 4)
     all_bytes = sum(v["algorithmic_bytes_per_call"] * v["calls_per_step"] for v in stages.values())
 
     out = {

@@ -20,6 +20,7 @@ using namespace dgnn;
 constexpr int kRowThreads = 256;
 constexpr int kRowsPerThread = 4;
 constexpr int kRowTile = kRowThreads * kRowsPerThread;
+constexpr int kHeavyList = 16 * kRowTile;    // list entries per row tile beyond which counting walks no more
 
 constexpr int kPerLane = 8;                  // old entries per lane and sub-tile of the merge
 constexpr int kSub = kWave * kPerLane;       // old entries per sub-tile, at most
@@ -52,6 +53,23 @@ __device__ __forceinline__ void count_runs(const int32_t *__restrict__ rows, int
     }
 }
 
+// The same counts from lower bounds: thread t finds where each of its rows begins inside [lo, hi),
+// each search starting where the previous one ended.
+__device__ __forceinline__ void count_by_search(const int32_t *__restrict__ rows, int lo, int hi, int r0, int nr,
+                                                int *cnt, int tid) {
+    int from = lo;
+    int begin = 0;
+#pragma unroll 1
+    for (int k = 0; k <= kRowsPerThread; ++k) {
+        const int t = tid * kRowsPerThread + k;
+        if (t > nr) break;
+        const int pos = lower_bound(rows, from, hi, r0 + t);     // first entry whose row is >= r0 + t
+        if (k > 0) cnt[t - 1] = pos - begin;
+        begin = pos;
+        from = pos;
+    }
+}
+
 __global__ __launch_bounds__(kRowThreads) void rowptr_kernel(
     int n, const int32_t *__restrict__ rowptr_prev,
     const int32_t *__restrict__ add_row, int n_add, const int32_t *__restrict__ del_row, int n_del,
@@ -78,8 +96,12 @@ __global__ __launch_bounds__(kRowThreads) void rowptr_kernel(
     for (int i = tid; i < kRowTile; i += kRowThreads) { s_add[i] = 0; s_del[i] = 0; }
     __syncthreads();
     const int a0 = s_bound[0], a1 = s_bound[1], d0 = s_bound[2], d1 = s_bound[3];
-    count_runs(add_row, a0, a1, r0, nr, s_add, tid);
-    count_runs(del_row, d0, d1, r0, nr, s_del, tid);
+    // A tile of hub rows can own a very long stretch of a list; walking it would leave the whole chip
+    // waiting for this workgroup, so there the counts come from one lower bound per row instead.
+    if (a1 - a0 <= kHeavyList) count_runs(add_row, a0, a1, r0, nr, s_add, tid);
+    else count_by_search(add_row, a0, a1, r0, nr, s_add, tid);
+    if (d1 - d0 <= kHeavyList) count_runs(del_row, d0, d1, r0, nr, s_del, tid);
+    else count_by_search(del_row, d0, d1, r0, nr, s_del, tid);
     __syncthreads();
 
     int ca[kRowsPerThread], cd[kRowsPerThread];

@@ -38,6 +38,7 @@ constexpr int kPer = 32;             // entries a lane group walks per sub-tile 
 constexpr int kMaxRange = 8192;      // entries streamed by one wavefront, at most
 constexpr int kTargetWaves = 16384;  // ranges shrink on small inputs so that about this many wavefronts exist
 constexpr int kXcds = 8;             // accelerator dies of an MI355X, each with its own L2
+constexpr int kXcdChunk = 16;        // consecutive ranges that go to the same XCD
 
 enum : int32_t { kLeft = 1, kLeftClosed = 2, kRight = 4 };
 struct RangeRec { int32_t flags, row_last, pad0, pad1; };
@@ -110,7 +111,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) v
     constexpr int SUB = G * kPer;           // entries per sub-tile
     constexpr int CPL = kPer / LPR;         // column indices held by one lane
     constexpr int kRowBytes = LPR * 16;
-    constexpr int kRowCap = SUB / 8 > kWave ? SUB / 8 : kWave;   // consecutive rows staged per sub-tile
+    constexpr int kRowCap = SUB + kWave;    // most rows a sub-tile can need: one per entry, plus the bounding one
     constexpr int ROUNDS = kRowCap / kWave;
 
     __shared__ int s_rp[kRowCap];           // row pointers of the staged rows
@@ -120,11 +121,12 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) v
 
     const int lane = threadIdx.x;
     const int sub = lane % LPR, g = lane / LPR, gbase = lane - sub;
-    // Workgroups are dealt to the eight XCDs in turn, and each XCD has an L2 of its own: give XCD x the
-    // x-th contiguous eighth of the ranges, so that rows which lie close together (and in a graph with
-    // locality gather the same rows of H) meet in one L2.
-    const int per_xcd = (gridDim.x + kXcds - 1) / kXcds;
-    const int range = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+    // Workgroups are dealt to the eight XCDs in turn, and each XCD has an L2 of its own.  Ranges are handed
+    // out in chunks of kXcdChunk consecutive ones per XCD, so that rows which lie close together (and in a
+    // graph with locality gather the same rows of H) meet in one L2, while every XCD still gets a share of
+    // every part of the matrix (parts differ in cost per entry when row lengths are clustered).
+    const int slot = blockIdx.x / kXcds, xcd = blockIdx.x % kXcds;
+    const int range = ((slot / kXcdChunk) * kXcds + xcd) * kXcdChunk + slot % kXcdChunk;
     if (range >= n_ranges) return;
     const int e_begin = (int)((int64_t)range * range_len);
     const int e_end = (int)min((int64_t)e_begin + range_len, (int64_t)nnz);
@@ -159,56 +161,69 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) v
             }
         }
     };
-    int m_v[ROUNDS];
-    float m_du[ROUNDS];
+    // row pointers (and dinv) of the first 64 rows of the coming sub-tile; further rows are read on demand
+    int m_v = 0;
+    float m_du = 1.0f;
     auto fetch_rows = [&](int k0) {
-#pragma unroll
-        for (int round = 0; round < ROUNDS; ++round) {
-            const int k = k0 + lane + round * kWave;
-            m_v[round] = k <= n ? rowptr[k] : 0x7fffffff;
-            m_du[round] = (dinv && k < n) ? dinv[k] : 1.0f;
-        }
+        const int k = k0 + lane;
+        m_v = k <= n ? rowptr[k] : 0x7fffffff;
+        m_du = (dinv && k < n) ? dinv[k] : 1.0f;
     };
     fetch_cols(e_begin);
     fetch_rows(k_cur);
-    int k_win = k_cur;
+    int k_win = k_cur, staged_last = kWave;   // the last staged window, for the rows beyond it
     int e = e_begin;
     while (e < e_end) {
-        // ---- stage rows k_cur .. k_cur + kRowCap - 1
-        int le_e = 0;
-        int v_[ROUNDS];
-#pragma unroll
-        for (int round = 0; round < ROUNDS; ++round) {
-            const int t = lane + round * kWave;
-            v_[round] = m_v[round];
-            s_rp[t] = m_v[round];
-            s_du[t] = m_du[round];
-            le_e += __popcll(__ballot(v_[round] <= e));
+        // ---- stage rows k_cur, k_cur + 1, ... in LDS until one begins at or beyond the end of the sub-tile
+        const int e_lim = min(e + SUB, e_end);
+        int staged = 0, le_e = 0, le_stop = 0, lt_stop = 0;
+        bool complete = false;
+        {
+            int v = m_v;
+            float du = m_du;
+#pragma unroll 1
+            for (int round = 0; round < ROUNDS && !complete; ++round) {
+                const int t = lane + round * kWave;
+                if (round > 0) {
+                    const int k = k_cur + t;
+                    v = k <= n ? rowptr[k] : 0x7fffffff;
+                    du = (dinv && k < n) ? dinv[k] : 1.0f;
+                }
+                s_rp[t] = v;
+                s_du[t] = du;
+                le_e += __popcll(__ballot(v <= e));
+                le_stop += __popcll(__ballot(v <= e_lim));
+                lt_stop += __popcll(__ballot(v < e_lim));
+                staged += kWave;
+                complete = __ballot(v >= e_lim) != 0;
+            }
         }
         k_win = k_cur;
+        staged_last = staged;
         const int t0 = max(le_e - 1, 0);                 // the staged row that holds entry e
         __syncthreads();
         // rows without entries give zero output (none exist when every row holds its diagonal)
-#pragma unroll
-        for (int round = 0; round < ROUNDS; ++round) {
-            const int t = lane + round * kWave;
-            if (t + 1 < kRowCap && k_cur + t + 1 <= n && s_rp[t] == s_rp[t + 1]) zero_row<BF16, LPR>(z, k_cur + t);
-        }
+#pragma unroll 1
+        for (int t = lane; t + 1 < staged; t += kWave)
+            if (k_cur + t + 1 <= n && s_rp[t] == s_rp[t + 1]) zero_row<BF16, LPR>(z, k_cur + t);
         if (t0 > 0) {                                    // rows without entries were stepped over: restage from the row of e
             k_cur += t0;
             fetch_rows(k_cur);
             __syncthreads();
             continue;
         }
-        const int v_last = __shfl(v_[ROUNDS - 1], kWave - 1, kWave);   // start of the last staged row (> e)
-        const int e_stop = min(min(e + SUB, e_end), v_last);
-        const int cnt = e_stop - e;
-        int le_stop = 0, lt_stop = 0;
-#pragma unroll
-        for (int round = 0; round < ROUNDS; ++round) {
-            le_stop += __popcll(__ballot(v_[round] <= e_stop));
-            lt_stop += __popcll(__ballot(v_[round] < e_stop));
+        int e_stop = e_lim;
+        if (!complete) {                                 // more rows begin here than fit (rows without entries): end early
+            e_stop = min(e_lim, s_rp[staged - 1]);
+            le_stop = lt_stop = 0;
+#pragma unroll 1
+            for (int t = lane; t - lane < staged; t += kWave) {
+                const int v = t < staged ? s_rp[t] : 0x7fffffff;
+                le_stop += __popcll(__ballot(v <= e_stop));
+                lt_stop += __popcll(__ballot(v < e_stop));
+            }
         }
+        const int cnt = e_stop - e;
         const int t_last = lt_stop - 1;                  // last staged row with entries in this sub-tile
         const int k_next = k_cur + le_stop - 1;          // a row with rowptr <= e_stop
 
@@ -226,15 +241,15 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) v
         }
         __syncthreads();
         // ---- row starts inside the sub-tile -> mask bits
-#pragma unroll
-        for (int round = 0; round < ROUNDS; ++round) {
-            const int t = lane + round * kWave;
-            if (t > 0 && v_[round] < e_stop) {
-                const int p = v_[round] - e;
+#pragma unroll 1
+        for (int t = lane; t < staged; t += kWave) {
+            const int v = s_rp[t];
+            if (t > 0 && v < e_stop) {
+                const int p = v - e;
                 atomicOr(&s_heads[p >> 5], 1u << (p & 31));
             }
         }
-        if (lane == 0 && v_[0] == e) atomicOr(&s_heads[0], 1u);
+        if (lane == 0 && s_rp[0] == e) atomicOr(&s_heads[0], 1u);
         __syncthreads();
 
         // ---- every lane group walks its 32 entries
@@ -421,7 +436,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) v
         if (lane == 0) recs[range] = RangeRec{range_flags, run_row, 0, 0};
     }
     if (e_end == nnz)                                    // rows without entries beyond the last staged window
-        for (int k = k_win + kRowCap - 1 + lane; k < n; k += kWave)
+        for (int k = k_win + staged_last - 1 + lane; k < n; k += kWave)
             if (rowptr[k] == rowptr[k + 1]) zero_row<BF16, LPR>(z, k);
 }
 
@@ -487,7 +502,7 @@ int launch(int64_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx,
     constexpr int G = 256 / LPR;
     const int range_len = range_length(nnz, (kWave / LPR) * kPer);
     const int ranges = (int)((nnz + range_len - 1) / range_len);
-    const int grid = (ranges + kXcds - 1) / kXcds * kXcds;   // a whole number of rounds over the XCDs
+    const int grid = (ranges + kXcds * kXcdChunk - 1) / (kXcds * kXcdChunk) * (kXcds * kXcdChunk);   // whole chunk rounds
     if (scale_v)
         hipLaunchKernelGGL((spmm_stream_kernel<LPR, BF16, true>), dim3(grid), dim3(kWave), 0, s, (int)n, (int)nnz, range_len, ranges,
                            rowptr, colidx, dinv, static_cast<const char *>(h), static_cast<char *>(z), relu, ws.recs, ws.carry);

@@ -110,6 +110,31 @@ def test_rebuild_heavy_rows_and_many_adds_between_neighbours():
     assert np.array_equal(grp, erp) and np.array_equal(gci, eci)
 
 
+def test_rebuild_many_changes_in_one_row_tile():
+    """More than 16 list entries per row over a whole tile of 1024 rows (the row-pointer kernel then counts
+    by searching instead of walking the list), next to tiles that get nothing."""
+    n = 5000
+    rng = np.random.default_rng(12)
+    rows_r, rows_c = [np.arange(n)], [np.arange(n)]
+    for u in range(300, 1500):
+        cols = np.setdiff1d(rng.choice(n, 40, replace=False), [u])
+        rows_r.append(np.full(cols.size, u)); rows_c.append(cols)
+    rp, ci = oracle.csr_from_edges(n, np.concatenate(rows_r).astype(np.int32), np.concatenate(rows_c).astype(np.int32))
+    adds, dels = [], []
+    for u in range(300, 1500):
+        old = ci[rp[u]:rp[u + 1]]
+        dels += [(u, int(c)) for c in old[old != u][::2]]
+        fresh = np.setdiff1d(rng.choice(n, 30, replace=False), old)
+        adds += [(u, int(c)) for c in fresh]
+    a, d = coo(adds), coo(dels)
+    assert a[0].size > 16 * 1024 and d[0].size > 16 * 1024
+    erp, eci = oracle.delta_apply(n, rp, ci, *a, *d)
+    grp, gci, dinv, status, _ = gpu_rebuild(n, rp, ci, *a, *d)
+    assert status == 0
+    assert np.array_equal(grp, erp) and np.array_equal(gci, eci)
+    assert np.allclose(dinv, 1.0 / np.sqrt(np.diff(erp)), rtol=3e-7, atol=0)
+
+
 def test_rebuild_validation_codes():
     n = 6
     base = [(u, u) for u in range(n)] + [(0, 1), (1, 0), (2, 3), (3, 2)]
