@@ -16,6 +16,8 @@
 // the rows of X as the B operand: lane (i, h) then holds row i of the result and, in every four
 // consecutive accumulator registers, four consecutive columns of it, which turns sixty-four
 // 2-byte stores per lane into sixteen 8-byte ones and makes row_scale one value per lane.
+#include <algorithm>
+
 #include "common.hpp"
 
 namespace {
@@ -102,11 +104,103 @@ __global__ __launch_bounds__(kThreads) void xw_f32_kernel(const float *__restric
     }
 }
 
+// The same product with both tiles staged through LDS, for widths whose tiles fit: the 32 rows of X arrive as
+// one contiguous block (every load instruction of the wavefront covers whole 128-byte lines), are laid down
+// in LDS with padded rows and picked up again in operand order; the result tile takes the same way back, so
+// the stores are whole lines too.  The product is computed transposed, (X W)^T = W^T X^T, which leaves lane
+// (i, h) with row i of the result and four consecutive columns in every four accumulator registers.
+template <int FIN, int FOUT>
+__global__ __launch_bounds__(kThreads) void xw_f32_staged_kernel(const float *__restrict__ x, const float *__restrict__ w,
+                                                                 const float *__restrict__ row_scale, float *__restrict__ h,
+                                                                 int64_t n, int64_t n_tiles) {
+    constexpr int NT = FOUT / 32;
+    constexpr int KH = FIN / 2;
+    constexpr int FMAX = FIN > FOUT ? FIN : FOUT;
+    constexpr int LDT = FMAX + 4;                    // padded tile row (floats): 16 bytes of padding
+    constexpr int IN_PIECES = 32 * FIN / 4 / kWave;  // 16-byte pieces per lane of an input tile
+    constexpr int OUT_PIECES = 32 * FOUT / 4 / kWave;
+    static_assert(FOUT % 32 == 0 && FIN % 8 == 0, "staged kernel needs whole 32-column tiles");
+    __shared__ float s_w[FIN * FOUT];
+    __shared__ __attribute__((aligned(16))) float s_tile[kWavesPerBlock][32 * LDT];
+
+    const int tid = threadIdx.x;
+    for (int idx = tid; idx < FIN * FOUT; idx += kThreads) s_w[idx] = w[idx];
+    const int lane = tid & (kWave - 1), wave = tid / kWave;
+    const int i = lane & 31, hh = lane >> 5;
+    float *tile_lds = s_tile[wave];
+    const int64_t stride = (int64_t)gridDim.x * kWavesPerBlock;
+    const int64_t first = (int64_t)blockIdx.x * kWavesPerBlock + wave;
+    const int64_t iters = (n_tiles - (int64_t)blockIdx.x * kWavesPerBlock + stride - 1) / stride;   // same for the whole block
+
+    floatx4 in_next[IN_PIECES];
+    auto fetch = [&](int64_t t) {
+#pragma unroll
+        for (int q = 0; q < IN_PIECES; ++q) {
+            const int64_t piece = t * (32 * FIN / 4) + q * kWave + lane;      // 16-byte pieces from the start of X
+            in_next[q] = (t < n_tiles && piece * 4 < n * FIN) ? reinterpret_cast<const floatx4 *>(x)[piece]
+                                                               : floatx4{0.f, 0.f, 0.f, 0.f};
+        }
+    };
+    fetch(first);
+    __syncthreads();
+    for (int64_t it = 0; it < iters; ++it) {
+        const int64_t tile = first + it * stride;
+        // ---- input tile: registers -> LDS (padded rows)
+#pragma unroll
+        for (int q = 0; q < IN_PIECES; ++q) {
+            const int e = (q * kWave + lane) * 4;                             // float index inside the tile
+            *reinterpret_cast<floatx4 *>(&tile_lds[(e / FIN) * LDT + e % FIN]) = in_next[q];
+        }
+        fetch(tile + stride);
+        __syncthreads();
+        floatx4 a[KH / 4];
+#pragma unroll
+        for (int q = 0; q < KH / 4; ++q) a[q] = *reinterpret_cast<const floatx4 *>(&tile_lds[i * LDT + hh * KH + q * 4]);
+        const int64_t row = tile * 32 + i;
+        const float scale = (row_scale && tile < n_tiles && row < n) ? row_scale[row] : 1.0f;
+        floatx16 acc[NT];
+#pragma unroll
+        for (int jt = 0; jt < NT; ++jt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[jt][v] = 0.0f;
+#pragma unroll
+        for (int s = 0; s < KH; ++s) {
+            const float xv = a[s / 4][s % 4];
+#pragma unroll
+            for (int jt = 0; jt < NT; ++jt) {
+                const float wv = s_w[(hh * KH + s) * FOUT + jt * 32 + i];
+                acc[jt] = __builtin_amdgcn_mfma_f32_32x32x2f32(wv, xv, acc[jt], 0, 0, 0);   // (X W)^T tile
+            }
+        }
+        __syncthreads();                                                      // every lane has its operands
+        // ---- result tile: accumulators -> LDS -> whole lines
+#pragma unroll
+        for (int jt = 0; jt < NT; ++jt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+                *reinterpret_cast<floatx4 *>(&tile_lds[i * LDT + jt * 32 + 8 * g + 4 * hh]) =
+                    floatx4{acc[jt][4 * g] * scale, acc[jt][4 * g + 1] * scale, acc[jt][4 * g + 2] * scale,
+                            acc[jt][4 * g + 3] * scale};
+        __syncthreads();
+        if (tile < n_tiles) {
+#pragma unroll
+            for (int q = 0; q < OUT_PIECES; ++q) {
+                const int e = (q * kWave + lane) * 4;
+                const int64_t piece = tile * (32 * FOUT / 4) + q * kWave + lane;
+                if (piece * 4 < n * FOUT)
+                    reinterpret_cast<floatx4 *>(h)[piece] = *reinterpret_cast<const floatx4 *>(&tile_lds[(e / FOUT) * LDT + e % FOUT]);
+            }
+        }
+        __syncthreads();                                                      // the tile buffer is reused
+    }
+}
+
 template <int FIN, int FOUT>
 __global__ __launch_bounds__(kThreads) void xw_bf16_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ w,
                                                            const float *__restrict__ row_scale, uint16_t *__restrict__ h,
                                                            int64_t n, int64_t n_tiles) {
     constexpr int NT = (FOUT + 31) / 32;
+    constexpr int JG = NT > 2 ? 2 : NT;    // column tiles accumulated at a time (bounds the live accumulators)
     constexpr int KH = FIN / 2;            // bf16 values owned by one lane
     constexpr int KS = KH / 8;             // MFMA steps of depth 16 (8 per lane half)
     constexpr int LDW = FIN + 8;           // padded row of W^T in LDS, keeps 16-byte reads conflict-free
@@ -146,47 +240,74 @@ __global__ __launch_bounds__(kThreads) void xw_bf16_kernel(const uint16_t *__res
 #pragma unroll
         for (int s = 0; s < KS; ++s) a[s] = a_next[s];
         const float scale = sc_next;
-        fetch(tile + stride);
-        floatx16 acc[NT];
-#pragma unroll
-        for (int jt = 0; jt < NT; ++jt)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[jt][v] = 0.0f;
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-#pragma unroll
-            for (int jt = 0; jt < NT; ++jt) {
-                const bf16x8 wv = *reinterpret_cast<const bf16x8 *>(&s_wt[(jt * 32 + i) * LDW + hh * KH + s * 8]);
-                acc[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, a[s], acc[jt], 0, 0, 0);   // (X W)^T tile
-            }
-        }
+        fetch(tile + stride);              // the next tile's rows travel while this one is multiplied
         const int64_t row = tile * 32 + i;
-        if (row < n) {
 #pragma unroll
-            for (int jt = 0; jt < NT; ++jt)
+        for (int j0 = 0; j0 < NT; j0 += JG) {
+            floatx16 acc[JG];
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int col = jt * 32 + 8 * g + 4 * hh;
-                    if (col < FOUT) {
-                        const uint32_t lo = f32_to_bf16(acc[jt][4 * g] * scale) | (f32_to_bf16(acc[jt][4 * g + 1] * scale) << 16);
-                        const uint32_t hi = f32_to_bf16(acc[jt][4 * g + 2] * scale) | (f32_to_bf16(acc[jt][4 * g + 3] * scale) << 16);
-                        *reinterpret_cast<uint2 *>(h + row * FOUT + col) = make_uint2(lo, hi);
-                    }
+            for (int jj = 0; jj < JG; ++jj)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[jj][v] = 0.0f;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+#pragma unroll
+                for (int jj = 0; jj < JG; ++jj) {
+                    const bf16x8 wv = *reinterpret_cast<const bf16x8 *>(&s_wt[((j0 + jj) * 32 + i) * LDW + hh * KH + s * 8]);
+                    acc[jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, a[s], acc[jj], 0, 0, 0);   // (X W)^T tile
                 }
+            }
+            if (row < n) {
+#pragma unroll
+                for (int jj = 0; jj < JG; ++jj)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int col = (j0 + jj) * 32 + 8 * g + 4 * hh;
+                        if (col < FOUT) {
+                            const uint32_t lo = f32_to_bf16(acc[jj][4 * g] * scale) | (f32_to_bf16(acc[jj][4 * g + 1] * scale) << 16);
+                            const uint32_t hi = f32_to_bf16(acc[jj][4 * g + 2] * scale) | (f32_to_bf16(acc[jj][4 * g + 3] * scale) << 16);
+                            *reinterpret_cast<uint2 *>(h + row * FOUT + col) = make_uint2(lo, hi);
+                        }
+                    }
+            }
+            __builtin_amdgcn_sched_barrier(0);   // keep the column groups apart: their accumulators share registers
         }
     }
+}
+
+// Grid of a persistent launch: as many workgroups as the device holds at once, so that W is staged
+// once per resident workgroup and every wavefront walks many row tiles.
+template <typename K>
+int64_t resident_blocks(K kernel) {
+    static int64_t cached = 0;             // one value per kernel instantiation; the device type is fixed
+    if (cached == 0) {
+        int dev = 0, cus = 0, per_cu = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kThreads, 0) != hipSuccess || cus <= 0 ||
+            per_cu <= 0) {
+            (void)hipGetLastError();
+            return 1024;
+        }
+        cached = (int64_t)cus * per_cu;
+    }
+    return cached;
 }
 
 template <int FIN, int FOUT>
 int launch(const void *x, const void *w, const float *row_scale, void *h, int64_t n, dgnn_dtype dt, hipStream_t s) {
     const int64_t n_tiles = (n + 31) / 32;
-    int64_t blocks = (n_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
-    if (blocks > 4096) blocks = 4096;
+    const int64_t needed = (n_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
+    auto grid = [&](auto kernel) { return dim3((unsigned)std::min(needed, resident_blocks(kernel))); };
     if (dt == DGNN_F32) {
-        hipLaunchKernelGGL((xw_f32_kernel<FIN, FOUT>), dim3((unsigned)blocks), dim3(kThreads), 0, s,
-                           static_cast<const float *>(x), static_cast<const float *>(w), row_scale, static_cast<float *>(h), n, n_tiles);
+        if constexpr (FIN <= 64 && FOUT <= 64 && FOUT % 32 == 0)   // both tiles and W fit in LDS
+            hipLaunchKernelGGL((xw_f32_staged_kernel<FIN, FOUT>), grid(xw_f32_staged_kernel<FIN, FOUT>), dim3(kThreads), 0, s,
+                               static_cast<const float *>(x), static_cast<const float *>(w), row_scale, static_cast<float *>(h), n, n_tiles);
+        else
+            hipLaunchKernelGGL((xw_f32_kernel<FIN, FOUT>), grid(xw_f32_kernel<FIN, FOUT>), dim3(kThreads), 0, s,
+                               static_cast<const float *>(x), static_cast<const float *>(w), row_scale, static_cast<float *>(h), n, n_tiles);
     } else {
-        hipLaunchKernelGGL((xw_bf16_kernel<FIN, FOUT>), dim3((unsigned)blocks), dim3(kThreads), 0, s,
+        hipLaunchKernelGGL((xw_bf16_kernel<FIN, FOUT>), grid(xw_bf16_kernel<FIN, FOUT>), dim3(kThreads), 0, s,
                            static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(w), row_scale,
                            static_cast<uint16_t *>(h), n, n_tiles);
     }
