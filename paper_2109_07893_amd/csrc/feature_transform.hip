@@ -16,6 +16,12 @@
 // the rows of X as the B operand: lane (i, h) then holds row i of the result and, in every four
 // consecutive accumulator registers, four consecutive columns of it, which turns sixty-four
 // 2-byte stores per lane into sixteen 8-byte ones and makes row_scale one value per lane.
+//
+// Where W and one 32-row tile per wavefront fit in LDS together (fp32 up to width 64, bf16 from width 32 on)
+// the "staged" kernels are used instead: a tile is read from global memory as consecutive 16-byte pieces,
+// laid down in LDS with padded rows, picked up in operand layout, and the result goes back the same way,
+// so that every global access of a wavefront is a run of whole lines.  The direct kernels serve the rest.
+// Every kernel is launched as a persistent grid (as many workgroups as fit on the device at once).
 #include <algorithm>
 
 #include "common.hpp"
@@ -27,6 +33,7 @@ using namespace dgnn;
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
 constexpr int kWavesPerBlock = kThreads / kWave;
@@ -275,6 +282,101 @@ __global__ __launch_bounds__(kThreads) void xw_bf16_kernel(const uint16_t *__res
     }
 }
 
+// bf16 with both widths at least 32: as the staged fp32 kernel, tiles pass through LDS so that every global
+// access is a run of whole lines, and the transposed product leaves four consecutive columns per lane.
+template <int FIN, int FOUT>
+__global__ __launch_bounds__(kThreads) void xw_bf16_staged_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ w,
+                                                                  const float *__restrict__ row_scale, uint16_t *__restrict__ h,
+                                                                  int64_t n, int64_t n_tiles) {
+    constexpr int NT = FOUT / 32;
+    constexpr int JG = NT > 2 ? 2 : NT;              // column tiles accumulated at a time
+    constexpr int KH = FIN / 2;
+    constexpr int KS = KH / 8;
+    constexpr int LDW = FIN + 8;                     // padded row of W^T (bf16 values)
+    constexpr int FMAX = FIN > FOUT ? FIN : FOUT;
+    constexpr int LDT = FMAX + 8;                    // padded tile row
+    constexpr int IN_PIECES = 32 * FIN / 8 / kWave;  // 16-byte pieces per lane of an input tile
+    constexpr int OUT_PIECES = 32 * FOUT / 8 / kWave;
+    static_assert(FOUT % 32 == 0 && FIN % 32 == 0, "staged kernel needs whole 32-column tiles");
+    __shared__ __attribute__((aligned(16))) uint16_t s_wt[FOUT * LDW];
+    __shared__ __attribute__((aligned(16))) uint16_t s_tile[kWavesPerBlock][32 * LDT];
+
+    const int tid = threadIdx.x;
+    for (int idx = tid; idx < FIN * FOUT; idx += kThreads) {
+        const int k = idx / FOUT, j = idx % FOUT;
+        s_wt[j * LDW + k] = w[idx];
+    }
+    const int lane = tid & (kWave - 1), wave = tid / kWave;
+    const int i = lane & 31, hh = lane >> 5;
+    uint16_t *tile_lds = s_tile[wave];
+    const int64_t stride = (int64_t)gridDim.x * kWavesPerBlock;
+    const int64_t first = (int64_t)blockIdx.x * kWavesPerBlock + wave;
+    const int64_t iters = (n_tiles - (int64_t)blockIdx.x * kWavesPerBlock + stride - 1) / stride;   // same for the whole block
+
+    uintx4 in_next[IN_PIECES];
+    auto fetch = [&](int64_t t) {
+#pragma unroll
+        for (int q = 0; q < IN_PIECES; ++q) {
+            const int64_t piece = t * (32 * FIN / 8) + q * kWave + lane;      // 16-byte pieces from the start of X
+            in_next[q] = (t < n_tiles && piece * 8 < n * FIN) ? reinterpret_cast<const uintx4 *>(x)[piece]
+                                                               : uintx4{0u, 0u, 0u, 0u};
+        }
+    };
+    fetch(first);
+    __syncthreads();
+    for (int64_t it = 0; it < iters; ++it) {
+        const int64_t tile = first + it * stride;
+#pragma unroll
+        for (int q = 0; q < IN_PIECES; ++q) {
+            const int e = (q * kWave + lane) * 8;                             // bf16 index inside the tile
+            *reinterpret_cast<uintx4 *>(&tile_lds[(e / FIN) * LDT + e % FIN]) = in_next[q];
+        }
+        fetch(tile + stride);
+        __syncthreads();
+        bf16x8 a[KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) a[s] = *reinterpret_cast<const bf16x8 *>(&tile_lds[i * LDT + hh * KH + s * 8]);
+        const int64_t row = tile * 32 + i;
+        const float scale = (row_scale && tile < n_tiles && row < n) ? row_scale[row] : 1.0f;
+        __syncthreads();                                                      // every lane has its operands
+#pragma unroll
+        for (int j0 = 0; j0 < NT; j0 += JG) {
+            floatx16 acc[JG];
+#pragma unroll
+            for (int jj = 0; jj < JG; ++jj)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[jj][v] = 0.0f;
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+#pragma unroll
+                for (int jj = 0; jj < JG; ++jj) {
+                    const bf16x8 wv = *reinterpret_cast<const bf16x8 *>(&s_wt[((j0 + jj) * 32 + i) * LDW + hh * KH + s * 8]);
+                    acc[jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, a[s], acc[jj], 0, 0, 0);   // (X W)^T tile
+                }
+#pragma unroll
+            for (int jj = 0; jj < JG; ++jj)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const uint32_t lo = f32_to_bf16(acc[jj][4 * g] * scale) | (f32_to_bf16(acc[jj][4 * g + 1] * scale) << 16);
+                    const uint32_t hi = f32_to_bf16(acc[jj][4 * g + 2] * scale) | (f32_to_bf16(acc[jj][4 * g + 3] * scale) << 16);
+                    *reinterpret_cast<uint2 *>(&tile_lds[i * LDT + (j0 + jj) * 32 + 8 * g + 4 * hh]) = make_uint2(lo, hi);
+                }
+            __builtin_amdgcn_sched_barrier(0);   // keep the column groups apart: their accumulators share registers
+        }
+        __syncthreads();
+        if (tile < n_tiles) {
+#pragma unroll
+            for (int q = 0; q < OUT_PIECES; ++q) {
+                const int e = (q * kWave + lane) * 8;
+                const int64_t piece = tile * (32 * FOUT / 8) + q * kWave + lane;
+                if (piece * 8 < n * FOUT)
+                    reinterpret_cast<uintx4 *>(h)[piece] = *reinterpret_cast<const uintx4 *>(&tile_lds[(e / FOUT) * LDT + e % FOUT]);
+            }
+        }
+        __syncthreads();                                                      // the tile buffer is reused
+    }
+}
+
 // Grid of a persistent launch: as many workgroups as the device holds at once, so that W is staged
 // once per resident workgroup and every wavefront walks many row tiles.
 template <typename K>
@@ -307,9 +409,14 @@ int launch(const void *x, const void *w, const float *row_scale, void *h, int64_
             hipLaunchKernelGGL((xw_f32_kernel<FIN, FOUT>), grid(xw_f32_kernel<FIN, FOUT>), dim3(kThreads), 0, s,
                                static_cast<const float *>(x), static_cast<const float *>(w), row_scale, static_cast<float *>(h), n, n_tiles);
     } else {
-        hipLaunchKernelGGL((xw_bf16_kernel<FIN, FOUT>), grid(xw_bf16_kernel<FIN, FOUT>), dim3(kThreads), 0, s,
-                           static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(w), row_scale,
-                           static_cast<uint16_t *>(h), n, n_tiles);
+        if constexpr (FIN % 32 == 0 && FOUT % 32 == 0)
+            hipLaunchKernelGGL((xw_bf16_staged_kernel<FIN, FOUT>), grid(xw_bf16_staged_kernel<FIN, FOUT>), dim3(kThreads), 0, s,
+                               static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(w), row_scale,
+                               static_cast<uint16_t *>(h), n, n_tiles);
+        else
+            hipLaunchKernelGGL((xw_bf16_kernel<FIN, FOUT>), grid(xw_bf16_kernel<FIN, FOUT>), dim3(kThreads), 0, s,
+                               static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(w), row_scale,
+                               static_cast<uint16_t *>(h), n, n_tiles);
     }
     DGNN_RETURN_IF_LAUNCH_FAILED();
     return DGNN_OK;
