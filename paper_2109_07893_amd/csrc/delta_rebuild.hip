@@ -7,6 +7,7 @@
 // and "#entries with row < r" is a lower bound in a sorted list.  Every tile is independent:
 //   1. rowptr_kernel  (tiles of rows)         new row pointers, dinv = (row length)^(-1/2),
 //                                             and add_ptr[r] = #added with row < r (workspace);
+//      extent_kernel  (difference entries)    the extent of each entry's row in A_prev (workspace);
 //   2. merge_kernel   (ranges of old entries) streams A_prev's column indices once: deleted entries
 //      are struck out, added entries slotted in, a prefix sum per sub-tile gives the positions.
 //      Ranges hold equal numbers of old entries, so hub rows of power-law graphs are spread over
@@ -137,6 +138,23 @@ __global__ __launch_bounds__(kRowThreads) void rowptr_kernel(
     }
 }
 
+// Where the row of every difference entry lies in A_prev: ext[j] = (rowptr_prev[row_j], rowptr_prev[row_j + 1]),
+// added entries first, then deleted ones.  The merge needs this pair for every entry it places; looked up
+// there, it would be a load that depends on a load in the middle of a stream.
+__global__ __launch_bounds__(256) void extent_kernel(int n, const int32_t *__restrict__ rowptr_prev,
+                                                     const int32_t *__restrict__ add_row, int n_add,
+                                                     const int32_t *__restrict__ del_row, int n_del,
+                                                     int2 *__restrict__ add_ext, int2 *__restrict__ del_ext) {
+    const int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (g >= (int64_t)n_add + n_del) return;
+    const bool is_add = g < n_add;
+    const int j = is_add ? (int)g : (int)(g - n_add);
+    const int r = is_add ? add_row[j] : del_row[j];
+    int2 x = make_int2(0x7fffffff, 0x7fffffff);          // a row outside [0, n) owns nothing
+    if ((unsigned)r < (unsigned)n) x = make_int2(rowptr_prev[r], rowptr_prev[r + 1]);
+    (is_add ? add_ext : del_ext)[j] = x;
+}
+
 // First position in the ascending LDS array a[lo, hi) whose value is >= key (STRICT = false) or > key.
 template <bool STRICT>
 __device__ __forceinline__ int lds_bound(const int *a, int lo, int hi, int key) {
@@ -154,8 +172,8 @@ __device__ __forceinline__ int lds_bound(const int *a, int lo, int hi, int key) 
 //   - the sub-tile's column indices are staged in LDS; each deleted entry that falls into the
 //     sub-tile finds its old entry there by binary search and marks it dead, each added entry
 //     finds the old entry it goes in front of (its slot) and counts itself there.  Where the row
-//     of a difference entry lies inside the sub-tile follows from two row pointers of A_prev,
-//     fetched together with the entry itself one sub-tile ahead;
+//     of a difference entry lies inside the sub-tile follows from its row's extent in A_prev,
+//     which extent_kernel has written next to the lists, so that no load here depends on another;
 //   - both lists are consumed in order through two cursors, so the lists are never searched
 //     (except once, where a range begins in the middle of a row);
 //   - one prefix sum over (alive, added-before) gives every old entry and every slot its place
@@ -165,8 +183,8 @@ __device__ __forceinline__ int lds_bound(const int *a, int lo, int hi, int key) 
 // indices of the next sub-tile are fetched while this one is placed.
 __global__ __launch_bounds__(kWave) void merge_kernel(
     int n, const int32_t *__restrict__ rowptr_prev, const int32_t *__restrict__ colidx_prev, int nnz_prev, int range_len,
-    const int32_t *__restrict__ add_row, const int32_t *__restrict__ add_col, int n_add,
-    const int32_t *__restrict__ del_row, const int32_t *__restrict__ del_col, int n_del,
+    const int32_t *__restrict__ add_col, const int2 *__restrict__ add_ext, int n_add,
+    const int32_t *__restrict__ del_col, const int2 *__restrict__ del_ext, int n_del,
     const int32_t *__restrict__ rowptr_next, const int32_t *__restrict__ add_ptr,
     int32_t *__restrict__ colidx_next, int cap_next) {
     __shared__ int s_col[kSub];
@@ -203,23 +221,36 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
         d_cur = min(max(d_cur, 0), n_del);
         base = rn + (e_begin - rp) - (d_cur - ds) + (a_cur - as);
     }
-    // the 64 list entries at each cursor, with the extent of their rows in A_prev, are fetched ahead of use
-    int pa_col = 0, pa_lo = 0, pa_hi = 0, pd_col = 0, pd_lo = 0, pd_hi = 0;
-    auto fetch_lists = [&]() {
-        pa_lo = pd_lo = 0x7fffffff;      // "row begins beyond everything": not owned
-        pa_hi = pd_hi = 0x7fffffff;
-        if (a_cur + lane < n_add) {
-            const int r = add_row[a_cur + lane];
-            pa_col = add_col[a_cur + lane];
-            if ((unsigned)r < (unsigned)n) { pa_lo = rowptr_prev[r]; pa_hi = rowptr_prev[r + 1]; }
-        }
-        if (d_cur + lane < n_del) {
-            const int r = del_row[d_cur + lane];
-            pd_col = del_col[d_cur + lane];
-            if ((unsigned)r < (unsigned)n) { pd_lo = rowptr_prev[r]; pd_hi = rowptr_prev[r + 1]; }
+    // The 64 list entries at each cursor (column, and where the entry's row lies in A_prev) are held in
+    // registers ahead of use.  A sub-tile consumes only some of them: the rest slide down to lane 0 and only
+    // the freed lanes load, without anyone waiting for those loads before the next sub-tile needs them.
+    constexpr int kNone = 0x7fffffff;    // "row begins beyond everything": the entry is not owned
+    constexpr int kVmcntZero = 0x0F70;   // s_waitcnt operand: every vector memory load has returned, other counters untouched
+    int pa_col = 0, pa_lo = kNone, pa_hi = kNone, pd_col = 0, pd_lo = kNone, pd_hi = kNone;
+    auto load_entry = [&](const int32_t *__restrict__ cols, const int2 *__restrict__ ext, int len, int j, bool want,
+                          int &c, int &lo, int &hi) {
+        if (want && j < len) {
+            c = cols[j];
+            const int2 x = ext[j];
+            lo = x.x;
+            hi = x.y;
         }
     };
-    fetch_lists();
+    // registers hold the entries from (cur - got) on; afterwards from cur on
+    auto slide = [&](const int32_t *__restrict__ cols, const int2 *__restrict__ ext, int len, int cur, int got, int &c,
+                     int &lo, int &hi) {
+        const int src = lane + got;
+        const int c2 = __shfl(c, src & (kWave - 1), kWave);
+        const int lo2 = __shfl(lo, src & (kWave - 1), kWave);
+        const int hi2 = __shfl(hi, src & (kWave - 1), kWave);
+        const bool fresh = src >= kWave;
+        c = c2;
+        lo = fresh ? kNone : lo2;
+        hi = fresh ? kNone : hi2;
+        load_entry(cols, ext, len, cur + lane, fresh, c, lo, hi);
+    };
+    load_entry(add_col, add_ext, n_add, a_cur + lane, true, pa_col, pa_lo, pa_hi);
+    load_entry(del_col, del_ext, n_del, d_cur + lane, true, pd_col, pd_lo, pd_hi);
 
     for (int e = e_begin; e < e_end; e += kSub) {
         const int e_stop = min(e + kSub, e_end);
@@ -239,59 +270,58 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
         }
         __syncthreads();
 
-        // ---- deleted entries: mark the old entry dead
-        {
-            int c = pd_col, lo_g = pd_lo, hi_g = pd_hi;
-            for (int j0 = d_cur;; j0 += kWave) {
-                const int j = j0 + lane;
-                if (j0 != d_cur) {
-                    lo_g = hi_g = 0x7fffffff;
-                    if (j < n_del) {
-                        const int r = del_row[j];
-                        c = del_col[j];
-                        if ((unsigned)r < (unsigned)n) { lo_g = rowptr_prev[r]; hi_g = rowptr_prev[r + 1]; }
-                    }
-                }
-                bool owned = false;
-                if (j < n_del && lo_g < e_stop && hi_g > e) {        // its row has entries in this sub-tile
-                    const int lo = max(lo_g - e, 0), hi = min(hi_g - e, cnt);
-                    const int p = lds_bound<false>(s_col, lo, hi, c);
-                    owned = p < hi && s_col[p] == c;
-                    if (owned) atomicOr(&s_mark[p], 1);
-                }
-                const int got = __popcll(__ballot(owned));
-                if (got < kWave) { d_cur = j0 + got; break; }
+        // ---- deleted entries: mark the old entry dead.  The first 64 are in registers already; a sub-tile
+        // with more than that is rare and pays for its loads on the spot.
+        auto strike = [&](int j) {
+            bool owned = false;
+            if (j < n_del && pd_lo < e_stop && pd_hi > e) {      // its row has entries in this sub-tile
+                const int lo = max(pd_lo - e, 0), hi = min(pd_hi - e, cnt);
+                const int p = lds_bound<false>(s_col, lo, hi, pd_col);
+                owned = p < hi && s_col[p] == pd_col;
+                if (owned) atomicOr(&s_mark[p], 1);
             }
+            return __popcll(__ballot(owned));
+        };
+        int d_got = strike(d_cur + lane);
+#pragma unroll 1
+        while (d_got == kWave) {
+            d_cur += kWave;
+            pd_lo = pd_hi = kNone;
+            load_entry(del_col, del_ext, n_del, d_cur + lane, true, pd_col, pd_lo, pd_hi);
+            __builtin_amdgcn_s_waitcnt(kVmcntZero);
+            d_got = strike(d_cur + lane);
         }
+        d_cur += d_got;
         // ---- added entries: count at the slot (old entry they precede; a row's end if none)
         const int a_tile = a_cur;
-        int q_first = -2 - lane, c_first = 0;     // slot and column of the first 64, kept for the write below
-        {
-            int c = pa_col, lo_g = pa_lo, hi_g = pa_hi;
-            for (int j0 = a_tile;; j0 += kWave) {
-                const int j = j0 + lane;
-                if (j0 != a_tile) {
-                    lo_g = hi_g = 0x7fffffff;
-                    if (j < n_add) {
-                        const int r = add_row[j];
-                        c = add_col[j];
-                        if ((unsigned)r < (unsigned)n) { lo_g = rowptr_prev[r]; hi_g = rowptr_prev[r + 1]; }
-                    }
-                }
-                bool owned = false;
-                int q = -2 - lane;
-                if (j < n_add && lo_g < e_stop && hi_g > e) {
-                    const int lo = max(lo_g - e, 0), hi = min(hi_g - e, cnt);
-                    q = lds_bound<true>(s_col, lo, hi, c);
-                    owned = q < hi || hi_g <= e_stop;      // beyond the sub-tile's part of an unfinished row: later
-                    if (owned) atomicAdd(&s_mark[q], 2);
-                }
-                if (j0 == a_tile) { q_first = owned ? q : -2 - lane; c_first = c; }
-                const int got = __popcll(__ballot(owned));
-                if (got < kWave) { a_cur = j0 + got; break; }
+        auto slot = [&](int j, int &q) {
+            bool owned = false;
+            q = -2 - lane;
+            if (j < n_add && pa_lo < e_stop && pa_hi > e) {
+                const int lo = max(pa_lo - e, 0), hi = min(pa_hi - e, cnt);
+                q = lds_bound<true>(s_col, lo, hi, pa_col);
+                owned = q < hi || pa_hi <= e_stop;         // beyond the sub-tile's part of an unfinished row: later
+                if (owned) atomicAdd(&s_mark[q], 2);
             }
+            if (!owned) q = -2 - lane;
+            return __popcll(__ballot(owned));
+        };
+        int q_first;                              // slot and column of the first 64, kept for the write below
+        const int c_first = pa_col;
+        int a_got = slot(a_cur + lane, q_first);
+#pragma unroll 1
+        while (a_got == kWave) {
+            a_cur += kWave;
+            pa_lo = pa_hi = kNone;
+            load_entry(add_col, add_ext, n_add, a_cur + lane, true, pa_col, pa_lo, pa_hi);
+            __builtin_amdgcn_s_waitcnt(kVmcntZero);
+            int q_unused;
+            a_got = slot(a_cur + lane, q_unused);
         }
-        fetch_lists();            // the list entries at the new cursors, for the next sub-tile
+        a_cur += a_got;
+        // the list entries at the new cursors, for the next sub-tile
+        slide(del_col, del_ext, n_del, d_cur, d_got, pd_col, pd_lo, pd_hi);
+        slide(add_col, add_ext, n_add, a_cur, a_got, pa_col, pa_lo, pa_hi);
         __syncthreads();
 
         // ---- prefix sums: s_start[p] = kept entries before p + added entries of slots before p
@@ -329,20 +359,10 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
                 if (!(mk & 1) && pos < (unsigned)cap_next) colidx_next[pos] = c_[j];
             }
         }
-        // ---- added entries: their slot, then the rank among the adds of the same slot (they are consecutive)
+        // ---- added entries: their slot, then the rank among the adds of the same slot (they are consecutive).
+        // The first 64 kept their slot and column from the search above; more than 64 per sub-tile are rare.
         int q_carry = -1, rank_carry = 0;
-        for (int j0 = a_tile; j0 < a_cur; j0 += kWave) {
-            const int j = j0 + lane;
-            int q = q_first, c = c_first;
-            if (j0 != a_tile) {
-                q = -2 - lane;
-                if (j < a_cur) {
-                    const int r = add_row[j];
-                    c = add_col[j];
-                    const int lo = max(rowptr_prev[r] - e, 0), hi = min(rowptr_prev[r + 1] - e, cnt);
-                    q = lds_bound<true>(s_col, lo, hi, c);
-                }
-            }
+        auto place = [&](int j, int q, int c) {
             const int q_left = __shfl_up(q, 1, kWave);
             const bool head = lane == 0 ? q != q_carry : q != q_left;
             const unsigned long long true_heads = __ballot(head);
@@ -356,6 +376,19 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
             }
             q_carry = __shfl(q, kWave - 1, kWave);
             rank_carry = __shfl(rank, kWave - 1, kWave) + 1;
+        };
+        if (a_tile < a_cur) place(a_tile + lane, q_first, c_first);
+#pragma unroll 1
+        for (int j0 = a_tile + kWave; j0 < a_cur; j0 += kWave) {
+            const int j = j0 + lane;
+            int q = -2 - lane, c = 0;
+            if (j < a_cur) {
+                const int2 x = add_ext[j];
+                c = add_col[j];
+                const int lo = max(x.x - e, 0), hi = min(x.y - e, cnt);
+                q = lds_bound<true>(s_col, lo, hi, c);
+            }
+            place(j, q, c);
         }
         base += written;
         __syncthreads();           // LDS is rewritten by the next sub-tile
@@ -447,7 +480,9 @@ extern "C" int dgnn_delta_rebuild_workspace(int64_t n, int64_t nnz_prev, int64_t
     if (!bytes) return DGNN_ERR_NULL;
     if (n <= 0 || nnz_prev < 0 || n_add < 0 || n_del < 0) return DGNN_ERR_SHAPE;
     if (!fits_i32(n + 1) || !fits_i32(nnz_prev + n_add)) return DGNN_ERR_OVERFLOW;
-    *bytes = round_up((size_t)(n + 1) * sizeof(int32_t), 256);   // add_ptr
+    *bytes = round_up((size_t)(n + 1) * sizeof(int32_t), 256)     // add_ptr
+             + round_up((size_t)n_add * sizeof(int2), 256)         // row extents of the added entries
+             + round_up((size_t)n_del * sizeof(int2), 256);        // ... of the deleted entries
     return DGNN_OK;
 }
 
@@ -475,7 +510,10 @@ extern "C" int dgnn_delta_rebuild(int64_t n,
     if (nnz_next) *nnz_next = nnz_new;
 
     hipStream_t s = (hipStream_t)stream;
-    int32_t *add_ptr = static_cast<int32_t *>(ws);
+    char *wsb = static_cast<char *>(ws);
+    int32_t *add_ptr = reinterpret_cast<int32_t *>(wsb);
+    int2 *add_ext = reinterpret_cast<int2 *>(wsb + round_up((size_t)(n + 1) * sizeof(int32_t), 256));
+    int2 *del_ext = reinterpret_cast<int2 *>(reinterpret_cast<char *>(add_ext) + round_up((size_t)n_add * sizeof(int2), 256));
     const int cap = (int)min(cap_next, (int64_t)2147483647LL);
 
     hipLaunchKernelGGL(rowptr_kernel, dim3((unsigned)((n + kRowTile - 1) / kRowTile)), dim3(kRowThreads), 0, s,
@@ -489,11 +527,16 @@ extern "C" int dgnn_delta_rebuild(int64_t n,
                            (int)n_del, d_status);
         DGNN_RETURN_IF_LAUNCH_FAILED();
     }
+    if (n_add + n_del > 0) {
+        hipLaunchKernelGGL(extent_kernel, dim3((unsigned)((n_add + n_del + 255) / 256)), dim3(256), 0, s, (int)n, rowptr_prev,
+                           add_row, (int)n_add, del_row, (int)n_del, add_ext, del_ext);
+        DGNN_RETURN_IF_LAUNCH_FAILED();
+    }
     int64_t range_len = (nnz_prev + kTargetWaves - 1) / kTargetWaves;
     range_len = (range_len + kSub - 1) / kSub * kSub;
     if (range_len > kMaxRange) range_len = kMaxRange;
     hipLaunchKernelGGL(merge_kernel, dim3((unsigned)((nnz_prev + range_len - 1) / range_len)), dim3(kWave), 0, s,
-                       (int)n, rowptr_prev, colidx_prev, (int)nnz_prev, (int)range_len, add_row, add_col, (int)n_add, del_row, del_col,
+                       (int)n, rowptr_prev, colidx_prev, (int)nnz_prev, (int)range_len, add_col, add_ext, (int)n_add, del_col, del_ext,
                        (int)n_del, rowptr_next, add_ptr, colidx_next, cap);
     DGNN_RETURN_IF_LAUNCH_FAILED();
     return DGNN_OK;
