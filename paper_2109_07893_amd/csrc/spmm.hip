@@ -39,6 +39,7 @@ constexpr int kMaxRange = 8192;      // entries streamed by one wavefront, at mo
 constexpr int kTargetWaves = 16384;  // ranges shrink on small inputs so that about this many wavefronts exist
 constexpr int kXcds = 8;             // accelerator dies of an MI355X, each with its own L2
 constexpr int kXcdChunk = 16;        // consecutive ranges that go to the same XCD
+constexpr int kVmcntZero = 0x0F70;   // s_waitcnt operand: all vector memory loads returned, other counters untouched
 
 enum : int32_t { kLeft = 1, kLeftClosed = 2, kRight = 4 };
 struct RangeRec { int32_t flags, row_last, pad0, pad1; };
@@ -235,6 +236,9 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) v
             if (SCALE_V) dd[i] = d_next[i];
         }
         if (lane <= G) s_heads[lane] = 0u;
+        // Every load issued so far has been used or is used next; saying so here, ahead of the prefetch, keeps
+        // the gathers below from being held up by waits for "possibly outstanding" column indices.
+        __builtin_amdgcn_s_waitcnt(kVmcntZero);
         if (e_stop < e_end) {                            // fetched while this sub-tile is summed
             fetch_cols(e_stop);
             fetch_rows(k_next);
@@ -290,14 +294,17 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) v
             };
             // batch b covers entries 8 b .. 8 b + 7 of the group; ODD (the parity of b) makes the register
             // slot q % CPL a compile-time constant while b itself stays a run-time loop counter
-            auto batch = [&](int b, auto odd) {
+            // FULL: all 32 entries of every group exist (any sub-tile but a range's last), so nothing about the
+            // gathers is conditional and each one is waited for by itself, in the order they were issued
+            auto batch = [&](int b, auto odd, auto full) {
                 constexpr int ODD = decltype(odd)::value;
+                constexpr bool FULL = decltype(full)::value;
                 constexpr int slot_odd = (ODD * kBatch) % CPL;
                 Raw buf[kBatch];
 #pragma unroll
                 for (int k = 0; k < kBatch; ++k) {
                     const int q = b * kBatch + k;
-                    if (p0 + q < c1) {
+                    if (FULL || p0 + q < c1) {
                         const int c = __shfl(cc[(slot_odd + k) % CPL], gbase + q / CPL, kWave);
                         buf[k] = *reinterpret_cast<const Raw *>(h + (int64_t)c * kRowBytes + sub * 16);
                     }
@@ -306,7 +313,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) v
 #pragma unroll
                 for (int k = 0; k < kBatch; ++k) {
                     const int q = b * kBatch + k;
-                    if (p0 + q < c1) {
+                    if (FULL || p0 + q < c1) {
                         if (q > 0 && ((wb >> k) & 1u)) {
                             flush(true);
                             left_closed = true;
@@ -319,10 +326,18 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) v
                     }
                 }
             };
+            if (cnt == SUB) {
 #pragma unroll 1
-            for (int b = 0; b < kPer / kBatch; b += 2) {
-                batch(b, std::integral_constant<int, 0>{});
-                batch(b + 1, std::integral_constant<int, 1>{});
+                for (int b = 0; b < kPer / kBatch; b += 2) {
+                    batch(b, std::integral_constant<int, 0>{}, std::true_type{});
+                    batch(b + 1, std::integral_constant<int, 1>{}, std::true_type{});
+                }
+            } else {
+#pragma unroll 1
+                for (int b = 0; b < kPer / kBatch; b += 2) {
+                    batch(b, std::integral_constant<int, 0>{}, std::false_type{});
+                    batch(b + 1, std::integral_constant<int, 1>{}, std::false_type{});
+                }
             }
             // does the row of the last entry end with it?
             flush(c1 == cnt ? s_rp[t_last + 1] == e_stop : (s_heads[g + 1] & 1u) != 0);
