@@ -7,7 +7,8 @@
 // The time loop is unrolled by the ring size so that ring slots are compile-time registers.
 // With the paper's weights (every term 1/min(w,t)) the window sum is kept as a running sum,
 // S_t = S_{t-1} + Z_t - Z_{t-w}, with a ring of exactly w slots (the slot about to be overwritten
-// holds Z_{t-w}); explicit coefficients take the general kernel, w multiply-adds per element.
+// holds Z_{t-w}) and up to four frames fetched ahead; explicit coefficients take the general
+// kernel, w multiply-adds per element.
 #include "common.hpp"
 
 namespace {
@@ -106,10 +107,14 @@ __global__ __launch_bounds__(kThreads) void mproduct_kernel(const char *z, char 
 }
 
 // The paper's weights: ring of exactly W raw 16-byte pieces, running window sum in fp32.
+// D frames are fetched ahead of the one being summed.  Every load is unconditional (beyond the last frame the
+// last one is simply read again), so each is waited for by itself and a lane keeps D loads and its stores in
+// flight; whole rounds of W steps run without a bounds test, the remainder of the series with one.
 template <int W, bool BF16>
 __global__ __launch_bounds__(kThreads) void mproduct_uniform_kernel(const char *z, char *y, int T, int64_t pieces,
                                                                     int64_t frame_bytes) {
     constexpr int NV = Vec<BF16>::kVals;
+    constexpr int D = W % 4 == 0 ? 4 : (W % 2 == 0 ? 2 : 1);     // divides W, so a frame's queue slot is t % D = jj % D
     const int64_t piece = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (piece >= pieces) return;
     const char *src = z + piece * 16;
@@ -122,28 +127,34 @@ __global__ __launch_bounds__(kThreads) void mproduct_uniform_kernel(const char *
 #pragma unroll
     for (int e = 0; e < NV; ++e) sum[e] = 0.0f;
 
-    uintx4 next = *reinterpret_cast<const uintx4 *>(src);
-    for (int tb = 0; tb < T; tb += W) {
+    uintx4 ahead[D];
 #pragma unroll
-        for (int jj = 0; jj < W; ++jj) {
-            const int t = tb + jj;             // 0-based timestep; slot jj holds frame t - W
-            if (t < T) {
-                const uintx4 cur = next;
-                if (t + 1 < T) next = *reinterpret_cast<const uintx4 *>(src + (int64_t)(t + 1) * frame_bytes);   // before the store: y may be z
-                float in[NV], old[NV], out[NV];
-                Vec<BF16>::unpack(in, cur);
-                Vec<BF16>::unpack(old, ring[jj]);
-                ring[jj] = cur;
-                const float scale = 1.0f / (float)min(W, t + 1);
+    for (int d = 0; d < D; ++d) ahead[d] = *reinterpret_cast<const uintx4 *>(src + (int64_t)min(d, T - 1) * frame_bytes);
+
+    // one timestep t (0-based); `slot` holds frame t - W, `queued` frame t
+    auto step = [&](int t, uintx4 &slot, uintx4 &queued) {
+        const uintx4 cur = queued;
+        queued = *reinterpret_cast<const uintx4 *>(src + (int64_t)min(t + D, T - 1) * frame_bytes);   // before the store: y may be z
+        float in[NV], old[NV], out[NV];
+        Vec<BF16>::unpack(in, cur);
+        Vec<BF16>::unpack(old, slot);
+        slot = cur;
+        const float scale = 1.0f / (float)min(W, t + 1);
 #pragma unroll
-                for (int e = 0; e < NV; ++e) {
-                    sum[e] += in[e] - old[e];
-                    out[e] = sum[e] * scale;
-                }
-                Vec<BF16>::store(dst + (int64_t)t * frame_bytes, out);
-            }
+        for (int e = 0; e < NV; ++e) {
+            sum[e] += in[e] - old[e];
+            out[e] = sum[e] * scale;
         }
+        Vec<BF16>::store(dst + (int64_t)t * frame_bytes, out);
+    };
+    int tb = 0;
+    for (; tb + W <= T; tb += W) {
+#pragma unroll
+        for (int jj = 0; jj < W; ++jj) step(tb + jj, ring[jj], ahead[jj % D]);
     }
+#pragma unroll
+    for (int jj = 0; jj < W; ++jj)
+        if (tb + jj < T) step(tb + jj, ring[jj], ahead[jj % D]);
 }
 
 template <int W>
