@@ -6,7 +6,8 @@ Arrays go in and out as numpy; real numbers are float64 throughout.
 
 Passages followed: reconstruction from a graph difference -- Section "Graph-difference Based
 Input Transfer"; normalised adjacency -- Eqn (1); GCN operation -- Eqn (2); M-transform and
-its matrix M -- Section "TM-GCN".
+its matrix M -- Section "TM-GCN"; gradient propagation through a block in the reverse direction
+-- Section "Gradient Checkpoint" (the adjoint of each forward step).
 """
 from __future__ import annotations
 
@@ -56,6 +57,12 @@ def _load():
         lib.oracle_m_matrix.argtypes = [_i64, _i64, _f64p]
         lib.oracle_mproduct.restype = None
         lib.oracle_mproduct.argtypes = [_i64, _i64, _f64p, _f64p, _f64p]
+        lib.oracle_spmm_t.restype = None
+        lib.oracle_spmm_t.argtypes = [_i64, _i32p, _i32p, _f64p, _f64p, _i64, _f64p]
+        lib.oracle_weight_grad.restype = None
+        lib.oracle_weight_grad.argtypes = [_i64, _i64, _i64, _f64p, _f64p, _f64p]
+        lib.oracle_mproduct_t.restype = None
+        lib.oracle_mproduct_t.argtypes = [_i64, _i64, _f64p, _f64p, _f64p]
         lib.oracle_num_threads.restype = ctypes.c_int
         lib.oracle_set_threads.argtypes = [ctypes.c_int]
         _lib = lib
@@ -167,3 +174,57 @@ def mproduct(z, M) -> np.ndarray:
 def gcn_layer(rowptr, colidx, x, w, relu: bool = False, rows=None) -> np.ndarray:
     """sigma?(A~ (X W)), Eqn (2)."""
     return spmm(rowptr, colidx, xw(x, w), relu=relu, rows=rows)
+
+
+# ---- backward of the same path (Section "Gradient Checkpoint") ------------------------------------
+
+def spmm_t(rowptr, colidx, g, val: Optional[np.ndarray] = None) -> np.ndarray:
+    """A~^T G: the adjoint of the aggregation of Eqn (2)."""
+    rowptr, colidx, g = _a(rowptr, np.int32), _a(colidx, np.int32), _a(g, np.float64)
+    n = rowptr.size - 1
+    f = g.shape[1]
+    assert g.shape[0] == n
+    if val is None:
+        val = gcn_values(rowptr, colidx)
+    val = _a(val, np.float64)
+    out = np.zeros((n, f), np.float64)
+    _load().oracle_spmm_t(n, _p(rowptr, _i32p), _p(colidx, _i32p), _p(val, _f64p), _p(g, _f64p), f, _p(out, _f64p))
+    return out
+
+
+def weight_grad(x, g) -> np.ndarray:
+    """dW = X^T G for H = X W and G = dL/dH."""
+    x, g = _a(x, np.float64), _a(g, np.float64)
+    n, fi = x.shape
+    fo = g.shape[1]
+    assert g.shape[0] == n
+    dw = np.zeros((fi, fo), np.float64)
+    _load().oracle_weight_grad(n, fi, fo, _p(x, _f64p), _p(g, _f64p), _p(dw, _f64p))
+    return dw
+
+
+def input_grad(g, w) -> np.ndarray:
+    """dX = G W^T for H = X W and G = dL/dH."""
+    return xw(g, _a(w, np.float64).T.copy())
+
+
+def mproduct_t(g, M) -> np.ndarray:
+    """G x_1 M^T: the adjoint of the M-transform; out_k = sum_t M[t][k] G_t."""
+    g, M = _a(g, np.float64), _a(M, np.float64)
+    T = g.shape[0]
+    assert M.shape == (T, T)
+    frame = int(np.prod(g.shape[1:]))
+    out = np.zeros_like(g)
+    _load().oracle_mproduct_t(T, frame, _p(M, _f64p), _p(g, _f64p), _p(out, _f64p))
+    return out
+
+
+def relu_grad(g, z) -> np.ndarray:
+    """Gradient through Z = max(P, 0): G where Z > 0, else 0 (Z > 0 exactly where P > 0)."""
+    return np.where(_a(z, np.float64) > 0.0, _a(g, np.float64), 0.0)
+
+
+def gcn_layer_backward(rowptr, colidx, x, w, z, g_z):
+    """Gradients of Z = relu(A~ (X W)) for upstream g_z = dL/dZ: returns (dW, dX)."""
+    g_h = spmm_t(rowptr, colidx, relu_grad(g_z, z))
+    return weight_grad(x, g_h), input_grad(g_h, w)

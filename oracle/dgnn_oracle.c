@@ -11,7 +11,9 @@
  *   - normalised adjacency: Eqn (1), A~ = D^{-1/2} (A + I) D^{-1/2}, D[u,u] = 1 + deg_u;
  *   - GCN operation: Eqn (2), Y = sigma(A~ X W), evaluated as A~ (X W);
  *   - M-transform: Section "TM-GCN", Y = X x_1 M with the banded lower-triangular M printed
- *     there (M_tk = 1 / min(w, t) for max(1, t-w+1) <= k <= t, 1-based).
+ *     there (M_tk = 1 / min(w, t) for max(1, t-w+1) <= k <= t, 1-based);
+ *   - gradient propagation through those steps (Section "Gradient Checkpoint"): the adjoint of each
+ *     step, A~^T G, X^T G, G W^T, G x_1 M^T, and the ReLU mask.
  *
  * Conventions: the stored matrix is A + I (every row holds its diagonal entry), rows are CSR
  * with ascending, duplicate-free columns, indices are 0-based int32.  With the diagonal stored,
@@ -183,6 +185,44 @@ void oracle_mproduct(int64_t T, int64_t frame, const double *M, const double *z,
             double s = 0.0;
             for (int64_t k = 0; k < T; ++k) s += M[t * T + k] * z[k * frame + i];
             y[t * frame + i] = s;
+        }
+}
+
+/* ---- backward of the same path (Section "Gradient Checkpoint": after a block has been run forward
+ * again, gradients are propagated through it in the reverse direction).  Each function is the adjoint of
+ * one forward step above, written out from the definition of that step. ---- */
+
+/* Adjoint of the aggregation of Eqn (2): out = A~^T G, i.e. every stored entry (u, v) of A + I sends
+ * val(u, v) * G[u] to out[v].  Entries are visited in storage order, one thread per feature column. */
+void oracle_spmm_t(int64_t n, const int32_t *rowptr, const int32_t *colidx, const double *val,
+                   const double *g, int64_t f, double *out) {
+    for (int64_t i = 0; i < n * f; ++i) out[i] = 0.0;
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < f; ++j)
+        for (int64_t u = 0; u < n; ++u)
+            for (int64_t e = rowptr[u]; e < rowptr[u + 1]; ++e)
+                out[(int64_t)colidx[e] * f + j] += val[e] * g[u * f + j];
+}
+
+/* Gradient of the weight of H = X W (dense factor of Eqn (2)) for an upstream G = dL/dH: dW = X^T G. */
+void oracle_weight_grad(int64_t n, int64_t f_in, int64_t f_out, const double *x, const double *g, double *dw) {
+#pragma omp parallel for schedule(static)
+    for (int64_t k = 0; k < f_in; ++k)
+        for (int64_t j = 0; j < f_out; ++j) {
+            double s = 0.0;
+            for (int64_t i = 0; i < n; ++i) s += x[i * f_in + k] * g[i * f_out + j];
+            dw[k * f_out + j] = s;
+        }
+}
+
+/* Adjoint of the M-transform (Section "TM-GCN"): out_k = sum_t M[t][k] G_t. */
+void oracle_mproduct_t(int64_t T, int64_t frame, const double *M, const double *g, double *out) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < frame; ++i)
+        for (int64_t k = 0; k < T; ++k) {
+            double s = 0.0;
+            for (int64_t t = 0; t < T; ++t) s += M[t * T + k] * g[t * frame + i];
+            out[k * frame + i] = s;
         }
 }
 

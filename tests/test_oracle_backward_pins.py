@@ -1,0 +1,150 @@
+"""Pins for the backward half of the CPU oracle (gradient propagation through a block, Section
+"Gradient Checkpoint").  Each adjoint is checked against things that are not itself: the inner-product
+identity <A^T g, h> = <g, A h> with the forward oracle (pinned elsewhere) on the other side, dense
+transposes built here in numpy, closed forms, and central finite differences of the forward path in
+double precision.  All CPU."""
+import numpy as np
+import pytest
+
+import oracle
+from test_oracle_pins import csr_from_dense, dense_gcn_matrix, random_graph_dense
+
+
+def _graph(n, p, seed, symmetric):
+    rng = np.random.default_rng(seed)
+    a = random_graph_dense(n, p, rng, symmetric)
+    rp, ci = csr_from_dense(a)
+    return a, rp, ci, rng
+
+
+# ----------------------------------------------------------------------------- A~^T G
+@pytest.mark.parametrize("symmetric", [False, True])
+def test_spmm_t_matches_dense_transpose(symmetric):
+    a, rp, ci, rng = _graph(57, 0.1, 11, symmetric)
+    g = rng.standard_normal((57, 5))
+    want = dense_gcn_matrix(a).T @ g
+    np.testing.assert_allclose(oracle.spmm_t(rp, ci, g), want, rtol=1e-12, atol=1e-13)
+
+
+def test_spmm_t_is_the_adjoint_of_spmm():
+    _, rp, ci, rng = _graph(200, 0.05, 12, False)
+    g, h = rng.standard_normal((200, 7)), rng.standard_normal((200, 7))
+    lhs = np.sum(oracle.spmm_t(rp, ci, g) * h)
+    rhs = np.sum(g * oracle.spmm(rp, ci, h))
+    assert abs(lhs - rhs) <= 1e-11 * (abs(lhs) + 1)
+
+
+def test_spmm_t_equals_spmm_on_undirected_graphs_only():
+    _, rp, ci, rng = _graph(80, 0.08, 13, True)
+    g = rng.standard_normal((80, 3))
+    np.testing.assert_allclose(oracle.spmm_t(rp, ci, g), oracle.spmm(rp, ci, g), rtol=1e-12, atol=1e-13)
+    _, rp, ci, rng = _graph(80, 0.08, 14, False)
+    g = rng.standard_normal((80, 3))
+    assert np.max(np.abs(oracle.spmm_t(rp, ci, g) - oracle.spmm(rp, ci, g))) > 1e-3
+
+
+def test_spmm_t_closed_form_sqrt_degree():
+    # y_u = sqrt(1 + deg_u): every stored (u, v) sends 1 / sqrt(1 + deg_v) to v, so
+    # (A~^T y)_v = (number of stored entries in column v) / sqrt(1 + deg_v), directed or not.
+    a, rp, ci, _ = _graph(120, 0.06, 15, False)
+    d = np.diff(rp).astype(np.float64)
+    col_count = a.sum(axis=0).astype(np.float64)
+    got = oracle.spmm_t(rp, ci, np.sqrt(d)[:, None])[:, 0]
+    np.testing.assert_allclose(got, col_count / np.sqrt(d), rtol=1e-12)
+
+
+# ----------------------------------------------------------------------------- X^T G and G W^T
+def test_weight_grad_special_cases_and_numpy():
+    rng = np.random.default_rng(16)
+    g = rng.standard_normal((40, 6))
+    x = np.zeros((40, 9))
+    x[np.arange(9), np.arange(9)] = 1.0                       # X = [I; 0]  =>  X^T G = first rows of G
+    np.testing.assert_array_equal(oracle.weight_grad(x, g), g[:9])
+    x = rng.standard_normal((40, 9))
+    np.testing.assert_allclose(oracle.weight_grad(x, g), x.T @ g, rtol=1e-12, atol=1e-13)
+    # transposing the roles transposes the result: (X^T G)^T = G^T X
+    np.testing.assert_allclose(oracle.weight_grad(g, x), oracle.weight_grad(x, g).T, rtol=1e-12, atol=1e-13)
+
+
+def test_input_grad_matches_numpy_and_adjoint():
+    rng = np.random.default_rng(17)
+    g, w, x = rng.standard_normal((30, 6)), rng.standard_normal((9, 6)), rng.standard_normal((30, 9))
+    np.testing.assert_allclose(oracle.input_grad(g, w), g @ w.T, rtol=1e-12, atol=1e-13)
+    lhs, rhs = np.sum(oracle.input_grad(g, w) * x), np.sum(g * oracle.xw(x, w))   # <G W^T, X> = <G, X W>
+    assert abs(lhs - rhs) <= 1e-11 * (abs(lhs) + 1)
+
+
+# ----------------------------------------------------------------------------- G x_1 M^T
+@pytest.mark.parametrize("T,w", [(7, 3), (5, 1), (6, 9), (12, 4)])
+def test_mproduct_t_adjoint_and_closed_forms(T, w):
+    rng = np.random.default_rng(18 + T)
+    M = oracle.m_matrix(T, w)
+    g, z = rng.standard_normal((T, 4, 3)), rng.standard_normal((T, 4, 3))
+    got = oracle.mproduct_t(g, M)
+    lhs, rhs = np.sum(got * z), np.sum(g * oracle.mproduct(z, M))
+    assert abs(lhs - rhs) <= 1e-11 * (abs(lhs) + 1)
+    # written out from the band: out_k = sum_{t=k}^{min(T, k+w-1)} g_t / min(w, t)   (1-based)
+    want = np.zeros_like(g)
+    for k in range(1, T + 1):
+        for t in range(k, min(T, k + w - 1) + 1):
+            want[k - 1] += g[t - 1] / min(w, t)
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-13)
+    if w == 1:
+        np.testing.assert_array_equal(got, g)
+    if w >= T:   # all-ones gradient: harmonic tail sums H_T - H_{k-1}
+        ones = oracle.mproduct_t(np.ones((T, 1)), M)[:, 0]
+        harm = np.cumsum(1.0 / np.arange(1, T + 1))
+        np.testing.assert_allclose(ones, harm[-1] - np.concatenate([[0.0], harm[:-1]]), rtol=1e-12)
+
+
+# ----------------------------------------------------------------------------- whole layer, finite differences
+def _layer_loss(rp, ci, xs, w, M, c):
+    z = np.stack([oracle.gcn_layer(rp_t, ci_t, x_t, w, relu=True) for rp_t, ci_t, x_t in zip(rp, ci, xs)])
+    return float(np.sum(c * oracle.mproduct(z, M))), z
+
+
+def test_layer_backward_matches_finite_differences():
+    T, n, f, wdw = 4, 23, 3, 2
+    rng = np.random.default_rng(19)
+    rps, cis = [], []
+    for t in range(T):
+        a = random_graph_dense(n, 0.15, rng, False)
+        r, c = csr_from_dense(a)
+        rps.append(r)
+        cis.append(c)
+    xs = [rng.standard_normal((n, f)) for _ in range(T)]
+    w = rng.standard_normal((f, f))
+    c = rng.standard_normal((T, n, f))
+    M = oracle.m_matrix(T, wdw)
+    loss, z = _layer_loss(rps, cis, xs, w, M, c)
+    pre = np.stack([oracle.gcn_layer(r, ci_, x, w, relu=False) for r, ci_, x in zip(rps, cis, xs)])
+    assert np.min(np.abs(pre)) > 1e-4          # no pre-activation sits on the kink of the ReLU
+
+    g_z = oracle.mproduct_t(c, M)               # dL/dZ
+    dw = np.zeros_like(w)
+    dxs = []
+    for t in range(T):
+        dw_t, dx_t = oracle.gcn_layer_backward(rps[t], cis[t], xs[t], w, z[t], g_z[t])
+        dw += dw_t
+        dxs.append(dx_t)
+
+    eps = 1e-6
+    for (i, j) in [(0, 0), (1, 2), (2, 1)]:
+        wp, wm = w.copy(), w.copy()
+        wp[i, j] += eps
+        wm[i, j] -= eps
+        fd = (_layer_loss(rps, cis, xs, wp, M, c)[0] - _layer_loss(rps, cis, xs, wm, M, c)[0]) / (2 * eps)
+        assert abs(fd - dw[i, j]) <= 1e-6 * (abs(fd) + 1), (i, j, fd, dw[i, j])
+    for (t, u, j) in [(0, 0, 0), (2, 7, 1), (3, 22, 2)]:
+        xp = [x.copy() for x in xs]
+        xm = [x.copy() for x in xs]
+        xp[t][u, j] += eps
+        xm[t][u, j] -= eps
+        fd = (_layer_loss(rps, cis, xp, w, M, c)[0] - _layer_loss(rps, cis, xm, w, M, c)[0]) / (2 * eps)
+        assert abs(fd - dxs[t][u, j]) <= 1e-6 * (abs(fd) + 1), (t, u, j, fd, dxs[t][u, j])
+
+
+def test_relu_grad_masks_where_output_is_zero():
+    g = np.array([[1.0, -2.0, 3.0]])
+    z = np.array([[0.5, 0.0, 2.0]])
+    np.testing.assert_array_equal(oracle.relu_grad(g, z), [[1.0, 0.0, 3.0]])
