@@ -168,6 +168,63 @@ int dgnn_spmm(int64_t n, int64_t nnz, const int32_t *rowptr, const int32_t *coli
 int dgnn_mproduct(const void *z, void *y, int64_t T, int64_t n, int32_t f, int32_t w,
                   const float *m_band, dgnn_dtype dt, void *stream);
 
+/*
+ * ---- Gradient propagation through the same path (Section "Gradient Checkpoint": a block is run forward
+ * again and gradients then travel through it in the reverse direction).  For one GCN layer
+ *     H = X W,  P = A~ H,  Z = max(P, 0),  Y = Z x_1 M
+ * with G_Y = dL/dY given, the adjoints of the forward steps, in the order they are applied:
+ *     G_Z = G_Y x_1 M^T                              dgnn_mproduct_backward
+ *     G_P = G_Z where Z > 0, else 0                  dgnn_relu_backward
+ *     G_H = A~^T G_P                                 dgnn_spmm on the TRANSPOSED snapshot (see below)
+ *     dW += X^T G_H,   dX = G_H W^T                  dgnn_weight_grad, dgnn_input_grad
+ *
+ * A~^T G = D^(-1/2) (A + I)^T D^(-1/2) G needs no kernel of its own: call dgnn_spmm with rowptr/colidx of
+ * (A + I)^T and with dinv of A (NOT the one derived from the transposed row lengths).  For an undirected
+ * snapshot the transpose is the snapshot itself.  For a directed one the transposed snapshots form a dynamic
+ * graph of their own, rebuilt by dgnn_delta_rebuild from the difference lists sorted by (col, row) with rows
+ * and columns swapped.  Walking a block backwards needs A_{t-1} from A_t: that is dgnn_delta_rebuild with the
+ * added and deleted lists exchanged.
+ */
+
+/*
+ * Adjoint of the M-transform (Section "TM-GCN"): G_Z = G_Y x_1 M^T,
+ *     G_Z[k] = sum_{j=0}^{min(w, T-k+1)-1} m(k+j, j) G_Y[k+j],   k = 1..T (1-based),
+ * with the same m, w, m_band, layouts, limits and aliasing rules as dgnn_mproduct (g_z may be g_y).
+ */
+int dgnn_mproduct_backward(const void *g_y, void *g_z, int64_t T, int64_t n, int32_t f, int32_t w,
+                           const float *m_band, dgnn_dtype dt, void *stream);
+
+/*
+ * Gradient through sigma = ReLU of Eqn (2): out[u][:] = row_scale[u] * (z[u][:] > 0 ? g[u][:] : 0).
+ *   g, z, out [n][f]        storage type dt; z is the layer's OUTPUT (positive exactly where the
+ *                           pre-activation was); out may be the same pointer as g
+ *   row_scale [n] fp32 or NULL; passing dinv prepares the rows for dgnn_spmm with DGNN_H_PRESCALED
+ */
+int dgnn_relu_backward(const void *g, const void *z, const float *row_scale, void *out, int64_t n, int32_t f,
+                       dgnn_dtype dt, void *stream);
+
+/* Workspace size of dgnn_weight_grad in bytes (HOST out-parameter); depends on the widths only. */
+int dgnn_weight_grad_workspace(int32_t f_in, int32_t f_out, size_t *bytes);
+
+/*
+ * Gradient of the weight of H = X W (dense factor of Eqn (2)): dw = X^T G, or dw += X^T G.
+ *   x [n][f_in], g [n][f_out]   storage type dt (g = dL/dH); products accumulate in fp32 on the matrix cores
+ *   dw [f_in][f_out]            fp32 whatever dt is; with accumulate != 0 the result is added to it (the sum
+ *                               over the timesteps of a block that share one W)
+ *   ws, ws_bytes                scratch of at least dgnn_weight_grad_workspace() bytes
+ * The sum over rows has a fixed order: results repeat bit for bit.
+ */
+int dgnn_weight_grad(const void *x, const void *g, int64_t n, int32_t f_in, int32_t f_out, float *dw,
+                     int32_t accumulate, dgnn_dtype dt, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Gradient of the input of H = X W: dx = G W^T, or diag(row_scale) G W^T.
+ *   g [n][f_out], w [f_in][f_out] (the forward layout, read transposed), dx [n][f_in]; otherwise as
+ *   dgnn_feature_transform.
+ */
+int dgnn_input_grad(const void *g, int64_t n, int32_t f_out, const void *w, int32_t f_in,
+                    const float *row_scale, void *dx, dgnn_dtype dt, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

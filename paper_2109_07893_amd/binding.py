@@ -24,6 +24,7 @@ DGNN_H_PRESCALED = 2
 EXPORTS = (
     "dgnn_strerror", "dgnn_csr_dinv", "dgnn_delta_h2d", "dgnn_delta_rebuild_workspace",
     "dgnn_delta_rebuild", "dgnn_feature_transform", "dgnn_spmm_workspace", "dgnn_spmm", "dgnn_mproduct",
+    "dgnn_mproduct_backward", "dgnn_relu_backward", "dgnn_weight_grad_workspace", "dgnn_weight_grad", "dgnn_input_grad",
 )
 
 
@@ -77,6 +78,11 @@ def load_library():
     lib.dgnn_spmm_workspace.argtypes = [_i64, _i64, _i32, ctypes.POINTER(_sz)]
     lib.dgnn_spmm.argtypes = [_i64, _i64, _vp, _vp, _vp, _vp, _i32, _vp, ctypes.c_int, _u32, _vp, _sz, _vp]
     lib.dgnn_mproduct.argtypes = [_vp, _vp, _i64, _i64, _i32, _i32, _vp, ctypes.c_int, _vp]
+    lib.dgnn_mproduct_backward.argtypes = [_vp, _vp, _i64, _i64, _i32, _i32, _vp, ctypes.c_int, _vp]
+    lib.dgnn_relu_backward.argtypes = [_vp, _vp, _vp, _vp, _i64, _i32, ctypes.c_int, _vp]
+    lib.dgnn_weight_grad_workspace.argtypes = [_i32, _i32, ctypes.POINTER(_sz)]
+    lib.dgnn_weight_grad.argtypes = [_vp, _vp, _i64, _i32, _i32, _vp, _i32, ctypes.c_int, _vp, _sz, _vp]
+    lib.dgnn_input_grad.argtypes = [_vp, _i64, _i32, _vp, _i32, _vp, _vp, ctypes.c_int, _vp]
     for name in EXPORTS:
         if name != "dgnn_strerror":
             getattr(lib, name).restype = ctypes.c_int
@@ -208,6 +214,65 @@ def mproduct(z: torch.Tensor, y: torch.Tensor, w: int, m_band: Optional[torch.Te
         if m_band.numel() != T * w:
             raise ValueError("m_band must be [T, w]")
     _check(load_library().dgnn_mproduct(_ptr(z), _ptr(y), T, n, f, w, _ptr(m_band), dt, _stream(z)), "dgnn_mproduct")
+
+
+def mproduct_backward(g_y: torch.Tensor, g_z: torch.Tensor, w: int, m_band: Optional[torch.Tensor] = None) -> None:
+    """G_Z = G_Y x_1 M^T over tensors [T, n, f]; g_z may be g_y itself."""
+    dt = _dtype_code(g_y)
+    T, n, f = g_y.shape
+    if tuple(g_z.shape) != (T, n, f) or g_z.dtype != g_y.dtype:
+        raise ValueError("shape mismatch in mproduct_backward")
+    if m_band is not None:
+        _need(m_band, torch.float32, "m_band")
+        if m_band.numel() != T * w:
+            raise ValueError("m_band must be [T, w]")
+    _check(load_library().dgnn_mproduct_backward(_ptr(g_y), _ptr(g_z), T, n, f, w, _ptr(m_band), dt, _stream(g_y)),
+           "dgnn_mproduct_backward")
+
+
+def relu_backward(g: torch.Tensor, z: torch.Tensor, out: torch.Tensor, row_scale: Optional[torch.Tensor] = None) -> None:
+    """out = row_scale * (z > 0 ? g : 0); out may be g itself."""
+    dt = _dtype_code(g)
+    n, f = g.shape
+    if tuple(z.shape) != (n, f) or tuple(out.shape) != (n, f) or z.dtype != g.dtype or out.dtype != g.dtype:
+        raise ValueError("shape mismatch in relu_backward")
+    if row_scale is not None:
+        _need(row_scale, torch.float32, "row_scale")
+        if row_scale.numel() != n:
+            raise ValueError("row_scale must have one entry per row")
+    _check(load_library().dgnn_relu_backward(_ptr(g), _ptr(z), _ptr(row_scale), _ptr(out), n, f, dt, _stream(g)),
+           "dgnn_relu_backward")
+
+
+def weight_grad_workspace(f_in: int, f_out: int) -> int:
+    out = _sz(0)
+    _check(load_library().dgnn_weight_grad_workspace(f_in, f_out, ctypes.byref(out)), "dgnn_weight_grad_workspace")
+    return int(out.value)
+
+
+def weight_grad(x: torch.Tensor, g: torch.Tensor, dw: torch.Tensor, ws: torch.Tensor, accumulate: bool = False) -> None:
+    """dw = X^T G (or dw += X^T G); dw is float32 whatever the storage type of x and g."""
+    dt = _dtype_code(x)
+    n, f_in = x.shape
+    f_out = g.shape[1]
+    _need(dw, torch.float32, "dw")
+    if g.dtype != x.dtype or g.shape[0] != n or tuple(dw.shape) != (f_in, f_out):
+        raise ValueError("shape mismatch in weight_grad")
+    _check(load_library().dgnn_weight_grad(_ptr(x), _ptr(g), n, f_in, f_out, _ptr(dw), int(bool(accumulate)), dt,
+                                           _ptr(ws), ws.numel() * ws.element_size(), _stream(x)), "dgnn_weight_grad")
+
+
+def input_grad(g: torch.Tensor, w: torch.Tensor, dx: torch.Tensor, row_scale: Optional[torch.Tensor] = None) -> None:
+    """dX = G W^T with w in its forward layout [f_in, f_out]."""
+    dt = _dtype_code(g)
+    n, f_out = g.shape
+    f_in = w.shape[0]
+    if w.dtype != g.dtype or dx.dtype != g.dtype or w.shape[1] != f_out or tuple(dx.shape) != (n, f_in):
+        raise ValueError("shape mismatch in input_grad")
+    if row_scale is not None:
+        _need(row_scale, torch.float32, "row_scale")
+    _check(load_library().dgnn_input_grad(_ptr(g), n, f_out, _ptr(w), f_in, _ptr(row_scale), _ptr(dx), dt, _stream(g)),
+           "dgnn_input_grad")
 
 
 # codes a device-side validation can leave in d_status (include/dgnn.h)

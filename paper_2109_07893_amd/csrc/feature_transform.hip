@@ -41,7 +41,7 @@ constexpr int kWavesPerBlock = kThreads / kWave;
 template <int FIN, int FOUT>
 __global__ __launch_bounds__(kThreads) void xw_f32_kernel(const float *__restrict__ x, const float *__restrict__ w,
                                                           const float *__restrict__ row_scale, float *__restrict__ h,
-                                                          int64_t n, int64_t n_tiles) {
+                                                          int64_t n, int64_t n_tiles, int wt) {
     constexpr int NT = (FOUT + 31) / 32;   // 32-wide column tiles (FOUT = 16 is zero-padded)
     constexpr int LD = NT * 32;
     constexpr int KH = FIN / 2;            // k values owned by one lane
@@ -50,7 +50,7 @@ __global__ __launch_bounds__(kThreads) void xw_f32_kernel(const float *__restric
     const int tid = threadIdx.x;
     for (int idx = tid; idx < FIN * LD; idx += kThreads) {
         int k = idx / LD, j = idx % LD;
-        s_w[idx] = j < FOUT ? w[k * FOUT + j] : 0.0f;
+        s_w[idx] = j < FOUT ? w[wt ? j * FIN + k : k * FOUT + j] : 0.0f;
     }
     __syncthreads();
 
@@ -119,7 +119,7 @@ __global__ __launch_bounds__(kThreads) void xw_f32_kernel(const float *__restric
 template <int FIN, int FOUT>
 __global__ __launch_bounds__(kThreads) void xw_f32_staged_kernel(const float *__restrict__ x, const float *__restrict__ w,
                                                                  const float *__restrict__ row_scale, float *__restrict__ h,
-                                                                 int64_t n, int64_t n_tiles) {
+                                                                 int64_t n, int64_t n_tiles, int wt) {
     constexpr int NT = FOUT / 32;
     constexpr int KH = FIN / 2;
     constexpr int FMAX = FIN > FOUT ? FIN : FOUT;
@@ -131,7 +131,7 @@ __global__ __launch_bounds__(kThreads) void xw_f32_staged_kernel(const float *__
     __shared__ __attribute__((aligned(16))) float s_tile[kWavesPerBlock][32 * LDT];
 
     const int tid = threadIdx.x;
-    for (int idx = tid; idx < FIN * FOUT; idx += kThreads) s_w[idx] = w[idx];
+    for (int idx = tid; idx < FIN * FOUT; idx += kThreads) s_w[idx] = w[wt ? (idx % FOUT) * FIN + idx / FOUT : idx];
     const int lane = tid & (kWave - 1), wave = tid / kWave;
     const int i = lane & 31, hh = lane >> 5;
     float *tile_lds = s_tile[wave];
@@ -205,7 +205,7 @@ __global__ __launch_bounds__(kThreads) void xw_f32_staged_kernel(const float *__
 template <int FIN, int FOUT>
 __global__ __launch_bounds__(kThreads) void xw_bf16_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ w,
                                                            const float *__restrict__ row_scale, uint16_t *__restrict__ h,
-                                                           int64_t n, int64_t n_tiles) {
+                                                           int64_t n, int64_t n_tiles, int wt) {
     constexpr int NT = (FOUT + 31) / 32;
     constexpr int JG = NT > 2 ? 2 : NT;    // column tiles accumulated at a time (bounds the live accumulators)
     constexpr int KH = FIN / 2;            // bf16 values owned by one lane
@@ -216,7 +216,7 @@ __global__ __launch_bounds__(kThreads) void xw_bf16_kernel(const uint16_t *__res
     const int tid = threadIdx.x;
     for (int idx = tid; idx < FIN * NT * 32; idx += kThreads) {
         int k = idx / (NT * 32), j = idx % (NT * 32);
-        s_wt[j * LDW + k] = j < FOUT ? w[k * FOUT + j] : (uint16_t)0;
+        s_wt[j * LDW + k] = j < FOUT ? w[wt ? j * FIN + k : k * FOUT + j] : (uint16_t)0;
     }
     __syncthreads();
 
@@ -287,7 +287,7 @@ __global__ __launch_bounds__(kThreads) void xw_bf16_kernel(const uint16_t *__res
 template <int FIN, int FOUT>
 __global__ __launch_bounds__(kThreads) void xw_bf16_staged_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ w,
                                                                   const float *__restrict__ row_scale, uint16_t *__restrict__ h,
-                                                                  int64_t n, int64_t n_tiles) {
+                                                                  int64_t n, int64_t n_tiles, int wt) {
     constexpr int NT = FOUT / 32;
     constexpr int JG = NT > 2 ? 2 : NT;              // column tiles accumulated at a time
     constexpr int KH = FIN / 2;
@@ -304,7 +304,7 @@ __global__ __launch_bounds__(kThreads) void xw_bf16_staged_kernel(const uint16_t
     const int tid = threadIdx.x;
     for (int idx = tid; idx < FIN * FOUT; idx += kThreads) {
         const int k = idx / FOUT, j = idx % FOUT;
-        s_wt[j * LDW + k] = w[idx];
+        s_wt[j * LDW + k] = w[wt ? j * FIN + k : idx];
     }
     const int lane = tid & (kWave - 1), wave = tid / kWave;
     const int i = lane & 31, hh = lane >> 5;
@@ -397,47 +397,49 @@ int64_t resident_blocks(K kernel) {
 }
 
 template <int FIN, int FOUT>
-int launch(const void *x, const void *w, const float *row_scale, void *h, int64_t n, dgnn_dtype dt, hipStream_t s) {
+int launch(const void *x, const void *w, int wt, const float *row_scale, void *h, int64_t n, dgnn_dtype dt, hipStream_t s) {
     const int64_t n_tiles = (n + 31) / 32;
     const int64_t needed = (n_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
     auto grid = [&](auto kernel) { return dim3((unsigned)std::min(needed, resident_blocks(kernel))); };
     if (dt == DGNN_F32) {
         if constexpr (FIN <= 64 && FOUT <= 64 && FOUT % 32 == 0)   // both tiles and W fit in LDS
             hipLaunchKernelGGL((xw_f32_staged_kernel<FIN, FOUT>), grid(xw_f32_staged_kernel<FIN, FOUT>), dim3(kThreads), 0, s,
-                               static_cast<const float *>(x), static_cast<const float *>(w), row_scale, static_cast<float *>(h), n, n_tiles);
+                               static_cast<const float *>(x), static_cast<const float *>(w), row_scale, static_cast<float *>(h), n, n_tiles, wt);
         else
             hipLaunchKernelGGL((xw_f32_kernel<FIN, FOUT>), grid(xw_f32_kernel<FIN, FOUT>), dim3(kThreads), 0, s,
-                               static_cast<const float *>(x), static_cast<const float *>(w), row_scale, static_cast<float *>(h), n, n_tiles);
+                               static_cast<const float *>(x), static_cast<const float *>(w), row_scale, static_cast<float *>(h), n, n_tiles, wt);
     } else {
         if constexpr (FIN % 32 == 0 && FOUT % 32 == 0)
             hipLaunchKernelGGL((xw_bf16_staged_kernel<FIN, FOUT>), grid(xw_bf16_staged_kernel<FIN, FOUT>), dim3(kThreads), 0, s,
                                static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(w), row_scale,
-                               static_cast<uint16_t *>(h), n, n_tiles);
+                               static_cast<uint16_t *>(h), n, n_tiles, wt);
         else
             hipLaunchKernelGGL((xw_bf16_kernel<FIN, FOUT>), grid(xw_bf16_kernel<FIN, FOUT>), dim3(kThreads), 0, s,
                                static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(w), row_scale,
-                               static_cast<uint16_t *>(h), n, n_tiles);
+                               static_cast<uint16_t *>(h), n, n_tiles, wt);
     }
     DGNN_RETURN_IF_LAUNCH_FAILED();
     return DGNN_OK;
 }
 
 template <int FIN>
-int launch_out(int32_t f_out, const void *x, const void *w, const float *row_scale, void *h, int64_t n, dgnn_dtype dt,
-               hipStream_t s) {
+int launch_out(int32_t f_out, const void *x, const void *w, int wt, const float *row_scale, void *h, int64_t n,
+               dgnn_dtype dt, hipStream_t s) {
     switch (f_out) {
-        case 16: return launch<FIN, 16>(x, w, row_scale, h, n, dt, s);
-        case 32: return launch<FIN, 32>(x, w, row_scale, h, n, dt, s);
-        case 64: return launch<FIN, 64>(x, w, row_scale, h, n, dt, s);
-        case 128: return launch<FIN, 128>(x, w, row_scale, h, n, dt, s);
+        case 16: return launch<FIN, 16>(x, w, wt, row_scale, h, n, dt, s);
+        case 32: return launch<FIN, 32>(x, w, wt, row_scale, h, n, dt, s);
+        case 64: return launch<FIN, 64>(x, w, wt, row_scale, h, n, dt, s);
+        case 128: return launch<FIN, 128>(x, w, wt, row_scale, h, n, dt, s);
         default: return DGNN_ERR_SHAPE;
     }
 }
 
 }  // namespace
 
-extern "C" int dgnn_feature_transform(const void *x, int64_t n, int32_t f_in, const void *w, int32_t f_out,
-                                      const float *row_scale, void *h, dgnn_dtype dt, void *stream) {
+namespace {
+
+int transform(const void *x, int64_t n, int32_t f_in, const void *w, int wt, int32_t f_out, const float *row_scale,
+              void *h, dgnn_dtype dt, void *stream) {
     if (!x || !w || !h) return DGNN_ERR_NULL;
     if (n <= 0 || !supported_width(f_in) || !supported_width(f_out)) return DGNN_ERR_SHAPE;
     if (dt != DGNN_F32 && dt != DGNN_BF16) return DGNN_ERR_SHAPE;
@@ -446,10 +448,24 @@ extern "C" int dgnn_feature_transform(const void *x, int64_t n, int32_t f_in, co
     if (x == h) return DGNN_ERR_ALIAS;
     hipStream_t s = (hipStream_t)stream;
     switch (f_in) {
-        case 16: return launch_out<16>(f_out, x, w, row_scale, h, n, dt, s);
-        case 32: return launch_out<32>(f_out, x, w, row_scale, h, n, dt, s);
-        case 64: return launch_out<64>(f_out, x, w, row_scale, h, n, dt, s);
-        case 128: return launch_out<128>(f_out, x, w, row_scale, h, n, dt, s);
+        case 16: return launch_out<16>(f_out, x, w, wt, row_scale, h, n, dt, s);
+        case 32: return launch_out<32>(f_out, x, w, wt, row_scale, h, n, dt, s);
+        case 64: return launch_out<64>(f_out, x, w, wt, row_scale, h, n, dt, s);
+        case 128: return launch_out<128>(f_out, x, w, wt, row_scale, h, n, dt, s);
         default: return DGNN_ERR_SHAPE;
     }
+}
+
+}  // namespace
+
+extern "C" int dgnn_feature_transform(const void *x, int64_t n, int32_t f_in, const void *w, int32_t f_out,
+                                      const float *row_scale, void *h, dgnn_dtype dt, void *stream) {
+    return transform(x, n, f_in, w, 0, f_out, row_scale, h, dt, stream);
+}
+
+// dX = G W^T: the same product with W read transposed while it is parked in LDS; the contraction runs over
+// the columns of W, so the kernel's inner width is f_out and its outer width f_in.
+extern "C" int dgnn_input_grad(const void *g, int64_t n, int32_t f_out, const void *w, int32_t f_in,
+                               const float *row_scale, void *dx, dgnn_dtype dt, void *stream) {
+    return transform(g, n, f_out, w, 1, f_in, row_scale, dx, dt, stream);
 }

@@ -128,3 +128,31 @@ def test_python_binding_rejects_wrong_dtypes():
     rp = torch.zeros(5, dtype=torch.int64)
     with pytest.raises(TypeError):
         dg.csr_dinv(rp, torch.zeros(4))
+
+
+def test_backward_argument_errors(lib):
+    out = ctypes.c_size_t(0)
+    assert lib.dgnn_weight_grad_workspace(32, 64, ctypes.byref(out)) == 0 and out.value >= 32 * 64 * 4
+    assert lib.dgnn_weight_grad_workspace(32, 64, None) == -1
+    assert lib.dgnn_weight_grad_workspace(32, 48, ctypes.byref(out)) == -2
+    big = 1 << 30
+    f = lib.dgnn_weight_grad
+    assert f(None, FAKE, 10, 32, 32, FAKE, 0, 0, FAKE, big, None) == -1
+    assert f(FAKE, FAKE, 10, 32, 32, None, 0, 0, FAKE, big, None) == -1
+    assert f(FAKE, FAKE, 0, 32, 32, FAKE, 0, 0, FAKE, big, None) == -2
+    assert f(FAKE, FAKE, 10, 32, 20, FAKE, 0, 0, FAKE, big, None) == -2
+    assert f(FAKE, FAKE, 10, 32, 32, FAKE, 0, 0, FAKE, 1024, None) == -3
+    assert f(FAKE + 2, FAKE, 10, 32, 32, FAKE, 0, 0, FAKE, big, None) == -7
+    f = lib.dgnn_relu_backward
+    assert f(FAKE, None, None, FAKE, 10, 32, 0, None) == -1
+    assert f(FAKE, FAKE, None, FAKE, 10, 33, 0, None) == -2
+    assert f(FAKE, FAKE, None, FAKE, 10, 32, 5, None) == -2
+    assert f(FAKE, FAKE + 8, None, FAKE, 10, 32, 0, None) == -7
+    f = lib.dgnn_input_grad
+    assert f(None, 10, 32, FAKE, 32, None, FAKE + 4096, 0, None) == -1
+    assert f(FAKE, 10, 32, FAKE, 48, None, FAKE + 4096, 0, None) == -2
+    assert f(FAKE, 10, 32, FAKE + 64, 32, None, FAKE, 0, None) == -5
+    f = lib.dgnn_mproduct_backward
+    assert f(None, FAKE, 8, 10, 16, 3, None, 0, None) == -1
+    assert f(FAKE, FAKE, 8, 10, 16, 0, None, 0, None) == -2
+    assert f(FAKE, FAKE + 16, 8, 10, 16, 3, None, 0, None) == -5
