@@ -29,7 +29,7 @@ import torch
 
 __all__ = [
     "Workload", "WORKLOADS", "DynamicGraph", "mix64", "rand_bits", "rand_below",
-    "stream_base", "features", "glorot_weight", "keys_to_coo", "keys_to_csr",
+    "stream_base", "features", "glorot_weight", "keys_to_coo", "keys_to_csr", "transpose_coo", "gradient",
 ]
 
 _M64 = (1 << 64) - 1
@@ -88,7 +88,7 @@ def rand_below(base: int, idx: torch.Tensor, m: int) -> torch.Tensor:
 
 
 # purposes of the random streams
-_P_ER, _P_RMAT, _P_PERM, _P_DEL, _P_ADD_U, _P_ADD_V, _P_FEAT, _P_W = range(1, 9)
+_P_ER, _P_RMAT, _P_PERM, _P_DEL, _P_ADD_U, _P_ADD_V, _P_FEAT, _P_W, _P_GRAD = range(1, 10)
 
 
 @dataclass(frozen=True)
@@ -153,6 +153,14 @@ def _member(sorted_keys: torch.Tensor, q: torch.Tensor) -> torch.Tensor:
 def keys_to_coo(keys: torch.Tensor) -> Tuple[torch.Tensor, torch.Tensor]:
     """64-bit keys (row << 32 | col) -> int32 row, int32 col."""
     return (keys >> 32).to(torch.int32), (keys & MASK32).to(torch.int32)
+
+
+def transpose_coo(row: torch.Tensor, col: torch.Tensor) -> Tuple[torch.Tensor, torch.Tensor]:
+    """The same entries with rows and columns exchanged, sorted by their new (row, col): the form in which
+    a difference list (or a snapshot) of the transposed dynamic graph is handed over.  Input formatting
+    only."""
+    keys = torch.sort((col.to(torch.int64) << 32) | row.to(torch.int64)).values
+    return keys_to_coo(keys)
 
 
 def keys_to_csr(keys: torch.Tensor, n: int) -> Tuple[torch.Tensor, torch.Tensor]:
@@ -359,6 +367,17 @@ def features(wl: Workload, t: int, device="cpu", chunk_rows: int = 1 << 20) -> t
     """Frame X_t, N x F, entries N(0,1); float32, or rounded to bfloat16 for bf16 workloads."""
     out = torch.empty((wl.n, wl.f), dtype=torch.float32, device=device)
     base = stream_base(wl.seed, _P_FEAT, t, 0)
+    for r0 in range(0, wl.n, chunk_rows):
+        r1 = min(wl.n, r0 + chunk_rows)
+        out[r0:r1] = _normal(base, r0 * wl.f, (r1 - r0) * wl.f, device).view(r1 - r0, wl.f)
+    return out.to(torch.bfloat16) if wl.dtype == "bf16" else out
+
+
+def gradient(wl: Workload, t: int, device="cpu", chunk_rows: int = 1 << 20) -> torch.Tensor:
+    """Frame t of a stand-in upstream gradient dL/dY, N x F, entries N(0,1) (what a loss layer above the
+    block would send down); float32, or rounded to bfloat16 for bf16 workloads."""
+    out = torch.empty((wl.n, wl.f), dtype=torch.float32, device=device)
+    base = stream_base(wl.seed, _P_GRAD, t, 0)
     for r0 in range(0, wl.n, chunk_rows):
         r1 = min(wl.n, r0 + chunk_rows)
         out[r0:r1] = _normal(base, r0 * wl.f, (r1 - r0) * wl.f, device).view(r1 - r0, wl.f)

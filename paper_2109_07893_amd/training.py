@@ -1,0 +1,170 @@
+"""Caller-side plumbing for a training step over one GPU's block of timesteps (Section "Gradient
+Checkpoint": a block is run forward, keeping its activations, and gradients then travel through it in
+the reverse direction).  Like pipeline.py this owns buffers and the order of library calls only:
+
+    forward    t = 1..T:   A_t by dgnn_delta_rebuild (t >= 2), per layer H = X W, Z = relu(A~_t H) -- every
+                           Z is kept; then Y = Z x_1 M
+    backward   G = G_Y x_1 M^T (dgnn_mproduct_backward), then t = T..1:
+                   per layer, last to first:   G_P = dinv * (Z > 0 ? G : 0)      dgnn_relu_backward
+                                               G_H = A~_t^T G_P                  dgnn_spmm on the transposed snapshot
+                                               dW += X^T G_H                     dgnn_weight_grad
+                                               G   = G_H W^T  (if a layer lies below)   dgnn_input_grad
+                   A_{t-1} from A_t by dgnn_delta_rebuild with the added and deleted lists exchanged
+
+For a directed workload the transposed snapshots are a second dynamic graph, rebuilt the same way from the
+difference lists sorted by (col, row).  Nothing here computes: every step runs in the HIP kernels.
+"""
+from __future__ import annotations
+
+from typing import List, Optional, Tuple
+
+import torch
+
+from . import binding as B
+from .pipeline import BlockInputs, BlockRunner
+
+
+class _Chain:
+    """Two alternating CSR slots plus a kept first snapshot, walked forwards or backwards by rebuilds."""
+
+    def __init__(self, n, cap, dev, rowptr1, colidx1, with_dinv: bool):
+        self.rowptr = [torch.empty(n + 1, dtype=torch.int32, device=dev) for _ in range(3)]
+        self.colidx = [torch.empty(cap, dtype=torch.int32, device=dev) for _ in range(3)]
+        self.dinv = [torch.empty(n, dtype=torch.float32, device=dev) if with_dinv else None for _ in range(3)]
+        self.rowptr[2].copy_(rowptr1)
+        self.colidx[2][: colidx1.numel()].copy_(colidx1)
+        if with_dinv:
+            B.csr_dinv(self.rowptr[2], self.dinv[2])
+
+    @staticmethod
+    def slot_of(t: int) -> int:
+        return 2 if t == 1 else t % 2
+
+
+class BlockTrainer:
+    """Forward and backward over one block; gradients of the layer weights (fp32) come out in `dw`."""
+
+    def __init__(self, blk: BlockInputs, directed: bool,
+                 transposed_first: Optional[Tuple[torch.Tensor, torch.Tensor]] = None,
+                 transposed_deltas: Optional[List[Tuple[torch.Tensor, ...]]] = None, want_dx: bool = False):
+        self.blk = blk
+        dev = blk.rowptr1.device
+        self.dev = dev
+        n, f, T, L = blk.n, blk.f, blk.T, blk.layers
+        dt = blk.x[0].dtype
+        cap = max(blk.nnz)
+        self.directed = directed
+        self.a = _Chain(n, cap, dev, blk.rowptr1, blk.colidx1, with_dinv=True)
+        self.at = None
+        if directed:
+            assert transposed_first is not None and transposed_deltas is not None
+            self.at = _Chain(n, cap, dev, transposed_first[0], transposed_first[1], with_dinv=False)
+            self.t_deltas = transposed_deltas
+        self.z = torch.empty((L, T, n, f), dtype=dt, device=dev)          # activations of the block
+        self.y = torch.empty((T, n, f), dtype=dt, device=dev) if blk.window else None
+        self.g = torch.empty((T, n, f), dtype=dt, device=dev)             # dL/dZ of the last layer, per frame
+        self.h = torch.empty((n, f), dtype=dt, device=dev)                # H going forward, G_H going back
+        self.gp = torch.empty((n, f), dtype=dt, device=dev)
+        self.g_mid = torch.empty((n, f), dtype=dt, device=dev) if L > 1 else None
+        self.dx = torch.empty((T, n, f), dtype=dt, device=dev) if want_dx else None
+        self.dw = [torch.zeros((f, f), dtype=torch.float32, device=dev) for _ in range(L)]
+        max_list = max([int(d[0].numel()) for d in blk.deltas] + [int(d[2].numel()) for d in blk.deltas] + [1])
+        self.ws_rebuild = torch.empty(B.delta_rebuild_workspace(n, cap, max_list, max_list), dtype=torch.uint8, device=dev)
+        self.ws_spmm = torch.empty(B.spmm_workspace(n, cap, f), dtype=torch.uint8, device=dev)
+        self.ws_wgrad = torch.empty(B.weight_grad_workspace(f, f), dtype=torch.uint8, device=dev)
+        self.timer = None
+
+    def _stage(self, name):
+        import contextlib
+        return self.timer.stage(name) if self.timer is not None else contextlib.nullcontext()
+
+    def _rebuild(self, chain: _Chain, lists, nnz_src: int, src_t: int, dst_t: int, reverse: bool) -> None:
+        ar, ac, dr, dc = lists
+        if reverse:
+            ar, ac, dr, dc = dr, dc, ar, ac
+        s, d = chain.slot_of(src_t), chain.slot_of(dst_t)
+        with self._stage("delta_rebuild"):
+            B.delta_rebuild(chain.rowptr[s], chain.colidx[s], nnz_src, ar, ac, int(ar.numel()), dr, dc, int(dr.numel()),
+                            chain.rowptr[d], chain.colidx[d], chain.dinv[d], self.ws_rebuild)
+
+    # ------------------------------------------------------------------ forward, keeping activations
+    def forward(self) -> torch.Tensor:
+        blk = self.blk
+        for t in range(1, blk.T + 1):
+            if t >= 2:
+                self._rebuild(self.a, blk.deltas[t - 2], blk.nnz[t - 2], t - 1, t, reverse=False)
+                if self.directed:
+                    self._rebuild(self.at, self.t_deltas[t - 2], blk.nnz[t - 2], t - 1, t, reverse=False)
+            slot = self.a.slot_of(t)
+            cur = blk.x[t - 1]
+            for layer in range(blk.layers):
+                with self._stage("feature_transform"):
+                    B.feature_transform(cur, blk.w[layer], self.h, row_scale=self.a.dinv[slot])
+                with self._stage("spmm"):
+                    B.spmm(self.a.rowptr[slot], self.a.colidx[slot], blk.nnz[t - 1], self.a.dinv[slot], self.h,
+                           self.z[layer, t - 1], self.ws_spmm, flags=B.DGNN_RELU | B.DGNN_H_PRESCALED)
+                cur = self.z[layer, t - 1]
+        if blk.window:
+            with self._stage("mproduct"):
+                B.mproduct(self.z[blk.layers - 1], self.y, blk.window)
+            return self.y
+        return self.z[blk.layers - 1]
+
+    # ------------------------------------------------------------------ backward
+    def backward(self, g_y: torch.Tensor) -> None:
+        """g_y [T, n, f] = dL/dY.  Must follow forward() (A_T and, if directed, A_T^T are resident)."""
+        blk = self.blk
+        L, T = blk.layers, blk.T
+        if blk.window:
+            with self._stage("mproduct_backward"):
+                B.mproduct_backward(g_y, self.g, blk.window)
+            g_top = self.g
+        else:
+            g_top = g_y
+        first_call = [True] * L
+        for t in range(T, 0, -1):
+            slot = self.a.slot_of(t)
+            tc = self.at if self.directed else self.a           # the chain that holds (A_t + I)^T
+            dinv = self.a.dinv[slot]
+            g_in = g_top[t - 1]
+            for layer in range(L - 1, -1, -1):
+                with self._stage("relu_backward"):
+                    B.relu_backward(g_in, self.z[layer, t - 1], self.gp, row_scale=dinv)
+                with self._stage("spmm_transposed"):
+                    B.spmm(tc.rowptr[slot], tc.colidx[slot], blk.nnz[t - 1], dinv, self.gp, self.h, self.ws_spmm,
+                           flags=B.DGNN_H_PRESCALED)
+                below = blk.x[t - 1] if layer == 0 else self.z[layer - 1, t - 1]
+                with self._stage("weight_grad"):
+                    B.weight_grad(below, self.h, self.dw[layer], self.ws_wgrad, accumulate=not first_call[layer])
+                first_call[layer] = False
+                if layer > 0:
+                    with self._stage("input_grad"):
+                        B.input_grad(self.h, blk.w[layer], self.g_mid)
+                    g_in = self.g_mid
+                elif self.dx is not None:
+                    with self._stage("input_grad"):
+                        B.input_grad(self.h, blk.w[0], self.dx[t - 1])
+            if t >= 3:   # A_{t-1} from A_t: the same rebuild with the two lists exchanged (A_1 was kept)
+                self._rebuild(self.a, blk.deltas[t - 2], blk.nnz[t - 1], t, t - 1, reverse=True)
+                if self.directed:
+                    self._rebuild(self.at, self.t_deltas[t - 2], blk.nnz[t - 1], t, t - 1, reverse=True)
+
+
+def make_trainer(wl, blk: BlockInputs, want_dx: bool = False) -> BlockTrainer:
+    """Trainer for a generated block; for a directed workload the transposed first snapshot and lists are
+    prepared here with the generator's formatting helper."""
+    from dtdg_synth import transpose_coo
+    directed = wl.graph != "er"
+    if not directed:
+        return BlockTrainer(blk, False, want_dx=want_dx)
+    n = blk.n
+    rows = torch.repeat_interleave(torch.arange(n, dtype=torch.int32, device=blk.rowptr1.device),
+                                   (blk.rowptr1[1:] - blk.rowptr1[:-1]).to(torch.int64))
+    tr, tc = transpose_coo(rows, blk.colidx1)
+    counts = torch.bincount(tr.to(torch.int64), minlength=n)
+    rowptr_t = torch.zeros(n + 1, dtype=torch.int32, device=tr.device)
+    rowptr_t[1:] = torch.cumsum(counts, 0).to(torch.int32)
+    t_deltas = []
+    for ar, ac, dr, dc in blk.deltas:
+        t_deltas.append(transpose_coo(ar, ac) + transpose_coo(dr, dc))
+    return BlockTrainer(blk, True, transposed_first=(rowptr_t, tc), transposed_deltas=t_deltas, want_dx=want_dx)

@@ -1,0 +1,116 @@
+"""GPU parity of a whole training step over a block (forward keeping activations, then gradient
+propagation in the reverse direction, Section "Gradient Checkpoint") against the CPU oracle: weight
+gradients of every layer, the input gradient, and the snapshots met on the way back."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2109_07893_amd as dg
+from dtdg_synth import WORKLOADS, DynamicGraph, features, glorot_weight, gradient
+from helpers import assert_close, to_f64
+from paper_2109_07893_amd.pipeline import make_block
+from paper_2109_07893_amd.training import make_trainer
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+CASES = {
+    "undirected_1layer_window": WORKLOADS["c1"],
+    "undirected_2layers_window": replace(WORKLOADS["c1"], layers=2, f=32, name="c1-2l"),
+    "directed_1layer": WORKLOADS["c3"].scaled(4096, T=5),
+    "directed_2layers_window": replace(WORKLOADS["c3"].scaled(4096, T=6), layers=2, window=3, name="c3-2l-w"),
+    "bf16_window": replace(WORKLOADS["c4"].scaled(3000, T=6), window=4, name="c4-small"),
+    "bf16_directed_2layers": replace(WORKLOADS["c3"].scaled(2048, T=4), layers=2, dtype="bf16", f=64, name="c3-bf16"),
+}
+
+
+def oracle_training_step(wl):
+    """Forward and backward of the block in float64; returns (dW per layer, dX per frame, Y, snapshots,
+    stored activations).  Which gradient elements the ReLU lets through is a yes/no decision taken on the
+    activations as they are STORED (float32 or bfloat16): the backward half therefore starts from the oracle's
+    activations rounded to the storage type, and the GPU is handed the same stored activations, so that both
+    sides take that decision on identical numbers."""
+    T, L = wl.T, wl.layers
+    store = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    g = DynamicGraph(wl)
+    rp, ci = (x.numpy() for x in g.csr())
+    ws = [to_f64(glorot_weight(wl, layer)) for layer in range(L)]
+    snaps, acts, xs = [], [], []
+    for t in range(1, T + 1):
+        if t > 1:
+            rp, ci = oracle.delta_apply(wl.n, rp, ci, *[x.numpy() for x in g.advance()])
+        snaps.append((rp, ci))
+        cur = to_f64(features(wl, t))
+        xs.append(cur)
+        layer_out = []
+        for layer in range(L):
+            cur = oracle.gcn_layer(rp, ci, cur, ws[layer], relu=True)
+            layer_out.append(cur)
+        acts.append(layer_out)
+    z_top = np.stack([a[-1] for a in acts])
+    stored = [[torch.from_numpy(a).to(store) for a in layer_out] for layer_out in acts]
+    g_y = np.stack([to_f64(gradient(wl, t)) for t in range(1, T + 1)])
+    if wl.window:
+        M = oracle.m_matrix(T, wl.window)
+        y = oracle.mproduct(z_top, M)
+        g_z = oracle.mproduct_t(g_y, M)
+    else:
+        y, g_z = z_top, g_y
+    dws = [np.zeros_like(w) for w in ws]
+    dxs = []
+    for t in range(T, 0, -1):
+        rp, ci = snaps[t - 1]
+        gin = g_z[t - 1]
+        for layer in range(L - 1, -1, -1):
+            below = xs[t - 1] if layer == 0 else to_f64(stored[t - 1][layer - 1])
+            dw, gin = oracle.gcn_layer_backward(rp, ci, below, ws[layer], to_f64(stored[t - 1][layer]), gin)
+            dws[layer] += dw
+        dxs.append(gin)
+    return dws, dxs[::-1], y, snaps, stored
+
+
+@pytest.mark.parametrize("case", sorted(CASES))
+def test_training_step_matches_oracle(case):
+    wl = CASES[case]
+    dtype = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    dws, dxs, y, snaps, stored = oracle_training_step(wl)
+    blk = make_block(wl, DEV, gen_device="cpu")
+    tr = make_trainer(wl, blk, want_dx=True)
+    out = tr.forward()
+    assert_close(to_f64(out), y, dtype, f"{case}: forward output")
+    for t in range(wl.T):                     # the stored activations the backward half starts from (see above)
+        for layer in range(wl.layers):
+            tr.z[layer, t].copy_(stored[t][layer])
+    g_y = torch.stack([gradient(wl, t) for t in range(1, wl.T + 1)]).to(DEV)
+    tr.backward(g_y)
+    torch.cuda.synchronize()
+    # after the walk back, the two alternating slots hold A_2 and A_3 again, bit for bit
+    for t in (2, 3):
+        if t <= wl.T:
+            slot = tr.a.slot_of(t)
+            rp, ci = snaps[t - 1]
+            assert np.array_equal(tr.a.rowptr[slot].cpu().numpy(), rp), (case, t)
+            assert np.array_equal(tr.a.colidx[slot][: ci.size].cpu().numpy(), ci), (case, t)
+    for layer in range(wl.layers):
+        assert_close(to_f64(tr.dw[layer]), dws[layer], dtype, f"{case}: dW of layer {layer}")
+    # dX has gone through three stored tensors per layer (masked gradient, aggregated gradient, input gradient)
+    for t in range(wl.T):
+        assert_close(to_f64(tr.dx[t]), dxs[t], dtype, f"{case}: dX of frame {t + 1}", stores=3 * wl.layers)
+
+
+def test_training_step_repeats_bit_for_bit():
+    wl = CASES["directed_2layers_window"]
+    blk = make_block(wl, DEV, gen_device="cpu")
+    g_y = torch.stack([gradient(wl, t) for t in range(1, wl.T + 1)]).to(DEV)
+    runs = []
+    for _ in range(2):
+        tr = make_trainer(wl, blk)
+        tr.forward()
+        tr.backward(g_y)
+        torch.cuda.synchronize()
+        runs.append([d.clone() for d in tr.dw])
+    for a, b in zip(*runs):
+        assert torch.equal(a, b)
