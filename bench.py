@@ -38,6 +38,7 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="stop the oracle sample after this much work")
     ap.add_argument("--pinned", action="store_true", help="also time the pass with difference lists in pinned host memory")
+    ap.add_argument("--no-train", action="store_true", help="skip the training-step (forward + backward) measurement")
     ap.add_argument("--natural-labels", action="store_true",
                     help="R-MAT workloads: keep the generator's vertex labels (locality) instead of scrambling them")
     return ap.parse_args()
@@ -54,8 +55,14 @@ def algorithmic_bytes(blk, stage, t=None):
         return 2 * s * n * f + s * f * f
     if stage == "spmm":            # lower bound: every row of H fetched once
         return 4 * blk.nnz[t - 1] + 8 * n + 2 * s * n * f
-    if stage == "mproduct":
+    if stage in ("mproduct", "mproduct_backward"):
         return 2 * s * n * f * blk.T
+    if stage == "spmm_transposed":
+        return 4 * blk.nnz[t - 1] + 8 * n + 2 * s * n * f
+    if stage == "relu_backward":   # gradient in, activation in, masked gradient out
+        return 3 * s * n * f + 4 * n
+    if stage in ("weight_grad", "input_grad"):
+        return 2 * s * n * f + s * f * f
     raise KeyError(stage)
 
 
@@ -99,6 +106,64 @@ def cpu_baseline(wl, blk, first, budget_s):
             "kind": "oracle", "seconds": round(spent, 3),
             "sample": f"timesteps t={done[0]}..{done[-1]} of the same block (rebuild + {len(ws)} GCN layer(s), "
                       f"no M-transform), full graph, {edges} edges"}
+
+
+def training_step(args, wl, blk, dev):
+    """Forward keeping activations plus backward over the same block (every snapshot t = 1..T); an extra
+    figure next to the headline, which stays the forward pass."""
+    import torch
+    from dtdg_synth import gradient
+    from paper_2109_07893_amd.pipeline import StageTimer
+    from paper_2109_07893_amd.training import make_trainer
+    # One checkpoint block: as many timesteps as leave room for the block's activations and gradients next to
+    # the inputs (four more tensors of T x N x F), at most the workload's T.
+    frame = blk.n * blk.f * blk.x[0].element_size()
+    free_bytes, _ = torch.cuda.mem_get_info(dev)
+    Tb = int(max(2, min(blk.T, (0.8 * free_bytes) // (4 * frame))))
+    if Tb < blk.T:
+        from paper_2109_07893_amd.pipeline import BlockInputs
+        blk = BlockInputs(n=blk.n, T=Tb, f=blk.f, layers=blk.layers, window=blk.window, rowptr1=blk.rowptr1,
+                          colidx1=blk.colidx1, deltas=blk.deltas[:Tb - 1], x=blk.x[:Tb], w=blk.w, nnz=blk.nnz[:Tb])
+    tr = make_trainer(wl, blk)
+    g_y = torch.empty((blk.T, blk.n, blk.f), dtype=blk.x[0].dtype, device=dev)
+    for t in range(1, blk.T + 1):
+        g_y[t - 1].copy_(gradient(wl, t, device=dev))
+    torch.cuda.synchronize()
+
+    def one_step():
+        tr.forward()
+        tr.backward(g_y)
+
+    for _ in range(max(1, args.warmup - 1)):
+        one_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    tr.timer = StageTimer(dev)
+    one_step()
+    torch.cuda.synchronize()
+    stages = {}
+    for name, (calls, total_ms) in tr.timer.totals().items():
+        if name in ("mproduct", "mproduct_backward"):
+            byts = algorithmic_bytes(blk, name)
+        elif name == "delta_rebuild":
+            byts = None
+        else:
+            byts = sum(algorithmic_bytes(blk, "spmm" if name == "spmm" else name, t) for t in range(1, blk.T + 1)) \
+                   * blk.layers / calls if name != "input_grad" else algorithmic_bytes(blk, name, 1)
+        entry = {"calls_per_step": calls, "avg_ms": round(total_ms / calls, 4), "ms_per_step": round(total_ms, 4)}
+        if byts:
+            entry["algorithmic_bytes_per_call"] = int(byts)
+            entry["algorithmic_GBps"] = round(byts / (total_ms / calls * 1e-3) / 1e9, 1)
+        stages[name] = entry
+    edges = sum(blk.nnz)
+    return {"ms_per_step": ms, "value": edges / (ms * 1e-3), "unit": "edges/s",
+            "what": f"forward keeping activations + backward over t=1..{blk.T} ({'directed: second chain of transposed snapshots' if tr.directed else 'undirected: the snapshot is its own transpose'}); "
+                    "weight gradients of every layer, reverse rebuilds with exchanged lists",
+            "edges_per_step": edges, "stages": stages}
 
 
 def main():
@@ -214,6 +279,11 @@ def main():
         out["pinned_host_lists"] = {"value": edges_per_step / (el / args.steps), "unit": "edges/s",
                                     "ms_per_step": el / args.steps * 1e3, "h2d_bytes_per_step": h2d,
                                     "whole_snapshot_bytes_per_step": sum(4 * (z + blk.n + 1) for z in blk.nnz[1:])}
+
+    if not args.no_train:
+        del runner
+        torch.cuda.empty_cache()
+        out["training_step"] = training_step(args, wl, blk, dev)
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, blk, first, args.cpu_seconds)

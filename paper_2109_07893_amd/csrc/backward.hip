@@ -32,7 +32,7 @@ typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
 constexpr int kThreads = 256;
 constexpr int kWavesPerBlock = kThreads / kWave;
 constexpr int kStepRows = 16;        // rows per step: eight fp32 MFMAs of depth 2, or one bf16 MFMA of depth 16
-constexpr int kMaxBlocks = 1024;     // bounds the workspace
+constexpr int kMaxBlocks = 512;      // two workgroups per compute unit keep enough loads in flight; bounds the workspace
 
 // How the 32x32 tiles of the F x F' accumulator are shared out inside a workgroup: a wavefront holds
 // TI x TJ tiles (at most four), GROUPS wavefronts cover all tiles, and the remaining factor of the four
@@ -100,6 +100,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const void *__restrict_
             for (int tj = 0; tj < S::TJ; ++tj) gb[tj][e] = (row_ok && (jt0 + tj) * 32 + i < FOUT) ? gb_next[tj][e] : Raw(0);
         }
         fetch(std::min(step + workers, n_steps - 1));      // the next step's rows travel while this one is multiplied
+        __builtin_amdgcn_sched_barrier(0);                  // ... so the loads must stay ahead of the multiplications
         if constexpr (BF16) {
             bf16x8 a[S::TI], b[S::TJ];
 #pragma unroll
@@ -144,14 +145,16 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const void *__restrict_
             }
 }
 
-// dw[e] = (accumulate ? dw[e] : 0) + sum over the workers' partial results, in worker order within four
-// slices and then across the slices: a fixed order.
-__global__ __launch_bounds__(kThreads) void wgrad_reduce_kernel(const float *__restrict__ partial, int workers, int elems,
-                                                                float *__restrict__ dw, int accumulate) {
-    __shared__ float s_sum[kWavesPerBlock][kWave];
+// dw[e] = (accumulate ? dw[e] : 0) + sum over the workers' partial results: sixteen wavefronts take a slice of
+// the workers each (in worker order), then the sixteen slice sums are added in slice order: a fixed order.
+constexpr int kReduceSlices = 16;
+__global__ __launch_bounds__(kReduceSlices *kWave) void wgrad_reduce_kernel(const float *__restrict__ partial, int workers,
+                                                                            int elems, float *__restrict__ dw,
+                                                                            int accumulate) {
+    __shared__ float s_sum[kReduceSlices][kWave];
     const int lane = threadIdx.x & (kWave - 1), slice = threadIdx.x / kWave;
     const int e = blockIdx.x * kWave + lane;
-    const int per = (workers + kWavesPerBlock - 1) / kWavesPerBlock;
+    const int per = (workers + kReduceSlices - 1) / kReduceSlices;
     const int p0 = slice * per, p1 = min(p0 + per, workers);
     float sum = 0.0f;
     if (e < elems) {
@@ -161,7 +164,9 @@ __global__ __launch_bounds__(kThreads) void wgrad_reduce_kernel(const float *__r
     s_sum[slice][lane] = sum;
     __syncthreads();
     if (slice == 0 && e < elems) {
-        const float total = ((s_sum[0][lane] + s_sum[1][lane]) + s_sum[2][lane]) + s_sum[3][lane];
+        float total = s_sum[0][lane];
+#pragma unroll
+        for (int k = 1; k < kReduceSlices; ++k) total += s_sum[k][lane];
         dw[e] = accumulate ? dw[e] + total : total;
     }
 }
@@ -220,7 +225,7 @@ int launch_wgrad(const void *x, const void *g, int64_t n, float *dw, int accumul
     hipLaunchKernelGGL((wgrad_kernel<FIN, FOUT, BF16>), dim3((unsigned)blocks), dim3(kThreads), 0, s, x, g, n, n_steps, partial);
     DGNN_RETURN_IF_LAUNCH_FAILED();
     constexpr int elems = FIN * FOUT;
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((elems + kWave - 1) / kWave), dim3(kThreads), 0, s, partial,
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((elems + kWave - 1) / kWave), dim3(kReduceSlices * kWave), 0, s, partial,
                        (int)(blocks * S::RS), elems, dw, accumulate);
     DGNN_RETURN_IF_LAUNCH_FAILED();
     return DGNN_OK;

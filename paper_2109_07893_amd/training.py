@@ -62,7 +62,7 @@ class BlockTrainer:
             self.t_deltas = transposed_deltas
         self.z = torch.empty((L, T, n, f), dtype=dt, device=dev)          # activations of the block
         self.y = torch.empty((T, n, f), dtype=dt, device=dev) if blk.window else None
-        self.g = torch.empty((T, n, f), dtype=dt, device=dev)             # dL/dZ of the last layer, per frame
+        self.g = None                                                     # dL/dZ of the last layer, if g_y must be kept
         self.h = torch.empty((n, f), dtype=dt, device=dev)                # H going forward, G_H going back
         self.gp = torch.empty((n, f), dtype=dt, device=dev)
         self.g_mid = torch.empty((n, f), dtype=dt, device=dev) if L > 1 else None
@@ -111,14 +111,20 @@ class BlockTrainer:
         return self.z[blk.layers - 1]
 
     # ------------------------------------------------------------------ backward
-    def backward(self, g_y: torch.Tensor) -> None:
-        """g_y [T, n, f] = dL/dY.  Must follow forward() (A_T and, if directed, A_T^T are resident)."""
+    def backward(self, g_y: torch.Tensor, overwrite: bool = False) -> None:
+        """g_y [T, n, f] = dL/dY.  Must follow forward() (A_T and, if directed, A_T^T are resident).
+        With overwrite the adjoint of the M-transform is taken in place, on g_y itself."""
         blk = self.blk
         L, T = blk.layers, blk.T
         if blk.window:
+            if overwrite:
+                g_top = g_y
+            else:
+                if self.g is None:
+                    self.g = torch.empty_like(g_y)
+                g_top = self.g
             with self._stage("mproduct_backward"):
-                B.mproduct_backward(g_y, self.g, blk.window)
-            g_top = self.g
+                B.mproduct_backward(g_y, g_top, blk.window)
         else:
             g_top = g_y
         first_call = [True] * L
