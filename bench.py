@@ -27,6 +27,11 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 
 
+def progress(msg):
+    """One line per finished step on stderr, so that a long run is never silent."""
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -125,6 +130,7 @@ def training_step(args, wl, blk, dev):
         blk = BlockInputs(n=blk.n, T=Tb, f=blk.f, layers=blk.layers, window=blk.window, rowptr1=blk.rowptr1,
                           colidx1=blk.colidx1, deltas=blk.deltas[:Tb - 1], x=blk.x[:Tb], w=blk.w, nnz=blk.nnz[:Tb])
     tr = make_trainer(wl, blk)
+    progress(f"trainer ready (block of {blk.T} timesteps)")
     g_y = torch.empty((blk.T, blk.n, blk.f), dtype=blk.x[0].dtype, device=dev)
     for t in range(1, blk.T + 1):
         g_y[t - 1].copy_(gradient(wl, t, device=dev))
@@ -142,6 +148,7 @@ def training_step(args, wl, blk, dev):
         one_step()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) / args.steps * 1e3
+    progress(f"training step timed: {ms:.2f} ms per step")
     tr.timer = StageTimer(dev)
     one_step()
     torch.cuda.synchronize()
@@ -192,6 +199,7 @@ def main():
     blk = make_block(wl, dev, gen_device=dev, pinned=args.pinned, T=T)
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
+    progress(f"inputs of {wl.name} generated in {t_gen:.1f} s")
 
     runner = BlockRunner(blk)
     runner.load_first()
@@ -213,6 +221,7 @@ def main():
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
     value = edges_per_step / (elapsed / args.steps)
+    progress(f"forward timed: {ms_per_step:.2f} ms per step")
 
     # per-stage durations: the same steps again with an event pair around every library call
     runner.timer = StageTimer(dev)
@@ -280,12 +289,14 @@ def main():
                                     "ms_per_step": el / args.steps * 1e3, "h2d_bytes_per_step": h2d,
                                     "whole_snapshot_bytes_per_step": sum(4 * (z + blk.n + 1) for z in blk.nnz[1:])}
 
+    progress("per-stage pass done")
     if not args.no_train:
         del runner
         torch.cuda.empty_cache()
         out["training_step"] = training_step(args, wl, blk, dev)
 
     if not args.no_cpu_baseline:
+        progress("timing the CPU oracle")
         out["cpu_baseline"] = cpu_baseline(wl, blk, first, args.cpu_seconds)
     print(json.dumps(out))
 
