@@ -195,6 +195,33 @@ int dgnn_mproduct_backward(const void *g_y, void *g_z, int64_t T, int64_t n, int
                            const float *m_band, dgnn_dtype dt, void *stream);
 
 /*
+ * The M-transform of a series that is processed in blocks of timesteps (Section "Gradient Checkpoint": the
+ * frames of the last w timesteps of a block are among what is handed to the next block).  The block holds the
+ * frames of timesteps t0+1 .. t0+T (1-based) of the whole series; the weights are those of the whole series,
+ * 1/min(w, t) with t counted from the start of the series.
+ *   z_before [n_before][n][f]   the frames of timesteps t0-n_before+1 .. t0, oldest first;
+ *                               n_before must be min(w-1, t0) (NULL when that is 0)
+ *   m_band [T][w]               optional, the block's rows of the band
+ * Everything else as dgnn_mproduct; y must not overlap z_before.  Blocks chained this way give exactly the
+ * frames dgnn_mproduct gives on the whole series.
+ */
+int dgnn_mproduct_block(const void *z, void *y, int64_t T, int64_t n, int32_t f, int32_t w,
+                        const float *m_band, int64_t t0, const void *z_before, int64_t n_before,
+                        dgnn_dtype dt, void *stream);
+
+/*
+ * Its adjoint, block by block from the last block to the first: the gradient frames of a block depend on the
+ * upstream gradient of up to w-1 timesteps AFTER the block.
+ *   g_after [n_after][n][f]     upstream gradient frames of timesteps t0+T+1 .. t0+T+n_after, nearest first
+ *                               (in time order); n_after = min(w-1, timesteps after the block)
+ *   m_band [T + n_after][w]     optional, the rows of the band for the block and for the frames after it
+ * Everything else as dgnn_mproduct_backward; g_z must not overlap g_after.
+ */
+int dgnn_mproduct_backward_block(const void *g_y, void *g_z, int64_t T, int64_t n, int32_t f, int32_t w,
+                                 const float *m_band, int64_t t0, const void *g_after, int64_t n_after,
+                                 dgnn_dtype dt, void *stream);
+
+/*
  * Gradient through sigma = ReLU of Eqn (2): out[u][:] = row_scale[u] * (z[u][:] > 0 ? g[u][:] : 0).
  *   g, z, out [n][f]        storage type dt; z is the layer's OUTPUT (positive exactly where the
  *                           pre-activation was); out may be the same pointer as g

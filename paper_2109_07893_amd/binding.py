@@ -24,7 +24,7 @@ DGNN_H_PRESCALED = 2
 EXPORTS = (
     "dgnn_strerror", "dgnn_csr_dinv", "dgnn_delta_h2d", "dgnn_delta_rebuild_workspace",
     "dgnn_delta_rebuild", "dgnn_feature_transform", "dgnn_spmm_workspace", "dgnn_spmm", "dgnn_mproduct",
-    "dgnn_mproduct_backward", "dgnn_relu_backward", "dgnn_weight_grad_workspace", "dgnn_weight_grad", "dgnn_input_grad",
+    "dgnn_mproduct_backward", "dgnn_mproduct_block", "dgnn_mproduct_backward_block", "dgnn_relu_backward", "dgnn_weight_grad_workspace", "dgnn_weight_grad", "dgnn_input_grad",
 )
 
 
@@ -79,6 +79,8 @@ def load_library():
     lib.dgnn_spmm.argtypes = [_i64, _i64, _vp, _vp, _vp, _vp, _i32, _vp, ctypes.c_int, _u32, _vp, _sz, _vp]
     lib.dgnn_mproduct.argtypes = [_vp, _vp, _i64, _i64, _i32, _i32, _vp, ctypes.c_int, _vp]
     lib.dgnn_mproduct_backward.argtypes = [_vp, _vp, _i64, _i64, _i32, _i32, _vp, ctypes.c_int, _vp]
+    lib.dgnn_mproduct_block.argtypes = [_vp, _vp, _i64, _i64, _i32, _i32, _vp, _i64, _vp, _i64, ctypes.c_int, _vp]
+    lib.dgnn_mproduct_backward_block.argtypes = [_vp, _vp, _i64, _i64, _i32, _i32, _vp, _i64, _vp, _i64, ctypes.c_int, _vp]
     lib.dgnn_relu_backward.argtypes = [_vp, _vp, _vp, _vp, _i64, _i32, ctypes.c_int, _vp]
     lib.dgnn_weight_grad_workspace.argtypes = [_i32, _i32, ctypes.POINTER(_sz)]
     lib.dgnn_weight_grad.argtypes = [_vp, _vp, _i64, _i32, _i32, _vp, _i32, ctypes.c_int, _vp, _sz, _vp]
@@ -228,6 +230,33 @@ def mproduct_backward(g_y: torch.Tensor, g_z: torch.Tensor, w: int, m_band: Opti
             raise ValueError("m_band must be [T, w]")
     _check(load_library().dgnn_mproduct_backward(_ptr(g_y), _ptr(g_z), T, n, f, w, _ptr(m_band), dt, _stream(g_y)),
            "dgnn_mproduct_backward")
+
+
+def _mproduct_block(fn, name, src, dst, w, t0, halo, m_band):
+    dt = _dtype_code(src)
+    T, n, f = src.shape
+    if tuple(dst.shape) != (T, n, f) or dst.dtype != src.dtype:
+        raise ValueError(f"shape mismatch in {name}")
+    n_halo = 0
+    if halo is not None and halo.numel() > 0:
+        if halo.dtype != src.dtype or tuple(halo.shape[1:]) != (n, f):
+            raise ValueError("hand-over frames must have the block's frame shape and dtype")
+        n_halo = halo.shape[0]
+    if m_band is not None:
+        _need(m_band, torch.float32, "m_band")
+    _check(fn(_ptr(src), _ptr(dst), T, n, f, w, _ptr(m_band), t0, _ptr(halo) if n_halo else None, n_halo, dt,
+              _stream(src)), name)
+
+
+def mproduct_block(z, y, w: int, t0: int, z_before: Optional[torch.Tensor] = None, m_band=None) -> None:
+    """The M-transform of timesteps t0+1 .. t0+T of a longer series; z_before = the min(w-1, t0) frames before."""
+    _mproduct_block(load_library().dgnn_mproduct_block, "dgnn_mproduct_block", z, y, w, t0, z_before, m_band)
+
+
+def mproduct_backward_block(g_y, g_z, w: int, t0: int, g_after: Optional[torch.Tensor] = None, m_band=None) -> None:
+    """Its adjoint for one block; g_after = upstream gradient of the (up to w-1) timesteps after the block."""
+    _mproduct_block(load_library().dgnn_mproduct_backward_block, "dgnn_mproduct_backward_block", g_y, g_z, w, t0,
+                    g_after, m_band)
 
 
 def relu_backward(g: torch.Tensor, z: torch.Tensor, out: torch.Tensor, row_scale: Optional[torch.Tensor] = None) -> None:

@@ -9,11 +9,25 @@
 // S_t = S_{t-1} + Z_t - Z_{t-w}, with a ring of exactly w slots (the slot about to be overwritten
 // holds Z_{t-w}) and up to four frames fetched ahead; explicit coefficients take the general
 // kernel, w multiply-adds per element.
+//
+// A series longer than one block of timesteps is mixed block by block (Section "Gradient Checkpoint": what a
+// block needs from the one before it is handed over).  Going forward the hand-over is the last w - 1 frames
+// before the block, going back the first w - 1 gradient frames after it; either way they are put into the ring
+// before the walk begins, as if the walk had just passed them, and t0 (the number of timesteps before the
+// block) enters the weights 1/min(w, t).
 #include "common.hpp"
 
 namespace {
 
 using namespace dgnn;
+
+// Frames handed over from the neighbouring block: `count` frames of the block's shape, the nearest LAST going
+// forward (oldest first) and the nearest FIRST going back; t0 = timesteps before the block.
+struct Halo {
+    const char *frames;
+    int count;
+    int t0;
+};
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
@@ -66,7 +80,8 @@ template <> struct Vec<true> {
 // (step i handles frame T - 1 - i, the ring then holds the frames after it).
 template <int RING, bool BF16, bool REVERSE>
 __global__ __launch_bounds__(kThreads) void mproduct_kernel(const char *z, char *y, int T, int64_t pieces,
-                                                            int64_t frame_bytes, int w, const float *__restrict__ m_band) {
+                                                            int64_t frame_bytes, int w, const float *__restrict__ m_band,
+                                                            Halo halo) {
     constexpr int NV = Vec<BF16>::kVals;
     const int64_t piece = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (piece >= pieces) return;
@@ -74,11 +89,15 @@ __global__ __launch_bounds__(kThreads) void mproduct_kernel(const char *z, char 
     char *dst = y + piece * 16;
     auto frame_of = [&](int i) { return REVERSE ? T - 1 - i : i; };
 
+    // slot r of the ring is where step (r - RING) would have left its frame: the handed-over frames go there
     float ring[RING][NV];
 #pragma unroll
-    for (int r = 0; r < RING; ++r)
+    for (int r = 0; r < RING; ++r) {
 #pragma unroll
         for (int e = 0; e < NV; ++e) ring[r][e] = 0.0f;
+        const int h = REVERSE ? RING - 1 - r : halo.count - (RING - r);
+        if (h >= 0 && h < halo.count) Vec<BF16>::load(ring[r], halo.frames + (int64_t)h * frame_bytes + piece * 16);
+    }
 
     float next[NV];
     Vec<BF16>::load(next, src + (int64_t)frame_of(0) * frame_bytes);
@@ -91,8 +110,8 @@ __global__ __launch_bounds__(kThreads) void mproduct_kernel(const char *z, char 
 #pragma unroll
                 for (int e = 0; e < NV; ++e) ring[jj][e] = next[e];
                 if (i + 1 < T) Vec<BF16>::load(next, src + (int64_t)frame_of(i + 1) * frame_bytes);   // before the store: y may be z
-                const int terms = REVERSE ? min(w, T - t) : min(w, t + 1);
-                const float uniform = 1.0f / (float)terms;
+                const int terms = REVERSE ? min(w, T - t + halo.count) : min(w, t + 1 + halo.count);
+                const float uniform = 1.0f / (float)min(w, halo.t0 + t + 1);
                 float out[NV];
 #pragma unroll
                 for (int e = 0; e < NV; ++e) out[e] = 0.0f;
@@ -118,7 +137,7 @@ __global__ __launch_bounds__(kThreads) void mproduct_kernel(const char *z, char 
 // a frame enters the running sum already divided by its own min(W, t) and leaves it the same way.
 template <int W, bool BF16, bool REVERSE>
 __global__ __launch_bounds__(kThreads) void mproduct_uniform_kernel(const char *z, char *y, int T, int64_t pieces,
-                                                                    int64_t frame_bytes) {
+                                                                    int64_t frame_bytes, Halo halo) {
     constexpr int NV = Vec<BF16>::kVals;
     constexpr int D = W % 4 == 0 ? 4 : (W % 2 == 0 ? 2 : 1);     // divides W, so a frame's queue slot is i % D = jj % D
     const int64_t piece = (int64_t)blockIdx.x * kThreads + threadIdx.x;
@@ -128,11 +147,24 @@ __global__ __launch_bounds__(kThreads) void mproduct_uniform_kernel(const char *
     auto frame_of = [&](int i) { return REVERSE ? T - 1 - i : i; };
 
     uintx4 ring[W];
-#pragma unroll
-    for (int r = 0; r < W; ++r) ring[r] = uintx4{0u, 0u, 0u, 0u};   // the bit pattern of zeros in either type
     float sum[NV];
 #pragma unroll
     for (int e = 0; e < NV; ++e) sum[e] = 0.0f;
+    // slot r of the ring is where step (r - W) would have left its frame: the handed-over frames go there and
+    // into the running sum
+#pragma unroll
+    for (int r = 0; r < W; ++r) {
+        ring[r] = uintx4{0u, 0u, 0u, 0u};   // the bit pattern of zeros in either type
+        const int h = REVERSE ? W - 1 - r : halo.count - (W - r);
+        if (h >= 0 && h < halo.count) {
+            ring[r] = *reinterpret_cast<const uintx4 *>(halo.frames + (int64_t)h * frame_bytes + piece * 16);
+            float v[NV];
+            Vec<BF16>::unpack(v, ring[r]);
+            const float sc = REVERSE ? 1.0f / (float)min(W, halo.t0 + T + h + 1) : 1.0f;
+#pragma unroll
+            for (int e = 0; e < NV; ++e) sum[e] += v[e] * sc;
+        }
+    }
 
     uintx4 ahead[D];
 #pragma unroll
@@ -147,7 +179,7 @@ __global__ __launch_bounds__(kThreads) void mproduct_uniform_kernel(const char *
         Vec<BF16>::unpack(in, cur);
         Vec<BF16>::unpack(old, slot);
         slot = cur;
-        const float scale = 1.0f / (float)min(W, t + 1);
+        const float scale = 1.0f / (float)min(W, halo.t0 + t + 1);
 #pragma unroll
         for (int e = 0; e < NV; ++e) {
             if (REVERSE) {
@@ -171,77 +203,98 @@ __global__ __launch_bounds__(kThreads) void mproduct_uniform_kernel(const char *
 }
 
 template <int W, bool REVERSE>
-int launch_uniform(const void *z, void *y, int64_t T, int64_t n, int32_t f, dgnn_dtype dt, hipStream_t s) {
+int launch_uniform(const void *z, void *y, int64_t T, int64_t n, int32_t f, dgnn_dtype dt, Halo halo, hipStream_t s) {
     const int64_t frame_bytes = n * f * (dt == DGNN_F32 ? 4 : 2);
     const int64_t pieces = frame_bytes / 16;
     const unsigned blocks = (unsigned)((pieces + kThreads - 1) / kThreads);
     if (dt == DGNN_F32)
         hipLaunchKernelGGL((mproduct_uniform_kernel<W, false, REVERSE>), dim3(blocks), dim3(kThreads), 0, s,
-                           static_cast<const char *>(z), static_cast<char *>(y), (int)T, pieces, frame_bytes);
+                           static_cast<const char *>(z), static_cast<char *>(y), (int)T, pieces, frame_bytes, halo);
     else
         hipLaunchKernelGGL((mproduct_uniform_kernel<W, true, REVERSE>), dim3(blocks), dim3(kThreads), 0, s,
-                           static_cast<const char *>(z), static_cast<char *>(y), (int)T, pieces, frame_bytes);
+                           static_cast<const char *>(z), static_cast<char *>(y), (int)T, pieces, frame_bytes, halo);
     DGNN_RETURN_IF_LAUNCH_FAILED();
     return DGNN_OK;
 }
 
 template <int W, bool REVERSE>
-int dispatch_uniform(int w, const void *z, void *y, int64_t T, int64_t n, int32_t f, dgnn_dtype dt, hipStream_t s) {
-    if (w == W) return launch_uniform<W, REVERSE>(z, y, T, n, f, dt, s);
-    if constexpr (W > 1) return dispatch_uniform<W - 1, REVERSE>(w, z, y, T, n, f, dt, s);
+int dispatch_uniform(int w, const void *z, void *y, int64_t T, int64_t n, int32_t f, dgnn_dtype dt, Halo halo,
+                     hipStream_t s) {
+    if (w == W) return launch_uniform<W, REVERSE>(z, y, T, n, f, dt, halo, s);
+    if constexpr (W > 1) return dispatch_uniform<W - 1, REVERSE>(w, z, y, T, n, f, dt, halo, s);
     return DGNN_ERR_SHAPE;
 }
 
 template <int RING, bool REVERSE>
 int launch(const void *z, void *y, int64_t T, int64_t n, int32_t f, int32_t w, const float *m_band, dgnn_dtype dt,
-           hipStream_t s) {
+           Halo halo, hipStream_t s) {
     const int64_t frame_bytes = n * f * (dt == DGNN_F32 ? 4 : 2);
     const int64_t pieces = frame_bytes / 16;
     const unsigned blocks = (unsigned)((pieces + kThreads - 1) / kThreads);
     if (dt == DGNN_F32)
         hipLaunchKernelGGL((mproduct_kernel<RING, false, REVERSE>), dim3(blocks), dim3(kThreads), 0, s,
-                           static_cast<const char *>(z), static_cast<char *>(y), (int)T, pieces, frame_bytes, (int)w, m_band);
+                           static_cast<const char *>(z), static_cast<char *>(y), (int)T, pieces, frame_bytes, (int)w, m_band, halo);
     else
         hipLaunchKernelGGL((mproduct_kernel<RING, true, REVERSE>), dim3(blocks), dim3(kThreads), 0, s,
-                           static_cast<const char *>(z), static_cast<char *>(y), (int)T, pieces, frame_bytes, (int)w, m_band);
+                           static_cast<const char *>(z), static_cast<char *>(y), (int)T, pieces, frame_bytes, (int)w, m_band, halo);
     DGNN_RETURN_IF_LAUNCH_FAILED();
     return DGNN_OK;
 }
 
 template <bool REVERSE>
-int mproduct(const void *z, void *y, int64_t T, int64_t n, int32_t f, int32_t w, const float *m_band, dgnn_dtype dt,
-             void *stream) {
+int mproduct(const void *z, void *y, int64_t T, int64_t n, int32_t f, int32_t w, const float *m_band, int64_t t0,
+             const void *halo_frames, int64_t n_halo, dgnn_dtype dt, void *stream) {
     if (!z || !y) return DGNN_ERR_NULL;
-    if (T <= 0 || n <= 0 || w <= 0 || !supported_width(f)) return DGNN_ERR_SHAPE;
+    if (T <= 0 || n <= 0 || w <= 0 || t0 < 0 || n_halo < 0 || !supported_width(f)) return DGNN_ERR_SHAPE;
     if (dt != DGNN_F32 && dt != DGNN_BF16) return DGNN_ERR_SHAPE;
-    if (!fits_i32(n) || !fits_i32(T)) return DGNN_ERR_OVERFLOW;
-    if (!aligned16(z) || !aligned16(y)) return DGNN_ERR_ALIGN;
-    const int64_t bytes = T * n * f * (dt == DGNN_F32 ? 4 : 2);
-    if (y != z) {   // partial overlap is not allowed
-        const char *a = static_cast<const char *>(z), *b = static_cast<const char *>(y);
-        if (a < b + bytes && b < a + bytes) return DGNN_ERR_ALIAS;
+    if (!fits_i32(n) || !fits_i32(T) || !fits_i32(t0 + T + n_halo)) return DGNN_ERR_OVERFLOW;
+    if (n_halo > 0 && !halo_frames) return DGNN_ERR_NULL;
+    if (n_halo > w - 1) return DGNN_ERR_SHAPE;
+    if (!REVERSE && n_halo != (t0 < w - 1 ? t0 : w - 1)) return DGNN_ERR_SHAPE;   // exactly the frames the window reaches
+    if (!aligned16(z) || !aligned16(y) || !aligned16(halo_frames)) return DGNN_ERR_ALIGN;
+    const int64_t frame = n * f * (dt == DGNN_F32 ? 4 : 2);
+    const int64_t bytes = T * frame;
+    const char *a = static_cast<const char *>(z), *b = static_cast<const char *>(y);
+    if (y != z && a < b + bytes && b < a + bytes) return DGNN_ERR_ALIAS;             // partial overlap is not allowed
+    if (n_halo > 0) {
+        const char *h = static_cast<const char *>(halo_frames);
+        if (h < b + bytes && b < h + n_halo * frame) return DGNN_ERR_ALIAS;           // the output would overwrite the hand-over
     }
-    // A window longer than the series acts like the series length; with explicit coefficients the
-    // band layout keeps the caller's w as its row stride, so w itself must fit the ring.
-    const int64_t eff = m_band ? (int64_t)w : (w < T ? (int64_t)w : T);
+    // The ring holds min(w, length of the series so far) frames; with explicit coefficients the band layout
+    // keeps the caller's w as its row stride, so w itself must fit the ring.
+    const int64_t seen = t0 + T + (REVERSE ? n_halo : 0);
+    const int64_t eff = m_band ? (int64_t)w : (w < seen ? (int64_t)w : seen);
     if (eff > 32) return DGNN_ERR_SHAPE;
     const int32_t wk = m_band ? w : (int32_t)eff;
+    const Halo halo{static_cast<const char *>(halo_frames), (int)n_halo, (int)t0};
     hipStream_t s = (hipStream_t)stream;
-    if (!m_band) return dispatch_uniform<32, REVERSE>((int)eff, z, y, T, n, f, dt, s);
-    if (eff <= 4) return launch<4, REVERSE>(z, y, T, n, f, wk, m_band, dt, s);
-    if (eff <= 8) return launch<8, REVERSE>(z, y, T, n, f, wk, m_band, dt, s);
-    if (eff <= 16) return launch<16, REVERSE>(z, y, T, n, f, wk, m_band, dt, s);
-    return launch<32, REVERSE>(z, y, T, n, f, wk, m_band, dt, s);
+    if (!m_band) return dispatch_uniform<32, REVERSE>((int)eff, z, y, T, n, f, dt, halo, s);
+    if (eff <= 4) return launch<4, REVERSE>(z, y, T, n, f, wk, m_band, dt, halo, s);
+    if (eff <= 8) return launch<8, REVERSE>(z, y, T, n, f, wk, m_band, dt, halo, s);
+    if (eff <= 16) return launch<16, REVERSE>(z, y, T, n, f, wk, m_band, dt, halo, s);
+    return launch<32, REVERSE>(z, y, T, n, f, wk, m_band, dt, halo, s);
 }
 
 }  // namespace
 
 extern "C" int dgnn_mproduct(const void *z, void *y, int64_t T, int64_t n, int32_t f, int32_t w,
                              const float *m_band, dgnn_dtype dt, void *stream) {
-    return mproduct<false>(z, y, T, n, f, w, m_band, dt, stream);
+    return mproduct<false>(z, y, T, n, f, w, m_band, 0, nullptr, 0, dt, stream);
 }
 
 extern "C" int dgnn_mproduct_backward(const void *g_y, void *g_z, int64_t T, int64_t n, int32_t f, int32_t w,
                                       const float *m_band, dgnn_dtype dt, void *stream) {
-    return mproduct<true>(g_y, g_z, T, n, f, w, m_band, dt, stream);
+    return mproduct<true>(g_y, g_z, T, n, f, w, m_band, 0, nullptr, 0, dt, stream);
+}
+
+extern "C" int dgnn_mproduct_block(const void *z, void *y, int64_t T, int64_t n, int32_t f, int32_t w,
+                                   const float *m_band, int64_t t0, const void *z_before, int64_t n_before,
+                                   dgnn_dtype dt, void *stream) {
+    return mproduct<false>(z, y, T, n, f, w, m_band, t0, z_before, n_before, dt, stream);
+}
+
+extern "C" int dgnn_mproduct_backward_block(const void *g_y, void *g_z, int64_t T, int64_t n, int32_t f, int32_t w,
+                                            const float *m_band, int64_t t0, const void *g_after, int64_t n_after,
+                                            dgnn_dtype dt, void *stream) {
+    return mproduct<true>(g_y, g_z, T, n, f, w, m_band, t0, g_after, n_after, dt, stream);
 }

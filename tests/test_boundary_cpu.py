@@ -156,3 +156,10 @@ def test_backward_argument_errors(lib):
     assert f(None, FAKE, 8, 10, 16, 3, None, 0, None) == -1
     assert f(FAKE, FAKE, 8, 10, 16, 0, None, 0, None) == -2
     assert f(FAKE, FAKE + 16, 8, 10, 16, 3, None, 0, None) == -5
+    f = lib.dgnn_mproduct_block
+    assert f(FAKE, FAKE, 8, 10, 16, 3, None, 5, None, 2, 0, None) == -1          # frames promised but no pointer
+    assert f(FAKE, FAKE, 8, 10, 16, 3, None, 5, FAKE + (1 << 20), 1, 0, None) == -2   # window 3 after 5 steps needs 2
+    assert f(FAKE, FAKE, 8, 10, 16, 3, None, -1, None, 0, 0, None) == -2
+    f = lib.dgnn_mproduct_backward_block
+    assert f(FAKE, FAKE, 8, 10, 16, 3, None, 0, FAKE + (1 << 20), 3, 0, None) == -2
+    assert f(FAKE, FAKE + (1 << 20), 8, 10, 16, 3, None, 0, FAKE + (1 << 20), 2, 0, None) == -5   # output over the hand-over

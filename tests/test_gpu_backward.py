@@ -162,3 +162,55 @@ def test_transposed_aggregation_on_a_directed_graph(dtype, prescaled):
     else:
         dg.spmm(rpt_d, cit_d, int(cit.size), dinv, gd, out, ws)
     assert_close(to_f64(out), expect, dtype, "A~^T G")
+
+
+# ------------------------------------------------------------------------------- M-transform block by block
+def _band_matrix(band, T, w):
+    M = np.zeros((T, T))
+    for t in range(T):
+        for j in range(min(w, t + 1)):
+            M[t, t - j] = float(band[t, j])
+    return M
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("T,w,cuts", [(20, 6, [7, 13]), (12, 5, [2, 3, 4]), (9, 12, [4]), (40, 16, [16, 17, 39]),
+                                       (10, 1, [5]), (33, 32, [1, 32])])
+@pytest.mark.parametrize("explicit_band", [False, True])
+def test_mproduct_in_blocks_equals_whole_series(dtype, T, w, cuts, explicit_band):
+    """Forward with the frames before each block handed over, adjoint with the gradient frames after it: the
+    pieces must be the frames of the transform of the whole series."""
+    n, f = 130, 16
+    z, g = randn((T, n, f), 31 * T + w, dtype), randn((T, n, f), 37 * T + w, dtype)
+    if explicit_band:
+        band = randn((T, w), 41 * T + w)
+        M = _band_matrix(band, T, w)
+    else:
+        band, M = None, oracle.m_matrix(T, w)
+    y_want, gz_want = oracle.mproduct(to_f64(z), M), oracle.mproduct_t(to_f64(g), M)
+    zd, gd = z.to(DEV), g.to(DEV)
+    y, gz = torch.full_like(zd, float("nan")), torch.full_like(gd, float("nan"))
+    bounds = [0] + cuts + [T]
+    for a, b in zip(bounds[:-1], bounds[1:]):
+        nb = min(w - 1, a)
+        na = min(w - 1, T - b)
+        fb = band[a:b].contiguous().to(DEV) if explicit_band else None
+        bb = band[a:b + na].contiguous().to(DEV) if explicit_band else None
+        dg.mproduct_block(zd[a:b], y[a:b], w, a, z_before=zd[a - nb:a] if nb else None, m_band=fb)
+        dg.mproduct_backward_block(gd[a:b], gz[a:b], w, a, g_after=gd[b:b + na] if na else None, m_band=bb)
+    assert_close(to_f64(y), y_want, dtype, f"blocks forward T={T} w={w}")
+    assert_close(to_f64(gz), gz_want, dtype, f"blocks adjoint T={T} w={w}")
+    if not explicit_band:     # and bit for bit what the one-call transform gives
+        y1, gz1 = torch.empty_like(zd), torch.empty_like(gd)
+        dg.mproduct(zd, y1, w)
+        dg.mproduct_backward(gd, gz1, w)
+        assert_close(to_f64(y), to_f64(y1), dtype, "blocks vs one call")
+        assert_close(to_f64(gz), to_f64(gz1), dtype, "blocks vs one call, adjoint")
+
+
+def test_mproduct_block_argument_checks():
+    z = torch.zeros((4, 10, 16), device=DEV)
+    with pytest.raises(dg.DgnnError):      # three timesteps before the block, window 3: two frames must come along
+        dg.mproduct_block(z, torch.empty_like(z), 3, 3, z_before=z[:1])
+    with pytest.raises(dg.DgnnError):      # more gradient frames than the window reaches
+        dg.mproduct_backward_block(z, torch.empty_like(z), 3, 0, g_after=torch.zeros((3, 10, 16), device=DEV))
