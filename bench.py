@@ -120,25 +120,34 @@ def training_step(args, wl, blk, dev):
     from dtdg_synth import gradient
     from paper_2109_07893_amd.pipeline import StageTimer
     from paper_2109_07893_amd.training import make_trainer
-    # One checkpoint block: as many timesteps as leave room for the block's activations and gradients next to
-    # the inputs (four more tensors of T x N x F), at most the workload's T.
+    # The whole series in one block if its activations and gradients fit next to the inputs (the upstream
+    # gradient and three more tensors of T x N x F); otherwise the paper's gradient checkpointing: blocks of
+    # timesteps, a forward pass that keeps only the hand-over, then per block a rerun and the backward pass.
+    from paper_2109_07893_amd.training import CheckpointedTrainer
     frame = blk.n * blk.f * blk.x[0].element_size()
     free_bytes, _ = torch.cuda.mem_get_info(dev)
-    Tb = int(max(2, min(blk.T, (0.8 * free_bytes) // (4 * frame))))
-    if Tb < blk.T:
-        from paper_2109_07893_amd.pipeline import BlockInputs
-        blk = BlockInputs(n=blk.n, T=Tb, f=blk.f, layers=blk.layers, window=blk.window, rowptr1=blk.rowptr1,
-                          colidx1=blk.colidx1, deltas=blk.deltas[:Tb - 1], x=blk.x[:Tb], w=blk.w, nnz=blk.nnz[:Tb])
-    tr = make_trainer(wl, blk)
-    progress(f"trainer ready (block of {blk.T} timesteps)")
+    fit = int((0.85 * free_bytes - blk.T * frame) // (3 * frame))
+    n_blocks = 1 if fit >= blk.T else -(-blk.T // max(fit, 2))
     g_y = torch.empty((blk.T, blk.n, blk.f), dtype=blk.x[0].dtype, device=dev)
     for t in range(1, blk.T + 1):
         g_y[t - 1].copy_(gradient(wl, t, device=dev))
-    torch.cuda.synchronize()
+    if n_blocks == 1:
+        tr = make_trainer(wl, blk)
+        timed = tr
 
-    def one_step():
-        tr.forward()
-        tr.backward(g_y)
+        def one_step():
+            tr.forward()
+            tr.backward(g_y)
+    else:
+        ck = CheckpointedTrainer(wl, blk, -(-blk.T // n_blocks))
+        timed = ck.trainer
+
+        def one_step():
+            ck.forward()
+            ck.backward(g_y)
+    directed = timed.directed
+    progress(f"trainer ready ({n_blocks} block(s) of timesteps)")
+    torch.cuda.synchronize()
 
     for _ in range(max(1, args.warmup - 1)):
         one_step()
@@ -149,18 +158,19 @@ def training_step(args, wl, blk, dev):
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) / args.steps * 1e3
     progress(f"training step timed: {ms:.2f} ms per step")
-    tr.timer = StageTimer(dev)
+    timed.timer = StageTimer(dev)
     one_step()
     torch.cuda.synchronize()
     stages = {}
-    for name, (calls, total_ms) in tr.timer.totals().items():
+    for name, (calls, total_ms) in timed.timer.totals().items():
         if name in ("mproduct", "mproduct_backward"):
-            byts = algorithmic_bytes(blk, name)
+            byts = algorithmic_bytes(blk, name) / n_blocks          # a call mixes one block of the series
         elif name == "delta_rebuild":
             byts = None
+        elif name in ("spmm", "spmm_transposed"):
+            byts = sum(algorithmic_bytes(blk, name, t) for t in range(1, blk.T + 1)) / blk.T
         else:
-            byts = sum(algorithmic_bytes(blk, "spmm" if name == "spmm" else name, t) for t in range(1, blk.T + 1)) \
-                   * blk.layers / calls if name != "input_grad" else algorithmic_bytes(blk, name, 1)
+            byts = algorithmic_bytes(blk, name, 1)
         entry = {"calls_per_step": calls, "avg_ms": round(total_ms / calls, 4), "ms_per_step": round(total_ms, 4)}
         if byts:
             entry["algorithmic_bytes_per_call"] = int(byts)
@@ -168,8 +178,10 @@ def training_step(args, wl, blk, dev):
         stages[name] = entry
     edges = sum(blk.nnz)
     return {"ms_per_step": ms, "value": edges / (ms * 1e-3), "unit": "edges/s",
-            "what": f"forward keeping activations + backward over t=1..{blk.T} ({'directed: second chain of transposed snapshots' if tr.directed else 'undirected: the snapshot is its own transpose'}); "
-                    "weight gradients of every layer, reverse rebuilds with exchanged lists",
+            "what": f"forward keeping activations + backward over t=1..{blk.T} ({'directed: second chain of transposed snapshots' if directed else 'undirected: the snapshot is its own transpose'}); "
+                    "weight gradients of every layer, reverse rebuilds with exchanged lists"
+                    + (f"; gradient checkpointing over {n_blocks} blocks: every block's forward pass runs twice" if n_blocks > 1 else ""),
+            "checkpoint_blocks": n_blocks,
             "edges_per_step": edges, "stages": stages}
 
 

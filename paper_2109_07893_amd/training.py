@@ -31,9 +31,13 @@ class _Chain:
         self.rowptr = [torch.empty(n + 1, dtype=torch.int32, device=dev) for _ in range(3)]
         self.colidx = [torch.empty(cap, dtype=torch.int32, device=dev) for _ in range(3)]
         self.dinv = [torch.empty(n, dtype=torch.float32, device=dev) if with_dinv else None for _ in range(3)]
+        self.load_first(rowptr1, colidx1)
+
+    def load_first(self, rowptr1, colidx1) -> None:
+        """The block's first snapshot, which arrives whole, goes into the kept slot."""
         self.rowptr[2].copy_(rowptr1)
         self.colidx[2][: colidx1.numel()].copy_(colidx1)
-        if with_dinv:
+        if self.dinv[2] is not None:
             B.csr_dinv(self.rowptr[2], self.dinv[2])
 
     @staticmethod
@@ -46,13 +50,17 @@ class BlockTrainer:
 
     def __init__(self, blk: BlockInputs, directed: bool,
                  transposed_first: Optional[Tuple[torch.Tensor, torch.Tensor]] = None,
-                 transposed_deltas: Optional[List[Tuple[torch.Tensor, ...]]] = None, want_dx: bool = False):
+                 transposed_deltas: Optional[List[Tuple[torch.Tensor, ...]]] = None, want_dx: bool = False,
+                 cap: Optional[int] = None, max_list: Optional[int] = None):
         self.blk = blk
         dev = blk.rowptr1.device
         self.dev = dev
         n, f, T, L = blk.n, blk.f, blk.T, blk.layers
         dt = blk.x[0].dtype
-        cap = max(blk.nnz)
+        cap = max(max(blk.nnz), cap or 0)          # room for the densest snapshot this trainer will ever hold
+        self.cap, self.T_max = cap, T
+        self.t0 = 0                     # timesteps of the series before this block
+        self.z_before = None            # last w-1 frames of the top layer's Z before this block
         self.directed = directed
         self.a = _Chain(n, cap, dev, blk.rowptr1, blk.colidx1, with_dinv=True)
         self.at = None
@@ -68,11 +76,21 @@ class BlockTrainer:
         self.g_mid = torch.empty((n, f), dtype=dt, device=dev) if L > 1 else None
         self.dx = torch.empty((T, n, f), dtype=dt, device=dev) if want_dx else None
         self.dw = [torch.zeros((f, f), dtype=torch.float32, device=dev) for _ in range(L)]
-        max_list = max([int(d[0].numel()) for d in blk.deltas] + [int(d[2].numel()) for d in blk.deltas] + [1])
+        max_list = max([int(d[0].numel()) for d in blk.deltas] + [int(d[2].numel()) for d in blk.deltas] + [1, max_list or 0])
         self.ws_rebuild = torch.empty(B.delta_rebuild_workspace(n, cap, max_list, max_list), dtype=torch.uint8, device=dev)
         self.ws_spmm = torch.empty(B.spmm_workspace(n, cap, f), dtype=torch.uint8, device=dev)
         self.ws_wgrad = torch.empty(B.weight_grad_workspace(f, f), dtype=torch.uint8, device=dev)
         self.timer = None
+
+    def rebind(self, blk: BlockInputs, t0: int = 0, z_before: Optional[torch.Tensor] = None,
+               transposed_first=None, transposed_deltas=None) -> None:
+        """Point the same buffers at another block of the same series (not longer, not denser than the first)."""
+        assert blk.T <= self.T_max and max(blk.nnz) <= self.cap and blk.n == self.blk.n and blk.f == self.blk.f
+        self.blk, self.t0, self.z_before = blk, t0, z_before
+        self.a.load_first(blk.rowptr1, blk.colidx1)
+        if self.directed:
+            self.at.load_first(*transposed_first)
+            self.t_deltas = transposed_deltas
 
     def _stage(self, name):
         import contextlib
@@ -104,16 +122,19 @@ class BlockTrainer:
                     B.spmm(self.a.rowptr[slot], self.a.colidx[slot], blk.nnz[t - 1], self.a.dinv[slot], self.h,
                            self.z[layer, t - 1], self.ws_spmm, flags=B.DGNN_RELU | B.DGNN_H_PRESCALED)
                 cur = self.z[layer, t - 1]
+        top = self.z[blk.layers - 1, : blk.T]
         if blk.window:
             with self._stage("mproduct"):
-                B.mproduct(self.z[blk.layers - 1], self.y, blk.window)
-            return self.y
-        return self.z[blk.layers - 1]
+                B.mproduct_block(top, self.y[: blk.T], blk.window, self.t0, z_before=self.z_before)
+            return self.y[: blk.T]
+        return top
 
     # ------------------------------------------------------------------ backward
-    def backward(self, g_y: torch.Tensor, overwrite: bool = False) -> None:
+    def backward(self, g_y: torch.Tensor, overwrite: bool = False, g_after: Optional[torch.Tensor] = None,
+                 accumulate: bool = False) -> None:
         """g_y [T, n, f] = dL/dY.  Must follow forward() (A_T and, if directed, A_T^T are resident).
-        With overwrite the adjoint of the M-transform is taken in place, on g_y itself."""
+        With overwrite the adjoint of the M-transform is taken in place, on g_y itself; g_after = upstream
+        gradient of the (up to w-1) timesteps after this block; accumulate adds to dw instead of replacing it."""
         blk = self.blk
         L, T = blk.layers, blk.T
         if blk.window:
@@ -121,13 +142,13 @@ class BlockTrainer:
                 g_top = g_y
             else:
                 if self.g is None:
-                    self.g = torch.empty_like(g_y)
-                g_top = self.g
+                    self.g = torch.empty((self.T_max,) + tuple(g_y.shape[1:]), dtype=g_y.dtype, device=g_y.device)
+                g_top = self.g[:T]
             with self._stage("mproduct_backward"):
-                B.mproduct_backward(g_y, g_top, blk.window)
+                B.mproduct_backward_block(g_y, g_top, blk.window, self.t0, g_after=g_after)
         else:
             g_top = g_y
-        first_call = [True] * L
+        first_call = [not accumulate] * L
         for t in range(T, 0, -1):
             slot = self.a.slot_of(t)
             tc = self.at if self.directed else self.a           # the chain that holds (A_t + I)^T
@@ -174,3 +195,98 @@ def make_trainer(wl, blk: BlockInputs, want_dx: bool = False) -> BlockTrainer:
     for ar, ac, dr, dc in blk.deltas:
         t_deltas.append(transpose_coo(ar, ac) + transpose_coo(dr, dc))
     return BlockTrainer(blk, True, transposed_first=(rowptr_t, tc), transposed_deltas=t_deltas, want_dx=want_dx)
+
+
+class CheckpointedTrainer:
+    """The paper's gradient checkpointing over a series of T timesteps cut into blocks (Section "Gradient
+    Checkpoint"): a forward pass block by block that keeps only what the next block needs (the last w - 1 frames
+    of Z; here also each block's first snapshot, which the paper sends whole), then, from the last block to the
+    first, a rerun of the block's forward pass followed by its backward pass.  Activations of one block at a
+    time are resident."""
+
+    def __init__(self, wl, series: BlockInputs, bsize: int):
+        from dtdg_synth import transpose_coo
+        self.series, self.bsize = series, bsize
+        self.directed = wl.graph != "er"
+        T = series.T
+        self.bounds = [(a, min(a + bsize, T)) for a in range(0, T, bsize)]
+        dev = series.rowptr1.device
+        # first snapshot of every block: block 0 has it, the others are filled in by the forward pass
+        self.first = [(series.rowptr1, series.colidx1)] + [
+            (torch.empty_like(series.rowptr1), torch.empty(series.nnz[a], dtype=torch.int32, device=dev))
+            for a, _ in self.bounds[1:]]
+        self.t_first, self.t_deltas = None, None
+        if self.directed:
+            n = series.n
+            rows = torch.repeat_interleave(torch.arange(n, dtype=torch.int32, device=dev),
+                                           (series.rowptr1[1:] - series.rowptr1[:-1]).to(torch.int64))
+            tr, tc = transpose_coo(rows, series.colidx1)
+            rp_t = torch.zeros(n + 1, dtype=torch.int32, device=dev)
+            rp_t[1:] = torch.cumsum(torch.bincount(tr.to(torch.int64), minlength=n), 0).to(torch.int32)
+            self.t_first = [(rp_t, tc)] + [(torch.empty_like(rp_t), torch.empty(series.nnz[a], dtype=torch.int32, device=dev))
+                                           for a, _ in self.bounds[1:]]
+            self.t_deltas = [transpose_coo(ar, ac) + transpose_coo(dr, dc) for ar, ac, dr, dc in series.deltas]
+        self.pi: List[Optional[torch.Tensor]] = [None] * len(self.bounds)   # frames handed to block b
+        longest_list = max([int(d[0].numel()) for d in series.deltas] + [int(d[2].numel()) for d in series.deltas] + [1])
+        self.trainer = BlockTrainer(self._block(0), self.directed,       # block 0 is as long as any
+                                    transposed_first=self.t_first[0] if self.directed else None,
+                                    transposed_deltas=self._t_deltas(*self.bounds[0]),
+                                    cap=max(series.nnz), max_list=longest_list)
+        self.dw = self.trainer.dw
+
+    def _block(self, b: int) -> BlockInputs:
+        s = self.series
+        a, e = self.bounds[b]
+        nnz = list(s.nnz[a:e])
+        blk = BlockInputs(n=s.n, T=e - a, f=s.f, layers=s.layers, window=s.window, rowptr1=self.first[b][0],
+                          colidx1=self.first[b][1], deltas=s.deltas[a:e - 1], x=s.x[a:e], w=s.w, nnz=nnz)
+        return blk
+
+    def _t_deltas(self, a: int, e: int):
+        return self.t_deltas[a:e - 1] if self.directed else None
+
+    def _bind(self, b: int) -> None:
+        a, e = self.bounds[b]
+        self.trainer.rebind(self._block(b), t0=a, z_before=self.pi[b],
+                            transposed_first=self.t_first[b] if self.directed else None,
+                            transposed_deltas=self._t_deltas(a, e))
+
+    def forward(self, on_block=None) -> None:
+        """Block by block; on_block(b, a, e, y) sees the block's output frames before they are overwritten."""
+        s, tr = self.series, self.trainer
+        w1 = max(s.window - 1, 0)
+        for b, (a, e) in enumerate(self.bounds):
+            self._bind(b)
+            y = tr.forward()
+            if on_block is not None:
+                on_block(b, a, e, y)
+            if b + 1 < len(self.bounds):
+                if w1:
+                    top = tr.z[s.layers - 1, : e - a]
+                    keep = min(w1, e)                       # frames of the series so far that the window reaches
+                    own = top[max(e - a - keep, 0):]
+                    if own.shape[0] < keep:                 # a block shorter than the window: older frames come along
+                        own = torch.cat([self.pi[b][-(keep - own.shape[0]):], own])
+                    self.pi[b + 1] = own.clone()
+                # the next block's first snapshot (the paper sends it whole; here it is one more rebuild)
+                slot = tr.a.slot_of(e - a)
+                ar, ac, dr, dc = s.deltas[e - 1]
+                B.delta_rebuild(tr.a.rowptr[slot], tr.a.colidx[slot], s.nnz[e - 1], ar, ac, int(ar.numel()), dr, dc,
+                                int(dr.numel()), self.first[b + 1][0], self.first[b + 1][1], None, tr.ws_rebuild)
+                if self.directed:
+                    ar, ac, dr, dc = self.t_deltas[e - 1]
+                    B.delta_rebuild(tr.at.rowptr[slot], tr.at.colidx[slot], s.nnz[e - 1], ar, ac, int(ar.numel()), dr,
+                                    dc, int(dr.numel()), self.t_first[b + 1][0], self.t_first[b + 1][1], None,
+                                    tr.ws_rebuild)
+
+    def backward(self, g_y: torch.Tensor) -> None:
+        """g_y [T, n, f] for the whole series.  Must follow forward()."""
+        s, tr = self.series, self.trainer
+        w1 = max(s.window - 1, 0)
+        last = len(self.bounds) - 1
+        for b in range(last, -1, -1):
+            a, e = self.bounds[b]
+            self._bind(b)
+            tr.forward()                                                    # the rerun
+            after = g_y[e:min(e + w1, s.T)] if (w1 and e < s.T) else None
+            tr.backward(g_y[a:e], g_after=after, accumulate=b != last)

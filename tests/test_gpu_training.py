@@ -114,3 +114,36 @@ def test_training_step_repeats_bit_for_bit():
         runs.append([d.clone() for d in tr.dw])
     for a, b in zip(*runs):
         assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("case,bsize", [("undirected_2layers_window", 3), ("directed_2layers_window", 2),
+                                        ("directed_2layers_window", 4), ("undirected_1layer_window", 1),
+                                        ("directed_1layer", 2), ("bf16_window", 4)])
+def test_checkpointed_training_equals_the_one_block_step(case, bsize):
+    """The series cut into checkpoint blocks (forward keeping only the hand-over, then per block a rerun and the
+    backward pass, last block first) must give the gradients of the whole series."""
+    from paper_2109_07893_amd.training import CheckpointedTrainer
+    wl = CASES[case]
+    dtype = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    dws, _, y, _, _ = oracle_training_step(wl)
+    series = make_block(wl, DEV, gen_device="cpu")
+    ck = CheckpointedTrainer(wl, series, bsize)
+    outs = {}
+    ck.forward(on_block=lambda b, a, e, yb: outs.__setitem__((a, e), yb.clone()))
+    got_y = torch.cat([outs[k] for k in sorted(outs)])
+    assert_close(to_f64(got_y), y, dtype, f"{case}: forward output in blocks of {bsize}")
+    g_y = torch.stack([gradient(wl, t) for t in range(1, wl.T + 1)]).to(DEV)
+    ck.backward(g_y)
+    torch.cuda.synchronize()
+    # here both sides decide the ReLU mask on their own activations: a result rounded once through fp32 storage
+    # leaves the mask alone except for pre-activations within rounding of zero, of which these cases have none;
+    # with bf16 storage the mask differs in a fraction of a percent of the elements, so dW is only required to
+    # agree with the one-block GPU step, bit for bit, and that one is checked against the oracle above
+    one = make_trainer(wl, series)
+    one.forward()
+    one.backward(g_y)
+    torch.cuda.synchronize()
+    for layer in range(wl.layers):
+        if dtype == torch.float32:
+            assert_close(to_f64(ck.dw[layer]), dws[layer], dtype, f"{case}: dW of layer {layer}, blocks of {bsize}")
+        assert_close(to_f64(ck.dw[layer]), to_f64(one.dw[layer]), torch.float32, f"{case}: blocks vs one block, layer {layer}")
