@@ -163,3 +163,61 @@ def test_temporal_stress_full_size():
     assert len(frames) == 20 + w_len + 1
     sel = np.array(frames) - 1
     assert_close(got[sel], expect[sel], torch.bfloat16, f"c4 output, {len(frames)} frames on {rows.size} sampled rows")
+
+
+@pytest.mark.timeout(900)
+def test_power_law_training_step_full_size():
+    """c3 at full size, two timesteps: backward through the block at the launch configuration the benchmark's
+    training step uses.  The oracle carries the whole computation (its transposed aggregation is a serial scatter
+    per feature column): dW is compared in full, the aggregated gradient on sampled rows written out from the
+    definition in numpy (entries of column v found by scanning colidx)."""
+    from dtdg_synth import gradient
+    from paper_2109_07893_amd.training import make_trainer
+    wl = WORKLOADS["c3"]
+    T = 2
+    blk = make_block(wl, DEV, gen_device=DEV, T=T)
+    tr = make_trainer(wl, blk)
+    tr.forward()
+    torch.cuda.synchronize()
+    w = to_f64(blk.w[0])
+    rp, ci = blk.rowptr1.cpu().numpy(), blk.colidx1.cpu().numpy()
+    snaps, stored = [], []
+    for t in range(1, T + 1):
+        if t >= 2:
+            rp, ci = oracle.delta_apply(wl.n, rp, ci, *host_lists(blk, t))
+        snaps.append((rp, ci))
+        z = oracle.gcn_layer(rp, ci, to_f64(blk.x[t - 1]), w, relu=True)
+        progress(f"c3 oracle forward t={t}")
+        # both sides decide the ReLU mask on the same stored activations (see test_gpu_training.py)
+        zs = torch.from_numpy(z).to(torch.float32)
+        rows = sample_rows(rp, 1 << 14, 256, seed=10 + t)
+        assert_close(to_f64(tr.z[0, t - 1][torch.as_tensor(rows, device=DEV)]), z[rows], torch.float32, f"Z_{t}")
+        tr.z[0, t - 1].copy_(zs)
+        stored.append(zs.numpy().astype(np.float64))
+    g_y = torch.stack([gradient(wl, t, device=DEV) for t in range(1, T + 1)])
+    tr.backward(g_y)
+    torch.cuda.synchronize()
+    captured = {1: tr.h.clone()}        # the buffer still holds G_H of the timestep processed last, t = 1
+    dw = np.zeros_like(w)
+    for t in range(T, 0, -1):
+        rp, ci = snaps[t - 1]
+        g_p = oracle.relu_grad(to_f64(g_y[t - 1]), stored[t - 1])
+        g_h = oracle.spmm_t(rp, ci, g_p)
+        progress(f"c3 oracle transposed aggregation t={t}")
+        dw += oracle.weight_grad(to_f64(blk.x[t - 1]), g_h)
+        if t == 1:
+            # sampled rows of A~^T G_P straight from the definition: entries (u, v) with v in the sample
+            cols = sample_rows(rp, 512, 64, seed=77)
+            hit = np.flatnonzero(np.isin(ci, cols))
+            u = np.searchsorted(rp, hit, side="right") - 1
+            v = ci[hit]
+            d = np.diff(rp).astype(np.float64)
+            contrib = g_p[u] / np.sqrt(d[u] * d[v])[:, None]
+            order = np.argsort(v, kind="stable")
+            v_sorted, starts = np.unique(v[order], return_index=True)
+            sums = np.add.reduceat(contrib[order], starts, axis=0)
+            assert np.array_equal(v_sorted, cols)          # every sampled column has at least its diagonal
+            np.testing.assert_allclose(g_h[cols], sums, rtol=1e-9, atol=1e-12)       # the oracle against the definition
+            got = to_f64(captured[1][torch.as_tensor(cols, device=DEV)])
+            assert_close(got, sums, torch.float32, "A~^T G_P on sampled rows")
+    assert_close(to_f64(tr.dw[0]), dw, torch.float32, "c3 dW over two full-size timesteps")
