@@ -31,7 +31,8 @@ class BlockInputs:
     colidx1: torch.Tensor                  # int32 [nnz_1]
     deltas: List[Tuple[torch.Tensor, ...]]  # per t = 2..T: (add_row, add_col, del_row, del_col), int32, device
     x: List[torch.Tensor]                  # T frames [n, f]
-    w: List[torch.Tensor]                  # one weight [f, f] per layer
+    w: List[torch.Tensor]                  # one weight [f, f] per layer, shared by all timesteps
+    w_t: Optional[List[List[torch.Tensor]]] = None   # or one per timestep and layer (Section "EvolveGCN": W_t evolves)
     pinned: Optional[List[Tuple[torch.Tensor, ...]]] = None   # the same lists in pinned host memory
     nnz: List[int] = field(default_factory=list)              # nnz_t, t = 1..T (host arithmetic on list lengths)
 
@@ -42,6 +43,10 @@ class BlockInputs:
             for ar, _, dr, _ in self.deltas:
                 cur += int(ar.numel()) - int(dr.numel())
                 self.nnz.append(cur)
+
+    def weight(self, t: int, layer: int) -> torch.Tensor:
+        """The weight of `layer` at timestep t (1-based)."""
+        return self.w_t[t - 1][layer] if self.w_t is not None else self.w[layer]
 
 
 def make_block(wl, device, gen_device=None, pinned: bool = False, T: Optional[int] = None) -> BlockInputs:
@@ -165,7 +170,7 @@ class BlockRunner:
         for layer in range(blk.layers):
             # the right-hand D^(-1/2) of the normalised adjacency is folded into the rows of H
             with self._stage("feature_transform"):
-                B.feature_transform(cur, blk.w[layer], self.h, row_scale=self.dinv[slot])
+                B.feature_transform(cur, blk.weight(t, layer), self.h, row_scale=self.dinv[slot])
             dst = out if layer == blk.layers - 1 else self.z_mid
             with self._stage("spmm"):
                 B.spmm(self.rowptr[slot], self.colidx[slot], blk.nnz[t - 1], self.dinv[slot], self.h, dst,

@@ -76,6 +76,9 @@ class BlockTrainer:
         self.g_mid = torch.empty((n, f), dtype=dt, device=dev) if L > 1 else None
         self.dx = torch.empty((T, n, f), dtype=dt, device=dev) if want_dx else None
         self.dw = [torch.zeros((f, f), dtype=torch.float32, device=dev) for _ in range(L)]
+        # with one weight per timestep (Section "EvolveGCN") every timestep has a gradient of its own
+        self.dw_t = ([[torch.zeros((f, f), dtype=torch.float32, device=dev) for _ in range(L)] for _ in range(T)]
+                     if blk.w_t is not None else None)
         max_list = max([int(d[0].numel()) for d in blk.deltas] + [int(d[2].numel()) for d in blk.deltas] + [1, max_list or 0])
         self.ws_rebuild = torch.empty(B.delta_rebuild_workspace(n, cap, max_list, max_list), dtype=torch.uint8, device=dev)
         self.ws_spmm = torch.empty(B.spmm_workspace(n, cap, f), dtype=torch.uint8, device=dev)
@@ -117,7 +120,7 @@ class BlockTrainer:
             cur = blk.x[t - 1]
             for layer in range(blk.layers):
                 with self._stage("feature_transform"):
-                    B.feature_transform(cur, blk.w[layer], self.h, row_scale=self.a.dinv[slot])
+                    B.feature_transform(cur, blk.weight(t, layer), self.h, row_scale=self.a.dinv[slot])
                 with self._stage("spmm"):
                     B.spmm(self.a.rowptr[slot], self.a.colidx[slot], blk.nnz[t - 1], self.a.dinv[slot], self.h,
                            self.z[layer, t - 1], self.ws_spmm, flags=B.DGNN_RELU | B.DGNN_H_PRESCALED)
@@ -162,15 +165,18 @@ class BlockTrainer:
                            flags=B.DGNN_H_PRESCALED)
                 below = blk.x[t - 1] if layer == 0 else self.z[layer - 1, t - 1]
                 with self._stage("weight_grad"):
-                    B.weight_grad(below, self.h, self.dw[layer], self.ws_wgrad, accumulate=not first_call[layer])
+                    if self.dw_t is not None:
+                        B.weight_grad(below, self.h, self.dw_t[t - 1][layer], self.ws_wgrad)
+                    else:
+                        B.weight_grad(below, self.h, self.dw[layer], self.ws_wgrad, accumulate=not first_call[layer])
                 first_call[layer] = False
                 if layer > 0:
                     with self._stage("input_grad"):
-                        B.input_grad(self.h, blk.w[layer], self.g_mid)
+                        B.input_grad(self.h, blk.weight(t, layer), self.g_mid)
                     g_in = self.g_mid
                 elif self.dx is not None:
                     with self._stage("input_grad"):
-                        B.input_grad(self.h, blk.w[0], self.dx[t - 1])
+                        B.input_grad(self.h, blk.weight(t, 0), self.dx[t - 1])
             if t >= 3:   # A_{t-1} from A_t: the same rebuild with the two lists exchanged (A_1 was kept)
                 self._rebuild(self.a, blk.deltas[t - 2], blk.nnz[t - 1], t, t - 1, reverse=True)
                 if self.directed:
@@ -239,7 +245,8 @@ class CheckpointedTrainer:
         a, e = self.bounds[b]
         nnz = list(s.nnz[a:e])
         blk = BlockInputs(n=s.n, T=e - a, f=s.f, layers=s.layers, window=s.window, rowptr1=self.first[b][0],
-                          colidx1=self.first[b][1], deltas=s.deltas[a:e - 1], x=s.x[a:e], w=s.w, nnz=nnz)
+                          colidx1=self.first[b][1], deltas=s.deltas[a:e - 1], x=s.x[a:e], w=s.w,
+                          w_t=s.w_t[a:e] if s.w_t is not None else None, nnz=nnz)
         return blk
 
     def _t_deltas(self, a: int, e: int):

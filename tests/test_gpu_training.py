@@ -147,3 +147,44 @@ def test_checkpointed_training_equals_the_one_block_step(case, bsize):
         if dtype == torch.float32:
             assert_close(to_f64(ck.dw[layer]), dws[layer], dtype, f"{case}: dW of layer {layer}, blocks of {bsize}")
         assert_close(to_f64(ck.dw[layer]), to_f64(one.dw[layer]), torch.float32, f"{case}: blocks vs one block, layer {layer}")
+
+
+def test_one_weight_per_timestep():
+    """Section "EvolveGCN": the GCN weight differs from timestep to timestep; the library takes W per call, the
+    driver passes W_t, and every timestep gets a weight gradient of its own."""
+    from paper_2109_07893_amd.pipeline import BlockRunner
+    wl = replace(WORKLOADS["c3"].scaled(4096, T=4), layers=2, name="c3-evolving")
+    blk = make_block(wl, DEV, gen_device="cpu")
+    blk.w_t = [[glorot_weight(wl, layer, t=t).to(DEV) for layer in range(wl.layers)] for t in range(1, wl.T + 1)]
+    g = DynamicGraph(wl)
+    rp, ci = (x.numpy() for x in g.csr())
+    snaps, acts = [], []
+    for t in range(1, wl.T + 1):
+        if t > 1:
+            rp, ci = oracle.delta_apply(wl.n, rp, ci, *[x.numpy() for x in g.advance()])
+        snaps.append((rp, ci))
+        cur, outs = to_f64(features(wl, t)), []
+        for layer in range(wl.layers):
+            cur = oracle.gcn_layer(rp, ci, cur, to_f64(blk.w_t[t - 1][layer]), relu=True)
+            outs.append(cur)
+        acts.append(outs)
+    runner = BlockRunner(blk, keep_all_z=True)
+    runner.load_first()
+    runner.run_resident()
+    for t in range(wl.T):
+        assert_close(to_f64(runner.z[t]), acts[t][-1], torch.float32, f"forward with W_t, t={t + 1}")
+    tr = make_trainer(wl, blk)
+    tr.forward()
+    stored = [[torch.from_numpy(a).to(torch.float32) for a in outs] for outs in acts]
+    for t in range(wl.T):
+        for layer in range(wl.layers):
+            tr.z[layer, t].copy_(stored[t][layer])
+    g_y = torch.stack([gradient(wl, t) for t in range(1, wl.T + 1)]).to(DEV)
+    tr.backward(g_y)
+    for t in range(wl.T):
+        rp, ci = snaps[t]
+        gin = to_f64(g_y[t])
+        for layer in range(wl.layers - 1, -1, -1):
+            below = to_f64(features(wl, t + 1)) if layer == 0 else to_f64(stored[t][layer - 1])
+            dw, gin = oracle.gcn_layer_backward(rp, ci, below, to_f64(blk.w_t[t][layer]), to_f64(stored[t][layer]), gin)
+            assert_close(to_f64(tr.dw_t[t][layer]), dw, torch.float32, f"dW_t t={t + 1} layer {layer}")
