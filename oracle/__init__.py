@@ -47,6 +47,9 @@ def _load():
         lib.oracle_delta_apply.restype = _i64
         lib.oracle_delta_apply.argtypes = [_i64, _i32p, _i32p, _i32p, _i32p, _i64, _i32p, _i32p, _i64,
                                            _i32p, _i32p, _i64]
+        lib.oracle_delta_apply_weighted.restype = _i64
+        lib.oracle_delta_apply_weighted.argtypes = [_i64, _i32p, _i32p, _f64p, _i32p, _i32p, _f64p, _i64, _i32p, _i32p, _i64,
+                                                    _i32p, _i32p, _f64p, _i64, _i32p, _i32p, _f64p, _i64]
         lib.oracle_gcn_values.restype = None
         lib.oracle_gcn_values.argtypes = [_i64, _i32p, _i32p, _f64p]
         lib.oracle_xw.restype = None
@@ -111,6 +114,27 @@ def delta_apply(n: int, rowptr, colidx, add_row, add_col, del_row, del_col) -> T
     if rc < 0:
         raise ValueError(f"oracle_delta_apply failed: {rc}")
     return rp, ci[:rc].copy()
+
+
+def delta_apply_weighted(n: int, rowptr, colidx, val, add=None, dele=None, upd=None):
+    """Snapshots with a value per stored entry: (prev minus deleted edges, values replaced where `upd` names the
+    edge) plus the added edges with their values.  add = (row, col, val), dele = (row, col), upd = (row, col, val);
+    returns (rowptr, colidx, val) in canonical order."""
+    rowptr, colidx, val = _a(rowptr, np.int32), _a(colidx, np.int32), _a(val, np.float64)
+    e_i, e_f = np.zeros(0, np.int32), np.zeros(0, np.float64)
+    ar, ac, av = (_a(add[0], np.int32), _a(add[1], np.int32), _a(add[2], np.float64)) if add is not None else (e_i, e_i, e_f)
+    dr, dc = (_a(dele[0], np.int32), _a(dele[1], np.int32)) if dele is not None else (e_i, e_i)
+    ur, uc, uv = (_a(upd[0], np.int32), _a(upd[1], np.int32), _a(upd[2], np.float64)) if upd is not None else (e_i, e_i, e_f)
+    cap = int(rowptr[n]) + ar.size + 1
+    rp, ci, vo = np.zeros(n + 1, np.int32), np.zeros(cap, np.int32), np.zeros(cap, np.float64)
+    rc = _load().oracle_delta_apply_weighted(n, _p(rowptr, _i32p), _p(colidx, _i32p), _p(val, _f64p),
+                                             _p(ar, _i32p), _p(ac, _i32p), _p(av, _f64p), ar.size,
+                                             _p(dr, _i32p), _p(dc, _i32p), dr.size,
+                                             _p(ur, _i32p), _p(uc, _i32p), _p(uv, _f64p), ur.size,
+                                             _p(rp, _i32p), _p(ci, _i32p), _p(vo, _f64p), cap)
+    if rc < 0:
+        raise ValueError(f"oracle_delta_apply_weighted failed: {rc}")
+    return rp, ci[:rc].copy(), vo[:rc].copy()
 
 
 def gcn_values(rowptr, colidx) -> np.ndarray:

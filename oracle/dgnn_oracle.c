@@ -125,6 +125,73 @@ int64_t oracle_delta_apply(int64_t n, const int32_t *rowptr, const int32_t *coli
     return rc;
 }
 
+/* ---- snapshots that carry a value per stored entry (Section "Graph-difference Based Input Transfer" ships
+ * the values of the new snapshot next to the two index lists; Section "Smoothening the Input Graphs" is where
+ * values other than 0/1 come from).  A snapshot is then a map (row, col) -> value, and a difference is
+ *   deleted edges, added edges with their values, and surviving edges whose value changes. ---- */
+typedef struct { key_t_ key; double val; } kv_t_;
+
+static int cmp_kv(const void *a, const void *b) {
+    key_t_ x = ((const kv_t_ *)a)->key, y = ((const kv_t_ *)b)->key;
+    return (x > y) - (x < y);
+}
+
+static int64_t find_kv(const kv_t_ *sorted, int64_t m, key_t_ q) {
+    int64_t lo = 0, hi = m;
+    while (lo < hi) { int64_t mid = lo + (hi - lo) / 2; if (sorted[mid].key < q) lo = mid + 1; else hi = mid; }
+    return (lo < m && sorted[lo].key == q) ? lo : -1;
+}
+
+/* next = (prev without the deleted edges, values replaced where the update list names the edge) plus the added
+ * edges with their values.  An added edge that survives from prev takes the added value.  Returns nnz of the
+ * result, or <0 as oracle_delta_apply. */
+int64_t oracle_delta_apply_weighted(int64_t n, const int32_t *rowptr, const int32_t *colidx, const double *val,
+                                    const int32_t *add_row, const int32_t *add_col, const double *add_val, int64_t n_add,
+                                    const int32_t *del_row, const int32_t *del_col, int64_t n_del,
+                                    const int32_t *upd_row, const int32_t *upd_col, const double *upd_val, int64_t n_upd,
+                                    int32_t *rowptr_out, int32_t *colidx_out, double *val_out, int64_t cap) {
+    int64_t nnz = rowptr[n];
+    kv_t_ *all = (kv_t_ *)malloc(sizeof(kv_t_) * (size_t)(nnz + n_add + 1));
+    kv_t_ *add = (kv_t_ *)malloc(sizeof(kv_t_) * (size_t)(n_add + 1));
+    kv_t_ *upd = (kv_t_ *)malloc(sizeof(kv_t_) * (size_t)(n_upd + 1));
+    key_t_ *del = (key_t_ *)malloc(sizeof(key_t_) * (size_t)(n_del + 1));
+    if (!all || !add || !upd || !del) { free(all); free(add); free(upd); free(del); return -3; }
+    for (int64_t i = 0; i < n_add; ++i) { add[i].key = make_key(add_row[i], add_col[i]); add[i].val = add_val[i]; }
+    for (int64_t i = 0; i < n_upd; ++i) { upd[i].key = make_key(upd_row[i], upd_col[i]); upd[i].val = upd_val[i]; }
+    for (int64_t i = 0; i < n_del; ++i) del[i] = make_key(del_row[i], del_col[i]);
+    qsort(add, (size_t)n_add, sizeof(kv_t_), cmp_kv);
+    qsort(upd, (size_t)n_upd, sizeof(kv_t_), cmp_kv);
+    n_del = sort_unique(del, n_del);
+    int64_t m = 0;
+    for (int64_t r = 0; r < n; ++r)
+        for (int64_t e = rowptr[r]; e < rowptr[r + 1]; ++e) {
+            key_t_ k = make_key((int32_t)r, colidx[e]);
+            if (is_member(del, n_del, k)) continue;
+            if (find_kv(add, n_add, k) >= 0) continue;          /* comes back below with the added value */
+            int64_t u = find_kv(upd, n_upd, k);
+            all[m].key = k;
+            all[m].val = u >= 0 ? upd[u].val : val[e];
+            ++m;
+        }
+    for (int64_t i = 0; i < n_add; ++i)
+        if (i == 0 || add[i].key != add[i - 1].key) all[m++] = add[i];
+    qsort(all, (size_t)m, sizeof(kv_t_), cmp_kv);
+    int64_t rc = m <= cap ? m : -1;
+    if (rc >= 0) {
+        for (int64_t r = 0; r <= n; ++r) rowptr_out[r] = 0;
+        for (int64_t i = 0; i < m; ++i) {
+            int64_t r = (int64_t)(all[i].key >> 32), c = (int64_t)(all[i].key & 0xffffffffu);
+            if (r < 0 || r >= n || c < 0 || c >= n) { rc = -2; break; }
+            rowptr_out[r + 1]++;
+            colidx_out[i] = (int32_t)c;
+            val_out[i] = all[i].val;
+        }
+        if (rc >= 0) for (int64_t r = 0; r < n; ++r) rowptr_out[r + 1] += rowptr_out[r];
+    }
+    free(all); free(add); free(upd); free(del);
+    return rc;
+}
+
 /* Eqn (1): explicit value of every stored entry of A~: 1 / sqrt((1+deg_u) (1+deg_v)), where the
  * stored matrix is A + I so that 1 + deg_u is the length of row u. */
 void oracle_gcn_values(int64_t n, const int32_t *rowptr, const int32_t *colidx, double *val) {

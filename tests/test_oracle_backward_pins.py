@@ -148,3 +148,68 @@ def test_relu_grad_masks_where_output_is_zero():
     g = np.array([[1.0, -2.0, 3.0]])
     z = np.array([[0.5, 0.0, 2.0]])
     np.testing.assert_array_equal(oracle.relu_grad(g, z), [[1.0, 0.0, 3.0]])
+
+
+# ----------------------------------------------------------------------------- snapshots that carry values
+def _dense_weighted(n, rp, ci, val):
+    w = np.full((n, n), np.nan)
+    for u in range(n):
+        w[u, ci[rp[u]:rp[u + 1]]] = val[rp[u]:rp[u + 1]]
+    return w
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_weighted_delta_apply_matches_dense_brute_force(seed):
+    """Dense n x n arrays with NaN for "no edge": deleting writes NaN, updating and adding write the value."""
+    n = 40
+    a, rp, ci, rng = _graph(n, 0.12, 100 + seed, False)
+    val = rng.uniform(0.5, 1.5, ci.size)
+    dense = _dense_weighted(n, rp, ci, val)
+    present = np.argwhere(a & ~np.eye(n, dtype=bool))
+    absent = np.argwhere(~a)
+    pick = rng.permutation(len(present))
+    dele = present[pick[:15]]
+    upd = present[pick[15:40]]
+    add = absent[rng.permutation(len(absent))[:20]]
+    add_v, upd_v = rng.uniform(2, 3, len(add)), rng.uniform(4, 5, len(upd))
+    want = dense.copy()
+    want[dele[:, 0], dele[:, 1]] = np.nan
+    want[upd[:, 0], upd[:, 1]] = upd_v
+    want[add[:, 0], add[:, 1]] = add_v
+    # lists in arbitrary order: the oracle does not rely on their order
+    rp2, ci2, v2 = oracle.delta_apply_weighted(n, rp, ci, val, add=(add[:, 0], add[:, 1], add_v),
+                                               dele=(dele[:, 0], dele[:, 1]), upd=(upd[:, 0], upd[:, 1], upd_v))
+    got = _dense_weighted(n, rp2, ci2, v2)
+    assert np.array_equal(np.isnan(got), np.isnan(want))
+    np.testing.assert_array_equal(got[~np.isnan(want)], want[~np.isnan(want)])
+    for u in range(n):
+        assert np.all(np.diff(ci2[rp2[u]:rp2[u + 1]]) > 0)
+    # the structure is what the unweighted rule gives
+    rp3, ci3 = oracle.delta_apply(n, rp, ci, add[:, 0], add[:, 1], dele[:, 0], dele[:, 1])
+    assert np.array_equal(rp2, rp3) and np.array_equal(ci2, ci3)
+    # and it can be undone: re-adding the deleted edges with their old values, deleting the added ones, writing the
+    # old values back
+    back = oracle.delta_apply_weighted(n, rp2, ci2, v2, add=(dele[:, 0], dele[:, 1], dense[dele[:, 0], dele[:, 1]]),
+                                       dele=(add[:, 0], add[:, 1]), upd=(upd[:, 0], upd[:, 1], dense[upd[:, 0], upd[:, 1]]))
+    assert np.array_equal(back[0], rp) and np.array_equal(back[1], ci)
+    np.testing.assert_array_equal(back[2], val)
+
+
+def test_weighted_delta_apply_trivial_cases():
+    n = 5
+    rp, ci = oracle.csr_from_edges(n, [0, 1, 2, 3, 4, 0, 3], [0, 1, 2, 3, 4, 2, 1])
+    val = np.arange(1.0, ci.size + 1)
+    same = oracle.delta_apply_weighted(n, rp, ci, val)
+    assert np.array_equal(same[0], rp) and np.array_equal(same[1], ci) and np.array_equal(same[2], val)
+    only_upd = oracle.delta_apply_weighted(n, rp, ci, val, upd=([0], [2], [9.0]))
+    assert np.array_equal(only_upd[1], ci) and only_upd[2][1] == 9.0 and only_upd[2].sum() == val.sum() - val[1] + 9.0
+
+
+def test_spmm_with_explicit_values_is_a_plain_sparse_product():
+    n = 60
+    a, rp, ci, rng = _graph(n, 0.1, 200, False)
+    val = rng.standard_normal(ci.size)
+    h = rng.standard_normal((n, 4))
+    dense = np.nan_to_num(_dense_weighted(n, rp, ci, val), nan=0.0)
+    np.testing.assert_allclose(oracle.spmm(rp, ci, h, val=val), dense @ h, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(oracle.spmm_t(rp, ci, h, val=val), dense.T @ h, rtol=1e-12, atol=1e-13)
