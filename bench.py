@@ -44,6 +44,8 @@ def parse_args():
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="stop the oracle sample after this much work")
     ap.add_argument("--pinned", action="store_true", help="also time the pass with difference lists in pinned host memory")
     ap.add_argument("--no-train", action="store_true", help="skip the training-step (forward + backward) measurement")
+    ap.add_argument("--weighted", action="store_true",
+                    help="also time one step of the path for snapshots that carry a value per entry")
     ap.add_argument("--natural-labels", action="store_true",
                     help="R-MAT workloads: keep the generator's vertex labels (locality) instead of scrambling them")
     return ap.parse_args()
@@ -111,6 +113,59 @@ def cpu_baseline(wl, blk, first, budget_s):
             "kind": "oracle", "seconds": round(spent, 3),
             "sample": f"timesteps t={done[0]}..{done[-1]} of the same block (rebuild + {len(ws)} GCN layer(s), "
                       f"no M-transform), full graph, {edges} edges"}
+
+
+def weighted_step(args, wl, blk, dev):
+    """A_2 from A_1 with a value per stored entry (values carried, added entries bring theirs, 5 % of the
+    survivors get a new one), then Z = relu(V H) on the rebuilt snapshot: an extra figure."""
+    import torch
+    import paper_2109_07893_amd as dg
+    n, f = blk.n, blk.f
+    gen = torch.Generator(device=dev).manual_seed(wl.seed)
+    nnz1 = blk.nnz[0]
+    ar, ac, dr, dc = blk.deltas[0]
+    val1 = torch.rand(nnz1, generator=gen, device=dev) + 0.5
+    add_val = torch.rand(ar.numel(), generator=gen, device=dev) + 0.5
+    # update list: a seeded 5 % of A_1's entries that are not deleted
+    pos = torch.randint(0, nnz1, (nnz1 // 20,), generator=gen, device=dev).unique()
+    rows = torch.searchsorted(blk.rowptr1.to(torch.int64), pos, right=True) - 1
+    keys = (rows << 32) | blk.colidx1[pos].to(torch.int64)
+    keys = keys[~torch.isin(keys, (dr.to(torch.int64) << 32) | dc.to(torch.int64))]
+    ur, uc = (keys >> 32).to(torch.int32), (keys & 0xffffffff).to(torch.int32)
+    uv = torch.rand(ur.numel(), generator=gen, device=dev) + 2.0
+    cap = blk.nnz[1]
+    rpn = torch.empty(n + 1, dtype=torch.int32, device=dev)
+    cin = torch.empty(cap, dtype=torch.int32, device=dev)
+    vn = torch.empty(cap, dtype=torch.float32, device=dev)
+    ws_r = torch.empty(dg.delta_rebuild_workspace(n, nnz1, ar.numel(), dr.numel()), dtype=torch.uint8, device=dev)
+    ws_s = torch.empty(dg.spmm_workspace(n, cap, f), dtype=torch.uint8, device=dev)
+    h, z = blk.x[1], torch.empty_like(blk.x[1])
+
+    def rebuild():
+        dg.delta_rebuild_weighted(blk.rowptr1, blk.colidx1, val1, nnz1, (ar, ac, add_val), (dr, dc), (ur, uc, uv), rpn, cin,
+                                  vn, ws_r)
+
+    def aggregate():
+        dg.spmm_weighted(rpn, cin, vn, cap, h, z, ws_s, flags=dg.DGNN_RELU)
+
+    out = {}
+    s = h.element_size()
+    for name, fn, byts in (("delta_rebuild_weighted", rebuild, 8 * nnz1 + 8 * cap + 16 * n + 20 * (ar.numel() + dr.numel()) + 12 * ur.numel()),
+                           ("spmm_weighted", aggregate, 8 * cap + 4 * n + 2 * s * n * f)):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        out[name] = {"avg_ms": round(ms, 4), "algorithmic_bytes_per_call": int(byts),
+                     "algorithmic_GBps": round(byts / (ms * 1e-3) / 1e9, 1)}
+    out["lists"] = {"added": int(ar.numel()), "deleted": int(dr.numel()), "value_updates": int(ur.numel())}
+    return out
 
 
 def training_step(args, wl, blk, dev):
@@ -302,6 +357,9 @@ def main():
                                     "whole_snapshot_bytes_per_step": sum(4 * (z + blk.n + 1) for z in blk.nnz[1:])}
 
     progress("per-stage pass done")
+    if args.weighted:
+        out["weighted_step"] = weighted_step(args, wl, blk, dev)
+        progress("weighted step timed")
     if not args.no_train:
         del runner
         torch.cuda.empty_cache()

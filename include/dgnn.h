@@ -169,6 +169,45 @@ int dgnn_mproduct(const void *z, void *y, int64_t T, int64_t n, int32_t f, int32
                   const float *m_band, dgnn_dtype dt, void *stream);
 
 /*
+ * ---- Snapshots that carry a value per stored entry (Section "Graph-difference Based Input Transfer" ships the
+ * values of the new snapshot along with the two index lists; the smoothed graphs of Section "Smoothening the
+ * Input Graphs" are where values other than 0/1 come from).  val[e] belongs to the stored entry colidx[e].
+ * Two ways to get the values of the next snapshot onto the device:
+ *   - as the paper does: rebuild the structure with dgnn_delta_rebuild and copy the whole value array of the new
+ *     snapshot (it is in the canonical entry order, which both sides know);
+ *   - only what changed: dgnn_delta_rebuild_weighted below.
+ */
+
+/*
+ * A_next = (A_prev minus the deleted edges) plus the added edges, as dgnn_delta_rebuild, with values: surviving
+ * entries keep their value unless the update list names them, added entries bring theirs.
+ *   val_prev [nnz_prev], val_next [cap_next]    fp32, must not be the same array
+ *   add_val [n_add]                             values of the added edges (list order)
+ *   upd_row/upd_col/upd_val, n_upd              surviving edges whose value changes, any order; must name
+ *                                               neither deleted nor added edges (entries that are not in A_next
+ *                                               are skipped)
+ * No dinv is produced: the values are the matrix.  Everything else as dgnn_delta_rebuild (same workspace query).
+ */
+int dgnn_delta_rebuild_weighted(int64_t n,
+                                const int32_t *rowptr_prev, const int32_t *colidx_prev, const float *val_prev,
+                                int64_t nnz_prev,
+                                const int32_t *add_row, const int32_t *add_col, const float *add_val, int64_t n_add,
+                                const int32_t *del_row, const int32_t *del_col, int64_t n_del,
+                                const int32_t *upd_row, const int32_t *upd_col, const float *upd_val, int64_t n_upd,
+                                int32_t *rowptr_next, int32_t *colidx_next, float *val_next, int64_t cap_next,
+                                int64_t *nnz_next,
+                                void *ws, size_t ws_bytes, uint32_t flags, int32_t *d_status, void *stream);
+
+/*
+ * Z = sigma?(V H) for a snapshot with explicit values, Z[u] = sum over stored (u,v) of val(u,v) * H[v]
+ * (Eqn (2) with the matrix given entry by entry instead of through Eqn (1)).  flags: DGNN_RELU or 0; everything
+ * else as dgnn_spmm (same workspace query).  The adjoint V^T G is the same call on the transposed snapshot.
+ */
+int dgnn_spmm_weighted(int64_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *val,
+                       const void *h, int32_t f, void *z, dgnn_dtype dt, uint32_t flags,
+                       void *ws, size_t ws_bytes, void *stream);
+
+/*
  * ---- Gradient propagation through the same path (Section "Gradient Checkpoint": a block is run forward
  * again and gradients then travel through it in the reverse direction).  For one GCN layer
  *     H = X W,  P = A~ H,  Z = max(P, 0),  Y = Z x_1 M

@@ -24,6 +24,7 @@ DGNN_H_PRESCALED = 2
 EXPORTS = (
     "dgnn_strerror", "dgnn_csr_dinv", "dgnn_delta_h2d", "dgnn_delta_rebuild_workspace",
     "dgnn_delta_rebuild", "dgnn_feature_transform", "dgnn_spmm_workspace", "dgnn_spmm", "dgnn_mproduct",
+    "dgnn_delta_rebuild_weighted", "dgnn_spmm_weighted",
     "dgnn_mproduct_backward", "dgnn_mproduct_block", "dgnn_mproduct_backward_block", "dgnn_relu_backward", "dgnn_weight_grad_workspace", "dgnn_weight_grad", "dgnn_input_grad",
 )
 
@@ -79,6 +80,10 @@ def load_library():
     lib.dgnn_spmm.argtypes = [_i64, _i64, _vp, _vp, _vp, _vp, _i32, _vp, ctypes.c_int, _u32, _vp, _sz, _vp]
     lib.dgnn_mproduct.argtypes = [_vp, _vp, _i64, _i64, _i32, _i32, _vp, ctypes.c_int, _vp]
     lib.dgnn_mproduct_backward.argtypes = [_vp, _vp, _i64, _i64, _i32, _i32, _vp, ctypes.c_int, _vp]
+    lib.dgnn_delta_rebuild_weighted.argtypes = [_i64, _vp, _vp, _vp, _i64, _vp, _vp, _vp, _i64, _vp, _vp, _i64,
+                                                _vp, _vp, _vp, _i64, _vp, _vp, _vp, _i64, ctypes.POINTER(_i64),
+                                                _vp, _sz, _u32, _vp, _vp]
+    lib.dgnn_spmm_weighted.argtypes = [_i64, _i64, _vp, _vp, _vp, _vp, _i32, _vp, ctypes.c_int, _u32, _vp, _sz, _vp]
     lib.dgnn_mproduct_block.argtypes = [_vp, _vp, _i64, _i64, _i32, _i32, _vp, _i64, _vp, _i64, ctypes.c_int, _vp]
     lib.dgnn_mproduct_backward_block.argtypes = [_vp, _vp, _i64, _i64, _i32, _i32, _vp, _i64, _vp, _i64, ctypes.c_int, _vp]
     lib.dgnn_relu_backward.argtypes = [_vp, _vp, _vp, _vp, _i64, _i32, ctypes.c_int, _vp]
@@ -216,6 +221,40 @@ def mproduct(z: torch.Tensor, y: torch.Tensor, w: int, m_band: Optional[torch.Te
         if m_band.numel() != T * w:
             raise ValueError("m_band must be [T, w]")
     _check(load_library().dgnn_mproduct(_ptr(z), _ptr(y), T, n, f, w, _ptr(m_band), dt, _stream(z)), "dgnn_mproduct")
+
+
+def delta_rebuild_weighted(rowptr_prev, colidx_prev, val_prev, nnz_prev: int, add, dele, upd,
+                           rowptr_next, colidx_next, val_next, ws, flags: int = 0, d_status=None) -> int:
+    """Snapshots with values: add = (row, col, val), dele = (row, col), upd = (row, col, val) device tensors
+    (or None); returns nnz of A_next."""
+    n = rowptr_prev.numel() - 1
+    ar, ac, av = add if add is not None else (None, None, None)
+    dr, dc = dele if dele is not None else (None, None)
+    ur, uc, uv = upd if upd is not None else (None, None, None)
+    cnt = lambda t: 0 if t is None else int(t.numel())
+    for t in (val_prev, val_next, av, uv):
+        if t is not None:
+            _need(t, torch.float32, "values")
+    nnz_next = _i64(0)
+    rc = load_library().dgnn_delta_rebuild_weighted(
+        n, _ptr(rowptr_prev), _ptr(colidx_prev), _ptr(val_prev), nnz_prev, _ptr(ar), _ptr(ac), _ptr(av), cnt(ar),
+        _ptr(dr), _ptr(dc), cnt(dr), _ptr(ur), _ptr(uc), _ptr(uv), cnt(ur), _ptr(rowptr_next), _ptr(colidx_next),
+        _ptr(val_next), min(colidx_next.numel(), val_next.numel()), ctypes.byref(nnz_next), _ptr(ws),
+        ws.numel() * ws.element_size(), flags, _ptr(d_status), _stream(rowptr_prev))
+    _check(rc, "dgnn_delta_rebuild_weighted")
+    return int(nnz_next.value)
+
+
+def spmm_weighted(rowptr, colidx, val, nnz: int, h: torch.Tensor, z: torch.Tensor, ws, flags: int = 0) -> None:
+    """Z = sigma?(V H) with one explicit value per stored entry."""
+    _need(rowptr, torch.int32, "rowptr"); _need(colidx, torch.int32, "colidx"); _need(val, torch.float32, "val")
+    dt = _dtype_code(h)
+    n, f = h.shape
+    if rowptr.numel() != n + 1 or tuple(z.shape) != (n, f) or z.dtype != h.dtype or colidx.numel() < nnz or val.numel() < nnz:
+        raise ValueError("shape mismatch in spmm_weighted")
+    _check(load_library().dgnn_spmm_weighted(n, nnz, _ptr(rowptr), _ptr(colidx), _ptr(val), _ptr(h), f, _ptr(z), dt,
+                                             flags, _ptr(ws), ws.numel() * ws.element_size(), _stream(h)),
+           "dgnn_spmm_weighted")
 
 
 def mproduct_backward(g_y: torch.Tensor, g_z: torch.Tensor, w: int, m_band: Optional[torch.Tensor] = None) -> None:

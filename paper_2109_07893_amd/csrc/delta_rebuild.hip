@@ -181,12 +181,16 @@ __device__ __forceinline__ int lds_bound(const int *a, int lo, int hi, int key) 
 //     at the start of the range and simply advances by what each sub-tile wrote.
 // Lane l owns entries l, l + 64, ... of the sub-tile, so loads and stores coalesce; the column
 // indices of the next sub-tile are fetched while this one is placed.
+// VALUES: every stored entry carries a value, which travels with its column index (same position); added
+// entries bring theirs.
+template <bool VALUES>
 __global__ __launch_bounds__(kWave) void merge_kernel(
     int n, const int32_t *__restrict__ rowptr_prev, const int32_t *__restrict__ colidx_prev, int nnz_prev, int range_len,
     const int32_t *__restrict__ add_col, const int2 *__restrict__ add_ext, int n_add,
     const int32_t *__restrict__ del_col, const int2 *__restrict__ del_ext, int n_del,
     const int32_t *__restrict__ rowptr_next, const int32_t *__restrict__ add_ptr,
-    int32_t *__restrict__ colidx_next, int cap_next) {
+    int32_t *__restrict__ colidx_next, int cap_next,
+    const float *__restrict__ val_prev, const float *__restrict__ add_val, float *__restrict__ val_next) {
     __shared__ int s_col[kSub];
     __shared__ int s_mark[kSub + kWave];    // bit 0: deleted; bits 1..: added entries that go right before this slot
     __shared__ int s_start[kSub + kWave];   // outputs (kept + added) that precede the slot's block
@@ -196,10 +200,12 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
     const int e_end = (int)min((int64_t)e_begin + range_len, (int64_t)nnz_prev);
 
     int c_next[kPerLane];
+    float v_next[VALUES ? kPerLane : 1];
 #pragma unroll
     for (int j = 0; j < kPerLane; ++j) {
         const int i = e_begin + lane + j * kWave;
         c_next[j] = i < e_end ? colidx_prev[i] : 0;
+        if (VALUES) v_next[j] = i < e_end ? val_prev[i] : 0.0f;
     }
 
     // ---- start of the range: its row, the list cursors, the first output position
@@ -256,9 +262,11 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
         const int e_stop = min(e + kSub, e_end);
         const int cnt = e_stop - e;
         int c_[kPerLane];
+        float v_[VALUES ? kPerLane : 1];
 #pragma unroll
         for (int j = 0; j < kPerLane; ++j) {
             c_[j] = c_next[j];
+            if (VALUES) v_[j] = v_next[j];
             s_col[lane + j * kWave] = c_[j];
             s_mark[lane + j * kWave] = 0;
         }
@@ -267,7 +275,11 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
         for (int j = 0; j < kPerLane; ++j) {      // fetched while this sub-tile is placed
             const int i = e_stop + lane + j * kWave;
             c_next[j] = i < e_end ? colidx_prev[i] : 0;
+            if (VALUES) v_next[j] = i < e_end ? val_prev[i] : 0.0f;
         }
+        // the values of the (at most 64) added entries placed first in this sub-tile, fetched ahead of their use
+        float av_first = 0.0f;
+        if (VALUES && n_add > 0) av_first = add_val[min(a_cur + lane, n_add - 1)];
         __syncthreads();
 
         // ---- deleted entries: mark the old entry dead.  The first 64 are in registers already; a sub-tile
@@ -356,13 +368,16 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
             if (p < cnt) {
                 const int mk = s_mark[p];
                 const unsigned pos = (unsigned)(base + s_start[p] + (mk >> 1));
-                if (!(mk & 1) && pos < (unsigned)cap_next) colidx_next[pos] = c_[j];
+                if (!(mk & 1) && pos < (unsigned)cap_next) {
+                    colidx_next[pos] = c_[j];
+                    if (VALUES) val_next[pos] = v_[j];
+                }
             }
         }
         // ---- added entries: their slot, then the rank among the adds of the same slot (they are consecutive).
         // The first 64 kept their slot and column from the search above; more than 64 per sub-tile are rare.
         int q_carry = -1, rank_carry = 0;
-        auto place = [&](int j, int q, int c) {
+        auto place = [&](int j, int q, int c, float v) {
             const int q_left = __shfl_up(q, 1, kWave);
             const bool head = lane == 0 ? q != q_carry : q != q_left;
             const unsigned long long true_heads = __ballot(head);
@@ -372,27 +387,49 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
             if (run_start == 0 && !(true_heads & 1ull)) rank += rank_carry;   // run continues from the previous 64
             if (j < a_cur) {
                 const unsigned pos = (unsigned)(base + s_start[q] + rank);
-                if (pos < (unsigned)cap_next) colidx_next[pos] = c;
+                if (pos < (unsigned)cap_next) {
+                    colidx_next[pos] = c;
+                    if (VALUES) val_next[pos] = v;
+                }
             }
             q_carry = __shfl(q, kWave - 1, kWave);
             rank_carry = __shfl(rank, kWave - 1, kWave) + 1;
         };
-        if (a_tile < a_cur) place(a_tile + lane, q_first, c_first);
+        if (a_tile < a_cur) place(a_tile + lane, q_first, c_first, av_first);
 #pragma unroll 1
         for (int j0 = a_tile + kWave; j0 < a_cur; j0 += kWave) {
             const int j = j0 + lane;
             int q = -2 - lane, c = 0;
+            float v = 0.0f;
             if (j < a_cur) {
                 const int2 x = add_ext[j];
                 c = add_col[j];
+                if (VALUES) v = add_val[j];
                 const int lo = max(x.x - e, 0), hi = min(x.y - e, cnt);
                 q = lds_bound<true>(s_col, lo, hi, c);
             }
-            place(j, q, c);
+            place(j, q, c, v);
         }
         base += written;
         __syncthreads();           // LDS is rewritten by the next sub-tile
     }
+}
+
+// Surviving entries whose value changes: one thread per listed entry finds it in its (new) row and overwrites
+// the value.  Entries that are not there are skipped.
+__global__ __launch_bounds__(256) void update_values_kernel(int n, const int32_t *__restrict__ rowptr,
+                                                            const int32_t *__restrict__ colidx,
+                                                            const int32_t *__restrict__ upd_row,
+                                                            const int32_t *__restrict__ upd_col,
+                                                            const float *__restrict__ upd_val, int n_upd,
+                                                            float *__restrict__ val) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= n_upd) return;
+    const int r = upd_row[j], c = upd_col[j];
+    if ((unsigned)r >= (unsigned)n) return;
+    const int lo = rowptr[r], hi = rowptr[r + 1];
+    const int p = lower_bound(colidx, lo, hi, c);
+    if (p < hi && colidx[p] == c) val[p] = upd_val[j];
 }
 
 // One thread per difference entry (added first, then deleted), then one per row of A_prev.
@@ -486,17 +523,24 @@ extern "C" int dgnn_delta_rebuild_workspace(int64_t n, int64_t nnz_prev, int64_t
     return DGNN_OK;
 }
 
-extern "C" int dgnn_delta_rebuild(int64_t n,
-                                  const int32_t *rowptr_prev, const int32_t *colidx_prev, int64_t nnz_prev,
-                                  const int32_t *add_row, const int32_t *add_col, int64_t n_add,
-                                  const int32_t *del_row, const int32_t *del_col, int64_t n_del,
-                                  int32_t *rowptr_next, int32_t *colidx_next, int64_t cap_next, int64_t *nnz_next,
-                                  float *dinv_next,
-                                  void *ws, size_t ws_bytes, uint32_t flags, int32_t *d_status, void *stream) {
+namespace {
+
+struct Values {
+    const float *prev;
+    const float *add;
+    float *next;
+};
+
+int rebuild(int64_t n, const int32_t *rowptr_prev, const int32_t *colidx_prev, int64_t nnz_prev,
+            const int32_t *add_row, const int32_t *add_col, int64_t n_add,
+            const int32_t *del_row, const int32_t *del_col, int64_t n_del,
+            int32_t *rowptr_next, int32_t *colidx_next, int64_t cap_next, int64_t *nnz_next, float *dinv_next,
+            const Values *vals, void *ws, size_t ws_bytes, uint32_t flags, int32_t *d_status, void *stream) {
     if (!rowptr_prev || !colidx_prev || !rowptr_next || !colidx_next || !ws) return DGNN_ERR_NULL;
     if (n_add < 0 || n_del < 0) return DGNN_ERR_SHAPE;
     if (n_add > 0 && (!add_row || !add_col)) return DGNN_ERR_NULL;
     if (n_del > 0 && (!del_row || !del_col)) return DGNN_ERR_NULL;
+    if (vals && (!vals->prev || !vals->next || (n_add > 0 && !vals->add))) return DGNN_ERR_NULL;
     if (n <= 0 || nnz_prev <= 0 || (flags & ~DGNN_VALIDATE)) return DGNN_ERR_SHAPE;
     if (!fits_i32(n + 1) || !fits_i32(nnz_prev + n_add)) return DGNN_ERR_OVERFLOW;
     const int64_t nnz_new = nnz_prev + n_add - n_del;
@@ -507,6 +551,7 @@ extern "C" int dgnn_delta_rebuild(int64_t n,
     if (rc != DGNN_OK) return rc;
     if (ws_bytes < need) return DGNN_ERR_CAPACITY;
     if (rowptr_next == rowptr_prev || colidx_next == colidx_prev) return DGNN_ERR_ALIAS;
+    if (vals && vals->next == vals->prev) return DGNN_ERR_ALIAS;
     if (nnz_next) *nnz_next = nnz_new;
 
     hipStream_t s = (hipStream_t)stream;
@@ -535,9 +580,50 @@ extern "C" int dgnn_delta_rebuild(int64_t n,
     int64_t range_len = (nnz_prev + kTargetWaves - 1) / kTargetWaves;
     range_len = (range_len + kSub - 1) / kSub * kSub;
     if (range_len > kMaxRange) range_len = kMaxRange;
-    hipLaunchKernelGGL(merge_kernel, dim3((unsigned)((nnz_prev + range_len - 1) / range_len)), dim3(kWave), 0, s,
-                       (int)n, rowptr_prev, colidx_prev, (int)nnz_prev, (int)range_len, add_col, add_ext, (int)n_add, del_col, del_ext,
-                       (int)n_del, rowptr_next, add_ptr, colidx_next, cap);
+    const dim3 grid((unsigned)((nnz_prev + range_len - 1) / range_len));
+    if (vals)
+        hipLaunchKernelGGL(merge_kernel<true>, grid, dim3(kWave), 0, s, (int)n, rowptr_prev, colidx_prev, (int)nnz_prev,
+                           (int)range_len, add_col, add_ext, (int)n_add, del_col, del_ext, (int)n_del, rowptr_next, add_ptr,
+                           colidx_next, cap, vals->prev, vals->add, vals->next);
+    else
+        hipLaunchKernelGGL(merge_kernel<false>, grid, dim3(kWave), 0, s, (int)n, rowptr_prev, colidx_prev, (int)nnz_prev,
+                           (int)range_len, add_col, add_ext, (int)n_add, del_col, del_ext, (int)n_del, rowptr_next, add_ptr,
+                           colidx_next, cap, nullptr, nullptr, nullptr);
+    DGNN_RETURN_IF_LAUNCH_FAILED();
+    return DGNN_OK;
+}
+
+}  // namespace
+
+extern "C" int dgnn_delta_rebuild(int64_t n,
+                                  const int32_t *rowptr_prev, const int32_t *colidx_prev, int64_t nnz_prev,
+                                  const int32_t *add_row, const int32_t *add_col, int64_t n_add,
+                                  const int32_t *del_row, const int32_t *del_col, int64_t n_del,
+                                  int32_t *rowptr_next, int32_t *colidx_next, int64_t cap_next, int64_t *nnz_next,
+                                  float *dinv_next,
+                                  void *ws, size_t ws_bytes, uint32_t flags, int32_t *d_status, void *stream) {
+    return rebuild(n, rowptr_prev, colidx_prev, nnz_prev, add_row, add_col, n_add, del_row, del_col, n_del, rowptr_next,
+                   colidx_next, cap_next, nnz_next, dinv_next, nullptr, ws, ws_bytes, flags, d_status, stream);
+}
+
+extern "C" int dgnn_delta_rebuild_weighted(int64_t n,
+                                           const int32_t *rowptr_prev, const int32_t *colidx_prev, const float *val_prev,
+                                           int64_t nnz_prev,
+                                           const int32_t *add_row, const int32_t *add_col, const float *add_val, int64_t n_add,
+                                           const int32_t *del_row, const int32_t *del_col, int64_t n_del,
+                                           const int32_t *upd_row, const int32_t *upd_col, const float *upd_val, int64_t n_upd,
+                                           int32_t *rowptr_next, int32_t *colidx_next, float *val_next, int64_t cap_next,
+                                           int64_t *nnz_next,
+                                           void *ws, size_t ws_bytes, uint32_t flags, int32_t *d_status, void *stream) {
+    if (n_upd < 0) return DGNN_ERR_SHAPE;
+    if (n_upd > 0 && (!upd_row || !upd_col || !upd_val)) return DGNN_ERR_NULL;
+    if (!fits_i32(n_upd)) return DGNN_ERR_OVERFLOW;
+    const Values vals{val_prev, add_val, val_next};
+    const int rc = rebuild(n, rowptr_prev, colidx_prev, nnz_prev, add_row, add_col, n_add, del_row, del_col, n_del,
+                           rowptr_next, colidx_next, cap_next, nnz_next, nullptr, &vals, ws, ws_bytes, flags, d_status, stream);
+    if (rc != DGNN_OK || n_upd == 0) return rc;
+    hipLaunchKernelGGL(update_values_kernel, dim3((unsigned)((n_upd + 255) / 256)), dim3(256), 0, (hipStream_t)stream, (int)n,
+                       rowptr_next, colidx_next, upd_row, upd_col, upd_val, (int)n_upd, val_next);
     DGNN_RETURN_IF_LAUNCH_FAILED();
     return DGNN_OK;
 }

@@ -98,13 +98,13 @@ __device__ __forceinline__ void zero_row(char *z, int64_t row) {
     for (int s = 0; s < LPR; ++s) Piece<BF16>::store(z + row * (LPR * 16) + s * 16, zero);
 }
 
-// LPR: lanes per feature row.  SCALE_V: multiply every gathered row by dinv of its column
-// (otherwise H already carries it).
+// LPR: lanes per feature row.  SCALE_V: multiply every gathered row by a per-entry factor: dinv of its
+// column, or the entry's own value when the snapshot carries values (otherwise H already carries the factor).
 template <int LPR, bool BF16, bool SCALE_V>
 __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) void spmm_stream_kernel(
     int n, int nnz, int range_len, int n_ranges, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
     const float *__restrict__ dinv, const char *__restrict__ h, char *__restrict__ z, int relu,
-    RangeRec *__restrict__ recs, float *__restrict__ carry) {
+    RangeRec *__restrict__ recs, float *__restrict__ carry, const float *__restrict__ vals) {
     typedef typename Piece<BF16>::Raw Raw;
     constexpr int NV = Piece<BF16>::kVals;
     constexpr int F = LPR * NV;
@@ -158,7 +158,8 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) v
 #pragma unroll
             for (int i = 0; i < CPL; ++i) {
                 const int idx = e0 + g * kPer + sub * CPL + i;
-                d_next[i] = idx < e_end ? dinv[c_next[i]] : 0.0f;
+                // an explicit value per stored entry (one coalesced stream), else dinv of the entry's column
+                d_next[i] = idx < e_end ? (vals ? vals[idx] : dinv[c_next[i]]) : 0.0f;
             }
         }
     };
@@ -513,17 +514,17 @@ size_t workspace_layout(int64_t nnz, int32_t f, Workspace *ws, void *base) {
 
 template <int LPR, bool BF16>
 int launch(int64_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *dinv, bool scale_v,
-           const void *h, void *z, int relu, const Workspace &ws, hipStream_t s) {
+           const void *h, void *z, int relu, const Workspace &ws, hipStream_t s, const float *vals = nullptr) {
     constexpr int G = 256 / LPR;
     const int range_len = range_length(nnz, (kWave / LPR) * kPer);
     const int ranges = (int)((nnz + range_len - 1) / range_len);
     const int grid = (ranges + kXcds * kXcdChunk - 1) / (kXcds * kXcdChunk) * (kXcds * kXcdChunk);   // whole chunk rounds
     if (scale_v)
         hipLaunchKernelGGL((spmm_stream_kernel<LPR, BF16, true>), dim3(grid), dim3(kWave), 0, s, (int)n, (int)nnz, range_len, ranges,
-                           rowptr, colidx, dinv, static_cast<const char *>(h), static_cast<char *>(z), relu, ws.recs, ws.carry);
+                           rowptr, colidx, dinv, static_cast<const char *>(h), static_cast<char *>(z), relu, ws.recs, ws.carry, vals);
     else
         hipLaunchKernelGGL((spmm_stream_kernel<LPR, BF16, false>), dim3(grid), dim3(kWave), 0, s, (int)n, (int)nnz, range_len, ranges,
-                           rowptr, colidx, dinv, static_cast<const char *>(h), static_cast<char *>(z), relu, ws.recs, ws.carry);
+                           rowptr, colidx, dinv, static_cast<const char *>(h), static_cast<char *>(z), relu, ws.recs, ws.carry, vals);
     DGNN_RETURN_IF_LAUNCH_FAILED();
     hipLaunchKernelGGL((spmm_carry_kernel<LPR, BF16>), dim3((ranges + G - 1) / G), dim3(256), 0, s, ranges, ws.recs,
                        ws.carry, dinv, static_cast<char *>(z), relu);
@@ -541,11 +542,13 @@ extern "C" int dgnn_spmm_workspace(int64_t n, int64_t nnz, int32_t f, size_t *by
     return DGNN_OK;
 }
 
-extern "C" int dgnn_spmm(int64_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *dinv,
-                         const void *h, int32_t f, void *z, dgnn_dtype dt, uint32_t flags,
-                         void *ws, size_t ws_bytes, void *stream) {
+namespace {
+
+int spmm(int64_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *dinv, const float *vals,
+         const void *h, int32_t f, void *z, dgnn_dtype dt, uint32_t flags, uint32_t allowed, void *ws, size_t ws_bytes,
+         void *stream) {
     if (!rowptr || !colidx || !h || !z || !ws) return DGNN_ERR_NULL;
-    if (n <= 0 || nnz <= 0 || !supported_width(f) || (flags & ~(DGNN_RELU | DGNN_H_PRESCALED))) return DGNN_ERR_SHAPE;
+    if (n <= 0 || nnz <= 0 || !supported_width(f) || (flags & ~allowed)) return DGNN_ERR_SHAPE;
     if (dt != DGNN_F32 && dt != DGNN_BF16) return DGNN_ERR_SHAPE;
     if (!fits_i32(n + 1) || !fits_i32(nnz)) return DGNN_ERR_OVERFLOW;
     if (!aligned16(h) || !aligned16(z) || !aligned16(ws)) return DGNN_ERR_ALIGN;
@@ -554,18 +557,33 @@ extern "C" int dgnn_spmm(int64_t n, int64_t nnz, const int32_t *rowptr, const in
     if (ws_bytes < workspace_layout(nnz, f, &w, ws)) return DGNN_ERR_CAPACITY;
     hipStream_t s = (hipStream_t)stream;
     const int relu = (flags & DGNN_RELU) ? 1 : 0;
-    const bool scale_v = dinv != nullptr && !(flags & DGNN_H_PRESCALED);
+    const bool scale_v = vals != nullptr || (dinv != nullptr && !(flags & DGNN_H_PRESCALED));
     const int lpr = dt == DGNN_F32 ? f / 4 : f / 8;   // lanes per feature row, 16 bytes each
     const bool bf = dt == DGNN_BF16;
     switch (lpr) {
-        case 2: return launch<2, true>(n, nnz, rowptr, colidx, dinv, scale_v, h, z, relu, w, s);
-        case 4: return bf ? launch<4, true>(n, nnz, rowptr, colidx, dinv, scale_v, h, z, relu, w, s)
-                          : launch<4, false>(n, nnz, rowptr, colidx, dinv, scale_v, h, z, relu, w, s);
-        case 8: return bf ? launch<8, true>(n, nnz, rowptr, colidx, dinv, scale_v, h, z, relu, w, s)
-                          : launch<8, false>(n, nnz, rowptr, colidx, dinv, scale_v, h, z, relu, w, s);
-        case 16: return bf ? launch<16, true>(n, nnz, rowptr, colidx, dinv, scale_v, h, z, relu, w, s)
-                           : launch<16, false>(n, nnz, rowptr, colidx, dinv, scale_v, h, z, relu, w, s);
-        case 32: return launch<32, false>(n, nnz, rowptr, colidx, dinv, scale_v, h, z, relu, w, s);
+        case 2: return launch<2, true>(n, nnz, rowptr, colidx, dinv, scale_v, h, z, relu, w, s, vals);
+        case 4: return bf ? launch<4, true>(n, nnz, rowptr, colidx, dinv, scale_v, h, z, relu, w, s, vals)
+                          : launch<4, false>(n, nnz, rowptr, colidx, dinv, scale_v, h, z, relu, w, s, vals);
+        case 8: return bf ? launch<8, true>(n, nnz, rowptr, colidx, dinv, scale_v, h, z, relu, w, s, vals)
+                          : launch<8, false>(n, nnz, rowptr, colidx, dinv, scale_v, h, z, relu, w, s, vals);
+        case 16: return bf ? launch<16, true>(n, nnz, rowptr, colidx, dinv, scale_v, h, z, relu, w, s, vals)
+                           : launch<16, false>(n, nnz, rowptr, colidx, dinv, scale_v, h, z, relu, w, s, vals);
+        case 32: return launch<32, false>(n, nnz, rowptr, colidx, dinv, scale_v, h, z, relu, w, s, vals);
         default: return DGNN_ERR_SHAPE;
     }
+}
+
+}  // namespace
+
+extern "C" int dgnn_spmm(int64_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *dinv,
+                         const void *h, int32_t f, void *z, dgnn_dtype dt, uint32_t flags,
+                         void *ws, size_t ws_bytes, void *stream) {
+    return spmm(n, nnz, rowptr, colidx, dinv, nullptr, h, f, z, dt, flags, DGNN_RELU | DGNN_H_PRESCALED, ws, ws_bytes, stream);
+}
+
+extern "C" int dgnn_spmm_weighted(int64_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *val,
+                                  const void *h, int32_t f, void *z, dgnn_dtype dt, uint32_t flags,
+                                  void *ws, size_t ws_bytes, void *stream) {
+    if (!val) return DGNN_ERR_NULL;
+    return spmm(n, nnz, rowptr, colidx, nullptr, val, h, f, z, dt, flags, DGNN_RELU, ws, ws_bytes, stream);
 }

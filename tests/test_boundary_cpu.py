@@ -163,3 +163,21 @@ def test_backward_argument_errors(lib):
     f = lib.dgnn_mproduct_backward_block
     assert f(FAKE, FAKE, 8, 10, 16, 3, None, 0, FAKE + (1 << 20), 3, 0, None) == -2
     assert f(FAKE, FAKE + (1 << 20), 8, 10, 16, 3, None, 0, FAKE + (1 << 20), 2, 0, None) == -5   # output over the hand-over
+
+
+def test_weighted_argument_errors(lib):
+    nn = ctypes.c_int64(0)
+
+    def call(n=10, rp=FAKE, ci=FAKE, vp=FAKE, nnz=20, ar=FAKE, ac=FAKE, av=FAKE, na=2, dr=FAKE, dc=FAKE, nd=1, ur=FAKE,
+             uc=FAKE, uv=FAKE, nu=1, rpn=FAKE + 64, cin=FAKE + 128, vn=FAKE + 256, cap=64, ws=FAKE + 512, wsb=1 << 20):
+        return lib.dgnn_delta_rebuild_weighted(n, rp, ci, vp, nnz, ar, ac, av, na, dr, dc, nd, ur, uc, uv, nu, rpn, cin, vn,
+                                               cap, ctypes.byref(nn), ws, wsb, 0, None, None)
+
+    assert call(vp=None) == -1 and call(vn=None) == -1 and call(av=None) == -1 and call(uv=None) == -1
+    assert call(nu=-1) == -2 and call(n=0) == -2
+    assert call(cap=20) == -3
+    assert call(vn=FAKE) == -5
+    f = lib.dgnn_spmm_weighted
+    assert f(10, 20, FAKE, FAKE, None, FAKE, 32, FAKE + 4096, 0, 0, FAKE + 8192, 1 << 24, None) == -1
+    assert f(10, 20, FAKE, FAKE, FAKE, FAKE, 32, FAKE + 4096, 0, 2, FAKE + 8192, 1 << 24, None) == -2   # no pre-scaled mode
+    assert f(10, 20, FAKE, FAKE, FAKE, FAKE, 32, FAKE, 0, 0, FAKE + 8192, 1 << 24, None) == -5

@@ -1,0 +1,121 @@
+"""GPU parity of the entry points for snapshots that carry a value per stored entry (Section "Graph-difference
+Based Input Transfer": the values of the new snapshot travel with the index lists) against the CPU oracle:
+structure and carried values bit for bit, aggregation within the floating-point bound."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2109_07893_amd as dg
+from dtdg_synth import WORKLOADS, DynamicGraph
+from helpers import assert_close, to_f64
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def dev(a, dtype):
+    return torch.as_tensor(np.ascontiguousarray(a), dtype=dtype).to(DEV)
+
+
+def gpu_rebuild_weighted(n, rp, ci, val, add, dele, upd):
+    """add/dele/upd as numpy tuples sorted by (row, col) (upd in any order); returns numpy (rowptr, colidx, val)."""
+    nnz_prev = int(ci.size)
+    n_add, n_del = int(add[0].size), int(dele[0].size)
+    cap = nnz_prev + n_add - n_del + 5
+    rpn = torch.full((n + 1,), -7, dtype=torch.int32, device=DEV)
+    cin = torch.full((cap,), -7, dtype=torch.int32, device=DEV)
+    vn = torch.full((cap,), float("nan"), dtype=torch.float32, device=DEV)
+    ws = torch.empty(dg.delta_rebuild_workspace(n, nnz_prev, n_add, n_del), dtype=torch.uint8, device=DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    nnz = dg.delta_rebuild_weighted(
+        dev(rp, torch.int32), dev(ci, torch.int32), dev(val, torch.float32), nnz_prev,
+        (dev(add[0], torch.int32), dev(add[1], torch.int32), dev(add[2], torch.float32)) if n_add else None,
+        (dev(dele[0], torch.int32), dev(dele[1], torch.int32)) if n_del else None,
+        (dev(upd[0], torch.int32), dev(upd[1], torch.int32), dev(upd[2], torch.float32)) if upd[0].size else None,
+        rpn, cin, vn, ws, flags=dg.DGNN_VALIDATE, d_status=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    assert torch.isnan(vn[nnz:]).all() and (cin[nnz:] == -7).all()      # nothing written beyond the result
+    return rpn.cpu().numpy(), cin.cpu().numpy()[:nnz], vn.cpu().numpy()[:nnz]
+
+
+def f32(x):
+    return np.asarray(x, dtype=np.float32)
+
+
+def step_lists(wl_graph, rng, upd_frac):
+    """One step of the generator's structure plus seeded values: returns (add, dele, upd) for the current snapshot."""
+    keys_before = wl_graph.keys.clone()
+    ar, ac, dr, dc = (x.numpy() for x in wl_graph.advance())
+    kb = keys_before.numpy()
+    deleted = (dr.astype(np.int64) << 32) | dc.astype(np.int64)
+    surv = kb[~np.isin(kb, deleted)]
+    surv = surv[(surv >> 32) != (surv & 0xffffffff)]
+    pick = rng.permutation(surv.size)[: int(upd_frac * surv.size)]
+    ur, uc = (surv[pick] >> 32).astype(np.int32), (surv[pick] & 0xffffffff).astype(np.int32)
+    return ((ar, ac, f32(rng.uniform(1, 2, ar.size))), (dr, dc), (ur, uc, f32(rng.uniform(3, 4, ur.size))))
+
+
+@pytest.mark.parametrize("name,n,upd_frac", [("c1", 1000, 0.1), ("c3", 1 << 14, 0.05), ("c3", 1 << 14, 0.0), ("c2", 30_000, 0.3)])
+def test_weighted_rebuild_chain(name, n, upd_frac):
+    wl = WORKLOADS[name].scaled(n, T=5) if n != WORKLOADS[name].n else WORKLOADS[name]
+    g = DynamicGraph(wl)
+    rng = np.random.default_rng(n)
+    rp, ci = (x.numpy() for x in g.csr())
+    val = f32(rng.uniform(0.1, 1.0, ci.size))
+    for t in range(2, 6):
+        add, dele, upd = step_lists(g, rng, upd_frac)
+        want = oracle.delta_apply_weighted(wl.n, rp, ci, val, add=add, dele=dele, upd=upd)
+        got = gpu_rebuild_weighted(wl.n, rp, ci, val, add, dele, upd)
+        assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1]), (name, t)
+        assert np.array_equal(got[2], f32(want[2])), (name, t)                 # values are carried, not computed
+        rp, ci, val = got
+
+
+def test_weighted_rebuild_edge_cases():
+    n = 6
+    base = [(u, u) for u in range(n)] + [(0, 1), (0, 5), (1, 0), (2, 3), (2, 4), (2, 5), (5, 0), (5, 4)]
+    rows = np.array([p[0] for p in sorted(base)], np.int32)
+    cols = np.array([p[1] for p in sorted(base)], np.int32)
+    rp, ci = oracle.csr_from_edges(n, rows, cols)
+    val = f32(np.arange(1, ci.size + 1))
+    e_i, e_f = np.zeros(0, np.int32), np.zeros(0, np.float32)
+    cases = {
+        "nothing": ((e_i, e_i, e_f), (e_i, e_i), (e_i, e_i, e_f)),
+        "only_updates_incl_diagonal": ((e_i, e_i, e_f), (e_i, e_i), (np.array([0, 3, 5], np.int32), np.array([5, 3, 0], np.int32), f32([9, 8, 7]))),
+        "update_of_absent_edge_is_skipped": ((e_i, e_i, e_f), (e_i, e_i), (np.array([4], np.int32), np.array([0], np.int32), f32([5]))),
+        "all_three": ((np.array([0, 3], np.int32), np.array([2, 0], np.int32), f32([20, 30])),
+                      (np.array([2, 5], np.int32), np.array([4, 4], np.int32)),
+                      (np.array([2], np.int32), np.array([3], np.int32), f32([40]))),
+    }
+    for name, (add, dele, upd) in cases.items():
+        want = oracle.delta_apply_weighted(n, rp, ci, val, add=add, dele=dele, upd=upd)
+        got = gpu_rebuild_weighted(n, rp, ci, val, add, dele, upd)
+        assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1]), name
+        assert np.array_equal(got[2], f32(want[2])), name
+
+
+@pytest.mark.parametrize("dtype,f", [(torch.float32, 16), (torch.float32, 32), (torch.float32, 128), (torch.bfloat16, 64),
+                                     (torch.bfloat16, 128)])
+@pytest.mark.parametrize("relu", [False, True])
+def test_weighted_spmm(dtype, f, relu):
+    wl = WORKLOADS["c3"].scaled(1 << 13, T=1)
+    g = DynamicGraph(wl)
+    rp, ci = (x.numpy() for x in g.csr())
+    n = wl.n
+    rng = np.random.default_rng(f)
+    val = f32(rng.standard_normal(ci.size))
+    h = torch.randn((n, f), generator=torch.Generator().manual_seed(f)).to(dtype)
+    want = oracle.spmm(rp, ci, to_f64(h), relu=relu, val=val.astype(np.float64))
+    ws = torch.empty(dg.spmm_workspace(n, int(ci.size), f), dtype=torch.uint8, device=DEV)
+    z = torch.full((n, f), float("nan"), dtype=dtype, device=DEV)
+    dg.spmm_weighted(dev(rp, torch.int32), dev(ci, torch.int32), dev(val, torch.float32), int(ci.size), h.to(DEV), z, ws,
+                     flags=dg.DGNN_RELU if relu else 0)
+    assert_close(to_f64(z), want, dtype, f"weighted spmm f={f}")
+    # the paper's way of bringing the values: the normalised values of Eqn (1) shipped whole give the GCN aggregation
+    if not relu:
+        vals_eq1 = oracle.gcn_values(rp, ci)
+        dg.spmm_weighted(dev(rp, torch.int32), dev(ci, torch.int32), dev(f32(vals_eq1), torch.float32), int(ci.size),
+                         h.to(DEV), z, ws)
+        assert_close(to_f64(z), oracle.spmm(rp, ci, to_f64(h)), dtype, "Eqn (1) values shipped whole")
