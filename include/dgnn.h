@@ -25,7 +25,8 @@
  *     between calls, nothing is printed.
  *   - Return value: DGNN_OK (0) or a negative dgnn_status.  Argument errors are detected on
  *     the host before anything is enqueued.
- *   - All indices and counts that live in device arrays are int32; n and nnz must be below 2^31.
+ *   - All indices and counts that live in device arrays are int32; n and nnz (and the lengths of the
+ *     difference lists) must not exceed 2^31 - 2^16 - 1, else DGNN_ERR_OVERFLOW.
  */
 #ifndef DGNN_H
 #define DGNN_H
@@ -42,7 +43,7 @@ typedef enum {
     DGNN_ERR_NULL = -1,      /* a required pointer is NULL                                   */
     DGNN_ERR_SHAPE = -2,     /* non-positive size, unsupported feature width / window / dtype */
     DGNN_ERR_CAPACITY = -3,  /* output buffer or workspace too small                          */
-    DGNN_ERR_OVERFLOW = -4,  /* n or nnz does not fit in int32                                */
+    DGNN_ERR_OVERFLOW = -4,  /* n or nnz beyond the int32 index range (see below)             */
     DGNN_ERR_ALIAS = -5,     /* output aliases an input where that is not allowed             */
     DGNN_ERR_HIP = -6,       /* the HIP runtime refused a launch or copy                      */
     DGNN_ERR_ALIGN = -7      /* a feature pointer is not 16-byte aligned                      */

@@ -269,7 +269,7 @@ extern "C" int dgnn_weight_grad(const void *x, const void *g, int64_t n, int32_t
     if (!x || !g || !dw || !ws) return DGNN_ERR_NULL;
     if (n <= 0 || !supported_width(f_in) || !supported_width(f_out)) return DGNN_ERR_SHAPE;
     if (dt != DGNN_F32 && dt != DGNN_BF16) return DGNN_ERR_SHAPE;
-    if (!fits_i32(n)) return DGNN_ERR_OVERFLOW;
+    if (!fits_index(n)) return DGNN_ERR_OVERFLOW;
     if (!aligned16(x) || !aligned16(g) || !aligned16(ws)) return DGNN_ERR_ALIGN;
     size_t need = 0;
     dgnn_weight_grad_workspace(f_in, f_out, &need);
@@ -285,7 +285,7 @@ extern "C" int dgnn_relu_backward(const void *g, const void *z, const float *row
     if (!g || !z || !out) return DGNN_ERR_NULL;
     if (n <= 0 || !supported_width(f)) return DGNN_ERR_SHAPE;
     if (dt != DGNN_F32 && dt != DGNN_BF16) return DGNN_ERR_SHAPE;
-    if (!fits_i32(n)) return DGNN_ERR_OVERFLOW;
+    if (!fits_index(n)) return DGNN_ERR_OVERFLOW;
     if (!aligned16(g) || !aligned16(z) || !aligned16(out)) return DGNN_ERR_ALIGN;
     const int pieces_per_row = f * (dt == DGNN_F32 ? 4 : 2) / 16;
     const int64_t pieces = n * pieces_per_row;

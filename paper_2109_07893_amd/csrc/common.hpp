@@ -16,6 +16,9 @@ namespace dgnn {
 constexpr int kWave = 64;   // wavefront width on CDNA4
 
 inline bool fits_i32(int64_t v) { return v >= 0 && v <= 2147483647LL; }
+// Row and entry counts: kernels form "index + a tile's worth" in int32 before comparing with the count, so the
+// counts themselves stop 2^16 short of 2^31.
+inline bool fits_index(int64_t v) { return v >= 0 && v <= 2147483647LL - 65536; }
 inline bool supported_width(int32_t f) { return f == 16 || f == 32 || f == 64 || f == 128; }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }

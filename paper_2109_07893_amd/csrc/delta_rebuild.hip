@@ -486,7 +486,7 @@ extern "C" const char *dgnn_strerror(int code) {
 extern "C" int dgnn_csr_dinv(int64_t n, const int32_t *rowptr, float *dinv, void *stream) {
     if (!rowptr || !dinv) return DGNN_ERR_NULL;
     if (n <= 0) return DGNN_ERR_SHAPE;
-    if (!fits_i32(n)) return DGNN_ERR_OVERFLOW;
+    if (!fits_index(n)) return DGNN_ERR_OVERFLOW;
     hipLaunchKernelGGL(dinv_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
                        (int)n, rowptr, dinv);
     DGNN_RETURN_IF_LAUNCH_FAILED();
@@ -498,7 +498,7 @@ extern "C" int dgnn_delta_h2d(const int32_t *h_add_row, const int32_t *h_add_col
                               int32_t *d_add_row, int32_t *d_add_col, int32_t *d_del_row, int32_t *d_del_col,
                               void *stream) {
     if (n_add < 0 || n_del < 0) return DGNN_ERR_SHAPE;
-    if (!fits_i32(n_add) || !fits_i32(n_del)) return DGNN_ERR_OVERFLOW;
+    if (!fits_index(n_add) || !fits_index(n_del)) return DGNN_ERR_OVERFLOW;
     if (n_add > 0 && (!h_add_row || !h_add_col || !d_add_row || !d_add_col)) return DGNN_ERR_NULL;
     if (n_del > 0 && (!h_del_row || !h_del_col || !d_del_row || !d_del_col)) return DGNN_ERR_NULL;
     hipStream_t s = (hipStream_t)stream;
@@ -516,7 +516,7 @@ extern "C" int dgnn_delta_h2d(const int32_t *h_add_row, const int32_t *h_add_col
 extern "C" int dgnn_delta_rebuild_workspace(int64_t n, int64_t nnz_prev, int64_t n_add, int64_t n_del, size_t *bytes) {
     if (!bytes) return DGNN_ERR_NULL;
     if (n <= 0 || nnz_prev < 0 || n_add < 0 || n_del < 0) return DGNN_ERR_SHAPE;
-    if (!fits_i32(n + 1) || !fits_i32(nnz_prev + n_add)) return DGNN_ERR_OVERFLOW;
+    if (!fits_index(n + 1) || !fits_index(nnz_prev + n_add)) return DGNN_ERR_OVERFLOW;
     *bytes = round_up((size_t)(n + 1) * sizeof(int32_t), 256)     // add_ptr
              + round_up((size_t)n_add * sizeof(int2), 256)         // row extents of the added entries
              + round_up((size_t)n_del * sizeof(int2), 256);        // ... of the deleted entries
@@ -542,7 +542,7 @@ int rebuild(int64_t n, const int32_t *rowptr_prev, const int32_t *colidx_prev, i
     if (n_del > 0 && (!del_row || !del_col)) return DGNN_ERR_NULL;
     if (vals && (!vals->prev || !vals->next || (n_add > 0 && !vals->add))) return DGNN_ERR_NULL;
     if (n <= 0 || nnz_prev <= 0 || (flags & ~DGNN_VALIDATE)) return DGNN_ERR_SHAPE;
-    if (!fits_i32(n + 1) || !fits_i32(nnz_prev + n_add)) return DGNN_ERR_OVERFLOW;
+    if (!fits_index(n + 1) || !fits_index(nnz_prev + n_add)) return DGNN_ERR_OVERFLOW;
     const int64_t nnz_new = nnz_prev + n_add - n_del;
     if (nnz_new < 0) return DGNN_ERR_SHAPE;
     if (cap_next < nnz_new) return DGNN_ERR_CAPACITY;
@@ -617,7 +617,7 @@ extern "C" int dgnn_delta_rebuild_weighted(int64_t n,
                                            void *ws, size_t ws_bytes, uint32_t flags, int32_t *d_status, void *stream) {
     if (n_upd < 0) return DGNN_ERR_SHAPE;
     if (n_upd > 0 && (!upd_row || !upd_col || !upd_val)) return DGNN_ERR_NULL;
-    if (!fits_i32(n_upd)) return DGNN_ERR_OVERFLOW;
+    if (!fits_index(n_upd)) return DGNN_ERR_OVERFLOW;
     const Values vals{val_prev, add_val, val_next};
     const int rc = rebuild(n, rowptr_prev, colidx_prev, nnz_prev, add_row, add_col, n_add, del_row, del_col, n_del,
                            rowptr_next, colidx_next, cap_next, nnz_next, nullptr, &vals, ws, ws_bytes, flags, d_status, stream);

@@ -443,7 +443,7 @@ int transform(const void *x, int64_t n, int32_t f_in, const void *w, int wt, int
     if (!x || !w || !h) return DGNN_ERR_NULL;
     if (n <= 0 || !supported_width(f_in) || !supported_width(f_out)) return DGNN_ERR_SHAPE;
     if (dt != DGNN_F32 && dt != DGNN_BF16) return DGNN_ERR_SHAPE;
-    if (!fits_i32(n)) return DGNN_ERR_OVERFLOW;
+    if (!fits_index(n)) return DGNN_ERR_OVERFLOW;
     if (!aligned16(x) || !aligned16(h)) return DGNN_ERR_ALIGN;
     if (x == h) return DGNN_ERR_ALIAS;
     hipStream_t s = (hipStream_t)stream;

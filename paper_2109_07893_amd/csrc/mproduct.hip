@@ -247,7 +247,7 @@ int mproduct(const void *z, void *y, int64_t T, int64_t n, int32_t f, int32_t w,
     if (!z || !y) return DGNN_ERR_NULL;
     if (T <= 0 || n <= 0 || w <= 0 || t0 < 0 || n_halo < 0 || !supported_width(f)) return DGNN_ERR_SHAPE;
     if (dt != DGNN_F32 && dt != DGNN_BF16) return DGNN_ERR_SHAPE;
-    if (!fits_i32(n) || !fits_i32(T) || !fits_i32(t0 + T + n_halo)) return DGNN_ERR_OVERFLOW;
+    if (!fits_index(n) || !fits_i32(T) || !fits_i32(t0 + T + n_halo)) return DGNN_ERR_OVERFLOW;
     if (n_halo > 0 && !halo_frames) return DGNN_ERR_NULL;
     if (n_halo > w - 1) return DGNN_ERR_SHAPE;
     if (!REVERSE && n_halo != (t0 < w - 1 ? t0 : w - 1)) return DGNN_ERR_SHAPE;   // exactly the frames the window reaches

@@ -537,7 +537,7 @@ int launch(int64_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx,
 extern "C" int dgnn_spmm_workspace(int64_t n, int64_t nnz, int32_t f, size_t *bytes) {
     if (!bytes) return DGNN_ERR_NULL;
     if (n <= 0 || nnz < 0 || !supported_width(f)) return DGNN_ERR_SHAPE;
-    if (!fits_i32(n + 1) || !fits_i32(nnz)) return DGNN_ERR_OVERFLOW;
+    if (!fits_index(n + 1) || !fits_index(nnz)) return DGNN_ERR_OVERFLOW;
     *bytes = workspace_layout(nnz, f, nullptr, nullptr);
     return DGNN_OK;
 }
@@ -550,7 +550,7 @@ int spmm(int64_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, c
     if (!rowptr || !colidx || !h || !z || !ws) return DGNN_ERR_NULL;
     if (n <= 0 || nnz <= 0 || !supported_width(f) || (flags & ~allowed)) return DGNN_ERR_SHAPE;
     if (dt != DGNN_F32 && dt != DGNN_BF16) return DGNN_ERR_SHAPE;
-    if (!fits_i32(n + 1) || !fits_i32(nnz)) return DGNN_ERR_OVERFLOW;
+    if (!fits_index(n + 1) || !fits_index(nnz)) return DGNN_ERR_OVERFLOW;
     if (!aligned16(h) || !aligned16(z) || !aligned16(ws)) return DGNN_ERR_ALIGN;
     if (h == z) return DGNN_ERR_ALIAS;
     Workspace w;

@@ -55,6 +55,9 @@ def test_workspace_queries(lib):
     assert lib.dgnn_spmm_workspace(1000, 11000, 32, ctypes.byref(out)) == 0 and out.value > 0
     assert lib.dgnn_spmm_workspace(1000, 11000, 24, ctypes.byref(out)) == -2
     assert lib.dgnn_spmm_workspace(1000, 1 << 31, 32, ctypes.byref(out)) == -4
+    limit = (1 << 31) - (1 << 16) - 1               # the largest accepted count: kernels add a tile to an index in int32
+    assert lib.dgnn_spmm_workspace(1000, limit, 32, ctypes.byref(out)) == 0
+    assert lib.dgnn_spmm_workspace(1000, limit + 1, 32, ctypes.byref(out)) == -4
 
 
 def test_delta_rebuild_argument_errors(lib):
