@@ -29,7 +29,7 @@ import torch
 
 __all__ = [
     "Workload", "WORKLOADS", "DynamicGraph", "mix64", "rand_bits", "rand_below",
-    "stream_base", "features", "glorot_weight", "keys_to_coo", "keys_to_csr", "transpose_coo", "gradient",
+    "stream_base", "features", "glorot_weight", "keys_to_coo", "keys_to_csr", "transpose_coo", "gradient", "SmoothedGraph",
 ]
 
 _M64 = (1 << 64) - 1
@@ -361,6 +361,55 @@ def _normal(base: int, start: int, count: int, device) -> torch.Tensor:
     u2 = ((_lsr(h, 16) & 0xFFFFFF).to(torch.float64)) / 16777216.0           # [0, 1)
     z = torch.sqrt(-2.0 * torch.log(u1)) * torch.cos(2.0 * math.pi * u2)
     return z.to(torch.float32)
+
+
+class SmoothedGraph:
+    """The smoothed series of a dynamic graph (Section "Smoothening the Input Graphs"), prepared the way that
+    section describes it, as pre-processing: snapshot t of the smoothed series is the sum of the raw snapshots
+    of the last `life` timesteps, S_t = sum_{i = max(1, t-life+1)}^{t} A_i, so a stored entry carries the number
+    of those snapshots that hold the edge (mode "edge_life"), or that number divided by min(life, t), which is
+    what the M-transform of the adjacency tensor gives (mode "mproduct").
+
+    `keys` / `vals` are S_t as sorted unique int64 keys and float32 values; `advance()` moves to S_{t+1} and
+    returns the weighted graph difference in the form the weighted rebuild takes:
+        (add_row, add_col, add_val), (del_row, del_col), (upd_row, upd_col, upd_val)
+    each sorted by (row, col).  Input formatting: the method's arithmetic is not here."""
+
+    def __init__(self, wl: Workload, life: int, mode: str = "edge_life", device="cpu"):
+        assert life >= 1 and mode in ("edge_life", "mproduct")
+        self.raw = DynamicGraph(wl, device=device)
+        self.life, self.mode = life, mode
+        self.window = [self.raw.keys]
+        self.t = 1
+        self.keys, self.vals = self._sum()
+
+    def _sum(self):
+        keys, counts = torch.unique(torch.cat(self.window), return_counts=True)      # sorted
+        vals = counts.to(torch.float32)
+        if self.mode == "mproduct":
+            vals = vals / float(min(self.life, self.t))
+        return keys, vals
+
+    def csr(self):
+        rp, ci = keys_to_csr(self.keys, self.raw.wl.n)
+        return rp, ci, self.vals
+
+    def advance(self):
+        self.raw.advance()
+        self.t += 1
+        self.window.append(self.raw.keys)
+        if len(self.window) > self.life:
+            self.window.pop(0)
+        old_k, old_v = self.keys, self.vals
+        self.keys, self.vals = self._sum()
+        in_old = _member(old_k, self.keys)
+        in_new = _member(self.keys, old_k)
+        add_k, add_v = self.keys[~in_old], self.vals[~in_old]
+        del_k = old_k[~in_new]
+        stay_new, stay_old = self.vals[in_old], old_v[in_new]          # same keys, same order
+        changed = stay_new != stay_old
+        upd_k, upd_v = self.keys[in_old][changed], stay_new[changed]
+        return (keys_to_coo(add_k) + (add_v,), keys_to_coo(del_k), keys_to_coo(upd_k) + (upd_v,))
 
 
 def features(wl: Workload, t: int, device="cpu", chunk_rows: int = 1 << 20) -> torch.Tensor:

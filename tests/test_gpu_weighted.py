@@ -119,3 +119,39 @@ def test_weighted_spmm(dtype, f, relu):
         dg.spmm_weighted(dev(rp, torch.int32), dev(ci, torch.int32), dev(f32(vals_eq1), torch.float32), int(ci.size),
                          h.to(DEV), z, ws)
         assert_close(to_f64(z), oracle.spmm(rp, ci, to_f64(h)), dtype, "Eqn (1) values shipped whole")
+
+
+@pytest.mark.parametrize("name,n,life,mode", [("c1", 1000, 3, "edge_life"), ("c3", 1 << 13, 4, "edge_life"),
+                                              ("c3", 1 << 13, 3, "mproduct"), ("c2", 20_000, 2, "mproduct")])
+def test_smoothed_series_through_the_weighted_path(name, n, life, mode):
+    """The smoothed graphs the paper's models are trained on (sum of the raw snapshots of the last `life`
+    timesteps), carried from step to step by weighted differences.  The expected snapshots are built here from
+    the raw oracle snapshots with numpy, not from the lists."""
+    from dtdg_synth import SmoothedGraph
+    wl = WORKLOADS[name].scaled(n, T=7) if n != WORKLOADS[name].n else WORKLOADS[name]
+    raw = DynamicGraph(wl)
+    rp, ci = (x.numpy() for x in raw.csr())
+    raw_keys = [(np.repeat(np.arange(wl.n, dtype=np.int64), np.diff(rp)) << 32) | ci.astype(np.int64)]
+    sm = SmoothedGraph(wl, life, mode)
+    g_rp, g_ci, g_val = (x.numpy() for x in sm.csr())
+    f = 32
+    h = torch.randn((wl.n, f), generator=torch.Generator().manual_seed(3))
+    for t in range(2, 8):
+        rp, ci = oracle.delta_apply(wl.n, rp, ci, *[x.numpy() for x in raw.advance()])
+        raw_keys.append((np.repeat(np.arange(wl.n, dtype=np.int64), np.diff(rp)) << 32) | ci.astype(np.int64))
+        window = raw_keys[max(0, t - life):t]
+        keys, counts = np.unique(np.concatenate(window), return_counts=True)
+        want_val = f32(counts) / (np.float32(min(life, t)) if mode == "mproduct" else np.float32(1))
+        add, dele, upd = sm.advance()
+        add, dele, upd = tuple(x.numpy() for x in add), tuple(x.numpy() for x in dele), tuple(x.numpy() for x in upd)
+        g_rp, g_ci, g_val = gpu_rebuild_weighted(wl.n, g_rp, g_ci, g_val, add, dele, upd)
+        got_keys = (np.repeat(np.arange(wl.n, dtype=np.int64), np.diff(g_rp)) << 32) | g_ci.astype(np.int64)
+        assert np.array_equal(got_keys, keys), (name, t)
+        assert np.array_equal(g_val, want_val), (name, t)
+    # aggregation with the smoothed values of the last snapshot
+    want = oracle.spmm(g_rp, g_ci, to_f64(h), relu=True, val=g_val.astype(np.float64))
+    ws = torch.empty(dg.spmm_workspace(wl.n, int(g_ci.size), f), dtype=torch.uint8, device=DEV)
+    z = torch.empty((wl.n, f), device=DEV)
+    dg.spmm_weighted(dev(g_rp, torch.int32), dev(g_ci, torch.int32), dev(g_val, torch.float32), int(g_ci.size), h.to(DEV), z,
+                     ws, flags=dg.DGNN_RELU)
+    assert_close(to_f64(z), want, torch.float32, f"aggregation over the smoothed snapshot ({mode})")
