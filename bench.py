@@ -352,8 +352,16 @@ def main():
         torch.cuda.synchronize()
         el = time.perf_counter() - t0
         h2d = sum(8 * (d[0].numel() + d[2].numel()) for d in blk.deltas)
+        # the copies alone, nothing computing: what the host link delivers for these list sizes
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for lists in blk.pinned:
+            dg.delta_h2d(*lists, *runner.stage[0])
+        torch.cuda.synchronize()
+        link_s = time.perf_counter() - t0
         out["pinned_host_lists"] = {"value": edges_per_step / (el / args.steps), "unit": "edges/s",
                                     "ms_per_step": el / args.steps * 1e3, "h2d_bytes_per_step": h2d,
+                                    "h2d_alone_ms": link_s * 1e3, "h2d_alone_GBps": h2d / link_s / 1e9,
                                     "whole_snapshot_bytes_per_step": sum(4 * (z + blk.n + 1) for z in blk.nnz[1:])}
 
     progress("per-stage pass done")
