@@ -44,6 +44,8 @@ def parse_args():
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="stop the oracle sample after this much work")
     ap.add_argument("--pinned", action="store_true", help="also time the pass with difference lists in pinned host memory")
     ap.add_argument("--no-train", action="store_true", help="skip the training-step (forward + backward) measurement")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the forward pass replayed as one HIP graph (for launch-bound small workloads)")
     ap.add_argument("--weighted", action="store_true",
                     help="also time one step of the path for snapshots that carry a value per entry")
     ap.add_argument("--natural-labels", action="store_true",
@@ -365,6 +367,19 @@ def main():
                                     "whole_snapshot_bytes_per_step": sum(4 * (z + blk.n + 1) for z in blk.nnz[1:])}
 
     progress("per-stage pass done")
+    if args.graph:
+        graph = runner.capture(first=first)
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        el = (time.perf_counter() - t0) / args.steps
+        out["hip_graph_replay"] = {"value": edges_per_step / el, "unit": "edges/s", "ms_per_step": el * 1e3}
+        del graph
+        progress("graph replay timed")
     if args.weighted:
         out["weighted_step"] = weighted_step(args, wl, blk, dev)
         progress("weighted step timed")

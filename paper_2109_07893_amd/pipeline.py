@@ -199,6 +199,18 @@ class BlockRunner:
                 on_snapshot(t, self.slot_of(t))
         self.mix()
 
+    def capture(self, first: int = 1) -> "torch.cuda.CUDAGraph":
+        """The resident pass recorded once as a HIP graph (every library call only enqueues kernels on the
+        current stream, so the whole pass is capturable); replaying it costs one launch instead of one per
+        kernel, which is what bounds small workloads.  The pass is run once eagerly first, so that one-time
+        host-side set-up inside the library (occupancy queries) is not part of the recording."""
+        self.run_resident(first=first)
+        torch.cuda.synchronize(self.dev)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            self.run_resident(first=first)
+        return graph
+
     def run_from_pinned(self, first: int = 1) -> None:
         """Same pass with the difference lists of step t+1 copied from pinned host memory on a second
         stream while step t computes (two staging sets, events both ways)."""

@@ -72,3 +72,28 @@ def test_transfer_size_of_graph_difference():
         assert shipped == 8 * (lists[0].numel() + lists[2].numel())
         whole = 4 * (blk.nnz[t - 1] + blk.n + 1)
         assert shipped < whole / 4
+
+
+def test_forward_pass_as_a_hip_graph_repeats_the_eager_result():
+    """The resident pass captured once and replayed several times, with eager work of the same program and
+    synchronisations between the replays; every replay must leave exactly what the eager pass leaves."""
+    wl = WORKLOADS["c1"]
+    blk = make_block(wl, DEV, gen_device="cpu")
+    runner = BlockRunner(blk)
+    runner.load_first()
+    runner.run_resident()
+    torch.cuda.synchronize()
+    want = runner.z.clone()
+    want_rp, want_ci = runner.snapshot_to_host(wl.T)
+    graph = runner.capture()
+    for k in range(4):
+        runner.z.fill_(float("nan"))
+        runner.rowptr[wl.T % 2].fill_(-1)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(runner.z, want), k
+        rp, ci = runner.snapshot_to_host(wl.T)
+        assert np.array_equal(rp, want_rp) and np.array_equal(ci, want_ci), k
+        runner.run_resident()                      # eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(runner.z, want), k
