@@ -46,6 +46,8 @@ def parse_args():
     ap.add_argument("--no-train", action="store_true", help="skip the training-step (forward + backward) measurement")
     ap.add_argument("--graph", action="store_true",
                     help="also time the forward pass replayed as one HIP graph (for launch-bound small workloads)")
+    ap.add_argument("--cdgcn", action="store_true",
+                    help="also time the forward pass of one CD-GCN layer (skip-concat GCN + LSTM over time) over the block")
     ap.add_argument("--weighted", action="store_true",
                     help="also time one step of the path for snapshots that carry a value per entry")
     ap.add_argument("--natural-labels", action="store_true",
@@ -168,6 +170,38 @@ def weighted_step(args, wl, blk, dev):
                      "algorithmic_GBps": round(byts / (ms * 1e-3) / 1e9, 1)}
     out["lists"] = {"added": int(ar.numel()), "deleted": int(dr.numel()), "value_updates": int(ur.numel())}
     return out
+
+
+def cdgcn_layer(args, wl, blk, dev):
+    """Forward pass of one CD-GCN layer over the block (every snapshot t = 1..T): an extra figure."""
+    import math
+    import torch
+    from paper_2109_07893_amd.cdgcn import CdgcnLayer
+    from paper_2109_07893_amd.pipeline import StageTimer
+    f, hidden = blk.f, 32
+    dt = blk.x[0].dtype
+    gen = torch.Generator(device=dev).manual_seed(wl.seed)
+    w_x = (torch.randn((2 * f, 4 * hidden), generator=gen, device=dev) / math.sqrt(2 * f)).to(dt)
+    w_h = (torch.randn((hidden, 4 * hidden), generator=gen, device=dev) / math.sqrt(hidden)).to(dt)
+    bias = torch.zeros(4 * hidden, device=dev)
+    layer = CdgcnLayer(blk, blk.w[0], w_x, w_h, bias, hidden)
+    layer.load_first()
+    for _ in range(max(1, args.warmup - 1)):
+        layer.run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        layer.run()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    layer.timer = StageTimer(dev)
+    layer.run()
+    torch.cuda.synchronize()
+    stages = {k: {"calls_per_step": c, "avg_ms": round(t / c, 4)} for k, (c, t) in layer.timer.totals().items()}
+    edges = sum(blk.nnz)
+    return {"ms_per_step": ms, "value": edges / (ms * 1e-3), "unit": "edges/s", "hidden": hidden, "stages": stages,
+            "what": f"t=1..{blk.T}: rebuild (t>=2), row scale, Y0 = A~ X, Y1 = Y0 W, relu(Y0 o Y1), "
+                    "two gate products, LSTM cell"}
 
 
 def training_step(args, wl, blk, dev):
@@ -380,6 +414,9 @@ def main():
         out["hip_graph_replay"] = {"value": edges_per_step / el, "unit": "edges/s", "ms_per_step": el * 1e3}
         del graph
         progress("graph replay timed")
+    if args.cdgcn:
+        out["cdgcn_layer"] = cdgcn_layer(args, wl, blk, dev)
+        progress("CD-GCN layer timed")
     if args.weighted:
         out["weighted_step"] = weighted_step(args, wl, blk, dev)
         progress("weighted step timed")

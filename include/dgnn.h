@@ -292,6 +292,28 @@ int dgnn_weight_grad(const void *x, const void *g, int64_t n, int32_t f_in, int3
 int dgnn_input_grad(const void *g, int64_t n, int32_t f_out, const void *w, int32_t f_in,
                     const float *row_scale, void *dx, dgnn_dtype dt, void *stream);
 
+/*
+ * ---- The CD-GCN layer (Section "CD-GCN"): its GCN operation has a skip connection,
+ *     Y0 = A~ X,   Y1 = Y0 W,   Y = sigma(Y0 o Y1)      (o = side by side: F + F' features),
+ * and an LSTM aggregates over time, one state (h, c) per vertex.  Y0 is dgnn_spmm (without DGNN_RELU and without
+ * DGNN_H_PRESCALED), Y1 and the two products of the gate pre-activations are dgnn_feature_transform; the two calls
+ * below are the steps that are left.  Forward only.
+ */
+
+/* out [n][f0 + f1] = relu of the rows of y0 [n][f0] and y1 [n][f1] laid side by side; out must not be y0 or y1. */
+int dgnn_concat_relu(const void *y0, int32_t f0, const void *y1, int32_t f1, void *out, int64_t n,
+                     dgnn_dtype dt, void *stream);
+
+/*
+ * LSTM cell.  gates_x = X_t W_x and gates_h = h_{t-1} W_h, both [n][4 * hidden] with the gates in the order
+ * (input, forget, cell, output); bias fp32 [4 * hidden] or NULL.  With a = gates_x + gates_h + bias:
+ *     c_next = sig(a_f) * c_prev + sig(a_i) * tanh(a_g),     h_next = sig(a_o) * tanh(c_next).
+ * c_prev, c_next, h_next [n][hidden]; c_next may be c_prev (in place); h_next must be a buffer of its own.
+ * hidden must be a supported feature width.
+ */
+int dgnn_lstm_cell(const void *gates_x, const void *gates_h, const float *bias, const void *c_prev, void *c_next,
+                   void *h_next, int64_t n, int32_t hidden, dgnn_dtype dt, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -252,3 +252,27 @@ def gcn_layer_backward(rowptr, colidx, x, w, z, g_z):
     """Gradients of Z = relu(A~ (X W)) for upstream g_z = dL/dZ: returns (dW, dX)."""
     g_h = spmm_t(rowptr, colidx, relu_grad(g_z, z))
     return weight_grad(x, g_h), input_grad(g_h, w)
+
+
+# ---- CD-GCN (Section "CD-GCN"): GCN operation with skip connection, LSTM over time ------------------
+
+def cdgcn_gcn(rowptr, colidx, x, w) -> np.ndarray:
+    """Y = relu(Y0 o Y1) with Y0 = A~ X and Y1 = Y0 W; F + F' features per vertex."""
+    y0 = spmm(rowptr, colidx, _a(x, np.float64))
+    y1 = xw(y0, w)
+    return np.maximum(np.concatenate([y0, y1], axis=1), 0.0)
+
+
+def _sig(a):
+    return 1.0 / (1.0 + np.exp(-a))
+
+
+def lstm_cell(x, h, c, w_x, w_h, bias):
+    """One step of the standard LSTM (state (h, c)); gates in the order (input, forget, cell, output):
+    a = x W_x + h W_h + b,  c' = sig(a_f) c + sig(a_i) tanh(a_g),  h' = sig(a_o) tanh(c')."""
+    x, h, c = _a(x, np.float64), _a(h, np.float64), _a(c, np.float64)
+    a = xw(x, w_x) + xw(h, w_h) + (0.0 if bias is None else _a(bias, np.float64)[None, :])
+    hid = c.shape[1]
+    ai, af, ag, ao = (a[:, q * hid:(q + 1) * hid] for q in range(4))
+    c2 = _sig(af) * c + _sig(ai) * np.tanh(ag)
+    return _sig(ao) * np.tanh(c2), c2

@@ -24,7 +24,7 @@ DGNN_H_PRESCALED = 2
 EXPORTS = (
     "dgnn_strerror", "dgnn_csr_dinv", "dgnn_delta_h2d", "dgnn_delta_rebuild_workspace",
     "dgnn_delta_rebuild", "dgnn_feature_transform", "dgnn_spmm_workspace", "dgnn_spmm", "dgnn_mproduct",
-    "dgnn_delta_rebuild_weighted", "dgnn_spmm_weighted",
+    "dgnn_delta_rebuild_weighted", "dgnn_spmm_weighted", "dgnn_concat_relu", "dgnn_lstm_cell",
     "dgnn_mproduct_backward", "dgnn_mproduct_block", "dgnn_mproduct_backward_block", "dgnn_relu_backward", "dgnn_weight_grad_workspace", "dgnn_weight_grad", "dgnn_input_grad",
 )
 
@@ -84,6 +84,8 @@ def load_library():
                                                 _vp, _vp, _vp, _i64, _vp, _vp, _vp, _i64, ctypes.POINTER(_i64),
                                                 _vp, _sz, _u32, _vp, _vp]
     lib.dgnn_spmm_weighted.argtypes = [_i64, _i64, _vp, _vp, _vp, _vp, _i32, _vp, ctypes.c_int, _u32, _vp, _sz, _vp]
+    lib.dgnn_concat_relu.argtypes = [_vp, _i32, _vp, _i32, _vp, _i64, ctypes.c_int, _vp]
+    lib.dgnn_lstm_cell.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _i32, ctypes.c_int, _vp]
     lib.dgnn_mproduct_block.argtypes = [_vp, _vp, _i64, _i64, _i32, _i32, _vp, _i64, _vp, _i64, ctypes.c_int, _vp]
     lib.dgnn_mproduct_backward_block.argtypes = [_vp, _vp, _i64, _i64, _i32, _i32, _vp, _i64, _vp, _i64, ctypes.c_int, _vp]
     lib.dgnn_relu_backward.argtypes = [_vp, _vp, _vp, _vp, _i64, _i32, ctypes.c_int, _vp]
@@ -255,6 +257,34 @@ def spmm_weighted(rowptr, colidx, val, nnz: int, h: torch.Tensor, z: torch.Tenso
     _check(load_library().dgnn_spmm_weighted(n, nnz, _ptr(rowptr), _ptr(colidx), _ptr(val), _ptr(h), f, _ptr(z), dt,
                                              flags, _ptr(ws), ws.numel() * ws.element_size(), _stream(h)),
            "dgnn_spmm_weighted")
+
+
+def concat_relu(y0: torch.Tensor, y1: torch.Tensor, out: torch.Tensor) -> None:
+    """out = relu([y0 | y1]) row by row."""
+    dt = _dtype_code(y0)
+    n, f0 = y0.shape
+    f1 = y1.shape[1]
+    if y1.shape[0] != n or tuple(out.shape) != (n, f0 + f1) or y1.dtype != y0.dtype or out.dtype != y0.dtype:
+        raise ValueError("shape mismatch in concat_relu")
+    _check(load_library().dgnn_concat_relu(_ptr(y0), f0, _ptr(y1), f1, _ptr(out), n, dt, _stream(y0)), "dgnn_concat_relu")
+
+
+def lstm_cell(gates_x, gates_h, bias, c_prev, c_next, h_next) -> None:
+    """One LSTM step from the two halves of the gate pre-activations (gate order: input, forget, cell, output)."""
+    dt = _dtype_code(gates_x)
+    n, hidden = c_prev.shape
+    for t in (gates_x, gates_h):
+        if tuple(t.shape) != (n, 4 * hidden) or t.dtype != gates_x.dtype:
+            raise ValueError("gate pre-activations must be [n, 4 * hidden]")
+    for t in (c_prev, c_next, h_next):
+        if tuple(t.shape) != (n, hidden) or t.dtype != gates_x.dtype:
+            raise ValueError("state tensors must be [n, hidden]")
+    if bias is not None:
+        _need(bias, torch.float32, "bias")
+        if bias.numel() != 4 * hidden:
+            raise ValueError("bias must have 4 * hidden entries")
+    _check(load_library().dgnn_lstm_cell(_ptr(gates_x), _ptr(gates_h), _ptr(bias), _ptr(c_prev), _ptr(c_next), _ptr(h_next),
+                                         n, hidden, dt, _stream(gates_x)), "dgnn_lstm_cell")
 
 
 def mproduct_backward(g_y: torch.Tensor, g_z: torch.Tensor, w: int, m_band: Optional[torch.Tensor] = None) -> None:

@@ -213,3 +213,41 @@ def test_spmm_with_explicit_values_is_a_plain_sparse_product():
     dense = np.nan_to_num(_dense_weighted(n, rp, ci, val), nan=0.0)
     np.testing.assert_allclose(oracle.spmm(rp, ci, h, val=val), dense @ h, rtol=1e-12, atol=1e-13)
     np.testing.assert_allclose(oracle.spmm_t(rp, ci, h, val=val), dense.T @ h, rtol=1e-12, atol=1e-13)
+
+
+# ----------------------------------------------------------------------------- CD-GCN pieces
+def test_lstm_cell_matches_the_library_cell_and_closed_forms():
+    import torch
+    rng = np.random.default_rng(300)
+    n, fin, hid = 17, 6, 5
+    x, h, c = rng.standard_normal((n, fin)), rng.standard_normal((n, hid)), rng.standard_normal((n, hid))
+    w_x, w_h, b = rng.standard_normal((fin, 4 * hid)), rng.standard_normal((hid, 4 * hid)), rng.standard_normal(4 * hid)
+    cell = torch.nn.LSTMCell(fin, hid).double()            # same gate order (input, forget, cell, output)
+    with torch.no_grad():
+        cell.weight_ih.copy_(torch.from_numpy(w_x.T))
+        cell.weight_hh.copy_(torch.from_numpy(w_h.T))
+        cell.bias_ih.copy_(torch.from_numpy(b))
+        cell.bias_hh.zero_()
+        h_t, c_t = cell(torch.from_numpy(x), (torch.from_numpy(h), torch.from_numpy(c)))
+    h2, c2 = oracle.lstm_cell(x, h, c, w_x, w_h, b)
+    np.testing.assert_allclose(h2, h_t.numpy(), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(c2, c_t.numpy(), rtol=1e-12, atol=1e-13)
+    # all pre-activations zero: every gate is 1/2 and the candidate is 0
+    z = np.zeros
+    h3, c3 = oracle.lstm_cell(z((n, fin)), z((n, hid)), c, z((fin, 4 * hid)), z((hid, 4 * hid)), None)
+    np.testing.assert_allclose(c3, 0.5 * c, rtol=1e-15)
+    np.testing.assert_allclose(h3, 0.5 * np.tanh(0.5 * c), rtol=1e-15)
+
+
+def test_cdgcn_gcn_on_special_graphs():
+    rng = np.random.default_rng(301)
+    n, f = 9, 3
+    x, w = rng.standard_normal((n, f)), rng.standard_normal((f, 4))
+    rp, ci = oracle.csr_from_edges(n, np.arange(n), np.arange(n))          # no edges: A~ = I
+    y = oracle.cdgcn_gcn(rp, ci, x, w)
+    np.testing.assert_allclose(y, np.maximum(np.concatenate([x, x @ w], axis=1), 0.0), rtol=1e-12, atol=1e-13)
+    a, rp, ci, _ = _graph(n, 0.4, 302, False)
+    dense = dense_gcn_matrix(a)
+    y0 = dense @ x
+    np.testing.assert_allclose(oracle.cdgcn_gcn(rp, ci, x, w), np.maximum(np.concatenate([y0, y0 @ w], axis=1), 0.0),
+                               rtol=1e-12, atol=1e-13)
