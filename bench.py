@@ -387,6 +387,15 @@ def main():
             runner.run_from_pinned(first=first)
         torch.cuda.synchronize()
         el = time.perf_counter() - t0
+        # a stream of blocks: the first lists of the next pass are requested while this pass finishes
+        runner.run_from_pinned(first=first, prefetch_next=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            runner.run_from_pinned(first=first, prefetch_next=True)
+        torch.cuda.synchronize()
+        el_stream = time.perf_counter() - t0
+        runner.run_from_pinned(first=first)          # consumes the outstanding request
         h2d = sum(8 * (d[0].numel() + d[2].numel()) for d in blk.deltas)
         # the copies alone, nothing computing: what the host link delivers for these list sizes
         torch.cuda.synchronize()
@@ -398,6 +407,8 @@ def main():
         out["pinned_host_lists"] = {"value": edges_per_step / (el / args.steps), "unit": "edges/s",
                                     "ms_per_step": el / args.steps * 1e3, "h2d_bytes_per_step": h2d,
                                     "h2d_alone_ms": link_s * 1e3, "h2d_alone_GBps": h2d / link_s / 1e9,
+                                    "streamed_blocks": {"value": edges_per_step / (el_stream / args.steps),
+                                                        "ms_per_step": el_stream / args.steps * 1e3},
                                     "whole_snapshot_bytes_per_step": sum(4 * (z + blk.n + 1) for z in blk.nnz[1:])}
 
     progress("per-stage pass done")

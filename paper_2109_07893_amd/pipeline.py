@@ -211,9 +211,11 @@ class BlockRunner:
             self.run_resident(first=first)
         return graph
 
-    def run_from_pinned(self, first: int = 1) -> None:
+    def run_from_pinned(self, first: int = 1, prefetch_next: bool = False) -> None:
         """Same pass with the difference lists of step t+1 copied from pinned host memory on a second
-        stream while step t computes (two staging sets, events both ways)."""
+        stream while step t computes (two staging sets, events both ways).  With prefetch_next the lists of
+        the next pass's first step are already requested while this pass finishes (a stream of blocks: the
+        next block's first lists travel during the current block's last steps)."""
         blk = self.blk
         assert self.stage is not None
         main = torch.cuda.current_stream(self.dev)
@@ -225,10 +227,12 @@ class BlockRunner:
                 B.delta_h2d(*blk.pinned[t - 2], *self.stage[k])
                 self.copied[k].record(self.copy_stream)
 
-        for k in range(2):
-            self.consumed[k].record(main)
-        if blk.T >= 2:
-            issue_copy(2)
+        if not getattr(self, "_first_lists_requested", False):
+            for k in range(2):
+                self.consumed[k].record(main)
+            if blk.T >= 2:
+                issue_copy(2)
+        self._first_lists_requested = False
         for t in range(1, blk.T + 1):
             if t >= 2:
                 k = t % 2
@@ -237,6 +241,9 @@ class BlockRunner:
                     issue_copy(t + 1)
                 self.rebuild(t, self.stage[k])
                 self.consumed[k].record(main)
+                if t == blk.T and prefetch_next and blk.T >= 3:     # both staging sets have been used and released
+                    issue_copy(2)
+                    self._first_lists_requested = True
             if t >= first:
                 self.gcn(t)
         self.mix()

@@ -55,6 +55,27 @@ def test_pinned_host_pipeline_equals_resident():
         assert torch.equal(a.colidx[slot][:nnz], b.colidx[slot][:nnz])
 
 
+def test_pinned_host_pipeline_with_lists_requested_ahead():
+    """A stream of passes in which the first lists of the next pass are requested while the current one finishes:
+    every pass must leave what the resident pass leaves."""
+    wl = WORKLOADS["c5"].scaled(1 << 14)
+    a, _ = run_gpu(wl)
+    blk = make_block(wl, DEV, gen_device="cpu", pinned=True)
+    runner = BlockRunner(blk, keep_all_z=True)
+    runner.load_first()
+    for k in range(3):
+        runner.z.fill_(float("nan"))
+        runner.run_from_pinned(prefetch_next=True)
+        torch.cuda.synchronize()
+        assert torch.equal(a.z, runner.z), k
+    runner.run_from_pinned()                      # takes up the outstanding request, asks for nothing more
+    torch.cuda.synchronize()
+    assert torch.equal(a.z, runner.z)
+    runner.run_from_pinned()                      # and a pass that starts from scratch again
+    torch.cuda.synchronize()
+    assert torch.equal(a.z, runner.z)
+
+
 def test_block_forward_is_deterministic():
     wl = WORKLOADS["c3"].scaled(1 << 13, T=3)
     a, _ = run_gpu(wl)
