@@ -184,3 +184,16 @@ def test_weighted_argument_errors(lib):
     assert f(10, 20, FAKE, FAKE, None, FAKE, 32, FAKE + 4096, 0, 0, FAKE + 8192, 1 << 24, None) == -1
     assert f(10, 20, FAKE, FAKE, FAKE, FAKE, 32, FAKE + 4096, 0, 2, FAKE + 8192, 1 << 24, None) == -2   # no pre-scaled mode
     assert f(10, 20, FAKE, FAKE, FAKE, FAKE, 32, FAKE, 0, 0, FAKE + 8192, 1 << 24, None) == -5
+
+
+def test_cdgcn_argument_errors(lib):
+    f = lib.dgnn_concat_relu
+    assert f(None, 32, FAKE, 32, FAKE + 4096, 10, 0, None) == -1
+    assert f(FAKE, 24, FAKE, 32, FAKE + 4096, 10, 0, None) == -2
+    assert f(FAKE, 32, FAKE, 32, FAKE, 10, 0, None) == -5
+    assert f(FAKE, 32, FAKE + 4, 32, FAKE + 4096, 10, 0, None) == -7
+    f = lib.dgnn_lstm_cell
+    assert f(FAKE, FAKE, None, None, FAKE, FAKE + 64, 10, 32, 0, None) == -1
+    assert f(FAKE, FAKE + 64, None, FAKE + 128, FAKE + 128, FAKE + 256, 10, 20, 0, None) == -2
+    assert f(FAKE, FAKE + 64, None, FAKE + 128, FAKE + 128, FAKE + 128, 10, 32, 0, None) == -5   # h_next over the state
+    assert f(FAKE, FAKE + 64, None, FAKE + 128, FAKE + 128, FAKE + 256, 0, 32, 0, None) == -2
