@@ -188,3 +188,23 @@ def test_one_weight_per_timestep():
             below = to_f64(features(wl, t + 1)) if layer == 0 else to_f64(stored[t][layer - 1])
             dw, gin = oracle.gcn_layer_backward(rp, ci, below, to_f64(blk.w_t[t][layer]), to_f64(stored[t][layer]), gin)
             assert_close(to_f64(tr.dw_t[t][layer]), dw, torch.float32, f"dW_t t={t + 1} layer {layer}")
+
+
+def test_gradient_descent_on_the_weights_reduces_a_loss():
+    """End to end: the weight gradients drive plain gradient descent on L = 1/2 |Y - Y*|^2, where Y* comes from a
+    hidden weight pair; the loss layer (Y - Y*) is the caller's, everything below it is the library's."""
+    wl = replace(WORKLOADS["c1"], layers=2, f=32, name="c1-descent")
+    blk = make_block(wl, DEV, gen_device="cpu")
+    tr = make_trainer(wl, blk)
+    target = tr.forward().clone()                           # outputs under the generator's weights
+    blk.w = [w + 0.3 * torch.randn(w.shape, generator=torch.Generator().manual_seed(k)).to(DEV) for k, w in enumerate(blk.w)]
+    losses = []
+    lr = 2e-5
+    for _ in range(40):
+        y = tr.forward()
+        g_y = (y - target).contiguous()
+        losses.append(float(0.5 * (g_y.double() ** 2).sum()))
+        tr.backward(g_y)
+        blk.w = [(w - lr * dw).contiguous() for w, dw in zip(blk.w, tr.dw)]
+    assert losses[-1] < 0.2 * losses[0], losses[::8]
+    assert all(b <= a * 1.001 for a, b in zip(losses, losses[1:])), losses
