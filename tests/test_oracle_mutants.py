@@ -1,0 +1,110 @@
+"""Do the pins bite?  Each case below plants ONE plausible mistake in a copy of the oracle's C source (a dropped
+factor, a wrong index, an off-by-one window, a transposed operand, a forgotten deletion), builds it, swaps it in
+for the oracle library, and runs the pin tests: at least one of them must fail.  CPU only; the mistakes live in
+copies under a temporary directory, the oracle itself is untouched."""
+import ctypes
+import os
+import subprocess
+
+import pytest
+
+import oracle
+import test_oracle_backward_pins as bwd
+import test_oracle_pins as fwd
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+SRC = os.path.join(os.path.dirname(HERE), "oracle", "dgnn_oracle.c")
+GOLDEN = os.path.join(HERE, "golden")
+
+# (name, text in the oracle source, what a mistaken author might have written instead)
+MUTANTS = [
+    ("normalisation uses the row degree twice", "val[e] = 1.0 / sqrt(du * dv);", "val[e] = 1.0 / sqrt(du * du);"),
+    ("normalisation without the square root", "val[e] = 1.0 / sqrt(du * dv);", "val[e] = 1.0 / (du * dv);"),
+    ("degree counted without the self loop", "double dv = (double)(rowptr[v + 1] - rowptr[v]);",
+     "double dv = (double)(rowptr[v + 1] - rowptr[v]) - 1.0 + (rowptr[v + 1] - rowptr[v] == 1);"),
+    ("aggregation drops the edge weight", "zu[j] += val[e] * hv[j];", "zu[j] += hv[j];"),
+    ("aggregation reads the row's own features", "const double *hv = h + (int64_t)colidx[e] * f;", "const double *hv = h + u * f;"),
+    ("ReLU clamps the wrong side", "if (zu[j] < 0.0) zu[j] = 0.0;", "if (zu[j] > 0.0) zu[j] = 0.0;"),
+    ("dense transform with W transposed", "s += x[i * f_in + k] * w[k * f_out + j];", "s += x[i * f_in + k] * w[(k % f_out) * f_out + (j % f_in)];"),
+    ("window one step too long", "int64_t lo = t - w + 1 > 1 ? t - w + 1 : 1;", "int64_t lo = t - w > 1 ? t - w : 1;"),
+    ("weights 1/w from the first step on", "double mn = (double)(w < t ? w : t);", "double mn = (double)w;"),
+    ("M applied transposed", "s += M[t * T + k] * z[k * frame + i];", "s += M[k * T + t] * z[k * frame + i];"),
+    ("deleted edges are kept", "if (!is_member(del, n_del, prev[e])) prev[m++] = prev[e];", "prev[m++] = prev[e];"),
+    ("added edges are dropped", "else if (i >= m || add[j] < prev[i]) next[o++] = add[j++];", "else if (i >= m || add[j] < prev[i]) j++;"),
+    ("adjoint aggregation not transposed", "out[(int64_t)colidx[e] * f + j] += val[e] * g[u * f + j];",
+     "out[u * f + j] += val[e] * g[(int64_t)colidx[e] * f + j];"),
+    ("weight gradient with the operands exchanged", "s += x[i * f_in + k] * g[i * f_out + j];",
+     "s += x[i * f_in + (j % f_in)] * g[i * f_out + (k % f_out)];"),
+    ("adjoint M-transform not transposed", "s += M[t * T + k] * g[t * frame + i];", "s += M[k * T + t] * g[t * frame + i];"),
+    ("value updates ignored", "all[m].val = u >= 0 ? upd[u].val : val[e];", "all[m].val = val[e];"),
+    ("added values not taken", "if (i == 0 || add[i].key != add[i - 1].key) all[m++] = add[i];",
+     "if (i == 0 || add[i].key != add[i - 1].key) { all[m] = add[i]; all[m].val = 1.0; ++m; }"),
+]
+
+
+def pins():
+    """Every pin test as a zero-argument callable."""
+    calls = []
+    for seed in (0, 1, 2):
+        for sym in (True, False):
+            calls.append(lambda s=seed, y=sym: fwd.test_delta_apply_matches_dense_boolean_brute_force(s, y))
+    calls += [fwd.test_delta_apply_adversarial_tiny_cases, fwd.test_delta_apply_equals_from_scratch_every_step_c1,
+              fwd.test_delta_involution_and_composition, fwd.test_csr_from_edges_handles_repeats_and_order,
+              lambda: fwd.test_gcn_values_match_hand_worked_path(GOLDEN), fwd.test_xw_matches_numpy_rectangular,
+              fwd.test_spmm_c1_whole_layer_vs_dense, fwd.test_spmm_sqrt_degree_is_fixed_vector, fwd.test_spmm_special_graphs,
+              fwd.test_mproduct_closed_forms, fwd.test_c1_end_to_end_vs_dense_brute_force]
+    for sym in (True, False):
+        calls.append(lambda y=sym: fwd.test_gcn_values_match_dense_matrix_form(y))
+        for relu in (False, True):
+            calls.append(lambda y=sym, r=relu: fwd.test_spmm_matches_dense_brute_force(y, r))
+    calls += [lambda: fwd.test_m_matrix_matches_hand_worked(GOLDEN, "m_matrix_T3_w2.txt", 3, 2),
+              lambda: fwd.test_m_matrix_matches_hand_worked(GOLDEN, "m_matrix_T5_w3.txt", 5, 3)]
+    for T, w in ((8, 3), (32, 8), (5, 1), (6, 9)):
+        calls.append(lambda a=T, b=w: fwd.test_m_matrix_structure(a, b))
+    for sym in (False, True):
+        calls.append(lambda y=sym: bwd.test_spmm_t_matches_dense_transpose(y))
+    calls += [bwd.test_spmm_t_is_the_adjoint_of_spmm, bwd.test_spmm_t_equals_spmm_on_undirected_graphs_only,
+              bwd.test_spmm_t_closed_form_sqrt_degree, bwd.test_weight_grad_special_cases_and_numpy,
+              bwd.test_input_grad_matches_numpy_and_adjoint, bwd.test_layer_backward_matches_finite_differences,
+              bwd.test_weighted_delta_apply_trivial_cases, bwd.test_spmm_with_explicit_values_is_a_plain_sparse_product]
+    for T, w in ((7, 3), (5, 1), (6, 9), (12, 4)):
+        calls.append(lambda a=T, b=w: bwd.test_mproduct_t_adjoint_and_closed_forms(a, b))
+    for seed in (0, 1, 2):
+        calls.append(lambda s=seed: bwd.test_weighted_delta_apply_matches_dense_brute_force(s))
+    return calls
+
+
+def first_failure():
+    for call in pins():
+        try:
+            call()
+        except Exception as exc:          # an assertion, or an error the mistake provokes
+            return exc
+    return None
+
+
+def test_the_unmodified_oracle_passes_every_pin_called_this_way():
+    assert first_failure() is None
+
+
+@pytest.mark.parametrize("name,good,bad", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_a_planted_mistake_is_caught(tmp_path, name, good, bad):
+    text = open(SRC).read()
+    assert text.count(good) == 1, f"the oracle source no longer contains exactly one: {good}"
+    src, lib = tmp_path / "mutant.c", tmp_path / "libmutant.so"
+    src.write_text(text.replace(good, bad))
+    subprocess.check_call(["gcc", "-O1", "-fopenmp", "-fPIC", "-shared", "-w", "-o", str(lib), str(src), "-lm"])
+    oracle._load()                                       # make sure the real one is loaded, then swap
+    real = oracle._lib
+    mutant = ctypes.CDLL(str(lib))
+    for attr in dir(real):                               # same prototypes as the real library
+        fn = getattr(real, attr, None)
+        if attr.startswith("oracle_") and hasattr(fn, "argtypes"):
+            getattr(mutant, attr).argtypes = fn.argtypes
+            getattr(mutant, attr).restype = fn.restype
+    oracle._lib = mutant
+    try:
+        caught = first_failure()
+    finally:
+        oracle._lib = real
+    assert caught is not None, f"no pin noticed: {name}"
