@@ -314,6 +314,18 @@ int dgnn_concat_relu(const void *y0, int32_t f0, const void *y1, int32_t f1, voi
 int dgnn_lstm_cell(const void *gates_x, const void *gates_h, const float *bias, const void *c_prev, void *c_next,
                    void *h_next, int64_t n, int32_t hidden, dgnn_dtype dt, void *stream);
 
+/*
+ * One whole LSTM step without materialising the gate pre-activations: a = [y | h_prev] [w_x ; w_h] + bias is formed
+ * on the matrix cores and the cell of dgnn_lstm_cell is applied to the accumulators.
+ *   y [n][f_y], h_prev [n][hidden], w_x [f_y][4 * hidden], w_h [hidden][4 * hidden], bias fp32 [4 * hidden] or NULL
+ *   c [n][hidden]        cell state, updated IN PLACE;   h_next [n][hidden]   a buffer of its own
+ * Supported: fp32 storage, hidden = 32, f_y = 32 or 64 (DGNN_ERR_SHAPE otherwise: use the two dense transforms and
+ * dgnn_lstm_cell).  Same result as that composition up to the order of the fp32 sums.
+ */
+int dgnn_lstm_step(const void *y, int32_t f_y, const void *h_prev, const void *w_x, const void *w_h,
+                   const float *bias, void *c, void *h_next, int64_t n, int32_t hidden, dgnn_dtype dt,
+                   void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,7 +24,7 @@ DGNN_H_PRESCALED = 2
 EXPORTS = (
     "dgnn_strerror", "dgnn_csr_dinv", "dgnn_delta_h2d", "dgnn_delta_rebuild_workspace",
     "dgnn_delta_rebuild", "dgnn_feature_transform", "dgnn_spmm_workspace", "dgnn_spmm", "dgnn_mproduct",
-    "dgnn_delta_rebuild_weighted", "dgnn_spmm_weighted", "dgnn_concat_relu", "dgnn_lstm_cell",
+    "dgnn_delta_rebuild_weighted", "dgnn_spmm_weighted", "dgnn_concat_relu", "dgnn_lstm_cell", "dgnn_lstm_step",
     "dgnn_mproduct_backward", "dgnn_mproduct_block", "dgnn_mproduct_backward_block", "dgnn_relu_backward", "dgnn_weight_grad_workspace", "dgnn_weight_grad", "dgnn_input_grad",
 )
 
@@ -86,6 +86,7 @@ def load_library():
     lib.dgnn_spmm_weighted.argtypes = [_i64, _i64, _vp, _vp, _vp, _vp, _i32, _vp, ctypes.c_int, _u32, _vp, _sz, _vp]
     lib.dgnn_concat_relu.argtypes = [_vp, _i32, _vp, _i32, _vp, _i64, ctypes.c_int, _vp]
     lib.dgnn_lstm_cell.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _i32, ctypes.c_int, _vp]
+    lib.dgnn_lstm_step.argtypes = [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i32, ctypes.c_int, _vp]
     lib.dgnn_mproduct_block.argtypes = [_vp, _vp, _i64, _i64, _i32, _i32, _vp, _i64, _vp, _i64, ctypes.c_int, _vp]
     lib.dgnn_mproduct_backward_block.argtypes = [_vp, _vp, _i64, _i64, _i32, _i32, _vp, _i64, _vp, _i64, ctypes.c_int, _vp]
     lib.dgnn_relu_backward.argtypes = [_vp, _vp, _vp, _vp, _i64, _i32, ctypes.c_int, _vp]
@@ -285,6 +286,24 @@ def lstm_cell(gates_x, gates_h, bias, c_prev, c_next, h_next) -> None:
             raise ValueError("bias must have 4 * hidden entries")
     _check(load_library().dgnn_lstm_cell(_ptr(gates_x), _ptr(gates_h), _ptr(bias), _ptr(c_prev), _ptr(c_next), _ptr(h_next),
                                          n, hidden, dt, _stream(gates_x)), "dgnn_lstm_cell")
+
+
+def lstm_step_supported(y: torch.Tensor, hidden: int) -> bool:
+    return y.dtype == torch.float32 and hidden == 32 and y.shape[1] in (32, 64)
+
+
+def lstm_step(y, h_prev, w_x, w_h, bias, c, h_next) -> None:
+    """One LSTM step with the gate pre-activations kept on chip; c is updated in place."""
+    dt = _dtype_code(y)
+    n, f_y = y.shape
+    hidden = c.shape[1]
+    if (tuple(h_prev.shape) != (n, hidden) or tuple(h_next.shape) != (n, hidden) or tuple(w_x.shape) != (f_y, 4 * hidden)
+            or tuple(w_h.shape) != (hidden, 4 * hidden)):
+        raise ValueError("shape mismatch in lstm_step")
+    if bias is not None:
+        _need(bias, torch.float32, "bias")
+    _check(load_library().dgnn_lstm_step(_ptr(y), f_y, _ptr(h_prev), _ptr(w_x), _ptr(w_h), _ptr(bias), _ptr(c), _ptr(h_next),
+                                         n, hidden, dt, _stream(y)), "dgnn_lstm_step")
 
 
 def mproduct_backward(g_y: torch.Tensor, g_z: torch.Tensor, w: int, m_band: Optional[torch.Tensor] = None) -> None:

@@ -21,8 +21,9 @@ class CdgcnLayer(BlockRunner):
     blk.f + f_out must be feature widths the dense transform takes)."""
 
     def __init__(self, blk: BlockInputs, w: torch.Tensor, w_x: torch.Tensor, w_h: torch.Tensor,
-                 bias: Optional[torch.Tensor], hidden: int):
+                 bias: Optional[torch.Tensor], hidden: int, fused: bool = True):
         super().__init__(blk, keep_all_z=False)
+        self.fused = fused            # one-kernel LSTM step where the library has it (fp32, hidden 32)
         n, f = blk.n, blk.f
         f_out = w.shape[1]
         dt, dev = blk.x[0].dtype, self.dev
@@ -54,6 +55,10 @@ class CdgcnLayer(BlockRunner):
         with self._stage("concat_relu"):
             B.concat_relu(self.y0, self.y1, self.y)
         h_prev = self.h0 if t == 1 else self.h_all[t - 2]
+        if self.fused and B.lstm_step_supported(self.y, self.hidden):
+            with self._stage("lstm_step"):
+                B.lstm_step(self.y, h_prev, self.w_x, self.w_h, self.bias, self.c, self.h_all[t - 1])
+            return
         with self._stage("feature_transform"):
             B.feature_transform(self.y, self.w_x, self.gx)
             B.feature_transform(h_prev, self.w_h, self.gh)

@@ -146,3 +146,179 @@ extern "C" int dgnn_lstm_cell(const void *gates_x, const void *gates_h, const fl
     DGNN_RETURN_IF_LAUNCH_FAILED();
     return DGNN_OK;
 }
+
+// ---- One LSTM step with the gate pre-activations kept on chip -------------------------------------------
+// a = [Y | h_prev] [W_x ; W_h] + b is 4 * hidden wide and, written out, is two thirds of the traffic of an LSTM
+// step.  Here a wavefront takes 32 vertices, forms the TRANSPOSED gate tiles (W^T as the A operand, the rows
+// of [Y | h_prev] as the B operand) on the matrix cores, and applies the cell straight to the accumulators: with
+// hidden = 32 the four 32-column tiles ARE the four gates, and lane (i, h) holds, for vertex i and four consecutive
+// state elements per four registers, the input, forget, cell and output pre-activation in the same register slot of
+// the four tiles.  Traffic: Y, h_prev, c in; c, h out.  fp32 storage.
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// In the fused step the nonlinearities compete with the matrix cores for issue slots (they are as many cycles as
+// the products when taken from the math library), so they are built from the hardware exponential and reciprocal:
+// sig(x) = 1 / (1 + 2^(-x log2 e)), tanh(x) = 2 sig(2x) - 1; absolute error a few 1e-7.
+__device__ __forceinline__ float fast_sigmoid(float x) { return __frcp_rn(1.0f + __expf(-x)); }
+__device__ __forceinline__ float fast_tanh(float x) { return 2.0f * fast_sigmoid(2.0f * x) - 1.0f; }
+
+constexpr int kLstmHidden = 32;
+constexpr int kLstmThreads = 512;   // eight wavefronts share W in LDS: two per SIMD, so one multiplies while the other moves data
+constexpr int kLstmWaves = kLstmThreads / kWave;
+
+template <int FY>
+__global__ __launch_bounds__(kLstmThreads) void lstm_step_f32_kernel(const float *__restrict__ y, const float *__restrict__ h_prev,
+                                                                 const float *__restrict__ w_x, const float *__restrict__ w_h,
+                                                                 const float *__restrict__ bias, float *c,
+                                                                 float *__restrict__ h_next, int64_t n, int64_t n_tiles) {
+    constexpr int HID = kLstmHidden, G4 = 4 * HID;
+    constexpr int K = FY + HID, KH = K / 2;
+    constexpr int LDT = K + 4;                          // padded tile row (floats)
+    constexpr int Y_PIECES = 32 * FY / 4 / kWave;       // 16-byte pieces per lane of a tile of Y
+    constexpr int S_PIECES = 32 * HID / 4 / kWave;      // ... of a tile of h or c
+    static_assert(K >= 2 * HID && KH % 4 == 0, "the tile buffer also carries c and h (2 * hidden columns)");
+    __shared__ float s_w[K * G4];                       // rows 0 .. FY-1: W_x, then W_h
+    __shared__ __attribute__((aligned(16))) float s_tile[kLstmWaves][32 * LDT];
+
+    const int tid = threadIdx.x;
+    for (int idx = tid; idx < K * G4; idx += kLstmThreads) s_w[idx] = idx < FY * G4 ? w_x[idx] : w_h[idx - FY * G4];
+    const int lane = tid & (kWave - 1), wave = tid / kWave;
+    const int i = lane & 31, hh = lane >> 5;
+    float *tile_lds = s_tile[wave];
+    const int64_t stride = (int64_t)gridDim.x * kLstmWaves;
+    const int64_t first = (int64_t)blockIdx.x * kLstmWaves + wave;
+    __syncthreads();                                   // W is in LDS; from here on every wavefront is on its own
+    for (int64_t tile = first; tile < n_tiles; tile += stride) {
+        // ---- [Y | h_prev] tile: global -> LDS in whole lines (the other wavefront of the SIMD multiplies meanwhile)
+        const floatx4 zero = {0.f, 0.f, 0.f, 0.f};
+        floatx4 c_cur[S_PIECES];
+        {
+            floatx4 yv[Y_PIECES], hv[S_PIECES];
+#pragma unroll
+            for (int q = 0; q < Y_PIECES; ++q) {
+                const int64_t piece = tile * (32 * FY / 4) + q * kWave + lane;
+                yv[q] = (tile < n_tiles && piece * 4 < n * FY) ? reinterpret_cast<const floatx4 *>(y)[piece] : zero;
+            }
+#pragma unroll
+            for (int q = 0; q < S_PIECES; ++q) {
+                const int64_t piece = tile * (32 * HID / 4) + q * kWave + lane;
+                const bool ok = tile < n_tiles && piece * 4 < n * HID;
+                hv[q] = ok ? reinterpret_cast<const floatx4 *>(h_prev)[piece] : zero;
+                c_cur[q] = ok ? reinterpret_cast<const floatx4 *>(c)[piece] : zero;
+            }
+#pragma unroll
+            for (int q = 0; q < Y_PIECES; ++q) {
+                const int e = (q * kWave + lane) * 4;
+                *reinterpret_cast<floatx4 *>(&tile_lds[(e / FY) * LDT + e % FY]) = yv[q];
+            }
+#pragma unroll
+            for (int q = 0; q < S_PIECES; ++q) {
+                const int e = (q * kWave + lane) * 4;
+                *reinterpret_cast<floatx4 *>(&tile_lds[(e / HID) * LDT + FY + e % HID]) = hv[q];
+            }
+        }
+        wave_lds_sync();
+        floatx4 a[KH / 4];
+#pragma unroll
+        for (int q = 0; q < KH / 4; ++q) a[q] = *reinterpret_cast<const floatx4 *>(&tile_lds[i * LDT + hh * KH + q * 4]);
+        wave_lds_sync();                                                      // every lane has its operands
+        // the tile buffer now takes the old cell state in columns [0, hidden)
+#pragma unroll
+        for (int q = 0; q < S_PIECES; ++q) {
+            const int e = (q * kWave + lane) * 4;
+            *reinterpret_cast<floatx4 *>(&tile_lds[(e / HID) * LDT + e % HID]) = c_cur[q];
+        }
+        floatx16 acc[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[g][v] = 0.0f;
+#pragma unroll
+        for (int s = 0; s < KH; ++s) {
+            const float xv = a[s / 4][s % 4];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const float wv = s_w[(hh * KH + s) * G4 + g * 32 + i];
+                acc[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(wv, xv, acc[g], 0, 0, 0);     // transposed gate tile g
+            }
+        }
+        wave_lds_sync();                                                      // the old cell state is in LDS
+        // ---- the cell, on the accumulators: register 4 q + r of lane (i, h) is state element 8 q + 4 h + r of vertex i
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int k0 = 8 * q + 4 * hh;
+            const floatx4 c_old = *reinterpret_cast<const floatx4 *>(&tile_lds[i * LDT + k0]);
+            floatx4 c_new, h_new;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int k = k0 + r;
+                const float ai = acc[0][4 * q + r] + (bias ? bias[k] : 0.0f);
+                const float af = acc[1][4 * q + r] + (bias ? bias[HID + k] : 0.0f);
+                const float ag = acc[2][4 * q + r] + (bias ? bias[2 * HID + k] : 0.0f);
+                const float ao = acc[3][4 * q + r] + (bias ? bias[3 * HID + k] : 0.0f);
+                c_new[r] = fast_sigmoid(af) * c_old[r] + fast_sigmoid(ai) * fast_tanh(ag);
+                h_new[r] = fast_sigmoid(ao) * fast_tanh(c_new[r]);
+            }
+            *reinterpret_cast<floatx4 *>(&tile_lds[i * LDT + k0]) = c_new;
+            *reinterpret_cast<floatx4 *>(&tile_lds[i * LDT + HID + k0]) = h_new;
+        }
+        wave_lds_sync();
+        if (tile < n_tiles) {
+#pragma unroll
+            for (int q = 0; q < S_PIECES; ++q) {
+                const int e = (q * kWave + lane) * 4;
+                const int64_t piece = tile * (32 * HID / 4) + q * kWave + lane;
+                if (piece * 4 < n * HID) {
+                    reinterpret_cast<floatx4 *>(c)[piece] = *reinterpret_cast<const floatx4 *>(&tile_lds[(e / HID) * LDT + e % HID]);
+                    reinterpret_cast<floatx4 *>(h_next)[piece] =
+                        *reinterpret_cast<const floatx4 *>(&tile_lds[(e / HID) * LDT + HID + e % HID]);
+                }
+            }
+        }
+        wave_lds_sync();                                                      // the tile buffer is reused
+    }
+}
+
+template <int FY>
+int launch_lstm_step(const void *y, const void *h_prev, const void *w_x, const void *w_h, const float *bias, void *c,
+                     void *h_next, int64_t n, hipStream_t s) {
+    const int64_t n_tiles = (n + 31) / 32;
+    const int64_t needed = (n_tiles + kLstmWaves - 1) / kLstmWaves;
+    static int64_t resident = 0;               // workgroups the device holds at once (one value per instantiation)
+    if (resident == 0) {
+        int dev = 0, cus = 0, per_cu = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, lstm_step_f32_kernel<FY>, kLstmThreads, 0) == hipSuccess &&
+            cus > 0 && per_cu > 0)
+            resident = (int64_t)cus * per_cu;
+        else {
+            (void)hipGetLastError();
+            resident = 256;
+        }
+    }
+    const unsigned blocks = (unsigned)(needed < resident ? needed : resident);
+    hipLaunchKernelGGL(lstm_step_f32_kernel<FY>, dim3(blocks), dim3(kLstmThreads), 0, s, static_cast<const float *>(y),
+                       static_cast<const float *>(h_prev), static_cast<const float *>(w_x), static_cast<const float *>(w_h),
+                       bias, static_cast<float *>(c), static_cast<float *>(h_next), n, n_tiles);
+    DGNN_RETURN_IF_LAUNCH_FAILED();
+    return DGNN_OK;
+}
+
+}  // namespace
+
+extern "C" int dgnn_lstm_step(const void *y, int32_t f_y, const void *h_prev, const void *w_x, const void *w_h,
+                              const float *bias, void *c, void *h_next, int64_t n, int32_t hidden, dgnn_dtype dt,
+                              void *stream) {
+    if (!y || !h_prev || !w_x || !w_h || !c || !h_next) return DGNN_ERR_NULL;
+    if (n <= 0 || hidden != kLstmHidden || dt != DGNN_F32 || (f_y != 32 && f_y != 64)) return DGNN_ERR_SHAPE;
+    if (!fits_index(n)) return DGNN_ERR_OVERFLOW;
+    if (!aligned16(y) || !aligned16(h_prev) || !aligned16(c) || !aligned16(h_next)) return DGNN_ERR_ALIGN;
+    if (h_next == h_prev || h_next == c || h_next == y || c == y || c == h_prev) return DGNN_ERR_ALIAS;
+    hipStream_t s = (hipStream_t)stream;
+    return f_y == 32 ? launch_lstm_step<32>(y, h_prev, w_x, w_h, bias, c, h_next, n, s)
+                     : launch_lstm_step<64>(y, h_prev, w_x, w_h, bias, c, h_next, n, s);
+}

@@ -51,6 +51,15 @@ __device__ __forceinline__ int wave_find_row(const int32_t *__restrict__ rowptr,
     return lo - 1;
 }
 
+// Orders the LDS traffic of ONE wavefront: what its lanes have written to LDS before is visible to all of its
+// lanes after.  No s_barrier: other wavefronts of the workgroup are not waited for, so wavefronts that work on
+// private LDS tiles can drift apart (one loads while another multiplies).
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
 // Inclusive wavefront scans over 64 lanes.
 __device__ __forceinline__ int wave_scan_add(int v, int lane) {
 #pragma unroll

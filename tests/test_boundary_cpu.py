@@ -197,3 +197,17 @@ def test_cdgcn_argument_errors(lib):
     assert f(FAKE, FAKE + 64, None, FAKE + 128, FAKE + 128, FAKE + 256, 10, 20, 0, None) == -2
     assert f(FAKE, FAKE + 64, None, FAKE + 128, FAKE + 128, FAKE + 128, 10, 32, 0, None) == -5   # h_next over the state
     assert f(FAKE, FAKE + 64, None, FAKE + 128, FAKE + 128, FAKE + 256, 0, 32, 0, None) == -2
+
+
+def test_lstm_step_argument_errors(lib):
+    f = lib.dgnn_lstm_step
+    ok = [FAKE, 64, FAKE + 0x1000, FAKE + 0x2000, FAKE + 0x3000, None, FAKE + 0x4000, FAKE + 0x5000, 10, 32, 0, None]
+    def call(**kw):
+        a = list(ok)
+        for k, v in kw.items():
+            a[{"y": 0, "f_y": 1, "h_prev": 2, "c": 6, "h_next": 7, "n": 8, "hidden": 9, "dt": 10}[k]] = v
+        return f(*a)
+    assert call(y=None) == -1 and call(c=None) == -1
+    assert call(f_y=128) == -2 and call(hidden=64) == -2 and call(dt=1) == -2 and call(n=0) == -2
+    assert call(h_next=FAKE + 0x4000) == -5 and call(h_next=FAKE + 0x1000) == -5
+    assert call(y=FAKE + 8) == -7

@@ -80,3 +80,37 @@ def test_cdgcn_layer_over_a_block(case):
         h, c = oracle.lstm_cell(y, h, c, to_f64(w_x), to_f64(w_h), to_f64(bias))
         # every timestep adds stored tensors between the inputs and h_t (Y0, Y1, Y, the two gate halves, c, h)
         assert_close(to_f64(got[t - 1]), h, dtype, f"{case}: h_{t}", stores=7 * t)
+
+
+@pytest.mark.parametrize("f_y", [32, 64])
+@pytest.mark.parametrize("n", [1, 31, 32, 33, 4097, 20_011])
+@pytest.mark.parametrize("with_bias", [False, True])
+def test_fused_lstm_step(f_y, n, with_bias):
+    hidden = 32
+    y, h = randn((n, f_y), n + f_y), randn((n, hidden), n + 1)
+    c = randn((n, hidden), n + 2)
+    w_x = randn((f_y, 4 * hidden), 5) / np.sqrt(f_y)
+    w_h = randn((hidden, 4 * hidden), 6) / np.sqrt(hidden)
+    bias = randn((4 * hidden,), 7) if with_bias else None
+    h_want, c_want = oracle.lstm_cell(to_f64(y), to_f64(h), to_f64(c), to_f64(w_x), to_f64(w_h),
+                                      to_f64(bias) if with_bias else None)
+    cd = c.to(DEV)
+    hn = torch.full((n, hidden), float("nan"), device=DEV)
+    dg.lstm_step(y.to(DEV), h.to(DEV), w_x.to(DEV), w_h.to(DEV), bias.to(DEV) if with_bias else None, cd, hn)
+    assert_close(to_f64(cd), c_want, torch.float32, f"fused step: c, n={n}")
+    assert_close(to_f64(hn), h_want, torch.float32, f"fused step: h, n={n}")
+
+
+def test_fused_and_composed_layers_agree():
+    wl = replace(WORKLOADS["c3"].scaled(4096, T=5), name="cd-c3")
+    f, hidden = wl.f, 32
+    w = glorot_weight(wl, 0).to(DEV)
+    w_x = (randn((2 * f, 4 * hidden), 11) / np.sqrt(2 * f)).to(DEV)
+    w_h = (randn((hidden, 4 * hidden), 12) / np.sqrt(hidden)).to(DEV)
+    blk = make_block(wl, DEV, gen_device="cpu")
+    outs = []
+    for fused in (True, False):
+        layer = CdgcnLayer(blk, w, w_x, w_h, None, hidden, fused=fused)
+        layer.load_first()
+        outs.append(layer.run().clone())
+    assert_close(to_f64(outs[0]), to_f64(outs[1]), torch.float32, "fused vs composed layer")
