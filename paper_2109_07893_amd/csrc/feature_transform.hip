@@ -21,6 +21,8 @@
 // the "staged" kernels are used instead: a tile is read from global memory as consecutive 16-byte pieces,
 // laid down in LDS with padded rows, picked up in operand layout, and the result goes back the same way,
 // so that every global access of a wavefront is a run of whole lines.  The direct kernels serve the rest.
+// A tile buffer belongs to one wavefront, so its phases are ordered by wavefront-level LDS synchronisation, not by
+// workgroup barriers: the wavefronts of a workgroup drift apart and one multiplies while another moves data.
 // Every kernel is launched as a persistent grid (as many workgroups as fit on the device at once).
 #include <algorithm>
 
@@ -159,7 +161,7 @@ __global__ __launch_bounds__(kThreads) void xw_f32_staged_kernel(const float *__
             *reinterpret_cast<floatx4 *>(&tile_lds[(e / FIN) * LDT + e % FIN]) = in_next[q];
         }
         fetch(tile + stride);
-        __syncthreads();
+        wave_lds_sync();
         floatx4 a[KH / 4];
 #pragma unroll
         for (int q = 0; q < KH / 4; ++q) a[q] = *reinterpret_cast<const floatx4 *>(&tile_lds[i * LDT + hh * KH + q * 4]);
@@ -179,7 +181,7 @@ __global__ __launch_bounds__(kThreads) void xw_f32_staged_kernel(const float *__
                 acc[jt] = __builtin_amdgcn_mfma_f32_32x32x2f32(wv, xv, acc[jt], 0, 0, 0);   // (X W)^T tile
             }
         }
-        __syncthreads();                                                      // every lane has its operands
+        wave_lds_sync();                                                      // every lane has its operands
         // ---- result tile: accumulators -> LDS -> whole lines
 #pragma unroll
         for (int jt = 0; jt < NT; ++jt)
@@ -188,7 +190,7 @@ __global__ __launch_bounds__(kThreads) void xw_f32_staged_kernel(const float *__
                 *reinterpret_cast<floatx4 *>(&tile_lds[i * LDT + jt * 32 + 8 * g + 4 * hh]) =
                     floatx4{acc[jt][4 * g] * scale, acc[jt][4 * g + 1] * scale, acc[jt][4 * g + 2] * scale,
                             acc[jt][4 * g + 3] * scale};
-        __syncthreads();
+        wave_lds_sync();
         if (tile < n_tiles) {
 #pragma unroll
             for (int q = 0; q < OUT_PIECES; ++q) {
@@ -198,7 +200,7 @@ __global__ __launch_bounds__(kThreads) void xw_f32_staged_kernel(const float *__
                     reinterpret_cast<floatx4 *>(h)[piece] = *reinterpret_cast<const floatx4 *>(&tile_lds[(e / FOUT) * LDT + e % FOUT]);
             }
         }
-        __syncthreads();                                                      // the tile buffer is reused
+        wave_lds_sync();                                                      // the tile buffer is reused
     }
 }
 
@@ -332,13 +334,13 @@ __global__ __launch_bounds__(kThreads) void xw_bf16_staged_kernel(const uint16_t
             *reinterpret_cast<uintx4 *>(&tile_lds[(e / FIN) * LDT + e % FIN]) = in_next[q];
         }
         fetch(tile + stride);
-        __syncthreads();
+        wave_lds_sync();
         bf16x8 a[KS];
 #pragma unroll
         for (int s = 0; s < KS; ++s) a[s] = *reinterpret_cast<const bf16x8 *>(&tile_lds[i * LDT + hh * KH + s * 8]);
         const int64_t row = tile * 32 + i;
         const float scale = (row_scale && tile < n_tiles && row < n) ? row_scale[row] : 1.0f;
-        __syncthreads();                                                      // every lane has its operands
+        wave_lds_sync();                                                      // every lane has its operands
 #pragma unroll
         for (int j0 = 0; j0 < NT; j0 += JG) {
             floatx16 acc[JG];
@@ -363,7 +365,7 @@ __global__ __launch_bounds__(kThreads) void xw_bf16_staged_kernel(const uint16_t
                 }
             __builtin_amdgcn_sched_barrier(0);   // keep the column groups apart: their accumulators share registers
         }
-        __syncthreads();
+        wave_lds_sync();
         if (tile < n_tiles) {
 #pragma unroll
             for (int q = 0; q < OUT_PIECES; ++q) {
@@ -373,7 +375,7 @@ __global__ __launch_bounds__(kThreads) void xw_bf16_staged_kernel(const uint16_t
                     reinterpret_cast<uintx4 *>(h)[piece] = *reinterpret_cast<const uintx4 *>(&tile_lds[(e / FOUT) * LDT + e % FOUT]);
             }
         }
-        __syncthreads();                                                      // the tile buffer is reused
+        wave_lds_sync();                                                      // the tile buffer is reused
     }
 }
 
