@@ -40,17 +40,35 @@ def library_path() -> str:
 
 
 def build_library(verbose: bool = False) -> str:
-    """Compile csrc/*.hip for gfx950 into csrc/libdgnn.so with hipcc (cross-compiles without a GPU)."""
+    """Compile csrc/*.hip for gfx950 into csrc/libdgnn.so with hipcc (cross-compiles without a GPU): one object per
+    source, compiled side by side, then one link."""
+    from concurrent.futures import ThreadPoolExecutor
     srcs = sorted(glob.glob(os.path.join(_CSRC, "*.hip")))
-    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-I", os.path.join(_ROOT, "include"), "-I", _CSRC, "-o", _LIB_PATH] + srcs
-    res = subprocess.run(cmd, capture_output=True, text=True)
+    objdir = os.path.join(_CSRC, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    flags = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+             "-I", os.path.join(_ROOT, "include"), "-I", _CSRC]
+
+    def compile_one(src):
+        obj = os.path.join(objdir, os.path.basename(src)[:-4] + ".o")
+        return obj, subprocess.run(["hipcc", "-c"] + flags + ["-o", obj, src], capture_output=True, text=True)
+
+    with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as pool:
+        results = list(pool.map(compile_one, srcs))
+    for obj, res in results:
+        if verbose or res.returncode != 0:
+            print(res.stdout)
+            print(res.stderr)
+        if res.returncode != 0:
+            raise RuntimeError(f"hipcc failed compiling {obj}")
+    res = subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", _LIB_PATH] + [o for o, _ in results],
+                         capture_output=True, text=True)
     if verbose or res.returncode != 0:
         print(res.stdout)
         print(res.stderr)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed building libdgnn.so")
+        raise RuntimeError("hipcc failed linking libdgnn.so")
     return _LIB_PATH
 
 
