@@ -152,10 +152,17 @@ def weighted_step(args, wl, blk, dev):
     def aggregate():
         dg.spmm_weighted(rpn, cin, vn, cap, h, z, ws_s, flags=dg.DGNN_RELU)
 
+    dinv_w = torch.empty(n, dtype=torch.float32, device=dev)
+    ws_d = torch.empty(dg.csr_weighted_dinv_workspace(cap), dtype=torch.uint8, device=dev)
+
+    def normalise():
+        dg.csr_weighted_dinv(rpn, vn, cap, dinv_w, ws_d)
+
     out = {}
     s = h.element_size()
     for name, fn, byts in (("delta_rebuild_weighted", rebuild, 8 * nnz1 + 8 * cap + 16 * n + 20 * (ar.numel() + dr.numel()) + 12 * ur.numel()),
-                           ("spmm_weighted", aggregate, 8 * cap + 4 * n + 2 * s * n * f)):
+                           ("spmm_weighted", aggregate, 8 * cap + 4 * n + 2 * s * n * f),
+                           ("csr_weighted_dinv", normalise, 4 * cap + 8 * n)):
         for _ in range(2):
             fn()
         torch.cuda.synchronize()

@@ -201,12 +201,31 @@ int dgnn_delta_rebuild_weighted(int64_t n,
 
 /*
  * Z = sigma?(V H) for a snapshot with explicit values, Z[u] = sum over stored (u,v) of val(u,v) * H[v]
- * (Eqn (2) with the matrix given entry by entry instead of through Eqn (1)).  flags: DGNN_RELU or 0; everything
- * else as dgnn_spmm (same workspace query).  The adjoint V^T G is the same call on the transposed snapshot.
+ * (Eqn (2) with the matrix given entry by entry instead of through Eqn (1)).
+ *   dinv NULL:      exactly that; flags: DGNN_RELU or 0.
+ *   dinv [n] given: the sym-normalised weighted matrix D^(-1/2) V D^(-1/2) without materialising its values,
+ *                   Z[u] = dinv[u] * sum val(u,v) * h[v] with h[v] = dinv[v] * H[v] already (DGNN_H_PRESCALED is
+ *                   then required: the row_scale of dgnn_feature_transform).  With dinv from
+ *                   dgnn_csr_weighted_dinv this is Eqn (1) generalised to weighted snapshots: only the values that
+ *                   change travel from the host (dgnn_delta_rebuild_weighted), the normalisation is recomputed here.
+ * Everything else as dgnn_spmm (same workspace query).  The adjoint is the same call on the transposed snapshot.
  */
 int dgnn_spmm_weighted(int64_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *val,
-                       const void *h, int32_t f, void *z, dgnn_dtype dt, uint32_t flags,
+                       const float *dinv, const void *h, int32_t f, void *z, dgnn_dtype dt, uint32_t flags,
                        void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * dinv[u] = (sum of val over row u)^(-1/2): the weighted counterpart of (1 + deg_u)^(-1/2) of Eqn (1) (for values
+ * that are all 1 it is the same number).  Reading: the paper normalises its smoothed, weighted snapshots but does
+ * not print the formula; this is Eqn (1) with the degree taken as the weighted row sum, self loop included.
+ * ws: device scratch (16-byte aligned) of at least dgnn_csr_weighted_dinv_workspace(nnz) bytes (pieces of rows
+ * that are summed by several wavefronts); contents need not be preserved.  Every sum has a fixed
+ * order, results repeat bit for bit.  val[0 .. nnz) is read; errors: NULL, SHAPE (n <= 0, nnz <= 0), OVERFLOW,
+ * CAPACITY (workspace too small), ALIGN.  A row without entries gets +inf.
+ */
+int dgnn_csr_weighted_dinv_workspace(int64_t nnz, size_t *bytes);
+int dgnn_csr_weighted_dinv(int64_t n, int64_t nnz, const int32_t *rowptr, const float *val, float *dinv,
+                           void *ws, size_t ws_bytes, void *stream);
 
 /*
  * ---- Gradient propagation through the same path (Section "Gradient Checkpoint": a block is run forward

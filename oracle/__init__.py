@@ -276,3 +276,13 @@ def lstm_cell(x, h, c, w_x, w_h, bias):
     ai, af, ag, ao = (a[:, q * hid:(q + 1) * hid] for q in range(4))
     c2 = _sig(af) * c + _sig(ai) * np.tanh(ag)
     return _sig(ao) * np.tanh(c2), c2
+
+
+def gcn_values_weighted(rowptr, colidx, val) -> np.ndarray:
+    """Eqn (1) for a snapshot with a value per stored entry: val(u,v) / sqrt(d_u d_v) with d_u the sum of the
+    values of row u (self loop included); for values that are all 1 this is gcn_values."""
+    rowptr, colidx, val = _a(rowptr, np.int32), _a(colidx, np.int32), _a(val, np.float64)
+    n = rowptr.size - 1
+    d = np.array([val[rowptr[u]:rowptr[u + 1]].sum() for u in range(n)])
+    rows = np.repeat(np.arange(n), np.diff(rowptr))
+    return val / np.sqrt(d[rows] * d[colidx])

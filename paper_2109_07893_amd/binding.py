@@ -24,7 +24,7 @@ DGNN_H_PRESCALED = 2
 EXPORTS = (
     "dgnn_strerror", "dgnn_csr_dinv", "dgnn_delta_h2d", "dgnn_delta_rebuild_workspace",
     "dgnn_delta_rebuild", "dgnn_feature_transform", "dgnn_spmm_workspace", "dgnn_spmm", "dgnn_mproduct",
-    "dgnn_delta_rebuild_weighted", "dgnn_spmm_weighted", "dgnn_concat_relu", "dgnn_lstm_cell", "dgnn_lstm_step",
+    "dgnn_delta_rebuild_weighted", "dgnn_spmm_weighted", "dgnn_csr_weighted_dinv_workspace", "dgnn_csr_weighted_dinv", "dgnn_concat_relu", "dgnn_lstm_cell", "dgnn_lstm_step",
     "dgnn_mproduct_backward", "dgnn_mproduct_block", "dgnn_mproduct_backward_block", "dgnn_relu_backward", "dgnn_weight_grad_workspace", "dgnn_weight_grad", "dgnn_input_grad",
 )
 
@@ -101,7 +101,9 @@ def load_library():
     lib.dgnn_delta_rebuild_weighted.argtypes = [_i64, _vp, _vp, _vp, _i64, _vp, _vp, _vp, _i64, _vp, _vp, _i64,
                                                 _vp, _vp, _vp, _i64, _vp, _vp, _vp, _i64, ctypes.POINTER(_i64),
                                                 _vp, _sz, _u32, _vp, _vp]
-    lib.dgnn_spmm_weighted.argtypes = [_i64, _i64, _vp, _vp, _vp, _vp, _i32, _vp, ctypes.c_int, _u32, _vp, _sz, _vp]
+    lib.dgnn_spmm_weighted.argtypes = [_i64, _i64, _vp, _vp, _vp, _vp, _vp, _i32, _vp, ctypes.c_int, _u32, _vp, _sz, _vp]
+    lib.dgnn_csr_weighted_dinv_workspace.argtypes = [_i64, ctypes.POINTER(_sz)]
+    lib.dgnn_csr_weighted_dinv.argtypes = [_i64, _i64, _vp, _vp, _vp, _vp, _sz, _vp]
     lib.dgnn_concat_relu.argtypes = [_vp, _i32, _vp, _i32, _vp, _i64, ctypes.c_int, _vp]
     lib.dgnn_lstm_cell.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _i32, ctypes.c_int, _vp]
     lib.dgnn_lstm_step.argtypes = [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i32, ctypes.c_int, _vp]
@@ -266,16 +268,34 @@ def delta_rebuild_weighted(rowptr_prev, colidx_prev, val_prev, nnz_prev: int, ad
     return int(nnz_next.value)
 
 
-def spmm_weighted(rowptr, colidx, val, nnz: int, h: torch.Tensor, z: torch.Tensor, ws, flags: int = 0) -> None:
-    """Z = sigma?(V H) with one explicit value per stored entry."""
+def spmm_weighted(rowptr, colidx, val, nnz: int, h: torch.Tensor, z: torch.Tensor, ws, flags: int = 0,
+                  dinv: Optional[torch.Tensor] = None) -> None:
+    """Z = sigma?(V H) with one explicit value per stored entry; with dinv (and DGNN_H_PRESCALED) the
+    sym-normalised weighted matrix."""
     _need(rowptr, torch.int32, "rowptr"); _need(colidx, torch.int32, "colidx"); _need(val, torch.float32, "val")
     dt = _dtype_code(h)
     n, f = h.shape
     if rowptr.numel() != n + 1 or tuple(z.shape) != (n, f) or z.dtype != h.dtype or colidx.numel() < nnz or val.numel() < nnz:
         raise ValueError("shape mismatch in spmm_weighted")
-    _check(load_library().dgnn_spmm_weighted(n, nnz, _ptr(rowptr), _ptr(colidx), _ptr(val), _ptr(h), f, _ptr(z), dt,
-                                             flags, _ptr(ws), ws.numel() * ws.element_size(), _stream(h)),
+    _check(load_library().dgnn_spmm_weighted(n, nnz, _ptr(rowptr), _ptr(colidx), _ptr(val), _ptr(dinv), _ptr(h), f, _ptr(z),
+                                             dt, flags, _ptr(ws), ws.numel() * ws.element_size(), _stream(h)),
            "dgnn_spmm_weighted")
+
+
+def csr_weighted_dinv_workspace(nnz: int) -> int:
+    out = _sz(0)
+    _check(load_library().dgnn_csr_weighted_dinv_workspace(nnz, ctypes.byref(out)), "dgnn_csr_weighted_dinv_workspace")
+    return int(out.value)
+
+
+def csr_weighted_dinv(rowptr: torch.Tensor, val: torch.Tensor, nnz: int, dinv: torch.Tensor, ws: torch.Tensor) -> None:
+    """dinv[u] = (sum of the values of row u)^(-1/2)."""
+    _need(rowptr, torch.int32, "rowptr"); _need(val, torch.float32, "val"); _need(dinv, torch.float32, "dinv")
+    n = rowptr.numel() - 1
+    if dinv.numel() != n or val.numel() < nnz:
+        raise ValueError("shape mismatch in csr_weighted_dinv")
+    _check(load_library().dgnn_csr_weighted_dinv(n, nnz, _ptr(rowptr), _ptr(val), _ptr(dinv), _ptr(ws),
+                                                 ws.numel() * ws.element_size(), _stream(rowptr)), "dgnn_csr_weighted_dinv")
 
 
 def concat_relu(y0: torch.Tensor, y1: torch.Tensor, out: torch.Tensor) -> None:

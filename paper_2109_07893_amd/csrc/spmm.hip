@@ -582,8 +582,162 @@ extern "C" int dgnn_spmm(int64_t n, int64_t nnz, const int32_t *rowptr, const in
 }
 
 extern "C" int dgnn_spmm_weighted(int64_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *val,
-                                  const void *h, int32_t f, void *z, dgnn_dtype dt, uint32_t flags,
+                                  const float *dinv, const void *h, int32_t f, void *z, dgnn_dtype dt, uint32_t flags,
                                   void *ws, size_t ws_bytes, void *stream) {
     if (!val) return DGNN_ERR_NULL;
-    return spmm(n, nnz, rowptr, colidx, nullptr, val, h, f, z, dt, flags, DGNN_RELU, ws, ws_bytes, stream);
+    // with a normalisation the right-hand factor must already be in the rows of h: the kernel gathers one
+    // per-entry factor (the value), not two
+    if (dinv && !(flags & DGNN_H_PRESCALED)) return DGNN_ERR_SHAPE;
+    if (!dinv && (flags & DGNN_H_PRESCALED)) return DGNN_ERR_SHAPE;
+    return spmm(n, nnz, rowptr, colidx, dinv, val, h, f, z, dt, flags, DGNN_RELU | DGNN_H_PRESCALED, ws, ws_bytes, stream);
+}
+
+namespace {
+
+// ---- dinv[u] = (sum of the values of row u)^(-1/2): the weighted counterpart of 1 + deg_u -------------------
+// Split by ENTRIES like the aggregation, so that hub rows of a power-law graph cost what their entries cost:
+// a wavefront owns kSumRange consecutive entries, copies their values to LDS with coalesced loads, and then
+// every lane adds up whole rows out of LDS (rows that hold more than kCoop of the range's entries are summed
+// by the 64 lanes together).  A row cut by the range's ends leaves a piece in the workspace; a second small
+// kernel adds a cut row's pieces in entry order.  Every sum has an order fixed by the row structure alone:
+// results repeat bit for bit.
+constexpr int kSumRange = 4096;
+constexpr int kCoop = 64;
+
+// p_cont: piece of the row that began in an earlier range; p_own/owner: first piece of the row that begins in
+// this range and runs past its end (owner = -1: there is none)
+struct SumRec { float p_cont, p_own; int32_t owner, pad; };
+
+// Sums of eight rows at once: v[q] is this lane's share of row q.  Three exchange steps halve what a lane keeps
+// (the lane's bit 0 chooses the half of q, bit 1 the quarter, bit 2 the row), three more add up over the other
+// lane bits: eleven cross-lane moves instead of forty-eight.  Returns, in lane l, the sum of row l % 8.
+__device__ __forceinline__ float wave_sum8(const float (&v)[8], int lane) {
+    float w4[4], w2[2];
+    const bool b0 = lane & 1, b1 = lane & 2, b2 = lane & 4;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) w4[q] = (b0 ? v[q + 4] : v[q]) + __shfl_xor(b0 ? v[q] : v[q + 4], 1, kWave);
+#pragma unroll
+    for (int q = 0; q < 2; ++q) w2[q] = (b1 ? w4[q + 2] : w4[q]) + __shfl_xor(b1 ? w4[q] : w4[q + 2], 2, kWave);
+    float r = (b2 ? w2[1] : w2[0]) + __shfl_xor(b2 ? w2[0] : w2[1], 4, kWave);
+    r += __shfl_xor(r, 8, kWave);
+    r += __shfl_xor(r, 16, kWave);
+    r += __shfl_xor(r, 32, kWave);
+    // this lane now holds row 4 * bit0 + 2 * bit1 + bit2; row q is wanted in the lanes with l % 8 == q
+    const int q = lane & 7;
+    return __shfl(r, ((q >> 2) & 1) | (q & 2) | ((q & 1) << 2), kWave);
+}
+
+__global__ __launch_bounds__(kWave) void weighted_rowsum_kernel(int n, int nnz, const int32_t *__restrict__ rowptr,
+                                                               const float *__restrict__ val, SumRec *__restrict__ recs,
+                                                               float *__restrict__ dinv) {
+    __shared__ float s_val[kSumRange];
+    const int lane = threadIdx.x, range = blockIdx.x;
+    const int e0 = range * kSumRange, e1 = (int)min((int64_t)e0 + kSumRange, (int64_t)nnz);
+    const bool last = e1 == nnz;
+    // the values of the range, 64 consecutive ones per load
+#pragma unroll 16
+    for (int i = lane; i < kSumRange; i += kWave) s_val[i] = val[min(e0 + i, nnz - 1)];   // unconditional: loads stay in flight together
+    // rows of the range: the one cut by its begin (if any), then every row that begins in [e0, e1), empty ones
+    // included; the last range also takes the empty rows behind the last entry
+    const int k_lo = wave_find_row(rowptr, n, e0 - 1, lane) + 1;          // first row that begins at e0 or later
+    const int k_first = rowptr[k_lo] > e0 ? k_lo - 1 : k_lo;              // rowptr[n] = nnz > e0
+    wave_lds_sync();
+    float p_cont = 0.0f, p_own = 0.0f;
+    int owner = -1;
+    bool more = true;
+    for (int base = k_first; more; base += kWave) {
+        const int r = base + lane;
+        const int rb_raw = rowptr[min(r, n)];
+        const bool valid = r < n && (last || rb_raw < e1);     // the range's rows end where a row begins at e1 or later
+        more = __ballot(valid) == ~0ull;
+        const int rb = valid ? rb_raw : e1, re = valid ? rowptr[r + 1] : e1;
+        const int b = max(rb, e0) - e0, e = min(re, e1) - e0;
+        const bool coop = e - b > kCoop;
+        float sum = 0.0f;
+        if (!coop) {                                                       // four entries a round, reads past the row's end masked
+            float s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+            for (int i = b; i < e; i += 4) {
+                const float x0 = s_val[i], x1 = s_val[min(i + 1, kSumRange - 1)], x2 = s_val[min(i + 2, kSumRange - 1)],
+                            x3 = s_val[min(i + 3, kSumRange - 1)];
+                sum += x0;
+                s1 += i + 1 < e ? x1 : 0.0f;
+                s2 += i + 2 < e ? x2 : 0.0f;
+                s3 += i + 3 < e ? x3 : 0.0f;
+            }
+            sum = (sum + s1) + (s2 + s3);
+        }
+        // longer rows: all lanes together, eight rows per round so that one set of cross-lane moves serves eight sums
+        const uint64_t coop_mask = __ballot(coop);
+        const int rank = __popcll(coop_mask & ((1ull << lane) - 1));
+        int group = 0;
+        for (uint64_t todo = coop_mask; todo; ++group) {
+            float v[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                float a0 = 0.0f, a1 = 0.0f;
+                if (todo) {
+                    const int src = __builtin_ctzll(todo);
+                    todo &= todo - 1;
+                    const int bb = __builtin_amdgcn_readlane(b, src), ee = __builtin_amdgcn_readlane(e, src);
+                    int i = bb + lane;
+                    for (; i + kWave < ee; i += 2 * kWave) { a0 += s_val[i]; a1 += s_val[i + kWave]; }
+                    if (i < ee) a0 += s_val[i];
+                }
+                v[q] = a0 + a1;
+            }
+            const float t = __shfl(wave_sum8(v, lane), rank & 7, kWave);
+            if (coop && (rank >> 3) == group) sum = t;
+        }
+        const bool open_l = rb < e0, open_r = re > e1;
+        if (valid && !open_l && !open_r) dinv[r] = 1.0f / sqrtf(sum);
+        const uint64_t m_cont = __ballot(valid && open_l), m_own = __ballot(valid && !open_l && open_r);
+        if (m_cont) p_cont = __shfl(sum, __builtin_ctzll(m_cont), kWave);
+        if (m_own) { const int src = __builtin_ctzll(m_own); p_own = __shfl(sum, src, kWave); owner = base + src; }
+    }
+    if (lane == 0) recs[range] = SumRec{p_cont, p_own, owner, 0};
+}
+
+// a row that begins in range w and ends in a later one: its pieces in entry order
+__global__ __launch_bounds__(256) void weighted_rowsum_fix_kernel(int n_ranges, const int32_t *__restrict__ rowptr,
+                                                                  const SumRec *__restrict__ recs, float *__restrict__ dinv) {
+    const int w = blockIdx.x * 256 + threadIdx.x;
+    if (w >= n_ranges) return;
+    const SumRec rec = recs[w];
+    if (rec.owner < 0) return;
+    const int end = rowptr[rec.owner + 1];
+    float acc = rec.p_own;
+    for (int r = w + 1; (int64_t)r * kSumRange < end; ++r) acc += recs[r].p_cont;
+    dinv[rec.owner] = 1.0f / sqrtf(acc);
+}
+
+size_t weighted_dinv_workspace(int64_t nnz) {
+    return round_up(sizeof(SumRec) * (size_t)((nnz + kSumRange - 1) / kSumRange), (size_t)256) + 256;
+}
+
+}  // namespace
+
+extern "C" int dgnn_csr_weighted_dinv_workspace(int64_t nnz, size_t *bytes) {
+    if (!bytes) return DGNN_ERR_NULL;
+    if (nnz < 0) return DGNN_ERR_SHAPE;
+    if (!fits_index(nnz)) return DGNN_ERR_OVERFLOW;
+    *bytes = weighted_dinv_workspace(nnz);
+    return DGNN_OK;
+}
+
+extern "C" int dgnn_csr_weighted_dinv(int64_t n, int64_t nnz, const int32_t *rowptr, const float *val, float *dinv,
+                                      void *ws, size_t ws_bytes, void *stream) {
+    if (!rowptr || !val || !dinv || !ws) return DGNN_ERR_NULL;
+    if (n <= 0 || nnz <= 0) return DGNN_ERR_SHAPE;
+    if (!fits_index(n + 1) || !fits_index(nnz)) return DGNN_ERR_OVERFLOW;
+    if (!aligned16(ws)) return DGNN_ERR_ALIGN;
+    if (ws_bytes < weighted_dinv_workspace(nnz)) return DGNN_ERR_CAPACITY;
+    hipStream_t s = (hipStream_t)stream;
+    const int ranges = (int)((nnz + kSumRange - 1) / kSumRange);
+    hipLaunchKernelGGL(weighted_rowsum_kernel, dim3((unsigned)ranges), dim3(kWave), 0, s, (int)n, (int)nnz, rowptr, val,
+                       (SumRec *)ws, dinv);
+    DGNN_RETURN_IF_LAUNCH_FAILED();
+    hipLaunchKernelGGL(weighted_rowsum_fix_kernel, dim3((unsigned)((ranges + 255) / 256)), dim3(256), 0, s, ranges, rowptr,
+                       (const SumRec *)ws, dinv);
+    DGNN_RETURN_IF_LAUNCH_FAILED();
+    return DGNN_OK;
 }

@@ -181,9 +181,13 @@ def test_weighted_argument_errors(lib):
     assert call(cap=20) == -3
     assert call(vn=FAKE) == -5
     f = lib.dgnn_spmm_weighted
-    assert f(10, 20, FAKE, FAKE, None, FAKE, 32, FAKE + 4096, 0, 0, FAKE + 8192, 1 << 24, None) == -1
-    assert f(10, 20, FAKE, FAKE, FAKE, FAKE, 32, FAKE + 4096, 0, 2, FAKE + 8192, 1 << 24, None) == -2   # no pre-scaled mode
-    assert f(10, 20, FAKE, FAKE, FAKE, FAKE, 32, FAKE, 0, 0, FAKE + 8192, 1 << 24, None) == -5
+    assert f(10, 20, FAKE, FAKE, None, None, FAKE, 32, FAKE + 4096, 0, 0, FAKE + 8192, 1 << 24, None) == -1
+    assert f(10, 20, FAKE, FAKE, FAKE, None, FAKE, 32, FAKE + 4096, 0, 2, FAKE + 8192, 1 << 24, None) == -2   # pre-scaled needs dinv
+    assert f(10, 20, FAKE, FAKE, FAKE, FAKE, FAKE, 32, FAKE + 4096, 0, 0, FAKE + 8192, 1 << 24, None) == -2   # dinv needs pre-scaled h
+    assert f(10, 20, FAKE, FAKE, FAKE, None, FAKE, 32, FAKE, 0, 0, FAKE + 8192, 1 << 24, None) == -5
+    assert lib.dgnn_csr_weighted_dinv(10, 20, FAKE, None, FAKE, FAKE, 1 << 20, None) == -1
+    assert lib.dgnn_csr_weighted_dinv(0, 20, FAKE, FAKE, FAKE, FAKE, 1 << 20, None) == -2
+    assert lib.dgnn_csr_weighted_dinv(10, 1 << 20, FAKE, FAKE, FAKE, FAKE, 64, None) == -3
 
 
 def test_cdgcn_argument_errors(lib):

@@ -155,3 +155,74 @@ def test_smoothed_series_through_the_weighted_path(name, n, life, mode):
     dg.spmm_weighted(dev(g_rp, torch.int32), dev(g_ci, torch.int32), dev(g_val, torch.float32), int(g_ci.size), h.to(DEV), z,
                      ws, flags=dg.DGNN_RELU)
     assert_close(to_f64(z), want, torch.float32, f"aggregation over the smoothed snapshot ({mode})")
+    # and normalised as in Eqn (1), from the same carried values: nothing but the count changes travelled
+    want = oracle.spmm(g_rp, g_ci, to_f64(h), relu=True, val=oracle.gcn_values_weighted(g_rp, g_ci, g_val.astype(np.float64)))
+    rp_d, val_d = dev(g_rp, torch.int32), dev(g_val, torch.float32)
+    dinv = torch.empty(wl.n, device=DEV)
+    dg.csr_weighted_dinv(rp_d, val_d, int(g_ci.size), dinv, ws_dinv(int(g_ci.size)))
+    hs = torch.empty((wl.n, f), device=DEV)
+    dg.feature_transform(h.to(DEV), torch.eye(f, device=DEV), hs, row_scale=dinv)
+    dg.spmm_weighted(rp_d, dev(g_ci, torch.int32), val_d, int(g_ci.size), hs, z, ws,
+                     flags=dg.DGNN_RELU | dg.DGNN_H_PRESCALED, dinv=dinv)
+    assert_close(to_f64(z), want, torch.float32, f"normalised aggregation over the smoothed snapshot ({mode})")
+
+
+@pytest.mark.parametrize("dtype,f", [(torch.float32, 32), (torch.bfloat16, 128)])
+def test_normalised_weighted_aggregation_recomputed_on_the_gpu(dtype, f):
+    """D^(-1/2) V D^(-1/2) H from the raw values: weighted row sums -> dinv, rows of H pre-scaled by the dense
+    transform, aggregation with the raw values; against the oracle's explicit normalised values."""
+    wl = WORKLOADS["c3"].scaled(1 << 13, T=1)
+    g = DynamicGraph(wl)
+    rp, ci = (x.numpy() for x in g.csr())
+    n = wl.n
+    rng = np.random.default_rng(f)
+    val = f32(rng.integers(1, 5, ci.size))                                  # counts, as a smoothed snapshot has
+    x = torch.randn((n, f), generator=torch.Generator().manual_seed(f)).to(dtype)
+    w = (torch.randn((f, f), generator=torch.Generator().manual_seed(f + 1)) / np.sqrt(f)).to(dtype)
+    want = oracle.spmm(rp, ci, oracle.xw(to_f64(x), to_f64(w)), relu=True,
+                       val=oracle.gcn_values_weighted(rp, ci, val.astype(np.float64)))
+    rp_d, ci_d, val_d = dev(rp, torch.int32), dev(ci, torch.int32), dev(val, torch.float32)
+    dinv = torch.empty(n, device=DEV)
+    dg.csr_weighted_dinv(rp_d, val_d, int(ci.size), dinv, ws_dinv(int(ci.size)))
+    d = np.array([val[rp[u]:rp[u + 1]].astype(np.float64).sum() for u in range(n)])
+    np.testing.assert_allclose(to_f64(dinv), d ** -0.5, rtol=2e-6)
+    h = torch.empty((n, f), dtype=dtype, device=DEV)
+    dg.feature_transform(x.to(DEV), w.to(DEV), h, row_scale=dinv)
+    z = torch.empty((n, f), dtype=dtype, device=DEV)
+    ws = torch.empty(dg.spmm_workspace(n, int(ci.size), f), dtype=torch.uint8, device=DEV)
+    dg.spmm_weighted(rp_d, ci_d, val_d, int(ci.size), h, z, ws, flags=dg.DGNN_RELU | dg.DGNN_H_PRESCALED, dinv=dinv)
+    assert_close(to_f64(z), want, dtype, "normalised weighted aggregation")
+
+
+def ws_dinv(nnz):
+    return torch.empty(dg.csr_weighted_dinv_workspace(nnz), dtype=torch.uint8, device=DEV)
+
+
+def test_weighted_row_sums_with_hub_rows_cut_into_pieces():
+    """Row lengths around the piece length: rows that begin exactly on a piece boundary, end on one, span
+    several pieces, follow each other directly, with empty rows between; against fp64 sums.  Twice: the
+    result must repeat bit for bit."""
+    piece = 4096
+    lens = [5, 0, 20000, 3, piece, piece + 1, 0, 0, 40000, 64, 65, 1, 3 * piece, 7, 2 * piece + 1, 128, 129, 100000,
+            piece - 1, 1, piece, 0, 2 * piece - 3, 3]
+    pad = (-sum(lens[:2])) % piece                      # make the third row begin exactly on a piece boundary
+    lens = lens[:1] + [pad + lens[1]] + lens[2:] + [3] * 150 + [9000] + [1] * 37 + [0] * 70
+    rp = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    assert rp[2] % piece == 0
+    nnz = int(rp[-1])
+    rng = np.random.default_rng(5)
+    val = f32(rng.uniform(0.5, 2.0, nnz))
+    want = np.array([val[rp[u]:rp[u + 1]].astype(np.float64).sum() for u in range(len(lens))])
+    rp_d, val_d = dev(rp, torch.int32), dev(val, torch.float32)
+    outs = []
+    for _ in range(2):
+        dinv = torch.full((len(lens),), float("nan"), device=DEV)
+        ws = ws_dinv(nnz)
+        ws.fill_(0xff)
+        dg.csr_weighted_dinv(rp_d, val_d, nnz, dinv, ws)
+        outs.append(dinv.cpu())
+    assert torch.equal(outs[0], outs[1])
+    got = to_f64(outs[0])
+    nz = want > 0
+    np.testing.assert_allclose(got[nz], want[nz] ** -0.5, rtol=2e-6)
+    assert np.all(np.isinf(got[~nz]))                   # an empty row has no normalisation

@@ -251,3 +251,18 @@ def test_cdgcn_gcn_on_special_graphs():
     y0 = dense @ x
     np.testing.assert_allclose(oracle.cdgcn_gcn(rp, ci, x, w), np.maximum(np.concatenate([y0, y0 @ w], axis=1), 0.0),
                                rtol=1e-12, atol=1e-13)
+
+
+def test_weighted_normalisation_reduces_to_eqn_1_and_matches_the_dense_form():
+    n = 50
+    a, rp, ci, rng = _graph(n, 0.15, 400, False)
+    np.testing.assert_allclose(oracle.gcn_values_weighted(rp, ci, np.ones(ci.size)), oracle.gcn_values(rp, ci), rtol=1e-14)
+    val = rng.uniform(0.5, 3.0, ci.size)
+    dense = np.nan_to_num(_dense_weighted(n, rp, ci, val), nan=0.0)
+    d = dense.sum(axis=1)
+    want = np.diag(d ** -0.5) @ dense @ np.diag(d ** -0.5)
+    got = np.nan_to_num(_dense_weighted(n, rp, ci, oracle.gcn_values_weighted(rp, ci, val)), nan=0.0)
+    np.testing.assert_allclose(got, want, rtol=1e-13, atol=1e-15)
+    # sqrt(d) is a fixed vector of the normalised matrix, as in the unweighted case
+    np.testing.assert_allclose(oracle.spmm(rp, ci, np.sqrt(d)[:, None], val=oracle.gcn_values_weighted(rp, ci, val))[:, 0],
+                               np.sqrt(d), rtol=1e-12)
