@@ -228,6 +228,32 @@ int dgnn_csr_weighted_dinv(int64_t n, int64_t nnz, const int32_t *rowptr, const 
                            void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * One step of the sliding-window sum that smooths the input graphs (Section "Smoothening the Input Graphs"):
+ *     C = S + alpha * A_in + beta * A_out
+ * with S a snapshot with values and A_in, A_out unweighted snapshots (every stored entry counts 1), all n x n in
+ * CSR with rows sorted by column: S_t = S_{t-1} + A_t - A_{t-l} is alpha = 1, beta = -1 (A_out NULL while the
+ * window still grows); divided by min(l, t), which the symmetric normalisation cancels, it is the M-transform
+ * applied to the adjacency tensor.  Entries of equal (row, column) are added as S, then alpha, then beta, in fp32;
+ * an entry whose result is exactly 0 is not stored (counts are small integers, so this is exact for them).
+ *   rowptr_s/colidx_s/val_s, nnz_s: S; val_s NULL = all ones (S_1 = A_1).  rowptr_in/colidx_in, nnz_in and
+ *   rowptr_out_of/colidx_out_of, nnz_out_of: A_in and A_out, each may be NULL (nothing to add).
+ *   rowptr_c [n+1], colidx_c / val_c [capacity]: the result, canonical order; must not be S's arrays.
+ *   nnz_c (host): the number of stored entries of C.  It is not known beforehand (at most nnz_s + nnz_in +
+ *   nnz_out_of): the call counts first, WAITS for the stream to read the count back, and writes only if it fits;
+ *   DGNN_ERR_CAPACITY otherwise, with *nnz_c set, and nothing written.  Because of the wait the call cannot be
+ *   captured in a HIP graph; smoothing is pre-processing, outside the training step.
+ *   ws: device scratch of at least dgnn_csr_combine_workspace(nnz_s) bytes.
+ * All device pointers except nnz_c.  Errors: NULL, SHAPE, OVERFLOW (nnz_s + nnz_in + nnz_out_of beyond the index
+ * range), CAPACITY, ALIAS, HIP.
+ */
+int dgnn_csr_combine_workspace(int64_t nnz_s, size_t *bytes);
+int dgnn_csr_combine(int64_t n, const int32_t *rowptr_s, const int32_t *colidx_s, const float *val_s, int64_t nnz_s,
+                     const int32_t *rowptr_in, const int32_t *colidx_in, int64_t nnz_in, float alpha,
+                     const int32_t *rowptr_out_of, const int32_t *colidx_out_of, int64_t nnz_out_of, float beta,
+                     int32_t *rowptr_c, int32_t *colidx_c, float *val_c, int64_t capacity, int64_t *nnz_c,
+                     void *ws, size_t ws_bytes, void *stream);
+
+/*
  * ---- Gradient propagation through the same path (Section "Gradient Checkpoint": a block is run forward
  * again and gradients then travel through it in the reverse direction).  For one GCN layer
  *     H = X W,  P = A~ H,  Z = max(P, 0),  Y = Z x_1 M

@@ -286,3 +286,31 @@ def gcn_values_weighted(rowptr, colidx, val) -> np.ndarray:
     d = np.array([val[rowptr[u]:rowptr[u + 1]].sum() for u in range(n)])
     rows = np.repeat(np.arange(n), np.diff(rowptr))
     return val / np.sqrt(d[rows] * d[colidx])
+
+
+def csr_combine(n: int, s, a_in=None, alpha: float = 1.0, a_out=None, beta: float = -1.0):
+    """S + alpha * A_in + beta * A_out as sparse matrices, entries whose result is exactly 0 removed: one step of
+    the sliding-window sum of Section "Smoothening the Input Graphs" (S_t = S_{t-1} + A_t - A_{t-l}).
+    s = (rowptr, colidx, val or None for all ones); a_in, a_out = (rowptr, colidx) of unweighted snapshots, or
+    None.  Returns (rowptr, colidx, val) with val in float64.  Written as the definition: every stored entry of
+    the three operands is one term (row, col, weight), terms of equal (row, col) are added up."""
+    keys, wts = [], []
+    for op, scale in ((s, None), (a_in, alpha), (a_out, beta)):
+        if op is None:
+            continue
+        rp, ci = _a(op[0], np.int32), _a(op[1], np.int32)
+        rows = np.repeat(np.arange(n, dtype=np.int64), np.diff(rp))
+        keys.append((rows << 32) | ci.astype(np.int64))
+        if scale is None:
+            wts.append(np.ones(ci.size) if len(op) < 3 or op[2] is None else _a(op[2], np.float64))
+        else:
+            wts.append(np.full(ci.size, float(scale)))
+    keys, wts = np.concatenate(keys), np.concatenate(wts)
+    uniq, inv = np.unique(keys, return_inverse=True)
+    total = np.zeros(uniq.size)
+    np.add.at(total, inv, wts)
+    keep = total != 0.0
+    uniq, total = uniq[keep], total[keep]
+    rowptr = np.zeros(n + 1, dtype=np.int32)
+    np.cumsum(np.bincount(uniq >> 32, minlength=n), out=rowptr[1:])
+    return rowptr, (uniq & 0xffffffff).astype(np.int32), total

@@ -24,7 +24,7 @@ DGNN_H_PRESCALED = 2
 EXPORTS = (
     "dgnn_strerror", "dgnn_csr_dinv", "dgnn_delta_h2d", "dgnn_delta_rebuild_workspace",
     "dgnn_delta_rebuild", "dgnn_feature_transform", "dgnn_spmm_workspace", "dgnn_spmm", "dgnn_mproduct",
-    "dgnn_delta_rebuild_weighted", "dgnn_spmm_weighted", "dgnn_csr_weighted_dinv_workspace", "dgnn_csr_weighted_dinv", "dgnn_concat_relu", "dgnn_lstm_cell", "dgnn_lstm_step",
+    "dgnn_delta_rebuild_weighted", "dgnn_spmm_weighted", "dgnn_csr_combine_workspace", "dgnn_csr_combine", "dgnn_csr_weighted_dinv_workspace", "dgnn_csr_weighted_dinv", "dgnn_concat_relu", "dgnn_lstm_cell", "dgnn_lstm_step",
     "dgnn_mproduct_backward", "dgnn_mproduct_block", "dgnn_mproduct_backward_block", "dgnn_relu_backward", "dgnn_weight_grad_workspace", "dgnn_weight_grad", "dgnn_input_grad",
 )
 
@@ -102,6 +102,9 @@ def load_library():
                                                 _vp, _vp, _vp, _i64, _vp, _vp, _vp, _i64, ctypes.POINTER(_i64),
                                                 _vp, _sz, _u32, _vp, _vp]
     lib.dgnn_spmm_weighted.argtypes = [_i64, _i64, _vp, _vp, _vp, _vp, _vp, _i32, _vp, ctypes.c_int, _u32, _vp, _sz, _vp]
+    lib.dgnn_csr_combine_workspace.argtypes = [_i64, ctypes.POINTER(_sz)]
+    lib.dgnn_csr_combine.argtypes = [_i64, _vp, _vp, _vp, _i64, _vp, _vp, _i64, ctypes.c_float, _vp, _vp, _i64, ctypes.c_float,
+                                     _vp, _vp, _vp, _i64, ctypes.POINTER(_i64), _vp, _sz, _vp]
     lib.dgnn_csr_weighted_dinv_workspace.argtypes = [_i64, ctypes.POINTER(_sz)]
     lib.dgnn_csr_weighted_dinv.argtypes = [_i64, _i64, _vp, _vp, _vp, _vp, _sz, _vp]
     lib.dgnn_concat_relu.argtypes = [_vp, _i32, _vp, _i32, _vp, _i64, ctypes.c_int, _vp]
@@ -280,6 +283,43 @@ def spmm_weighted(rowptr, colidx, val, nnz: int, h: torch.Tensor, z: torch.Tenso
     _check(load_library().dgnn_spmm_weighted(n, nnz, _ptr(rowptr), _ptr(colidx), _ptr(val), _ptr(dinv), _ptr(h), f, _ptr(z),
                                              dt, flags, _ptr(ws), ws.numel() * ws.element_size(), _stream(h)),
            "dgnn_spmm_weighted")
+
+
+def csr_combine_workspace(nnz_s: int) -> int:
+    out = _sz(0)
+    _check(load_library().dgnn_csr_combine_workspace(nnz_s, ctypes.byref(out)), "dgnn_csr_combine_workspace")
+    return int(out.value)
+
+
+def csr_combine(s, a_in, alpha: float, a_out, beta: float, out, ws: torch.Tensor) -> int:
+    """C = S + alpha * A_in + beta * A_out.  s = (rowptr, colidx, val or None, nnz); a_in, a_out = (rowptr, colidx,
+    nnz) or None; out = (rowptr, colidx, val) with capacity = colidx.numel().  Returns nnz of C."""
+    rp_s, ci_s, val_s, nnz_s = s
+    rp_c, ci_c, val_c = out
+    n = rp_s.numel() - 1
+    _need(rp_s, torch.int32, "rowptr_s"); _need(ci_s, torch.int32, "colidx_s")
+    _need(rp_c, torch.int32, "rowptr_c"); _need(ci_c, torch.int32, "colidx_c"); _need(val_c, torch.float32, "val_c")
+    if val_s is not None:
+        _need(val_s, torch.float32, "val_s")
+    if rp_c.numel() != n + 1 or val_c.numel() < ci_c.numel() or ci_s.numel() < nnz_s or (val_s is not None and val_s.numel() < nnz_s):
+        raise ValueError("shape mismatch in csr_combine")
+    args = []
+    for op, name in ((a_in, "a_in"), (a_out, "a_out")):
+        if op is None:
+            args.append((None, None, 0))
+            continue
+        rp, ci, nnz = op
+        _need(rp, torch.int32, name + " rowptr"); _need(ci, torch.int32, name + " colidx")
+        if rp.numel() != n + 1 or ci.numel() < nnz:
+            raise ValueError(f"shape mismatch in csr_combine ({name})")
+        args.append((rp, ci, nnz))
+    nnz_c = _i64(0)
+    (rp_a, ci_a, nnz_a), (rp_o, ci_o, nnz_o) = args
+    _check(load_library().dgnn_csr_combine(n, _ptr(rp_s), _ptr(ci_s), _ptr(val_s), nnz_s, _ptr(rp_a), _ptr(ci_a), nnz_a,
+                                           float(alpha), _ptr(rp_o), _ptr(ci_o), nnz_o, float(beta), _ptr(rp_c), _ptr(ci_c),
+                                           _ptr(val_c), ci_c.numel(), ctypes.byref(nnz_c), _ptr(ws),
+                                           ws.numel() * ws.element_size(), _stream(rp_s)), "dgnn_csr_combine")
+    return int(nnz_c.value)
 
 
 def csr_weighted_dinv_workspace(nnz: int) -> int:

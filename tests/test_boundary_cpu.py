@@ -215,3 +215,23 @@ def test_lstm_step_argument_errors(lib):
     assert call(f_y=128) == -2 and call(hidden=64) == -2 and call(dt=1) == -2 and call(n=0) == -2
     assert call(h_next=FAKE + 0x4000) == -5 and call(h_next=FAKE + 0x1000) == -5
     assert call(y=FAKE + 8) == -7
+
+
+def test_csr_combine_argument_errors(lib):
+    f = lib.dgnn_csr_combine
+    out = ctypes.c_int64(0)
+
+    def call(n=10, rp_s=FAKE, ci_s=FAKE, nnz_s=20, rp_a=FAKE, ci_a=FAKE, nnz_a=5, rp_c=FAKE + 4096, ci_c=FAKE + 8192,
+             val_c=FAKE + 12288, cap=100, ws=FAKE + 16384, ws_bytes=1 << 20, nnz_c=ctypes.byref(out)):
+        return f(n, rp_s, ci_s, None, nnz_s, rp_a, ci_a, nnz_a, 1.0, None, None, 0, -1.0, rp_c, ci_c, val_c, cap, nnz_c, ws,
+                 ws_bytes, None)
+
+    assert call(rp_s=None) == -1 and call(ci_s=None) == -1 and call(ci_a=None) == -1 and call(val_c=None) == -1
+    assert call(nnz_c=None) == -1 and call(ws=None) == -1
+    assert call(n=0) == -2 and call(nnz_s=-1) == -2 and call(cap=-1) == -2
+    assert call(nnz_s=(1 << 31) - (1 << 16) - 10, nnz_a=100) == -4
+    assert call(ws_bytes=4) == -3
+    assert call(rp_c=FAKE) == -5 and call(ci_c=FAKE) == -5
+    b = ctypes.c_size_t(0)
+    assert lib.dgnn_csr_combine_workspace(1 << 20, ctypes.byref(b)) == 0 and b.value >= 4 * ((1 << 10) + 1)
+    assert lib.dgnn_csr_combine_workspace(-1, ctypes.byref(b)) == -2

@@ -1,0 +1,129 @@
+"""GPU parity of the sliding-window sum of snapshots (Section "Smoothening the Input Graphs") computed on the
+device, C = S + alpha A_in + beta A_out, against the oracle: structure and values bit for bit (the values are
+counts or dyadic fractions, exact in fp32 and fp64 alike, so the decision "is the result zero" is the same on
+both sides)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2109_07893_amd as dg
+from dtdg_synth import WORKLOADS, DynamicGraph
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def dev(a, dt):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(dt).to(DEV)
+
+
+def gpu_combine(n, s, a_in, alpha, a_out, beta, slack=0):
+    rp_s, ci_s, val_s = s
+    s_d = (dev(rp_s, torch.int32), dev(ci_s, torch.int32), None if val_s is None else dev(val_s, torch.float32), int(ci_s.size))
+    ops = [None if a is None else (dev(a[0], torch.int32), dev(a[1], torch.int32), int(a[1].size)) for a in (a_in, a_out)]
+    cap = int(ci_s.size) + sum(0 if a is None else int(a[1].size) for a in (a_in, a_out)) + slack
+    out = (torch.full((n + 1,), -7, dtype=torch.int32, device=DEV), torch.full((max(cap, 1),), -7, dtype=torch.int32, device=DEV),
+           torch.full((max(cap, 1),), float("nan"), device=DEV))
+    ws = torch.empty(dg.csr_combine_workspace(int(ci_s.size)), dtype=torch.uint8, device=DEV)
+    nnz = dg.csr_combine(s_d, ops[0], alpha, ops[1], beta, out, ws)
+    torch.cuda.synchronize()
+    # nothing written behind the result
+    assert bool((out[1][nnz:] == -7).all()) and bool(torch.isnan(out[2][nnz:]).all())
+    return out[0].cpu().numpy(), out[1][:nnz].cpu().numpy(), out[2][:nnz].cpu().numpy()
+
+
+def check(n, s, a_in, alpha, a_out, beta, what):
+    want = oracle.csr_combine(n, s, a_in, alpha, a_out, beta)
+    got = gpu_combine(n, s, a_in, alpha, a_out, beta)
+    assert np.array_equal(got[0], want[0]), f"{what}: rowptr"
+    assert np.array_equal(got[1], want[1]), f"{what}: colidx"
+    assert np.array_equal(got[2].astype(np.float64), want[2]), f"{what}: values"
+
+
+def random_csr(n, density, rng, hubs=()):
+    """Rows of binomial length; `hubs` = (row, length) pairs get that many entries instead."""
+    rows, cols = [], []
+    for u in range(n):
+        k = dict(hubs).get(u, rng.binomial(n, density))
+        c = np.sort(rng.choice(n, size=min(k, n), replace=False))
+        rows.append(np.full(c.size, u)); cols.append(c)
+    return oracle.csr_from_edges(n, np.concatenate(rows), np.concatenate(cols))
+
+
+@pytest.mark.parametrize("n,density,seed", [(300, 0.05, 0), (2000, 0.02, 1), (5000, 0.004, 2), (700, 0.3, 3)])
+@pytest.mark.parametrize("alpha,beta", [(1.0, -1.0), (2.0, 0.5)])
+def test_combine_random_operands(n, density, seed, alpha, beta):
+    rng = np.random.default_rng(seed)
+    s = random_csr(n, density, rng)
+    a_in, a_out = random_csr(n, density, rng), random_csr(n, density / 2, rng)
+    val = rng.integers(1, 4, s[1].size).astype(np.float64)
+    check(n, s + (val,), a_in, alpha, a_out, beta, "three operands")
+    check(n, s + (None,), a_in, alpha, None, beta, "no A_out, S unweighted")
+    check(n, s + (val,), None, alpha, a_out, beta, "no A_in")
+    check(n, s + (val,), None, alpha, None, beta, "S alone")
+
+
+def test_combine_hub_rows_empty_rows_and_long_spans():
+    """Rows much longer than a wavefront's range in each of the operands in turn (so a row is cut at columns,
+    pieces are merged by all lanes, and spans of A_in / A_out exceed the staging area), next to empty rows."""
+    n = 9000
+    rng = np.random.default_rng(11)
+    s = random_csr(n, 0.001, rng, hubs=((3, 5000), (4, 0), (5, 0), (100, 2047), (101, 1), (4000, 8999), (8999, 3000)))
+    a_in = random_csr(n, 0.001, rng, hubs=((3, 4000), (4, 6000), (7, 0), (101, 7000), (4000, 10), (8998, 0), (8999, 2500)))
+    a_out = random_csr(n, 0.0005, rng, hubs=((3, 4500), (5, 3000), (100, 2047), (4000, 8000)))
+    val = rng.integers(1, 3, s[1].size).astype(np.float64)
+    check(n, s + (val,), a_in, 1.0, a_out, -1.0, "hubs")
+    check(n, s + (val,), a_in, 1.0, s, -1.0, "S partly cancelled by itself")
+    check(n, a_in + (None,), s, 1.0, a_out, -1.0, "operands exchanged")
+
+
+def test_combine_empty_s_and_total_cancellation():
+    n = 500
+    rng = np.random.default_rng(5)
+    a = random_csr(n, 0.05, rng)
+    empty = (np.zeros(n + 1, dtype=np.int32), np.zeros(0, dtype=np.int32))
+    check(n, empty + (None,), a, 1.0, None, -1.0, "S empty")
+    check(n, empty + (None,), None, 1.0, None, -1.0, "everything empty")
+    check(n, a + (None,), None, 1.0, a, -1.0, "S - S")
+    check(n, a + (None,), a, 1.0, a, -2.0, "S + S - 2 S")
+
+
+def test_combine_reports_the_size_when_the_result_does_not_fit():
+    n = 400
+    rng = np.random.default_rng(6)
+    s, a = random_csr(n, 0.05, rng), random_csr(n, 0.05, rng)
+    want = oracle.csr_combine(n, s + (None,), a, 1.0)
+    s_d = (dev(s[0], torch.int32), dev(s[1], torch.int32), None, int(s[1].size))
+    a_d = (dev(a[0], torch.int32), dev(a[1], torch.int32), int(a[1].size))
+    cap = int(want[1].size) - 1
+    out = (torch.full((n + 1,), -7, dtype=torch.int32, device=DEV), torch.full((cap,), -7, dtype=torch.int32, device=DEV),
+           torch.zeros(cap, device=DEV))
+    ws = torch.empty(dg.csr_combine_workspace(int(s[1].size)), dtype=torch.uint8, device=DEV)
+    with pytest.raises(dg.DgnnError):
+        dg.csr_combine(s_d, a_d, 1.0, None, -1.0, out, ws)
+    torch.cuda.synchronize()
+    assert bool((out[0] == -7).all()) and bool((out[1] == -7).all())      # nothing written
+
+
+@pytest.mark.parametrize("name,n,life", [("c1", 1000, 3), ("c3", 1 << 13, 4), ("c2", 20_000, 2), ("c5", 1 << 13, 8)])
+def test_sliding_window_sum_on_the_device(name, n, life):
+    """S_t = S_{t-1} + A_t - A_{t-l} carried on the device over a series; the expected S_t is formed here from the
+    raw oracle snapshots (sorted keys of the window, counted with numpy), not step by step."""
+    T = 10
+    wl = WORKLOADS[name].scaled(n, T=T) if n != WORKLOADS[name].n else WORKLOADS[name]
+    T = min(T, wl.T)
+    raw = DynamicGraph(wl)
+    rp, ci = (x.numpy() for x in raw.csr())
+    snaps = [(rp, ci)]
+    s = (rp, ci, None)
+    for t in range(2, T + 1):
+        rp, ci = oracle.delta_apply(wl.n, rp, ci, *[x.numpy() for x in raw.advance()])
+        snaps.append((rp, ci))
+        s = gpu_combine(wl.n, s, snaps[t - 1], 1.0, snaps[t - 1 - life] if t - life >= 1 else None, -1.0)
+        keys = [(np.repeat(np.arange(wl.n, dtype=np.int64), np.diff(p)) << 32) | c.astype(np.int64)
+                for p, c in snaps[max(0, t - life):t]]
+        want_keys, counts = np.unique(np.concatenate(keys), return_counts=True)
+        got_keys = (np.repeat(np.arange(wl.n, dtype=np.int64), np.diff(s[0])) << 32) | s[1].astype(np.int64)
+        assert np.array_equal(got_keys, want_keys), (name, t)
+        assert np.array_equal(s[2], counts.astype(np.float32)), (name, t)

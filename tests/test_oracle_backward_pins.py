@@ -266,3 +266,67 @@ def test_weighted_normalisation_reduces_to_eqn_1_and_matches_the_dense_form():
     # sqrt(d) is a fixed vector of the normalised matrix, as in the unweighted case
     np.testing.assert_allclose(oracle.spmm(rp, ci, np.sqrt(d)[:, None], val=oracle.gcn_values_weighted(rp, ci, val))[:, 0],
                                np.sqrt(d), rtol=1e-12)
+
+
+def _dense_unweighted(n, rp, ci):
+    d = np.zeros((n, n))
+    for u in range(n):
+        d[u, ci[rp[u]:rp[u + 1]]] = 1.0
+    return d
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_csr_combine_matches_dense_matrices(seed):
+    """S + alpha A_in + beta A_out with dense n x n arrays; entries that cancel must disappear from the structure."""
+    n = 40
+    rng = np.random.default_rng(seed)
+    mats = []
+    for p in (0.2, 0.15, 0.1):
+        m = rng.random((n, n)) < p
+        mats.append(oracle.csr_from_edges(n, *np.nonzero(m)))
+    (s_rp, s_ci), a_in, a_out = mats
+    s_val = rng.integers(1, 4, s_ci.size).astype(np.float64)
+    s_dense = np.nan_to_num(_dense_weighted(n, s_rp, s_ci, s_val), nan=0.0)
+    for alpha, beta in ((1.0, -1.0), (2.0, 0.5), (1.0, -2.0)):
+        want = s_dense + alpha * _dense_unweighted(n, *a_in) + beta * _dense_unweighted(n, *a_out)
+        rp, ci, val = oracle.csr_combine(n, (s_rp, s_ci, s_val), a_in, alpha, a_out, beta)
+        assert np.all(val != 0.0)
+        got = np.nan_to_num(_dense_weighted(n, rp, ci, val), nan=0.0)
+        np.testing.assert_array_equal(got, want)
+        assert ci.size == np.count_nonzero(want)                      # nothing stored that is zero, nothing missing
+        for u in range(n):
+            assert np.all(np.diff(ci[rp[u]:rp[u + 1]]) > 0)           # canonical order within each row
+
+
+def test_csr_combine_special_cases():
+    n = 30
+    rng = np.random.default_rng(9)
+    s = oracle.csr_from_edges(n, *np.nonzero(rng.random((n, n)) < 0.2))
+    a = oracle.csr_from_edges(n, *np.nonzero(rng.random((n, n)) < 0.2))
+    ones = np.ones(s[1].size)
+    # nothing added, nothing removed: S itself (values all ones when none are given)
+    rp, ci, val = oracle.csr_combine(n, s + (None,))
+    assert np.array_equal(rp, s[0]) and np.array_equal(ci, s[1]) and np.array_equal(val, ones)
+    # S - S is empty, S + S doubles every value
+    rp, ci, val = oracle.csr_combine(n, s + (ones,), None, 1.0, s, -1.0)
+    assert ci.size == 0 and np.all(rp == 0)
+    rp, ci, val = oracle.csr_combine(n, s + (ones,), s, 1.0)
+    assert np.array_equal(ci, s[1]) and np.array_equal(val, 2 * ones)
+    # adding then removing the same snapshot gives S back
+    rp, ci, val = oracle.csr_combine(n, s + (ones,), a, 1.0, a, -1.0)
+    assert np.array_equal(rp, s[0]) and np.array_equal(ci, s[1]) and np.array_equal(val, ones)
+
+
+def test_sliding_window_sum_by_csr_combine_equals_the_windowed_sum():
+    """S_t = S_{t-1} + A_t - A_{t-l} carried over a series equals the sum of the last l snapshots formed
+    directly (dense), Section "Smoothening the Input Graphs"."""
+    n, life, T = 25, 3, 8
+    rng = np.random.default_rng(4)
+    snaps = [oracle.csr_from_edges(n, *np.nonzero((rng.random((n, n)) < 0.15) | np.eye(n, dtype=bool))) for _ in range(T)]
+    s = snaps[0] + (None,)
+    for t in range(2, T + 1):
+        out = snaps[t - 1 - life] if t - life >= 1 else None
+        s = oracle.csr_combine(n, s, snaps[t - 1], 1.0, out, -1.0)
+        want = sum(_dense_unweighted(n, *snaps[i - 1]) for i in range(max(1, t - life + 1), t + 1))
+        got = np.nan_to_num(_dense_weighted(n, *s), nan=0.0)
+        np.testing.assert_array_equal(got, want)
