@@ -50,6 +50,8 @@ def parse_args():
                     help="also time the forward pass of one CD-GCN layer (skip-concat GCN + LSTM over time) over the block")
     ap.add_argument("--weighted", action="store_true",
                     help="also time one step of the path for snapshots that carry a value per entry")
+    ap.add_argument("--smoothing", action="store_true",
+                    help="also time the sliding-window sum of the block's snapshots (edge life 4) computed on the device")
     ap.add_argument("--natural-labels", action="store_true",
                     help="R-MAT workloads: keep the generator's vertex labels (locality) instead of scrambling them")
     return ap.parse_args()
@@ -177,6 +179,61 @@ def weighted_step(args, wl, blk, dev):
                      "algorithmic_GBps": round(byts / (ms * 1e-3) / 1e9, 1)}
     out["lists"] = {"added": int(ar.numel()), "deleted": int(dr.numel()), "value_updates": int(ur.numel())}
     return out
+
+
+def smoothing_steps(args, wl, blk, dev, life=4):
+    """S_t = S_{t-1} + A_t - A_{t-life} over the block with all raw snapshots resident (rebuilt on the device from
+    the difference lists), then the normalisation of the last S_t: an extra figure."""
+    import torch
+    import paper_2109_07893_amd as dg
+    n = blk.n
+    snaps = [(blk.rowptr1, blk.colidx1, blk.nnz[0])]
+    ws_r = torch.empty(dg.delta_rebuild_workspace(n, max(blk.nnz), max(int(d[0].numel()) for d in blk.deltas),
+                                                  max(int(d[2].numel()) for d in blk.deltas)), dtype=torch.uint8, device=dev)
+    for t in range(2, blk.T + 1):
+        ar, ac, dr, dc = blk.deltas[t - 2]
+        rp = torch.empty(n + 1, dtype=torch.int32, device=dev)
+        ci = torch.empty(blk.nnz[t - 1], dtype=torch.int32, device=dev)
+        dinv = torch.empty(n, device=dev)
+        prp, pci, pnnz = snaps[-1]
+        dg.delta_rebuild(prp, pci, pnnz, ar, ac, int(ar.numel()), dr, dc, int(dr.numel()), rp, ci, dinv, ws_r)
+        snaps.append((rp, ci, blk.nnz[t - 1]))
+    cap = int(max(blk.nnz) * 1.6)
+    bufs = [(torch.empty(n + 1, dtype=torch.int32, device=dev), torch.empty(cap, dtype=torch.int32, device=dev),
+             torch.empty(cap, device=dev)) for _ in range(2)]
+    ws = torch.empty(dg.csr_combine_workspace(cap), dtype=torch.uint8, device=dev)
+    rows = []
+
+    def series(record):
+        s = (snaps[0][0], snaps[0][1], None, snaps[0][2])
+        for t in range(2, blk.T + 1):
+            out = bufs[t % 2]
+            a_out = snaps[t - 1 - life] if t - life >= 1 else None
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            nnz = dg.csr_combine(s, snaps[t - 1], 1.0, a_out, -1.0, out, ws)
+            e1.record()
+            torch.cuda.synchronize()
+            if record:
+                byts = 8 * s[3] + 4 * snaps[t - 1][2] + (4 * a_out[2] if a_out else 0) + 8 * nnz + 4 * (n + 1) * (4 if a_out else 3)
+                rows.append({"t": t, "nnz_s": s[3], "nnz_c": nnz, "ms": round(e0.elapsed_time(e1), 3),
+                             "algorithmic_GBps": round(byts / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)})
+            s = (out[0], out[1], out[2], nnz)
+        return s
+
+    series(False)
+    s = series(True)
+    dinv = torch.empty(n, device=dev)
+    ws_d = torch.empty(dg.csr_weighted_dinv_workspace(s[3]), dtype=torch.uint8, device=dev)
+    dg.csr_weighted_dinv(s[0], s[2], s[3], dinv, ws_d)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    dg.csr_weighted_dinv(s[0], s[2], s[3], dinv, ws_d)
+    e1.record()
+    torch.cuda.synchronize()
+    return {"edge_life": life, "steps": rows, "csr_weighted_dinv_ms": round(e0.elapsed_time(e1), 3),
+            "note": "each step: count launch, scan, read-back of the size (a stream synchronisation), write launch"}
 
 
 def cdgcn_layer(args, wl, blk, dev):
@@ -437,6 +494,8 @@ def main():
         progress("CD-GCN layer timed")
     if args.weighted:
         out["weighted_step"] = weighted_step(args, wl, blk, dev)
+    if args.smoothing:
+        out["smoothing"] = smoothing_steps(args, wl, blk, dev)
         progress("weighted step timed")
     if not args.no_train:
         del runner

@@ -2,17 +2,17 @@
 //     C = S + alpha * A_in + beta * A_out        (S_t = S_{t-1} + A_t - A_{t-l} with alpha = 1, beta = -1)
 // for a weighted snapshot S and two unweighted ones, all in CSR with sorted rows, on the device: entries of
 // equal (row, column) are added up, entries whose result is exactly 0 leave the structure.  It is a three-way
-// merge per row, made into work of equal size the way the other sparse kernels here are: split by ENTRIES of S,
-// not by rows, so that the hub rows of a power-law graph are spread over many wavefronts.
-//   - a wavefront owns kRange consecutive entries of S and stages them in LDS; a row cut by the range's begin
-//     or end is cut at a COLUMN (the column of the S entry the range begins or ends at), so every term of
-//     A_in and A_out falls into exactly one range, found by a lower bound in its row;
-//   - the A_in and A_out terms of the range are consecutive in their arrays and are staged as well (a span
-//     longer than the staging area is read in place instead);
-//   - each lane merges whole row pieces out of LDS, one after the other; a piece with many terms is merged by
-//     all lanes, each taking an equal share of its longest list and the matching column interval of the others;
-//   - the size of the result is not known beforehand: a first launch only counts (per range), a single-workgroup
-//     scan turns the counts into positions, the second launch merges again and writes, rowptr included.
+// merge in the order (row, column), made into work of equal size the way the other sparse kernels here are:
+// split by ENTRIES of S, not by rows, so that the hub rows of a power-law graph are spread over many lanes.
+//   - a wavefront owns kRange consecutive entries of S and stages them in LDS, a lane kPer of those.  A share
+//     begins at a BOUNDARY: the (row, column) of its first S entry.  Every term of A_in and A_out belongs to the
+//     share whose boundary is the last one not behind it, found by one lower bound in the boundary's row; rows
+//     that begin between two boundaries (rows without S entries included) belong to the share in front;
+//   - the A_in and A_out terms of a range are consecutive in their arrays and are staged as well (a span longer
+//     than the staging area is read in place instead);
+//   - each lane merges its share out of LDS, row piece after row piece;
+//   - the size of the result is not known beforehand: a first launch only counts (per lane), a single-workgroup
+//     scan turns the range totals into positions, the second launch merges again and writes, rowptr included.
 // The result's order is the canonical one (rows ascending, columns ascending), whatever the launch shape.
 #include <hip/hip_runtime.h>
 
@@ -22,173 +22,195 @@ namespace {
 
 using namespace dgnn;
 
-constexpr int kRange = 1024;        // entries of S per wavefront
-constexpr int kCapIn = 1536;        // staged terms of A_in per range
-constexpr int kCapOut = 1024;       // staged terms of A_out per range
-constexpr int kCoop = 96;           // a row piece with more terms than this is merged by all lanes together
-constexpr int kNoCol = 0x7fffffff;  // larger than any column index the library accepts
+constexpr int kPer = 16;               // entries of S per lane
+constexpr int kRange = kPer * kWave;   // entries of S per wavefront
+constexpr int kCapIn = 1536;           // staged terms of A_in per range
+constexpr int kCapOut = 1024;          // staged terms of A_out per range
+constexpr int kCapRows = 384;          // staged row pointers per range and operand
+constexpr int kNoCol = 0x7fffffff;     // larger than any column index the library accepts
 constexpr int kScanThreads = 1024;
 
-// entry i of a list is c[i - off]: the list either lies in global memory (off = 0) or a span of it is staged
-struct List {
-    const int32_t *c;
-    int off;
-    __device__ __forceinline__ int at(int i) const { return c[i - off]; }
+// Where a share begins.  Rows k, k+1, ... begin at or behind the boundary; cut: the boundary lies inside row k-1.
+// a, o: the first terms of A_in and A_out that are not in front of the boundary.
+struct Bound { int k, cut, a, o; };
+
+// What a lane reads besides its S entries: the terms of A_in and A_out and the row pointers of the three operands,
+// from the spans staged in LDS or in place.
+template <bool STAGED>
+struct Terms {
+    const int *s_a, *s_o;                  // LDS: terms
+    const int *s_rs, *s_ra, *s_ro;         // LDS: row pointers of rows row_off, row_off + 1, ...
+    const int32_t *col_a, *col_o;          // global
+    const int32_t *rp_s, *rp_a, *rp_o;     // global; rp_a / rp_o may be null: no such operand
+    int a_off, o_off, row_off;             // first staged term / row
+    __device__ __forceinline__ int a(int i) const { return STAGED ? s_a[i - a_off] : col_a[i]; }
+    __device__ __forceinline__ int o(int i) const { return STAGED ? s_o[i - o_off] : col_o[i]; }
+    __device__ __forceinline__ int rs(int r) const { return STAGED ? s_rs[r - row_off] : rp_s[r]; }
+    __device__ __forceinline__ int ra(int r) const { return STAGED ? s_ra[r - row_off] : (rp_a ? rp_a[r] : 0); }
+    __device__ __forceinline__ int ro(int r) const { return STAGED ? s_ro[r - row_off] : (rp_o ? rp_o[r] : 0); }
+    // first position in [b, e) whose column is >= key
+    __device__ __forceinline__ int a_lower(int b, int e, int key) const {
+        while (b < e) { const int mid = b + ((e - b) >> 1); if (a(mid) < key) b = mid + 1; else e = mid; }
+        return b;
+    }
+    __device__ __forceinline__ int o_lower(int b, int e, int key) const {
+        while (b < e) { const int mid = b + ((e - b) >> 1); if (o(mid) < key) b = mid + 1; else e = mid; }
+        return b;
+    }
+    // first r in [lo, hi] with rs(r) >= key (rs(hi) >= key is known)
+    __device__ __forceinline__ int first_row_at_or_after(int lo, int hi, int key) const {
+        while (lo < hi) { const int mid = lo + ((hi - lo) >> 1); if (rs(mid) < key) lo = mid + 1; else hi = mid; }
+        return lo;
+    }
 };
 
-// first position in [b, e) whose column is >= key
-__device__ __forceinline__ int list_lower_bound(const List &l, int b, int e, int key) {
-    while (b < e) {
-        const int mid = b + ((e - b) >> 1);
-        if (l.at(mid) < key) b = mid + 1; else e = mid;
+struct Operands {
+    int n, nnz_s, nnz_a, nnz_o;
+    const int32_t *rp_s, *col_s;
+    const float *val_s;
+    const int32_t *rp_a, *col_a, *rp_o, *col_o;      // rp_a / rp_o may be null: no such operand
+    float alpha, beta;
+};
+
+// The boundary at S entry `pos` (0 <= pos < nnz_s, or pos = 0 when S is empty); k_lo = first row in [k_lo, k_hi] that
+// begins at pos or later, found by the caller.  Terms are looked up in [a_lo, a_hi) x [o_lo, o_hi) only (the
+// spans that are known to hold the boundary).
+template <bool STAGED>
+__device__ __forceinline__ Bound make_bound(const Terms<STAGED> &T, int pos, int k, int col_at_pos, int a_lo, int a_hi,
+                                            int o_lo, int o_hi) {
+    Bound b;
+    b.k = k;
+    b.cut = T.rs(k) > pos;                         // k <= n and rp_s[n] = nnz_s
+    if (b.cut) {                                   // inside row k-1: its terms from column col_at_pos on
+        b.a = T.a_lower(max(T.ra(k - 1), a_lo), min(T.ra(k), a_hi), col_at_pos);
+        b.o = T.o_lower(max(T.ro(k - 1), o_lo), min(T.ro(k), o_hi), col_at_pos);
+    } else {
+        b.a = T.ra(k);
+        b.o = T.ro(k);
     }
     return b;
 }
 
-// Three-way merge of S[sb, se) (columns and values in LDS, index relative to e0), A[ab, ae) and O[ob, oe).
-// Returns the number of results; WRITE: stores them from position pos on.
-template <bool WRITE>
-__device__ __forceinline__ int merge3(const int *s_col, const float *s_val, int e0, int sb, int se, const List &A, int ab,
-                                      int ae, float alpha, const List &O, int ob, int oe, float beta,
-                                      int32_t *__restrict__ out_col, float *__restrict__ out_val, int64_t pos) {
-    int cs = sb < se ? s_col[sb - e0] : kNoCol;
-    int ca = ab < ae ? A.at(ab) : kNoCol;
-    int co = ob < oe ? O.at(ob) : kNoCol;
-    int cnt = 0;
+// One lane's share: from boundary `mine` (S entry sb0) to boundary `next` (S entry sb1).  cnt counts the results;
+// WRITE: `cnt` starts at the share's position in C and the results and the row pointers of the rows that begin
+// in the share are stored.
+template <bool WRITE, bool STAGED>
+__device__ __forceinline__ int64_t merge_share(const Operands &P, const Terms<STAGED> &T, const int *s_col, const float *s_val,
+                                               int e0, const Bound &mine, int sb0, const Bound &next, int sb1, int64_t cnt,
+                                               int32_t *__restrict__ rowptr_out, int32_t *__restrict__ out_col,
+                                               float *__restrict__ out_val) {
+    // One loop over terms AND rows: a lane whose row piece is finished moves to its next row in the same trip in
+    // which other lanes merge a term, so the trip count of the wavefront is that of its longest share, not the
+    // sum over row positions of the longest piece.
+    int r = mine.k - (mine.cut ? 1 : 0);
+    if (r >= next.k) return cnt;
+    int sb = max(T.rs(r), sb0), ab = max(T.ra(r), mine.a), ob = max(T.ro(r), mine.o);
+    int se = min(T.rs(r + 1), sb1), ae = min(T.ra(r + 1), next.a), oe = min(T.ro(r + 1), next.o);
+    if (WRITE && r >= mine.k) rowptr_out[r] = (int32_t)cnt;                // the row begins in this share
     for (;;) {
+        const int cs = sb < se ? s_col[sb - e0] : kNoCol;
+        const int ca = ab < ae ? T.a(ab) : kNoCol;
+        const int co = ob < oe ? T.o(ob) : kNoCol;
         const int c = min(cs, min(ca, co));
-        if (c == kNoCol) break;
-        float v = 0.0f;
-        if (cs == c) { v = s_val[sb - e0]; ++sb; cs = sb < se ? s_col[sb - e0] : kNoCol; }
-        if (ca == c) { v += alpha; ++ab; ca = ab < ae ? A.at(ab) : kNoCol; }
-        if (co == c) { v += beta; ++ob; co = ob < oe ? O.at(ob) : kNoCol; }
-        if (v != 0.0f) {
-            if (WRITE) { out_col[pos + cnt] = c; out_val[pos + cnt] = v; }
-            ++cnt;
+        if (c == kNoCol) {
+            // next row: its pieces begin where the finished ones ended (rows are consecutive in all three arrays)
+            if (++r >= next.k) break;
+            se = min(T.rs(r + 1), sb1); ae = min(T.ra(r + 1), next.a); oe = min(T.ro(r + 1), next.o);
+            if (WRITE) rowptr_out[r] = (int32_t)cnt;
+        } else {
+            float v = 0.0f;
+            if (cs == c) { v = s_val[sb - e0]; ++sb; }
+            if (ca == c) { v += P.alpha; ++ab; }
+            if (co == c) { v += P.beta; ++ob; }
+            if (v != 0.0f) {
+                if (WRITE) { out_col[cnt] = c; out_val[cnt] = v; }
+                ++cnt;
+            }
         }
     }
     return cnt;
 }
 
-// The share of lane `lane` when 64 lanes merge one row piece together: an equal share of the longest list, and
-// of the two others the terms whose columns lie between the share's first column and the next share's.
-struct Share { int sb, se, ab, ae, ob, oe; };
-__device__ __forceinline__ Share coop_share(const int *s_col, int e0, int sb, int se, const List &A, int ab, int ae,
-                                            const List &O, int ob, int oe, int lane) {
-    const int ls = se - sb, la = ae - ab, lo = oe - ob;
-    const int which = (ls >= la && ls >= lo) ? 0 : (la >= lo ? 1 : 2);
-    const int lb = which == 0 ? sb : which == 1 ? ab : ob, le = which == 0 ? se : which == 1 ? ae : oe;
-    const int q = (le - lb + kWave - 1) / kWave;                 // >= 1: the longest list is not empty
-    const int mb = min(lb + lane * q, le), me = min(mb + q, le);
-    const bool active = mb < le, first = lane == 0, final = me == le;
-    auto col_of = [&](int i) { return which == 0 ? s_col[i - e0] : which == 1 ? A.at(i) : O.at(i); };
-    const int c_lo = (active && !first) ? col_of(mb) : 0, c_hi = (active && !final) ? col_of(me) : 0;
-    const List S{s_col, e0};
-    Share sh;
-    auto cut = [&](const List &l, int b, int e, int &ob_, int &oe_) {
-        ob_ = first ? b : list_lower_bound(l, b, e, c_lo);
-        oe_ = final ? e : list_lower_bound(l, b, e, c_hi);
-        if (!active) ob_ = oe_ = e;
-    };
-    cut(S, sb, se, sh.sb, sh.se);
-    cut(A, ab, ae, sh.ab, sh.ae);
-    cut(O, ob, oe, sh.ob, sh.oe);
-    return sh;
+// bounds[w] = the boundary at S entry w * kRange (w < n_ranges), bounds[n_ranges] = the end of everything.
+__global__ __launch_bounds__(256) void bounds_kernel(Operands P, int n_ranges, Bound *__restrict__ bounds) {
+    const int w = blockIdx.x * 256 + threadIdx.x;
+    if (w > n_ranges) return;
+    if (w == n_ranges) { bounds[w] = Bound{P.n, 0, P.nnz_a, P.nnz_o}; return; }
+    const Terms<false> G{nullptr, nullptr, nullptr, nullptr, nullptr, P.col_a, P.col_o, P.rp_s, P.rp_a, P.rp_o, 0, 0, 0};
+    const int pos = (int)min((int64_t)w * kRange, (int64_t)P.nnz_s);
+    const int k = lower_bound(P.rp_s, 0, P.n, pos);               // first row that begins at pos or later (rp_s[n] >= pos)
+    bounds[w] = make_bound(G, pos, k, pos < P.nnz_s ? P.col_s[pos] : 0, 0, P.nnz_a, 0, P.nnz_o);
 }
 
 template <bool WRITE>
-__global__ __launch_bounds__(kWave) void combine_kernel(
-    int n, int nnz_s, int n_ranges, const int32_t *__restrict__ rp_s, const int32_t *__restrict__ col_s,
-    const float *__restrict__ val_s, const int32_t *__restrict__ rp_a, const int32_t *__restrict__ col_a, float alpha,
-    const int32_t *__restrict__ rp_o, const int32_t *__restrict__ col_o, float beta, int32_t *__restrict__ totals,
-    int32_t *__restrict__ rowptr_out, int32_t *__restrict__ out_col, float *__restrict__ out_val) {
+__global__ __launch_bounds__(kWave) void combine_kernel(Operands P, int n_ranges, const Bound *__restrict__ bounds,
+                                                       int32_t *__restrict__ totals,
+                                                       int32_t *__restrict__ lane_counts, int32_t *__restrict__ rowptr_out,
+                                                       int32_t *__restrict__ out_col, float *__restrict__ out_val) {
     __shared__ int s_col[kRange];
     __shared__ float s_val[kRange];
     __shared__ int s_a[kCapIn];
     __shared__ int s_o[kCapOut];
+    __shared__ int s_rs[kCapRows], s_ra[kCapRows], s_ro[kCapRows];
 
     const int lane = threadIdx.x, range = blockIdx.x;
-    const int e0 = (int)min((int64_t)range * kRange, (int64_t)nnz_s), e1 = (int)min((int64_t)e0 + kRange, (int64_t)nnz_s);
+    const int e0 = (int)min((int64_t)range * kRange, (int64_t)P.nnz_s), e1 = (int)min((int64_t)e0 + kRange, (int64_t)P.nnz_s);
     const bool last = range == n_ranges - 1;
-    if (nnz_s > 0)
+    if (P.nnz_s > 0)
         for (int i = lane; i < kRange; i += kWave) {               // unconditional (clamped): the loads stay in flight together
-            const int src = min(e0 + i, nnz_s - 1);
-            s_col[i] = col_s[src];
-            s_val[i] = val_s ? val_s[src] : 1.0f;
+            const int src = min(e0 + i, P.nnz_s - 1);
+            s_col[i] = P.col_s[src];
+            s_val[i] = P.val_s ? P.val_s[src] : 1.0f;
         }
-    // rows of the range: the one cut by its begin (if any), then every row that begins in [e0, e1), rows without
-    // entries included; the last range also takes the rows behind the last entry of S
-    const int k_lo = wave_find_row(rp_s, n, e0 - 1, lane) + 1;           // first row that begins at e0 or later
-    const int k_first = (k_lo == n || rp_s[k_lo] > e0) ? k_lo - 1 : k_lo;
-    const int k_end = last ? n - 1 : wave_find_row(rp_s, n, e1 - 1, lane);
-    const bool cut_l = rp_s[k_first] < e0, cut_r = rp_s[k_end + 1] > e1;
-    wave_lds_sync();
-    // the terms of A_in and A_out that belong to the range: whole rows, except in the cut rows, where they are
-    // the ones from the column of S's entry e0 on, and below the column of S's entry e1
-    const int col_l = cut_l ? s_col[0] : 0, col_r = cut_r ? col_s[e1] : 0;
-    auto span = [&](const int32_t *rp, const int32_t *col, int &b, int &e) {
-        b = e = 0;
-        if (!rp) return;
-        const List g{col, 0};
-        b = cut_l ? list_lower_bound(g, rp[k_first], rp[k_first + 1], col_l) : rp[k_first];
-        e = cut_r ? list_lower_bound(g, rp[k_end], rp[k_end + 1], col_r) : rp[k_end + 1];
-    };
-    int a_begin, a_end, o_begin, o_end;
-    span(rp_a, col_a, a_begin, a_end);
-    span(rp_o, col_o, o_begin, o_end);
-    const bool a_staged = a_end - a_begin <= kCapIn, o_staged = o_end - o_begin <= kCapOut;
-    if (a_staged) for (int i = a_begin + lane; i < a_end; i += kWave) s_a[i - a_begin] = col_a[i];
-    if (o_staged) for (int i = o_begin + lane; i < o_end; i += kWave) s_o[i - o_begin] = col_o[i];
-    wave_lds_sync();
-    const List A{a_staged ? (const int32_t *)s_a : col_a, a_staged ? a_begin : 0};
-    const List O{o_staged ? (const int32_t *)s_o : col_o, o_staged ? o_begin : 0};
-
-    const int64_t base = WRITE ? (int64_t)totals[range] : 0;      // position of the range's first result
-    int run = 0;                                                  // results of the rows handled so far
-    for (int row0 = k_first; row0 <= k_end; row0 += kWave) {
-        const int r = row0 + lane;
-        const bool valid = r <= k_end;
-        const int rb = valid ? rp_s[r] : e1, re = valid ? rp_s[r + 1] : e1;
-        const bool open_l = valid && rb < e0, open_r = valid && re > e1;
-        const int sb = max(rb, e0), se = min(re, e1);
-        int ab = 0, ae = 0, ob = 0, oe = 0;
-        if (valid && rp_a) { ab = open_l ? a_begin : rp_a[r]; ae = open_r ? a_end : rp_a[r + 1]; }
-        if (valid && rp_o) { ob = open_l ? o_begin : rp_o[r]; oe = open_r ? o_end : rp_o[r + 1]; }
-        const bool coop = (se - sb) + (ae - ab) + (oe - ob) > kCoop;
-        // results per row piece
-        int cnt = 0;
-        if (valid && !coop) cnt = merge3<false>(s_col, s_val, e0, sb, se, A, ab, ae, alpha, O, ob, oe, beta, nullptr, nullptr, 0);
-        const uint64_t coop_mask = __ballot(coop);
-        for (uint64_t todo = coop_mask; todo; todo &= todo - 1) {
-            const int src = __builtin_ctzll(todo);
-            const Share sh = coop_share(s_col, e0, __shfl(sb, src, kWave), __shfl(se, src, kWave), A, __shfl(ab, src, kWave),
-                                        __shfl(ae, src, kWave), O, __shfl(ob, src, kWave), __shfl(oe, src, kWave), lane);
-            const int mine = merge3<false>(s_col, s_val, e0, sh.sb, sh.se, A, sh.ab, sh.ae, alpha, O, sh.ob, sh.oe, beta,
-                                           nullptr, nullptr, 0);
-            const int total = __shfl(wave_scan_add(mine, lane), kWave - 1, kWave);
-            if (lane == src) cnt = total;
+    // the range's own boundaries (found beforehand by bounds_kernel: one chain of dependent look-ups per range,
+    // which the few wavefronts that fit beside this kernel's LDS could not hide)
+    const Terms<false> G{nullptr, nullptr, nullptr, nullptr, nullptr, P.col_a, P.col_o, P.rp_s, P.rp_a, P.rp_o, 0, 0, 0};
+    const Bound B0 = bounds[range], B1 = bounds[range + 1];
+    // rows whose pointers the lanes read: from the row the range begins in to the first row behind it
+    const int row_lo = max(B0.k - 1, 0), row_hi = B1.k;
+    const bool staged = B1.a - B0.a <= kCapIn && B1.o - B0.o <= kCapOut && row_hi - row_lo + 1 <= kCapRows;
+    if (staged) {
+        for (int i = B0.a + lane; i < B1.a; i += kWave) s_a[i - B0.a] = P.col_a[i];
+        for (int i = B0.o + lane; i < B1.o; i += kWave) s_o[i - B0.o] = P.col_o[i];
+        for (int r = row_lo + lane; r <= row_hi; r += kWave) {
+            s_rs[r - row_lo] = P.rp_s[r];
+            s_ra[r - row_lo] = P.rp_a ? P.rp_a[r] : 0;
+            s_ro[r - row_lo] = P.rp_o ? P.rp_o[r] : 0;
         }
-        const int incl = wave_scan_add(cnt, lane);
-        if (WRITE) {
-            const int64_t pos = base + run + incl - cnt;          // where this lane's row piece begins
-            if (valid && !open_l) rowptr_out[r] = (int32_t)pos;   // the row begins in this range
-            if (valid && !coop) merge3<true>(s_col, s_val, e0, sb, se, A, ab, ae, alpha, O, ob, oe, beta, out_col, out_val, pos);
-            for (uint64_t todo = coop_mask; todo; todo &= todo - 1) {
-                const int src = __builtin_ctzll(todo);
-                const Share sh = coop_share(s_col, e0, __shfl(sb, src, kWave), __shfl(se, src, kWave), A, __shfl(ab, src, kWave),
-                                            __shfl(ae, src, kWave), O, __shfl(ob, src, kWave), __shfl(oe, src, kWave), lane);
-                const int mine = merge3<false>(s_col, s_val, e0, sh.sb, sh.se, A, sh.ab, sh.ae, alpha, O, sh.ob, sh.oe, beta,
-                                               nullptr, nullptr, 0);
-                const int before = wave_scan_add(mine, lane) - mine;
-                const int64_t row_pos = __shfl((int)(pos - base), src, kWave) + base;
-                merge3<true>(s_col, s_val, e0, sh.sb, sh.se, A, sh.ab, sh.ae, alpha, O, sh.ob, sh.oe, beta, out_col, out_val,
-                             row_pos + before);
-            }
-        }
-        run += __shfl(incl, kWave - 1, kWave);
     }
-    if (!WRITE && lane == 0) totals[range] = run;
-    if (WRITE && last && lane == 0) rowptr_out[n] = (int32_t)(base + run);
+    wave_lds_sync();
+
+    // this lane's share: S entries [sb0, sb1); an empty S still gives lane 0 of the only range a share (all rows)
+    const int sb0 = min(e0 + lane * kPer, e1), sb1 = min(sb0 + kPer, e1);
+    const bool active = sb0 < e1 || (P.nnz_s == 0 && lane == 0);
+    auto run = [&](auto T) {
+        Bound mine = B1;
+        if (lane == 0) mine = B0;
+        else if (active)
+            mine = make_bound(T, sb0, T.first_row_at_or_after(B0.k, B1.k, sb0), s_col[sb0 - e0], B0.a, B1.a, B0.o, B1.o);
+        // the next lane's boundary; the last lane with a share ends at the range's end
+        Bound next;
+        next.k = __shfl_down(mine.k, 1, kWave); next.cut = __shfl_down(mine.cut, 1, kWave);
+        next.a = __shfl_down(mine.a, 1, kWave); next.o = __shfl_down(mine.o, 1, kWave);
+        if (lane == kWave - 1 || sb1 >= e1) next = B1;
+        int64_t begin = 0;
+        if (WRITE) {
+            const int mine_cnt = active ? lane_counts[(int64_t)range * kWave + lane] : 0;
+            const int incl = wave_scan_add(mine_cnt, lane);
+            begin = (int64_t)totals[range] + incl - mine_cnt;
+            if (last && lane == kWave - 1) rowptr_out[P.n] = (int32_t)(totals[range] + incl);
+        }
+        int64_t end = begin;
+        if (active) end = merge_share<WRITE>(P, T, s_col, s_val, e0, mine, sb0, next, sb1, begin, rowptr_out, out_col, out_val);
+        if (!WRITE) {
+            const int cnt = (int)(end - begin);
+            lane_counts[(int64_t)range * kWave + lane] = cnt;
+            const int incl = wave_scan_add(cnt, lane);
+            if (lane == kWave - 1) totals[range] = incl;
+        }
+    };
+    if (staged) run(Terms<true>{s_a, s_o, s_rs, s_ra, s_ro, P.col_a, P.col_o, P.rp_s, P.rp_a, P.rp_o, B0.a, B0.o, row_lo});
+    else run(G);
 }
 
 // In place: counts[0 .. m) -> their exclusive prefix sums, counts[m] = the total.  One workgroup; m is a number of
@@ -219,7 +241,12 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(int m, int32_t *__re
 
 int64_t range_count(int64_t nnz_s) { return std::max<int64_t>(1, (nnz_s + kRange - 1) / kRange); }
 
-size_t combine_workspace(int64_t nnz_s) { return round_up((size_t)(4 * (range_count(nnz_s) + 1)), (size_t)256); }
+// range totals (+ the grand total), then one count per lane
+size_t totals_bytes(int64_t nnz_s) { return round_up((size_t)(4 * (range_count(nnz_s) + 1)), (size_t)256); }
+size_t counts_bytes(int64_t nnz_s) { return round_up((size_t)(4 * kWave * range_count(nnz_s)), (size_t)256); }
+size_t combine_workspace(int64_t nnz_s) {
+    return totals_bytes(nnz_s) + counts_bytes(nnz_s) + round_up(sizeof(Bound) * (size_t)(range_count(nnz_s) + 1), (size_t)256);
+}
 
 }  // namespace
 
@@ -243,14 +270,20 @@ extern "C" int dgnn_csr_combine(int64_t n, const int32_t *rowptr_s, const int32_
     if (!rowptr_in) nnz_in = 0;
     if (!rowptr_out_of) nnz_out_of = 0;
     if (!fits_index(n + 1) || !fits_index(nnz_s + nnz_in + nnz_out_of)) return DGNN_ERR_OVERFLOW;
+    if (!aligned16(ws)) return DGNN_ERR_ALIGN;
     if (ws_bytes < combine_workspace(nnz_s)) return DGNN_ERR_CAPACITY;
     if (rowptr_c == rowptr_s || colidx_c == colidx_s || (val_s && val_c == val_s)) return DGNN_ERR_ALIAS;
     hipStream_t s = (hipStream_t)stream;
     const int ranges = (int)range_count(nnz_s);
     int32_t *totals = (int32_t *)ws;
-    hipLaunchKernelGGL(combine_kernel<false>, dim3((unsigned)ranges), dim3(kWave), 0, s, (int)n, (int)nnz_s, ranges, rowptr_s,
-                       colidx_s, val_s, rowptr_in, colidx_in, alpha, rowptr_out_of, colidx_out_of, beta, totals, nullptr, nullptr,
-                       nullptr);
+    int32_t *lane_counts = (int32_t *)((char *)ws + totals_bytes(nnz_s));
+    const Operands P{(int)n, (int)nnz_s, (int)nnz_in, (int)nnz_out_of, rowptr_s, colidx_s, val_s, rowptr_in, colidx_in,
+                     rowptr_out_of, colidx_out_of, alpha, beta};
+    Bound *bounds = (Bound *)((char *)ws + totals_bytes(nnz_s) + counts_bytes(nnz_s));
+    hipLaunchKernelGGL(bounds_kernel, dim3((unsigned)(ranges / 256 + 1)), dim3(256), 0, s, P, ranges, bounds);
+    DGNN_RETURN_IF_LAUNCH_FAILED();
+    hipLaunchKernelGGL(combine_kernel<false>, dim3((unsigned)ranges), dim3(kWave), 0, s, P, ranges, bounds, totals, lane_counts,
+                       nullptr, nullptr, nullptr);
     DGNN_RETURN_IF_LAUNCH_FAILED();
     hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(kScanThreads), 0, s, ranges, totals);
     DGNN_RETURN_IF_LAUNCH_FAILED();
@@ -259,9 +292,8 @@ extern "C" int dgnn_csr_combine(int64_t n, const int32_t *rowptr_s, const int32_
     if (hipStreamSynchronize(s) != hipSuccess) return DGNN_ERR_HIP;
     *nnz_c = total;
     if (total > capacity) return DGNN_ERR_CAPACITY;
-    hipLaunchKernelGGL(combine_kernel<true>, dim3((unsigned)ranges), dim3(kWave), 0, s, (int)n, (int)nnz_s, ranges, rowptr_s,
-                       colidx_s, val_s, rowptr_in, colidx_in, alpha, rowptr_out_of, colidx_out_of, beta, totals, rowptr_c,
-                       colidx_c, val_c);
+    hipLaunchKernelGGL(combine_kernel<true>, dim3((unsigned)ranges), dim3(kWave), 0, s, P, ranges, bounds, totals, lane_counts,
+                       rowptr_c, colidx_c, val_c);
     DGNN_RETURN_IF_LAUNCH_FAILED();
     return DGNN_OK;
 }
