@@ -22,11 +22,11 @@ namespace {
 
 using namespace dgnn;
 
-constexpr int kPer = 16;               // entries of S per lane
+constexpr int kPer = 4;                // entries of S per lane
 constexpr int kRange = kPer * kWave;   // entries of S per wavefront
-constexpr int kCapIn = 1536;           // staged terms of A_in per range
-constexpr int kCapOut = 1024;          // staged terms of A_out per range
-constexpr int kCapRows = 384;          // staged row pointers per range and operand
+constexpr int kCapIn = 384;            // staged terms of A_in per range
+constexpr int kCapOut = 256;           // staged terms of A_out per range
+constexpr int kCapRows = 128;          // staged row pointers per range and operand
 constexpr int kNoCol = 0x7fffffff;     // larger than any column index the library accepts
 constexpr int kScanThreads = 1024;
 
@@ -213,30 +213,40 @@ __global__ __launch_bounds__(kWave) void combine_kernel(Operands P, int n_ranges
     else run(G);
 }
 
-// In place: counts[0 .. m) -> their exclusive prefix sums, counts[m] = the total.  One workgroup; m is a number of
-// ranges, a few hundred thousand at the largest supported snapshot.
+// In place: counts[0 .. m) -> their exclusive prefix sums, counts[m] = the total.  One workgroup walks tiles of
+// 4096 counts (four per thread, scanned within the wavefront by lane shifts, across wavefronts through LDS); m is
+// a number of ranges, about a million at the largest supported snapshot.
 __global__ __launch_bounds__(kScanThreads) void scan_kernel(int m, int32_t *__restrict__ counts) {
-    __shared__ int s_part[kScanThreads];
-    const int tid = threadIdx.x;
-    const int per = (m + kScanThreads - 1) / kScanThreads;
-    const int b = min(tid * per, m), e = min(b + per, m);
-    int sum = 0;
-    for (int i = b; i < e; ++i) sum += counts[i];
-    s_part[tid] = sum;
-    __syncthreads();
-    for (int d = 1; d < kScanThreads; d <<= 1) {                  // inclusive scan of the per-thread sums
-        const int add = tid >= d ? s_part[tid - d] : 0;
+    constexpr int kWaves = kScanThreads / kWave;
+    __shared__ int s_wave[kWaves];
+    const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+    int carry = 0;                                                // total of the tiles done so far (same in all threads)
+    for (int base = 0; base < m; base += 4 * kScanThreads) {
+        const int i = base + 4 * tid;
+        int v[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] = i + q < m ? counts[i + q] : 0;
+        const int mine = (v[0] + v[1]) + (v[2] + v[3]);
+        const int incl = wave_scan_add(mine, lane);
+        if (lane == kWave - 1) s_wave[wave] = incl;
         __syncthreads();
-        s_part[tid] += add;
-        __syncthreads();
+        int before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const int t = s_wave[w];
+            if (w < wave) before += t;
+            total += t;
+        }
+        int run = carry + before + incl - mine;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (i + q < m) counts[i + q] = run;
+            run += v[q];
+        }
+        carry += total;
+        __syncthreads();                                          // s_wave is written again in the next tile
     }
-    int run = s_part[tid] - sum;
-    for (int i = b; i < e; ++i) {
-        const int c = counts[i];
-        counts[i] = run;
-        run += c;
-    }
-    if (tid == kScanThreads - 1) counts[m] = s_part[tid];
+    if (tid == 0) counts[m] = carry;
 }
 
 int64_t range_count(int64_t nnz_s) { return std::max<int64_t>(1, (nnz_s + kRange - 1) / kRange); }

@@ -221,3 +221,57 @@ def test_power_law_training_step_full_size():
             got = to_f64(captured[1][torch.as_tensor(cols, device=DEV)])
             assert_close(got, sums, torch.float32, "A~^T G_P on sampled rows")
     assert_close(to_f64(tr.dw[0]), dw, torch.float32, "c3 dW over two full-size timesteps")
+
+
+@pytest.mark.timeout(600)
+def test_sliding_window_sum_full_size():
+    """c5 at full size: S_2 = A_1 + A_2 and S_3 = S_2 + A_3 - A_1 (edge life 2) from the snapshots the runner leaves
+    resident.  Sizes and value totals follow from the difference lists; 2^14 sampled rows and the 256 longest are
+    compared entry by entry with the oracle's sum of the same rows of the oracle's snapshots."""
+    import paper_2109_07893_amd as dg
+    wl = WORKLOADS["c5"]
+    blk = make_block(wl, DEV, gen_device=DEV, T=3)
+    runner = BlockRunner(blk, keep_all_z=False)
+    runner.load_first()
+    runner.run_resident(first=4)                     # rebuilds only: A_1, A_2, A_3 stay in the three slots
+    torch.cuda.synchronize()
+    n = wl.n
+    snap = {t: (runner.rowptr[runner.slot_of(t)], runner.colidx[runner.slot_of(t)], blk.nnz[t - 1]) for t in (1, 2, 3)}
+    cap = blk.nnz[0] + blk.nnz[1]
+    bufs = [(torch.empty(n + 1, dtype=torch.int32, device=DEV), torch.empty(cap, dtype=torch.int32, device=DEV),
+             torch.empty(cap, device=DEV)) for _ in range(2)]
+    ws = torch.empty(dg.csr_combine_workspace(cap), dtype=torch.uint8, device=DEV)
+    progress("S_2 = A_1 + A_2")
+    nnz2 = dg.csr_combine((snap[1][0], snap[1][1], None, snap[1][2]), snap[2], 1.0, None, -1.0, bufs[0], ws)
+    progress("S_3 = S_2 + A_3 - A_1")
+    nnz3 = dg.csr_combine((bufs[0][0], bufs[0][1], bufs[0][2], nnz2), snap[3], 1.0, snap[1], -1.0, bufs[1], ws)
+    torch.cuda.synchronize()
+    n_add = [int(d[0].numel()) for d in blk.deltas]
+    assert nnz2 == blk.nnz[0] + n_add[0]             # A_1 united with what step 2 adds
+    assert nnz3 == blk.nnz[1] + n_add[1]             # A_2 united with what step 3 adds
+    for (rp_c, ci_c, val_c), nnz, total in ((bufs[0], nnz2, blk.nnz[0] + blk.nnz[1]), (bufs[1], nnz3, blk.nnz[1] + blk.nnz[2])):
+        assert int(rp_c[0]) == 0 and int(rp_c[n]) == nnz and bool((rp_c[1:] >= rp_c[:-1]).all())
+        assert int(val_c[:nnz].to(torch.int64).sum()) == total
+        assert float(val_c[:nnz].min()) == 1.0 and float(val_c[:nnz].max()) == 2.0
+    progress("oracle snapshots")
+    rp, ci = blk.rowptr1.cpu().numpy(), blk.colidx1.cpu().numpy()
+    host = {1: (rp, ci)}
+    for t in (2, 3):
+        rp, ci = oracle.delta_apply(n, rp, ci, *host_lists(blk, t))
+        host[t] = (rp, ci)
+    rows = sample_rows(host[3][0], 1 << 14, 256, seed=3)
+
+    def sub(rp, ci, val=None):
+        """The sampled rows as a CSR of their own (row i of it = sampled row i, columns unchanged)."""
+        lens = rp[rows + 1] - rp[rows]
+        take = np.concatenate([np.arange(rp[r], rp[r + 1]) for r in rows])
+        out = (np.concatenate([[0], np.cumsum(lens)]).astype(np.int32), ci[take])
+        return out + ((val[take],) if val is not None else ())
+
+    progress("sampled rows")
+    want2 = oracle.csr_combine(rows.size, sub(*host[1]) + (None,), sub(*host[2]), 1.0)
+    want3 = oracle.csr_combine(rows.size, want2, sub(*host[3]), 1.0, sub(*host[1]), -1.0)
+    for (rp_c, ci_c, val_c), nnz, want in ((bufs[0], nnz2, want2), (bufs[1], nnz3, want3)):
+        got = sub(rp_c.cpu().numpy(), ci_c[:nnz].cpu().numpy(), val_c[:nnz].cpu().numpy())
+        assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1])
+        assert np.array_equal(got[2].astype(np.float64), want[2])

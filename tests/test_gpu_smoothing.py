@@ -106,11 +106,11 @@ def test_combine_reports_the_size_when_the_result_does_not_fit():
     assert bool((out[0] == -7).all()) and bool((out[1] == -7).all())      # nothing written
 
 
-@pytest.mark.parametrize("name,n,life", [("c1", 1000, 3), ("c3", 1 << 13, 4), ("c2", 20_000, 2), ("c5", 1 << 13, 8)])
-def test_sliding_window_sum_on_the_device(name, n, life):
+@pytest.mark.parametrize("name,n,life,T", [("c1", 1000, 3, 10), ("c3", 1 << 13, 4, 10), ("c2", 20_000, 2, 10), ("c5", 1 << 13, 8, 10),
+                                           ("c5", 1 << 17, 2, 4)])     # the last one: several tiles of the scan over ranges
+def test_sliding_window_sum_on_the_device(name, n, life, T):
     """S_t = S_{t-1} + A_t - A_{t-l} carried on the device over a series; the expected S_t is formed here from the
     raw oracle snapshots (sorted keys of the window, counted with numpy), not step by step."""
-    T = 10
     wl = WORKLOADS[name].scaled(n, T=T) if n != WORKLOADS[name].n else WORKLOADS[name]
     T = min(T, wl.T)
     raw = DynamicGraph(wl)
