@@ -232,8 +232,29 @@ def smoothing_steps(args, wl, blk, dev, life=4):
     dg.csr_weighted_dinv(s[0], s[2], s[3], dinv, ws_d)
     e1.record()
     torch.cuda.synchronize()
-    return {"edge_life": life, "steps": rows, "csr_weighted_dinv_ms": round(e0.elapsed_time(e1), 3),
-            "note": "each step: count launch, scan, read-back of the size (a stream synchronisation), write launch"}
+    out = {"edge_life": life, "steps": rows, "csr_weighted_dinv_ms": round(e0.elapsed_time(e1), 3),
+           "note": "each step: count launch, scan, read-back of the size (a stream synchronisation), write launch"}
+    del snaps, bufs, ws, s
+    torch.cuda.empty_cache()
+    # the whole forward pass on smoothed snapshots: rebuild, sliding-window sum, normalisation, X W, aggregation
+    from paper_2109_07893_amd.pipeline import SmoothedRunner, StageTimer
+    runner = SmoothedRunner(blk, life)
+    runner.run_resident()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        runner.run_resident()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    runner.timer = StageTimer(dev)
+    runner.run_resident()
+    torch.cuda.synchronize()
+    stored = runner.cur[3]
+    out["forward_pass"] = {"ms_per_step": round(ms, 3), "snapshots_per_step": blk.T, "stored_entries_last": stored,
+                           "stages": {k: {"calls_per_step": c, "avg_ms": round(t / c, 4)}
+                                      for k, (c, t) in runner.timer.totals().items()},
+                           "note": "every snapshot t = 1..T, including the copy of A_1 into the ring at the start of the pass"}
+    return out
 
 
 def cdgcn_layer(args, wl, blk, dev):

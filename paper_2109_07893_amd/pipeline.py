@@ -251,3 +251,91 @@ class BlockRunner:
     def snapshot_to_host(self, t: int):
         slot = self.slot_of(t)
         return self.rowptr[slot].cpu().numpy(), self.colidx[slot][: self.blk.nnz[t - 1]].cpu().numpy()
+
+
+class SmoothedRunner(BlockRunner):
+    """Forward pass over a block on SMOOTHED snapshots (Section "Smoothening the Input Graphs"), with the smoothing
+    done on the device: the raw snapshot A_t is rebuilt from the difference lists as before, the smoothed one is
+    S_t = S_{t-1} + A_t - A_{t-life} (dgnn_csr_combine on resident snapshots: a ring of life + 1 raw ones), its
+    normalisation is recomputed from the weighted row sums (dgnn_csr_weighted_dinv), and the GCN step aggregates
+    with the raw counts as values (dgnn_spmm_weighted with dinv).  Only the raw difference lists ever travel."""
+
+    def __init__(self, blk: BlockInputs, life: int, keep_all_z: Optional[bool] = None):
+        super().__init__(blk, keep_all_z)
+        assert life >= 1
+        self.life = life
+        dev, n = self.dev, blk.n
+        while len(self.rowptr) < life + 1:
+            self.rowptr.append(torch.empty(n + 1, dtype=torch.int32, device=dev))
+            self.colidx.append(torch.empty(self.cap, dtype=torch.int32, device=dev))
+            self.dinv.append(torch.empty(n, dtype=torch.float32, device=dev))
+        # the window's union holds A_t and whatever the window's steps deleted
+        max_del = max([int(d[2].numel()) for d in blk.deltas] + [0])
+        self.cap_s = self.cap + life * max_del
+        self.s = [(torch.empty(n + 1, dtype=torch.int32, device=dev), torch.empty(self.cap_s, dtype=torch.int32, device=dev),
+                   torch.empty(self.cap_s, dtype=torch.float32, device=dev)) for _ in range(2)]
+        self.s_nnz = 0
+        self.cur = None                                 # (rowptr, colidx, val, nnz) of S_t
+        self.dinv_s = torch.empty(n, dtype=torch.float32, device=dev)
+        self.ws_combine = torch.empty(B.csr_combine_workspace(self.cap_s), dtype=torch.uint8, device=dev)
+        self.ws_dinv = torch.empty(B.csr_weighted_dinv_workspace(self.cap_s), dtype=torch.uint8, device=dev)
+        self.ws_spmm = torch.empty(B.spmm_workspace(n, self.cap_s, blk.f), dtype=torch.uint8, device=dev)
+
+    def slot_of(self, t: int) -> int:                   # a ring: A_{t-life} is still there when S_t is formed
+        return t % (self.life + 1)
+
+    def load_first(self) -> None:
+        blk = self.blk
+        slot = self.slot_of(1)
+        self.rowptr[slot].copy_(blk.rowptr1)
+        self.colidx[slot][: blk.nnz[0]].copy_(blk.colidx1)
+        B.csr_dinv(self.rowptr[slot], self.dinv[slot])
+        rp, ci, val = self.s[1]                          # S_1 = A_1, every entry counted once
+        rp.copy_(blk.rowptr1)
+        ci[: blk.nnz[0]].copy_(blk.colidx1)
+        val[: blk.nnz[0]].fill_(1.0)
+        self.cur = (rp, ci, val, blk.nnz[0])
+
+    def smooth(self, t: int) -> None:
+        """S_t from S_{t-1}, A_t and A_{t-life} (t >= 2), then its normalisation."""
+        blk = self.blk
+        if t >= 2:
+            a_in = (self.rowptr[self.slot_of(t)], self.colidx[self.slot_of(t)], blk.nnz[t - 1])
+            a_out = None
+            if t - self.life >= 1:
+                k = t - self.life
+                a_out = (self.rowptr[self.slot_of(k)], self.colidx[self.slot_of(k)], blk.nnz[k - 1])
+            out = self.s[t % 2]
+            with self._stage("csr_combine"):
+                nnz = B.csr_combine(self.cur, a_in, 1.0, a_out, -1.0, out, self.ws_combine)
+            self.cur = (out[0], out[1], out[2], nnz)
+        with self._stage("csr_weighted_dinv"):
+            B.csr_weighted_dinv(self.cur[0], self.cur[2], self.cur[3], self.dinv_s, self.ws_dinv)
+
+    def gcn(self, t: int) -> torch.Tensor:
+        blk = self.blk
+        rp, ci, val, nnz = self.cur
+        out = self.z[t - 1] if self.keep_all_z else self.z[0]
+        cur = blk.x[t - 1]
+        for layer in range(blk.layers):
+            with self._stage("feature_transform"):
+                B.feature_transform(cur, blk.weight(t, layer), self.h, row_scale=self.dinv_s)
+            dst = out if layer == blk.layers - 1 else self.z_mid
+            with self._stage("spmm_weighted"):
+                B.spmm_weighted(rp, ci, val, nnz, self.h, dst, self.ws_spmm, flags=B.DGNN_RELU | B.DGNN_H_PRESCALED,
+                                dinv=self.dinv_s)
+            cur = dst
+        return out
+
+    def run_resident(self, first: int = 1, validate: bool = False, on_snapshot=None) -> None:
+        blk = self.blk
+        self.load_first()                                # the ring overwrites A_1: every pass starts from the inputs
+        for t in range(1, blk.T + 1):
+            if t >= 2:
+                self.rebuild(t, blk.deltas[t - 2], validate)
+            self.smooth(t)
+            if t >= first:
+                self.gcn(t)
+            if on_snapshot is not None:
+                on_snapshot(t, self.slot_of(t))
+        self.mix()

@@ -127,3 +127,39 @@ def test_sliding_window_sum_on_the_device(name, n, life, T):
         got_keys = (np.repeat(np.arange(wl.n, dtype=np.int64), np.diff(s[0])) << 32) | s[1].astype(np.int64)
         assert np.array_equal(got_keys, want_keys), (name, t)
         assert np.array_equal(s[2], counts.astype(np.float32)), (name, t)
+
+
+@pytest.mark.parametrize("name,n,T,life", [("c3", 1 << 13, 6, 3), ("c2", 20_000, 5, 2), ("c4", 10_000, 9, 4), ("c1", 1000, 8, 8)])
+def test_forward_pass_on_smoothed_snapshots(name, n, T, life):
+    """The whole forward pass with the smoothing done on the device (rebuild, sliding-window sum, weighted
+    normalisation, X W, aggregation, M-transform) against the oracle: the expected smoothed snapshot is the sum of
+    the oracle's raw snapshots of the window, normalised by the weighted form of Eqn (1)."""
+    from helpers import assert_close, to_f64
+    from paper_2109_07893_amd.pipeline import SmoothedRunner, make_block
+    wl = WORKLOADS[name].scaled(n, T=T) if n != WORKLOADS[name].n else WORKLOADS[name]
+    T = min(T, wl.T)
+    blk = make_block(wl, DEV, gen_device="cpu", T=T)
+    runner = SmoothedRunner(blk, life, keep_all_z=True)
+    runner.run_resident(validate=True)
+    torch.cuda.synchronize()
+    assert int(runner.status.abs().sum()) == 0
+    raw = DynamicGraph(wl)
+    rp, ci = (x.numpy() for x in raw.csr())
+    snaps, zs = [(rp, ci)], []
+    ws = [to_f64(w) for w in blk.w]
+    for t in range(1, T + 1):
+        if t >= 2:
+            rp, ci = oracle.delta_apply(wl.n, rp, ci, *[x.numpy() for x in raw.advance()])
+            snaps.append((rp, ci))
+        s = snaps[max(0, t - life)] + (None,)
+        for other in snaps[max(0, t - life) + 1:t]:
+            s = oracle.csr_combine(wl.n, s, other, 1.0)
+        val = oracle.gcn_values_weighted(s[0], s[1], np.ones(s[1].size) if s[2] is None else s[2])
+        cur = to_f64(blk.x[t - 1])
+        for w in ws:
+            cur = oracle.spmm(s[0], s[1], oracle.xw(cur, w), relu=True, val=val)
+        zs.append(cur)
+    expect = np.stack(zs)
+    if wl.window:
+        expect = oracle.mproduct(expect, oracle.m_matrix(T, wl.window))
+    assert_close(to_f64(runner.z), expect, runner.z.dtype, f"{wl.name} smoothed forward", stores=blk.layers + (1 if wl.window else 0))
