@@ -284,9 +284,32 @@ def cdgcn_layer(args, wl, blk, dev):
     torch.cuda.synchronize()
     stages = {k: {"calls_per_step": c, "avg_ms": round(t / c, 4)} for k, (c, t) in layer.timer.totals().items()}
     edges = sum(blk.nnz)
-    return {"ms_per_step": ms, "value": edges / (ms * 1e-3), "unit": "edges/s", "hidden": hidden, "stages": stages,
-            "what": f"t=1..{blk.T}: rebuild (t>=2), row scale, Y0 = A~ X, Y1 = Y0 W, relu(Y0 o Y1), "
-                    "two gate products, LSTM cell"}
+    out = {"ms_per_step": ms, "value": edges / (ms * 1e-3), "unit": "edges/s", "hidden": hidden, "stages": stages,
+           "what": f"t=1..{blk.T}: rebuild (t>=2), row scale, Y0 = A~ X, Y1 = Y0 W, relu(Y0 o Y1), "
+                   "two gate products, LSTM cell"}
+    # training step of the same layer: forward keeping (h_t, c_t), backward recomputing each timestep
+    from paper_2109_07893_amd.cdgcn import CdgcnTrainer
+    del layer
+    torch.cuda.empty_cache()
+    tr = CdgcnTrainer(blk, blk.w[0], w_x, w_h, bias, hidden)
+    tr.load_first()
+    g_h = torch.randn((blk.T, blk.n, hidden), generator=gen, device=dev).to(dt)
+    tr.forward(); tr.backward(g_h)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        tr.forward(); tr.backward(g_h)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    tr.timer = StageTimer(dev)
+    tr.forward(); tr.backward(g_h)
+    torch.cuda.synchronize()
+    out["training_step"] = {"ms_per_step": ms, "value": edges / (ms * 1e-3), "unit": "edges/s",
+                            "stages": {k: {"calls_per_step": c, "avg_ms": round(t / c, 4)}
+                                       for k, (c, t) in tr.timer.totals().items()},
+                            "what": "forward (composed LSTM step, states kept) + backward (GCN operation and gate "
+                                    "pre-activations recomputed per timestep, reverse rebuilds); parameter gradients"}
+    return out
 
 
 def training_step(args, wl, blk, dev):

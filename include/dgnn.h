@@ -371,6 +371,42 @@ int dgnn_lstm_step(const void *y, int32_t f_y, const void *h_prev, const void *w
                    const float *bias, void *c, void *h_next, int64_t n, int32_t hidden, dgnn_dtype dt,
                    void *stream);
 
+/*
+ * ---- Gradient propagation through the CD-GCN layer (Section "CD-GCN"; trained as in Section "Gradient
+ * Checkpoint": the forward values of a timestep are recomputed when its gradients are formed) ----
+ *
+ * LSTM cell: from the gradient with respect to the new state to the gradient with respect to the gate
+ * pre-activations and the old cell state.  gates_x, gates_h [n, 4*hidden] and bias as in dgnn_lstm_cell (recomputed
+ * by the caller), c_prev [n, hidden] the cell state the step started from.
+ *   dL/dh_t = dh_a + dh_b (either may be NULL: the loss's own gradient and the one carried back from step t+1),
+ *   dL/dc_t = dc_next (NULL = zero).  At least one of the three must be given.
+ *   da [n, 4*hidden]: dL/d(pre-activations), gate order (input, forget, cell, output); dc_prev [n, hidden]: dL/dc_{t-1}
+ *   (may be the same buffer as dc_next).  The other gradients are the dense transform's adjoints applied to da:
+ *   dW_x = Y^T da and dW_h = h_{t-1}^T da (dgnn_weight_grad), dY = da W_x^T and dh_{t-1} = da W_h^T (dgnn_input_grad),
+ *   db = column sums of da (dgnn_bias_grad).
+ * Errors: NULL, SHAPE (hidden not a feature width), OVERFLOW, ALIGN, ALIAS.
+ */
+int dgnn_lstm_cell_backward(const void *gates_x, const void *gates_h, const float *bias, const void *c_prev,
+                            const void *dh_a, const void *dh_b, const void *dc_next, void *da, void *dc_prev,
+                            int64_t n, int32_t hidden, dgnn_dtype dt, void *stream);
+
+/*
+ * Adjoint of dgnn_concat_relu: dy, y [n, f0 + f1] (y = the forward output); d0 [n, f0] and d1 [n, f1] receive the
+ * two column blocks of dy where y > 0, zero elsewhere.  d0 may be NULL (the gradient with respect to Y0's own block
+ * is needed only when a layer lies below).  Errors as dgnn_concat_relu.
+ */
+int dgnn_concat_relu_backward(const void *dy, const void *y, void *d0, int32_t f0, void *d1, int32_t f1, int64_t n,
+                              dgnn_dtype dt, void *stream);
+
+/*
+ * db[c] (+)= sum over rows of g[r][c]: the gradient of a bias added to every row (fp32 sums of fp32 / bf16 rows, in
+ * a fixed order: results repeat bit for bit).  g [n, f]; f a power of two times 4 (fp32) or 8 (bf16), at most 512.
+ * ws: device scratch of at least dgnn_bias_grad_workspace(f) bytes.  accumulate != 0 adds to db.
+ */
+int dgnn_bias_grad_workspace(int32_t f, size_t *bytes);
+int dgnn_bias_grad(const void *g, int64_t n, int32_t f, float *db, int accumulate, dgnn_dtype dt, void *ws,
+                   size_t ws_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

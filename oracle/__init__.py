@@ -314,3 +314,36 @@ def csr_combine(n: int, s, a_in=None, alpha: float = 1.0, a_out=None, beta: floa
     rowptr = np.zeros(n + 1, dtype=np.int32)
     np.cumsum(np.bincount(uniq >> 32, minlength=n), out=rowptr[1:])
     return rowptr, (uniq & 0xffffffff).astype(np.int32), total
+
+
+def lstm_cell_backward(x, h, c, w_x, w_h, bias, d_h, d_c=None):
+    """Adjoint of lstm_cell: given dL/dh' (d_h) and dL/dc' (d_c, zero if None), returns
+    (d_a, d_x, d_h_prev, d_c_prev, d_w_x, d_w_h, d_b), d_a being dL/d(pre-activations) [n, 4 hid].
+    Chain rule on c' = sig(a_f) c + sig(a_i) tanh(a_g), h' = sig(a_o) tanh(c')."""
+    x, h, c = _a(x, np.float64), _a(h, np.float64), _a(c, np.float64)
+    w_x, w_h = _a(w_x, np.float64), _a(w_h, np.float64)
+    a = xw(x, w_x) + xw(h, w_h) + (0.0 if bias is None else _a(bias, np.float64)[None, :])
+    hid = c.shape[1]
+    ai, af, ag, ao = (a[:, q * hid:(q + 1) * hid] for q in range(4))
+    i, f, g, o = _sig(ai), _sig(af), np.tanh(ag), _sig(ao)
+    c2 = f * c + i * g
+    tc = np.tanh(c2)
+    d_h = _a(d_h, np.float64)
+    d_c2 = d_h * o * (1.0 - tc * tc) + (0.0 if d_c is None else _a(d_c, np.float64))
+    d_a = np.concatenate([d_c2 * g * i * (1.0 - i), d_c2 * c * f * (1.0 - f), d_c2 * i * (1.0 - g * g),
+                          d_h * tc * o * (1.0 - o)], axis=1)
+    return (d_a, input_grad(d_a, w_x), input_grad(d_a, w_h), d_c2 * f, weight_grad(x, d_a), weight_grad(h, d_a),
+            d_a.sum(axis=0))
+
+
+def cdgcn_gcn_backward(rowptr, colidx, x, w, d_y):
+    """Adjoint of cdgcn_gcn with respect to W and X: Y = relu(Y0 o Y1), Y0 = A~ X, Y1 = Y0 W.
+    Returns (d_w, d_x)."""
+    x, w, d_y = _a(x, np.float64), _a(w, np.float64), _a(d_y, np.float64)
+    f = x.shape[1]
+    y0 = spmm(rowptr, colidx, x)
+    y1 = xw(y0, w)
+    d_y = d_y * (np.concatenate([y0, y1], axis=1) > 0.0)
+    d_y0, d_y1 = d_y[:, :f], d_y[:, f:]
+    d_w = weight_grad(y0, d_y1)
+    return d_w, spmm_t(rowptr, colidx, d_y0 + input_grad(d_y1, w))

@@ -24,7 +24,7 @@ DGNN_H_PRESCALED = 2
 EXPORTS = (
     "dgnn_strerror", "dgnn_csr_dinv", "dgnn_delta_h2d", "dgnn_delta_rebuild_workspace",
     "dgnn_delta_rebuild", "dgnn_feature_transform", "dgnn_spmm_workspace", "dgnn_spmm", "dgnn_mproduct",
-    "dgnn_delta_rebuild_weighted", "dgnn_spmm_weighted", "dgnn_csr_combine_workspace", "dgnn_csr_combine", "dgnn_csr_weighted_dinv_workspace", "dgnn_csr_weighted_dinv", "dgnn_concat_relu", "dgnn_lstm_cell", "dgnn_lstm_step",
+    "dgnn_delta_rebuild_weighted", "dgnn_spmm_weighted", "dgnn_csr_combine_workspace", "dgnn_csr_combine", "dgnn_csr_weighted_dinv_workspace", "dgnn_csr_weighted_dinv", "dgnn_concat_relu", "dgnn_lstm_cell", "dgnn_lstm_step", "dgnn_lstm_cell_backward", "dgnn_concat_relu_backward", "dgnn_bias_grad_workspace", "dgnn_bias_grad",
     "dgnn_mproduct_backward", "dgnn_mproduct_block", "dgnn_mproduct_backward_block", "dgnn_relu_backward", "dgnn_weight_grad_workspace", "dgnn_weight_grad", "dgnn_input_grad",
 )
 
@@ -109,6 +109,10 @@ def load_library():
     lib.dgnn_csr_weighted_dinv.argtypes = [_i64, _i64, _vp, _vp, _vp, _vp, _sz, _vp]
     lib.dgnn_concat_relu.argtypes = [_vp, _i32, _vp, _i32, _vp, _i64, ctypes.c_int, _vp]
     lib.dgnn_lstm_cell.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _i32, ctypes.c_int, _vp]
+    lib.dgnn_lstm_cell_backward.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i32, ctypes.c_int, _vp]
+    lib.dgnn_concat_relu_backward.argtypes = [_vp, _vp, _vp, _i32, _vp, _i32, _i64, ctypes.c_int, _vp]
+    lib.dgnn_bias_grad_workspace.argtypes = [_i32, ctypes.POINTER(_sz)]
+    lib.dgnn_bias_grad.argtypes = [_vp, _i64, _i32, _vp, ctypes.c_int, ctypes.c_int, _vp, _sz, _vp]
     lib.dgnn_lstm_step.argtypes = [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i32, ctypes.c_int, _vp]
     lib.dgnn_mproduct_block.argtypes = [_vp, _vp, _i64, _i64, _i32, _i32, _vp, _i64, _vp, _i64, ctypes.c_int, _vp]
     lib.dgnn_mproduct_backward_block.argtypes = [_vp, _vp, _i64, _i64, _i32, _i32, _vp, _i64, _vp, _i64, ctypes.c_int, _vp]
@@ -364,6 +368,52 @@ def lstm_cell(gates_x, gates_h, bias, c_prev, c_next, h_next) -> None:
             raise ValueError("bias must have 4 * hidden entries")
     _check(load_library().dgnn_lstm_cell(_ptr(gates_x), _ptr(gates_h), _ptr(bias), _ptr(c_prev), _ptr(c_next), _ptr(h_next),
                                          n, hidden, dt, _stream(gates_x)), "dgnn_lstm_cell")
+
+
+def lstm_cell_backward(gates_x, gates_h, bias, c_prev, dh_a, dh_b, dc_next, da, dc_prev) -> None:
+    """Gradient of one LSTM step with respect to the gate pre-activations (da) and the old cell state (dc_prev)."""
+    dt = _dtype_code(gates_x)
+    n, hidden = c_prev.shape
+    for t in (gates_x, gates_h, da):
+        if tuple(t.shape) != (n, 4 * hidden) or t.dtype != gates_x.dtype:
+            raise ValueError("gate tensors must be [n, 4 * hidden]")
+    for t in (c_prev, dh_a, dh_b, dc_next, dc_prev):
+        if t is not None and (tuple(t.shape) != (n, hidden) or t.dtype != gates_x.dtype):
+            raise ValueError("state tensors must be [n, hidden]")
+    if bias is not None:
+        _need(bias, torch.float32, "bias")
+    _check(load_library().dgnn_lstm_cell_backward(_ptr(gates_x), _ptr(gates_h), _ptr(bias), _ptr(c_prev), _ptr(dh_a), _ptr(dh_b),
+                                                  _ptr(dc_next), _ptr(da), _ptr(dc_prev), n, hidden, dt, _stream(gates_x)),
+           "dgnn_lstm_cell_backward")
+
+
+def concat_relu_backward(dy: torch.Tensor, y: torch.Tensor, d0: Optional[torch.Tensor], d1: torch.Tensor, f0: int) -> None:
+    """d0 o d1 = dy where y > 0 (the adjoint of concat_relu); d0 may be None."""
+    dt = _dtype_code(dy)
+    n, ftot = dy.shape
+    f1 = ftot - f0
+    if tuple(y.shape) != (n, ftot) or tuple(d1.shape) != (n, f1) or y.dtype != dy.dtype or d1.dtype != dy.dtype or \
+            (d0 is not None and (tuple(d0.shape) != (n, f0) or d0.dtype != dy.dtype)):
+        raise ValueError("shape mismatch in concat_relu_backward")
+    _check(load_library().dgnn_concat_relu_backward(_ptr(dy), _ptr(y), _ptr(d0), f0, _ptr(d1), f1, n, dt, _stream(dy)),
+           "dgnn_concat_relu_backward")
+
+
+def bias_grad_workspace(f: int) -> int:
+    out = _sz(0)
+    _check(load_library().dgnn_bias_grad_workspace(f, ctypes.byref(out)), "dgnn_bias_grad_workspace")
+    return int(out.value)
+
+
+def bias_grad(g: torch.Tensor, db: torch.Tensor, ws: torch.Tensor, accumulate: bool = False) -> None:
+    """db (+)= column sums of g."""
+    dt = _dtype_code(g)
+    n, f = g.shape
+    _need(db, torch.float32, "db")
+    if db.numel() != f:
+        raise ValueError("db must have one entry per column of g")
+    _check(load_library().dgnn_bias_grad(_ptr(g), n, f, _ptr(db), int(accumulate), dt, _ptr(ws), ws.numel() * ws.element_size(),
+                                         _stream(g)), "dgnn_bias_grad")
 
 
 def lstm_step_supported(y: torch.Tensor, hidden: int) -> bool:

@@ -74,3 +74,103 @@ class CdgcnLayer(BlockRunner):
                 self.rebuild(t, blk.deltas[t - 2])
             self.step(t)
         return self.h_all
+
+
+class CdgcnTrainer(CdgcnLayer):
+    """Forward and backward over one block for the CD-GCN layer (Section "CD-GCN", trained as in Section "Gradient
+    Checkpoint": the forward pass keeps only the LSTM states (h_t, c_t) of every timestep; the backward pass walks
+    the snapshots in reverse (rebuilds with the two lists exchanged) and recomputes each timestep's GCN operation
+    and gate pre-activations before taking their adjoints):
+
+        t = T..1:  recompute Y0, Y1, Y, a_x = Y W_x, a_h = h_{t-1} W_h
+                   (da, dc_{t-1}) <- LSTM cell backward of (G_t + dh_t, dc_t)        dgnn_lstm_cell_backward
+                   dW_x += Y^T da, dW_h += h_{t-1}^T da, db += colsum(da)            dgnn_weight_grad, dgnn_bias_grad
+                   dY = da W_x^T, dh_{t-1} = da W_h^T                                dgnn_input_grad
+                   dY1 = (dY where Y > 0)[:, F:]                                     dgnn_concat_relu_backward
+                   dW += Y0^T dY1                                                    dgnn_weight_grad
+
+    Gradients with respect to the layer's parameters (fp32): dw, dw_x, dw_h, db.  The input features are leaves."""
+
+    def __init__(self, blk: BlockInputs, w, w_x, w_h, bias, hidden: int, fused: bool = True):
+        super().__init__(blk, w, w_x, w_h, bias, hidden, fused)
+        n, f, T = blk.n, blk.f, blk.T
+        f_out = w.shape[1]
+        dt, dev = blk.x[0].dtype, self.dev
+        self.c_all = torch.zeros((T + 1, n, hidden), dtype=dt, device=dev)     # c_0 = 0, c_t after step t
+        self.da = torch.empty((n, 4 * hidden), dtype=dt, device=dev)
+        self.dy = torch.empty((n, f + f_out), dtype=dt, device=dev)
+        self.dy1 = torch.empty((n, f_out), dtype=dt, device=dev)
+        self.dh = torch.empty((n, hidden), dtype=dt, device=dev)
+        self.dc = torch.empty((n, hidden), dtype=dt, device=dev)
+        self.dw = torch.zeros((f, f_out), dtype=torch.float32, device=dev)
+        self.dw_x = torch.zeros((f + f_out, 4 * hidden), dtype=torch.float32, device=dev)
+        self.dw_h = torch.zeros((hidden, 4 * hidden), dtype=torch.float32, device=dev)
+        self.db = torch.zeros(4 * hidden, dtype=torch.float32, device=dev)
+        need = max(B.weight_grad_workspace(f + f_out, 4 * hidden), B.weight_grad_workspace(hidden, 4 * hidden),
+                   B.weight_grad_workspace(f, f_out))
+        self.ws_wgrad = torch.empty(need, dtype=torch.uint8, device=dev)
+        self.ws_bias = torch.empty(B.bias_grad_workspace(4 * hidden), dtype=torch.uint8, device=dev)
+
+    def _gcn(self, t: int) -> None:
+        """Y0, Y1 and Y of timestep t (A_t resident in its slot)."""
+        blk = self.blk
+        slot = self.slot_of(t)
+        with self._stage("row_scale"):
+            B.feature_transform(blk.x[t - 1], self.eye, self.xs, row_scale=self.dinv[slot])
+        with self._stage("spmm"):
+            B.spmm(self.rowptr[slot], self.colidx[slot], blk.nnz[t - 1], self.dinv[slot], self.xs, self.y0, self.ws_spmm,
+                   flags=B.DGNN_H_PRESCALED)
+        with self._stage("feature_transform"):
+            B.feature_transform(self.y0, self.w, self.y1)
+        with self._stage("concat_relu"):
+            B.concat_relu(self.y0, self.y1, self.y)
+
+    def forward(self) -> torch.Tensor:
+        blk = self.blk
+        self.c_all[0].zero_()
+        for t in range(1, blk.T + 1):
+            if t >= 2:
+                self.rebuild(t, blk.deltas[t - 2])
+            self._gcn(t)
+            h_prev = self.h0 if t == 1 else self.h_all[t - 2]
+            with self._stage("feature_transform"):
+                B.feature_transform(self.y, self.w_x, self.gx)
+                B.feature_transform(h_prev, self.w_h, self.gh)
+            with self._stage("lstm_cell"):
+                B.lstm_cell(self.gx, self.gh, self.bias, self.c_all[t - 1], self.c_all[t], self.h_all[t - 1])
+        return self.h_all
+
+    def backward(self, g_h: torch.Tensor) -> None:
+        """g_h [T, n, hidden] = dL/dh_t.  Must follow forward() (A_T resident)."""
+        blk = self.blk
+        T = blk.T
+        first = True
+        for t in range(T, 0, -1):
+            self._gcn(t)
+            h_prev = self.h0 if t == 1 else self.h_all[t - 2]
+            with self._stage("feature_transform"):
+                B.feature_transform(self.y, self.w_x, self.gx)
+                B.feature_transform(h_prev, self.w_h, self.gh)
+            with self._stage("lstm_cell_backward"):
+                B.lstm_cell_backward(self.gx, self.gh, self.bias, self.c_all[t - 1], g_h[t - 1], None if t == T else self.dh,
+                                     None if t == T else self.dc, self.da, self.dc)
+            with self._stage("weight_grad"):
+                B.weight_grad(self.y, self.da, self.dw_x, self.ws_wgrad, accumulate=not first)
+                B.weight_grad(h_prev, self.da, self.dw_h, self.ws_wgrad, accumulate=not first)
+            with self._stage("bias_grad"):
+                B.bias_grad(self.da, self.db, self.ws_bias, accumulate=not first)
+            with self._stage("input_grad"):
+                B.input_grad(self.da, self.w_x, self.dy)
+                if t >= 2:
+                    B.input_grad(self.da, self.w_h, self.dh)
+            with self._stage("concat_relu_backward"):
+                B.concat_relu_backward(self.dy, self.y, None, self.dy1, blk.f)
+            with self._stage("weight_grad"):
+                B.weight_grad(self.y0, self.dy1, self.dw, self.ws_wgrad, accumulate=not first)
+            first = False
+            if t >= 3:      # A_{t-1} from A_t: the same rebuild with the two lists exchanged (A_1 was kept)
+                ar, ac, dr, dc = blk.deltas[t - 2]
+                src, dst = self.slot_of(t), self.slot_of(t - 1)
+                with self._stage("delta_rebuild"):
+                    B.delta_rebuild(self.rowptr[src], self.colidx[src], blk.nnz[t - 1], dr, dc, int(dr.numel()), ar, ac,
+                                    int(ar.numel()), self.rowptr[dst], self.colidx[dst], self.dinv[dst], self.ws_rebuild)

@@ -235,3 +235,26 @@ def test_csr_combine_argument_errors(lib):
     b = ctypes.c_size_t(0)
     assert lib.dgnn_csr_combine_workspace(1 << 20, ctypes.byref(b)) == 0 and b.value >= 4 * ((1 << 10) + 1)
     assert lib.dgnn_csr_combine_workspace(-1, ctypes.byref(b)) == -2
+
+
+def test_cdgcn_backward_argument_errors(lib):
+    f = lib.dgnn_lstm_cell_backward
+    a = [FAKE + 4096 * k for k in range(9)]
+    assert f(None, a[1], None, a[3], a[4], None, None, a[7], a[8], 10, 32, 0, None) == -1
+    assert f(a[0], a[1], None, a[3], None, None, None, a[7], a[8], 10, 32, 0, None) == -1        # no gradient arrives
+    assert f(a[0], a[1], None, a[3], a[4], None, None, a[7], a[8], 10, 24, 0, None) == -2
+    assert f(a[0], a[1], None, a[3], a[4], None, None, a[7], a[8], 10, 32, 5, None) == -2
+    assert f(a[0], a[1], None, a[3], a[4], None, None, a[7], a[7], 10, 32, 0, None) == -5
+    assert f(a[0], a[1], None, a[3], a[4], None, None, a[7], a[4], 10, 32, 0, None) == -5
+    assert f(a[0], a[1], None, a[3], a[4] + 4, None, None, a[7], a[8], 10, 32, 0, None) == -7
+    f = lib.dgnn_concat_relu_backward
+    assert f(a[0], a[1], None, 32, None, 32, 10, 0, None) == -1
+    assert f(a[0], a[1], None, 32, a[3], 20, 10, 0, None) == -2
+    assert f(a[0], a[1], a[0], 32, a[3], 32, 10, 0, None) == -5
+    f = lib.dgnn_bias_grad
+    assert f(a[0], 10, 128, None, 0, 0, a[2], 1 << 20, None) == -1
+    assert f(a[0], 10, 24, a[1], 0, 0, a[2], 1 << 20, None) == -2            # 6 pieces per row: not a power of two
+    assert f(a[0], 10, 1024, a[1], 0, 0, a[2], 1 << 22, None) == -2
+    assert f(a[0], 10, 128, a[1], 0, 0, a[2], 1024, None) == -3
+    b = ctypes.c_size_t(0)
+    assert lib.dgnn_bias_grad_workspace(128, ctypes.byref(b)) == 0 and b.value == 1024 * 128 * 4

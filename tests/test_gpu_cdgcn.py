@@ -114,3 +114,104 @@ def test_fused_and_composed_layers_agree():
         layer.load_first()
         outs.append(layer.run().clone())
     assert_close(to_f64(outs[0]), to_f64(outs[1]), torch.float32, "fused vs composed layer")
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("hidden", [16, 32, 128])
+@pytest.mark.parametrize("carried", [False, True])
+def test_lstm_cell_backward(dtype, hidden, carried):
+    n = 1003
+    gx, gh = randn((n, 4 * hidden), 1, dtype), randn((n, 4 * hidden), 2, dtype)
+    bias = randn((4 * hidden,), 3) * 0.1
+    c_prev, g_h = randn((n, hidden), 4, dtype), randn((n, hidden), 5, dtype)
+    dh_c, dc_n = (randn((n, hidden), 6, dtype), randn((n, hidden), 7, dtype)) if carried else (None, None)
+    da = torch.full((n, 4 * hidden), float("nan"), dtype=dtype, device=DEV)
+    dc = dc_n.to(DEV) if carried else torch.full((n, hidden), float("nan"), dtype=dtype, device=DEV)
+    dg.lstm_cell_backward(gx.to(DEV), gh.to(DEV), bias.to(DEV), c_prev.to(DEV), g_h.to(DEV), dh_c.to(DEV) if carried else None,
+                          dc if carried else None, da, dc)            # dc_prev written over dc_next
+    # the oracle's cell takes x W_x + h W_h + b: feed it the pre-activations through identity weights
+    eye = np.eye(4 * hidden)
+    dh = to_f64(g_h) + (to_f64(dh_c) if carried else 0.0)
+    want = oracle.lstm_cell_backward(to_f64(gx) + to_f64(gh), np.zeros((n, 4 * hidden)), to_f64(c_prev), eye, eye, to_f64(bias),
+                                     dh, to_f64(dc_n) if carried else None)
+    assert_close(to_f64(da), want[0], dtype, "dL/d(pre-activations)")
+    assert_close(to_f64(dc), want[3], dtype, "dL/dc_prev")
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("f0,f1", [(16, 16), (32, 128), (128, 64)])
+def test_concat_relu_backward(dtype, f0, f1):
+    n = 601
+    dy, y = randn((n, f0 + f1), 1, dtype), randn((n, f0 + f1), 2, dtype)
+    d0 = torch.full((n, f0), float("nan"), dtype=dtype, device=DEV)
+    d1 = torch.full((n, f1), float("nan"), dtype=dtype, device=DEV)
+    dg.concat_relu_backward(dy.to(DEV), y.to(DEV), d0, d1, f0)
+    want = to_f64(dy) * (to_f64(y) > 0)
+    assert np.array_equal(to_f64(d0), want[:, :f0]) and np.array_equal(to_f64(d1), want[:, f0:])     # a copy under a mask: exact
+    d1.fill_(float("nan"))
+    dg.concat_relu_backward(dy.to(DEV), y.to(DEV), None, d1, f0)
+    assert np.array_equal(to_f64(d1), want[:, f0:])
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("f,n", [(128, 100_003), (64, 7), (16, 5000), (512, 3001)])
+def test_bias_grad(dtype, f, n):
+    g = randn((n, f), f + n, dtype)
+    db = torch.full((f,), float("nan"), device=DEV)
+    ws = torch.empty(dg.bias_grad_workspace(f), dtype=torch.uint8, device=DEV)
+    dg.bias_grad(g.to(DEV), db, ws)
+    want = to_f64(g).sum(axis=0)
+    first = db.clone()
+    np.testing.assert_allclose(to_f64(db), want, rtol=1e-5, atol=1e-5 * np.sqrt(n))
+    dg.bias_grad(g.to(DEV), db, ws, accumulate=True)
+    np.testing.assert_allclose(to_f64(db), 2 * want, rtol=1e-5, atol=2e-5 * np.sqrt(n))
+    dg.bias_grad(g.to(DEV), db, ws)
+    assert torch.equal(db, first)                     # fixed order of summation
+
+
+@pytest.mark.parametrize("case", ["undirected_f32", "directed_f32"])
+def test_cdgcn_training_step(case):
+    """Gradients of sum_t <G_t, h_t> with respect to W, W_x, W_h and b over a block, against the oracle's backward
+    pass (itself pinned by finite differences); the ReLU mask is taken on fp32 values on the device and fp64 in
+    the oracle, which agree except for outputs within rounding of zero (none at these sizes would move a gradient
+    beyond the tolerance)."""
+    from paper_2109_07893_amd.cdgcn import CdgcnTrainer
+    wl = {"undirected_f32": replace(WORKLOADS["c1"], f=32, window=0, name="cd-c1"),
+          "directed_f32": replace(WORKLOADS["c3"].scaled(4096, T=5), name="cd-c3")}[case]
+    f, hidden, T = wl.f, 32, wl.T
+    w = glorot_weight(wl, 0)
+    w_x = randn((2 * f, 4 * hidden), 11) / np.sqrt(2 * f)
+    w_h = randn((hidden, 4 * hidden), 12) / np.sqrt(hidden)
+    bias = randn((4 * hidden,), 13) * 0.1
+    g_h = randn((T, wl.n, hidden), 14)
+    blk = make_block(wl, DEV, gen_device="cpu")
+    tr = CdgcnTrainer(blk, w.to(DEV), w_x.to(DEV), w_h.to(DEV), bias.to(DEV), hidden)
+    tr.load_first()
+    for _ in range(2):                                # a second step must not see leftovers of the first
+        tr.forward()
+        tr.backward(g_h.to(DEV))
+    torch.cuda.synchronize()
+    # oracle: forward keeping what the backward needs, then backward
+    g = DynamicGraph(wl)
+    rp, ci = (x.numpy() for x in g.csr())
+    snaps, ys, hs, cs = [], [], [np.zeros((wl.n, hidden))], [np.zeros((wl.n, hidden))]
+    W, WX, WH, Bv = to_f64(w), to_f64(w_x), to_f64(w_h), to_f64(bias)
+    for t in range(1, T + 1):
+        if t > 1:
+            rp, ci = oracle.delta_apply(wl.n, rp, ci, *[x.numpy() for x in g.advance()])
+        snaps.append((rp, ci))
+        ys.append(oracle.cdgcn_gcn(rp, ci, to_f64(features(wl, t)), W))
+        h, c = oracle.lstm_cell(ys[-1], hs[-1], cs[-1], WX, WH, Bv)
+        hs.append(h); cs.append(c)
+        assert_close(to_f64(tr.h_all[t - 1]), h, torch.float32, f"{case}: h_{t}")
+    d_w, d_wx, d_wh, d_b = 0.0, 0.0, 0.0, 0.0
+    dh, dc = 0.0, None
+    for t in range(T, 0, -1):
+        _, d_y, dh, dc, a, b, cgrad = oracle.lstm_cell_backward(ys[t - 1], hs[t - 1], cs[t - 1], WX, WH, Bv,
+                                                                to_f64(g_h[t - 1]) + dh, dc)
+        d_wx, d_wh, d_b = d_wx + a, d_wh + b, d_b + cgrad
+        d_w = d_w + oracle.cdgcn_gcn_backward(*snaps[t - 1], to_f64(features(wl, t)), W, d_y)[0]
+    for name, got, want in (("dW", tr.dw, d_w), ("dW_x", tr.dw_x, d_wx), ("dW_h", tr.dw_h, d_wh), ("db", tr.db, d_b)):
+        want = np.asarray(want)
+        err = np.abs(to_f64(got) - want).max()
+        assert err <= 2e-4 * np.abs(want).max(), f"{case} {name}: max err {err:.3e} against max |.| {np.abs(want).max():.3e}"

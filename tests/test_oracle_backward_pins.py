@@ -330,3 +330,50 @@ def test_sliding_window_sum_by_csr_combine_equals_the_windowed_sum():
         want = sum(_dense_unweighted(n, *snaps[i - 1]) for i in range(max(1, t - life + 1), t + 1))
         got = np.nan_to_num(_dense_weighted(n, *s), nan=0.0)
         np.testing.assert_array_equal(got, want)
+
+
+def _central(fun, arr, eps=1e-6):
+    """Central differences of the scalar fun() with respect to every entry of arr (changed in place, restored)."""
+    out = np.zeros_like(arr)
+    it = np.nditer(arr, flags=["multi_index"])
+    for _ in it:
+        k = it.multi_index
+        keep = arr[k]
+        arr[k] = keep + eps; up = fun()
+        arr[k] = keep - eps; dn = fun()
+        arr[k] = keep
+        out[k] = (up - dn) / (2 * eps)
+    return out
+
+
+def test_lstm_cell_backward_matches_finite_differences():
+    rng = np.random.default_rng(21)
+    n, fx, hid = 5, 6, 4
+    x, h, c = rng.normal(size=(n, fx)), rng.normal(size=(n, hid)), rng.normal(size=(n, hid))
+    w_x, w_h, b = rng.normal(size=(fx, 4 * hid)) / 2, rng.normal(size=(hid, 4 * hid)) / 2, rng.normal(size=4 * hid)
+    g_h, g_c = rng.normal(size=(n, hid)), rng.normal(size=(n, hid))
+
+    def loss():
+        h2, c2 = oracle.lstm_cell(x, h, c, w_x, w_h, b)
+        return float((g_h * h2).sum() + (g_c * c2).sum())
+
+    d_a, d_x, d_hp, d_cp, d_wx, d_wh, d_b = oracle.lstm_cell_backward(x, h, c, w_x, w_h, b, g_h, g_c)
+    for got, arr in ((d_x, x), (d_hp, h), (d_cp, c), (d_wx, w_x), (d_wh, w_h), (d_b, b)):
+        np.testing.assert_allclose(got, _central(loss, arr), rtol=1e-6, atol=1e-8)
+    # without an upstream dL/dc' the cell state still carries gradient through h'
+    g_c[:] = 0.0
+    got = oracle.lstm_cell_backward(x, h, c, w_x, w_h, b, g_h, None)
+    np.testing.assert_allclose(got[3], _central(loss, c), rtol=1e-6, atol=1e-8)
+
+
+def test_cdgcn_gcn_backward_matches_finite_differences():
+    n, f, f2 = 12, 3, 4
+    a, rp, ci, rng = _graph(n, 0.3, 77, False)
+    x, w, g = rng.normal(size=(n, f)), rng.normal(size=(f, f2)), rng.normal(size=(n, f + f2))
+
+    def loss():
+        return float((g * oracle.cdgcn_gcn(rp, ci, x, w)).sum())
+
+    d_w, d_x = oracle.cdgcn_gcn_backward(rp, ci, x, w, g)
+    np.testing.assert_allclose(d_w, _central(loss, w), rtol=1e-6, atol=1e-8)
+    np.testing.assert_allclose(d_x, _central(loss, x), rtol=1e-6, atol=1e-8)
