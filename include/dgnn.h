@@ -407,6 +407,12 @@ int dgnn_bias_grad_workspace(int32_t f, size_t *bytes);
 int dgnn_bias_grad(const void *g, int64_t n, int32_t f, float *db, int accumulate, dgnn_dtype dt, void *ws,
                    size_t ws_bytes, void *stream);
 
+/*
+ * out = a + b for [n, f] tensors of one storage type (the sum is formed in fp32 and rounded once): a gradient that
+ * reaches a tensor along two paths.  out may be a or b.  f a feature width.  Errors: NULL, SHAPE, OVERFLOW, ALIGN.
+ */
+int dgnn_add(const void *a, const void *b, void *out, int64_t n, int32_t f, dgnn_dtype dt, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -347,3 +347,29 @@ def cdgcn_gcn_backward(rowptr, colidx, x, w, d_y):
     d_y0, d_y1 = d_y[:, :f], d_y[:, f:]
     d_w = weight_grad(y0, d_y1)
     return d_w, spmm_t(rowptr, colidx, d_y0 + input_grad(d_y1, w))
+
+
+def evolve_weights(w0, u_x, u_h, bias, T: int):
+    """Section "EvolveGCN": W_t = LSTM(W_{t-1}), read as the EGCN-O variant it names: the weight matrix is the
+    LSTM's input and its hidden state (rows = batch), with a cell state C of the same shape, C_0 = 0.
+    Returns ([W_1 .. W_T], [C_0 .. C_T])."""
+    ws, cs = [_a(w0, np.float64)], [np.zeros(np.shape(w0))]
+    for _ in range(T):
+        w, c = lstm_cell(ws[-1], ws[-1], cs[-1], u_x, u_h, bias)
+        ws.append(w); cs.append(c)
+    return ws[1:], cs
+
+
+def evolve_weights_backward(w0, u_x, u_h, bias, d_w):
+    """Adjoint of evolve_weights for L = sum_t <d_w[t-1], W_t>: (dU_x, dU_h, db, dW_0)."""
+    T = len(d_w)
+    ws, cs = evolve_weights(w0, u_x, u_h, bias, T)
+    ws = [_a(w0, np.float64)] + ws
+    d_ux = d_uh = d_b = 0.0
+    carry, d_c = 0.0, None
+    for t in range(T, 0, -1):
+        _, d_x, d_hp, d_c, a, b, g = lstm_cell_backward(ws[t - 1], ws[t - 1], cs[t - 1], u_x, u_h, bias,
+                                                       _a(d_w[t - 1], np.float64) + carry, d_c)
+        d_ux, d_uh, d_b = d_ux + a, d_uh + b, d_b + g
+        carry = d_x + d_hp                    # W_{t-1} is input and hidden state at once
+    return d_ux, d_uh, d_b, carry

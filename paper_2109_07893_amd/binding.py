@@ -24,7 +24,7 @@ DGNN_H_PRESCALED = 2
 EXPORTS = (
     "dgnn_strerror", "dgnn_csr_dinv", "dgnn_delta_h2d", "dgnn_delta_rebuild_workspace",
     "dgnn_delta_rebuild", "dgnn_feature_transform", "dgnn_spmm_workspace", "dgnn_spmm", "dgnn_mproduct",
-    "dgnn_delta_rebuild_weighted", "dgnn_spmm_weighted", "dgnn_csr_combine_workspace", "dgnn_csr_combine", "dgnn_csr_weighted_dinv_workspace", "dgnn_csr_weighted_dinv", "dgnn_concat_relu", "dgnn_lstm_cell", "dgnn_lstm_step", "dgnn_lstm_cell_backward", "dgnn_concat_relu_backward", "dgnn_bias_grad_workspace", "dgnn_bias_grad",
+    "dgnn_delta_rebuild_weighted", "dgnn_spmm_weighted", "dgnn_csr_combine_workspace", "dgnn_csr_combine", "dgnn_csr_weighted_dinv_workspace", "dgnn_csr_weighted_dinv", "dgnn_concat_relu", "dgnn_lstm_cell", "dgnn_lstm_step", "dgnn_lstm_cell_backward", "dgnn_concat_relu_backward", "dgnn_bias_grad_workspace", "dgnn_bias_grad", "dgnn_add",
     "dgnn_mproduct_backward", "dgnn_mproduct_block", "dgnn_mproduct_backward_block", "dgnn_relu_backward", "dgnn_weight_grad_workspace", "dgnn_weight_grad", "dgnn_input_grad",
 )
 
@@ -113,6 +113,7 @@ def load_library():
     lib.dgnn_concat_relu_backward.argtypes = [_vp, _vp, _vp, _i32, _vp, _i32, _i64, ctypes.c_int, _vp]
     lib.dgnn_bias_grad_workspace.argtypes = [_i32, ctypes.POINTER(_sz)]
     lib.dgnn_bias_grad.argtypes = [_vp, _i64, _i32, _vp, ctypes.c_int, ctypes.c_int, _vp, _sz, _vp]
+    lib.dgnn_add.argtypes = [_vp, _vp, _vp, _i64, _i32, ctypes.c_int, _vp]
     lib.dgnn_lstm_step.argtypes = [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i32, ctypes.c_int, _vp]
     lib.dgnn_mproduct_block.argtypes = [_vp, _vp, _i64, _i64, _i32, _i32, _vp, _i64, _vp, _i64, ctypes.c_int, _vp]
     lib.dgnn_mproduct_backward_block.argtypes = [_vp, _vp, _i64, _i64, _i32, _i32, _vp, _i64, _vp, _i64, ctypes.c_int, _vp]
@@ -414,6 +415,15 @@ def bias_grad(g: torch.Tensor, db: torch.Tensor, ws: torch.Tensor, accumulate: b
         raise ValueError("db must have one entry per column of g")
     _check(load_library().dgnn_bias_grad(_ptr(g), n, f, _ptr(db), int(accumulate), dt, _ptr(ws), ws.numel() * ws.element_size(),
                                          _stream(g)), "dgnn_bias_grad")
+
+
+def add(a: torch.Tensor, b: torch.Tensor, out: torch.Tensor) -> None:
+    """out = a + b (out may be a or b)."""
+    dt = _dtype_code(a)
+    n, f = a.shape
+    if tuple(b.shape) != (n, f) or tuple(out.shape) != (n, f) or b.dtype != a.dtype or out.dtype != a.dtype:
+        raise ValueError("shape mismatch in add")
+    _check(load_library().dgnn_add(_ptr(a), _ptr(b), _ptr(out), n, f, dt, _stream(a)), "dgnn_add")
 
 
 def lstm_step_supported(y: torch.Tensor, hidden: int) -> bool:

@@ -152,6 +152,20 @@ __global__ __launch_bounds__(kThreads) void column_sum_kernel(const uintx4 *__re
     }
 }
 
+// out = a + b, piece by piece (a gradient that reaches a tensor along two paths)
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void add_kernel(const uintx4 *a, const uintx4 *b, uintx4 *out, int64_t pieces) {
+    constexpr int NV = Pack<BF16>::kVals;
+    const int64_t p = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (p >= pieces) return;
+    float x[NV], y[NV];
+    Pack<BF16>::unpack(x, a[p]);
+    Pack<BF16>::unpack(y, b[p]);
+#pragma unroll
+    for (int e = 0; e < NV; ++e) x[e] += y[e];
+    out[p] = Pack<BF16>::pack(x);
+}
+
 // second stage: db[c] (+)= sum over workgroups, in workgroup order
 __global__ __launch_bounds__(kThreads) void column_sum_reduce_kernel(const float *__restrict__ partial, int blocks, int f,
                                                                      float *__restrict__ db, int accumulate) {
@@ -245,6 +259,25 @@ extern "C" int dgnn_bias_grad(const void *g, int64_t n, int32_t f, float *db, in
     DGNN_RETURN_IF_LAUNCH_FAILED();
     hipLaunchKernelGGL(column_sum_reduce_kernel, dim3((f + kThreads - 1) / kThreads), dim3(kThreads), 0, st, (const float *)ws,
                        blocks, f, db, accumulate);
+    DGNN_RETURN_IF_LAUNCH_FAILED();
+    return DGNN_OK;
+}
+
+extern "C" int dgnn_add(const void *a, const void *b, void *out, int64_t n, int32_t f, dgnn_dtype dt, void *stream) {
+    if (!a || !b || !out) return DGNN_ERR_NULL;
+    if (n <= 0 || !supported_width(f)) return DGNN_ERR_SHAPE;
+    if (dt != DGNN_F32 && dt != DGNN_BF16) return DGNN_ERR_SHAPE;
+    if (!fits_index(n)) return DGNN_ERR_OVERFLOW;
+    if (!aligned16(a) || !aligned16(b) || !aligned16(out)) return DGNN_ERR_ALIGN;
+    const int64_t pieces = n * (f * (dt == DGNN_F32 ? 4 : 2) / 16);
+    const unsigned blocks = (unsigned)((pieces + kThreads - 1) / kThreads);
+    hipStream_t st = (hipStream_t)stream;
+    if (dt == DGNN_BF16)
+        hipLaunchKernelGGL(add_kernel<true>, dim3(blocks), dim3(kThreads), 0, st, static_cast<const uintx4 *>(a),
+                           static_cast<const uintx4 *>(b), static_cast<uintx4 *>(out), pieces);
+    else
+        hipLaunchKernelGGL(add_kernel<false>, dim3(blocks), dim3(kThreads), 0, st, static_cast<const uintx4 *>(a),
+                           static_cast<const uintx4 *>(b), static_cast<uintx4 *>(out), pieces);
     DGNN_RETURN_IF_LAUNCH_FAILED();
     return DGNN_OK;
 }

@@ -258,3 +258,10 @@ def test_cdgcn_backward_argument_errors(lib):
     assert f(a[0], 10, 128, a[1], 0, 0, a[2], 1024, None) == -3
     b = ctypes.c_size_t(0)
     assert lib.dgnn_bias_grad_workspace(128, ctypes.byref(b)) == 0 and b.value == 1024 * 128 * 4
+
+
+def test_add_argument_errors(lib):
+    f = lib.dgnn_add
+    assert f(None, FAKE, FAKE, 10, 32, 0, None) == -1
+    assert f(FAKE, FAKE, FAKE, 0, 32, 0, None) == -2 and f(FAKE, FAKE, FAKE, 10, 33, 0, None) == -2
+    assert f(FAKE, FAKE + 8, FAKE, 10, 32, 0, None) == -7

@@ -215,3 +215,13 @@ def test_cdgcn_training_step(case):
         want = np.asarray(want)
         err = np.abs(to_f64(got) - want).max()
         assert err <= 2e-4 * np.abs(want).max(), f"{case} {name}: max err {err:.3e} against max |.| {np.abs(want).max():.3e}"
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_add(dtype):
+    n, f = 999, 64
+    a, b = randn((n, f), 1, dtype), randn((n, f), 2, dtype)
+    out = a.to(DEV).clone()
+    dg.add(out, b.to(DEV), out)                          # in place
+    want = (a.to(torch.float32) + b.to(torch.float32)).to(dtype)
+    assert torch.equal(out.cpu(), want)                  # one fp32 sum, rounded once

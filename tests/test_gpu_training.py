@@ -208,3 +208,49 @@ def test_gradient_descent_on_the_weights_reduces_a_loss():
         blk.w = [(w - lr * dw).contiguous() for w, dw in zip(blk.w, tr.dw)]
     assert losses[-1] < 0.2 * losses[0], losses[::8]
     assert all(b <= a * 1.001 for a, b in zip(losses, losses[1:])), losses
+
+
+def test_evolving_weights_end_to_end():
+    """EvolveGCN (Section "EvolveGCN"): W_t = LSTM(W_{t-1}) produced on the device, used by the GCN steps of a
+    block, and the loss's gradient carried back through the GCN steps AND the weight recurrence to U_x, U_h, b and
+    W_0; against the oracle's chain (every link pinned by finite differences)."""
+    import oracle
+    from paper_2109_07893_amd.evolve import EvolvingWeights
+    wl = WORKLOADS["c3"].scaled(1 << 12, T=5)
+    T, f = wl.T, wl.f
+    gen = torch.Generator().manual_seed(5)
+    w0 = torch.randn((f, f), generator=gen) / np.sqrt(f)
+    u_x = torch.randn((f, 4 * f), generator=gen) / np.sqrt(f)
+    u_h = torch.randn((f, 4 * f), generator=gen) / np.sqrt(f)
+    bias = torch.randn(4 * f, generator=gen) * 0.1
+    ev = EvolvingWeights(w0.to(DEV), u_x.to(DEV), u_h.to(DEV), bias.to(DEV), T)
+    w_t = ev.forward()
+    blk = make_block(wl, DEV, gen_device="cpu")
+    blk.w_t = [[w] for w in w_t]
+    tr = make_trainer(wl, blk)
+    g_y = torch.randn((T, wl.n, f), generator=gen)
+    for _ in range(2):
+        ev.forward()
+        tr.forward()
+        tr.backward(g_y.to(DEV))
+        ev.backward([tr.dw_t[t][0] for t in range(T)])
+    torch.cuda.synchronize()
+    # oracle
+    W0, UX, UH, Bv = (to_f64(x) for x in (w0, u_x, u_h, bias))
+    ws, _ = oracle.evolve_weights(W0, UX, UH, Bv, T)
+    for t in range(T):
+        assert_close(to_f64(w_t[t]), ws[t], torch.float32, f"W_{t + 1}")
+    from dtdg_synth import DynamicGraph, features
+    g = DynamicGraph(wl)
+    rp, ci = (x.numpy() for x in g.csr())
+    d_w = []
+    for t in range(1, T + 1):
+        if t > 1:
+            rp, ci = oracle.delta_apply(wl.n, rp, ci, *[x.numpy() for x in g.advance()])
+        x = to_f64(features(wl, t))
+        z = oracle.gcn_layer(rp, ci, x, ws[t - 1], relu=True)
+        d_w.append(oracle.gcn_layer_backward(rp, ci, x, ws[t - 1], z, to_f64(g_y[t - 1]))[0])
+    want = oracle.evolve_weights_backward(W0, UX, UH, Bv, d_w)
+    for name, got, exp in (("dU_x", ev.du_x, want[0]), ("dU_h", ev.du_h, want[1]), ("db", ev.db, want[2]), ("dW_0", ev.dw0, want[3])):
+        err = np.abs(to_f64(got) - exp).max()
+        assert err <= 2e-4 * np.abs(exp).max(), f"{name}: max err {err:.3e} against max |.| {np.abs(exp).max():.3e}"

@@ -377,3 +377,23 @@ def test_cdgcn_gcn_backward_matches_finite_differences():
     d_w, d_x = oracle.cdgcn_gcn_backward(rp, ci, x, w, g)
     np.testing.assert_allclose(d_w, _central(loss, w), rtol=1e-6, atol=1e-8)
     np.testing.assert_allclose(d_x, _central(loss, x), rtol=1e-6, atol=1e-8)
+
+
+def test_evolving_weights_backward_matches_finite_differences():
+    rng = np.random.default_rng(31)
+    f, f2, T = 5, 3, 4
+    w0 = rng.normal(size=(f, f2))
+    u_x, u_h, b = rng.normal(size=(f2, 4 * f2)) / 2, rng.normal(size=(f2, 4 * f2)) / 2, rng.normal(size=4 * f2) / 4
+    g = [rng.normal(size=(f, f2)) for _ in range(T)]
+
+    def loss():
+        ws, _ = oracle.evolve_weights(w0, u_x, u_h, b, T)
+        return float(sum((gt * wt).sum() for gt, wt in zip(g, ws)))
+
+    d_ux, d_uh, d_b, d_w0 = oracle.evolve_weights_backward(w0, u_x, u_h, b, g)
+    for got, arr in ((d_ux, u_x), (d_uh, u_h), (d_b, b), (d_w0, w0)):
+        np.testing.assert_allclose(got, _central(loss, arr), rtol=1e-6, atol=1e-8)
+    # the first step alone is one LSTM cell with the weight as input and state
+    ws, cs = oracle.evolve_weights(w0, u_x, u_h, b, 1)
+    h, c = oracle.lstm_cell(w0, w0, np.zeros_like(w0), u_x, u_h, b)
+    assert np.array_equal(ws[0], h) and np.array_equal(cs[1], c)
