@@ -108,3 +108,71 @@ def test_a_planted_mistake_is_caught(tmp_path, name, good, bad):
     finally:
         oracle._lib = real
     assert caught is not None, f"no pin noticed: {name}"
+
+
+# ---- the same for the parts of the oracle written in Python (numpy) ---------------------------------------------
+PY_SRC = os.path.join(os.path.dirname(HERE), "oracle", "__init__.py")
+
+PY_MUTANTS = [
+    ("weighted normalisation uses the row sum twice", "return val / np.sqrt(d[rows] * d[colidx])", "return val / np.sqrt(d[rows] * d[rows])"),
+    ("weighted normalisation counts entries instead of adding values", "d = np.array([val[rowptr[u]:rowptr[u + 1]].sum() for u in range(n)])",
+     "d = np.array([float(rowptr[u + 1] - rowptr[u]) for u in range(n)])"),
+    ("combination keeps entries that cancel", "keep = total != 0.0", "keep = np.ones(total.size, dtype=bool)"),
+    ("combination ignores the weight of the removed snapshot", "wts.append(np.full(ci.size, float(scale)))", "wts.append(np.full(ci.size, abs(float(scale))))"),
+    ("combination forgets the values of S", "wts.append(np.ones(ci.size) if len(op) < 3 or op[2] is None else _a(op[2], np.float64))",
+     "wts.append(np.ones(ci.size))"),
+    ("LSTM: forget and input gates exchanged", "c2 = _sig(af) * c + _sig(ai) * np.tanh(ag)\n    return", "c2 = _sig(ai) * c + _sig(af) * np.tanh(ag)\n    return"),
+    ("LSTM backward: cell gradient without the carried part", "d_c2 = d_h * o * (1.0 - tc * tc) + (0.0 if d_c is None else _a(d_c, np.float64))",
+     "d_c2 = d_h * o * (1.0 - tc * tc)"),
+    ("LSTM backward: tanh derivative of the cell gate missing", "d_c2 * i * (1.0 - g * g)", "d_c2 * i"),
+    ("LSTM backward: output gate's gradient uses the cell state, not its tanh", "d_h * tc * o * (1.0 - o)", "d_h * c2 * o * (1.0 - o)"),
+    ("skip connection backward without the ReLU mask", "d_y = d_y * (np.concatenate([y0, y1], axis=1) > 0.0)", "d_y = d_y * 1.0"),
+    ("skip connection backward drops the path through Y1", "spmm_t(rowptr, colidx, d_y0 + input_grad(d_y1, w))", "spmm_t(rowptr, colidx, d_y0)"),
+    ("evolving weights: gradient reaches W through one product only", "carry = d_x + d_hp", "carry = d_hp"),
+]
+
+
+def py_pins():
+    calls = [bwd.test_weighted_normalisation_reduces_to_eqn_1_and_matches_the_dense_form, bwd.test_csr_combine_special_cases,
+             bwd.test_sliding_window_sum_by_csr_combine_equals_the_windowed_sum,
+             bwd.test_lstm_cell_backward_matches_finite_differences, bwd.test_cdgcn_gcn_backward_matches_finite_differences,
+             bwd.test_evolving_weights_backward_matches_finite_differences]
+    for seed in (0, 1, 2):
+        calls.append(lambda s=seed: bwd.test_csr_combine_matches_dense_matrices(s))
+    calls += [getattr(bwd, n) for n in dir(bwd) if n.startswith("test_lstm_cell_matches") or n.startswith("test_cdgcn_gcn_matches")]
+    return calls
+
+
+def py_first_failure():
+    for call in py_pins():
+        try:
+            call()
+        except Exception as exc:
+            return exc
+    return None
+
+
+def test_the_unmodified_python_oracle_passes_these_pins():
+    assert py_first_failure() is None
+
+
+@pytest.mark.parametrize("name,good,bad", PY_MUTANTS, ids=[m[0] for m in PY_MUTANTS])
+def test_a_planted_mistake_in_the_python_oracle_is_caught(name, good, bad):
+    import types
+    text = open(PY_SRC).read()
+    assert text.count(good) == 1, f"the oracle source no longer contains exactly one: {good}"
+    mutant = types.ModuleType("oracle_mutant")
+    mutant.__file__ = PY_SRC                              # it finds the same C library
+    mutant.__package__ = "oracle"
+    exec(compile(text.replace(good, bad), PY_SRC, "exec"), mutant.__dict__)
+    saved = {}
+    for attr, fn in vars(mutant).items():                 # the pins call oracle.<function>: hand them the mutant's
+        if callable(fn) and not attr.startswith("_") and hasattr(oracle, attr) and getattr(fn, "__module__", None) == "oracle_mutant":
+            saved[attr] = getattr(oracle, attr)
+            setattr(oracle, attr, fn)
+    try:
+        caught = py_first_failure()
+    finally:
+        for attr, fn in saved.items():
+            setattr(oracle, attr, fn)
+    assert caught is not None, f"no pin noticed: {name}"
