@@ -163,3 +163,27 @@ def test_forward_pass_on_smoothed_snapshots(name, n, T, life):
     if wl.window:
         expect = oracle.mproduct(expect, oracle.m_matrix(T, wl.window))
     assert_close(to_f64(runner.z), expect, runner.z.dtype, f"{wl.name} smoothed forward", stores=blk.layers + (1 if wl.window else 0))
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_combine_random_shapes(seed):
+    """Seeded random operand shapes: sizes, densities, hub rows, empty stretches, weights, presence of A_in / A_out."""
+    rng = np.random.default_rng(1000 + seed)
+    n = int(rng.integers(1, 3000))
+    dens = [float(rng.choice([0.0, 0.001, 0.01, 0.1])) * min(1.0, 300.0 / n) * 3 for _ in range(3)]
+
+    def operand(d):
+        hubs = tuple((int(rng.integers(0, n)), int(rng.integers(0, n + 1))) for _ in range(int(rng.integers(0, 4))))
+        rp, ci = random_csr(n, d, rng, hubs=hubs)
+        if rng.random() < 0.3 and n > 10:                 # a stretch of empty rows
+            a, b = sorted(rng.integers(0, n, 2))
+            keep = np.ones(ci.size, dtype=bool)
+            keep[rp[a]:rp[b]] = False
+            lens = np.diff(rp); lens[a:b] = 0
+            rp, ci = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32), ci[keep]
+        return rp, ci
+
+    s, a_in, a_out = operand(dens[0]), operand(dens[1]), operand(dens[2])
+    val = None if rng.random() < 0.3 else rng.integers(1, 5, s[1].size).astype(np.float64)
+    alpha, beta = float(rng.choice([1.0, 2.0, 0.5])), float(rng.choice([-1.0, -2.0, 1.0]))
+    check(n, s + (val,), a_in if rng.random() < 0.85 else None, alpha, a_out if rng.random() < 0.7 else None, beta, f"seed {seed}")
