@@ -91,11 +91,18 @@ class CdgcnTrainer(CdgcnLayer):
 
     Gradients with respect to the layer's parameters (fp32): dw, dw_x, dw_h, db.  The input features are leaves."""
 
-    def __init__(self, blk: BlockInputs, w, w_x, w_h, bias, hidden: int, fused: bool = True):
+    def __init__(self, blk: BlockInputs, w, w_x, w_h, bias, hidden: int, fused: bool = True, keep_activations: bool = False):
         super().__init__(blk, w, w_x, w_h, bias, hidden, fused)
         n, f, T = blk.n, blk.f, blk.T
         f_out = w.shape[1]
         dt, dev = blk.x[0].dtype, self.dev
+        # With keep_activations the forward pass also keeps Y0 and Y of every timestep (N x (2F + F') per step: 6.4 GB
+        # at c5's size, a matter of course in 288 GB) and the backward pass neither recomputes the GCN operation
+        # nor needs the snapshots again; without, only the LSTM states are kept, as gradient checkpointing has it.
+        self.keep = keep_activations
+        if keep_activations:
+            self.y0_all = torch.empty((T, n, f), dtype=dt, device=dev)
+            self.y_all = torch.empty((T, n, f + f_out), dtype=dt, device=dev)
         self.c_all = torch.zeros((T + 1, n, hidden), dtype=dt, device=dev)     # c_0 = 0, c_t after step t
         self.da = torch.empty((n, 4 * hidden), dtype=dt, device=dev)
         self.dy = torch.empty((n, f + f_out), dtype=dt, device=dev)
@@ -131,8 +138,15 @@ class CdgcnTrainer(CdgcnLayer):
         for t in range(1, blk.T + 1):
             if t >= 2:
                 self.rebuild(t, blk.deltas[t - 2])
+            if self.keep:
+                self.y0, self.y = self.y0_all[t - 1], self.y_all[t - 1]
             self._gcn(t)
             h_prev = self.h0 if t == 1 else self.h_all[t - 2]
+            if self.fused and B.lstm_step_supported(self.y, self.hidden):
+                with self._stage("lstm_step"):          # the fused step updates the cell state in place
+                    self.c_all[t].copy_(self.c_all[t - 1])
+                    B.lstm_step(self.y, h_prev, self.w_x, self.w_h, self.bias, self.c_all[t], self.h_all[t - 1])
+                continue
             with self._stage("feature_transform"):
                 B.feature_transform(self.y, self.w_x, self.gx)
                 B.feature_transform(h_prev, self.w_h, self.gh)
@@ -146,7 +160,10 @@ class CdgcnTrainer(CdgcnLayer):
         T = blk.T
         first = True
         for t in range(T, 0, -1):
-            self._gcn(t)
+            if self.keep:
+                self.y0, self.y = self.y0_all[t - 1], self.y_all[t - 1]
+            else:
+                self._gcn(t)
             h_prev = self.h0 if t == 1 else self.h_all[t - 2]
             with self._stage("feature_transform"):
                 B.feature_transform(self.y, self.w_x, self.gx)
@@ -168,7 +185,7 @@ class CdgcnTrainer(CdgcnLayer):
             with self._stage("weight_grad"):
                 B.weight_grad(self.y0, self.dy1, self.dw, self.ws_wgrad, accumulate=not first)
             first = False
-            if t >= 3:      # A_{t-1} from A_t: the same rebuild with the two lists exchanged (A_1 was kept)
+            if t >= 3 and not self.keep:      # A_{t-1} from A_t: the same rebuild with the two lists exchanged (A_1 was kept)
                 ar, ac, dr, dc = blk.deltas[t - 2]
                 src, dst = self.slot_of(t), self.slot_of(t - 1)
                 with self._stage("delta_rebuild"):

@@ -169,8 +169,9 @@ def test_bias_grad(dtype, f, n):
     assert torch.equal(db, first)                     # fixed order of summation
 
 
+@pytest.mark.parametrize("keep", [False, True])
 @pytest.mark.parametrize("case", ["undirected_f32", "directed_f32"])
-def test_cdgcn_training_step(case):
+def test_cdgcn_training_step(case, keep):
     """Gradients of sum_t <G_t, h_t> with respect to W, W_x, W_h and b over a block, against the oracle's backward
     pass (itself pinned by finite differences); the ReLU mask is taken on fp32 values on the device and fp64 in
     the oracle, which agree except for outputs within rounding of zero (none at these sizes would move a gradient
@@ -185,7 +186,7 @@ def test_cdgcn_training_step(case):
     bias = randn((4 * hidden,), 13) * 0.1
     g_h = randn((T, wl.n, hidden), 14)
     blk = make_block(wl, DEV, gen_device="cpu")
-    tr = CdgcnTrainer(blk, w.to(DEV), w_x.to(DEV), w_h.to(DEV), bias.to(DEV), hidden)
+    tr = CdgcnTrainer(blk, w.to(DEV), w_x.to(DEV), w_h.to(DEV), bias.to(DEV), hidden, keep_activations=keep)
     tr.load_first()
     for _ in range(2):                                # a second step must not see leftovers of the first
         tr.forward()
