@@ -391,6 +391,17 @@ int dgnn_lstm_cell_backward(const void *gates_x, const void *gates_h, const floa
                             int64_t n, int32_t hidden, dgnn_dtype dt, void *stream);
 
 /*
+ * The same with the gate pre-activations recomputed on chip (the adjoint of dgnn_lstm_step): takes Y, h_{t-1}, W_x,
+ * W_h and the bias instead of the two halves of the pre-activations, everything else as dgnn_lstm_cell_backward.
+ * fp32 storage, hidden = 32, f_y = 64 (DGNN_ERR_SHAPE otherwise: use the two dense transforms and
+ * dgnn_lstm_cell_backward).
+ */
+int dgnn_lstm_step_backward(const void *y, int32_t f_y, const void *h_prev, const void *w_x, const void *w_h,
+                            const float *bias, const void *c_prev, const void *dh_a, const void *dh_b,
+                            const void *dc_next, void *da, void *dc_prev, int64_t n, int32_t hidden, dgnn_dtype dt,
+                            void *stream);
+
+/*
  * Adjoint of dgnn_concat_relu: dy, y [n, f0 + f1] (y = the forward output); d0 [n, f0] and d1 [n, f1] receive the
  * two column blocks of dy where y > 0, zero elsewhere.  d0 may be NULL (the gradient with respect to Y0's own block
  * is needed only when a layer lies below).  Errors as dgnn_concat_relu.

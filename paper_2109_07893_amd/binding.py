@@ -24,7 +24,7 @@ DGNN_H_PRESCALED = 2
 EXPORTS = (
     "dgnn_strerror", "dgnn_csr_dinv", "dgnn_delta_h2d", "dgnn_delta_rebuild_workspace",
     "dgnn_delta_rebuild", "dgnn_feature_transform", "dgnn_spmm_workspace", "dgnn_spmm", "dgnn_mproduct",
-    "dgnn_delta_rebuild_weighted", "dgnn_spmm_weighted", "dgnn_csr_combine_workspace", "dgnn_csr_combine", "dgnn_csr_weighted_dinv_workspace", "dgnn_csr_weighted_dinv", "dgnn_concat_relu", "dgnn_lstm_cell", "dgnn_lstm_step", "dgnn_lstm_cell_backward", "dgnn_concat_relu_backward", "dgnn_bias_grad_workspace", "dgnn_bias_grad", "dgnn_add",
+    "dgnn_delta_rebuild_weighted", "dgnn_spmm_weighted", "dgnn_csr_combine_workspace", "dgnn_csr_combine", "dgnn_csr_weighted_dinv_workspace", "dgnn_csr_weighted_dinv", "dgnn_concat_relu", "dgnn_lstm_cell", "dgnn_lstm_step", "dgnn_lstm_cell_backward", "dgnn_lstm_step_backward", "dgnn_concat_relu_backward", "dgnn_bias_grad_workspace", "dgnn_bias_grad", "dgnn_add",
     "dgnn_mproduct_backward", "dgnn_mproduct_block", "dgnn_mproduct_backward_block", "dgnn_relu_backward", "dgnn_weight_grad_workspace", "dgnn_weight_grad", "dgnn_input_grad",
 )
 
@@ -110,6 +110,7 @@ def load_library():
     lib.dgnn_concat_relu.argtypes = [_vp, _i32, _vp, _i32, _vp, _i64, ctypes.c_int, _vp]
     lib.dgnn_lstm_cell.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _i32, ctypes.c_int, _vp]
     lib.dgnn_lstm_cell_backward.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i32, ctypes.c_int, _vp]
+    lib.dgnn_lstm_step_backward.argtypes = [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i32, ctypes.c_int, _vp]
     lib.dgnn_concat_relu_backward.argtypes = [_vp, _vp, _vp, _i32, _vp, _i32, _i64, ctypes.c_int, _vp]
     lib.dgnn_bias_grad_workspace.argtypes = [_i32, ctypes.POINTER(_sz)]
     lib.dgnn_bias_grad.argtypes = [_vp, _i64, _i32, _vp, ctypes.c_int, ctypes.c_int, _vp, _sz, _vp]
@@ -386,6 +387,26 @@ def lstm_cell_backward(gates_x, gates_h, bias, c_prev, dh_a, dh_b, dc_next, da, 
     _check(load_library().dgnn_lstm_cell_backward(_ptr(gates_x), _ptr(gates_h), _ptr(bias), _ptr(c_prev), _ptr(dh_a), _ptr(dh_b),
                                                   _ptr(dc_next), _ptr(da), _ptr(dc_prev), n, hidden, dt, _stream(gates_x)),
            "dgnn_lstm_cell_backward")
+
+
+def lstm_step_backward_supported(y: torch.Tensor, hidden: int) -> bool:
+    return y.dtype == torch.float32 and hidden == 32 and y.shape[1] == 64
+
+
+def lstm_step_backward(y, h_prev, w_x, w_h, bias, c_prev, dh_a, dh_b, dc_next, da, dc_prev) -> None:
+    """lstm_cell_backward with the gate pre-activations recomputed on chip from Y, h_prev and the weights."""
+    n, f_y = y.shape
+    hidden = c_prev.shape[1]
+    if tuple(w_x.shape) != (f_y, 4 * hidden) or tuple(w_h.shape) != (hidden, 4 * hidden) or tuple(da.shape) != (n, 4 * hidden):
+        raise ValueError("shape mismatch in lstm_step_backward")
+    for t in (h_prev, c_prev, dh_a, dh_b, dc_next, dc_prev):
+        if t is not None and (tuple(t.shape) != (n, hidden) or t.dtype != y.dtype):
+            raise ValueError("state tensors must be [n, hidden]")
+    if bias is not None:
+        _need(bias, torch.float32, "bias")
+    _check(load_library().dgnn_lstm_step_backward(_ptr(y), f_y, _ptr(h_prev), _ptr(w_x), _ptr(w_h), _ptr(bias), _ptr(c_prev),
+                                                  _ptr(dh_a), _ptr(dh_b), _ptr(dc_next), _ptr(da), _ptr(dc_prev), n, hidden,
+                                                  _dtype_code(y), _stream(y)), "dgnn_lstm_step_backward")
 
 
 def concat_relu_backward(dy: torch.Tensor, y: torch.Tensor, d0: Optional[torch.Tensor], d1: torch.Tensor, f0: int) -> None:

@@ -165,12 +165,18 @@ class CdgcnTrainer(CdgcnLayer):
             else:
                 self._gcn(t)
             h_prev = self.h0 if t == 1 else self.h_all[t - 2]
-            with self._stage("feature_transform"):
-                B.feature_transform(self.y, self.w_x, self.gx)
-                B.feature_transform(h_prev, self.w_h, self.gh)
-            with self._stage("lstm_cell_backward"):
-                B.lstm_cell_backward(self.gx, self.gh, self.bias, self.c_all[t - 1], g_h[t - 1], None if t == T else self.dh,
-                                     None if t == T else self.dc, self.da, self.dc)
+            carried = (None, None) if t == T else (self.dh, self.dc)
+            if self.fused and B.lstm_step_backward_supported(self.y, self.hidden):
+                with self._stage("lstm_step_backward"):
+                    B.lstm_step_backward(self.y, h_prev, self.w_x, self.w_h, self.bias, self.c_all[t - 1], g_h[t - 1],
+                                         carried[0], carried[1], self.da, self.dc)
+            else:
+                with self._stage("feature_transform"):
+                    B.feature_transform(self.y, self.w_x, self.gx)
+                    B.feature_transform(h_prev, self.w_h, self.gh)
+                with self._stage("lstm_cell_backward"):
+                    B.lstm_cell_backward(self.gx, self.gh, self.bias, self.c_all[t - 1], g_h[t - 1], carried[0], carried[1],
+                                         self.da, self.dc)
             with self._stage("weight_grad"):
                 B.weight_grad(self.y, self.da, self.dw_x, self.ws_wgrad, accumulate=not first)
                 B.weight_grad(h_prev, self.da, self.dw_h, self.ws_wgrad, accumulate=not first)

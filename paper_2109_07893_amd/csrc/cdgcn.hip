@@ -282,6 +282,157 @@ __global__ __launch_bounds__(kLstmThreads) void lstm_step_f32_kernel(const float
     }
 }
 
+// ---- The adjoint of that step, gate pre-activations recomputed on chip ----------------------------------------
+// Same tiles, same products; the cell's backward formulas are applied to the accumulators instead:
+//     dc = dh o (1 - tanh(c_t)^2) + dc_t,   da_i = dc g i (1 - i),  da_f = dc c_{t-1} f (1 - f),
+//     da_g = dc i (1 - g^2),  da_o = dh tanh(c_t) o (1 - o),   dc_{t-1} = dc f.
+// Traffic: Y, h_prev, c_prev, the incoming gradients in; da (4 * hidden wide) and dc_{t-1} out, instead of writing
+// and re-reading both halves of the pre-activations as well.  f_y = 64 only: the tile buffer (f_y + hidden columns)
+// has to hold c_prev, dh and dc_t side by side.
+__global__ __launch_bounds__(kLstmThreads) void lstm_step_backward_f32_kernel(
+    const float *__restrict__ y, const float *__restrict__ h_prev, const float *__restrict__ w_x, const float *__restrict__ w_h,
+    const float *__restrict__ bias, const float *__restrict__ c_prev, const float *__restrict__ dh_a,
+    const float *__restrict__ dh_b, const float *dc_next, float *__restrict__ da, float *dc_prev, int64_t n, int64_t n_tiles) {
+    constexpr int FY = 64, HID = kLstmHidden, G4 = 4 * HID;
+    constexpr int K = FY + HID, KH = K / 2;
+    constexpr int LDT = K + 4;
+    constexpr int Y_PIECES = 32 * FY / 4 / kWave;
+    constexpr int S_PIECES = 32 * HID / 4 / kWave;
+    constexpr int HALF_PIECES = 32 * (2 * HID) / 4 / kWave;   // 16-byte pieces per lane of half a tile of da
+    static_assert(K >= 3 * HID, "the tile buffer carries c_prev, dh and dc side by side");
+    __shared__ float s_w[K * G4];
+    __shared__ __attribute__((aligned(16))) float s_tile[kLstmWaves][32 * LDT];
+
+    const int tid = threadIdx.x;
+    for (int idx = tid; idx < K * G4; idx += kLstmThreads) s_w[idx] = idx < FY * G4 ? w_x[idx] : w_h[idx - FY * G4];
+    const int lane = tid & (kWave - 1), wave = tid / kWave;
+    const int i = lane & 31, hh = lane >> 5;
+    float *tile_lds = s_tile[wave];
+    const int64_t stride = (int64_t)gridDim.x * kLstmWaves;
+    const int64_t first = (int64_t)blockIdx.x * kLstmWaves + wave;
+    __syncthreads();
+    for (int64_t tile = first; tile < n_tiles; tile += stride) {
+        const floatx4 zero = {0.f, 0.f, 0.f, 0.f};
+        floatx4 c_cur[S_PIECES], dh_cur[S_PIECES], dc_cur[S_PIECES];
+        {
+            floatx4 yv[Y_PIECES], hv[S_PIECES];
+#pragma unroll
+            for (int q = 0; q < Y_PIECES; ++q) {
+                const int64_t piece = tile * (32 * FY / 4) + q * kWave + lane;
+                yv[q] = piece * 4 < n * FY ? reinterpret_cast<const floatx4 *>(y)[piece] : zero;
+            }
+#pragma unroll
+            for (int q = 0; q < S_PIECES; ++q) {
+                const int64_t piece = tile * (32 * HID / 4) + q * kWave + lane;
+                const bool ok = piece * 4 < n * HID;
+                hv[q] = ok ? reinterpret_cast<const floatx4 *>(h_prev)[piece] : zero;
+                c_cur[q] = ok ? reinterpret_cast<const floatx4 *>(c_prev)[piece] : zero;
+                dh_cur[q] = (ok && dh_a) ? reinterpret_cast<const floatx4 *>(dh_a)[piece] : zero;
+                if (ok && dh_b) dh_cur[q] += reinterpret_cast<const floatx4 *>(dh_b)[piece];
+                dc_cur[q] = (ok && dc_next) ? reinterpret_cast<const floatx4 *>(dc_next)[piece] : zero;
+            }
+#pragma unroll
+            for (int q = 0; q < Y_PIECES; ++q) {
+                const int e = (q * kWave + lane) * 4;
+                *reinterpret_cast<floatx4 *>(&tile_lds[(e / FY) * LDT + e % FY]) = yv[q];
+            }
+#pragma unroll
+            for (int q = 0; q < S_PIECES; ++q) {
+                const int e = (q * kWave + lane) * 4;
+                *reinterpret_cast<floatx4 *>(&tile_lds[(e / HID) * LDT + FY + e % HID]) = hv[q];
+            }
+        }
+        wave_lds_sync();
+        floatx4 a[KH / 4];
+#pragma unroll
+        for (int q = 0; q < KH / 4; ++q) a[q] = *reinterpret_cast<const floatx4 *>(&tile_lds[i * LDT + hh * KH + q * 4]);
+        wave_lds_sync();                                                      // every lane has its operands
+        // the tile buffer now takes c_prev, dh and dc in columns [0, hidden), [hidden, 2 hidden), [2 hidden, 3 hidden)
+#pragma unroll
+        for (int q = 0; q < S_PIECES; ++q) {
+            const int e = (q * kWave + lane) * 4;
+            float *row = &tile_lds[(e / HID) * LDT + e % HID];
+            *reinterpret_cast<floatx4 *>(row) = c_cur[q];
+            *reinterpret_cast<floatx4 *>(row + HID) = dh_cur[q];
+            *reinterpret_cast<floatx4 *>(row + 2 * HID) = dc_cur[q];
+        }
+        floatx16 acc[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[g][v] = 0.0f;
+#pragma unroll
+        for (int s = 0; s < KH; ++s) {
+            const float xv = a[s / 4][s % 4];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const float wv = s_w[(hh * KH + s) * G4 + g * 32 + i];
+                acc[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(wv, xv, acc[g], 0, 0, 0);     // transposed gate tile g
+            }
+        }
+        wave_lds_sync();                                                      // c_prev, dh, dc are in LDS
+        // ---- the cell's adjoint, on the accumulators (register 4 q + r of lane (i, h): state element 8 q + 4 h + r);
+        // the gradients replace the pre-activations in the accumulators, dc_{t-1} goes to the tile
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int k0 = 8 * q + 4 * hh;
+            const floatx4 c_old = *reinterpret_cast<const floatx4 *>(&tile_lds[i * LDT + k0]);
+            const floatx4 dh = *reinterpret_cast<const floatx4 *>(&tile_lds[i * LDT + HID + k0]);
+            const floatx4 dc_in = *reinterpret_cast<const floatx4 *>(&tile_lds[i * LDT + 2 * HID + k0]);
+            floatx4 dc_out;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int k = k0 + r;
+                const float gi = fast_sigmoid(acc[0][4 * q + r] + (bias ? bias[k] : 0.0f));
+                const float gf = fast_sigmoid(acc[1][4 * q + r] + (bias ? bias[HID + k] : 0.0f));
+                const float gg = fast_tanh(acc[2][4 * q + r] + (bias ? bias[2 * HID + k] : 0.0f));
+                const float go = fast_sigmoid(acc[3][4 * q + r] + (bias ? bias[3 * HID + k] : 0.0f));
+                const float tc = fast_tanh(gf * c_old[r] + gi * gg);
+                const float d = dh[r] * go * (1.0f - tc * tc) + dc_in[r];
+                acc[0][4 * q + r] = d * gg * gi * (1.0f - gi);
+                acc[1][4 * q + r] = d * c_old[r] * gf * (1.0f - gf);
+                acc[2][4 * q + r] = d * gi * (1.0f - gg * gg);
+                acc[3][4 * q + r] = dh[r] * tc * go * (1.0f - go);
+                dc_out[r] = d * gf;
+            }
+            *reinterpret_cast<floatx4 *>(&tile_lds[i * LDT + k0]) = dc_out;          // over c_prev: this lane alone read it
+        }
+        wave_lds_sync();
+#pragma unroll
+        for (int q = 0; q < S_PIECES; ++q) {
+            const int e = (q * kWave + lane) * 4;
+            const int64_t piece = tile * (32 * HID / 4) + q * kWave + lane;
+            if (piece * 4 < n * HID)
+                reinterpret_cast<floatx4 *>(dc_prev)[piece] = *reinterpret_cast<const floatx4 *>(&tile_lds[(e / HID) * LDT + e % HID]);
+        }
+        // da leaves in two halves of two gates each (a whole tile of it does not fit the buffer): columns
+        // [0, 2 hidden) of the tile rows, then whole 256-byte stretches of da's rows
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            wave_lds_sync();                                                  // the buffer's previous contents have been read
+#pragma unroll
+            for (int g = 0; g < 2; ++g)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const floatx16 &src = acc[2 * half + g];
+                    *reinterpret_cast<floatx4 *>(&tile_lds[i * LDT + g * HID + 8 * q + 4 * hh]) =
+                        floatx4{src[4 * q], src[4 * q + 1], src[4 * q + 2], src[4 * q + 3]};
+                }
+            wave_lds_sync();
+#pragma unroll
+            for (int q = 0; q < HALF_PIECES; ++q) {
+                const int e = (q * kWave + lane) * 4;                          // element of the 32 x 64 half tile
+                const int r = e / (2 * HID), col = e % (2 * HID);
+                const int64_t row = tile * 32 + r;
+                if (row < n)
+                    *reinterpret_cast<floatx4 *>(&da[row * G4 + half * 2 * HID + col]) =
+                        *reinterpret_cast<const floatx4 *>(&tile_lds[r * LDT + col]);
+            }
+        }
+        wave_lds_sync();                                                      // the tile buffer is reused
+    }
+}
+
 template <int FY>
 int launch_lstm_step(const void *y, const void *h_prev, const void *w_x, const void *w_h, const float *bias, void *c,
                      void *h_next, int64_t n, hipStream_t s) {
@@ -321,4 +472,42 @@ extern "C" int dgnn_lstm_step(const void *y, int32_t f_y, const void *h_prev, co
     hipStream_t s = (hipStream_t)stream;
     return f_y == 32 ? launch_lstm_step<32>(y, h_prev, w_x, w_h, bias, c, h_next, n, s)
                      : launch_lstm_step<64>(y, h_prev, w_x, w_h, bias, c, h_next, n, s);
+}
+
+extern "C" int dgnn_lstm_step_backward(const void *y, int32_t f_y, const void *h_prev, const void *w_x, const void *w_h,
+                                       const float *bias, const void *c_prev, const void *dh_a, const void *dh_b,
+                                       const void *dc_next, void *da, void *dc_prev, int64_t n, int32_t hidden, dgnn_dtype dt,
+                                       void *stream) {
+    if (!y || !h_prev || !w_x || !w_h || !c_prev || !da || !dc_prev) return DGNN_ERR_NULL;
+    if (!dh_a && !dh_b && !dc_next) return DGNN_ERR_NULL;
+    if (n <= 0 || hidden != kLstmHidden || dt != DGNN_F32 || f_y != 64) return DGNN_ERR_SHAPE;
+    if (!fits_index(n)) return DGNN_ERR_OVERFLOW;
+    for (const void *p : {y, h_prev, c_prev, dh_a, dh_b, dc_next, (const void *)da, (const void *)dc_prev})
+        if (p && !aligned16(p)) return DGNN_ERR_ALIGN;
+    if (da == y || da == h_prev || da == c_prev || da == dh_a || da == dh_b || da == dc_next || da == dc_prev ||
+        dc_prev == y || dc_prev == h_prev || dc_prev == c_prev || dc_prev == dh_a || dc_prev == dh_b)
+        return DGNN_ERR_ALIAS;                                     // dc_prev may be dc_next: a tile is read before it is written
+    const int64_t n_tiles = (n + 31) / 32;
+    const int64_t needed = (n_tiles + kLstmWaves - 1) / kLstmWaves;
+    static int64_t resident = 0;
+    if (resident == 0) {
+        int dev = 0, cus = 0, per_cu = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, lstm_step_backward_f32_kernel, kLstmThreads, 0) == hipSuccess &&
+            cus > 0 && per_cu > 0)
+            resident = (int64_t)cus * per_cu;
+        else {
+            (void)hipGetLastError();
+            resident = 256;
+        }
+    }
+    const unsigned blocks = (unsigned)(needed < resident ? needed : resident);
+    hipLaunchKernelGGL(lstm_step_backward_f32_kernel, dim3(blocks), dim3(kLstmThreads), 0, (hipStream_t)stream,
+                       static_cast<const float *>(y), static_cast<const float *>(h_prev), static_cast<const float *>(w_x),
+                       static_cast<const float *>(w_h), bias, static_cast<const float *>(c_prev),
+                       static_cast<const float *>(dh_a), static_cast<const float *>(dh_b), static_cast<const float *>(dc_next),
+                       static_cast<float *>(da), static_cast<float *>(dc_prev), n, n_tiles);
+    DGNN_RETURN_IF_LAUNCH_FAILED();
+    return DGNN_OK;
 }

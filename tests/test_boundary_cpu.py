@@ -265,3 +265,19 @@ def test_add_argument_errors(lib):
     assert f(None, FAKE, FAKE, 10, 32, 0, None) == -1
     assert f(FAKE, FAKE, FAKE, 0, 32, 0, None) == -2 and f(FAKE, FAKE, FAKE, 10, 33, 0, None) == -2
     assert f(FAKE, FAKE + 8, FAKE, 10, 32, 0, None) == -7
+
+
+def test_lstm_step_backward_argument_errors(lib):
+    f = lib.dgnn_lstm_step_backward
+    a = [FAKE + 4096 * k for k in range(12)]
+    ok = dict(y=a[0], f_y=64, h=a[1], wx=a[2], wh=a[3], c=a[4], dh=a[5], da=a[6], dc=a[7], hidden=32, dt=0)
+
+    def call(**kw):
+        p = dict(ok, **kw)
+        return f(p["y"], p["f_y"], p["h"], p["wx"], p["wh"], None, p["c"], p["dh"], None, None, p["da"], p["dc"], 10, p["hidden"],
+                 p["dt"], None)
+
+    assert call(y=None) == -1 and call(da=None) == -1 and call(dh=None) == -1
+    assert call(f_y=32) == -2 and call(hidden=64) == -2 and call(dt=1) == -2
+    assert call(da=a[0]) == -5 and call(dc=a[5]) == -5
+    assert call(c=a[4] + 4) == -7

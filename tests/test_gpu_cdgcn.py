@@ -169,9 +169,29 @@ def test_bias_grad(dtype, f, n):
     assert torch.equal(db, first)                     # fixed order of summation
 
 
-@pytest.mark.parametrize("keep", [False, True])
+@pytest.mark.parametrize("n", [1, 31, 32, 33, 4097, 20_011])
+@pytest.mark.parametrize("carried", [False, True])
+def test_fused_lstm_step_backward(n, carried):
+    f_y, hidden = 64, 32
+    y, h_prev = randn((n, f_y), 1), randn((n, hidden), 2)
+    w_x, w_h = randn((f_y, 4 * hidden), 3) / 8, randn((hidden, 4 * hidden), 4) / 6
+    bias = randn((4 * hidden,), 5) * 0.1
+    c_prev, g_h = randn((n, hidden), 6), randn((n, hidden), 7)
+    dh_c, dc_n = (randn((n, hidden), 8), randn((n, hidden), 9)) if carried else (None, None)
+    da = torch.full((n, 4 * hidden), float("nan"), device=DEV)
+    dc = dc_n.to(DEV) if carried else torch.full((n, hidden), float("nan"), device=DEV)
+    dg.lstm_step_backward(y.to(DEV), h_prev.to(DEV), w_x.to(DEV), w_h.to(DEV), bias.to(DEV), c_prev.to(DEV), g_h.to(DEV),
+                          dh_c.to(DEV) if carried else None, dc if carried else None, da, dc)
+    dh = to_f64(g_h) + (to_f64(dh_c) if carried else 0.0)
+    want = oracle.lstm_cell_backward(to_f64(y), to_f64(h_prev), to_f64(c_prev), to_f64(w_x), to_f64(w_h), to_f64(bias), dh,
+                                     to_f64(dc_n) if carried else None)
+    assert_close(to_f64(da), want[0], torch.float32, "dL/d(pre-activations), fused")
+    assert_close(to_f64(dc), want[3], torch.float32, "dL/dc_prev, fused")
+
+
+@pytest.mark.parametrize("keep,fused", [(False, True), (True, True), (False, False)])
 @pytest.mark.parametrize("case", ["undirected_f32", "directed_f32"])
-def test_cdgcn_training_step(case, keep):
+def test_cdgcn_training_step(case, keep, fused):
     """Gradients of sum_t <G_t, h_t> with respect to W, W_x, W_h and b over a block, against the oracle's backward
     pass (itself pinned by finite differences); the ReLU mask is taken on fp32 values on the device and fp64 in
     the oracle, which agree except for outputs within rounding of zero (none at these sizes would move a gradient
@@ -186,7 +206,7 @@ def test_cdgcn_training_step(case, keep):
     bias = randn((4 * hidden,), 13) * 0.1
     g_h = randn((T, wl.n, hidden), 14)
     blk = make_block(wl, DEV, gen_device="cpu")
-    tr = CdgcnTrainer(blk, w.to(DEV), w_x.to(DEV), w_h.to(DEV), bias.to(DEV), hidden, keep_activations=keep)
+    tr = CdgcnTrainer(blk, w.to(DEV), w_x.to(DEV), w_h.to(DEV), bias.to(DEV), hidden, fused=fused, keep_activations=keep)
     tr.load_first()
     for _ in range(2):                                # a second step must not see leftovers of the first
         tr.forward()
