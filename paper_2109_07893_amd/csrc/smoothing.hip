@@ -11,7 +11,7 @@
 //   - the A_in and A_out terms of a range are consecutive in their arrays and are staged as well (a span longer
 //     than the staging area is read in place instead);
 //   - each lane merges its share out of LDS, row piece after row piece;
-//   - the size of the result is not known beforehand: a first launch only counts (per lane), a single-workgroup
+//   - the size of the result is not known beforehand: a first launch only counts (per lane), a two-level
 //     scan turns the range totals into positions, the second launch merges again and writes, rowptr included.
 // The result's order is the canonical one (rows ascending, columns ascending), whatever the launch shape.
 #include <hip/hip_runtime.h>
@@ -29,6 +29,7 @@ constexpr int kCapOut = 256;           // staged terms of A_out per range
 constexpr int kCapRows = 128;          // staged row pointers per range and operand
 constexpr int kNoCol = 0x7fffffff;     // larger than any column index the library accepts
 constexpr int kScanThreads = 1024;
+constexpr int kScanTile = 4 * kScanThreads;   // counts per workgroup of the first scan level
 
 // Where a share begins.  Rows k, k+1, ... begin at or behind the boundary; cut: the boundary lies inside row k-1.
 // a, o: the first terms of A_in and A_out that are not in front of the boundary.
@@ -144,7 +145,7 @@ __global__ __launch_bounds__(256) void bounds_kernel(Operands P, int n_ranges, B
 
 template <bool WRITE>
 __global__ __launch_bounds__(kWave) void combine_kernel(Operands P, int n_ranges, const Bound *__restrict__ bounds,
-                                                       int32_t *__restrict__ totals,
+                                                       int32_t *__restrict__ totals, const int32_t *__restrict__ tile_off,
                                                        int32_t *__restrict__ lane_counts, int32_t *__restrict__ rowptr_out,
                                                        int32_t *__restrict__ out_col, float *__restrict__ out_val) {
     __shared__ int s_col[kRange];
@@ -197,8 +198,9 @@ __global__ __launch_bounds__(kWave) void combine_kernel(Operands P, int n_ranges
         if (WRITE) {
             const int mine_cnt = active ? lane_counts[(int64_t)range * kWave + lane] : 0;
             const int incl = wave_scan_add(mine_cnt, lane);
-            begin = (int64_t)totals[range] + incl - mine_cnt;
-            if (last && lane == kWave - 1) rowptr_out[P.n] = (int32_t)(totals[range] + incl);
+            const int64_t range_begin = (int64_t)totals[range] + tile_off[range / kScanTile];   // both scan levels
+            begin = range_begin + incl - mine_cnt;
+            if (last && lane == kWave - 1) rowptr_out[P.n] = (int32_t)(range_begin + incl);
         }
         int64_t end = begin;
         if (active) end = merge_share<WRITE>(P, T, s_col, s_val, e0, mine, sb0, next, sb1, begin, rowptr_out, out_col, out_val);
@@ -213,9 +215,40 @@ __global__ __launch_bounds__(kWave) void combine_kernel(Operands P, int n_ranges
     else run(G);
 }
 
+// First level of the scan over range totals: every workgroup turns its tile of counts into exclusive prefix sums
+// within the tile and leaves the tile's total; scan_kernel then scans the tile totals, and the write launch adds a
+// range's two levels together.
+__global__ __launch_bounds__(kScanThreads) void scan_tiles_kernel(int m, int32_t *__restrict__ counts, int32_t *__restrict__ tile_total) {
+    constexpr int kWaves = kScanThreads / kWave;
+    __shared__ int s_wave[kWaves];
+    const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+    const int i = blockIdx.x * kScanTile + 4 * tid;
+    int v[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) v[q] = i + q < m ? counts[i + q] : 0;
+    const int mine = (v[0] + v[1]) + (v[2] + v[3]);
+    const int incl = wave_scan_add(mine, lane);
+    if (lane == kWave - 1) s_wave[wave] = incl;
+    __syncthreads();
+    int before = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        const int t = s_wave[w];
+        if (w < wave) before += t;
+        total += t;
+    }
+    int run = before + incl - mine;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        if (i + q < m) counts[i + q] = run;
+        run += v[q];
+    }
+    if (tid == 0) tile_total[blockIdx.x] = total;
+}
+
 // In place: counts[0 .. m) -> their exclusive prefix sums, counts[m] = the total.  One workgroup walks tiles of
 // 4096 counts (four per thread, scanned within the wavefront by lane shifts, across wavefronts through LDS); m is
-// a number of ranges, about a million at the largest supported snapshot.
+// a number of tiles of ranges, about two thousand at the largest supported snapshot.
 __global__ __launch_bounds__(kScanThreads) void scan_kernel(int m, int32_t *__restrict__ counts) {
     constexpr int kWaves = kScanThreads / kWave;
     __shared__ int s_wave[kWaves];
@@ -254,8 +287,10 @@ int64_t range_count(int64_t nnz_s) { return std::max<int64_t>(1, (nnz_s + kRange
 // range totals (+ the grand total), then one count per lane
 size_t totals_bytes(int64_t nnz_s) { return round_up((size_t)(4 * (range_count(nnz_s) + 1)), (size_t)256); }
 size_t counts_bytes(int64_t nnz_s) { return round_up((size_t)(4 * kWave * range_count(nnz_s)), (size_t)256); }
+size_t bounds_bytes(int64_t nnz_s) { return round_up(sizeof(Bound) * (size_t)(range_count(nnz_s) + 1), (size_t)256); }
+int64_t tile_count(int64_t nnz_s) { return (range_count(nnz_s) + kScanTile - 1) / kScanTile; }
 size_t combine_workspace(int64_t nnz_s) {
-    return totals_bytes(nnz_s) + counts_bytes(nnz_s) + round_up(sizeof(Bound) * (size_t)(range_count(nnz_s) + 1), (size_t)256);
+    return totals_bytes(nnz_s) + counts_bytes(nnz_s) + bounds_bytes(nnz_s) + round_up((size_t)(4 * (tile_count(nnz_s) + 1)), (size_t)256);
 }
 
 }  // namespace
@@ -292,18 +327,22 @@ extern "C" int dgnn_csr_combine(int64_t n, const int32_t *rowptr_s, const int32_
     Bound *bounds = (Bound *)((char *)ws + totals_bytes(nnz_s) + counts_bytes(nnz_s));
     hipLaunchKernelGGL(bounds_kernel, dim3((unsigned)(ranges / 256 + 1)), dim3(256), 0, s, P, ranges, bounds);
     DGNN_RETURN_IF_LAUNCH_FAILED();
-    hipLaunchKernelGGL(combine_kernel<false>, dim3((unsigned)ranges), dim3(kWave), 0, s, P, ranges, bounds, totals, lane_counts,
-                       nullptr, nullptr, nullptr);
+    hipLaunchKernelGGL(combine_kernel<false>, dim3((unsigned)ranges), dim3(kWave), 0, s, P, ranges, bounds, totals, nullptr,
+                       lane_counts, nullptr, nullptr, nullptr);
     DGNN_RETURN_IF_LAUNCH_FAILED();
-    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(kScanThreads), 0, s, ranges, totals);
+    const int tiles = (int)tile_count(nnz_s);
+    int32_t *tile_off = (int32_t *)((char *)bounds + bounds_bytes(nnz_s));
+    hipLaunchKernelGGL(scan_tiles_kernel, dim3((unsigned)tiles), dim3(kScanThreads), 0, s, ranges, totals, tile_off);
+    DGNN_RETURN_IF_LAUNCH_FAILED();
+    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(kScanThreads), 0, s, tiles, tile_off);
     DGNN_RETURN_IF_LAUNCH_FAILED();
     int32_t total = 0;
-    if (hipMemcpyAsync(&total, totals + ranges, sizeof(total), hipMemcpyDeviceToHost, s) != hipSuccess) return DGNN_ERR_HIP;
+    if (hipMemcpyAsync(&total, tile_off + tiles, sizeof(total), hipMemcpyDeviceToHost, s) != hipSuccess) return DGNN_ERR_HIP;
     if (hipStreamSynchronize(s) != hipSuccess) return DGNN_ERR_HIP;
     *nnz_c = total;
     if (total > capacity) return DGNN_ERR_CAPACITY;
-    hipLaunchKernelGGL(combine_kernel<true>, dim3((unsigned)ranges), dim3(kWave), 0, s, P, ranges, bounds, totals, lane_counts,
-                       rowptr_c, colidx_c, val_c);
+    hipLaunchKernelGGL(combine_kernel<true>, dim3((unsigned)ranges), dim3(kWave), 0, s, P, ranges, bounds, totals, tile_off,
+                       lane_counts, rowptr_c, colidx_c, val_c);
     DGNN_RETURN_IF_LAUNCH_FAILED();
     return DGNN_OK;
 }
