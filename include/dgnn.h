@@ -221,7 +221,8 @@ int dgnn_spmm_weighted(int64_t n, int64_t nnz, const int32_t *rowptr, const int3
  * ws: device scratch (16-byte aligned) of at least dgnn_csr_weighted_dinv_workspace(nnz) bytes (pieces of rows
  * that are summed by several wavefronts); contents need not be preserved.  Every sum has a fixed
  * order, results repeat bit for bit.  val[0 .. nnz) is read; errors: NULL, SHAPE (n <= 0, nnz <= 0), OVERFLOW,
- * CAPACITY (workspace too small), ALIGN.  A row without entries gets +inf.
+ * CAPACITY (workspace too small), ALIGN.  A row whose sum is not positive (no entries, or
+ * weights that cancel) gets 0: such a vertex neither sends nor receives, instead of producing infinities.
  */
 int dgnn_csr_weighted_dinv_workspace(int64_t nnz, size_t *bytes);
 int dgnn_csr_weighted_dinv(int64_t n, int64_t nnz, const int32_t *rowptr, const float *val, float *dinv,

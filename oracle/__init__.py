@@ -285,7 +285,9 @@ def gcn_values_weighted(rowptr, colidx, val) -> np.ndarray:
     n = rowptr.size - 1
     d = np.array([val[rowptr[u]:rowptr[u + 1]].sum() for u in range(n)])
     rows = np.repeat(np.arange(n), np.diff(rowptr))
-    return val / np.sqrt(d[rows] * d[colidx])
+    # a vertex whose row sum is not positive has no normalisation: its factor is taken as 0 (it neither sends nor receives)
+    dinv = np.where(d > 0.0, 1.0 / np.sqrt(np.where(d > 0.0, d, 1.0)), 0.0)
+    return val * dinv[rows] * dinv[colidx]
 
 
 def csr_combine(n: int, s, a_in=None, alpha: float = 1.0, a_out=None, beta: float = -1.0):

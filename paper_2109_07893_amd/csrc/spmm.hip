@@ -627,6 +627,10 @@ __device__ __forceinline__ float wave_sum8(const float (&v)[8], int lane) {
     return __shfl(r, ((q >> 2) & 1) | (q & 2) | ((q & 1) << 2), kWave);
 }
 
+// A vertex whose row sum is not positive (no entries at all, or weights that cancel) has no normalisation; it gets
+// the factor 0, so it neither sends nor receives anything, instead of an infinity that would turn into NaN.
+__device__ __forceinline__ float inv_sqrt_or_zero(float s) { return s > 0.0f ? 1.0f / sqrtf(s) : 0.0f; }
+
 __global__ __launch_bounds__(kWave) void weighted_rowsum_kernel(int n, int nnz, const int32_t *__restrict__ rowptr,
                                                                const float *__restrict__ val, SumRec *__restrict__ recs,
                                                                float *__restrict__ dinv) {
@@ -689,7 +693,7 @@ __global__ __launch_bounds__(kWave) void weighted_rowsum_kernel(int n, int nnz, 
             if (coop && (rank >> 3) == group) sum = t;
         }
         const bool open_l = rb < e0, open_r = re > e1;
-        if (valid && !open_l && !open_r) dinv[r] = 1.0f / sqrtf(sum);
+        if (valid && !open_l && !open_r) dinv[r] = inv_sqrt_or_zero(sum);
         const uint64_t m_cont = __ballot(valid && open_l), m_own = __ballot(valid && !open_l && open_r);
         if (m_cont) p_cont = __shfl(sum, __builtin_ctzll(m_cont), kWave);
         if (m_own) { const int src = __builtin_ctzll(m_own); p_own = __shfl(sum, src, kWave); owner = base + src; }
@@ -707,7 +711,7 @@ __global__ __launch_bounds__(256) void weighted_rowsum_fix_kernel(int n_ranges, 
     const int end = rowptr[rec.owner + 1];
     float acc = rec.p_own;
     for (int r = w + 1; (int64_t)r * kSumRange < end; ++r) acc += recs[r].p_cont;
-    dinv[rec.owner] = 1.0f / sqrtf(acc);
+    dinv[rec.owner] = inv_sqrt_or_zero(acc);
 }
 
 size_t weighted_dinv_workspace(int64_t nnz) {

@@ -225,4 +225,37 @@ def test_weighted_row_sums_with_hub_rows_cut_into_pieces():
     got = to_f64(outs[0])
     nz = want > 0
     np.testing.assert_allclose(got[nz], want[nz] ** -0.5, rtol=2e-6)
-    assert np.all(np.isinf(got[~nz]))                   # an empty row has no normalisation
+    assert np.all(got[~nz] == 0.0)                      # an empty row has no normalisation: factor 0
+
+
+def test_normalised_aggregation_with_vertices_without_entries():
+    """Rows without stored entries that other rows point to: their factor is 0 on both sides, nothing turns into
+    inf or NaN, and the rest of the result is unaffected."""
+    wl = WORKLOADS["c3"].scaled(1 << 12, T=1)
+    g = DynamicGraph(wl)
+    rp, ci = (x.numpy() for x in g.csr())
+    n, f = wl.n, 32
+    rng = np.random.default_rng(8)
+    lens = np.diff(rp)
+    drop = rng.choice(n, size=n // 10, replace=False)                     # a tenth of the rows lose all their entries
+    keep = np.ones(ci.size, dtype=bool)
+    for u in drop:
+        keep[rp[u]:rp[u + 1]] = False
+    lens[drop] = 0
+    rp, ci = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32), ci[keep]
+    assert np.isin(ci, drop).any()                                        # emptied vertices are still pointed to
+    val = f32(rng.integers(1, 4, ci.size))
+    x = torch.randn((n, f), generator=torch.Generator().manual_seed(2))
+    w = torch.randn((f, f), generator=torch.Generator().manual_seed(3)) / np.sqrt(f)
+    want = oracle.spmm(rp, ci, oracle.xw(to_f64(x), to_f64(w)), relu=False, val=oracle.gcn_values_weighted(rp, ci, val.astype(np.float64)))
+    assert np.isfinite(want).all() and np.all(want[drop] == 0.0)
+    rp_d, ci_d, val_d = dev(rp, torch.int32), dev(ci, torch.int32), dev(val, torch.float32)
+    dinv = torch.empty(n, device=DEV)
+    dg.csr_weighted_dinv(rp_d, val_d, int(ci.size), dinv, ws_dinv(int(ci.size)))
+    h = torch.empty((n, f), device=DEV)
+    dg.feature_transform(x.to(DEV), w.to(DEV), h, row_scale=dinv)
+    z = torch.full((n, f), float("nan"), device=DEV)
+    ws = torch.empty(dg.spmm_workspace(n, int(ci.size), f), dtype=torch.uint8, device=DEV)
+    dg.spmm_weighted(rp_d, ci_d, val_d, int(ci.size), h, z, ws, flags=dg.DGNN_H_PRESCALED, dinv=dinv)
+    assert bool(torch.isfinite(z).all())
+    assert_close(to_f64(z), want, torch.float32, "normalised aggregation with empty rows")

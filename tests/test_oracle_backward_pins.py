@@ -263,6 +263,11 @@ def test_weighted_normalisation_reduces_to_eqn_1_and_matches_the_dense_form():
     want = np.diag(d ** -0.5) @ dense @ np.diag(d ** -0.5)
     got = np.nan_to_num(_dense_weighted(n, rp, ci, oracle.gcn_values_weighted(rp, ci, val)), nan=0.0)
     np.testing.assert_allclose(got, want, rtol=1e-13, atol=1e-15)
+    # a vertex without stored entries that others point to: the entries towards it weigh 0, nothing becomes infinite
+    rp2 = np.array([0, 2, 2, 3], dtype=np.int32)                       # row 1 is empty
+    ci2 = np.array([0, 1, 2], dtype=np.int32)                          # (0,0), (0,1), (2,2)
+    got2 = oracle.gcn_values_weighted(rp2, ci2, np.array([2.0, 2.0, 3.0]))
+    np.testing.assert_allclose(got2, [2.0 / 4.0, 0.0, 1.0], rtol=1e-15)
     # sqrt(d) is a fixed vector of the normalised matrix, as in the unweighted case
     np.testing.assert_allclose(oracle.spmm(rp, ci, np.sqrt(d)[:, None], val=oracle.gcn_values_weighted(rp, ci, val))[:, 0],
                                np.sqrt(d), rtol=1e-12)

@@ -114,7 +114,9 @@ def test_a_planted_mistake_is_caught(tmp_path, name, good, bad):
 PY_SRC = os.path.join(os.path.dirname(HERE), "oracle", "__init__.py")
 
 PY_MUTANTS = [
-    ("weighted normalisation uses the row sum twice", "return val / np.sqrt(d[rows] * d[colidx])", "return val / np.sqrt(d[rows] * d[rows])"),
+    ("weighted normalisation uses the row factor twice", "return val * dinv[rows] * dinv[colidx]", "return val * dinv[rows] * dinv[rows]"),
+    ("weighted normalisation: a vertex without entries poisons its neighbours", "dinv = np.where(d > 0.0, 1.0 / np.sqrt(np.where(d > 0.0, d, 1.0)), 0.0)",
+     "with np.errstate(all='ignore'):\n        dinv = 1.0 / np.sqrt(d)"),
     ("weighted normalisation counts entries instead of adding values", "d = np.array([val[rowptr[u]:rowptr[u + 1]].sum() for u in range(n)])",
      "d = np.array([float(rowptr[u + 1] - rowptr[u]) for u in range(n)])"),
     ("combination keeps entries that cancel", "keep = total != 0.0", "keep = np.ones(total.size, dtype=bool)"),
