@@ -91,8 +91,22 @@ class CdgcnTrainer(CdgcnLayer):
 
     Gradients with respect to the layer's parameters (fp32): dw, dw_x, dw_h, db.  The input features are leaves."""
 
-    def __init__(self, blk: BlockInputs, w, w_x, w_h, bias, hidden: int, fused: bool = True, keep_activations: bool = False):
+    def __init__(self, blk: BlockInputs, w, w_x, w_h, bias, hidden: int, fused: bool = True, keep_activations: bool = False,
+                 want_dx: bool = False, transposed_first=None, transposed_deltas=None):
         super().__init__(blk, w, w_x, w_h, bias, hidden, fused)
+        # want_dx: also dL/dX_t = A~_t^T (dY0 + dY1 W^T), for a layer that lies below (the paper stacks two of these
+        # layers).  For a directed workload that takes the transposed snapshots, a second chain rebuilt from the
+        # difference lists sorted by (col, row), handed in as (rowptr, colidx) of A_1^T and one list tuple per step.
+        self.want_dx = want_dx
+        self.at = None
+        if want_dx:
+            from .training import _Chain
+            self.dx = torch.empty((blk.T, blk.n, blk.f), dtype=blk.x[0].dtype, device=self.dev)
+            self.d0 = torch.empty((blk.n, blk.f), dtype=blk.x[0].dtype, device=self.dev)
+            self.tmp = torch.empty((blk.n, blk.f), dtype=blk.x[0].dtype, device=self.dev)
+            if transposed_first is not None:
+                self.at = _Chain(blk.n, self.cap, self.dev, transposed_first[0], transposed_first[1], with_dinv=False)
+                self.t_deltas = transposed_deltas
         n, f, T = blk.n, blk.f, blk.T
         f_out = w.shape[1]
         dt, dev = blk.x[0].dtype, self.dev
@@ -138,6 +152,8 @@ class CdgcnTrainer(CdgcnLayer):
         for t in range(1, blk.T + 1):
             if t >= 2:
                 self.rebuild(t, blk.deltas[t - 2])
+                if self.at is not None:
+                    self._rebuild_transposed(t - 1, t, blk.nnz[t - 2], reverse=False)
             if self.keep:
                 self.y0, self.y = self.y0_all[t - 1], self.y_all[t - 1]
             self._gcn(t)
@@ -153,6 +169,16 @@ class CdgcnTrainer(CdgcnLayer):
             with self._stage("lstm_cell"):
                 B.lstm_cell(self.gx, self.gh, self.bias, self.c_all[t - 1], self.c_all[t], self.h_all[t - 1])
         return self.h_all
+
+    def _rebuild_transposed(self, src_t: int, dst_t: int, nnz_src: int, reverse: bool) -> None:
+        ar, ac, dr, dc = self.t_deltas[max(src_t, dst_t) - 2]
+        if reverse:
+            ar, ac, dr, dc = dr, dc, ar, ac
+        a = self.at
+        s, d = a.slot_of(src_t), a.slot_of(dst_t)
+        with self._stage("delta_rebuild"):
+            B.delta_rebuild(a.rowptr[s], a.colidx[s], nnz_src, ar, ac, int(ar.numel()), dr, dc, int(dr.numel()),
+                            a.rowptr[d], a.colidx[d], None, self.ws_rebuild)
 
     def backward(self, g_h: torch.Tensor) -> None:
         """g_h [T, n, hidden] = dL/dh_t.  Must follow forward() (A_T resident)."""
@@ -187,11 +213,25 @@ class CdgcnTrainer(CdgcnLayer):
                 if t >= 2:
                     B.input_grad(self.da, self.w_h, self.dh)
             with self._stage("concat_relu_backward"):
-                B.concat_relu_backward(self.dy, self.y, None, self.dy1, blk.f)
+                B.concat_relu_backward(self.dy, self.y, self.d0 if self.want_dx else None, self.dy1, blk.f)
             with self._stage("weight_grad"):
                 B.weight_grad(self.y0, self.dy1, self.dw, self.ws_wgrad, accumulate=not first)
+            if self.want_dx:
+                slot = self.slot_of(t)
+                with self._stage("input_grad"):
+                    B.input_grad(self.dy1, self.w, self.tmp)
+                    B.add(self.d0, self.tmp, self.d0)                           # dY0: its own block and the path through Y1
+                with self._stage("row_scale"):
+                    B.feature_transform(self.d0, self.eye, self.tmp, row_scale=self.dinv[slot])
+                with self._stage("spmm_transposed"):
+                    rp, ci = ((self.at.rowptr[slot], self.at.colidx[slot]) if self.at is not None
+                              else (self.rowptr[slot], self.colidx[slot]))
+                    B.spmm(rp, ci, blk.nnz[t - 1], self.dinv[slot], self.tmp, self.dx[t - 1], self.ws_spmm,
+                           flags=B.DGNN_H_PRESCALED)
+                if t >= 3 and self.at is not None:
+                    self._rebuild_transposed(t, t - 1, blk.nnz[t - 1], reverse=True)
             first = False
-            if t >= 3 and not self.keep:      # A_{t-1} from A_t: the same rebuild with the two lists exchanged (A_1 was kept)
+            if t >= 3 and (self.want_dx or not self.keep):      # A_{t-1} from A_t: the two lists exchanged (A_1 was kept)
                 ar, ac, dr, dc = blk.deltas[t - 2]
                 src, dst = self.slot_of(t), self.slot_of(t - 1)
                 with self._stage("delta_rebuild"):

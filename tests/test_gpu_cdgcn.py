@@ -246,3 +246,80 @@ def test_add(dtype):
     dg.add(out, b.to(DEV), out)                          # in place
     want = (a.to(torch.float32) + b.to(torch.float32)).to(dtype)
     assert torch.equal(out.cpu(), want)                  # one fp32 sum, rounded once
+
+
+@pytest.mark.parametrize("case,keep", [("undirected_f32", False), ("directed_f32", False), ("directed_f32", True)])
+def test_two_layer_cdgcn_training_step(case, keep):
+    """The two-layer CD-GCN the paper trains (Section "CD-GCN"): the second layer's input is the first layer's h_t,
+    so its backward pass has to deliver dL/dX_t = A~_t^T (dY0 + dY1 W^T), which becomes the first layer's dL/dh_t.
+    Parameter gradients of both layers against the oracle's chain."""
+    from dtdg_synth import transpose_coo
+    from paper_2109_07893_amd.cdgcn import CdgcnTrainer
+    from paper_2109_07893_amd.pipeline import BlockInputs
+    wl = {"undirected_f32": replace(WORKLOADS["c1"], f=32, window=0, name="cd-c1"),
+          "directed_f32": replace(WORKLOADS["c3"].scaled(4096, T=4), name="cd-c3")}[case]
+    f, hidden, T, n = wl.f, 32, wl.T, wl.n
+    par = []
+    for layer, f_in in enumerate((f, hidden)):
+        par.append((randn((f_in, f_in), 20 + layer) / np.sqrt(f_in), randn((2 * f_in, 4 * hidden), 30 + layer) / np.sqrt(2 * f_in),
+                    randn((hidden, 4 * hidden), 40 + layer) / np.sqrt(hidden), randn((4 * hidden,), 50 + layer) * 0.1))
+    g_h = randn((T, n, hidden), 60)
+    blk = make_block(wl, DEV, gen_device="cpu")
+    l1 = CdgcnTrainer(blk, *[p.to(DEV) for p in par[0]], hidden, keep_activations=keep)
+    blk2 = BlockInputs(n=n, T=T, f=hidden, layers=1, window=0, rowptr1=blk.rowptr1, colidx1=blk.colidx1, deltas=blk.deltas,
+                       x=[l1.h_all[t] for t in range(T)], w=[par[1][0].to(DEV)], nnz=list(blk.nnz))
+    kw = {}
+    if wl.graph != "er":                                  # directed: the transposed first snapshot and lists
+        rows = torch.repeat_interleave(torch.arange(n, dtype=torch.int32, device=DEV), (blk.rowptr1[1:] - blk.rowptr1[:-1]).to(torch.int64))
+        tr_, tc_ = transpose_coo(rows, blk.colidx1)
+        rp_t = torch.zeros(n + 1, dtype=torch.int32, device=DEV)
+        rp_t[1:] = torch.cumsum(torch.bincount(tr_.to(torch.int64), minlength=n), 0).to(torch.int32)
+        kw = dict(transposed_first=(rp_t, tc_), transposed_deltas=[transpose_coo(ar, ac) + transpose_coo(dr, dc) for ar, ac, dr, dc in blk.deltas])
+    l2 = CdgcnTrainer(blk2, *[p.to(DEV) for p in par[1]], hidden, keep_activations=keep, want_dx=True, **kw)
+    l1.load_first(); l2.load_first()
+    for _ in range(2):
+        l1.forward(); l2.forward()
+        l2.backward(g_h.to(DEV))
+        l1.backward(l2.dx)
+    torch.cuda.synchronize()
+    # oracle: forward of both layers, then backward
+    P = [[to_f64(p) for p in layer] for layer in par]
+    g = DynamicGraph(wl)
+    rp, ci = (x.numpy() for x in g.csr())
+    snaps = []
+    xs = [[None] * T, [None] * T]
+    ys = [[None] * T, [None] * T]
+    hs = [[np.zeros((n, hidden))], [np.zeros((n, hidden))]]
+    cs = [[np.zeros((n, hidden))], [np.zeros((n, hidden))]]
+    for t in range(1, T + 1):
+        if t > 1:
+            rp, ci = oracle.delta_apply(n, rp, ci, *[x.numpy() for x in g.advance()])
+        snaps.append((rp, ci))
+        x = to_f64(features(wl, t))
+        for layer in range(2):
+            W, WX, WH, Bv = P[layer]
+            xs[layer][t - 1] = x
+            ys[layer][t - 1] = oracle.cdgcn_gcn(rp, ci, x, W)
+            h, c = oracle.lstm_cell(ys[layer][t - 1], hs[layer][-1], cs[layer][-1], WX, WH, Bv)
+            hs[layer].append(h); cs[layer].append(c)
+            x = h
+    assert_close(to_f64(l2.h_all[T - 1]), hs[1][T], torch.float32, "second layer's h_T")
+    grads = [None, None]
+    upstream = [to_f64(g_h[t]) for t in range(T)]
+    for layer in (1, 0):
+        W, WX, WH, Bv = P[layer]
+        d_w = d_wx = d_wh = d_b = 0.0
+        dh, dc = 0.0, None
+        d_x_all = [None] * T
+        for t in range(T, 0, -1):
+            _, d_y, dh, dc, a, b, cg = oracle.lstm_cell_backward(ys[layer][t - 1], hs[layer][t - 1], cs[layer][t - 1], WX, WH, Bv,
+                                                                 upstream[t - 1] + dh, dc)
+            d_wx, d_wh, d_b = d_wx + a, d_wh + b, d_b + cg
+            dw_t, d_x_all[t - 1] = oracle.cdgcn_gcn_backward(*snaps[t - 1], xs[layer][t - 1], W, d_y)
+            d_w = d_w + dw_t
+        grads[layer] = (d_w, d_wx, d_wh, d_b)
+        upstream = d_x_all
+    for layer, tr in enumerate((l1, l2)):
+        for name, got, want in zip(("dW", "dW_x", "dW_h", "db"), (tr.dw, tr.dw_x, tr.dw_h, tr.db), grads[layer]):
+            err = np.abs(to_f64(got) - want).max()
+            assert err <= 3e-4 * np.abs(want).max(), f"{case} layer {layer + 1} {name}: max err {err:.3e} against max |.| {np.abs(want).max():.3e}"
