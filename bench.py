@@ -254,6 +254,25 @@ def smoothing_steps(args, wl, blk, dev, life=4):
                            "stages": {k: {"calls_per_step": c, "avg_ms": round(t / c, 4)}
                                       for k, (c, t) in runner.timer.totals().items()},
                            "note": "every snapshot t = 1..T, including the copy of A_1 into the ring at the start of the pass"}
+    del runner
+    torch.cuda.empty_cache()
+    # training step on the smoothed snapshots: every S_t (and S_t^T) stays resident, the backward pass does no graph work
+    from dtdg_synth import gradient
+    from paper_2109_07893_amd.training import make_smoothed_trainer
+    tr = make_smoothed_trainer(wl, blk, life)
+    g_y = torch.stack([gradient(wl, t, dev) for t in range(1, blk.T + 1)])
+    tr.forward(); tr.backward(g_y)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        tr.forward(); tr.backward(g_y)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    tr.timer = StageTimer(dev)
+    tr.forward(); tr.backward(g_y)
+    torch.cuda.synchronize()
+    out["training_step"] = {"ms_per_step": round(ms, 3), "snapshots_per_step": blk.T,
+                            "stages": {k: {"calls_per_step": c, "avg_ms": round(t / c, 4)} for k, (c, t) in tr.timer.totals().items()}}
     return out
 
 

@@ -183,24 +183,35 @@ class BlockTrainer:
                     self._rebuild(self.at, self.t_deltas[t - 2], blk.nnz[t - 1], t, t - 1, reverse=True)
 
 
-def make_trainer(wl, blk: BlockInputs, want_dx: bool = False) -> BlockTrainer:
-    """Trainer for a generated block; for a directed workload the transposed first snapshot and lists are
-    prepared here with the generator's formatting helper."""
+def transposed_inputs(blk: BlockInputs):
+    """(rowptr, colidx) of A_1^T and the difference lists of the transposed series, prepared with the generator's
+    formatting helper (a sort by (col, row); input formatting, no arithmetic of the method)."""
     from dtdg_synth import transpose_coo
-    directed = wl.graph != "er"
-    if not directed:
-        return BlockTrainer(blk, False, want_dx=want_dx)
     n = blk.n
     rows = torch.repeat_interleave(torch.arange(n, dtype=torch.int32, device=blk.rowptr1.device),
                                    (blk.rowptr1[1:] - blk.rowptr1[:-1]).to(torch.int64))
     tr, tc = transpose_coo(rows, blk.colidx1)
-    counts = torch.bincount(tr.to(torch.int64), minlength=n)
     rowptr_t = torch.zeros(n + 1, dtype=torch.int32, device=tr.device)
-    rowptr_t[1:] = torch.cumsum(counts, 0).to(torch.int32)
-    t_deltas = []
-    for ar, ac, dr, dc in blk.deltas:
-        t_deltas.append(transpose_coo(ar, ac) + transpose_coo(dr, dc))
-    return BlockTrainer(blk, True, transposed_first=(rowptr_t, tc), transposed_deltas=t_deltas, want_dx=want_dx)
+    rowptr_t[1:] = torch.cumsum(torch.bincount(tr.to(torch.int64), minlength=n), 0).to(torch.int32)
+    return (rowptr_t, tc), [transpose_coo(ar, ac) + transpose_coo(dr, dc) for ar, ac, dr, dc in blk.deltas]
+
+
+def make_smoothed_trainer(wl, blk: BlockInputs, life: int) -> "SmoothedTrainer":
+    directed = wl.graph != "er"
+    if not directed:
+        return SmoothedTrainer(blk, life, False)
+    first, deltas = transposed_inputs(blk)
+    return SmoothedTrainer(blk, life, True, transposed_first=first, transposed_deltas=deltas)
+
+
+def make_trainer(wl, blk: BlockInputs, want_dx: bool = False) -> BlockTrainer:
+    """Trainer for a generated block; for a directed workload the transposed first snapshot and lists are
+    prepared here with the generator's formatting helper."""
+    directed = wl.graph != "er"
+    if not directed:
+        return BlockTrainer(blk, False, want_dx=want_dx)
+    first, t_deltas = transposed_inputs(blk)
+    return BlockTrainer(blk, True, transposed_first=first, transposed_deltas=t_deltas, want_dx=want_dx)
 
 
 class CheckpointedTrainer:
@@ -297,3 +308,162 @@ class CheckpointedTrainer:
             tr.forward()                                                    # the rerun
             after = g_y[e:min(e + w1, s.T)] if (w1 and e < s.T) else None
             tr.backward(g_y[a:e], g_after=after, accumulate=b != last)
+
+
+class _Ring:
+    """`slots` CSR slots used in turn by the raw snapshots A_1, A_2, ...: A_{t-life} is still resident when A_t is."""
+
+    def __init__(self, n, cap, dev, slots: int, with_dinv: bool):
+        self.slots = slots
+        self.rowptr = [torch.empty(n + 1, dtype=torch.int32, device=dev) for _ in range(slots)]
+        self.colidx = [torch.empty(cap, dtype=torch.int32, device=dev) for _ in range(slots)]
+        self.dinv = [torch.empty(n, dtype=torch.float32, device=dev) if with_dinv else None for _ in range(slots)]
+
+    def slot_of(self, t: int) -> int:
+        return t % self.slots
+
+    def load_first(self, rowptr1, colidx1) -> None:
+        s = self.slot_of(1)
+        self.rowptr[s].copy_(rowptr1)
+        self.colidx[s][: colidx1.numel()].copy_(colidx1)
+
+    def snapshot(self, t: int, nnz: int):
+        s = self.slot_of(t)
+        return self.rowptr[s], self.colidx[s], nnz
+
+
+class SmoothedTrainer:
+    """A training step on SMOOTHED snapshots (Section "Smoothening the Input Graphs": the graphs TM-GCN and EvolveGCN
+    are trained on), with the smoothing done on the device.  Forward: the raw A_t by dgnn_delta_rebuild,
+    S_t = S_{t-1} + A_t - A_{t-life} by dgnn_csr_combine, its normalisation by dgnn_csr_weighted_dinv, then per layer
+    H = X W and Z = relu(D^(-1/2) S_t D^(-1/2) H) with the counts as values (dgnn_spmm_weighted).  Every S_t stays
+    resident (index and value arrays of all T smoothed snapshots: 21 GB at c5's size; and as many again for the
+    transposed ones of a directed workload), so the backward pass needs no graph work at all: it is the one of
+    BlockTrainer with the weighted aggregation on S_t^T.  Buffers and call order only."""
+
+    def __init__(self, blk: BlockInputs, life: int, directed: bool,
+                 transposed_first: Optional[Tuple[torch.Tensor, torch.Tensor]] = None,
+                 transposed_deltas: Optional[List[Tuple[torch.Tensor, ...]]] = None):
+        self.blk, self.life, self.directed = blk, life, directed
+        dev = blk.rowptr1.device
+        self.dev = dev
+        n, f, T, L = blk.n, blk.f, blk.T, blk.layers
+        dt = blk.x[0].dtype
+        cap = max(blk.nnz)
+        max_del = max([int(d[2].numel()) for d in blk.deltas] + [0])
+        max_list = max([int(d[0].numel()) for d in blk.deltas] + [max_del, 1])
+        self.cap_s = cap + life * max_del                  # the window's union: A_t and what the window's steps deleted
+        self.raw = _Ring(n, cap, dev, life + 1, with_dinv=False)
+        self.raw_t = _Ring(n, cap, dev, life + 1, with_dinv=False) if directed else None
+        self.t_first, self.t_deltas = transposed_first, transposed_deltas
+        if directed:
+            assert transposed_first is not None and transposed_deltas is not None
+
+        def smoothed_slots():
+            return [(torch.empty(n + 1, dtype=torch.int32, device=dev), torch.empty(self.cap_s, dtype=torch.int32, device=dev),
+                     torch.empty(self.cap_s, dtype=torch.float32, device=dev)) for _ in range(T)]
+        self.s = smoothed_slots()
+        self.st = smoothed_slots() if directed else self.s
+        self.s_nnz = [0] * T
+        self.dinv_s = torch.empty((T, n), dtype=torch.float32, device=dev)
+        self.z = torch.empty((L, T, n, f), dtype=dt, device=dev)
+        self.y = torch.empty((T, n, f), dtype=dt, device=dev) if blk.window else None
+        self.g = None
+        self.h = torch.empty((n, f), dtype=dt, device=dev)
+        self.gp = torch.empty((n, f), dtype=dt, device=dev)
+        self.g_mid = torch.empty((n, f), dtype=dt, device=dev) if L > 1 else None
+        self.dw = [torch.zeros((f, f), dtype=torch.float32, device=dev) for _ in range(L)]
+        self.ws_rebuild = torch.empty(B.delta_rebuild_workspace(n, cap, max_list, max_list), dtype=torch.uint8, device=dev)
+        self.ws_combine = torch.empty(B.csr_combine_workspace(self.cap_s), dtype=torch.uint8, device=dev)
+        self.ws_dinv = torch.empty(B.csr_weighted_dinv_workspace(self.cap_s), dtype=torch.uint8, device=dev)
+        self.ws_spmm = torch.empty(B.spmm_workspace(n, self.cap_s, f), dtype=torch.uint8, device=dev)
+        self.ws_wgrad = torch.empty(B.weight_grad_workspace(f, f), dtype=torch.uint8, device=dev)
+        self.timer = None
+
+    def _stage(self, name):
+        import contextlib
+        return self.timer.stage(name) if self.timer is not None else contextlib.nullcontext()
+
+    def _advance(self, ring: _Ring, lists, t: int) -> None:
+        ar, ac, dr, dc = lists
+        s, d = ring.slot_of(t - 1), ring.slot_of(t)
+        with self._stage("delta_rebuild"):
+            B.delta_rebuild(ring.rowptr[s], ring.colidx[s], self.blk.nnz[t - 2], ar, ac, int(ar.numel()), dr, dc, int(dr.numel()),
+                            ring.rowptr[d], ring.colidx[d], None, self.ws_rebuild)
+
+    def _smooth(self, ring: _Ring, store, t: int) -> int:
+        """store[t-1] <- S_t (t >= 2) from store[t-2], A_t and A_{t-life}; returns its number of stored entries."""
+        blk = self.blk
+        prev = store[t - 2] + (self.s_nnz[t - 2],)
+        a_out = ring.snapshot(t - self.life, blk.nnz[t - self.life - 1]) if t - self.life >= 1 else None
+        with self._stage("csr_combine"):
+            return B.csr_combine(prev, ring.snapshot(t, blk.nnz[t - 1]), 1.0, a_out, -1.0, store[t - 1], self.ws_combine)
+
+    def forward(self) -> torch.Tensor:
+        blk = self.blk
+        self.raw.load_first(blk.rowptr1, blk.colidx1)
+        if self.directed:
+            self.raw_t.load_first(*self.t_first)
+        for t in range(1, blk.T + 1):
+            if t == 1:                                  # S_1 = A_1, every entry counted once
+                for store, (rp1, ci1) in ((self.s, (blk.rowptr1, blk.colidx1)),) + (((self.st, self.t_first),) if self.directed else ()):
+                    store[0][0].copy_(rp1)
+                    store[0][1][: blk.nnz[0]].copy_(ci1)
+                    store[0][2][: blk.nnz[0]].fill_(1.0)
+                self.s_nnz[0] = blk.nnz[0]
+            else:
+                self._advance(self.raw, blk.deltas[t - 2], t)
+                nnz = self._smooth(self.raw, self.s, t)
+                if self.directed:
+                    self._advance(self.raw_t, self.t_deltas[t - 2], t)
+                    assert self._smooth(self.raw_t, self.st, t) == nnz
+                self.s_nnz[t - 1] = nnz
+            rp, ci, val = self.s[t - 1]
+            nnz = self.s_nnz[t - 1]
+            with self._stage("csr_weighted_dinv"):
+                B.csr_weighted_dinv(rp, val, nnz, self.dinv_s[t - 1], self.ws_dinv)
+            cur = blk.x[t - 1]
+            for layer in range(blk.layers):
+                with self._stage("feature_transform"):
+                    B.feature_transform(cur, blk.weight(t, layer), self.h, row_scale=self.dinv_s[t - 1])
+                with self._stage("spmm_weighted"):
+                    B.spmm_weighted(rp, ci, val, nnz, self.h, self.z[layer, t - 1], self.ws_spmm,
+                                    flags=B.DGNN_RELU | B.DGNN_H_PRESCALED, dinv=self.dinv_s[t - 1])
+                cur = self.z[layer, t - 1]
+        top = self.z[blk.layers - 1]
+        if blk.window:
+            with self._stage("mproduct"):
+                B.mproduct_block(top, self.y, blk.window, 0)
+            return self.y
+        return top
+
+    def backward(self, g_y: torch.Tensor) -> None:
+        """g_y [T, n, f] = dL/dY.  Must follow forward()."""
+        blk = self.blk
+        L, T = blk.layers, blk.T
+        if blk.window:
+            if self.g is None:
+                self.g = torch.empty_like(g_y)
+            with self._stage("mproduct_backward"):
+                B.mproduct_backward_block(g_y, self.g, blk.window, 0)
+            g_top = self.g
+        else:
+            g_top = g_y
+        first_call = [True] * L
+        for t in range(T, 0, -1):
+            rp, ci, val = self.st[t - 1]                 # S_t^T (S_t itself for an undirected workload)
+            nnz, dinv = self.s_nnz[t - 1], self.dinv_s[t - 1]
+            g_in = g_top[t - 1]
+            for layer in range(L - 1, -1, -1):
+                with self._stage("relu_backward"):
+                    B.relu_backward(g_in, self.z[layer, t - 1], self.gp, row_scale=dinv)
+                with self._stage("spmm_weighted_transposed"):
+                    B.spmm_weighted(rp, ci, val, nnz, self.gp, self.h, self.ws_spmm, flags=B.DGNN_H_PRESCALED, dinv=dinv)
+                below = blk.x[t - 1] if layer == 0 else self.z[layer - 1, t - 1]
+                with self._stage("weight_grad"):
+                    B.weight_grad(below, self.h, self.dw[layer], self.ws_wgrad, accumulate=not first_call[layer])
+                first_call[layer] = False
+                if layer > 0:
+                    with self._stage("input_grad"):
+                        B.input_grad(self.h, blk.weight(t, layer), self.g_mid)
+                    g_in = self.g_mid

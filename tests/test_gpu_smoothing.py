@@ -187,3 +187,55 @@ def test_combine_random_shapes(seed):
     val = None if rng.random() < 0.3 else rng.integers(1, 5, s[1].size).astype(np.float64)
     alpha, beta = float(rng.choice([1.0, 2.0, 0.5])), float(rng.choice([-1.0, -2.0, 1.0]))
     check(n, s + (val,), a_in if rng.random() < 0.85 else None, alpha, a_out if rng.random() < 0.7 else None, beta, f"seed {seed}")
+
+
+@pytest.mark.parametrize("name,n,T,life", [("c2", 20_000, 6, 3), ("c3", 1 << 12, 5, 2), ("c1", 1000, 8, 4)])
+def test_training_step_on_smoothed_snapshots(name, n, T, life):
+    """Forward and backward on smoothed snapshots (the graphs TM-GCN and EvolveGCN train on), smoothing on the
+    device, every S_t (and S_t^T for the directed workload) kept resident; weight gradients against the oracle."""
+    from dtdg_synth import gradient
+    from helpers import assert_close, to_f64
+    from paper_2109_07893_amd.pipeline import make_block
+    from paper_2109_07893_amd.training import make_smoothed_trainer
+    wl = WORKLOADS[name].scaled(n, T=T) if n != WORKLOADS[name].n else WORKLOADS[name]
+    T = min(T, wl.T)
+    blk = make_block(wl, DEV, gen_device="cpu", T=T)
+    tr = make_smoothed_trainer(wl, blk, life)
+    g_y = torch.stack([gradient(wl, t, "cpu") for t in range(1, T + 1)]).to(DEV)
+    for _ in range(2):
+        y = tr.forward()
+        tr.backward(g_y)
+    torch.cuda.synchronize()
+    # oracle
+    raw = DynamicGraph(wl)
+    rp, ci = (x.numpy() for x in raw.csr())
+    snaps, sm, zs = [(rp, ci)], [], []
+    ws = [to_f64(w) for w in blk.w]
+    for t in range(1, T + 1):
+        if t >= 2:
+            rp, ci = oracle.delta_apply(wl.n, rp, ci, *[x.numpy() for x in raw.advance()])
+            snaps.append((rp, ci))
+        s = snaps[max(0, t - life)] + (None,)
+        for other in snaps[max(0, t - life) + 1:t]:
+            s = oracle.csr_combine(wl.n, s, other, 1.0)
+        val = oracle.gcn_values_weighted(s[0], s[1], np.ones(s[1].size) if s[2] is None else s[2])
+        sm.append((s[0], s[1], val))
+        acts = [to_f64(blk.x[t - 1])]
+        for w in ws:
+            acts.append(oracle.spmm(s[0], s[1], oracle.xw(acts[-1], w), relu=True, val=val))
+        zs.append(acts)
+    top = np.stack([a[-1] for a in zs])
+    M = oracle.m_matrix(T, wl.window) if wl.window else None
+    assert_close(to_f64(y), oracle.mproduct(top, M) if wl.window else top, y.dtype, f"{name}: smoothed forward",
+                 stores=blk.layers + (1 if wl.window else 0))
+    g_top = oracle.mproduct_t(to_f64(g_y), M) if wl.window else to_f64(g_y)
+    d_w = [0.0] * len(ws)
+    for t in range(T, 0, -1):
+        g = g_top[t - 1]
+        for layer in range(len(ws) - 1, -1, -1):
+            g_h = oracle.spmm_t(sm[t - 1][0], sm[t - 1][1], oracle.relu_grad(g, zs[t - 1][layer + 1]), val=sm[t - 1][2])
+            d_w[layer] = d_w[layer] + oracle.weight_grad(zs[t - 1][layer], g_h)
+            g = oracle.input_grad(g_h, ws[layer])
+    for layer in range(len(ws)):
+        err = np.abs(to_f64(tr.dw[layer]) - d_w[layer]).max()
+        assert err <= 3e-4 * np.abs(d_w[layer]).max(), f"{name} dW[{layer}]: max err {err:.3e} against {np.abs(d_w[layer]).max():.3e}"
