@@ -373,6 +373,9 @@ class SmoothedTrainer:
         self.gp = torch.empty((n, f), dtype=dt, device=dev)
         self.g_mid = torch.empty((n, f), dtype=dt, device=dev) if L > 1 else None
         self.dw = [torch.zeros((f, f), dtype=torch.float32, device=dev) for _ in range(L)]
+        # with one weight per timestep (Section "EvolveGCN") every timestep has a gradient of its own
+        self.dw_t = ([[torch.zeros((f, f), dtype=torch.float32, device=dev) for _ in range(L)] for _ in range(T)]
+                     if blk.w_t is not None else None)
         self.ws_rebuild = torch.empty(B.delta_rebuild_workspace(n, cap, max_list, max_list), dtype=torch.uint8, device=dev)
         self.ws_combine = torch.empty(B.csr_combine_workspace(self.cap_s), dtype=torch.uint8, device=dev)
         self.ws_dinv = torch.empty(B.csr_weighted_dinv_workspace(self.cap_s), dtype=torch.uint8, device=dev)
@@ -461,7 +464,10 @@ class SmoothedTrainer:
                     B.spmm_weighted(rp, ci, val, nnz, self.gp, self.h, self.ws_spmm, flags=B.DGNN_H_PRESCALED, dinv=dinv)
                 below = blk.x[t - 1] if layer == 0 else self.z[layer - 1, t - 1]
                 with self._stage("weight_grad"):
-                    B.weight_grad(below, self.h, self.dw[layer], self.ws_wgrad, accumulate=not first_call[layer])
+                    if self.dw_t is not None:
+                        B.weight_grad(below, self.h, self.dw_t[t - 1][layer], self.ws_wgrad)
+                    else:
+                        B.weight_grad(below, self.h, self.dw[layer], self.ws_wgrad, accumulate=not first_call[layer])
                 first_call[layer] = False
                 if layer > 0:
                     with self._stage("input_grad"):

@@ -239,3 +239,53 @@ def test_training_step_on_smoothed_snapshots(name, n, T, life):
     for layer in range(len(ws)):
         err = np.abs(to_f64(tr.dw[layer]) - d_w[layer]).max()
         assert err <= 3e-4 * np.abs(d_w[layer]).max(), f"{name} dW[{layer}]: max err {err:.3e} against {np.abs(d_w[layer]).max():.3e}"
+
+
+def test_evolvegcn_on_smoothed_snapshots():
+    """The EvolveGCN model of the paper in one piece: edge-life smoothing on the device, one GCN weight per timestep
+    produced by the LSTM over the weights, and the loss's gradient carried back through the GCN steps and the
+    weight recurrence; against the oracle's chain."""
+    from dtdg_synth import features, gradient
+    from helpers import assert_close, to_f64
+    from paper_2109_07893_amd.evolve import EvolvingWeights
+    from paper_2109_07893_amd.pipeline import make_block
+    from paper_2109_07893_amd.training import make_smoothed_trainer
+    wl = WORKLOADS["c3"].scaled(1 << 12, T=5)
+    T, f, life = wl.T, wl.f, 3
+    gen = torch.Generator().manual_seed(9)
+    w0 = torch.randn((f, f), generator=gen) / np.sqrt(f)
+    u_x, u_h = (torch.randn((f, 4 * f), generator=gen) / np.sqrt(f) for _ in range(2))
+    bias = torch.randn(4 * f, generator=gen) * 0.1
+    ev = EvolvingWeights(w0.to(DEV), u_x.to(DEV), u_h.to(DEV), bias.to(DEV), T)
+    blk = make_block(wl, DEV, gen_device="cpu")
+    blk.w_t = [[w] for w in ev.forward()]
+    tr = make_smoothed_trainer(wl, blk, life)
+    g_y = torch.stack([gradient(wl, t, "cpu") for t in range(1, T + 1)]).to(DEV)
+    for _ in range(2):
+        ev.forward()
+        tr.forward()
+        tr.backward(g_y)
+        ev.backward([tr.dw_t[t][0] for t in range(T)])
+    torch.cuda.synchronize()
+    W0, UX, UH, Bv = (to_f64(x) for x in (w0, u_x, u_h, bias))
+    ws, _ = oracle.evolve_weights(W0, UX, UH, Bv, T)
+    raw = DynamicGraph(wl)
+    rp, ci = (x.numpy() for x in raw.csr())
+    snaps, d_w = [(rp, ci)], []
+    for t in range(1, T + 1):
+        if t >= 2:
+            rp, ci = oracle.delta_apply(wl.n, rp, ci, *[x.numpy() for x in raw.advance()])
+            snaps.append((rp, ci))
+        s = snaps[max(0, t - life)] + (None,)
+        for other in snaps[max(0, t - life) + 1:t]:
+            s = oracle.csr_combine(wl.n, s, other, 1.0)
+        val = oracle.gcn_values_weighted(s[0], s[1], np.ones(s[1].size) if s[2] is None else s[2])
+        x = to_f64(features(wl, t))
+        z = oracle.spmm(s[0], s[1], oracle.xw(x, ws[t - 1]), relu=True, val=val)
+        assert_close(to_f64(tr.z[0, t - 1]), z, torch.float32, f"Z_{t}")
+        g_h = oracle.spmm_t(s[0], s[1], oracle.relu_grad(to_f64(g_y[t - 1]), z), val=val)
+        d_w.append(oracle.weight_grad(x, g_h))
+    want = oracle.evolve_weights_backward(W0, UX, UH, Bv, d_w)
+    for name, got, exp in (("dU_x", ev.du_x, want[0]), ("dU_h", ev.du_h, want[1]), ("db", ev.db, want[2]), ("dW_0", ev.dw0, want[3])):
+        err = np.abs(to_f64(got) - exp).max()
+        assert err <= 3e-4 * np.abs(exp).max(), f"{name}: max err {err:.3e} against max |.| {np.abs(exp).max():.3e}"
