@@ -6,9 +6,17 @@ include/dgnn.h; this package only marshals torch tensors (used for device memory
 into those calls.  There is no CPU fallback: without the built library the calls raise.
 """
 from .binding import (  # noqa: F401
-    DgnnError, build_library, library_path, load_library,
-    csr_dinv, delta_h2d, delta_rebuild, delta_rebuild_workspace, feature_transform,
-    spmm, spmm_workspace, mproduct, strerror, delta_rebuild_weighted, spmm_weighted, csr_weighted_dinv, csr_weighted_dinv_workspace, csr_combine, csr_combine_workspace, concat_relu, lstm_cell, lstm_step, lstm_step_supported, lstm_cell_backward, lstm_step_backward, lstm_step_backward_supported, concat_relu_backward, bias_grad, bias_grad_workspace, add,
-    mproduct_backward, mproduct_block, mproduct_backward_block, relu_backward, weight_grad, weight_grad_workspace, input_grad,
+    DgnnError, build_library, library_path, load_library, strerror,
+    # the hot path
+    csr_dinv, delta_h2d, delta_rebuild, delta_rebuild_workspace, feature_transform, spmm, spmm_workspace, mproduct,
+    # its backward half, and a series processed in blocks
+    mproduct_backward, mproduct_block, mproduct_backward_block, relu_backward, weight_grad, weight_grad_workspace,
+    input_grad,
+    # snapshots that carry values; smoothing on the device
+    delta_rebuild_weighted, spmm_weighted, csr_weighted_dinv, csr_weighted_dinv_workspace, csr_combine,
+    csr_combine_workspace,
+    # CD-GCN layer and the LSTM over weights
+    concat_relu, lstm_cell, lstm_step, lstm_step_supported, lstm_cell_backward, lstm_step_backward,
+    lstm_step_backward_supported, concat_relu_backward, bias_grad, bias_grad_workspace, add,
     DGNN_VALIDATE, DGNN_RELU, DGNN_H_PRESCALED, DGNN_F32, DGNN_BF16,
 )
