@@ -157,12 +157,16 @@ __global__ __launch_bounds__(kWave) void combine_kernel(Operands P, int n_ranges
     const int lane = threadIdx.x, range = blockIdx.x;
     const int e0 = (int)min((int64_t)range * kRange, (int64_t)P.nnz_s), e1 = (int)min((int64_t)e0 + kRange, (int64_t)P.nnz_s);
     const bool last = range == n_ranges - 1;
-    if (P.nnz_s > 0)
-        for (int i = lane; i < kRange; i += kWave) {               // unconditional (clamped): the loads stay in flight together
-            const int src = min(e0 + i, P.nnz_s - 1);
-            s_col[i] = P.col_s[src];
-            s_val[i] = P.val_s ? P.val_s[src] : 1.0f;
-        }
+    // S's entries go to registers first and to LDS only after the other spans' loads have been issued as well, so that
+    // everything a range needs is one round of loads in flight together
+    int sc[kPer];
+    float sv[kPer];
+#pragma unroll
+    for (int q = 0; q < kPer; ++q) {                               // unconditional (clamped)
+        const int src = max(min(e0 + q * kWave + lane, P.nnz_s - 1), 0);
+        sc[q] = P.nnz_s > 0 ? P.col_s[src] : 0;
+        sv[q] = (P.nnz_s > 0 && P.val_s) ? P.val_s[src] : 1.0f;
+    }
     // the range's own boundaries (found beforehand by bounds_kernel: one chain of dependent look-ups per range,
     // which the few wavefronts that fit beside this kernel's LDS could not hide)
     const Terms<false> G{nullptr, nullptr, nullptr, nullptr, nullptr, P.col_a, P.col_o, P.rp_s, P.rp_a, P.rp_o, 0, 0, 0};
@@ -171,13 +175,36 @@ __global__ __launch_bounds__(kWave) void combine_kernel(Operands P, int n_ranges
     const int row_lo = max(B0.k - 1, 0), row_hi = B1.k;
     const bool staged = B1.a - B0.a <= kCapIn && B1.o - B0.o <= kCapOut && row_hi - row_lo + 1 <= kCapRows;
     if (staged) {
-        for (int i = B0.a + lane; i < B1.a; i += kWave) s_a[i - B0.a] = P.col_a[i];
-        for (int i = B0.o + lane; i < B1.o; i += kWave) s_o[i - B0.o] = P.col_o[i];
-        for (int r = row_lo + lane; r <= row_hi; r += kWave) {
-            s_rs[r - row_lo] = P.rp_s[r];
-            s_ra[r - row_lo] = P.rp_a ? P.rp_a[r] : 0;
-            s_ro[r - row_lo] = P.rp_o ? P.rp_o[r] : 0;
+        // Fixed numbers of loads with clamped addresses, all issued before the first is waited for: loops over the
+        // spans' actual lengths would wait for every load before issuing the next (a round trip per 64 terms).
+        int va[kCapIn / kWave], vo[kCapOut / kWave], vrs[kCapRows / kWave], vra[kCapRows / kWave], vro[kCapRows / kWave];
+#pragma unroll
+        for (int q = 0; q < kCapIn / kWave; ++q) va[q] = P.nnz_a > 0 ? P.col_a[min(B0.a + q * kWave + lane, P.nnz_a - 1)] : 0;
+#pragma unroll
+        for (int q = 0; q < kCapOut / kWave; ++q) vo[q] = P.nnz_o > 0 ? P.col_o[min(B0.o + q * kWave + lane, P.nnz_o - 1)] : 0;
+#pragma unroll
+        for (int q = 0; q < kCapRows / kWave; ++q) {
+            const int r = min(row_lo + q * kWave + lane, P.n);
+            vrs[q] = P.rp_s[r];
+            vra[q] = P.rp_a ? P.rp_a[r] : 0;
+            vro[q] = P.rp_o ? P.rp_o[r] : 0;
         }
+#pragma unroll
+        for (int q = 0; q < kCapIn / kWave; ++q) if (B0.a + q * kWave + lane < B1.a) s_a[q * kWave + lane] = va[q];
+#pragma unroll
+        for (int q = 0; q < kCapOut / kWave; ++q) if (B0.o + q * kWave + lane < B1.o) s_o[q * kWave + lane] = vo[q];
+#pragma unroll
+        for (int q = 0; q < kCapRows / kWave; ++q)
+            if (row_lo + q * kWave + lane <= row_hi) {
+                s_rs[q * kWave + lane] = vrs[q];
+                s_ra[q * kWave + lane] = vra[q];
+                s_ro[q * kWave + lane] = vro[q];
+            }
+    }
+#pragma unroll
+    for (int q = 0; q < kPer; ++q) {
+        s_col[q * kWave + lane] = sc[q];
+        s_val[q * kWave + lane] = sv[q];
     }
     wave_lds_sync();
 
