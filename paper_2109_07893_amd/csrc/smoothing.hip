@@ -157,6 +157,13 @@ __global__ __launch_bounds__(kWave) void combine_kernel(Operands P, int n_ranges
     const int lane = threadIdx.x, range = blockIdx.x;
     const int e0 = (int)min((int64_t)range * kRange, (int64_t)P.nnz_s), e1 = (int)min((int64_t)e0 + kRange, (int64_t)P.nnz_s);
     const bool last = range == n_ranges - 1;
+    // (write pass) what the count pass and the scans left for this range, fetched with everything else
+    int counted = 0;
+    int64_t range_begin = 0;
+    if (WRITE) {
+        counted = lane_counts[(int64_t)range * kWave + lane];
+        range_begin = (int64_t)totals[range] + tile_off[range / kScanTile];   // both scan levels
+    }
     // S's entries go to registers first and to LDS only after the other spans' loads have been issued as well, so that
     // everything a range needs is one round of loads in flight together
     int sc[kPer];
@@ -223,9 +230,8 @@ __global__ __launch_bounds__(kWave) void combine_kernel(Operands P, int n_ranges
         if (lane == kWave - 1 || sb1 >= e1) next = B1;
         int64_t begin = 0;
         if (WRITE) {
-            const int mine_cnt = active ? lane_counts[(int64_t)range * kWave + lane] : 0;
+            const int mine_cnt = active ? counted : 0;
             const int incl = wave_scan_add(mine_cnt, lane);
-            const int64_t range_begin = (int64_t)totals[range] + tile_off[range / kScanTile];   // both scan levels
             begin = range_begin + incl - mine_cnt;
             if (last && lane == kWave - 1) rowptr_out[P.n] = (int32_t)(range_begin + incl);
         }
