@@ -402,3 +402,32 @@ def test_evolving_weights_backward_matches_finite_differences():
     ws, cs = oracle.evolve_weights(w0, u_x, u_h, b, 1)
     h, c = oracle.lstm_cell(w0, w0, np.zeros_like(w0), u_x, u_h, b)
     assert np.array_equal(ws[0], h) and np.array_equal(cs[1], c)
+
+
+def test_edge_life_smoothing_matches_hand_worked_series():
+    """The hand-worked series in tests/golden/edge_life_n3.txt: sliding-window sums by csr_combine, then the weighted
+    form of Eqn (1) on S_3."""
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "edge_life_n3.txt")
+    want = [np.array([[float(x) for x in row.split()] for row in line.split(";")])
+            for line in open(path) if not line.startswith("#")]
+    n, life = 3, 2
+    off = [[(0, 1)], [(0, 1), (1, 2)], [(1, 2), (2, 0)], [(2, 0)]]
+    snaps = []
+    for edges in off:
+        rows = [u for u, _ in edges] + list(range(n))
+        cols = [v for _, v in edges] + list(range(n))
+        snaps.append(oracle.csr_from_edges(n, np.array(rows), np.array(cols)))
+    s = snaps[0] + (None,)
+    got = [s]
+    for t in range(2, 5):
+        s = oracle.csr_combine(n, s, snaps[t - 1], 1.0, snaps[t - 1 - life] if t - life >= 1 else None, -1.0)
+        got.append(s)
+    for t, (g, w) in enumerate(zip(got, want), start=1):
+        val = np.ones(g[1].size) if g[2] is None else g[2]
+        dense = np.nan_to_num(_dense_weighted(n, g[0], g[1], val), nan=0.0)
+        assert np.array_equal(dense, w), f"S_{t}"
+        assert g[1].size == np.count_nonzero(w)               # an edge that left the window is not stored
+    s3 = got[2]
+    norm = oracle.gcn_values_weighted(s3[0], s3[1], s3[2])
+    np.testing.assert_allclose(norm, [2 / 3, 1 / np.sqrt(12), 2 / 4, 2 / np.sqrt(12), 1 / 3, 2 / 3], rtol=1e-15)

@@ -136,7 +136,7 @@ PY_MUTANTS = [
 
 def py_pins():
     calls = [bwd.test_weighted_normalisation_reduces_to_eqn_1_and_matches_the_dense_form, bwd.test_csr_combine_special_cases,
-             bwd.test_sliding_window_sum_by_csr_combine_equals_the_windowed_sum,
+             bwd.test_sliding_window_sum_by_csr_combine_equals_the_windowed_sum, bwd.test_edge_life_smoothing_matches_hand_worked_series,
              bwd.test_lstm_cell_backward_matches_finite_differences, bwd.test_cdgcn_gcn_backward_matches_finite_differences,
              bwd.test_evolving_weights_backward_matches_finite_differences]
     for seed in (0, 1, 2):
