@@ -245,7 +245,7 @@ int dgnn_csr_weighted_dinv(int64_t n, int64_t nnz, const int32_t *rowptr, const 
  *   captured in a HIP graph; smoothing is pre-processing, outside the training step.
  *   ws: device scratch of at least dgnn_csr_combine_workspace(nnz_s) bytes.
  * All device pointers except nnz_c.  Errors: NULL, SHAPE, OVERFLOW (nnz_s + nnz_in + nnz_out_of beyond the index
- * range), CAPACITY, ALIAS, HIP.
+ * range), CAPACITY, ALIAS, ALIGN (ws not 16-byte aligned), HIP.
  */
 int dgnn_csr_combine_workspace(int64_t nnz_s, size_t *bytes);
 int dgnn_csr_combine(int64_t n, const int32_t *rowptr_s, const int32_t *colidx_s, const float *val_s, int64_t nnz_s,

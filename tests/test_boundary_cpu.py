@@ -232,6 +232,7 @@ def test_csr_combine_argument_errors(lib):
     assert call(nnz_s=(1 << 31) - (1 << 16) - 10, nnz_a=100) == -4
     assert call(ws_bytes=4) == -3
     assert call(rp_c=FAKE) == -5 and call(ci_c=FAKE) == -5
+    assert call(ws=FAKE + 16384 + 4) == -7
     b = ctypes.c_size_t(0)
     assert lib.dgnn_csr_combine_workspace(1 << 20, ctypes.byref(b)) == 0 and b.value >= 4 * ((1 << 10) + 1)
     assert lib.dgnn_csr_combine_workspace(-1, ctypes.byref(b)) == -2
