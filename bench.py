@@ -259,6 +259,15 @@ def smoothing_steps(args, wl, blk, dev, life=4):
     # training step on the smoothed snapshots: every S_t (and S_t^T) stays resident, the backward pass does no graph work
     from dtdg_synth import gradient
     from paper_2109_07893_amd.training import make_smoothed_trainer
+    # as many timesteps as fit beside the inputs: activations, M-transformed output and two gradient tensors per frame,
+    # index and value arrays per smoothed snapshot (twice for a directed workload)
+    free, _ = torch.cuda.mem_get_info(dev)
+    per_t = 4 * blk.n * blk.f * blk.x[0].element_size() * max(blk.layers, 1) + 2 * 8 * int(max(blk.nnz) * 1.3)
+    t_fit = max(2, min(blk.T, int(0.6 * free / per_t)))
+    if t_fit < blk.T:
+        from paper_2109_07893_amd.pipeline import BlockInputs
+        blk = BlockInputs(n=blk.n, T=t_fit, f=blk.f, layers=blk.layers, window=blk.window, rowptr1=blk.rowptr1,
+                          colidx1=blk.colidx1, deltas=blk.deltas[:t_fit - 1], x=blk.x[:t_fit], w=blk.w, nnz=list(blk.nnz[:t_fit]))
     tr = make_smoothed_trainer(wl, blk, life)
     g_y = torch.stack([gradient(wl, t, dev) for t in range(1, blk.T + 1)])
     tr.forward(); tr.backward(g_y)
@@ -283,6 +292,8 @@ def cdgcn_layer(args, wl, blk, dev):
     from paper_2109_07893_amd.cdgcn import CdgcnLayer
     from paper_2109_07893_amd.pipeline import StageTimer
     f, hidden = blk.f, 32
+    if 2 * f > 128:
+        return {"skipped": f"the layer's concatenated output is {2 * f} wide; the dense transform takes widths up to 128"}
     dt = blk.x[0].dtype
     gen = torch.Generator(device=dev).manual_seed(wl.seed)
     w_x = (torch.randn((2 * f, 4 * hidden), generator=gen, device=dev) / math.sqrt(2 * f)).to(dt)
