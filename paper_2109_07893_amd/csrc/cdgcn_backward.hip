@@ -172,7 +172,15 @@ __global__ __launch_bounds__(kThreads) void column_sum_reduce_kernel(const float
     const int c = blockIdx.x * kThreads + threadIdx.x;
     if (c >= f) return;
     float s = 0.0f;
-    for (int b = 0; b < blocks; ++b) s += partial[(int64_t)b * f + c];
+    int b = 0;
+    for (; b + 16 <= blocks; b += 16) {                  // sixteen loads in flight, added in workgroup order
+        float v[16];
+#pragma unroll
+        for (int q = 0; q < 16; ++q) v[q] = partial[(int64_t)(b + q) * f + c];
+#pragma unroll
+        for (int q = 0; q < 16; ++q) s += v[q];
+    }
+    for (; b < blocks; ++b) s += partial[(int64_t)b * f + c];
     db[c] = accumulate ? db[c] + s : s;
 }
 
