@@ -12,37 +12,7 @@ namespace {
 
 using namespace dgnn;
 
-typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
-
 constexpr int kThreads = 256;
-
-template <bool BF16> struct Pack;
-template <> struct Pack<false> {
-    static constexpr int kVals = 4;
-    static __device__ __forceinline__ void unpack(float (&v)[4], uintx4 t) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = __uint_as_float(t[e]);
-    }
-    static __device__ __forceinline__ uintx4 pack(const float (&v)[4]) {
-        return uintx4{__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])};
-    }
-};
-template <> struct Pack<true> {
-    static constexpr int kVals = 8;
-    static __device__ __forceinline__ void unpack(float (&v)[8], uintx4 t) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            v[2 * e] = __uint_as_float(t[e] << 16);
-            v[2 * e + 1] = __uint_as_float(t[e] & 0xffff0000u);
-        }
-    }
-    static __device__ __forceinline__ uintx4 pack(const float (&v)[8]) {
-        uintx4 t;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) t[e] = f32_to_bf16(v[2 * e]) | (f32_to_bf16(v[2 * e + 1]) << 16);
-        return t;
-    }
-};
 
 // out[r] = relu(y0[r] o y1[r]); p0, p1 = 16-byte pieces per row of y0, y1.
 template <bool BF16>
@@ -61,8 +31,6 @@ __global__ __launch_bounds__(kThreads) void concat_relu_kernel(const uintx4 *__r
     for (int e = 0; e < NV; ++e) v[e] = fmaxf(v[e], 0.0f);
     out[p] = Pack<BF16>::pack(v);
 }
-
-__device__ __forceinline__ float sigmoidf(float x) { return 1.0f / (1.0f + expf(-x)); }
 
 // One 16-byte piece of the state per lane; the four gates of that piece lie `hp` pieces apart in a row of gates.
 template <bool BF16>

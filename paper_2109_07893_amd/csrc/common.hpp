@@ -87,4 +87,37 @@ __device__ __forceinline__ uint32_t f32_to_bf16(float f) {
     return u >> 16;
 }
 
+// ---- 16-byte pieces of feature rows: 4 fp32 or 8 bf16 values, unpacked to and packed from fp32 ------------
+typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
+
+template <bool BF16> struct Pack;
+template <> struct Pack<false> {
+    static constexpr int kVals = 4;
+    static __device__ __forceinline__ void unpack(float (&v)[4], uintx4 t) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = __uint_as_float(t[e]);
+    }
+    static __device__ __forceinline__ uintx4 pack(const float (&v)[4]) {
+        return uintx4{__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])};
+    }
+};
+template <> struct Pack<true> {
+    static constexpr int kVals = 8;
+    static __device__ __forceinline__ void unpack(float (&v)[8], uintx4 t) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            v[2 * e] = __uint_as_float(t[e] << 16);
+            v[2 * e + 1] = __uint_as_float(t[e] & 0xffff0000u);
+        }
+    }
+    static __device__ __forceinline__ uintx4 pack(const float (&v)[8]) {
+        uintx4 t;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) t[e] = f32_to_bf16(v[2 * e]) | (f32_to_bf16(v[2 * e + 1]) << 16);
+        return t;
+    }
+};
+
+__device__ __forceinline__ float sigmoidf(float x) { return 1.0f / (1.0f + expf(-x)); }
+
 }  // namespace dgnn

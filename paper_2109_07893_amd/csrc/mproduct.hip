@@ -30,7 +30,6 @@ struct Halo {
 };
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
 

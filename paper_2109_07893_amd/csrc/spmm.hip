@@ -31,7 +31,6 @@ namespace {
 using namespace dgnn;
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBatch = 8;            // gathers issued together by a lane group
 constexpr int kPer = 32;             // entries a lane group walks per sub-tile (one mask word)
