@@ -198,29 +198,12 @@ __global__ __launch_bounds__(kThreads) void relu_backward_kernel(const uintx4 *_
     out[p] = o;
 }
 
-template <typename K>
-int64_t resident_blocks(K kernel) {
-    static int64_t cached = 0;             // one value per kernel instantiation; the device type is fixed
-    if (cached == 0) {
-        int dev = 0, cus = 0, per_cu = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kThreads, 0) != hipSuccess || cus <= 0 ||
-            per_cu <= 0) {
-            (void)hipGetLastError();
-            return 512;
-        }
-        cached = (int64_t)cus * per_cu;
-    }
-    return cached;
-}
-
 template <int FIN, int FOUT, bool BF16>
 int launch_wgrad(const void *x, const void *g, int64_t n, float *dw, int accumulate, float *partial, hipStream_t s) {
     using S = Split<FIN, FOUT>;
     const int64_t n_steps = (n + kStepRows - 1) / kStepRows;
     const int64_t needed = (n_steps + S::RS - 1) / S::RS;
-    const int64_t blocks = std::min<int64_t>(std::min<int64_t>(needed, resident_blocks(wgrad_kernel<FIN, FOUT, BF16>)), kMaxBlocks);
+    const int64_t blocks = std::min<int64_t>(std::min<int64_t>(needed, resident_workgroups(wgrad_kernel<FIN, FOUT, BF16>, kThreads, 512)), kMaxBlocks);
     hipLaunchKernelGGL((wgrad_kernel<FIN, FOUT, BF16>), dim3((unsigned)blocks), dim3(kThreads), 0, s, x, g, n, n_steps, partial);
     DGNN_RETURN_IF_LAUNCH_FAILED();
     constexpr int elems = FIN * FOUT;

@@ -406,19 +406,7 @@ int launch_lstm_step(const void *y, const void *h_prev, const void *w_x, const v
                      void *h_next, int64_t n, hipStream_t s) {
     const int64_t n_tiles = (n + 31) / 32;
     const int64_t needed = (n_tiles + kLstmWaves - 1) / kLstmWaves;
-    static int64_t resident = 0;               // workgroups the device holds at once (one value per instantiation)
-    if (resident == 0) {
-        int dev = 0, cus = 0, per_cu = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, lstm_step_f32_kernel<FY>, kLstmThreads, 0) == hipSuccess &&
-            cus > 0 && per_cu > 0)
-            resident = (int64_t)cus * per_cu;
-        else {
-            (void)hipGetLastError();
-            resident = 256;
-        }
-    }
+    const int64_t resident = resident_workgroups(lstm_step_f32_kernel<FY>, kLstmThreads, 256);
     const unsigned blocks = (unsigned)(needed < resident ? needed : resident);
     hipLaunchKernelGGL(lstm_step_f32_kernel<FY>, dim3(blocks), dim3(kLstmThreads), 0, s, static_cast<const float *>(y),
                        static_cast<const float *>(h_prev), static_cast<const float *>(w_x), static_cast<const float *>(w_h),
@@ -457,19 +445,7 @@ extern "C" int dgnn_lstm_step_backward(const void *y, int32_t f_y, const void *h
         return DGNN_ERR_ALIAS;                                     // dc_prev may be dc_next: a tile is read before it is written
     const int64_t n_tiles = (n + 31) / 32;
     const int64_t needed = (n_tiles + kLstmWaves - 1) / kLstmWaves;
-    static int64_t resident = 0;
-    if (resident == 0) {
-        int dev = 0, cus = 0, per_cu = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, lstm_step_backward_f32_kernel, kLstmThreads, 0) == hipSuccess &&
-            cus > 0 && per_cu > 0)
-            resident = (int64_t)cus * per_cu;
-        else {
-            (void)hipGetLastError();
-            resident = 256;
-        }
-    }
+    const int64_t resident = resident_workgroups(lstm_step_backward_f32_kernel, kLstmThreads, 256);
     const unsigned blocks = (unsigned)(needed < resident ? needed : resident);
     hipLaunchKernelGGL(lstm_step_backward_f32_kernel, dim3(blocks), dim3(kLstmThreads), 0, (hipStream_t)stream,
                        static_cast<const float *>(y), static_cast<const float *>(h_prev), static_cast<const float *>(w_x),

@@ -4,6 +4,10 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+#include <utility>
+#include <vector>
+
 #include "dgnn.h"
 
 #define DGNN_RETURN_IF_LAUNCH_FAILED()                       \
@@ -22,6 +26,29 @@ inline bool fits_index(int64_t v) { return v >= 0 && v <= 2147483647LL - 65536; 
 inline bool supported_width(int32_t f) { return f == 16 || f == 32 || f == 64 || f == 128; }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Workgroups of `threads` threads of `kernel` that the device holds at once (compute units x workgroups per unit):
+// the grid of a kernel whose workgroups walk their share of the work in a loop.  Asked of the runtime once per
+// kernel (keyed by the kernel's address: kernels of equal signature are different kernels) and remembered; `fallback`
+// if the runtime cannot say.
+template <typename K>
+inline int64_t resident_workgroups(K kernel, int threads, int64_t fallback) {
+    static std::mutex lock;
+    static std::vector<std::pair<const void *, int64_t>> known;
+    const void *key = reinterpret_cast<const void *>(kernel);
+    std::lock_guard<std::mutex> guard(lock);
+    for (const auto &kv : known)
+        if (kv.first == key) return kv.second;
+    int dev = 0, cus = 0, per_cu = 0;
+    int64_t value = fallback;
+    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) == hipSuccess && cus > 0 && per_cu > 0)
+        value = (int64_t)cus * per_cu;
+    else
+        (void)hipGetLastError();
+    known.emplace_back(key, value);
+    return value;
+}
 
 // First index in [lo, hi) whose element is >= key (array ascending).
 __device__ __forceinline__ int lower_bound(const int32_t *__restrict__ a, int lo, int hi, int32_t key) {

@@ -380,28 +380,11 @@ __global__ __launch_bounds__(kThreads) void xw_bf16_staged_kernel(const uint16_t
 
 // Grid of a persistent launch: as many workgroups as the device holds at once, so that W is staged
 // once per resident workgroup and every wavefront walks many row tiles.
-template <typename K>
-int64_t resident_blocks(K kernel) {
-    static int64_t cached = 0;             // one value per kernel instantiation; the device type is fixed
-    if (cached == 0) {
-        int dev = 0, cus = 0, per_cu = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kThreads, 0) != hipSuccess || cus <= 0 ||
-            per_cu <= 0) {
-            (void)hipGetLastError();
-            return 1024;
-        }
-        cached = (int64_t)cus * per_cu;
-    }
-    return cached;
-}
-
 template <int FIN, int FOUT>
 int launch(const void *x, const void *w, int wt, const float *row_scale, void *h, int64_t n, dgnn_dtype dt, hipStream_t s) {
     const int64_t n_tiles = (n + 31) / 32;
     const int64_t needed = (n_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
-    auto grid = [&](auto kernel) { return dim3((unsigned)std::min(needed, resident_blocks(kernel))); };
+    auto grid = [&](auto kernel) { return dim3((unsigned)std::min(needed, resident_workgroups(kernel, kThreads, 1024))); };
     if (dt == DGNN_F32) {
         if constexpr (FIN <= 64 && FOUT <= 64 && FOUT % 32 == 0)   // both tiles and W fit in LDS
             hipLaunchKernelGGL((xw_f32_staged_kernel<FIN, FOUT>), grid(xw_f32_staged_kernel<FIN, FOUT>), dim3(kThreads), 0, s,
