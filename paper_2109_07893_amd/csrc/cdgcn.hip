@@ -255,19 +255,19 @@ __global__ __launch_bounds__(kLstmThreads) void lstm_step_f32_kernel(const float
 //     dc = dh o (1 - tanh(c_t)^2) + dc_t,   da_i = dc g i (1 - i),  da_f = dc c_{t-1} f (1 - f),
 //     da_g = dc i (1 - g^2),  da_o = dh tanh(c_t) o (1 - o),   dc_{t-1} = dc f.
 // Traffic: Y, h_prev, c_prev, the incoming gradients in; da (4 * hidden wide) and dc_{t-1} out, instead of writing
-// and re-reading both halves of the pre-activations as well.  f_y = 64 only: the tile buffer (f_y + hidden columns)
-// has to hold c_prev, dh and dc_t side by side.
+// and re-reading both halves of the pre-activations as well.
+template <int FY>
 __global__ __launch_bounds__(kLstmThreads) void lstm_step_backward_f32_kernel(
     const float *__restrict__ y, const float *__restrict__ h_prev, const float *__restrict__ w_x, const float *__restrict__ w_h,
     const float *__restrict__ bias, const float *__restrict__ c_prev, const float *__restrict__ dh_a,
     const float *__restrict__ dh_b, const float *dc_next, float *__restrict__ da, float *dc_prev, int64_t n, int64_t n_tiles) {
-    constexpr int FY = 64, HID = kLstmHidden, G4 = 4 * HID;
+    constexpr int HID = kLstmHidden, G4 = 4 * HID;
     constexpr int K = FY + HID, KH = K / 2;
-    constexpr int LDT = K + 4;
+    constexpr int LDT = (K > 3 * HID ? K : 3 * HID) + 4;      // the tile buffer also carries c_prev, dh and dc side by side
     constexpr int Y_PIECES = 32 * FY / 4 / kWave;
     constexpr int S_PIECES = 32 * HID / 4 / kWave;
     constexpr int HALF_PIECES = 32 * (2 * HID) / 4 / kWave;   // 16-byte pieces per lane of half a tile of da
-    static_assert(K >= 3 * HID, "the tile buffer carries c_prev, dh and dc side by side");
+    static_assert(KH % 4 == 0, "operand rows are read in 16-byte pieces");
     __shared__ float s_w[K * G4];
     __shared__ __attribute__((aligned(16))) float s_tile[kLstmWaves][32 * LDT];
 
@@ -436,7 +436,7 @@ extern "C" int dgnn_lstm_step_backward(const void *y, int32_t f_y, const void *h
                                        void *stream) {
     if (!y || !h_prev || !w_x || !w_h || !c_prev || !da || !dc_prev) return DGNN_ERR_NULL;
     if (!dh_a && !dh_b && !dc_next) return DGNN_ERR_NULL;
-    if (n <= 0 || hidden != kLstmHidden || dt != DGNN_F32 || f_y != 64) return DGNN_ERR_SHAPE;
+    if (n <= 0 || hidden != kLstmHidden || dt != DGNN_F32 || (f_y != 32 && f_y != 64)) return DGNN_ERR_SHAPE;
     if (!fits_index(n)) return DGNN_ERR_OVERFLOW;
     for (const void *p : {y, h_prev, c_prev, dh_a, dh_b, dc_next, (const void *)da, (const void *)dc_prev})
         if (p && !aligned16(p)) return DGNN_ERR_ALIGN;
@@ -445,13 +445,16 @@ extern "C" int dgnn_lstm_step_backward(const void *y, int32_t f_y, const void *h
         return DGNN_ERR_ALIAS;                                     // dc_prev may be dc_next: a tile is read before it is written
     const int64_t n_tiles = (n + 31) / 32;
     const int64_t needed = (n_tiles + kLstmWaves - 1) / kLstmWaves;
-    const int64_t resident = resident_workgroups(lstm_step_backward_f32_kernel, kLstmThreads, 256);
-    const unsigned blocks = (unsigned)(needed < resident ? needed : resident);
-    hipLaunchKernelGGL(lstm_step_backward_f32_kernel, dim3(blocks), dim3(kLstmThreads), 0, (hipStream_t)stream,
-                       static_cast<const float *>(y), static_cast<const float *>(h_prev), static_cast<const float *>(w_x),
-                       static_cast<const float *>(w_h), bias, static_cast<const float *>(c_prev),
-                       static_cast<const float *>(dh_a), static_cast<const float *>(dh_b), static_cast<const float *>(dc_next),
-                       static_cast<float *>(da), static_cast<float *>(dc_prev), n, n_tiles);
+    auto launch = [&](auto kernel) {
+        const int64_t resident = resident_workgroups(kernel, kLstmThreads, 256);
+        const unsigned blocks = (unsigned)(needed < resident ? needed : resident);
+        hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kLstmThreads), 0, (hipStream_t)stream, static_cast<const float *>(y),
+                           static_cast<const float *>(h_prev), static_cast<const float *>(w_x), static_cast<const float *>(w_h),
+                           bias, static_cast<const float *>(c_prev), static_cast<const float *>(dh_a),
+                           static_cast<const float *>(dh_b), static_cast<const float *>(dc_next), static_cast<float *>(da),
+                           static_cast<float *>(dc_prev), n, n_tiles);
+    };
+    if (f_y == 64) launch(lstm_step_backward_f32_kernel<64>); else launch(lstm_step_backward_f32_kernel<32>);
     DGNN_RETURN_IF_LAUNCH_FAILED();
     return DGNN_OK;
 }

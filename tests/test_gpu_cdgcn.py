@@ -169,10 +169,11 @@ def test_bias_grad(dtype, f, n):
     assert torch.equal(db, first)                     # fixed order of summation
 
 
+@pytest.mark.parametrize("f_y", [32, 64])
 @pytest.mark.parametrize("n", [1, 31, 32, 33, 4097, 20_011])
 @pytest.mark.parametrize("carried", [False, True])
-def test_fused_lstm_step_backward(n, carried):
-    f_y, hidden = 64, 32
+def test_fused_lstm_step_backward(n, carried, f_y):
+    hidden = 32
     y, h_prev = randn((n, f_y), 1), randn((n, hidden), 2)
     w_x, w_h = randn((f_y, 4 * hidden), 3) / 8, randn((hidden, 4 * hidden), 4) / 6
     bias = randn((4 * hidden,), 5) * 0.1
