@@ -52,6 +52,8 @@ def parse_args():
                     help="also time one step of the path for snapshots that carry a value per entry")
     ap.add_argument("--smoothing", action="store_true",
                     help="also time the sliding-window sum of the block's snapshots (edge life 4) computed on the device")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="only the headline figure (and whatever is asked for explicitly): skip the CD-GCN, weighted and smoothing figures")
     ap.add_argument("--natural-labels", action="store_true",
                     help="R-MAT workloads: keep the generator's vertex labels (locality) instead of scrambling them")
     return ap.parse_args()
@@ -566,14 +568,21 @@ def main():
         out["hip_graph_replay"] = {"value": edges_per_step / el, "unit": "edges/s", "ms_per_step": el * 1e3}
         del graph
         progress("graph replay timed")
-    if args.cdgcn:
-        out["cdgcn_layer"] = cdgcn_layer(args, wl, blk, dev)
-        progress("CD-GCN layer timed")
-    if args.weighted:
-        out["weighted_step"] = weighted_step(args, wl, blk, dev)
-    if args.smoothing:
-        out["smoothing"] = smoothing_steps(args, wl, blk, dev)
-        progress("weighted step timed")
+    # figures of the rows built after the hot path: on request, or all of them unless --no-extras; a failure there is
+    # reported in its own object and never costs the headline line
+    def extra(key, flag, fn):
+        if not (flag or not args.no_extras):
+            return
+        try:
+            out[key] = fn(args, wl, blk, dev)
+        except Exception as exc:                      # noqa: BLE001 -- reported, the headline still goes out
+            out[key] = {"error": f"{type(exc).__name__}: {exc}"[:300]}
+        torch.cuda.empty_cache()
+        progress(f"{key} timed")
+
+    extra("cdgcn_layer", args.cdgcn, cdgcn_layer)
+    extra("weighted_step", args.weighted, weighted_step)
+    extra("smoothing", args.smoothing, smoothing_steps)
     if not args.no_train:
         del runner
         torch.cuda.empty_cache()
