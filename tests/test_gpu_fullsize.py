@@ -275,3 +275,63 @@ def test_sliding_window_sum_full_size():
         got = sub(rp_c.cpu().numpy(), ci_c[:nnz].cpu().numpy(), val_c[:nnz].cpu().numpy())
         assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1])
         assert np.array_equal(got[2].astype(np.float64), want[2])
+    # the weighted normalisation of S_3 and one normalised aggregation with it, on the same sampled rows
+    progress("normalisation and aggregation on S_3")
+    rp_c, ci_c, val_c = bufs[1]
+    dinv = torch.empty(n, device=DEV)
+    dg.csr_weighted_dinv(rp_c, val_c, nnz3, dinv, torch.empty(dg.csr_weighted_dinv_workspace(nnz3), dtype=torch.uint8, device=DEV))
+    s3_rp, s3_ci, s3_val = rp_c.cpu().numpy(), ci_c[:nnz3].cpu().numpy(), val_c[:nnz3].cpu().numpy().astype(np.float64)
+    row_sum = np.add.reduceat(s3_val, s3_rp[:-1])                       # every row holds its diagonal: no empty segment
+    d_host = dinv.cpu().numpy().astype(np.float64)
+    np.testing.assert_allclose(d_host[rows], row_sum[rows] ** -0.5, rtol=2e-6)
+    f = wl.f
+    h = torch.empty((n, f), device=DEV)
+    dg.feature_transform(blk.x[2], blk.w[0], h, row_scale=dinv)
+    z = torch.empty((n, f), device=DEV)
+    ws_s = torch.empty(dg.spmm_workspace(n, nnz3, f), dtype=torch.uint8, device=DEV)
+    dg.spmm_weighted(rp_c, ci_c, val_c, nnz3, h, z, ws_s, flags=dg.DGNN_RELU | dg.DGNN_H_PRESCALED, dinv=dinv)
+    torch.cuda.synchronize()
+    # oracle on the sampled rows: their entries' normalised values from the device-independent row sums, H = X W in fp64
+    # only for the columns those rows touch
+    take = np.concatenate([np.arange(s3_rp[r], s3_rp[r + 1]) for r in rows])
+    cols, inv = np.unique(s3_ci[take], return_inverse=True)
+    hw = oracle.xw(to_f64(blk.x[2][torch.from_numpy(cols).to(DEV)]), to_f64(blk.w[0]))
+    lens = s3_rp[rows + 1] - s3_rp[rows]
+    sub_rp = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    vals = s3_val[take] * np.repeat(row_sum[rows] ** -0.5, lens) * (row_sum[s3_ci[take]] ** -0.5)
+    # the definition, row by row (the oracle's own aggregation takes a square matrix; this one is rows x touched columns)
+    want_z = np.maximum(np.add.reduceat(vals[:, None] * hw[inv], sub_rp[:-1], axis=0), 0.0)
+    assert_close(to_f64(z[torch.from_numpy(rows).to(DEV)]), want_z, torch.float32, "normalised aggregation on S_3, sampled rows")
+
+
+@pytest.mark.timeout(600)
+def test_fused_lstm_step_and_its_adjoint_full_size():
+    """The fused LSTM step and its adjoint at c5's vertex count (2^24 rows, f_y = 64, hidden 32), in the launch shape
+    the benchmark uses; 4096 sampled rows plus the first and last 64 against the oracle's cell and its backward."""
+    import paper_2109_07893_amd as dg
+    n, f_y, hidden = 1 << 24, 64, 32
+    gen = torch.Generator(device=DEV).manual_seed(77)
+    y = torch.randn((n, f_y), generator=gen, device=DEV)
+    h_prev, c_prev, g_h, dc_n = (torch.randn((n, hidden), generator=gen, device=DEV) for _ in range(4))
+    w_x = torch.randn((f_y, 4 * hidden), generator=gen, device=DEV) / 8
+    w_h = torch.randn((hidden, 4 * hidden), generator=gen, device=DEV) / 6
+    bias = torch.randn(4 * hidden, generator=gen, device=DEV) * 0.1
+    c = c_prev.clone()
+    h_next = torch.empty_like(h_prev)
+    progress("fused step")
+    dg.lstm_step(y, h_prev, w_x, w_h, bias, c, h_next)
+    da = torch.empty((n, 4 * hidden), device=DEV)
+    dc = dc_n.clone()
+    progress("fused adjoint")
+    dg.lstm_step_backward(y, h_prev, w_x, w_h, bias, c_prev, g_h, None, dc, da, dc)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(1)
+    rows = np.unique(np.concatenate([rng.choice(n, 4096, replace=False), np.arange(64), np.arange(n - 64, n)]))
+    idx = torch.from_numpy(rows).to(DEV)
+    args = [to_f64(t[idx]) for t in (y, h_prev, c_prev)] + [to_f64(w_x), to_f64(w_h), to_f64(bias)]
+    want_h, want_c = oracle.lstm_cell(*args)
+    assert_close(to_f64(h_next[idx]), want_h, torch.float32, "h_t, sampled rows")
+    assert_close(to_f64(c[idx]), want_c, torch.float32, "c_t, sampled rows")
+    back = oracle.lstm_cell_backward(*args, to_f64(g_h[idx]), to_f64(dc_n[idx]))
+    assert_close(to_f64(da[idx]), back[0], torch.float32, "dL/d(pre-activations), sampled rows")
+    assert_close(to_f64(dc[idx]), back[3], torch.float32, "dL/dc_prev, sampled rows")
