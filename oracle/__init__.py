@@ -7,7 +7,14 @@ Arrays go in and out as numpy; real numbers are float64 throughout.
 Passages followed: reconstruction from a graph difference -- Section "Graph-difference Based
 Input Transfer"; normalised adjacency -- Eqn (1); GCN operation -- Eqn (2); M-transform and
 its matrix M -- Section "TM-GCN"; gradient propagation through a block in the reverse direction
--- Section "Gradient Checkpoint" (the adjoint of each forward step).
+-- Section "Gradient Checkpoint" (the adjoint of each forward step); the sliding-window sum of
+snapshots and its normalisation -- Section "Smoothening the Input Graphs" with Eqn (1); the GCN
+operation with skip connection and the LSTM over time -- Section "CD-GCN"; the LSTM over the
+weights -- Section "EvolveGCN"; and the adjoints of those.  The parts added in numpy below are
+fp64 like the C part.  Parity status: every function here is pinned by tests that do not call
+it to produce their own expectation (dense brute force, closed forms, hand-worked fixtures under
+tests/golden/, a library LSTM cell, central differences); tests/test_oracle_mutants.py plants
+mistakes in copies of both sources and requires those pins to fail.
 """
 from __future__ import annotations
 
