@@ -62,6 +62,10 @@ typedef enum { DGNN_F32 = 0, DGNN_BF16 = 1 } dgnn_dtype;
 #define DGNN_BAD_DEL_ABSENT 4    /* a deleted edge is not in A_prev                              */
 #define DGNN_BAD_ADD_PRESENT 5   /* an added edge is already in A_prev                           */
 #define DGNN_BAD_EMPTY_ROW 6     /* A_prev has a row without entries (the diagonal is missing)   */
+/* ... and by dgnn_csr_validate: */
+#define DGNN_BAD_ROWPTR 7        /* rowptr[0] != 0, rowptr not ascending, or rowptr[n] != nnz     */
+#define DGNN_BAD_ROW_ORDER 8     /* the columns of a row are not strictly ascending              */
+#define DGNN_BAD_NO_DIAGONAL 9   /* a row does not hold its diagonal entry (only if asked for)   */
 
 /* Flags of dgnn_spmm. */
 #define DGNN_RELU 1u             /* apply sigma = ReLU to the aggregated rows (Eqn (2)) */
@@ -198,6 +202,17 @@ int dgnn_delta_rebuild_weighted(int64_t n,
                                 int32_t *rowptr_next, int32_t *colidx_next, float *val_next, int64_t cap_next,
                                 int64_t *nnz_next,
                                 void *ws, size_t ws_bytes, uint32_t flags, int32_t *d_status, void *stream);
+
+/*
+ * Checks that (rowptr, colidx) is a snapshot in the form every call here takes (the canonical form of a snapshot,
+ * Section "Graph-difference Based Input Transfer": sent whole once, rebuilt from differences afterwards): rowptr[0] = 0,
+ * rowptr ascending, rowptr[n] = nnz, every column in [0, n), columns strictly ascending inside a row and, with
+ * require_diagonal != 0, the diagonal entry present in every row (the stored matrix is A + I, Eqn (1)).
+ *   d_status  device int32, required: 0 if nothing was found, else the smallest DGNN_BAD_* code found.
+ * Enqueue-only.  Errors: NULL, SHAPE (n <= 0, nnz < 0), OVERFLOW.
+ */
+int dgnn_csr_validate(int64_t n, const int32_t *rowptr, const int32_t *colidx, int64_t nnz, int require_diagonal,
+                      int32_t *d_status, void *stream);
 
 /*
  * Z = sigma?(V H) for a snapshot with explicit values, Z[u] = sum over stored (u,v) of val(u,v) * H[v]

@@ -22,7 +22,7 @@ DGNN_RELU = 1
 DGNN_H_PRESCALED = 2
 
 EXPORTS = (
-    "dgnn_strerror", "dgnn_csr_dinv", "dgnn_delta_h2d", "dgnn_delta_rebuild_workspace",
+    "dgnn_strerror", "dgnn_csr_validate", "dgnn_csr_dinv", "dgnn_delta_h2d", "dgnn_delta_rebuild_workspace",
     "dgnn_delta_rebuild", "dgnn_feature_transform", "dgnn_spmm_workspace", "dgnn_spmm", "dgnn_mproduct",
     "dgnn_delta_rebuild_weighted", "dgnn_spmm_weighted", "dgnn_csr_combine_workspace", "dgnn_csr_combine", "dgnn_csr_weighted_dinv_workspace", "dgnn_csr_weighted_dinv", "dgnn_concat_relu", "dgnn_lstm_cell", "dgnn_lstm_step", "dgnn_lstm_cell_backward", "dgnn_lstm_step_backward", "dgnn_concat_relu_backward", "dgnn_bias_grad_workspace", "dgnn_bias_grad", "dgnn_add",
     "dgnn_mproduct_backward", "dgnn_mproduct_block", "dgnn_mproduct_backward_block", "dgnn_relu_backward", "dgnn_weight_grad_workspace", "dgnn_weight_grad", "dgnn_input_grad",
@@ -102,6 +102,7 @@ def load_library():
                                                 _vp, _vp, _vp, _i64, _vp, _vp, _vp, _i64, ctypes.POINTER(_i64),
                                                 _vp, _sz, _u32, _vp, _vp]
     lib.dgnn_spmm_weighted.argtypes = [_i64, _i64, _vp, _vp, _vp, _vp, _vp, _i32, _vp, ctypes.c_int, _u32, _vp, _sz, _vp]
+    lib.dgnn_csr_validate.argtypes = [_i64, _vp, _vp, _i64, ctypes.c_int, _vp, _vp]
     lib.dgnn_csr_combine_workspace.argtypes = [_i64, ctypes.POINTER(_sz)]
     lib.dgnn_csr_combine.argtypes = [_i64, _vp, _vp, _vp, _i64, _vp, _vp, _i64, ctypes.c_float, _vp, _vp, _i64, ctypes.c_float,
                                      _vp, _vp, _vp, _i64, ctypes.POINTER(_i64), _vp, _sz, _vp]
@@ -289,6 +290,15 @@ def spmm_weighted(rowptr, colidx, val, nnz: int, h: torch.Tensor, z: torch.Tenso
     _check(load_library().dgnn_spmm_weighted(n, nnz, _ptr(rowptr), _ptr(colidx), _ptr(val), _ptr(dinv), _ptr(h), f, _ptr(z),
                                              dt, flags, _ptr(ws), ws.numel() * ws.element_size(), _stream(h)),
            "dgnn_spmm_weighted")
+
+
+def csr_validate(rowptr: torch.Tensor, colidx: torch.Tensor, nnz: int, status: torch.Tensor, require_diagonal: bool = True) -> None:
+    """status[0] <- 0 if (rowptr, colidx) is a canonical snapshot, else the smallest DGNN_BAD_* code found."""
+    _need(rowptr, torch.int32, "rowptr"); _need(colidx, torch.int32, "colidx"); _need(status, torch.int32, "status")
+    if colidx.numel() < nnz:
+        raise ValueError("colidx shorter than nnz")
+    _check(load_library().dgnn_csr_validate(rowptr.numel() - 1, _ptr(rowptr), _ptr(colidx), nnz, int(require_diagonal),
+                                            _ptr(status), _stream(rowptr)), "dgnn_csr_validate")
 
 
 def csr_combine_workspace(nnz_s: int) -> int:

@@ -462,12 +462,52 @@ __global__ __launch_bounds__(256) void validate_kernel(
     if (!is_add && !present) report(status, DGNN_BAD_DEL_ABSENT);
 }
 
+// One thread per row: its pointers, then its columns one after the other (rows are short on average; a hub row
+// keeps one thread busy for its length, which a check that runs once per uploaded snapshot can afford).
+__global__ __launch_bounds__(256) void csr_validate_kernel(int n, const int32_t *__restrict__ rowptr,
+                                                           const int32_t *__restrict__ colidx, int nnz, int require_diagonal,
+                                                           int32_t *status) {
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= n) return;
+    const int lo = rowptr[r], hi = rowptr[r + 1];
+    if ((r == 0 && lo != 0) || (r == n - 1 && hi != nnz) || lo < 0 || hi < lo || hi > nnz) {
+        report(status, DGNN_BAD_ROWPTR);
+        return;                                             // the row's extent cannot be trusted
+    }
+    bool diagonal = false;
+    int prev = -1;
+    for (int e = lo; e < hi; ++e) {
+        const int c = colidx[e];
+        if (c < 0 || c >= n) { report(status, DGNN_BAD_INDEX_RANGE); return; }
+        if (c <= prev) { report(status, DGNN_BAD_ROW_ORDER); return; }
+        diagonal |= c == r;
+        prev = c;
+    }
+    if (require_diagonal && !diagonal) report(status, DGNN_BAD_NO_DIAGONAL);
+}
+
+__global__ __launch_bounds__(64) void reset_status_kernel(int32_t *status) { *status = 0; }
+
 __global__ __launch_bounds__(256) void dinv_kernel(int n, const int32_t *__restrict__ rowptr, float *__restrict__ dinv) {
     int r = blockIdx.x * blockDim.x + threadIdx.x;
     if (r < n) dinv[r] = 1.0f / sqrtf((float)(rowptr[r + 1] - rowptr[r]));
 }
 
 }  // namespace
+
+extern "C" int dgnn_csr_validate(int64_t n, const int32_t *rowptr, const int32_t *colidx, int64_t nnz, int require_diagonal,
+                                 int32_t *d_status, void *stream) {
+    if (!rowptr || !d_status || (nnz > 0 && !colidx)) return DGNN_ERR_NULL;
+    if (n <= 0 || nnz < 0) return DGNN_ERR_SHAPE;
+    if (!fits_index(n + 1) || !fits_index(nnz)) return DGNN_ERR_OVERFLOW;
+    hipStream_t s = (hipStream_t)stream;
+    hipLaunchKernelGGL(reset_status_kernel, dim3(1), dim3(64), 0, s, d_status);     // a fill kernel: capturable
+    DGNN_RETURN_IF_LAUNCH_FAILED();
+    hipLaunchKernelGGL(csr_validate_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (int)n, rowptr, colidx, (int)nnz,
+                       require_diagonal, d_status);
+    DGNN_RETURN_IF_LAUNCH_FAILED();
+    return DGNN_OK;
+}
 
 extern "C" const char *dgnn_strerror(int code) {
     switch (code) {

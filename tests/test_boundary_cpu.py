@@ -282,3 +282,11 @@ def test_lstm_step_backward_argument_errors(lib):
     assert call(f_y=16) == -2 and call(hidden=64) == -2 and call(dt=1) == -2
     assert call(da=a[0]) == -5 and call(dc=a[5]) == -5
     assert call(c=a[4] + 4) == -7
+
+
+def test_csr_validate_argument_errors(lib):
+    f = lib.dgnn_csr_validate
+    assert f(10, None, FAKE, 20, 1, FAKE + 4096, None) == -1 and f(10, FAKE, FAKE, 20, 1, None, None) == -1
+    assert f(10, FAKE, None, 20, 1, FAKE + 4096, None) == -1
+    assert f(0, FAKE, FAKE, 20, 1, FAKE + 4096, None) == -2 and f(10, FAKE, FAKE, -1, 1, FAKE + 4096, None) == -2
+    assert f(1 << 31, FAKE, FAKE, 20, 1, FAKE + 4096, None) == -4

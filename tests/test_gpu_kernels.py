@@ -367,3 +367,37 @@ def test_mproduct_explicit_band():
     y = torch.empty((T, n, f), device=DEV)
     dg.mproduct(z.to(DEV), y, w, m_band=band.to(DEV))
     assert_close(to_f64(y), oracle.mproduct(to_f64(z), M), torch.float32, "explicit band")
+
+
+def test_csr_validate_finds_what_is_wrong():
+    """A canonical snapshot passes; each way of breaking it is reported with its code."""
+    wl = WORKLOADS["c3"].scaled(1 << 12, T=1)
+    g = DynamicGraph(wl)
+    rp, ci = (x.numpy().copy() for x in g.csr())
+    n, nnz = wl.n, int(ci.size)
+    status = torch.full((1,), -9, dtype=torch.int32, device=DEV)
+
+    def code(rp_, ci_, nnz_=nnz, diag=True):
+        dg.csr_validate(torch.from_numpy(rp_).to(DEV), torch.from_numpy(ci_).to(DEV), nnz_, status, require_diagonal=diag)
+        return int(status.item())
+
+    assert code(rp, ci) == 0
+    u = int(np.argmax(np.diff(rp) >= 3))                                  # a row with at least three entries
+    bad = ci.copy(); bad[rp[u]], bad[rp[u] + 1] = bad[rp[u] + 1], bad[rp[u]]
+    assert code(rp, bad) == 8                                             # DGNN_BAD_ROW_ORDER
+    bad = ci.copy(); bad[rp[u] + 1] = bad[rp[u]]
+    assert code(rp, bad) == 8                                             # a repeated column
+    bad = ci.copy(); bad[rp[u + 1] - 1] = n
+    assert code(rp, bad) == 1                                             # DGNN_BAD_INDEX_RANGE
+    bad = rp.copy(); bad[u + 1] = bad[u] - 1
+    assert code(bad, ci) == 7                                             # DGNN_BAD_ROWPTR
+    assert code(rp, ci, nnz_=nnz - 1) == 7                                # rowptr[n] != nnz
+    bad = rp.copy(); bad[0] = 1
+    assert code(bad, ci) == 7
+    # a snapshot without one of its self loops: fine as a matrix, not as A + I
+    keep = np.ones(nnz, dtype=bool)
+    keep[rp[u] + int(np.searchsorted(ci[rp[u]:rp[u + 1]], u))] = False
+    lens = np.diff(rp); lens[u] -= 1
+    rp2 = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    assert code(rp2, ci[keep], nnz_=nnz - 1) == 9                         # DGNN_BAD_NO_DIAGONAL
+    assert code(rp2, ci[keep], nnz_=nnz - 1, diag=False) == 0
