@@ -290,3 +290,37 @@ def test_csr_validate_argument_errors(lib):
     assert f(10, FAKE, None, 20, 1, FAKE + 4096, None) == -1
     assert f(0, FAKE, FAKE, 20, 1, FAKE + 4096, None) == -2 and f(10, FAKE, FAKE, -1, 1, FAKE + 4096, None) == -2
     assert f(1 << 31, FAKE, FAKE, 20, 1, FAKE + 4096, None) == -4
+
+
+def test_boundary_is_callable_from_plain_c(tmp_path):
+    """A C99 program that includes include/dgnn.h, links libdgnn.so and calls it: host-side argument errors come back
+    as codes without a GPU being touched (no compute call is made)."""
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    lib_dir = os.path.join(root, "paper_2109_07893_amd", "csrc")
+    if not os.path.exists(os.path.join(lib_dir, "libdgnn.so")):
+        pytest.skip("libdgnn.so has not been built")
+    src = tmp_path / "use_dgnn.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include <string.h>
+#include "dgnn.h"
+int main(void) {
+    size_t bytes = 0;
+    int32_t fake[4] = {0, 0, 0, 0};
+    if (strcmp(dgnn_strerror(DGNN_OK), "ok") != 0) return 1;
+    if (dgnn_spmm_workspace(1000, 5000, 32, &bytes) != DGNN_OK || bytes == 0) return 2;
+    if (dgnn_spmm_workspace(1000, 5000, 24, &bytes) != DGNN_ERR_SHAPE) return 3;
+    if (dgnn_csr_combine_workspace(1 << 20, &bytes) != DGNN_OK || bytes < 4096) return 4;
+    if (dgnn_csr_dinv(10, NULL, NULL, NULL) != DGNN_ERR_NULL) return 5;
+    if (dgnn_csr_validate(0, fake, fake, 0, 1, fake, NULL) != DGNN_ERR_SHAPE) return 6;
+    if (dgnn_mproduct(NULL, NULL, 4, 10, 32, 3, NULL, DGNN_F32, NULL) != DGNN_ERR_NULL) return 7;
+    printf("boundary ok\n");
+    return 0;
+}
+''')
+    exe = tmp_path / "use_dgnn"
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(root, "include"), str(src), "-o", str(exe),
+                           "-L", lib_dir, "-ldgnn", f"-Wl,-rpath,{lib_dir}", "-Wl,-rpath,/opt/rocm/lib"])
+    out = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert out.returncode == 0 and "boundary ok" in out.stdout, (out.returncode, out.stdout, out.stderr)
