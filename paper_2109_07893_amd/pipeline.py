@@ -178,6 +178,12 @@ class BlockRunner:
             cur = dst
         return out
 
+    def begin_pass(self) -> None:
+        """Called at the start of every pass (subclasses that overwrite A_1's slot reload it here)."""
+
+    def snapshot_ready(self, t: int) -> None:
+        """Called once A_t is resident (after the rebuild for t >= 2), before its GCN step."""
+
     def mix(self) -> None:
         """In-place M-transform over the stored frames."""
         if self.blk.window:
@@ -190,9 +196,11 @@ class BlockRunner:
         on A_1 (timed regions that count only rebuilt snapshots).  on_snapshot(t, slot) is called
         after the work of timestep t has been enqueued."""
         blk = self.blk
+        self.begin_pass()
         for t in range(1, blk.T + 1):
             if t >= 2:
                 self.rebuild(t, blk.deltas[t - 2], validate)
+            self.snapshot_ready(t)
             if t >= first:
                 self.gcn(t)
             if on_snapshot is not None:
@@ -233,6 +241,7 @@ class BlockRunner:
             if blk.T >= 2:
                 issue_copy(2)
         self._first_lists_requested = False
+        self.begin_pass()
         for t in range(1, blk.T + 1):
             if t >= 2:
                 k = t % 2
@@ -244,6 +253,7 @@ class BlockRunner:
                 if t == blk.T and prefetch_next and blk.T >= 3:     # both staging sets have been used and released
                     issue_copy(2)
                     self._first_lists_requested = True
+            self.snapshot_ready(t)
             if t >= first:
                 self.gcn(t)
         self.mix()
@@ -327,15 +337,12 @@ class SmoothedRunner(BlockRunner):
             cur = dst
         return out
 
-    def run_resident(self, first: int = 1, validate: bool = False, on_snapshot=None) -> None:
-        blk = self.blk
+    def begin_pass(self) -> None:
         self.load_first()                                # the ring overwrites A_1: every pass starts from the inputs
-        for t in range(1, blk.T + 1):
-            if t >= 2:
-                self.rebuild(t, blk.deltas[t - 2], validate)
-            self.smooth(t)
-            if t >= first:
-                self.gcn(t)
-            if on_snapshot is not None:
-                on_snapshot(t, self.slot_of(t))
-        self.mix()
+
+    def snapshot_ready(self, t: int) -> None:
+        self.smooth(t)
+
+    def capture(self, first: int = 1):
+        raise RuntimeError("a pass on smoothed snapshots cannot be recorded as a HIP graph: dgnn_csr_combine reads the size of "
+                           "its result back to the host between its two launches")

@@ -289,3 +289,18 @@ def test_evolvegcn_on_smoothed_snapshots():
     for name, got, exp in (("dU_x", ev.du_x, want[0]), ("dU_h", ev.du_h, want[1]), ("db", ev.db, want[2]), ("dW_0", ev.dw0, want[3])):
         err = np.abs(to_f64(got) - exp).max()
         assert err <= 3e-4 * np.abs(exp).max(), f"{name}: max err {err:.3e} against max |.| {np.abs(exp).max():.3e}"
+
+
+def test_smoothed_forward_with_lists_from_pinned_host_memory():
+    """The smoothed forward pass with the raw difference lists streamed from pinned host memory (copies overlapped
+    with the computation) leaves exactly what the pass with resident lists leaves."""
+    from paper_2109_07893_amd.pipeline import SmoothedRunner, make_block
+    wl = WORKLOADS["c5"].scaled(1 << 13, T=7)
+    a = SmoothedRunner(make_block(wl, DEV, gen_device="cpu"), life=3, keep_all_z=True)
+    a.run_resident()
+    b = SmoothedRunner(make_block(wl, DEV, gen_device="cpu", pinned=True), life=3, keep_all_z=True)
+    for _ in range(2):
+        b.z.fill_(float("nan"))
+        b.run_from_pinned()
+        torch.cuda.synchronize()
+        assert torch.equal(a.z, b.z)
