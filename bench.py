@@ -366,7 +366,7 @@ def training_step(args, wl, blk, dev):
     for t in range(1, blk.T + 1):
         g_y[t - 1].copy_(gradient(wl, t, device=dev))
     if n_blocks == 1:
-        tr = make_trainer(wl, blk)
+        tr = make_trainer(wl, blk, keep_snapshots=getattr(args, "_keep_snapshots", False))
         timed = tr
 
         def one_step():
@@ -587,6 +587,16 @@ def main():
         del runner
         torch.cuda.empty_cache()
         out["training_step"] = training_step(args, wl, blk, dev)
+        if out["training_step"].get("checkpoint_blocks", 1) == 1:
+            # the same step with every snapshot of the block resident (no reverse rebuilds on the way back)
+            torch.cuda.empty_cache()
+            args._keep_snapshots = True
+            try:
+                kept = training_step(args, wl, blk, dev)
+                out["training_step_snapshots_kept"] = {k: kept[k] for k in ("ms_per_step", "value", "unit") if k in kept}
+            except Exception as exc:                  # noqa: BLE001 -- an extra figure
+                out["training_step_snapshots_kept"] = {"error": f"{type(exc).__name__}: {exc}"[:300]}
+            args._keep_snapshots = False
 
     if not args.no_cpu_baseline:
         progress("timing the CPU oracle")

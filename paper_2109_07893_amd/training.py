@@ -25,23 +25,29 @@ from .pipeline import BlockInputs, BlockRunner
 
 
 class _Chain:
-    """Two alternating CSR slots plus a kept first snapshot, walked forwards or backwards by rebuilds."""
+    """CSR slots for a series of snapshots walked forwards or backwards by rebuilds: by default two alternating slots
+    plus a kept first snapshot; with `slots` given, one slot per timestep, so that every snapshot of the block stays
+    resident and nothing has to be rebuilt on the way back."""
 
-    def __init__(self, n, cap, dev, rowptr1, colidx1, with_dinv: bool):
-        self.rowptr = [torch.empty(n + 1, dtype=torch.int32, device=dev) for _ in range(3)]
-        self.colidx = [torch.empty(cap, dtype=torch.int32, device=dev) for _ in range(3)]
-        self.dinv = [torch.empty(n, dtype=torch.float32, device=dev) if with_dinv else None for _ in range(3)]
+    def __init__(self, n, cap, dev, rowptr1, colidx1, with_dinv: bool, slots: Optional[int] = None):
+        self.per_step = slots is not None
+        count = slots if self.per_step else 3
+        self.rowptr = [torch.empty(n + 1, dtype=torch.int32, device=dev) for _ in range(count)]
+        self.colidx = [torch.empty(cap, dtype=torch.int32, device=dev) for _ in range(count)]
+        self.dinv = [torch.empty(n, dtype=torch.float32, device=dev) if with_dinv else None for _ in range(count)]
         self.load_first(rowptr1, colidx1)
 
     def load_first(self, rowptr1, colidx1) -> None:
-        """The block's first snapshot, which arrives whole, goes into the kept slot."""
-        self.rowptr[2].copy_(rowptr1)
-        self.colidx[2][: colidx1.numel()].copy_(colidx1)
-        if self.dinv[2] is not None:
-            B.csr_dinv(self.rowptr[2], self.dinv[2])
+        """The block's first snapshot, which arrives whole, goes into its slot."""
+        k = self.slot_of(1)
+        self.rowptr[k].copy_(rowptr1)
+        self.colidx[k][: colidx1.numel()].copy_(colidx1)
+        if self.dinv[k] is not None:
+            B.csr_dinv(self.rowptr[k], self.dinv[k])
 
-    @staticmethod
-    def slot_of(t: int) -> int:
+    def slot_of(self, t: int) -> int:
+        if self.per_step:
+            return t - 1
         return 2 if t == 1 else t % 2
 
 
@@ -51,7 +57,7 @@ class BlockTrainer:
     def __init__(self, blk: BlockInputs, directed: bool,
                  transposed_first: Optional[Tuple[torch.Tensor, torch.Tensor]] = None,
                  transposed_deltas: Optional[List[Tuple[torch.Tensor, ...]]] = None, want_dx: bool = False,
-                 cap: Optional[int] = None, max_list: Optional[int] = None):
+                 cap: Optional[int] = None, max_list: Optional[int] = None, keep_snapshots: bool = False):
         self.blk = blk
         dev = blk.rowptr1.device
         self.dev = dev
@@ -62,11 +68,16 @@ class BlockTrainer:
         self.t0 = 0                     # timesteps of the series before this block
         self.z_before = None            # last w-1 frames of the top layer's Z before this block
         self.directed = directed
-        self.a = _Chain(n, cap, dev, blk.rowptr1, blk.colidx1, with_dinv=True)
+        # keep_snapshots: every A_t (and A_t^T) of the block stays resident (T index arrays instead of three), so the
+        # backward pass rebuilds nothing; without, the snapshots are rebuilt in reverse, as gradient checkpointing
+        # has it.  4 nnz bytes per snapshot and chain: 9.6 GB for c5's eight, a matter of course in 288 GB.
+        self.keep_snapshots = keep_snapshots
+        slots = T if keep_snapshots else None
+        self.a = _Chain(n, cap, dev, blk.rowptr1, blk.colidx1, with_dinv=True, slots=slots)
         self.at = None
         if directed:
             assert transposed_first is not None and transposed_deltas is not None
-            self.at = _Chain(n, cap, dev, transposed_first[0], transposed_first[1], with_dinv=False)
+            self.at = _Chain(n, cap, dev, transposed_first[0], transposed_first[1], with_dinv=False, slots=slots)
             self.t_deltas = transposed_deltas
         self.z = torch.empty((L, T, n, f), dtype=dt, device=dev)          # activations of the block
         self.y = torch.empty((T, n, f), dtype=dt, device=dev) if blk.window else None
@@ -177,7 +188,7 @@ class BlockTrainer:
                 elif self.dx is not None:
                     with self._stage("input_grad"):
                         B.input_grad(self.h, blk.weight(t, 0), self.dx[t - 1])
-            if t >= 3:   # A_{t-1} from A_t: the same rebuild with the two lists exchanged (A_1 was kept)
+            if t >= 3 and not self.keep_snapshots:   # A_{t-1} from A_t: the same rebuild with the two lists exchanged (A_1 was kept)
                 self._rebuild(self.a, blk.deltas[t - 2], blk.nnz[t - 1], t, t - 1, reverse=True)
                 if self.directed:
                     self._rebuild(self.at, self.t_deltas[t - 2], blk.nnz[t - 1], t, t - 1, reverse=True)
@@ -204,14 +215,15 @@ def make_smoothed_trainer(wl, blk: BlockInputs, life: int) -> "SmoothedTrainer":
     return SmoothedTrainer(blk, life, True, transposed_first=first, transposed_deltas=deltas)
 
 
-def make_trainer(wl, blk: BlockInputs, want_dx: bool = False) -> BlockTrainer:
+def make_trainer(wl, blk: BlockInputs, want_dx: bool = False, keep_snapshots: bool = False) -> BlockTrainer:
     """Trainer for a generated block; for a directed workload the transposed first snapshot and lists are
     prepared here with the generator's formatting helper."""
     directed = wl.graph != "er"
     if not directed:
-        return BlockTrainer(blk, False, want_dx=want_dx)
+        return BlockTrainer(blk, False, want_dx=want_dx, keep_snapshots=keep_snapshots)
     first, t_deltas = transposed_inputs(blk)
-    return BlockTrainer(blk, True, transposed_first=first, transposed_deltas=t_deltas, want_dx=want_dx)
+    return BlockTrainer(blk, True, transposed_first=first, transposed_deltas=t_deltas, want_dx=want_dx,
+                        keep_snapshots=keep_snapshots)
 
 
 class CheckpointedTrainer:

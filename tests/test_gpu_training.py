@@ -254,3 +254,20 @@ def test_evolving_weights_end_to_end():
     for name, got, exp in (("dU_x", ev.du_x, want[0]), ("dU_h", ev.du_h, want[1]), ("db", ev.db, want[2]), ("dW_0", ev.dw0, want[3])):
         err = np.abs(to_f64(got) - exp).max()
         assert err <= 2e-4 * np.abs(exp).max(), f"{name}: max err {err:.3e} against max |.| {np.abs(exp).max():.3e}"
+
+
+@pytest.mark.parametrize("name", ["c1", "c3"])
+def test_training_step_with_all_snapshots_resident(name):
+    """keep_snapshots: every A_t (and A_t^T) of the block stays in a slot of its own and the backward pass rebuilds
+    nothing; the gradients are bit for bit those of the trainer that walks the snapshots back by reverse rebuilds."""
+    wl = WORKLOADS[name] if name == "c1" else WORKLOADS[name].scaled(1 << 12, T=5)
+    blk = make_block(wl, DEV, gen_device="cpu")
+    g_y = torch.stack([gradient(wl, t, "cpu") for t in range(1, wl.T + 1)]).to(DEV)
+    ref, kept = make_trainer(wl, blk), make_trainer(wl, blk, keep_snapshots=True)
+    for tr in (ref, kept):
+        for _ in range(2):
+            tr.forward()
+            tr.backward(g_y)
+    torch.cuda.synchronize()
+    for a, b in zip(ref.dw, kept.dw):
+        assert torch.equal(a, b)
