@@ -568,6 +568,26 @@ def main():
         out["hip_graph_replay"] = {"value": edges_per_step / el, "unit": "edges/s", "ms_per_step": el * 1e3}
         del graph
         progress("graph replay timed")
+        if not args.no_train:
+            # the training step (forward + backward over every snapshot) as one graph, if it fits in one block
+            try:
+                from dtdg_synth import gradient
+                from paper_2109_07893_amd.training import capture_training_step, make_trainer
+                g_y = torch.stack([gradient(wl, t, dev) for t in range(1, blk.T + 1)])
+                tr = make_trainer(wl, blk)
+                tgraph = capture_training_step(tr, g_y)
+                tgraph.replay()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(args.steps):
+                    tgraph.replay()
+                torch.cuda.synchronize()
+                el = (time.perf_counter() - t0) / args.steps
+                out["hip_graph_replay"]["training_step"] = {"value": sum(blk.nnz) / el, "unit": "edges/s", "ms_per_step": el * 1e3}
+                del tgraph, tr, g_y
+            except Exception as exc:                  # noqa: BLE001 -- an extra figure (a large workload may not fit twice)
+                out["hip_graph_replay"]["training_step"] = {"error": f"{type(exc).__name__}: {exc}"[:300]}
+            torch.cuda.empty_cache()
     # figures of the rows built after the hot path: on request, or all of them unless --no-extras; a failure there is
     # reported in its own object and never costs the headline line
     def extra(key, flag, fn):

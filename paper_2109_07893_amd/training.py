@@ -194,6 +194,22 @@ class BlockTrainer:
                     self._rebuild(self.at, self.t_deltas[t - 2], blk.nnz[t - 1], t, t - 1, reverse=True)
 
 
+def capture_training_step(tr: "BlockTrainer", g_y: torch.Tensor) -> "torch.cuda.CUDAGraph":
+    """One training step (forward keeping activations, then backward for the upstream gradient g_y) recorded as a HIP
+    graph: every library call on the way only enqueues kernels, so the step is capturable, and replaying it costs one
+    launch instead of one per kernel, which is what bounds small workloads.  The step is run once eagerly first, so
+    that one-time host-side set-up inside the library is not part of the recording.  Replays read g_y and the block's
+    inputs where they lie and leave the gradients in tr.dw."""
+    tr.forward()
+    tr.backward(g_y)
+    torch.cuda.synchronize(tr.dev)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        tr.forward()
+        tr.backward(g_y)
+    return graph
+
+
 def transposed_inputs(blk: BlockInputs):
     """(rowptr, colidx) of A_1^T and the difference lists of the transposed series, prepared with the generator's
     formatting helper (a sort by (col, row); input formatting, no arithmetic of the method)."""

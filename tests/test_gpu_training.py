@@ -271,3 +271,29 @@ def test_training_step_with_all_snapshots_resident(name):
     torch.cuda.synchronize()
     for a, b in zip(ref.dw, kept.dw):
         assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("name", ["c1", "c3"])
+def test_training_step_as_a_hip_graph_repeats_the_eager_result(name):
+    """The training step captured once and replayed several times, with eager steps and synchronisations between the
+    replays; every replay must leave exactly the gradients the eager step leaves."""
+    from paper_2109_07893_amd.training import capture_training_step
+    wl = WORKLOADS[name] if name == "c1" else WORKLOADS[name].scaled(1 << 12, T=4)
+    blk = make_block(wl, DEV, gen_device="cpu")
+    g_y = torch.stack([gradient(wl, t, "cpu") for t in range(1, wl.T + 1)]).to(DEV)
+    tr = make_trainer(wl, blk)
+    tr.forward(); tr.backward(g_y)
+    torch.cuda.synchronize()
+    want = [d.clone() for d in tr.dw]
+    graph = capture_training_step(tr, g_y)
+    for k in range(4):
+        for d in tr.dw:
+            d.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(tr.dw, want):
+            assert torch.equal(a, b), k
+        tr.forward(); tr.backward(g_y)                 # eager work between replays
+        torch.cuda.synchronize()
+        for a, b in zip(tr.dw, want):
+            assert torch.equal(a, b), k
