@@ -3,7 +3,8 @@
 
 A step is one forward pass over one GPU's block of snapshots of a seeded synthetic dynamic graph:
 for every snapshot after the first, rebuild its CSR on the GPU from the previous snapshot and the
-graph difference (lists already resident in HBM), then H = X W and Z = relu(A~ H) per GCN layer;
+graph difference (c5: lists copied from pinned host memory on a second stream inside the timed region;
+the other workloads: lists resident in HBM), then H = X W and Z = relu(A~ H) per GCN layer;
 workloads with a window finish with the M-transform over the block.  Throughput is the paper's
 definition (Section "Scaling Study", weak scaling): edges summed over the processed snapshots
 divided by time.
@@ -42,7 +43,10 @@ def parse_args():
     ap.add_argument("--T", type=int, default=0, help="override the number of snapshots (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="stop the oracle sample after this much work")
-    ap.add_argument("--pinned", action="store_true", help="also time the pass with difference lists in pinned host memory")
+    ap.add_argument("--pinned", action="store_true",
+                    help="difference lists in pinned host memory, copied on a second stream inside the timed region "
+                         "(the default for c5, whose definition says so)")
+    ap.add_argument("--resident", action="store_true", help="difference lists already in HBM (the default except for c5)")
     ap.add_argument("--no-train", action="store_true", help="skip the training-step (forward + backward) measurement")
     ap.add_argument("--graph", action="store_true",
                     help="also time the forward pass replayed as one HIP graph (for launch-bound small workloads)")
@@ -81,46 +85,88 @@ def algorithmic_bytes(blk, stage, t=None):
     raise KeyError(stage)
 
 
+STAGE_SOURCES = {"spmm": ("spmm.hip", "common.hpp"), "delta_rebuild": ("delta_rebuild.hip", "common.hpp"),
+                 "feature_transform": ("feature_transform.hip", "common.hpp"), "mproduct": ("mproduct.hip", "common.hpp")}
+
+
+def kernel_source_digest(stage):
+    """sha256 over the source files a stage's kernels are compiled from (what a committed counter profile is tied to)."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in STAGE_SOURCES[stage]:
+        with open(os.path.join(ROOT, "paper_2109_07893_amd", "csrc", name), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
 def committed_traffic(workload, stage):
-    """HBM bytes per call from the committed rocprofv3 counter summary, if there is one."""
-    path = os.path.join(ROOT, "profiles", f"{stage}_{workload}_hbm_traffic.txt")
+    """(bytes per call, where they come from).  The bytes are rocprofv3 FETCH_SIZE + WRITE_SIZE of the stage's kernels
+    from the committed counter summary, which names the digest of the kernel sources it was taken on; a summary taken
+    on other sources is refused (None), so the figure cannot go stale silently."""
+    rel = os.path.join("profiles", f"{stage}_{workload}_hbm_traffic.txt")
+    path = os.path.join(ROOT, rel)
     if not os.path.exists(path):
-        return None
-    m = re.search(r"^traffic_bytes_per_call:\s*([0-9.eE+]+)", open(path).read(), flags=re.M)
-    return float(m.group(1)) if m else None
+        return None, "no committed counter summary for this stage and workload"
+    text = open(path).read()
+    m = re.search(r"^traffic_bytes_per_call:\s*([0-9.eE+]+)", text, flags=re.M)
+    d = re.search(r"^kernel_source_digest:\s*([0-9a-f]+)", text, flags=re.M)
+    if not m:
+        return None, f"{rel} holds no traffic_bytes_per_call line"
+    now = kernel_source_digest(stage)
+    if not d or d.group(1) != now:
+        return None, (f"{rel} was taken on kernel sources {d.group(1) if d else '(not recorded)'}, the build now has {now}: "
+                      "refused, retake the counter passes")
+    return float(m.group(1)), f"{rel} (separate rocprofv3 --pmc passes on kernel sources {now})"
 
 
 def cpu_baseline(wl, blk, first, budget_s):
-    """The oracle as it stands, on the host cores, over the first timesteps of the same block."""
+    """The oracle as it stands on the host cores, over the first timesteps of the same block: one thread first (the
+    baseline figure), then all threads the box gives it."""
     import numpy as np
     import oracle
     n = blk.n
-    rp = blk.rowptr1.cpu().numpy()
-    ci = blk.colidx1.cpu().numpy()
     ws = [w.detach().cpu().double().numpy() for w in blk.w]
-    edges, spent, done = 0, 0.0, []
-    for t in range(1, blk.T + 1):
-        lists = [x.cpu().numpy() for x in blk.deltas[t - 2]] if t >= 2 else None
-        x = blk.x[t - 1].detach().cpu().double().numpy()
-        t0 = time.perf_counter()
-        if t >= 2:
-            rp, ci = oracle.delta_apply(n, rp, ci, *lists)
-        if t >= first:
-            val = oracle.gcn_values(rp, ci)
-            cur = x
-            for w in ws:
-                cur = oracle.spmm(rp, ci, oracle.xw(cur, w), relu=True, val=val)
-        dt = time.perf_counter() - t0
-        if t >= first:
-            spent += dt
-            edges += int(ci.size)
-            done.append(t)
-        if spent >= budget_s:
-            break
-    return {"value": edges / spent if spent > 0 else None, "unit": "edges/s", "cores": oracle.num_threads(),
-            "kind": "oracle", "seconds": round(spent, 3),
-            "sample": f"timesteps t={done[0]}..{done[-1]} of the same block (rebuild + {len(ws)} GCN layer(s), "
-                      f"no M-transform), full graph, {edges} edges"}
+    all_threads = oracle.num_threads()
+
+    def run(threads, t_stop, budget):
+        oracle.set_threads(threads)
+        rp = blk.rowptr1.cpu().numpy()
+        ci = blk.colidx1.cpu().numpy()
+        edges, spent, done = 0, 0.0, []
+        for t in range(1, min(blk.T, t_stop) + 1):
+            lists = [x.cpu().numpy() for x in blk.deltas[t - 2]] if t >= 2 else None
+            x = blk.x[t - 1].detach().cpu().double().numpy()
+            t0 = time.perf_counter()
+            if t >= 2:
+                rp, ci = oracle.delta_apply(n, rp, ci, *lists)
+            if t >= first:
+                val = oracle.gcn_values(rp, ci)
+                cur = x
+                for w in ws:
+                    cur = oracle.spmm(rp, ci, oracle.xw(cur, w), relu=True, val=val)
+            dt = time.perf_counter() - t0
+            if t >= first:
+                spent += dt
+                edges += int(ci.size)
+                done.append(t)
+            if spent >= budget:
+                break
+        progress(f"oracle with {threads} thread(s): t={done[0]}..{done[-1]} in {spent:.1f} s")
+        return {"value": edges / spent if spent > 0 else None, "unit": "edges/s", "cores": threads, "seconds": round(spent, 3),
+                "sample": f"timesteps t={done[0]}..{done[-1]} of the same block (rebuild + {len(ws)} GCN layer(s), "
+                          f"no M-transform), full graph, {edges} edges"}
+
+    try:
+        model = next(l.split(":", 1)[1].strip() for l in open("/proc/cpuinfo") if l.startswith("model name"))
+    except (OSError, StopIteration):
+        model = "unknown"
+    # one thread: a single timed timestep of a large workload is already tens of seconds; all threads: at least three
+    single = run(1, first + 2, budget_s)
+    multi = run(all_threads, first + 2, 3 * budget_s)
+    oracle.set_threads(all_threads)
+    out = dict(single)
+    out.update({"kind": "oracle", "all_cores": multi, "nproc": os.cpu_count(), "cpu_model": model})
+    return out
 
 
 def weighted_step(args, wl, blk, dev):
@@ -441,8 +487,11 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    # c5 is defined with its difference lists in pinned host memory: the copies (dgnn_delta_h2d on a second stream,
+    # one step ahead) are then inside the timed region.  The other workloads keep their lists in HBM.
+    pinned = (args.workload == "c5" or args.pinned) and not args.resident
     t_gen = time.perf_counter()
-    blk = make_block(wl, dev, gen_device=dev, pinned=args.pinned, T=T)
+    blk = make_block(wl, dev, gen_device=dev, pinned=pinned, T=T)
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
     progress(f"inputs of {wl.name} generated in {t_gen:.1f} s")
@@ -454,33 +503,61 @@ def main():
     first = 1 if blk.window else 2
     edges_per_step = sum(blk.nnz[first - 1:])
 
-    def one_step():
+    def timed(step_fn, before=None, after=None):
+        """Seconds per step of step_fn over args.steps back-to-back steps after args.warmup untimed ones."""
+        if before:
+            before()
+        for _ in range(args.warmup):
+            step_fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step_fn()
+        torch.cuda.synchronize()
+        el = (time.perf_counter() - t0) / args.steps
+        if after:
+            after()
+        return el
+
+    def resident_step():
         runner.run_resident(first=first)
 
-    for _ in range(args.warmup):
-        one_step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        one_step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed / args.steps * 1e3
-    value = edges_per_step / (elapsed / args.steps)
-    progress(f"forward timed: {ms_per_step:.2f} ms per step")
+    def pinned_step():            # steps follow one another: the first lists of the next step travel while this one finishes
+        runner.run_from_pinned(first=first, prefetch_next=True)
 
-    # per-stage durations: the same steps again with an event pair around every library call
+    def pinned_single_block():    # a step on its own: its first copy has nothing to hide behind
+        runner.run_from_pinned(first=first)
+
+    if pinned:
+        one_step = pinned_step
+        per_step = timed(pinned_step)
+        runner.run_from_pinned(first=first)          # consumes the outstanding request
+        torch.cuda.synchronize()
+    else:
+        one_step = resident_step
+        per_step = timed(resident_step)
+    ms_per_step = per_step * 1e3
+    value = edges_per_step / per_step
+    progress(f"forward timed: {ms_per_step:.2f} ms per step ({'pinned host lists' if pinned else 'lists resident'})")
+
+    # per-stage durations: the same steps again with an event pair around every library call, on the stream it is
+    # enqueued on (the list copies on the copy stream)
     runner.timer = StageTimer(dev)
     for _ in range(args.steps):
         one_step()
     torch.cuda.synchronize()
     totals = runner.timer.totals()
     runner.timer = None
+    if pinned:
+        runner.run_from_pinned(first=first)
+        torch.cuda.synchronize()
     stages = {}
     for name, (calls, ms) in totals.items():
         per_step_calls = calls // args.steps
         if name == "mproduct":
             byts = algorithmic_bytes(blk, name)
+        elif name == "delta_h2d":
+            byts = sum(8 * (d[0].numel() + d[2].numel()) for d in blk.deltas) / max(per_step_calls, 1)
         else:
             ts = range(2, T + 1) if name == "delta_rebuild" else range(first, T + 1)
             reps = blk.layers if name in ("feature_transform", "spmm") else 1
@@ -489,21 +566,28 @@ def main():
         stages[name] = {"calls_per_step": per_step_calls, "avg_ms": round(avg_ms, 4),
                         "ms_per_step": round(ms / args.steps, 4), "algorithmic_bytes_per_call": int(byts),
                         "algorithmic_GBps": round(byts / (avg_ms * 1e-3) / 1e9, 1)}
-    dominant = max(stages, key=lambda k: stages[k]["ms_per_step"])
+        if name == "delta_h2d":
+            stages[name]["note"] = "host link (PCIe), on the copy stream, overlapped with the other stages; not HBM traffic"
+    on_gpu = {k: v for k, v in stages.items() if k != "delta_h2d"}
+    dominant = max(on_gpu, key=lambda k: on_gpu[k]["ms_per_step"])
     achieved = stages[dominant]["algorithmic_GBps"]
     kernels = {"spmm": "dgnn_spmm (spmm_stream_kernel + spmm_carry_kernel)",
                "delta_rebuild": "dgnn_delta_rebuild (rowptr_kernel + merge_kernel)",
                "feature_transform": "dgnn_feature_transform (xw kernel)", "mproduct": "dgnn_mproduct (mproduct_kernel)"}
-    traffic = committed_traffic(args.workload, dominant)
+    traffic, traffic_note = committed_traffic(args.workload, dominant)
     roofline = {"bound": "hbm", "kernel": kernels[dominant], "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_source": traffic_note,
                 "avg_ms": stages[dominant]["avg_ms"],
                 "algorithmic_bytes_per_call": stages[dominant]["algorithmic_bytes_per_call"]}
-    if traffic:   # counter bytes of the committed profile over the duration measured now
-        roofline["traffic_GBps"] = round(traffic / (stages[dominant]["avg_ms"] * 1e-3) / 1e9, 1)
-        roofline["traffic_frac"] = round(roofline["traffic_GBps"] / HBM_PEAK_GBS, 4)
-    all_bytes = sum(v["algorithmic_bytes_per_call"] * v["calls_per_step"] for v in stages.values())
+    if traffic:   # counter bytes of the committed profile (taken on the same kernel source) over the duration measured now
+        roofline["traffic_l2_miss_GBps"] = round(traffic / (stages[dominant]["avg_ms"] * 1e-3) / 1e9, 1)
+        roofline["traffic_note"] = ("FETCH_SIZE / WRITE_SIZE count what leaves the L2s: fetches served by the Infinity Cache are "
+                                    "included, so the rate is L2-miss traffic, not an HBM fraction")
+    all_bytes = sum(v["algorithmic_bytes_per_call"] * v["calls_per_step"] for v in on_gpu.values())
 
+    lists_where = ("pinned host memory; dgnn_delta_h2d on a second stream inside the timed region, one step ahead; steps "
+                   "follow one another, so the first lists of the next step are requested while this one finishes"
+                   if pinned else "resident in HBM")
     out = {
         "metric": "snapshot-edges/sec (delta rebuild + SpMM)", "value": value, "unit": "edges/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
@@ -512,33 +596,23 @@ def main():
         "config": {"workload": f"{wl.name}: N={blk.n}, T={T}, {wl.graph}, F={blk.f}, {wl.dtype}, layers={blk.layers}, "
                                f"window={blk.window}, churn del {wl.del_frac:g} + add {wl.add_frac:g} per step",
                    "snapshots_per_step": T - first + 1, "edges_per_step": edges_per_step,
-                   "nnz_first": blk.nnz[0], "nnz_last": blk.nnz[-1], "difference_lists": "resident in HBM",
-                   "timed": f"t={first}..{T}: " + ("delta rebuild (t>=2) + " if first == 1 else "delta rebuild + ")
+                   "nnz_first": blk.nnz[0], "nnz_last": blk.nnz[-1], "difference_lists": lists_where,
+                   "timed": f"t={first}..{T}: " + ("list copy host -> device + " if pinned else "")
+                            + ("delta rebuild (t>=2) + " if first == 1 else "delta rebuild + ")
                             + f"{blk.layers}x(X W + SpMM)" + (" + M-transform" if blk.window else "")},
         "roofline": roofline,
         "stages": stages,
         "hbm_frac_algorithmic_whole_step": round(all_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "north_star_target": {"hbm_frac": 0.60, "met": bool(all_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS >= 0.60),
+                              "note": "target: delta rebuild + SpMM at 60 % of the HBM peak; the fractions above count "
+                                      "algorithmic bytes (every row of H fetched once), the gather of a scrambled power-law "
+                                      "graph moves several times that"},
         "generate_s": round(t_gen, 2),
     }
 
-    if args.pinned:
-        for _ in range(args.warmup):
-            runner.run_from_pinned(first=first)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            runner.run_from_pinned(first=first)
-        torch.cuda.synchronize()
-        el = time.perf_counter() - t0
-        # a stream of blocks: the first lists of the next pass are requested while this pass finishes
-        runner.run_from_pinned(first=first, prefetch_next=True)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            runner.run_from_pinned(first=first, prefetch_next=True)
-        torch.cuda.synchronize()
-        el_stream = time.perf_counter() - t0
-        runner.run_from_pinned(first=first)          # consumes the outstanding request
+    if pinned:
+        el_single = timed(pinned_single_block)
+        el_res = timed(resident_step)
         h2d = sum(8 * (d[0].numel() + d[2].numel()) for d in blk.deltas)
         # the copies alone, nothing computing: what the host link delivers for these list sizes
         torch.cuda.synchronize()
@@ -547,12 +621,12 @@ def main():
             dg.delta_h2d(*lists, *runner.stage[0])
         torch.cuda.synchronize()
         link_s = time.perf_counter() - t0
-        out["pinned_host_lists"] = {"value": edges_per_step / (el / args.steps), "unit": "edges/s",
-                                    "ms_per_step": el / args.steps * 1e3, "h2d_bytes_per_step": h2d,
-                                    "h2d_alone_ms": link_s * 1e3, "h2d_alone_GBps": h2d / link_s / 1e9,
-                                    "streamed_blocks": {"value": edges_per_step / (el_stream / args.steps),
-                                                        "ms_per_step": el_stream / args.steps * 1e3},
+        out["pinned_host_lists"] = {"h2d_bytes_per_step": h2d, "h2d_alone_ms": link_s * 1e3, "h2d_alone_GBps": h2d / link_s / 1e9,
+                                    "single_block": {"value": edges_per_step / el_single, "unit": "edges/s", "ms_per_step": el_single * 1e3,
+                                                     "note": "one step on its own: the first copy of the step is not hidden"},
                                     "whole_snapshot_bytes_per_step": sum(4 * (z + blk.n + 1) for z in blk.nnz[1:])}
+        out["lists_resident_in_hbm"] = {"value": edges_per_step / el_res, "unit": "edges/s", "ms_per_step": el_res * 1e3,
+                                        "note": "the same step without the host-to-device copies (not the headline)"}
 
     progress("per-stage pass done")
     if args.graph:

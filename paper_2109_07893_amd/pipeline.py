@@ -219,11 +219,12 @@ class BlockRunner:
             self.run_resident(first=first)
         return graph
 
-    def run_from_pinned(self, first: int = 1, prefetch_next: bool = False) -> None:
+    def run_from_pinned(self, first: int = 1, prefetch_next: bool = False, validate: bool = False, on_snapshot=None) -> None:
         """Same pass with the difference lists of step t+1 copied from pinned host memory on a second
         stream while step t computes (two staging sets, events both ways).  With prefetch_next the lists of
         the next pass's first step are already requested while this pass finishes (a stream of blocks: the
-        next block's first lists travel during the current block's last steps)."""
+        next block's first lists travel during the current block's last steps).  on_snapshot(t, slot) as in
+        run_resident."""
         blk = self.blk
         assert self.stage is not None
         main = torch.cuda.current_stream(self.dev)
@@ -232,7 +233,8 @@ class BlockRunner:
             k = t % 2
             with torch.cuda.stream(self.copy_stream):
                 self.copy_stream.wait_event(self.consumed[k])
-                B.delta_h2d(*blk.pinned[t - 2], *self.stage[k])
+                with self._stage("delta_h2d"):           # event pair on the copy stream (the current stream here)
+                    B.delta_h2d(*blk.pinned[t - 2], *self.stage[k])
                 self.copied[k].record(self.copy_stream)
 
         if not getattr(self, "_first_lists_requested", False):
@@ -248,7 +250,7 @@ class BlockRunner:
                 main.wait_event(self.copied[k])
                 if t + 1 <= blk.T:
                     issue_copy(t + 1)
-                self.rebuild(t, self.stage[k])
+                self.rebuild(t, self.stage[k], validate)
                 self.consumed[k].record(main)
                 if t == blk.T and prefetch_next and blk.T >= 3:     # both staging sets have been used and released
                     issue_copy(2)
@@ -256,6 +258,8 @@ class BlockRunner:
             self.snapshot_ready(t)
             if t >= first:
                 self.gcn(t)
+            if on_snapshot is not None:
+                on_snapshot(t, self.slot_of(t))
         self.mix()
 
     def snapshot_to_host(self, t: int):
