@@ -161,6 +161,21 @@ int dgnn_spmm(int64_t n, int64_t nnz, const int32_t *rowptr, const int32_t *coli
               void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * dgnn_spmm for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-for-bit the same result as dgnn_spmm, but no
+ * workspace argument: the carry records live in a device array of fixed size inside the library
+ * (dgnn_spmm_static_limit() bytes, 32 MiB, held by every GPU the library runs on until the process ends).
+ * DGNN_ERR_CAPACITY if the records of this call, (16 + 8 f) bytes per 8192 stored entries and never fewer than
+ * 16385 of them, exceed that limit (f = 32: beyond 1.0e9 stored entries; f = 128: beyond 2.6e8); nothing is
+ * enqueued then.  Neither this call nor anything it calls allocates or frees; the
+ * first call on a device looks up the array's address on that device, once.  All calls on one GPU share the one array:
+ * calls that overlap in time on the same GPU (two streams, two threads) race on it, and the caller must order them.
+ */
+int dgnn_spmm_static_limit(size_t *bytes);
+int dgnn_spmm_static(int64_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *dinv,
+                     const void *h, int32_t f, void *z, dgnn_dtype dt, uint32_t flags, void *stream);
+
+/*
  * M-transform (Section "TM-GCN"): Y = Z x_1 M for the banded lower-triangular M,
  *     Y_t = sum_{j=0}^{min(w,t)-1} m(t,j) Z_{t-j},   t = 1..T (1-based),
  *   z, y [T][n][f]          storage type dt; y may be the same pointer as z (in place), and

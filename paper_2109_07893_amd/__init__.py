@@ -8,7 +8,8 @@ into those calls.  There is no CPU fallback: without the built library the calls
 from .binding import (  # noqa: F401
     DgnnError, build_library, library_path, load_library, strerror,
     # the hot path
-    csr_validate, csr_dinv, delta_h2d, delta_rebuild, delta_rebuild_workspace, feature_transform, spmm, spmm_workspace, mproduct,
+    csr_validate, csr_dinv, delta_h2d, delta_rebuild, delta_rebuild_workspace, feature_transform, spmm, spmm_workspace, spmm_static,
+    spmm_static_limit, mproduct,
     # its backward half, and a series processed in blocks
     mproduct_backward, mproduct_block, mproduct_backward_block, relu_backward, weight_grad, weight_grad_workspace,
     input_grad,

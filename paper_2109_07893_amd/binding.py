@@ -23,7 +23,8 @@ DGNN_H_PRESCALED = 2
 
 EXPORTS = (
     "dgnn_strerror", "dgnn_csr_validate", "dgnn_csr_dinv", "dgnn_delta_h2d", "dgnn_delta_rebuild_workspace",
-    "dgnn_delta_rebuild", "dgnn_feature_transform", "dgnn_spmm_workspace", "dgnn_spmm", "dgnn_mproduct",
+    "dgnn_delta_rebuild", "dgnn_feature_transform", "dgnn_spmm_workspace", "dgnn_spmm", "dgnn_spmm_static_limit",
+    "dgnn_spmm_static", "dgnn_mproduct",
     "dgnn_delta_rebuild_weighted", "dgnn_spmm_weighted", "dgnn_csr_combine_workspace", "dgnn_csr_combine", "dgnn_csr_weighted_dinv_workspace", "dgnn_csr_weighted_dinv", "dgnn_concat_relu", "dgnn_lstm_cell", "dgnn_lstm_step", "dgnn_lstm_cell_backward", "dgnn_lstm_step_backward", "dgnn_concat_relu_backward", "dgnn_bias_grad_workspace", "dgnn_bias_grad", "dgnn_add",
     "dgnn_mproduct_backward", "dgnn_mproduct_block", "dgnn_mproduct_backward_block", "dgnn_relu_backward", "dgnn_weight_grad_workspace", "dgnn_weight_grad", "dgnn_input_grad",
 )
@@ -96,6 +97,8 @@ def load_library():
     lib.dgnn_feature_transform.argtypes = [_vp, _i64, _i32, _vp, _i32, _vp, _vp, ctypes.c_int, _vp]
     lib.dgnn_spmm_workspace.argtypes = [_i64, _i64, _i32, ctypes.POINTER(_sz)]
     lib.dgnn_spmm.argtypes = [_i64, _i64, _vp, _vp, _vp, _vp, _i32, _vp, ctypes.c_int, _u32, _vp, _sz, _vp]
+    lib.dgnn_spmm_static_limit.argtypes = [ctypes.POINTER(_sz)]
+    lib.dgnn_spmm_static.argtypes = [_i64, _i64, _vp, _vp, _vp, _vp, _i32, _vp, ctypes.c_int, _u32, _vp]
     lib.dgnn_mproduct.argtypes = [_vp, _vp, _i64, _i64, _i32, _i32, _vp, ctypes.c_int, _vp]
     lib.dgnn_mproduct_backward.argtypes = [_vp, _vp, _i64, _i64, _i32, _i32, _vp, ctypes.c_int, _vp]
     lib.dgnn_delta_rebuild_weighted.argtypes = [_i64, _vp, _vp, _vp, _i64, _vp, _vp, _vp, _i64, _vp, _vp, _i64,
@@ -241,6 +244,23 @@ def spmm(rowptr, colidx, nnz: int, dinv, h: torch.Tensor, z: torch.Tensor, ws, f
         raise ValueError("shape mismatch in spmm")
     _check(load_library().dgnn_spmm(n, nnz, _ptr(rowptr), _ptr(colidx), _ptr(dinv), _ptr(h), f, _ptr(z), dt, flags,
                                     _ptr(ws), ws.numel() * ws.element_size(), _stream(h)), "dgnn_spmm")
+
+
+def spmm_static_limit() -> int:
+    out = _sz(0)
+    _check(load_library().dgnn_spmm_static_limit(ctypes.byref(out)), "dgnn_spmm_static_limit")
+    return int(out.value)
+
+
+def spmm_static(rowptr, colidx, nnz: int, dinv, h: torch.Tensor, z: torch.Tensor, flags: int = 0) -> None:
+    """Z = sigma?(A~ H) without a workspace argument (scratch inside the library; nothing is allocated)."""
+    _need(rowptr, torch.int32, "rowptr"); _need(colidx, torch.int32, "colidx")
+    dt = _dtype_code(h)
+    n, f = h.shape
+    if rowptr.numel() != n + 1 or tuple(z.shape) != (n, f) or z.dtype != h.dtype or colidx.numel() < nnz:
+        raise ValueError("shape mismatch in spmm_static")
+    _check(load_library().dgnn_spmm_static(n, nnz, _ptr(rowptr), _ptr(colidx), _ptr(dinv), _ptr(h), f, _ptr(z), dt, flags,
+                                           _stream(h)), "dgnn_spmm_static")
 
 
 def mproduct(z: torch.Tensor, y: torch.Tensor, w: int, m_band: Optional[torch.Tensor] = None) -> None:

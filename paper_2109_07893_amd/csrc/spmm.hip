@@ -499,8 +499,10 @@ int range_length(int64_t nnz, int sub_tile) {
 // Sized for the largest number of ranges any call with at most nnz entries can have (a smaller snapshot gets
 // shorter ranges, never more than kTargetWaves + 1 of them), so a buffer queried for the largest snapshot of a
 // block serves every snapshot of it, and both dtypes.
-size_t workspace_layout(int64_t nnz, int32_t f, Workspace *ws, void *base) {
-    const int64_t ranges = std::max<int64_t>(kTargetWaves + 1, (nnz + kMaxRange - 1) / kMaxRange) + 1;
+size_t workspace_layout(int64_t nnz, int32_t f, Workspace *ws, void *base, int64_t exact_ranges = 0) {
+    // exact_ranges: the number of ranges of one particular call (a caller that knows the call and has little room)
+    const int64_t ranges = exact_ranges > 0 ? exact_ranges
+                                            : std::max<int64_t>(kTargetWaves + 1, (nnz + kMaxRange - 1) / kMaxRange) + 1;
     const size_t o_carry = round_up((size_t)ranges * sizeof(RangeRec), 256);
     const size_t total = o_carry + round_up((size_t)ranges * 2 * f * sizeof(float), 256);
     if (ws) {
@@ -543,9 +545,16 @@ extern "C" int dgnn_spmm_workspace(int64_t n, int64_t nnz, int32_t f, size_t *by
 
 namespace {
 
+// Ranges of one call: what launch() below will use for this snapshot, width and storage type.
+int64_t ranges_of_call(int64_t nnz, int32_t f, dgnn_dtype dt) {
+    const int lpr = dt == DGNN_F32 ? f / 4 : f / 8;
+    const int range_len = range_length(nnz, (kWave / lpr) * kPer);
+    return (nnz + range_len - 1) / range_len;
+}
+
 int spmm(int64_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *dinv, const float *vals,
          const void *h, int32_t f, void *z, dgnn_dtype dt, uint32_t flags, uint32_t allowed, void *ws, size_t ws_bytes,
-         void *stream) {
+         void *stream, bool exact_layout = false) {
     if (!rowptr || !colidx || !h || !z || !ws) return DGNN_ERR_NULL;
     if (n <= 0 || nnz <= 0 || !supported_width(f) || (flags & ~allowed)) return DGNN_ERR_SHAPE;
     if (dt != DGNN_F32 && dt != DGNN_BF16) return DGNN_ERR_SHAPE;
@@ -553,7 +562,7 @@ int spmm(int64_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, c
     if (!aligned16(h) || !aligned16(z) || !aligned16(ws)) return DGNN_ERR_ALIGN;
     if (h == z) return DGNN_ERR_ALIAS;
     Workspace w;
-    if (ws_bytes < workspace_layout(nnz, f, &w, ws)) return DGNN_ERR_CAPACITY;
+    if (ws_bytes < workspace_layout(nnz, f, &w, ws, exact_layout ? ranges_of_call(nnz, f, dt) : 0)) return DGNN_ERR_CAPACITY;
     hipStream_t s = (hipStream_t)stream;
     const int relu = (flags & DGNN_RELU) ? 1 : 0;
     const bool scale_v = vals != nullptr || (dinv != nullptr && !(flags & DGNN_H_PRESCALED));
@@ -578,6 +587,61 @@ extern "C" int dgnn_spmm(int64_t n, int64_t nnz, const int32_t *rowptr, const in
                          const void *h, int32_t f, void *z, dgnn_dtype dt, uint32_t flags,
                          void *ws, size_t ws_bytes, void *stream) {
     return spmm(n, nnz, rowptr, colidx, dinv, nullptr, h, f, z, dt, flags, DGNN_RELU | DGNN_H_PRESCALED, ws, ws_bytes, stream);
+}
+
+// ---- the same aggregation for callers that cannot allocate: its carry records live in a file-scope device array ----
+namespace {
+
+constexpr size_t kStaticScratchBytes = size_t(32) << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void *g_scratch_ptr[kMaxDevices];   // per device: the address of that device's copy of `scratch`, asked for once
+
+// The device address of the current device's `scratch` (the array's name is only a host-side handle).
+int static_scratch(void **out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return DGNN_ERR_HIP;
+    }
+    std::lock_guard<std::mutex> guard(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return DGNN_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return DGNN_OK;
+}
+
+}  // namespace
+
+extern "C" int dgnn_spmm_static_limit(size_t *bytes) {
+    if (!bytes) return DGNN_ERR_NULL;
+    *bytes = kStaticScratchBytes;
+    return DGNN_OK;
+}
+
+extern "C" int dgnn_spmm_static(int64_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *dinv,
+                                const void *h, int32_t f, void *z, dgnn_dtype dt, uint32_t flags, void *stream) {
+    // argument errors first, so that they are reported without touching the device
+    if (!rowptr || !colidx || !h || !z) return DGNN_ERR_NULL;
+    if (n <= 0 || nnz <= 0 || !supported_width(f) || (flags & ~(DGNN_RELU | DGNN_H_PRESCALED))) return DGNN_ERR_SHAPE;
+    if (dt != DGNN_F32 && dt != DGNN_BF16) return DGNN_ERR_SHAPE;
+    if (!fits_index(n + 1) || !fits_index(nnz)) return DGNN_ERR_OVERFLOW;
+    if (workspace_layout(nnz, f, nullptr, nullptr, ranges_of_call(nnz, f, dt)) > kStaticScratchBytes) return DGNN_ERR_CAPACITY;
+    void *ptr = nullptr;
+    const int rc = static_scratch(&ptr);
+    if (rc != DGNN_OK) return rc;
+    // every range writes its record and the carries its flags announce before the second kernel reads them, so nothing
+    // in the array has to start at zero; what the previous call left there is never read
+    return spmm(n, nnz, rowptr, colidx, dinv, nullptr, h, f, z, dt, flags, DGNN_RELU | DGNN_H_PRESCALED, ptr,
+                kStaticScratchBytes, stream, /*exact_layout=*/true);
 }
 
 extern "C" int dgnn_spmm_weighted(int64_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *val,

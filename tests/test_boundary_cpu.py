@@ -105,6 +105,22 @@ def test_spmm_argument_errors(lib):
     assert call(nnz=1 << 31) == -4
 
 
+def test_spmm_static_argument_errors(lib):
+    """The variant without a workspace argument refuses bad arguments, and sizes its fixed scratch array cannot serve,
+    on the host, before it touches the device."""
+    f = lib.dgnn_spmm_static
+    limit = ctypes.c_size_t(0)
+    assert lib.dgnn_spmm_static_limit(ctypes.byref(limit)) == 0 and limit.value == 32 << 20
+    assert lib.dgnn_spmm_static_limit(None) == -1
+    assert f(10, 20, None, FAKE, None, FAKE, 32, FAKE + 4096, 0, 0, None) == -1
+    assert f(10, 20, FAKE, FAKE, None, FAKE, 24, FAKE + 4096, 0, 0, None) == -2
+    assert f(10, 20, FAKE, FAKE, None, FAKE, 32, FAKE + 4096, 0, 8, None) == -2
+    assert f(10, 1 << 31, FAKE, FAKE, None, FAKE, 32, FAKE + 4096, 0, 0, None) == -4
+    need = ctypes.c_size_t(0)
+    assert lib.dgnn_spmm_workspace(1 << 20, 1 << 29, 128, ctypes.byref(need)) == 0 and need.value > limit.value
+    assert f(1 << 20, 1 << 29, FAKE, FAKE, None, FAKE, 128, FAKE + 4096, 0, 0, None) == -3
+
+
 def test_mproduct_argument_errors(lib):
     f = lib.dgnn_mproduct
     assert f(None, FAKE, 8, 10, 16, 3, None, 0, None) == -1
