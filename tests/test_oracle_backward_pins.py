@@ -404,6 +404,47 @@ def test_evolving_weights_backward_matches_finite_differences():
     assert np.array_equal(ws[0], h) and np.array_equal(cs[1], c)
 
 
+def test_evolving_weights_recurrence_beyond_the_first_step():
+    """W_t = LSTM(W_{t-1}) for t >= 2: what is fed forward.  (a) The closed form of tests/golden/
+    evolve_cell_gate_bias_only.txt (no products, a bias on the cell gate): C_t = tanh(beta)(1 - 2^-t) only if the cell
+    state is carried from step to step and starts at 0.  (b) A library LSTM cell in double precision applied T times
+    with the previous weight as input AND hidden state and the previous cell state: every W_t and C_t."""
+    import os
+    import torch
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "evolve_cell_gate_bias_only.txt")
+    rows = [line.split() for line in open(path) if not line.startswith("#")]
+    f, f2, beta = 3, 2, 0.5
+    bias = np.zeros(4 * f2)
+    bias[2 * f2:3 * f2] = beta                                   # gate order (input, forget, cell, output)
+    rng = np.random.default_rng(5)
+    ws, cs = oracle.evolve_weights(rng.normal(size=(f, f2)), np.zeros((f2, 4 * f2)), np.zeros((f2, 4 * f2)), bias, len(rows))
+    assert len(ws) == len(rows) and len(cs) == len(rows) + 1 and not cs[0].any()
+    for t_s, c_s, w_s in rows:
+        t = int(t_s)
+        np.testing.assert_allclose(cs[t], float(c_s), rtol=1e-14)
+        np.testing.assert_allclose(ws[t - 1], float(w_s), rtol=1e-14)
+        assert abs(float(c_s) - np.tanh(beta) * (1.0 - 2.0 ** -t)) < 1e-15
+    # (b) general parameters against the library cell, four steps
+    f, f2, T = 4, 3, 4
+    w0 = rng.normal(size=(f, f2))
+    u_x, u_h, b = rng.normal(size=(f2, 4 * f2)) / 2, rng.normal(size=(f2, 4 * f2)) / 2, rng.normal(size=4 * f2) / 3
+    cell = torch.nn.LSTMCell(f2, f2).double()
+    with torch.no_grad():
+        cell.weight_ih.copy_(torch.from_numpy(u_x.T))
+        cell.weight_hh.copy_(torch.from_numpy(u_h.T))
+        cell.bias_ih.copy_(torch.from_numpy(b))
+        cell.bias_hh.zero_()
+        w, c = torch.from_numpy(w0), torch.zeros((f, f2), dtype=torch.float64)
+        want = []
+        for _ in range(T):
+            w, c = cell(w, (w, c))
+            want.append((w.numpy().copy(), c.numpy().copy()))
+    ws, cs = oracle.evolve_weights(w0, u_x, u_h, b, T)
+    for t in range(T):
+        np.testing.assert_allclose(ws[t], want[t][0], rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(cs[t + 1], want[t][1], rtol=1e-12, atol=1e-13)
+
+
 def test_edge_life_smoothing_matches_hand_worked_series():
     """The hand-worked series in tests/golden/edge_life_n3.txt: sliding-window sums by csr_combine, then the weighted
     form of Eqn (1) on S_3."""

@@ -131,6 +131,12 @@ PY_MUTANTS = [
     ("skip connection backward without the ReLU mask", "d_y = d_y * (np.concatenate([y0, y1], axis=1) > 0.0)", "d_y = d_y * 1.0"),
     ("skip connection backward drops the path through Y1", "spmm_t(rowptr, colidx, d_y0 + input_grad(d_y1, w))", "spmm_t(rowptr, colidx, d_y0)"),
     ("evolving weights: gradient reaches W through one product only", "carry = d_x + d_hp", "carry = d_hp"),
+    ("evolving weights: the cell state is not carried past the first step", "w, c = lstm_cell(ws[-1], ws[-1], cs[-1], u_x, u_h, bias)",
+     "w, c = lstm_cell(ws[-1], ws[-1], cs[0], u_x, u_h, bias)"),
+    ("evolving weights: the hidden state stays the initial weight", "w, c = lstm_cell(ws[-1], ws[-1], cs[-1], u_x, u_h, bias)",
+     "w, c = lstm_cell(ws[-1], ws[0], cs[-1], u_x, u_h, bias)"),
+    ("evolving weights: the input stays the initial weight", "w, c = lstm_cell(ws[-1], ws[-1], cs[-1], u_x, u_h, bias)",
+     "w, c = lstm_cell(ws[0], ws[-1], cs[-1], u_x, u_h, bias)"),
 ]
 
 
@@ -138,7 +144,8 @@ def py_pins():
     calls = [bwd.test_weighted_normalisation_reduces_to_eqn_1_and_matches_the_dense_form, bwd.test_csr_combine_special_cases,
              bwd.test_sliding_window_sum_by_csr_combine_equals_the_windowed_sum, bwd.test_edge_life_smoothing_matches_hand_worked_series,
              bwd.test_lstm_cell_backward_matches_finite_differences, bwd.test_cdgcn_gcn_backward_matches_finite_differences,
-             bwd.test_evolving_weights_backward_matches_finite_differences]
+             bwd.test_evolving_weights_backward_matches_finite_differences,
+             bwd.test_evolving_weights_recurrence_beyond_the_first_step]
     for seed in (0, 1, 2):
         calls.append(lambda s=seed: bwd.test_csr_combine_matches_dense_matrices(s))
     calls += [getattr(bwd, n) for n in dir(bwd) if n.startswith("test_lstm_cell_matches") or n.startswith("test_cdgcn_gcn_matches")]
