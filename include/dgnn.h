@@ -66,6 +66,8 @@ typedef enum { DGNN_F32 = 0, DGNN_BF16 = 1 } dgnn_dtype;
 #define DGNN_BAD_ROWPTR 7        /* rowptr[0] != 0, rowptr not ascending, or rowptr[n] != nnz     */
 #define DGNN_BAD_ROW_ORDER 8     /* the columns of a row are not strictly ascending              */
 #define DGNN_BAD_NO_DIAGONAL 9   /* a row does not hold its diagonal entry (only if asked for)   */
+/* ... and by dgnn_csr_combine (the largest code found wins): */
+#define DGNN_BAD_CAPACITY 10     /* the result has more stored entries than colidx_c / val_c hold */
 
 /* Flags of dgnn_spmm. */
 #define DGNN_RELU 1u             /* apply sigma = ReLU to the aggregated rows (Eqn (2)) */
@@ -154,7 +156,8 @@ int dgnn_spmm_workspace(int64_t n, int64_t nnz, int32_t f, size_t *bytes);
  *                           are taken to be dinv[v] * H[v] already and only dinv[u] is applied:
  *                           Z[u] = dinv[u] * sum over stored (u,v) of h[v]
  *   ws, ws_bytes            scratch of at least dgnn_spmm_workspace() bytes
- * The result does not depend on scheduling: no floating-point atomics are used.
+ * nnz may be an upper bound of the number of stored entries (the capacity of colidx, say): the kernels take the
+ * smaller of it and rowptr[n].  The result does not depend on scheduling: no floating-point atomics are used.
  */
 int dgnn_spmm(int64_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *dinv,
               const void *h, int32_t f, void *z, dgnn_dtype dt, uint32_t flags,
@@ -250,7 +253,8 @@ int dgnn_spmm_weighted(int64_t n, int64_t nnz, const int32_t *rowptr, const int3
  * not print the formula; this is Eqn (1) with the degree taken as the weighted row sum, self loop included.
  * ws: device scratch (16-byte aligned) of at least dgnn_csr_weighted_dinv_workspace(nnz) bytes (pieces of rows
  * that are summed by several wavefronts); contents need not be preserved.  Every sum has a fixed
- * order, results repeat bit for bit.  val[0 .. nnz) is read; errors: NULL, SHAPE (n <= 0, nnz <= 0), OVERFLOW,
+ * order, results repeat bit for bit.  val[0 .. min(nnz, rowptr[n])) is read (nnz may be an upper bound of the
+ * number of stored entries); errors: NULL, SHAPE (n <= 0, nnz <= 0), OVERFLOW,
  * CAPACITY (workspace too small), ALIGN.  A row whose sum is not positive (no entries, or
  * weights that cancel) gets 0: such a vertex neither sends nor receives, instead of producing infinities.
  */
@@ -263,27 +267,35 @@ int dgnn_csr_weighted_dinv(int64_t n, int64_t nnz, const int32_t *rowptr, const 
  *     C = S + alpha * A_in + beta * A_out
  * with S a snapshot with values and A_in, A_out unweighted snapshots (every stored entry counts 1), all n x n in
  * CSR with rows sorted by column: S_t = S_{t-1} + A_t - A_{t-l} is alpha = 1, beta = -1 (A_out NULL while the
- * window still grows); divided by min(l, t), which the symmetric normalisation cancels, it is the M-transform
- * applied to the adjacency tensor.  Entries of equal (row, column) are added as S, then alpha, then beta, in fp32;
- * an entry whose result is exactly 0 is not stored (counts are small integers, so this is exact for them).
+ * window still grows).  Entries of equal (row, column) are added as S, then alpha, then beta, in fp32; an entry whose
+ * result is exactly 0 is not stored (counts are small integers, so this is exact for them).
+ *   diag_value: 0 = diagonal entries are summed like all others.  Otherwise every stored diagonal entry of C takes
+ *   this value: the snapshots here hold A + I, but the section smooths A and Eqn (1) then adds the self loop once,
+ *   so edge-life smoothing passes 1 (the self loop keeps weight 1 however long the window is); the M-transform of
+ *   the adjacency tensor divides the sum of the A_i by min(l, t) before I is added, which after the symmetric
+ *   normalisation is the same matrix as the plain sum with the diagonal at min(l, t): what 0 leaves there.
  *   rowptr_s/colidx_s/val_s, nnz_s: S; val_s NULL = all ones (S_1 = A_1).  rowptr_in/colidx_in, nnz_in and
  *   rowptr_out_of/colidx_out_of, nnz_out_of: A_in and A_out, each may be NULL (nothing to add).
  *   rowptr_c [n+1], colidx_c / val_c [capacity]: the result, canonical order; must not be S's arrays.
- *   nnz_c (host): the number of stored entries of C.  It is not known beforehand (at most nnz_s + nnz_in +
- *   nnz_out_of): the call counts first, WAITS for the stream to read the count back, and writes only if it fits;
- *   DGNN_ERR_CAPACITY otherwise, with *nnz_c set, and nothing written.  Because of the wait the call cannot be
- *   captured in a HIP graph; smoothing is pre-processing, outside the training step.
+ * The number of stored entries of C is not known beforehand (at most nnz_s + nnz_in + nnz_out_of) and the host never
+ * waits for it: it is left in rowptr_c[n], on the device.  The calls that take C afterwards (this one as S,
+ * dgnn_csr_weighted_dinv, dgnn_spmm_weighted) accept an upper bound as their nnz argument, e.g. `capacity`, and read
+ * the actual count from rowptr[n] themselves; so does this call for S.  If C does not fit `capacity`, nothing but
+ * rowptr_c[n] (the size needed) is written and *d_status becomes DGNN_BAD_CAPACITY.
+ *   d_status: device int32, may be NULL; reset to 0 by the call, DGNN_BAD_CAPACITY if C did not fit.
  *   ws: device scratch of at least dgnn_csr_combine_workspace(nnz_s) bytes.
- * All device pointers except nnz_c.  Errors: NULL, SHAPE, OVERFLOW (nnz_s + nnz_in + nnz_out_of beyond the index
- * range), CAPACITY, ALIAS, ALIGN (ws not 16-byte aligned), HIP.
+ * Enqueue-only like every other call (it can be recorded in a HIP graph): a count launch, a scan that leaves the
+ * total on the device, and a write launch that reads it there.
+ * All pointers are device pointers.  Errors: NULL, SHAPE, OVERFLOW (nnz_s + nnz_in + nnz_out_of beyond the index
+ * range), CAPACITY (workspace), ALIAS, ALIGN (ws not 16-byte aligned), HIP.
  */
 int dgnn_csr_combine_workspace(int64_t nnz_s, size_t *bytes);
 int dgnn_csr_combine(int64_t n, const int32_t *rowptr_s, const int32_t *colidx_s, const float *val_s, int64_t nnz_s,
                      const int32_t *rowptr_in, const int32_t *colidx_in, int64_t nnz_in, float alpha,
                      const int32_t *rowptr_out_of, const int32_t *colidx_out_of, int64_t nnz_out_of, float beta,
-                     int32_t *rowptr_c, int32_t *colidx_c, float *val_c, int64_t capacity, int64_t *nnz_c,
+                     float diag_value,
+                     int32_t *rowptr_c, int32_t *colidx_c, float *val_c, int64_t capacity, int32_t *d_status,
                      void *ws, size_t ws_bytes, void *stream);
-
 /*
  * ---- Gradient propagation through the same path (Section "Gradient Checkpoint": a block is run forward
  * again and gradients then travel through it in the reverse direction).  For one GCN layer

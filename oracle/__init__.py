@@ -297,12 +297,15 @@ def gcn_values_weighted(rowptr, colidx, val) -> np.ndarray:
     return val * dinv[rows] * dinv[colidx]
 
 
-def csr_combine(n: int, s, a_in=None, alpha: float = 1.0, a_out=None, beta: float = -1.0):
+def csr_combine(n: int, s, a_in=None, alpha: float = 1.0, a_out=None, beta: float = -1.0, diag: float = 0.0):
     """S + alpha * A_in + beta * A_out as sparse matrices, entries whose result is exactly 0 removed: one step of
     the sliding-window sum of Section "Smoothening the Input Graphs" (S_t = S_{t-1} + A_t - A_{t-l}).
     s = (rowptr, colidx, val or None for all ones); a_in, a_out = (rowptr, colidx) of unweighted snapshots, or
     None.  Returns (rowptr, colidx, val) with val in float64.  Written as the definition: every stored entry of
-    the three operands is one term (row, col, weight), terms of equal (row, col) are added up."""
+    the three operands is one term (row, col, weight), terms of equal (row, col) are added up.
+    diag != 0: the operands hold A + I, the section smooths A and Eqn (1) adds I afterwards, once: every stored
+    diagonal entry of the result is set to `diag` (1 for the edge-life sum) instead of the number of snapshots in
+    the window."""
     keys, wts = [], []
     for op, scale in ((s, None), (a_in, alpha), (a_out, beta)):
         if op is None:
@@ -320,6 +323,8 @@ def csr_combine(n: int, s, a_in=None, alpha: float = 1.0, a_out=None, beta: floa
     np.add.at(total, inv, wts)
     keep = total != 0.0
     uniq, total = uniq[keep], total[keep]
+    if diag != 0.0:
+        total = np.where((uniq >> 32) == (uniq & 0xffffffff), float(diag), total)
     rowptr = np.zeros(n + 1, dtype=np.int32)
     np.cumsum(np.bincount(uniq >> 32, minlength=n), out=rowptr[1:])
     return rowptr, (uniq & 0xffffffff).astype(np.int32), total

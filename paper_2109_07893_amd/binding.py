@@ -108,7 +108,7 @@ def load_library():
     lib.dgnn_csr_validate.argtypes = [_i64, _vp, _vp, _i64, ctypes.c_int, _vp, _vp]
     lib.dgnn_csr_combine_workspace.argtypes = [_i64, ctypes.POINTER(_sz)]
     lib.dgnn_csr_combine.argtypes = [_i64, _vp, _vp, _vp, _i64, _vp, _vp, _i64, ctypes.c_float, _vp, _vp, _i64, ctypes.c_float,
-                                     _vp, _vp, _vp, _i64, ctypes.POINTER(_i64), _vp, _sz, _vp]
+                                     ctypes.c_float, _vp, _vp, _vp, _i64, _vp, _vp, _sz, _vp]
     lib.dgnn_csr_weighted_dinv_workspace.argtypes = [_i64, ctypes.POINTER(_sz)]
     lib.dgnn_csr_weighted_dinv.argtypes = [_i64, _i64, _vp, _vp, _vp, _vp, _sz, _vp]
     lib.dgnn_concat_relu.argtypes = [_vp, _i32, _vp, _i32, _vp, _i64, ctypes.c_int, _vp]
@@ -327,9 +327,11 @@ def csr_combine_workspace(nnz_s: int) -> int:
     return int(out.value)
 
 
-def csr_combine(s, a_in, alpha: float, a_out, beta: float, out, ws: torch.Tensor) -> int:
-    """C = S + alpha * A_in + beta * A_out.  s = (rowptr, colidx, val or None, nnz); a_in, a_out = (rowptr, colidx,
-    nnz) or None; out = (rowptr, colidx, val) with capacity = colidx.numel().  Returns nnz of C."""
+def csr_combine(s, a_in, alpha: float, a_out, beta: float, out, ws: torch.Tensor, diag_value: float = 0.0,
+                status: Optional[torch.Tensor] = None) -> None:
+    """C = S + alpha * A_in + beta * A_out.  s = (rowptr, colidx, val or None, nnz or an upper bound of it); a_in,
+    a_out = (rowptr, colidx, nnz) or None; out = (rowptr, colidx, val) with capacity = colidx.numel().  Enqueue-only:
+    the number of stored entries of C is left on the device, in out[0][n]."""
     rp_s, ci_s, val_s, nnz_s = s
     rp_c, ci_c, val_c = out
     n = rp_s.numel() - 1
@@ -337,6 +339,8 @@ def csr_combine(s, a_in, alpha: float, a_out, beta: float, out, ws: torch.Tensor
     _need(rp_c, torch.int32, "rowptr_c"); _need(ci_c, torch.int32, "colidx_c"); _need(val_c, torch.float32, "val_c")
     if val_s is not None:
         _need(val_s, torch.float32, "val_s")
+    if status is not None:
+        _need(status, torch.int32, "status")
     if rp_c.numel() != n + 1 or val_c.numel() < ci_c.numel() or ci_s.numel() < nnz_s or (val_s is not None and val_s.numel() < nnz_s):
         raise ValueError("shape mismatch in csr_combine")
     args = []
@@ -349,13 +353,11 @@ def csr_combine(s, a_in, alpha: float, a_out, beta: float, out, ws: torch.Tensor
         if rp.numel() != n + 1 or ci.numel() < nnz:
             raise ValueError(f"shape mismatch in csr_combine ({name})")
         args.append((rp, ci, nnz))
-    nnz_c = _i64(0)
     (rp_a, ci_a, nnz_a), (rp_o, ci_o, nnz_o) = args
     _check(load_library().dgnn_csr_combine(n, _ptr(rp_s), _ptr(ci_s), _ptr(val_s), nnz_s, _ptr(rp_a), _ptr(ci_a), nnz_a,
-                                           float(alpha), _ptr(rp_o), _ptr(ci_o), nnz_o, float(beta), _ptr(rp_c), _ptr(ci_c),
-                                           _ptr(val_c), ci_c.numel(), ctypes.byref(nnz_c), _ptr(ws),
+                                           float(alpha), _ptr(rp_o), _ptr(ci_o), nnz_o, float(beta), float(diag_value),
+                                           _ptr(rp_c), _ptr(ci_c), _ptr(val_c), ci_c.numel(), _ptr(status), _ptr(ws),
                                            ws.numel() * ws.element_size(), _stream(rp_s)), "dgnn_csr_combine")
-    return int(nnz_c.value)
 
 
 def csr_weighted_dinv_workspace(nnz: int) -> int:

@@ -128,7 +128,13 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) v
     const int slot = blockIdx.x / kXcds, xcd = blockIdx.x % kXcds;
     const int range = ((slot / kXcdChunk) * kXcds + xcd) * kXcdChunk + slot % kXcdChunk;
     if (range >= n_ranges) return;
+    // the host's count may be an upper bound (a snapshot whose size only the device knows): the last row pointer decides
+    nnz = min(nnz, rowptr[n]);
     const int e_begin = (int)((int64_t)range * range_len);
+    if (e_begin >= nnz && range > 0) {                  // nothing stored here: a record that closes nothing and carries nothing
+        if (threadIdx.x == 0) recs[range] = RangeRec{0, 0, 0, 0};
+        return;
+    }
     const int e_end = (int)min((int64_t)e_begin + range_len, (int64_t)nnz);
     int k_cur = max(wave_find_row(rowptr, n, e_begin, lane), 0);   // a row with rowptr <= e_begin
     if (range == 0)                          // rows without entries ahead of the first stored entry
@@ -699,11 +705,16 @@ __global__ __launch_bounds__(kWave) void weighted_rowsum_kernel(int n, int nnz, 
                                                                float *__restrict__ dinv) {
     __shared__ float s_val[kSumRange];
     const int lane = threadIdx.x, range = blockIdx.x;
-    const int e0 = range * kSumRange, e1 = (int)min((int64_t)e0 + kSumRange, (int64_t)nnz);
+    nnz = min(nnz, rowptr[n]);                          // the host's count may be an upper bound: the last row pointer decides
+    const int e0 = (int)min((int64_t)range * kSumRange, (int64_t)nnz), e1 = (int)min((int64_t)e0 + kSumRange, (int64_t)nnz);
+    if (e0 >= nnz && range > 0) {                       // nothing stored here
+        if (lane == 0) recs[range] = SumRec{0.0f, 0.0f, -1, 0};
+        return;
+    }
     const bool last = e1 == nnz;
     // the values of the range, 64 consecutive ones per load
 #pragma unroll 16
-    for (int i = lane; i < kSumRange; i += kWave) s_val[i] = val[min(e0 + i, nnz - 1)];   // unconditional: loads stay in flight together
+    for (int i = lane; i < kSumRange; i += kWave) s_val[i] = val[max(min(e0 + i, nnz - 1), 0)];   // unconditional: loads stay in flight together
     // rows of the range: the one cut by its begin (if any), then every row that begins in [e0, e1), empty ones
     // included; the last range also takes the empty rows behind the last entry
     const int k_lo = wave_find_row(rowptr, n, e0 - 1, lane) + 1;          // first row that begins at e0 or later

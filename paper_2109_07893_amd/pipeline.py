@@ -274,10 +274,13 @@ class SmoothedRunner(BlockRunner):
     normalisation is recomputed from the weighted row sums (dgnn_csr_weighted_dinv), and the GCN step aggregates
     with the raw counts as values (dgnn_spmm_weighted with dinv).  Only the raw difference lists ever travel."""
 
-    def __init__(self, blk: BlockInputs, life: int, keep_all_z: Optional[bool] = None):
+    def __init__(self, blk: BlockInputs, life: int, keep_all_z: Optional[bool] = None, diag_value: float = 1.0):
         super().__init__(blk, keep_all_z)
         assert life >= 1
         self.life = life
+        # edge-life smoothing acts on A; Eqn (1) then adds the self loop once: the stored diagonal stays 1 (0.0 here
+        # leaves the summed diagonal min(life, t), which is the M-transform of the adjacency tensor instead)
+        self.diag_value = diag_value
         dev, n = self.dev, blk.n
         while len(self.rowptr) < life + 1:
             self.rowptr.append(torch.empty(n + 1, dtype=torch.int32, device=dev))
@@ -294,6 +297,11 @@ class SmoothedRunner(BlockRunner):
         self.ws_combine = torch.empty(B.csr_combine_workspace(self.cap_s), dtype=torch.uint8, device=dev)
         self.ws_dinv = torch.empty(B.csr_weighted_dinv_workspace(self.cap_s), dtype=torch.uint8, device=dev)
         self.ws_spmm = torch.empty(B.spmm_workspace(n, self.cap_s, blk.f), dtype=torch.uint8, device=dev)
+        self.status_s = torch.zeros(blk.T + 1, dtype=torch.int32, device=dev)   # per timestep: what dgnn_csr_combine found
+
+    def stored_entries(self) -> int:
+        """Entries of the current smoothed snapshot (reads the device: waits for the stream)."""
+        return int(self.cur[0][-1])
 
     def slot_of(self, t: int) -> int:                   # a ring: A_{t-life} is still there when S_t is formed
         return t % (self.life + 1)
@@ -321,8 +329,10 @@ class SmoothedRunner(BlockRunner):
                 a_out = (self.rowptr[self.slot_of(k)], self.colidx[self.slot_of(k)], blk.nnz[k - 1])
             out = self.s[t % 2]
             with self._stage("csr_combine"):
-                nnz = B.csr_combine(self.cur, a_in, 1.0, a_out, -1.0, out, self.ws_combine)
-            self.cur = (out[0], out[1], out[2], nnz)
+                B.csr_combine(self.cur, a_in, 1.0, a_out, -1.0, out, self.ws_combine, diag_value=self.diag_value,
+                              status=self.status_s[t:t + 1])
+            # the number of stored entries stays on the device (out[0][n]); the capacity serves as the upper bound
+            self.cur = (out[0], out[1], out[2], self.cap_s)
         with self._stage("csr_weighted_dinv"):
             B.csr_weighted_dinv(self.cur[0], self.cur[2], self.cur[3], self.dinv_s, self.ws_dinv)
 
@@ -346,7 +356,3 @@ class SmoothedRunner(BlockRunner):
 
     def snapshot_ready(self, t: int) -> None:
         self.smooth(t)
-
-    def capture(self, first: int = 1):
-        raise RuntimeError("a pass on smoothed snapshots cannot be recorded as a HIP graph: dgnn_csr_combine reads the size of "
-                           "its result back to the host between its two launches")

@@ -371,8 +371,11 @@ class SmoothedTrainer:
 
     def __init__(self, blk: BlockInputs, life: int, directed: bool,
                  transposed_first: Optional[Tuple[torch.Tensor, torch.Tensor]] = None,
-                 transposed_deltas: Optional[List[Tuple[torch.Tensor, ...]]] = None):
+                 transposed_deltas: Optional[List[Tuple[torch.Tensor, ...]]] = None, diag_value: float = 1.0):
         self.blk, self.life, self.directed = blk, life, directed
+        # edge-life smoothing acts on A; Eqn (1) then adds the self loop once: the stored diagonal stays 1 (0.0 here
+        # leaves the summed diagonal min(life, t), which is the M-transform of the adjacency tensor instead)
+        self.diag_value = diag_value
         dev = blk.rowptr1.device
         self.dev = dev
         n, f, T, L = blk.n, blk.f, blk.T, blk.layers
@@ -409,6 +412,7 @@ class SmoothedTrainer:
         self.ws_dinv = torch.empty(B.csr_weighted_dinv_workspace(self.cap_s), dtype=torch.uint8, device=dev)
         self.ws_spmm = torch.empty(B.spmm_workspace(n, self.cap_s, f), dtype=torch.uint8, device=dev)
         self.ws_wgrad = torch.empty(B.weight_grad_workspace(f, f), dtype=torch.uint8, device=dev)
+        self.status = torch.zeros(T + 1, dtype=torch.int32, device=dev)     # per timestep: what dgnn_csr_combine found
         self.timer = None
 
     def _stage(self, name):
@@ -422,13 +426,15 @@ class SmoothedTrainer:
             B.delta_rebuild(ring.rowptr[s], ring.colidx[s], self.blk.nnz[t - 2], ar, ac, int(ar.numel()), dr, dc, int(dr.numel()),
                             ring.rowptr[d], ring.colidx[d], None, self.ws_rebuild)
 
-    def _smooth(self, ring: _Ring, store, t: int) -> int:
-        """store[t-1] <- S_t (t >= 2) from store[t-2], A_t and A_{t-life}; returns its number of stored entries."""
+    def _smooth(self, ring: _Ring, store, t: int) -> None:
+        """store[t-1] <- S_t (t >= 2) from store[t-2], A_t and A_{t-life}.  Its number of stored entries stays on the
+        device (the last row pointer); the calls that take S_t are given the capacity as an upper bound."""
         blk = self.blk
         prev = store[t - 2] + (self.s_nnz[t - 2],)
         a_out = ring.snapshot(t - self.life, blk.nnz[t - self.life - 1]) if t - self.life >= 1 else None
         with self._stage("csr_combine"):
-            return B.csr_combine(prev, ring.snapshot(t, blk.nnz[t - 1]), 1.0, a_out, -1.0, store[t - 1], self.ws_combine)
+            B.csr_combine(prev, ring.snapshot(t, blk.nnz[t - 1]), 1.0, a_out, -1.0, store[t - 1], self.ws_combine,
+                          diag_value=self.diag_value, status=self.status[t:t + 1])
 
     def forward(self) -> torch.Tensor:
         blk = self.blk
@@ -444,11 +450,11 @@ class SmoothedTrainer:
                 self.s_nnz[0] = blk.nnz[0]
             else:
                 self._advance(self.raw, blk.deltas[t - 2], t)
-                nnz = self._smooth(self.raw, self.s, t)
+                self._smooth(self.raw, self.s, t)
                 if self.directed:
                     self._advance(self.raw_t, self.t_deltas[t - 2], t)
-                    assert self._smooth(self.raw_t, self.st, t) == nnz
-                self.s_nnz[t - 1] = nnz
+                    self._smooth(self.raw_t, self.st, t)
+                self.s_nnz[t - 1] = self.cap_s           # an upper bound: the kernels read the count from the last row pointer
             rp, ci, val = self.s[t - 1]
             nnz = self.s_nnz[t - 1]
             with self._stage("csr_weighted_dinv"):

@@ -235,15 +235,14 @@ def test_lstm_step_argument_errors(lib):
 
 def test_csr_combine_argument_errors(lib):
     f = lib.dgnn_csr_combine
-    out = ctypes.c_int64(0)
 
     def call(n=10, rp_s=FAKE, ci_s=FAKE, nnz_s=20, rp_a=FAKE, ci_a=FAKE, nnz_a=5, rp_c=FAKE + 4096, ci_c=FAKE + 8192,
-             val_c=FAKE + 12288, cap=100, ws=FAKE + 16384, ws_bytes=1 << 20, nnz_c=ctypes.byref(out)):
-        return f(n, rp_s, ci_s, None, nnz_s, rp_a, ci_a, nnz_a, 1.0, None, None, 0, -1.0, rp_c, ci_c, val_c, cap, nnz_c, ws,
+             val_c=FAKE + 12288, cap=100, ws=FAKE + 16384, ws_bytes=1 << 20):
+        return f(n, rp_s, ci_s, None, nnz_s, rp_a, ci_a, nnz_a, 1.0, None, None, 0, -1.0, 0.0, rp_c, ci_c, val_c, cap, None, ws,
                  ws_bytes, None)
 
     assert call(rp_s=None) == -1 and call(ci_s=None) == -1 and call(ci_a=None) == -1 and call(val_c=None) == -1
-    assert call(nnz_c=None) == -1 and call(ws=None) == -1
+    assert call(ws=None) == -1
     assert call(n=0) == -2 and call(nnz_s=-1) == -2 and call(cap=-1) == -2
     assert call(nnz_s=(1 << 31) - (1 << 16) - 10, nnz_a=100) == -4
     assert call(ws_bytes=4) == -3

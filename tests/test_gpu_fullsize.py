@@ -275,10 +275,14 @@ def test_sliding_window_sum_full_size():
              torch.empty(cap, device=DEV)) for _ in range(2)]
     ws = torch.empty(dg.csr_combine_workspace(cap), dtype=torch.uint8, device=DEV)
     progress("S_2 = A_1 + A_2")
-    nnz2 = dg.csr_combine((snap[1][0], snap[1][1], None, snap[1][2]), snap[2], 1.0, None, -1.0, bufs[0], ws)
+    status = torch.zeros(2, dtype=torch.int32, device=DEV)
+    dg.csr_combine((snap[1][0], snap[1][1], None, snap[1][2]), snap[2], 1.0, None, -1.0, bufs[0], ws, status=status[0:1])
     progress("S_3 = S_2 + A_3 - A_1")
-    nnz3 = dg.csr_combine((bufs[0][0], bufs[0][1], bufs[0][2], nnz2), snap[3], 1.0, snap[1], -1.0, bufs[1], ws)
+    # the size of S_2 is known to the device only: the capacity is passed as the upper bound
+    dg.csr_combine((bufs[0][0], bufs[0][1], bufs[0][2], cap), snap[3], 1.0, snap[1], -1.0, bufs[1], ws, status=status[1:2])
     torch.cuda.synchronize()
+    assert int(status.abs().sum()) == 0
+    nnz2, nnz3 = int(bufs[0][0][n]), int(bufs[1][0][n])
     n_add = [int(d[0].numel()) for d in blk.deltas]
     assert nnz2 == blk.nnz[0] + n_add[0]             # A_1 united with what step 2 adds
     assert nnz3 == blk.nnz[1] + n_add[1]             # A_2 united with what step 3 adds
@@ -312,7 +316,8 @@ def test_sliding_window_sum_full_size():
     progress("normalisation and aggregation on S_3")
     rp_c, ci_c, val_c = bufs[1]
     dinv = torch.empty(n, device=DEV)
-    dg.csr_weighted_dinv(rp_c, val_c, nnz3, dinv, torch.empty(dg.csr_weighted_dinv_workspace(nnz3), dtype=torch.uint8, device=DEV))
+    # the two calls that take S_3 get the capacity as an upper bound of its entry count, as a caller without the count would
+    dg.csr_weighted_dinv(rp_c, val_c, cap, dinv, torch.empty(dg.csr_weighted_dinv_workspace(cap), dtype=torch.uint8, device=DEV))
     s3_rp, s3_ci, s3_val = rp_c.cpu().numpy(), ci_c[:nnz3].cpu().numpy(), val_c[:nnz3].cpu().numpy().astype(np.float64)
     row_sum = np.add.reduceat(s3_val, s3_rp[:-1])                       # every row holds its diagonal: no empty segment
     d_host = dinv.cpu().numpy().astype(np.float64)
@@ -321,8 +326,8 @@ def test_sliding_window_sum_full_size():
     h = torch.empty((n, f), device=DEV)
     dg.feature_transform(blk.x[2], blk.w[0], h, row_scale=dinv)
     z = torch.empty((n, f), device=DEV)
-    ws_s = torch.empty(dg.spmm_workspace(n, nnz3, f), dtype=torch.uint8, device=DEV)
-    dg.spmm_weighted(rp_c, ci_c, val_c, nnz3, h, z, ws_s, flags=dg.DGNN_RELU | dg.DGNN_H_PRESCALED, dinv=dinv)
+    ws_s = torch.empty(dg.spmm_workspace(n, cap, f), dtype=torch.uint8, device=DEV)
+    dg.spmm_weighted(rp_c, ci_c, val_c, cap, h, z, ws_s, flags=dg.DGNN_RELU | dg.DGNN_H_PRESCALED, dinv=dinv)
     torch.cuda.synchronize()
     # oracle on the sampled rows: their entries' normalised values from the device-independent row sums, H = X W in fp64
     # only for the columns those rows touch

@@ -18,24 +18,33 @@ def dev(a, dt):
     return torch.from_numpy(np.ascontiguousarray(a)).to(dt).to(DEV)
 
 
-def gpu_combine(n, s, a_in, alpha, a_out, beta, slack=0):
+def gpu_combine(n, s, a_in, alpha, a_out, beta, slack=0, diag=0.0, s_bound=None):
+    """The result as the device leaves it: the number of stored entries read from rowptr_c[n].  s_bound: pass S's
+    entry count as this upper bound instead of the exact figure (the kernels must take the last row pointer)."""
     rp_s, ci_s, val_s = s
-    s_d = (dev(rp_s, torch.int32), dev(ci_s, torch.int32), None if val_s is None else dev(val_s, torch.float32), int(ci_s.size))
+    nnz_s = int(ci_s.size)
+    pad = 0 if s_bound is None else s_bound - nnz_s
+    ci_p = np.concatenate([ci_s, np.full(pad, 2**31 - 1, dtype=np.int32)]) if pad else ci_s          # poison behind the entries
+    val_p = None if val_s is None else (np.concatenate([val_s, np.full(pad, np.nan)]) if pad else val_s)
+    s_d = (dev(rp_s, torch.int32), dev(ci_p, torch.int32), None if val_p is None else dev(val_p, torch.float32), nnz_s + pad)
     ops = [None if a is None else (dev(a[0], torch.int32), dev(a[1], torch.int32), int(a[1].size)) for a in (a_in, a_out)]
-    cap = int(ci_s.size) + sum(0 if a is None else int(a[1].size) for a in (a_in, a_out)) + slack
+    cap = nnz_s + sum(0 if a is None else int(a[1].size) for a in (a_in, a_out)) + slack
     out = (torch.full((n + 1,), -7, dtype=torch.int32, device=DEV), torch.full((max(cap, 1),), -7, dtype=torch.int32, device=DEV),
            torch.full((max(cap, 1),), float("nan"), device=DEV))
-    ws = torch.empty(dg.csr_combine_workspace(int(ci_s.size)), dtype=torch.uint8, device=DEV)
-    nnz = dg.csr_combine(s_d, ops[0], alpha, ops[1], beta, out, ws)
+    ws = torch.empty(dg.csr_combine_workspace(nnz_s + pad), dtype=torch.uint8, device=DEV)
+    status = torch.full((1,), 99, dtype=torch.int32, device=DEV)
+    dg.csr_combine(s_d, ops[0], alpha, ops[1], beta, out, ws, diag_value=diag, status=status)
     torch.cuda.synchronize()
+    assert int(status) == 0
+    nnz = int(out[0][n])
     # nothing written behind the result
     assert bool((out[1][nnz:] == -7).all()) and bool(torch.isnan(out[2][nnz:]).all())
     return out[0].cpu().numpy(), out[1][:nnz].cpu().numpy(), out[2][:nnz].cpu().numpy()
 
 
-def check(n, s, a_in, alpha, a_out, beta, what):
-    want = oracle.csr_combine(n, s, a_in, alpha, a_out, beta)
-    got = gpu_combine(n, s, a_in, alpha, a_out, beta)
+def check(n, s, a_in, alpha, a_out, beta, what, diag=0.0, s_bound=None):
+    want = oracle.csr_combine(n, s, a_in, alpha, a_out, beta, diag=diag)
+    got = gpu_combine(n, s, a_in, alpha, a_out, beta, diag=diag, s_bound=s_bound)
     assert np.array_equal(got[0], want[0]), f"{what}: rowptr"
     assert np.array_equal(got[1], want[1]), f"{what}: colidx"
     assert np.array_equal(got[2].astype(np.float64), want[2]), f"{what}: values"
@@ -62,6 +71,8 @@ def test_combine_random_operands(n, density, seed, alpha, beta):
     check(n, s + (None,), a_in, alpha, None, beta, "no A_out, S unweighted")
     check(n, s + (val,), None, alpha, a_out, beta, "no A_in")
     check(n, s + (val,), None, alpha, None, beta, "S alone")
+    check(n, s + (val,), a_in, alpha, a_out, beta, "diagonal entries take a given value", diag=1.0)
+    check(n, s + (val,), a_in, alpha, a_out, beta, "S's entry count given as an upper bound", s_bound=int(s[1].size) + 777)
 
 
 def test_combine_hub_rows_empty_rows_and_long_spans():
@@ -100,10 +111,12 @@ def test_combine_reports_the_size_when_the_result_does_not_fit():
     out = (torch.full((n + 1,), -7, dtype=torch.int32, device=DEV), torch.full((cap,), -7, dtype=torch.int32, device=DEV),
            torch.zeros(cap, device=DEV))
     ws = torch.empty(dg.csr_combine_workspace(int(s[1].size)), dtype=torch.uint8, device=DEV)
-    with pytest.raises(dg.DgnnError):
-        dg.csr_combine(s_d, a_d, 1.0, None, -1.0, out, ws)
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    dg.csr_combine(s_d, a_d, 1.0, None, -1.0, out, ws, status=status)            # enqueue-only: the verdict is on the device
     torch.cuda.synchronize()
-    assert bool((out[0] == -7).all()) and bool((out[1] == -7).all())      # nothing written
+    assert int(status) == 10                                                     # DGNN_BAD_CAPACITY
+    assert int(out[0][n]) == want[1].size                                        # the size that would have been needed
+    assert bool((out[0][:n] == -7).all()) and bool((out[1] == -7).all())         # nothing else written
 
 
 @pytest.mark.parametrize("name,n,life,T", [("c1", 1000, 3, 10), ("c3", 1 << 13, 4, 10), ("c2", 20_000, 2, 10), ("c5", 1 << 13, 8, 10),
@@ -129,20 +142,22 @@ def test_sliding_window_sum_on_the_device(name, n, life, T):
         assert np.array_equal(s[2], counts.astype(np.float32)), (name, t)
 
 
-@pytest.mark.parametrize("name,n,T,life", [("c3", 1 << 13, 6, 3), ("c2", 20_000, 5, 2), ("c4", 10_000, 9, 4), ("c1", 1000, 8, 8)])
-def test_forward_pass_on_smoothed_snapshots(name, n, T, life):
+@pytest.mark.parametrize("name,n,T,life,diag", [("c3", 1 << 13, 6, 3, 1.0), ("c2", 20_000, 5, 2, 1.0), ("c4", 10_000, 9, 4, 1.0),
+                                                ("c1", 1000, 8, 8, 1.0), ("c3", 1 << 13, 6, 3, 0.0), ("c1", 1000, 8, 4, 0.0)])
+def test_forward_pass_on_smoothed_snapshots(name, n, T, life, diag):
     """The whole forward pass with the smoothing done on the device (rebuild, sliding-window sum, weighted
     normalisation, X W, aggregation, M-transform) against the oracle: the expected smoothed snapshot is the sum of
-    the oracle's raw snapshots of the window, normalised by the weighted form of Eqn (1)."""
+    the oracle's raw snapshots of the window, normalised by the weighted form of Eqn (1).  diag = 1: edge-life
+    smoothing (the self loop counts once); diag = 0: the M-transform of the adjacency tensor."""
     from helpers import assert_close, to_f64
     from paper_2109_07893_amd.pipeline import SmoothedRunner, make_block
     wl = WORKLOADS[name].scaled(n, T=T) if n != WORKLOADS[name].n else WORKLOADS[name]
     T = min(T, wl.T)
     blk = make_block(wl, DEV, gen_device="cpu", T=T)
-    runner = SmoothedRunner(blk, life, keep_all_z=True)
+    runner = SmoothedRunner(blk, life, keep_all_z=True, diag_value=diag)
     runner.run_resident(validate=True)
     torch.cuda.synchronize()
-    assert int(runner.status.abs().sum()) == 0
+    assert int(runner.status.abs().sum()) == 0 and int(runner.status_s.abs().sum()) == 0
     raw = DynamicGraph(wl)
     rp, ci = (x.numpy() for x in raw.csr())
     snaps, zs = [(rp, ci)], []
@@ -153,7 +168,7 @@ def test_forward_pass_on_smoothed_snapshots(name, n, T, life):
             snaps.append((rp, ci))
         s = snaps[max(0, t - life)] + (None,)
         for other in snaps[max(0, t - life) + 1:t]:
-            s = oracle.csr_combine(wl.n, s, other, 1.0)
+            s = oracle.csr_combine(wl.n, s, other, 1.0, diag=diag)
         val = oracle.gcn_values_weighted(s[0], s[1], np.ones(s[1].size) if s[2] is None else s[2])
         cur = to_f64(blk.x[t - 1])
         for w in ws:
@@ -217,7 +232,7 @@ def test_training_step_on_smoothed_snapshots(name, n, T, life):
             snaps.append((rp, ci))
         s = snaps[max(0, t - life)] + (None,)
         for other in snaps[max(0, t - life) + 1:t]:
-            s = oracle.csr_combine(wl.n, s, other, 1.0)
+            s = oracle.csr_combine(wl.n, s, other, 1.0, diag=1.0)
         val = oracle.gcn_values_weighted(s[0], s[1], np.ones(s[1].size) if s[2] is None else s[2])
         sm.append((s[0], s[1], val))
         acts = [to_f64(blk.x[t - 1])]
@@ -278,7 +293,7 @@ def test_evolvegcn_on_smoothed_snapshots():
             snaps.append((rp, ci))
         s = snaps[max(0, t - life)] + (None,)
         for other in snaps[max(0, t - life) + 1:t]:
-            s = oracle.csr_combine(wl.n, s, other, 1.0)
+            s = oracle.csr_combine(wl.n, s, other, 1.0, diag=1.0)
         val = oracle.gcn_values_weighted(s[0], s[1], np.ones(s[1].size) if s[2] is None else s[2])
         x = to_f64(features(wl, t))
         z = oracle.spmm(s[0], s[1], oracle.xw(x, ws[t - 1]), relu=True, val=val)
@@ -304,3 +319,33 @@ def test_smoothed_forward_with_lists_from_pinned_host_memory():
         b.run_from_pinned()
         torch.cuda.synchronize()
         assert torch.equal(a.z, b.z)
+
+
+def test_smoothed_pass_as_a_hip_graph_repeats_the_eager_result():
+    """Every call of the smoothed pass only enqueues (the sliding-window sum leaves its size on the device), so the
+    pass can be recorded as a HIP graph: replayed several times with eager passes and synchronisations in between,
+    every replay must leave exactly what the eager pass leaves -- frames, the smoothed snapshot, its size."""
+    from paper_2109_07893_amd.pipeline import SmoothedRunner, make_block
+    wl = WORKLOADS["c3"].scaled(1 << 13, T=6)
+    blk = make_block(wl, DEV, gen_device="cpu")
+    runner = SmoothedRunner(blk, 3, keep_all_z=True)
+    runner.run_resident()
+    torch.cuda.synchronize()
+    want_z = runner.z.clone()
+    nnz = runner.stored_entries()
+    want_s = [x.clone() for x in runner.cur[:3]]
+    graph = runner.capture()
+    for k in range(4):
+        runner.z.fill_(float("nan"))
+        for x in runner.cur[:3]:
+            x.fill_(0)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert int(runner.status_s.abs().sum()) == 0
+        assert torch.equal(runner.z.view(torch.int32), want_z.view(torch.int32)), k
+        assert runner.stored_entries() == nnz
+        assert torch.equal(runner.cur[0], want_s[0]) and torch.equal(runner.cur[1][:nnz], want_s[1][:nnz]), k
+        assert torch.equal(runner.cur[2][:nnz], want_s[2][:nnz]), k
+        runner.run_resident()                      # eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(runner.z.view(torch.int32), want_z.view(torch.int32)), k

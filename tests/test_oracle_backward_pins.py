@@ -462,7 +462,7 @@ def test_edge_life_smoothing_matches_hand_worked_series():
     s = snaps[0] + (None,)
     got = [s]
     for t in range(2, 5):
-        s = oracle.csr_combine(n, s, snaps[t - 1], 1.0, snaps[t - 1 - life] if t - life >= 1 else None, -1.0)
+        s = oracle.csr_combine(n, s, snaps[t - 1], 1.0, snaps[t - 1 - life] if t - life >= 1 else None, -1.0, diag=1.0)
         got.append(s)
     for t, (g, w) in enumerate(zip(got, want), start=1):
         val = np.ones(g[1].size) if g[2] is None else g[2]
@@ -471,4 +471,27 @@ def test_edge_life_smoothing_matches_hand_worked_series():
         assert g[1].size == np.count_nonzero(w)               # an edge that left the window is not stored
     s3 = got[2]
     norm = oracle.gcn_values_weighted(s3[0], s3[1], s3[2])
-    np.testing.assert_allclose(norm, [2 / 3, 1 / np.sqrt(12), 2 / 4, 2 / np.sqrt(12), 1 / 3, 2 / 3], rtol=1e-15)
+    np.testing.assert_allclose(norm, [1 / 2, 1 / np.sqrt(6), 1 / 3, 2 / np.sqrt(6), 1 / 2, 1 / 2], rtol=1e-15)
+
+
+def test_summed_diagonal_is_the_m_transform_of_the_adjacency_tensor():
+    """Without the diagonal rule the window sum of the stored A_i + I carries min(l, t) on its diagonal.  After Eqn (1)
+    that is the M-transform variant of the section: (1/min(l,t)) sum of the A_i, plus I, normalised -- formed here
+    densely from the raw edge sets."""
+    n, life, T = 14, 3, 6
+    rng = np.random.default_rng(12)
+    raw = [(rng.random((n, n)) < 0.2) & ~np.eye(n, dtype=bool) for _ in range(T)]
+    snaps = [oracle.csr_from_edges(n, *np.nonzero(a | np.eye(n, dtype=bool))) for a in raw]
+    s = snaps[0] + (None,)
+    for t in range(2, T + 1):
+        s = oracle.csr_combine(n, s, snaps[t - 1], 1.0, snaps[t - 1 - life] if t - life >= 1 else None, -1.0)
+        c = min(life, t)
+        b = sum(a.astype(np.float64) for a in raw[max(0, t - life):t]) / c + np.eye(n)
+        d = b.sum(axis=1) ** -0.5
+        want = d[:, None] * b * d[None, :]
+        got = np.nan_to_num(_dense_weighted(n, s[0], s[1], oracle.gcn_values_weighted(*s)), nan=0.0)
+        np.testing.assert_allclose(got, want, rtol=1e-13, atol=1e-15)
+        # and with the rule: the plain edge-life sum plus I
+        e = oracle.csr_combine(n, s, None, 1.0, None, -1.0, diag=1.0)
+        b1 = sum(a.astype(np.float64) for a in raw[max(0, t - life):t]) + np.eye(n)
+        np.testing.assert_array_equal(np.nan_to_num(_dense_weighted(n, *e), nan=0.0), b1)

@@ -120,6 +120,9 @@ PY_MUTANTS = [
     ("weighted normalisation counts entries instead of adding values", "d = np.array([val[rowptr[u]:rowptr[u + 1]].sum() for u in range(n)])",
      "d = np.array([float(rowptr[u + 1] - rowptr[u]) for u in range(n)])"),
     ("combination keeps entries that cancel", "keep = total != 0.0", "keep = np.ones(total.size, dtype=bool)"),
+    ("combination: the diagonal rule is ignored", "    if diag != 0.0:\n        total = np.where(", "    if False:\n        total = np.where("),
+    ("combination: the diagonal rule hits the whole matrix", "total = np.where((uniq >> 32) == (uniq & 0xffffffff), float(diag), total)",
+     "total = np.where((uniq >> 32) >= 0, float(diag), total)"),
     ("combination ignores the weight of the removed snapshot", "wts.append(np.full(ci.size, float(scale)))", "wts.append(np.full(ci.size, abs(float(scale))))"),
     ("combination forgets the values of S", "wts.append(np.ones(ci.size) if len(op) < 3 or op[2] is None else _a(op[2], np.float64))",
      "wts.append(np.ones(ci.size))"),
@@ -143,6 +146,7 @@ PY_MUTANTS = [
 def py_pins():
     calls = [bwd.test_weighted_normalisation_reduces_to_eqn_1_and_matches_the_dense_form, bwd.test_csr_combine_special_cases,
              bwd.test_sliding_window_sum_by_csr_combine_equals_the_windowed_sum, bwd.test_edge_life_smoothing_matches_hand_worked_series,
+             bwd.test_summed_diagonal_is_the_m_transform_of_the_adjacency_tensor,
              bwd.test_lstm_cell_backward_matches_finite_differences, bwd.test_cdgcn_gcn_backward_matches_finite_differences,
              bwd.test_evolving_weights_backward_matches_finite_differences,
              bwd.test_evolving_weights_recurrence_beyond_the_first_step]
