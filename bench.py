@@ -58,6 +58,10 @@ def parse_args():
                     help="also time the sliding-window sum of the block's snapshots (edge life 4) computed on the device")
     ap.add_argument("--no-extras", action="store_true",
                     help="only the headline figure (and whatever is asked for explicitly): skip the CD-GCN, weighted and smoothing figures")
+    ap.add_argument("--gen-device", default="cuda", choices=["cuda", "cpu"],
+                    help="where the seeded generator runs; cpu keeps every dispatch of a profiled run the library's own")
+    ap.add_argument("--repeat-features", action="store_true",
+                    help="X_t = X_1 for every t (counter runs: the traffic does not depend on the values)")
     ap.add_argument("--natural-labels", action="store_true",
                     help="R-MAT workloads: keep the generator's vertex labels (locality) instead of scrambling them")
     return ap.parse_args()
@@ -479,7 +483,8 @@ def main():
     import torch
     import paper_2109_07893_amd as dg
     from dtdg_synth import WORKLOADS
-    from paper_2109_07893_amd.pipeline import BlockRunner, StageTimer, make_block
+    from dtdg_synth.blocks import make_block
+    from paper_2109_07893_amd.pipeline import BlockRunner, StageTimer
 
     dg.load_library()
     wl = WORKLOADS[args.workload]
@@ -496,7 +501,8 @@ def main():
     # one step ahead) are then inside the timed region.  The other workloads keep their lists in HBM.
     pinned = (args.workload == "c5" or args.pinned) and not args.resident
     t_gen = time.perf_counter()
-    blk = make_block(wl, dev, gen_device=dev, pinned=pinned, T=T)
+    blk = make_block(wl, dev, gen_device=dev if args.gen_device == "cuda" else "cpu", pinned=pinned, T=T,
+                     repeat_features=args.repeat_features, progress=progress)
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
     progress(f"inputs of {wl.name} generated in {t_gen:.1f} s")

@@ -310,9 +310,32 @@ int dgnn_csr_combine(int64_t n, const int32_t *rowptr_s, const int32_t *colidx_s
  * (A + I)^T and with dinv of A (NOT the one derived from the transposed row lengths).  For an undirected
  * snapshot the transpose is the snapshot itself.  For a directed one the transposed snapshots form a dynamic
  * graph of their own, rebuilt by dgnn_delta_rebuild from the difference lists sorted by (col, row) with rows
- * and columns swapped.  Walking a block backwards needs A_{t-1} from A_t: that is dgnn_delta_rebuild with the
+ * and columns swapped (dgnn_csr_transpose for the first snapshot, dgnn_coo_transpose for the lists).  Walking a block backwards needs A_{t-1} from A_t: that is dgnn_delta_rebuild with the
  * added and deleted lists exchanged.
  */
+
+/*
+ * The transposed snapshot, for the adjoint of the aggregation (Section "Gradient Checkpoint": gradients travel through a
+ * block in the reverse direction, which needs A~^T): (rowptr_t, colidx_t) = CSR of the transpose of (rowptr, colidx), in
+ * the same canonical form (columns ascending inside a row); val / val_t: the values travel with their entries, or both
+ * NULL.  nnz must be exact here.  The pairs are sorted by (column, row) with the device library's radix sort; ws: device
+ * scratch of at least dgnn_csr_transpose_workspace() bytes (two arrays of 8-byte keys and the sort's own scratch; the
+ * query asks the sort, so it needs a device).  Input formatting, once per block: not meant for graph capture.
+ * Errors: NULL, SHAPE, OVERFLOW, ALIGN, ALIAS (an output is its input), CAPACITY, HIP.
+ */
+int dgnn_csr_transpose_workspace(int64_t n, int64_t nnz, int with_values, size_t *bytes);
+int dgnn_csr_transpose(int64_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *val,
+                       int32_t *rowptr_t, int32_t *colidx_t, float *val_t, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * A difference list for the transposed series: the m pairs (row[i], col[i]) with rows and columns exchanged and sorted
+ * by (new row, new column), i.e. (row_t[i], col_t[i]) = the pairs (col, row) in ascending order.  The transposed
+ * snapshots of a directed dynamic graph are rebuilt by dgnn_delta_rebuild from such lists.  n: vertices (indices lie
+ * in [0, n)).  Outputs must not overlap inputs.  ws as above, dgnn_coo_transpose_workspace() bytes.  m = 0 is allowed.
+ */
+int dgnn_coo_transpose_workspace(int64_t n, int64_t m, size_t *bytes);
+int dgnn_coo_transpose(int64_t n, int64_t m, const int32_t *row, const int32_t *col, int32_t *row_t, int32_t *col_t,
+                       void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Adjoint of the M-transform (Section "TM-GCN"): G_Z = G_Y x_1 M^T,

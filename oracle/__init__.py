@@ -10,7 +10,8 @@ its matrix M -- Section "TM-GCN"; gradient propagation through a block in the re
 -- Section "Gradient Checkpoint" (the adjoint of each forward step); the sliding-window sum of
 snapshots and its normalisation -- Section "Smoothening the Input Graphs" with Eqn (1); the GCN
 operation with skip connection and the LSTM over time -- Section "CD-GCN"; the LSTM over the
-weights -- Section "EvolveGCN"; and the adjoints of those.  The parts added in numpy below are
+weights -- Section "EvolveGCN"; and the adjoints of those; the transposed snapshot and lists the
+reverse pass of a directed graph needs -- Section "Gradient Checkpoint".  The parts added in numpy below are
 fp64 like the C part.  Parity status: every function here is pinned by tests that do not call
 it to produce their own expectation (dense brute force, closed forms, hand-worked fixtures under
 tests/golden/, a library LSTM cell, central differences); tests/test_oracle_mutants.py plants
@@ -328,6 +329,25 @@ def csr_combine(n: int, s, a_in=None, alpha: float = 1.0, a_out=None, beta: floa
     rowptr = np.zeros(n + 1, dtype=np.int32)
     np.cumsum(np.bincount(uniq >> 32, minlength=n), out=rowptr[1:])
     return rowptr, (uniq & 0xffffffff).astype(np.int32), total
+
+
+def csr_transpose(n: int, rowptr, colidx, val=None):
+    """CSR of the transposed matrix, canonical form (Section "Gradient Checkpoint": the reverse pass aggregates with
+    A~^T).  The definition written out: the stored pairs (u, v) become (v, u), sorted by (v, u)."""
+    rowptr, colidx = _a(rowptr, np.int32), _a(colidx, np.int32)
+    rows = np.repeat(np.arange(n, dtype=np.int64), np.diff(rowptr))
+    order = np.lexsort((rows, colidx))                    # by the old column, then by the old row
+    rowptr_t = np.zeros(n + 1, dtype=np.int32)
+    np.cumsum(np.bincount(colidx, minlength=n), out=rowptr_t[1:])
+    out = (rowptr_t, rows[order].astype(np.int32))
+    return out if val is None else out + (_a(val, np.float64)[order],)
+
+
+def coo_transpose(row, col):
+    """The pairs (col, row), sorted ascending: a difference list of the transposed series."""
+    row, col = _a(row, np.int32), _a(col, np.int32)
+    order = np.lexsort((row, col))
+    return col[order], row[order]
 
 
 def lstm_cell_backward(x, h, c, w_x, w_h, bias, d_h, d_c=None):

@@ -12,7 +12,7 @@ from .binding import (  # noqa: F401
     spmm_static_limit, mproduct,
     # its backward half, and a series processed in blocks
     mproduct_backward, mproduct_block, mproduct_backward_block, relu_backward, weight_grad, weight_grad_workspace,
-    input_grad,
+    input_grad, csr_transpose, coo_transpose,
     # snapshots that carry values; smoothing on the device
     delta_rebuild_weighted, spmm_weighted, csr_weighted_dinv, csr_weighted_dinv_workspace, csr_combine,
     csr_combine_workspace,

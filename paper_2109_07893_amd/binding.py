@@ -26,6 +26,7 @@ EXPORTS = (
     "dgnn_delta_rebuild", "dgnn_feature_transform", "dgnn_spmm_workspace", "dgnn_spmm", "dgnn_spmm_static_limit",
     "dgnn_spmm_static", "dgnn_mproduct",
     "dgnn_delta_rebuild_weighted", "dgnn_spmm_weighted", "dgnn_csr_combine_workspace", "dgnn_csr_combine", "dgnn_csr_weighted_dinv_workspace", "dgnn_csr_weighted_dinv", "dgnn_concat_relu", "dgnn_lstm_cell", "dgnn_lstm_step", "dgnn_lstm_cell_backward", "dgnn_lstm_step_backward", "dgnn_concat_relu_backward", "dgnn_bias_grad_workspace", "dgnn_bias_grad", "dgnn_add",
+    "dgnn_csr_transpose_workspace", "dgnn_csr_transpose", "dgnn_coo_transpose_workspace", "dgnn_coo_transpose",
     "dgnn_mproduct_backward", "dgnn_mproduct_block", "dgnn_mproduct_backward_block", "dgnn_relu_backward", "dgnn_weight_grad_workspace", "dgnn_weight_grad", "dgnn_input_grad",
 )
 
@@ -111,6 +112,10 @@ def load_library():
                                      ctypes.c_float, _vp, _vp, _vp, _i64, _vp, _vp, _sz, _vp]
     lib.dgnn_csr_weighted_dinv_workspace.argtypes = [_i64, ctypes.POINTER(_sz)]
     lib.dgnn_csr_weighted_dinv.argtypes = [_i64, _i64, _vp, _vp, _vp, _vp, _sz, _vp]
+    lib.dgnn_csr_transpose_workspace.argtypes = [_i64, _i64, ctypes.c_int, ctypes.POINTER(_sz)]
+    lib.dgnn_csr_transpose.argtypes = [_i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+    lib.dgnn_coo_transpose_workspace.argtypes = [_i64, _i64, ctypes.POINTER(_sz)]
+    lib.dgnn_coo_transpose.argtypes = [_i64, _i64, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     lib.dgnn_concat_relu.argtypes = [_vp, _i32, _vp, _i32, _vp, _i64, ctypes.c_int, _vp]
     lib.dgnn_lstm_cell.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _i32, ctypes.c_int, _vp]
     lib.dgnn_lstm_cell_backward.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i32, ctypes.c_int, _vp]
@@ -358,6 +363,44 @@ def csr_combine(s, a_in, alpha: float, a_out, beta: float, out, ws: torch.Tensor
                                            float(alpha), _ptr(rp_o), _ptr(ci_o), nnz_o, float(beta), float(diag_value),
                                            _ptr(rp_c), _ptr(ci_c), _ptr(val_c), ci_c.numel(), _ptr(status), _ptr(ws),
                                            ws.numel() * ws.element_size(), _stream(rp_s)), "dgnn_csr_combine")
+
+
+def csr_transpose(rowptr: torch.Tensor, colidx: torch.Tensor, nnz: int, val: Optional[torch.Tensor] = None):
+    """(rowptr_t, colidx_t[, val_t]) of the transposed snapshot, in new tensors (the workspace is allocated here too:
+    input formatting, once per block)."""
+    _need(rowptr, torch.int32, "rowptr"); _need(colidx, torch.int32, "colidx")
+    n = rowptr.numel() - 1
+    if colidx.numel() < nnz or (val is not None and (val.numel() < nnz or val.dtype != torch.float32)):
+        raise ValueError("shape mismatch in csr_transpose")
+    lib = load_library()
+    need = _sz(0)
+    _check(lib.dgnn_csr_transpose_workspace(n, nnz, 0 if val is None else 1, ctypes.byref(need)), "dgnn_csr_transpose_workspace")
+    dev = rowptr.device
+    ws = torch.empty(need.value, dtype=torch.uint8, device=dev)
+    rowptr_t = torch.empty(n + 1, dtype=torch.int32, device=dev)
+    colidx_t = torch.empty(max(nnz, 1), dtype=torch.int32, device=dev)
+    val_t = None if val is None else torch.empty(max(nnz, 1), dtype=torch.float32, device=dev)
+    _check(lib.dgnn_csr_transpose(n, nnz, _ptr(rowptr), _ptr(colidx), _ptr(val), _ptr(rowptr_t), _ptr(colidx_t), _ptr(val_t),
+                                  _ptr(ws), need.value, _stream(rowptr)), "dgnn_csr_transpose")
+    out = (rowptr_t, colidx_t[:nnz]) + (() if val is None else (val_t[:nnz],))
+    return out
+
+
+def coo_transpose(n: int, row: torch.Tensor, col: torch.Tensor):
+    """(row_t, col_t): the pairs (col, row) sorted ascending, in new tensors (a difference list of the transposed series)."""
+    _need(row, torch.int32, "row"); _need(col, torch.int32, "col")
+    m = int(row.numel())
+    if col.numel() != m:
+        raise ValueError("shape mismatch in coo_transpose")
+    lib = load_library()
+    need = _sz(0)
+    _check(lib.dgnn_coo_transpose_workspace(n, m, ctypes.byref(need)), "dgnn_coo_transpose_workspace")
+    dev = row.device
+    ws = torch.empty(need.value, dtype=torch.uint8, device=dev)
+    row_t, col_t = torch.empty(m, dtype=torch.int32, device=dev), torch.empty(m, dtype=torch.int32, device=dev)
+    _check(lib.dgnn_coo_transpose(n, m, _ptr(row), _ptr(col), _ptr(row_t), _ptr(col_t), _ptr(ws), need.value, _stream(row) if row.is_cuda else None),
+           "dgnn_coo_transpose")
+    return row_t, col_t
 
 
 def csr_weighted_dinv_workspace(nnz: int) -> int:

@@ -49,25 +49,6 @@ class BlockInputs:
         return self.w_t[t - 1][layer] if self.w_t is not None else self.w[layer]
 
 
-def make_block(wl, device, gen_device=None, pinned: bool = False, T: Optional[int] = None) -> BlockInputs:
-    """Generate a workload's block with the seeded generator and place it on `device`."""
-    from dtdg_synth import DynamicGraph, features, glorot_weight
-    gen_device = torch.device(gen_device if gen_device is not None else device)
-    T = T or wl.T
-    g = DynamicGraph(wl, device=gen_device)
-    rowptr1, colidx1 = (t.to(device) for t in g.csr())
-    deltas, pins = [], []
-    for _ in range(2, T + 1):
-        d = g.advance()
-        deltas.append(tuple(t.to(device) for t in d))
-        if pinned:
-            pins.append(tuple(torch.empty(t.shape, dtype=t.dtype, pin_memory=True).copy_(t) for t in d))
-    x = [features(wl, t, device=gen_device).to(device) for t in range(1, T + 1)]
-    w = [glorot_weight(wl, layer, device=gen_device).to(device) for layer in range(wl.layers)]
-    return BlockInputs(n=wl.n, T=T, f=wl.f, layers=wl.layers, window=wl.window, rowptr1=rowptr1,
-                       colidx1=colidx1, deltas=deltas, x=x, w=w, pinned=pins if pinned else None)
-
-
 class StageTimer:
     """Per-stage GPU time from event pairs recorded on the stream the kernels are launched on."""
 

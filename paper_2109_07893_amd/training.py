@@ -211,16 +211,11 @@ def capture_training_step(tr: "BlockTrainer", g_y: torch.Tensor) -> "torch.cuda.
 
 
 def transposed_inputs(blk: BlockInputs):
-    """(rowptr, colidx) of A_1^T and the difference lists of the transposed series, prepared with the generator's
-    formatting helper (a sort by (col, row); input formatting, no arithmetic of the method)."""
-    from dtdg_synth import transpose_coo
+    """(rowptr, colidx) of A_1^T and the difference lists of the transposed series (dgnn_csr_transpose,
+    dgnn_coo_transpose: input formatting, once per block)."""
     n = blk.n
-    rows = torch.repeat_interleave(torch.arange(n, dtype=torch.int32, device=blk.rowptr1.device),
-                                   (blk.rowptr1[1:] - blk.rowptr1[:-1]).to(torch.int64))
-    tr, tc = transpose_coo(rows, blk.colidx1)
-    rowptr_t = torch.zeros(n + 1, dtype=torch.int32, device=tr.device)
-    rowptr_t[1:] = torch.cumsum(torch.bincount(tr.to(torch.int64), minlength=n), 0).to(torch.int32)
-    return (rowptr_t, tc), [transpose_coo(ar, ac) + transpose_coo(dr, dc) for ar, ac, dr, dc in blk.deltas]
+    first = B.csr_transpose(blk.rowptr1, blk.colidx1, blk.nnz[0])
+    return first, [B.coo_transpose(n, ar, ac) + B.coo_transpose(n, dr, dc) for ar, ac, dr, dc in blk.deltas]
 
 
 def make_smoothed_trainer(wl, blk: BlockInputs, life: int) -> "SmoothedTrainer":
@@ -232,8 +227,7 @@ def make_smoothed_trainer(wl, blk: BlockInputs, life: int) -> "SmoothedTrainer":
 
 
 def make_trainer(wl, blk: BlockInputs, want_dx: bool = False, keep_snapshots: bool = False) -> BlockTrainer:
-    """Trainer for a generated block; for a directed workload the transposed first snapshot and lists are
-    prepared here with the generator's formatting helper."""
+    """Trainer for a block; for a directed workload the transposed first snapshot and lists are prepared here."""
     directed = wl.graph != "er"
     if not directed:
         return BlockTrainer(blk, False, want_dx=want_dx, keep_snapshots=keep_snapshots)
@@ -250,7 +244,6 @@ class CheckpointedTrainer:
     time are resident."""
 
     def __init__(self, wl, series: BlockInputs, bsize: int):
-        from dtdg_synth import transpose_coo
         self.series, self.bsize = series, bsize
         self.directed = wl.graph != "er"
         T = series.T
@@ -262,15 +255,9 @@ class CheckpointedTrainer:
             for a, _ in self.bounds[1:]]
         self.t_first, self.t_deltas = None, None
         if self.directed:
-            n = series.n
-            rows = torch.repeat_interleave(torch.arange(n, dtype=torch.int32, device=dev),
-                                           (series.rowptr1[1:] - series.rowptr1[:-1]).to(torch.int64))
-            tr, tc = transpose_coo(rows, series.colidx1)
-            rp_t = torch.zeros(n + 1, dtype=torch.int32, device=dev)
-            rp_t[1:] = torch.cumsum(torch.bincount(tr.to(torch.int64), minlength=n), 0).to(torch.int32)
+            (rp_t, tc), self.t_deltas = transposed_inputs(series)
             self.t_first = [(rp_t, tc)] + [(torch.empty_like(rp_t), torch.empty(series.nnz[a], dtype=torch.int32, device=dev))
                                            for a, _ in self.bounds[1:]]
-            self.t_deltas = [transpose_coo(ar, ac) + transpose_coo(dr, dc) for ar, ac, dr, dc in series.deltas]
         self.pi: List[Optional[torch.Tensor]] = [None] * len(self.bounds)   # frames handed to block b
         longest_list = max([int(d[0].numel()) for d in series.deltas] + [int(d[2].numel()) for d in series.deltas] + [1])
         self.trainer = BlockTrainer(self._block(0), self.directed,       # block 0 is as long as any

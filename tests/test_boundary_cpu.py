@@ -253,6 +253,25 @@ def test_csr_combine_argument_errors(lib):
     assert lib.dgnn_csr_combine_workspace(-1, ctypes.byref(b)) == -2
 
 
+def test_transpose_argument_errors(lib):
+    """Bad arguments are refused on the host, before the device or its sort are asked anything."""
+    f = lib.dgnn_csr_transpose
+    b = ctypes.c_size_t(0)
+    assert lib.dgnn_csr_transpose_workspace(0, 10, 0, ctypes.byref(b)) == -2
+    assert lib.dgnn_csr_transpose_workspace(10, -1, 0, ctypes.byref(b)) == -2
+    assert lib.dgnn_csr_transpose_workspace(10, 1 << 31, 0, ctypes.byref(b)) == -4
+    assert lib.dgnn_csr_transpose_workspace(10, 10, 0, None) == -1
+    assert lib.dgnn_coo_transpose_workspace(0, 10, ctypes.byref(b)) == -2 and lib.dgnn_coo_transpose_workspace(10, 10, None) == -1
+    assert f(10, 20, None, FAKE, None, FAKE + 4096, FAKE + 8192, None, FAKE + 16384, 1 << 20, None) == -1
+    assert f(10, 20, FAKE, FAKE, FAKE, FAKE + 4096, FAKE + 8192, None, FAKE + 16384, 1 << 20, None) == -1      # values in, none out
+    assert f(0, 20, FAKE, FAKE, None, FAKE + 4096, FAKE + 8192, None, FAKE + 16384, 1 << 20, None) == -2
+    assert f(10, 20, FAKE, FAKE, None, FAKE, FAKE + 8192, None, FAKE + 16384, 1 << 20, None) == -5
+    assert f(10, 20, FAKE, FAKE, None, FAKE + 4096, FAKE + 8192, None, FAKE + 16384 + 4, 1 << 20, None) == -7
+    g = lib.dgnn_coo_transpose
+    assert g(10, 5, None, FAKE, FAKE + 4096, FAKE + 8192, FAKE + 16384, 1 << 20, None) == -1
+    assert g(10, -1, FAKE, FAKE, FAKE + 4096, FAKE + 8192, FAKE + 16384, 1 << 20, None) == -2
+
+
 def test_cdgcn_backward_argument_errors(lib):
     f = lib.dgnn_lstm_cell_backward
     a = [FAKE + 4096 * k for k in range(9)]

@@ -11,7 +11,7 @@ import paper_2109_07893_amd as dg
 from dtdg_synth import WORKLOADS, DynamicGraph, features, glorot_weight
 from helpers import assert_close, to_f64
 from paper_2109_07893_amd.cdgcn import CdgcnLayer
-from paper_2109_07893_amd.pipeline import make_block
+from dtdg_synth.blocks import make_block
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"

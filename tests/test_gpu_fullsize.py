@@ -12,7 +12,8 @@ import sys
 import oracle
 from dtdg_synth import WORKLOADS, DynamicGraph
 from helpers import assert_close, to_f64
-from paper_2109_07893_amd.pipeline import BlockRunner, make_block
+from dtdg_synth.blocks import make_block
+from paper_2109_07893_amd.pipeline import BlockRunner
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"

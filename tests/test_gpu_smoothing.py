@@ -150,7 +150,8 @@ def test_forward_pass_on_smoothed_snapshots(name, n, T, life, diag):
     the oracle's raw snapshots of the window, normalised by the weighted form of Eqn (1).  diag = 1: edge-life
     smoothing (the self loop counts once); diag = 0: the M-transform of the adjacency tensor."""
     from helpers import assert_close, to_f64
-    from paper_2109_07893_amd.pipeline import SmoothedRunner, make_block
+    from dtdg_synth.blocks import make_block
+    from paper_2109_07893_amd.pipeline import SmoothedRunner
     wl = WORKLOADS[name].scaled(n, T=T) if n != WORKLOADS[name].n else WORKLOADS[name]
     T = min(T, wl.T)
     blk = make_block(wl, DEV, gen_device="cpu", T=T)
@@ -210,7 +211,7 @@ def test_training_step_on_smoothed_snapshots(name, n, T, life):
     device, every S_t (and S_t^T for the directed workload) kept resident; weight gradients against the oracle."""
     from dtdg_synth import gradient
     from helpers import assert_close, to_f64
-    from paper_2109_07893_amd.pipeline import make_block
+    from dtdg_synth.blocks import make_block
     from paper_2109_07893_amd.training import make_smoothed_trainer
     wl = WORKLOADS[name].scaled(n, T=T) if n != WORKLOADS[name].n else WORKLOADS[name]
     T = min(T, wl.T)
@@ -263,7 +264,7 @@ def test_evolvegcn_on_smoothed_snapshots():
     from dtdg_synth import features, gradient
     from helpers import assert_close, to_f64
     from paper_2109_07893_amd.evolve import EvolvingWeights
-    from paper_2109_07893_amd.pipeline import make_block
+    from dtdg_synth.blocks import make_block
     from paper_2109_07893_amd.training import make_smoothed_trainer
     wl = WORKLOADS["c3"].scaled(1 << 12, T=5)
     T, f, life = wl.T, wl.f, 3
@@ -309,7 +310,8 @@ def test_evolvegcn_on_smoothed_snapshots():
 def test_smoothed_forward_with_lists_from_pinned_host_memory():
     """The smoothed forward pass with the raw difference lists streamed from pinned host memory (copies overlapped
     with the computation) leaves exactly what the pass with resident lists leaves."""
-    from paper_2109_07893_amd.pipeline import SmoothedRunner, make_block
+    from dtdg_synth.blocks import make_block
+    from paper_2109_07893_amd.pipeline import SmoothedRunner
     wl = WORKLOADS["c5"].scaled(1 << 13, T=7)
     a = SmoothedRunner(make_block(wl, DEV, gen_device="cpu"), life=3, keep_all_z=True)
     a.run_resident()
@@ -325,7 +327,8 @@ def test_smoothed_pass_as_a_hip_graph_repeats_the_eager_result():
     """Every call of the smoothed pass only enqueues (the sliding-window sum leaves its size on the device), so the
     pass can be recorded as a HIP graph: replayed several times with eager passes and synchronisations in between,
     every replay must leave exactly what the eager pass leaves -- frames, the smoothed snapshot, its size."""
-    from paper_2109_07893_amd.pipeline import SmoothedRunner, make_block
+    from dtdg_synth.blocks import make_block
+    from paper_2109_07893_amd.pipeline import SmoothedRunner
     wl = WORKLOADS["c3"].scaled(1 << 13, T=6)
     blk = make_block(wl, DEV, gen_device="cpu")
     runner = SmoothedRunner(blk, 3, keep_all_z=True)

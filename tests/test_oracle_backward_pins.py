@@ -495,3 +495,45 @@ def test_summed_diagonal_is_the_m_transform_of_the_adjacency_tensor():
         e = oracle.csr_combine(n, s, None, 1.0, None, -1.0, diag=1.0)
         b1 = sum(a.astype(np.float64) for a in raw[max(0, t - life):t]) + np.eye(n)
         np.testing.assert_array_equal(np.nan_to_num(_dense_weighted(n, *e), nan=0.0), b1)
+
+
+def test_transposed_snapshot_and_lists():
+    """csr_transpose / coo_transpose against dense transposes, the involution, the identity <A^T g, h> = <g, A h> through
+    the aggregation oracle, and the snapshot rule: transposing the lists and applying them to A^T gives (A')^T."""
+    n = 23
+    rng = np.random.default_rng(90)
+    a = (rng.random((n, n)) < 0.2) | np.eye(n, dtype=bool)
+    a[:, 5] = False; a[5, 5] = True                      # a column with one entry; row 7 below gets none at all
+    rp, ci = oracle.csr_from_edges(n, *np.nonzero(a))
+    val = rng.normal(size=ci.size)
+    rp_t, ci_t, val_t = oracle.csr_transpose(n, rp, ci, val)
+    want = _dense_weighted(n, rp, ci, val).T
+    got = _dense_weighted(n, rp_t, ci_t, val_t)
+    assert np.array_equal(np.isnan(got), np.isnan(want)) and np.array_equal(np.nan_to_num(got), np.nan_to_num(want))
+    assert all(np.all(np.diff(ci_t[rp_t[u]:rp_t[u + 1]]) > 0) for u in range(n))          # canonical: columns ascending
+    back = oracle.csr_transpose(n, rp_t, ci_t, val_t)
+    assert np.array_equal(back[0], rp) and np.array_equal(back[1], ci) and np.array_equal(back[2], val)
+    # an empty row and an empty column survive
+    b = a.copy(); b[7, :] = False; b[:, 9] = False
+    rp_b, ci_b = oracle.csr_from_edges(n, *np.nonzero(b))
+    rp_bt, ci_bt = oracle.csr_transpose(n, rp_b, ci_b)
+    assert np.array_equal(_dense_unweighted(n, rp_bt, ci_bt), _dense_unweighted(n, rp_b, ci_b).T)
+    # the adjoint identity through the plain aggregation
+    g, h = rng.normal(size=(n, 3)), rng.normal(size=(n, 3))
+    lhs = (oracle.spmm(rp_t, ci_t, g, val=val_t) * h).sum()
+    rhs = (g * oracle.spmm(rp, ci, h, val=val)).sum()
+    assert abs(lhs - rhs) <= 1e-12 * max(1.0, abs(rhs))
+    # lists: pairs exchanged and sorted; applied to A^T they give the transpose of the next snapshot
+    off = a & ~np.eye(n, dtype=bool)
+    dr, dc = np.nonzero(off)
+    pick = rng.choice(dr.size, 9, replace=False); pick.sort()
+    absent = np.argwhere(~a)
+    add = absent[rng.choice(len(absent), 11, replace=False)]
+    add = add[np.lexsort((add[:, 1], add[:, 0]))]
+    lists = (add[:, 0], add[:, 1], dr[pick], dc[pick])
+    nxt = oracle.delta_apply(n, rp, ci, *lists)
+    t_add, t_del = oracle.coo_transpose(lists[0], lists[1]), oracle.coo_transpose(lists[2], lists[3])
+    assert all(np.all(np.diff(r.astype(np.int64) * n + c) > 0) for r, c in (t_add, t_del))
+    nxt_t = oracle.delta_apply(n, rp_t, ci_t, *t_add, *t_del)
+    want_t = oracle.csr_transpose(n, *nxt)
+    assert np.array_equal(nxt_t[0], want_t[0]) and np.array_equal(nxt_t[1], want_t[1])

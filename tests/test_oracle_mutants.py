@@ -133,6 +133,10 @@ PY_MUTANTS = [
     ("LSTM backward: output gate's gradient uses the cell state, not its tanh", "d_h * tc * o * (1.0 - o)", "d_h * c2 * o * (1.0 - o)"),
     ("skip connection backward without the ReLU mask", "d_y = d_y * (np.concatenate([y0, y1], axis=1) > 0.0)", "d_y = d_y * 1.0"),
     ("skip connection backward drops the path through Y1", "spmm_t(rowptr, colidx, d_y0 + input_grad(d_y1, w))", "spmm_t(rowptr, colidx, d_y0)"),
+    ("transpose: the entries of a new row come out in descending order", "order = np.lexsort((rows, colidx))", "order = np.lexsort((-rows, colidx))"),
+    ("transpose: row pointers counted from the rows, not the columns", "np.cumsum(np.bincount(colidx, minlength=n), out=rowptr_t[1:])",
+     "np.cumsum(np.bincount(rows, minlength=n), out=rowptr_t[1:])"),
+    ("transposed list sorted by the old row", "order = np.lexsort((row, col))", "order = np.lexsort((col, row))"),
     ("evolving weights: gradient reaches W through one product only", "carry = d_x + d_hp", "carry = d_hp"),
     ("evolving weights: the cell state is not carried past the first step", "w, c = lstm_cell(ws[-1], ws[-1], cs[-1], u_x, u_h, bias)",
      "w, c = lstm_cell(ws[-1], ws[-1], cs[0], u_x, u_h, bias)"),
@@ -149,7 +153,7 @@ def py_pins():
              bwd.test_summed_diagonal_is_the_m_transform_of_the_adjacency_tensor,
              bwd.test_lstm_cell_backward_matches_finite_differences, bwd.test_cdgcn_gcn_backward_matches_finite_differences,
              bwd.test_evolving_weights_backward_matches_finite_differences,
-             bwd.test_evolving_weights_recurrence_beyond_the_first_step]
+             bwd.test_evolving_weights_recurrence_beyond_the_first_step, bwd.test_transposed_snapshot_and_lists]
     for seed in (0, 1, 2):
         calls.append(lambda s=seed: bwd.test_csr_combine_matches_dense_matrices(s))
     calls += [getattr(bwd, n) for n in dir(bwd) if n.startswith("test_lstm_cell_matches") or n.startswith("test_cdgcn_gcn_matches")]
