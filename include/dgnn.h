@@ -95,8 +95,9 @@ int dgnn_delta_h2d(const int32_t *h_add_row, const int32_t *h_add_col, int64_t n
                    int32_t *d_add_row, int32_t *d_add_col, int32_t *d_del_row, int32_t *d_del_col,
                    void *stream);
 
-/* Workspace size of dgnn_delta_rebuild in bytes (HOST out-parameter): 4 (n + 1) + 8 (n_add + n_del), rounded up;
- * it grows with each argument, so the size queried for the longest lists of a block serves every step. */
+/* Workspace size of dgnn_delta_rebuild in bytes (HOST out-parameter): 8 (n_add + n_del) plus 32 per range of 8192
+ * stored entries (never fewer than 16386 ranges), rounded up; it grows with each argument, so the size queried for
+ * the largest snapshot and the longest lists of a block serves every step. */
 int dgnn_delta_rebuild_workspace(int64_t n, int64_t nnz_prev, int64_t n_add, int64_t n_del, size_t *bytes);
 
 /*

@@ -6,12 +6,15 @@
 //   rowptr_next[r] = rowptr_prev[r] + #added with row < r - #deleted with row < r
 // and "#entries with row < r" is a lower bound in a sorted list.  Every tile is independent:
 //   1. rowptr_kernel  (tiles of rows)         new row pointers, dinv = (row length)^(-1/2),
-//                                             and add_ptr[r] = #added with row < r (workspace);
-//      extent_kernel  (difference entries)    the extent of each entry's row in A_prev (workspace);
+//                                             the extent in A_prev of the row of every difference entry, and
+//                                             what the merge has to know about the row in which each of its
+//                                             ranges begins (both for the merge, in the workspace);
 //   2. merge_kernel   (ranges of old entries) streams A_prev's column indices once: deleted entries
 //      are struck out, added entries slotted in, a prefix sum per sub-tile gives the positions.
 //      Ranges hold equal numbers of old entries, so hub rows of power-law graphs are spread over
 //      many wavefronts, and an old entry costs one coalesced read and one coalesced write.
+#include <algorithm>
+
 #include "common.hpp"
 
 namespace {
@@ -28,6 +31,10 @@ constexpr int kSub = kWave * kPerLane;       // old entries per sub-tile, at mos
 constexpr int kMaxRange = kSub * 16;         // old entries streamed by one wavefront, at most
 constexpr int kTargetWaves = 16384;          // ranges shrink on small inputs so that about this many wavefronts exist
 
+// The row in which a range of the merge begins: its extent in A_prev (rp, rp1) and in A_next (rn, rn1), and the stretch
+// of the added list that belongs to it (as, ae); the deleted list's stretch follows from these.
+struct RangeStart { int rp, rp1, rn, rn1, as, ae, row, pad; };
+
 __device__ __forceinline__ void report(int32_t *status, int code) {
     if (!status) return;
     int old = *status;
@@ -39,17 +46,25 @@ __device__ __forceinline__ void report(int32_t *status, int code) {
 }
 
 // Per-row counts of a sorted row list restricted to [lo, hi), accumulated into LDS counters by
-// run boundaries: the last element of a run adds (j + 1), the first subtracts j.
+// run boundaries: the last element of a run adds (j + 1), the first subtracts j.  On the way, where the row of
+// every entry lies in A_prev is written next to the list: ext[j] = (rowptr_prev[row_j], rowptr_prev[row_j + 1]).
+// The merge needs this pair for every entry it places; looked up there, it would be a load that depends on a
+// load in the middle of a stream.  COUNT = false: only the extents (the counts come from searches).
+// s_rp: the tile's row pointers of A_prev (rows r0 .. r0 + nr), staged in LDS.
+template <bool COUNT>
 __device__ __forceinline__ void count_runs(const int32_t *__restrict__ rows, int lo, int hi, int r0, int nr,
-                                           int *cnt, int tid) {
+                                           int *cnt, int tid, const int *s_rp, int2 *__restrict__ ext) {
     for (int j = lo + tid; j < hi; j += kRowThreads) {
         int r = rows[j];
-        bool first = (j == lo) || rows[j - 1] != r;
-        bool last = (j == hi - 1) || rows[j + 1] != r;
         unsigned k = (unsigned)(r - r0);
         if (k < (unsigned)nr) {
-            if (last) atomicAdd(&cnt[k], j + 1);
-            if (first) atomicSub(&cnt[k], j);
+            if (COUNT) {
+                bool first = (j == lo) || rows[j - 1] != r;
+                bool last = (j == hi - 1) || rows[j + 1] != r;
+                if (last) atomicAdd(&cnt[k], j + 1);
+                if (first) atomicSub(&cnt[k], j);
+            }
+            ext[j] = make_int2(s_rp[k], s_rp[k + 1]);
         }
     }
 }
@@ -74,10 +89,12 @@ __device__ __forceinline__ void count_by_search(const int32_t *__restrict__ rows
 __global__ __launch_bounds__(kRowThreads) void rowptr_kernel(
     int n, const int32_t *__restrict__ rowptr_prev,
     const int32_t *__restrict__ add_row, int n_add, const int32_t *__restrict__ del_row, int n_del,
-    int32_t *__restrict__ rowptr_next, int32_t *__restrict__ add_ptr, float *__restrict__ dinv,
+    int32_t *__restrict__ rowptr_next, float *__restrict__ dinv,
+    int2 *__restrict__ add_ext, int2 *__restrict__ del_ext, int range_len, int n_ranges, RangeStart *__restrict__ range_start,
     int32_t *status) {
     __shared__ int s_add[kRowTile];
     __shared__ int s_del[kRowTile];
+    __shared__ int s_rp[kRowTile + 1];
     __shared__ int s_bound[4];
     __shared__ int s_wsum[2][kRowThreads / kWave];
 
@@ -95,14 +112,15 @@ __global__ __launch_bounds__(kRowThreads) void rowptr_kernel(
         if (lane == 0) s_bound[wave] = below;
     }
     for (int i = tid; i < kRowTile; i += kRowThreads) { s_add[i] = 0; s_del[i] = 0; }
+    for (int i = tid; i <= nr; i += kRowThreads) s_rp[i] = rowptr_prev[r0 + i];      // r0 + nr <= n
     __syncthreads();
     const int a0 = s_bound[0], a1 = s_bound[1], d0 = s_bound[2], d1 = s_bound[3];
     // A tile of hub rows can own a very long stretch of a list; walking it would leave the whole chip
     // waiting for this workgroup, so there the counts come from one lower bound per row instead.
-    if (a1 - a0 <= kHeavyList) count_runs(add_row, a0, a1, r0, nr, s_add, tid);
-    else count_by_search(add_row, a0, a1, r0, nr, s_add, tid);
-    if (d1 - d0 <= kHeavyList) count_runs(del_row, d0, d1, r0, nr, s_del, tid);
-    else count_by_search(del_row, d0, d1, r0, nr, s_del, tid);
+    if (a1 - a0 <= kHeavyList) count_runs<true>(add_row, a0, a1, r0, nr, s_add, tid, s_rp, add_ext);
+    else { count_by_search(add_row, a0, a1, r0, nr, s_add, tid); count_runs<false>(add_row, a0, a1, r0, nr, s_add, tid, s_rp, add_ext); }
+    if (d1 - d0 <= kHeavyList) count_runs<true>(del_row, d0, d1, r0, nr, s_del, tid, s_rp, del_ext);
+    else { count_by_search(del_row, d0, d1, r0, nr, s_del, tid); count_runs<false>(del_row, d0, d1, r0, nr, s_del, tid, s_rp, del_ext); }
     __syncthreads();
 
     int ca[kRowsPerThread], cd[kRowsPerThread];
@@ -124,35 +142,18 @@ __global__ __launch_bounds__(kRowThreads) void rowptr_kernel(
     for (int k = 0; k < kRowsPerThread; ++k) {
         int r = r0 + tid * kRowsPerThread + k;
         if (r < r1) {
-            int rp = rowptr_prev[r], rq = rowptr_prev[r + 1];
+            const int rp = s_rp[tid * kRowsPerThread + k], rq = s_rp[tid * kRowsPerThread + k + 1];
             rowptr_next[r] = rp + oa - od;
-            add_ptr[r] = oa;
             if (dinv) dinv[r] = 1.0f / sqrtf((float)(rq - rp + ca[k] - cd[k]));
+            // ranges of the merge that begin inside this row (few rows hold a multiple of the range length; a hub
+            // row several): what the merge needs to know about the row, so that it starts without a search
+            for (int g = max((rp + range_len - 1) / range_len, 0); g < n_ranges && (int64_t)g * range_len < rq; ++g)
+                range_start[g] = RangeStart{rp, rq, rp + oa - od, rq + oa + ca[k] - od - cd[k], oa, oa + ca[k], r, 0};
         }
         oa += ca[k];
         od += cd[k];
     }
-    if (r1 == n && tid == 0) {
-        rowptr_next[n] = rowptr_prev[n] + n_add - n_del;
-        add_ptr[n] = n_add;
-    }
-}
-
-// Where the row of every difference entry lies in A_prev: ext[j] = (rowptr_prev[row_j], rowptr_prev[row_j + 1]),
-// added entries first, then deleted ones.  The merge needs this pair for every entry it places; looked up
-// there, it would be a load that depends on a load in the middle of a stream.
-__global__ __launch_bounds__(256) void extent_kernel(int n, const int32_t *__restrict__ rowptr_prev,
-                                                     const int32_t *__restrict__ add_row, int n_add,
-                                                     const int32_t *__restrict__ del_row, int n_del,
-                                                     int2 *__restrict__ add_ext, int2 *__restrict__ del_ext) {
-    const int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (g >= (int64_t)n_add + n_del) return;
-    const bool is_add = g < n_add;
-    const int j = is_add ? (int)g : (int)(g - n_add);
-    const int r = is_add ? add_row[j] : del_row[j];
-    int2 x = make_int2(0x7fffffff, 0x7fffffff);          // a row outside [0, n) owns nothing
-    if ((unsigned)r < (unsigned)n) x = make_int2(rowptr_prev[r], rowptr_prev[r + 1]);
-    (is_add ? add_ext : del_ext)[j] = x;
+    if (r1 == n && tid == 0) rowptr_next[n] = rowptr_prev[n] + n_add - n_del;
 }
 
 // First position in the ascending LDS array a[lo, hi) whose value is >= key (STRICT = false) or > key.
@@ -173,9 +174,10 @@ __device__ __forceinline__ int lds_bound(const int *a, int lo, int hi, int key) 
 //     sub-tile finds its old entry there by binary search and marks it dead, each added entry
 //     finds the old entry it goes in front of (its slot) and counts itself there.  Where the row
 //     of a difference entry lies inside the sub-tile follows from its row's extent in A_prev,
-//     which extent_kernel has written next to the lists, so that no load here depends on another;
+//     which rowptr_kernel has written next to the lists, so that no load here depends on another;
 //   - both lists are consumed in order through two cursors, so the lists are never searched
-//     (except once, where a range begins in the middle of a row);
+//     (except once, where a range begins in the middle of a row); where a range's first row lies in A_prev,
+//     in A_next and in the lists comes from rowptr_kernel as well;
 //   - one prefix sum over (alive, added-before) gives every old entry and every slot its place
 //     relative to the sub-tile's first output position; that position follows from rowptr_next
 //     at the start of the range and simply advances by what each sub-tile wrote.
@@ -185,10 +187,10 @@ __device__ __forceinline__ int lds_bound(const int *a, int lo, int hi, int key) 
 // entries bring theirs.
 template <bool VALUES>
 __global__ __launch_bounds__(kWave) void merge_kernel(
-    int n, const int32_t *__restrict__ rowptr_prev, const int32_t *__restrict__ colidx_prev, int nnz_prev, int range_len,
+    const int32_t *__restrict__ colidx_prev, int nnz_prev, int range_len,
     const int32_t *__restrict__ add_col, const int2 *__restrict__ add_ext, int n_add,
     const int32_t *__restrict__ del_col, const int2 *__restrict__ del_ext, int n_del,
-    const int32_t *__restrict__ rowptr_next, const int32_t *__restrict__ add_ptr,
+    const RangeStart *__restrict__ range_start,
     int32_t *__restrict__ colidx_next, int cap_next,
     const float *__restrict__ val_prev, const float *__restrict__ add_val, float *__restrict__ val_next) {
     __shared__ int s_col[kSub];
@@ -209,13 +211,11 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
     }
 
     // ---- start of the range: its row, the list cursors, the first output position
-    const int k0 = max(wave_find_row(rowptr_prev, n, e_begin, lane), 0);   // row that holds entry e_begin
     int a_cur, d_cur;   // first added / deleted entry not yet placed
     int base;           // output position of the next entry to be written
     {
-        const int rp = rowptr_prev[k0], rp1 = rowptr_prev[k0 + 1];
-        const int rn = rowptr_next[k0], rn1 = rowptr_next[k0 + 1];
-        const int as = add_ptr[k0], ae = add_ptr[k0 + 1];
+        const RangeStart st = range_start[blockIdx.x];                     // the row that holds entry e_begin
+        const int rp = st.rp, rp1 = st.rp1, rn = st.rn, rn1 = st.rn1, as = st.as, ae = st.ae;
         const int ds = rp + as - rn, de = rp1 + ae - rn1;
         a_cur = as;
         d_cur = ds;
@@ -553,11 +553,25 @@ extern "C" int dgnn_delta_h2d(const int32_t *h_add_row, const int32_t *h_add_col
     return DGNN_OK;
 }
 
+namespace {
+
+// Entries per wavefront of the merge: a multiple of the sub-tile, at most kMaxRange, smaller when the input is small.
+int64_t merge_range_length(int64_t nnz_prev) {
+    int64_t range_len = (nnz_prev + kTargetWaves - 1) / kTargetWaves;
+    range_len = (range_len + kSub - 1) / kSub * kSub;
+    return std::min<int64_t>(std::max<int64_t>(range_len, kSub), kMaxRange);
+}
+// No call with at most nnz_prev entries has more ranges than this (a smaller snapshot gets shorter ranges, never more
+// than kTargetWaves + 1 of them), so a workspace sized for the largest snapshot of a block serves every step.
+int64_t max_ranges(int64_t nnz_prev) { return std::max<int64_t>(kTargetWaves + 1, (nnz_prev + kMaxRange - 1) / kMaxRange) + 1; }
+
+}  // namespace
+
 extern "C" int dgnn_delta_rebuild_workspace(int64_t n, int64_t nnz_prev, int64_t n_add, int64_t n_del, size_t *bytes) {
     if (!bytes) return DGNN_ERR_NULL;
     if (n <= 0 || nnz_prev < 0 || n_add < 0 || n_del < 0) return DGNN_ERR_SHAPE;
     if (!fits_index(n + 1) || !fits_index(nnz_prev + n_add)) return DGNN_ERR_OVERFLOW;
-    *bytes = round_up((size_t)(n + 1) * sizeof(int32_t), 256)     // add_ptr
+    *bytes = round_up((size_t)max_ranges(nnz_prev) * sizeof(RangeStart), 256)   // the row every range of the merge begins in
              + round_up((size_t)n_add * sizeof(int2), 256)         // row extents of the added entries
              + round_up((size_t)n_del * sizeof(int2), 256);        // ... of the deleted entries
     return DGNN_OK;
@@ -596,14 +610,15 @@ int rebuild(int64_t n, const int32_t *rowptr_prev, const int32_t *colidx_prev, i
 
     hipStream_t s = (hipStream_t)stream;
     char *wsb = static_cast<char *>(ws);
-    int32_t *add_ptr = reinterpret_cast<int32_t *>(wsb);
-    int2 *add_ext = reinterpret_cast<int2 *>(wsb + round_up((size_t)(n + 1) * sizeof(int32_t), 256));
+    RangeStart *range_start = reinterpret_cast<RangeStart *>(wsb);
+    int2 *add_ext = reinterpret_cast<int2 *>(wsb + round_up((size_t)max_ranges(nnz_prev) * sizeof(RangeStart), 256));
     int2 *del_ext = reinterpret_cast<int2 *>(reinterpret_cast<char *>(add_ext) + round_up((size_t)n_add * sizeof(int2), 256));
     const int cap = (int)min(cap_next, (int64_t)2147483647LL);
+    const int64_t range_len = merge_range_length(nnz_prev);
 
     hipLaunchKernelGGL(rowptr_kernel, dim3((unsigned)((n + kRowTile - 1) / kRowTile)), dim3(kRowThreads), 0, s,
-                       (int)n, rowptr_prev, add_row, (int)n_add, del_row, (int)n_del, rowptr_next, add_ptr,
-                       dinv_next, d_status);
+                       (int)n, rowptr_prev, add_row, (int)n_add, del_row, (int)n_del, rowptr_next,
+                       dinv_next, add_ext, del_ext, (int)range_len, (int)((nnz_prev + range_len - 1) / range_len), range_start, d_status);
     DGNN_RETURN_IF_LAUNCH_FAILED();
     if ((flags & DGNN_VALIDATE) && d_status) {
         int64_t work = n_add + n_del + n;
@@ -612,23 +627,15 @@ int rebuild(int64_t n, const int32_t *rowptr_prev, const int32_t *colidx_prev, i
                            (int)n_del, d_status);
         DGNN_RETURN_IF_LAUNCH_FAILED();
     }
-    if (n_add + n_del > 0) {
-        hipLaunchKernelGGL(extent_kernel, dim3((unsigned)((n_add + n_del + 255) / 256)), dim3(256), 0, s, (int)n, rowptr_prev,
-                           add_row, (int)n_add, del_row, (int)n_del, add_ext, del_ext);
-        DGNN_RETURN_IF_LAUNCH_FAILED();
-    }
-    int64_t range_len = (nnz_prev + kTargetWaves - 1) / kTargetWaves;
-    range_len = (range_len + kSub - 1) / kSub * kSub;
-    if (range_len > kMaxRange) range_len = kMaxRange;
     const dim3 grid((unsigned)((nnz_prev + range_len - 1) / range_len));
     if (vals)
-        hipLaunchKernelGGL(merge_kernel<true>, grid, dim3(kWave), 0, s, (int)n, rowptr_prev, colidx_prev, (int)nnz_prev,
-                           (int)range_len, add_col, add_ext, (int)n_add, del_col, del_ext, (int)n_del, rowptr_next, add_ptr,
-                           colidx_next, cap, vals->prev, vals->add, vals->next);
+        hipLaunchKernelGGL(merge_kernel<true>, grid, dim3(kWave), 0, s, colidx_prev, (int)nnz_prev,
+                           (int)range_len, add_col, add_ext, (int)n_add, del_col, del_ext, (int)n_del,
+                           range_start, colidx_next, cap, vals->prev, vals->add, vals->next);
     else
-        hipLaunchKernelGGL(merge_kernel<false>, grid, dim3(kWave), 0, s, (int)n, rowptr_prev, colidx_prev, (int)nnz_prev,
-                           (int)range_len, add_col, add_ext, (int)n_add, del_col, del_ext, (int)n_del, rowptr_next, add_ptr,
-                           colidx_next, cap, nullptr, nullptr, nullptr);
+        hipLaunchKernelGGL(merge_kernel<false>, grid, dim3(kWave), 0, s, colidx_prev, (int)nnz_prev,
+                           (int)range_len, add_col, add_ext, (int)n_add, del_col, del_ext, (int)n_del,
+                           range_start, colidx_next, cap, nullptr, nullptr, nullptr);
     DGNN_RETURN_IF_LAUNCH_FAILED();
     return DGNN_OK;
 }
