@@ -7,8 +7,10 @@
 // The time loop is unrolled by the ring size so that ring slots are compile-time registers.
 // With the paper's weights (every term 1/min(w,t)) the window sum is kept as a running sum,
 // S_t = S_{t-1} + Z_t - Z_{t-w}, with a ring of exactly w slots (the slot about to be overwritten
-// holds Z_{t-w}) and up to four frames fetched ahead; explicit coefficients take the general
-// kernel, w multiply-adds per element.
+// holds Z_{t-w}) and up to four frames fetched ahead; every w steps the sum is replaced by one formed
+// from that round's frames alone, so that what a frame leaves behind in it (rounding residue, or
+// not-a-number once an infinity has left the window) is gone less than two windows later.  Explicit
+// coefficients take the general kernels, w multiply-adds per element.
 //
 // A series longer than one block of timesteps is mixed block by block (Section "Gradient Checkpoint": what a
 // block needs from the one before it is handed over).  Going forward the hand-over is the last w - 1 frames
@@ -128,6 +130,55 @@ __global__ __launch_bounds__(kThreads) void mproduct_kernel(const char *z, char 
     }
 }
 
+// The same with explicit coefficients for rings too long for the kernel above (its body, unrolled over ring slots
+// times window terms, grows with the square of the ring, and the compiler then keeps the ring in scratch memory):
+// the ring holds raw 16-byte pieces, slot j always the frame of j steps ago, and moves down one slot per step, so
+// every slot is a fixed register and the body grows with the ring only.
+template <int RING, bool BF16, bool REVERSE>
+__global__ __launch_bounds__(kThreads) void mproduct_shift_kernel(const char *z, char *y, int T, int64_t pieces,
+                                                                  int64_t frame_bytes, int w, const float *__restrict__ m_band,
+                                                                  Halo halo) {
+    constexpr int NV = Vec<BF16>::kVals;
+    const int64_t piece = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (piece >= pieces) return;
+    const char *src = z + piece * 16;
+    char *dst = y + piece * 16;
+    auto frame_of = [&](int i) { return REVERSE ? T - 1 - i : i; };
+
+    // before the first step, slot j - 1 holds the frame of step -j: a handed-over frame, or nothing
+    uintx4 ring[RING];
+#pragma unroll
+    for (int j = 1; j <= RING; ++j) {
+        ring[j - 1] = uintx4{0u, 0u, 0u, 0u};
+        const int h = REVERSE ? j - 1 : halo.count - j;
+        if (h >= 0 && h < halo.count) ring[j - 1] = *reinterpret_cast<const uintx4 *>(halo.frames + (int64_t)h * frame_bytes + piece * 16);
+    }
+    uintx4 next = *reinterpret_cast<const uintx4 *>(src + (int64_t)frame_of(0) * frame_bytes);
+#pragma unroll 1
+    for (int i = 0; i < T; ++i) {
+        const int t = frame_of(i);
+#pragma unroll
+        for (int j = RING - 1; j > 0; --j) ring[j] = ring[j - 1];
+        ring[0] = next;
+        next = *reinterpret_cast<const uintx4 *>(src + (int64_t)frame_of(min(i + 1, T - 1)) * frame_bytes);   // before the store: y may be z
+        const int terms = REVERSE ? min(w, T - t + halo.count) : min(w, t + 1 + halo.count);
+        float out[NV];
+#pragma unroll
+        for (int e = 0; e < NV; ++e) out[e] = 0.0f;
+#pragma unroll
+        for (int j = 0; j < RING; ++j) {
+            if (j < terms) {
+                const float c = m_band[(int64_t)(REVERSE ? t + j : t) * w + j];
+                float v[NV];
+                Vec<BF16>::unpack(v, ring[j]);
+#pragma unroll
+                for (int e = 0; e < NV; ++e) out[e] = fmaf(c, v[e], out[e]);
+            }
+        }
+        Vec<BF16>::store(dst + (int64_t)t * frame_bytes, out);
+    }
+}
+
 // The paper's weights: ring of exactly W raw 16-byte pieces, running window sum in fp32.
 // D frames are fetched ahead of the one being summed.  Every load is unconditional (beyond the last frame the
 // last one is simply read again), so each is waited for by itself and a lane keeps D loads and its stores in
@@ -146,9 +197,9 @@ __global__ __launch_bounds__(kThreads) void mproduct_uniform_kernel(const char *
     auto frame_of = [&](int i) { return REVERSE ? T - 1 - i : i; };
 
     uintx4 ring[W];
-    float sum[NV];
+    float sum[NV], fresh[NV];          // the running window sum, and the sum of the frames of the current round
 #pragma unroll
-    for (int e = 0; e < NV; ++e) sum[e] = 0.0f;
+    for (int e = 0; e < NV; ++e) sum[e] = fresh[e] = 0.0f;
     // slot r of the ring is where step (r - W) would have left its frame: the handed-over frames go there and
     // into the running sum
 #pragma unroll
@@ -183,9 +234,11 @@ __global__ __launch_bounds__(kThreads) void mproduct_uniform_kernel(const char *
         for (int e = 0; e < NV; ++e) {
             if (REVERSE) {
                 sum[e] += in[e] * scale - old[e] * (1.0f / (float)W);    // the leaving frame is t + W: min(W, t + W + 1) = W
+                fresh[e] += in[e] * scale;
                 out[e] = sum[e];
             } else {
                 sum[e] += in[e] - old[e];
+                fresh[e] += in[e];
                 out[e] = sum[e] * scale;
             }
         }
@@ -194,7 +247,14 @@ __global__ __launch_bounds__(kThreads) void mproduct_uniform_kernel(const char *
     int tb = 0;
     for (; tb + W <= T; tb += W) {
 #pragma unroll
+        for (int e = 0; e < NV; ++e) fresh[e] = 0.0f;
+#pragma unroll
         for (int jj = 0; jj < W; ++jj) step(tb + jj, ring[jj], ahead[jj % D]);
+        // A whole round has gone by: the W frames it brought in are exactly the window now, and `fresh` is their sum
+        // formed on its own.  It replaces the running sum, so that rounding residue of large values, and anything
+        // that is not a number, stop travelling along here instead of staying in the sum for the rest of the series.
+#pragma unroll
+        for (int e = 0; e < NV; ++e) sum[e] = fresh[e];
     }
 #pragma unroll
     for (int jj = 0; jj < W; ++jj)
@@ -240,6 +300,22 @@ int launch(const void *z, void *y, int64_t T, int64_t n, int32_t f, int32_t w, c
     return DGNN_OK;
 }
 
+template <int RING, bool REVERSE>
+int launch_shift(const void *z, void *y, int64_t T, int64_t n, int32_t f, int32_t w, const float *m_band, dgnn_dtype dt,
+                 Halo halo, hipStream_t s) {
+    const int64_t frame_bytes = n * f * (dt == DGNN_F32 ? 4 : 2);
+    const int64_t pieces = frame_bytes / 16;
+    const unsigned blocks = (unsigned)((pieces + kThreads - 1) / kThreads);
+    if (dt == DGNN_F32)
+        hipLaunchKernelGGL((mproduct_shift_kernel<RING, false, REVERSE>), dim3(blocks), dim3(kThreads), 0, s,
+                           static_cast<const char *>(z), static_cast<char *>(y), (int)T, pieces, frame_bytes, (int)w, m_band, halo);
+    else
+        hipLaunchKernelGGL((mproduct_shift_kernel<RING, true, REVERSE>), dim3(blocks), dim3(kThreads), 0, s,
+                           static_cast<const char *>(z), static_cast<char *>(y), (int)T, pieces, frame_bytes, (int)w, m_band, halo);
+    DGNN_RETURN_IF_LAUNCH_FAILED();
+    return DGNN_OK;
+}
+
 template <bool REVERSE>
 int mproduct(const void *z, void *y, int64_t T, int64_t n, int32_t f, int32_t w, const float *m_band, int64_t t0,
              const void *halo_frames, int64_t n_halo, dgnn_dtype dt, void *stream) {
@@ -271,7 +347,8 @@ int mproduct(const void *z, void *y, int64_t T, int64_t n, int32_t f, int32_t w,
     if (eff <= 4) return launch<4, REVERSE>(z, y, T, n, f, wk, m_band, dt, halo, s);
     if (eff <= 8) return launch<8, REVERSE>(z, y, T, n, f, wk, m_band, dt, halo, s);
     if (eff <= 16) return launch<16, REVERSE>(z, y, T, n, f, wk, m_band, dt, halo, s);
-    return launch<32, REVERSE>(z, y, T, n, f, wk, m_band, dt, halo, s);
+    if (eff <= 24) return launch_shift<24, REVERSE>(z, y, T, n, f, wk, m_band, dt, halo, s);
+    return launch_shift<32, REVERSE>(z, y, T, n, f, wk, m_band, dt, halo, s);
 }
 
 }  // namespace

@@ -369,6 +369,64 @@ def test_mproduct_explicit_band():
     assert_close(to_f64(y), oracle.mproduct(to_f64(z), M), torch.float32, "explicit band")
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("T,w", [(40, 17), (50, 24), (70, 32), (20, 32), (33, 25)])
+def test_mproduct_explicit_band_long_windows(dtype, T, w):
+    """Explicit coefficients with windows beyond 16 (the kernels that keep the ring as raw pieces moving down one slot
+    per step), forward and adjoint, out of place and in place."""
+    n, f = 200, 32
+    gen = torch.Generator().manual_seed(T * 37 + w)
+    z = torch.randn((T, n, f), generator=gen).to(dtype)
+    band = torch.randn((T, w), generator=gen) / w ** 0.5
+    M = np.zeros((T, T))
+    for t in range(T):
+        for j in range(min(w, t + 1)):
+            M[t, t - j] = float(band[t, j])
+    zd, bd = z.to(DEV), band.to(DEV)
+    y = torch.full_like(zd, float("nan"))
+    dg.mproduct(zd, y, w, m_band=bd)
+    assert_close(to_f64(y), oracle.mproduct(to_f64(z), M), dtype, f"explicit band T={T} w={w}")
+    g = torch.full_like(zd, float("nan"))
+    dg.mproduct_backward(zd, g, w, m_band=bd)
+    assert_close(to_f64(g), oracle.mproduct_t(to_f64(z), M), dtype, f"adjoint, explicit band T={T} w={w}")
+    dg.mproduct(zd, zd, w, m_band=bd)
+    torch.cuda.synchronize()
+    assert torch.equal(zd, y)
+
+
+@pytest.mark.parametrize("w", [3, 8, 16])
+def test_mproduct_running_sum_forgets_what_has_left_the_window(w):
+    """The paper's weights are served by a running window sum.  What a frame leaves behind in it must not stay for the
+    rest of the series: after a spike of 1e6 and after an infinity, every frame from two windows behind the event on
+    is what the definition gives (exact zeros for a window of zeros, finite values after the infinity)."""
+    T, n, f = 7 * w + 5, 64, 16
+    z = torch.randn((T, n, f), generator=torch.Generator().manual_seed(w))
+    z[2] *= 1.0e6                                                         # a spike among ordinary values ...
+    z[4 * w + 1:] = 0.0                                                   # ... and, later, nothing but zeros
+    zd = z.to(DEV)
+    y = torch.empty_like(zd)
+    dg.mproduct(zd, y, w)
+    torch.cuda.synchronize()
+    expect = oracle.mproduct(to_f64(z), oracle.m_matrix(T, w))
+    assert_close(to_f64(y[:2 + w]), expect[:2 + w], torch.float32, "while the spike is in the window")
+    assert_close(to_f64(y[2 + 2 * w:4 * w + 1]), expect[2 + 2 * w:4 * w + 1], torch.float32, "two windows behind the spike")
+    assert float(y[6 * w + 1:].abs().max()) == 0.0                        # a window of zeros gives zeros, exactly
+    z2 = torch.randn((T, n, f), generator=torch.Generator().manual_seed(w + 1))
+    z2[3, 5, 7] = float("inf")
+    y2 = torch.empty((T, n, f), device=DEV)
+    dg.mproduct(z2.to(DEV), y2, w)
+    torch.cuda.synchronize()
+    clean = z2.clone(); clean[3, 5, 7] = 0.0
+    late = slice(3 + 2 * w, T)
+    assert bool(torch.isfinite(y2[late]).all())
+    assert_close(to_f64(y2[late]), oracle.mproduct(to_f64(clean), oracle.m_matrix(T, w))[late], torch.float32, "after the infinity has left")
+    g2 = torch.empty((T, n, f), device=DEV)
+    dg.mproduct_backward(z2.to(DEV), g2, w)                               # going back the walk starts at the end
+    torch.cuda.synchronize()
+    early = slice(0, 3 - 2 * w) if 3 - 2 * w > 0 else slice(0, 0)
+    assert bool(torch.isfinite(g2[early]).all())
+
+
 def test_csr_validate_finds_what_is_wrong():
     """A canonical snapshot passes; each way of breaking it is reported with its code."""
     wl = WORKLOADS["c3"].scaled(1 << 12, T=1)
