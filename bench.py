@@ -56,6 +56,10 @@ def parse_args():
                     help="also time one step of the path for snapshots that carry a value per entry")
     ap.add_argument("--smoothing", action="store_true",
                     help="also time the sliding-window sum of the block's snapshots (edge life 4) computed on the device")
+    ap.add_argument("--working-sets", action="store_true",
+                    help="also time the aggregation with its gathers confined to working sets of known size")
+    ap.add_argument("--mproduct-band", action="store_true",
+                    help="also time the M-transform with explicit coefficients and window 32")
     ap.add_argument("--no-extras", action="store_true",
                     help="only the headline figure (and whatever is asked for explicitly): skip the CD-GCN, weighted and smoothing figures")
     ap.add_argument("--gen-device", default="cuda", choices=["cuda", "cpu"],
@@ -171,6 +175,67 @@ def cpu_baseline(wl, blk, first, budget_s):
     out = dict(single)
     out.update({"kind": "oracle", "all_cores": multi, "nproc": os.cpu_count(), "cpu_model": model})
     return out
+
+
+def gather_working_sets(args, wl, blk, dev):
+    """dgnn_spmm on the first snapshot's row structure with the column indices replaced, so that the gathered rows of H
+    come from working sets of known size: inside one L2 (1 MB), inside the Infinity Cache (32 MB), or spread uniformly
+    over the whole of H.  Tells what bounds the aggregation on the real columns: an extra figure."""
+    import torch
+    import paper_2109_07893_amd as dg
+    n, f, nnz = blk.n, blk.f, blk.nnz[0]
+    h = blk.x[0]
+    z = torch.empty_like(h)
+    dinv = torch.empty(n, dtype=torch.float32, device=dev)
+    dg.csr_dinv(blk.rowptr1, dinv)
+    ws = torch.empty(dg.spmm_workspace(n, nnz, f), dtype=torch.uint8, device=dev)
+    idx = torch.arange(nnz, device=dev, dtype=torch.int64)
+    row_bytes = f * h.element_size()
+    patterns = [("the workload's columns", blk.colidx1)]
+    for size in (1 << 20, 32 << 20):
+        m = max(1, min(n, size // row_bytes))
+        patterns.append((f"columns inside {size >> 20} MB of H", ((idx * 2654435761) % m).to(torch.int32)))
+    gen = torch.Generator(device=dev).manual_seed(wl.seed)
+    patterns.append((f"uniformly random columns ({n * row_bytes / 1e9:.2f} GB of H)", torch.randint(0, n, (nnz,), generator=gen, device=dev, dtype=torch.int32)))
+    del idx
+    out = {"entries": nnz, "gathered_bytes": nnz * row_bytes, "cases": []}
+    for label, cols in patterns:
+        for _ in range(2):
+            dg.spmm(blk.rowptr1, cols, nnz, dinv, h, z, ws, flags=dg.DGNN_RELU | dg.DGNN_H_PRESCALED)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            dg.spmm(blk.rowptr1, cols, nnz, dinv, h, z, ws, flags=dg.DGNN_RELU | dg.DGNN_H_PRESCALED)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        out["cases"].append({"columns": label, "avg_ms": round(ms, 4), "gather_GBps": round(nnz * row_bytes / (ms * 1e-3) / 1e9, 1)})
+    return out
+
+
+def mproduct_band(args, wl, blk, dev):
+    """The M-transform with explicit coefficients and the longest window (32) over frames of the workload's shape:
+    an extra figure for the kernel that keeps its ring as raw pieces."""
+    import torch
+    import paper_2109_07893_amd as dg
+    n, f, T, w = blk.n, blk.f, 40, 32
+    free, _ = torch.cuda.mem_get_info(dev)
+    frame = n * f * blk.x[0].element_size()
+    T = int(max(w + 1, min(T, 0.4 * free // frame)))
+    z = torch.empty((T, n, f), dtype=blk.x[0].dtype, device=dev).normal_()
+    band = torch.full((T, w), 1.0 / w, device=dev)
+    for _ in range(2):
+        dg.mproduct(z, z, w, m_band=band)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        dg.mproduct(z, z, w, m_band=band)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    return {"window": w, "frames": T, "avg_ms": round(ms, 3), "algorithmic_GBps": round(2 * T * frame / (ms * 1e-3) / 1e9, 1)}
 
 
 def weighted_step(args, wl, blk, dev):
@@ -685,6 +750,8 @@ def main():
         torch.cuda.empty_cache()
         progress(f"{key} timed")
 
+    extra("gather_working_sets", args.working_sets, gather_working_sets)
+    extra("mproduct_explicit_band", args.mproduct_band, mproduct_band)
     extra("cdgcn_layer", args.cdgcn, cdgcn_layer)
     extra("weighted_step", args.weighted, weighted_step)
     extra("smoothing", args.smoothing, smoothing_steps)
