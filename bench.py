@@ -260,11 +260,15 @@ def weighted_step(args, wl, blk, dev):
     rpn = torch.empty(n + 1, dtype=torch.int32, device=dev)
     cin = torch.empty(cap, dtype=torch.int32, device=dev)
     vn = torch.empty(cap, dtype=torch.float32, device=dev)
-    ws_r = torch.empty(dg.delta_rebuild_workspace(n, nnz1, ar.numel(), dr.numel()), dtype=torch.uint8, device=dev)
+    ws_r = torch.empty(dg.delta_rebuild_weighted_workspace(n, nnz1, ar.numel(), dr.numel(), ur.numel()), dtype=torch.uint8, device=dev)
     ws_s = torch.empty(dg.spmm_workspace(n, cap, f), dtype=torch.uint8, device=dev)
     h, z = blk.x[1], torch.empty_like(blk.x[1])
 
-    def rebuild():
+    def rebuild():      # the update list is sorted by (row, col): the merge consumes it
+        dg.delta_rebuild_weighted(blk.rowptr1, blk.colidx1, val1, nnz1, (ar, ac, add_val), (dr, dc), (ur, uc, uv), rpn, cin,
+                                  vn, ws_r, flags=dg.DGNN_UPDATES_SORTED)
+
+    def rebuild_any_order():      # the same list handed over as unordered: a pass of its own after the merge
         dg.delta_rebuild_weighted(blk.rowptr1, blk.colidx1, val1, nnz1, (ar, ac, add_val), (dr, dc), (ur, uc, uv), rpn, cin,
                                   vn, ws_r)
 
@@ -279,7 +283,9 @@ def weighted_step(args, wl, blk, dev):
 
     out = {}
     s = h.element_size()
-    for name, fn, byts in (("delta_rebuild_weighted", rebuild, 8 * nnz1 + 8 * cap + 16 * n + 20 * (ar.numel() + dr.numel()) + 12 * ur.numel()),
+    rebuild_bytes = 8 * nnz1 + 8 * cap + 16 * n + 20 * (ar.numel() + dr.numel()) + 12 * ur.numel()
+    for name, fn, byts in (("delta_rebuild_weighted", rebuild, rebuild_bytes),
+                           ("delta_rebuild_weighted_updates_in_any_order", rebuild_any_order, rebuild_bytes),
                            ("spmm_weighted", aggregate, 8 * cap + 4 * n + 2 * s * n * f),
                            ("csr_weighted_dinv", normalise, 4 * cap + 8 * n)):
         for _ in range(2):

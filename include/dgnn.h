@@ -52,8 +52,9 @@ typedef enum {
 /* Storage type of feature matrices; accumulation is always fp32.  bf16 stores round to nearest even. */
 typedef enum { DGNN_F32 = 0, DGNN_BF16 = 1 } dgnn_dtype;
 
-/* Flags of dgnn_delta_rebuild. */
-#define DGNN_VALIDATE 1u     /* check the difference lists against A_prev on the device */
+/* Flags of dgnn_delta_rebuild and dgnn_delta_rebuild_weighted. */
+#define DGNN_VALIDATE 1u         /* check the difference lists against A_prev on the device */
+#define DGNN_UPDATES_SORTED 2u   /* weighted only: the value-update list is sorted by (row, col) without repeats */
 
 /* Codes written to *d_status by dgnn_delta_rebuild (0 = nothing found; the smallest code found wins). */
 #define DGNN_BAD_INDEX_RANGE 1   /* a row or column index outside [0, n)                         */
@@ -95,10 +96,12 @@ int dgnn_delta_h2d(const int32_t *h_add_row, const int32_t *h_add_col, int64_t n
                    int32_t *d_add_row, int32_t *d_add_col, int32_t *d_del_row, int32_t *d_del_col,
                    void *stream);
 
-/* Workspace size of dgnn_delta_rebuild in bytes (HOST out-parameter): 8 (n_add + n_del) plus 32 per range of 8192
+/* Workspace size of dgnn_delta_rebuild in bytes (HOST out-parameter): 8 (n_add + n_del) plus 40 per range of 8192
  * stored entries (never fewer than 16386 ranges), rounded up; it grows with each argument, so the size queried for
- * the largest snapshot and the longest lists of a block serves every step. */
+ * the largest snapshot and the longest lists of a block serves every step.  The second form adds 8 n_upd for a
+ * weighted rebuild that is given a sorted value-update list (DGNN_UPDATES_SORTED). */
 int dgnn_delta_rebuild_workspace(int64_t n, int64_t nnz_prev, int64_t n_add, int64_t n_del, size_t *bytes);
+int dgnn_delta_rebuild_weighted_workspace(int64_t n, int64_t nnz_prev, int64_t n_add, int64_t n_del, int64_t n_upd, size_t *bytes);
 
 /*
  * On-GPU reconstruction of a snapshot (same section): with A_prev on the device,
@@ -207,10 +210,18 @@ int dgnn_mproduct(const void *z, void *y, int64_t T, int64_t n, int32_t f, int32
  * entries keep their value unless the update list names them, added entries bring theirs.
  *   val_prev [nnz_prev], val_next [cap_next]    fp32, must not be the same array
  *   add_val [n_add]                             values of the added edges (list order)
- *   upd_row/upd_col/upd_val, n_upd              surviving edges whose value changes, any order; must name
+ *   upd_row/upd_col/upd_val, n_upd              surviving edges whose value changes, each named once; must name
  *                                               neither deleted nor added edges (entries that are not in A_next
  *                                               are skipped)
- * No dinv is produced: the values are the matrix.  Everything else as dgnn_delta_rebuild (same workspace query).
+ *   flags                                       DGNN_VALIDATE and/or DGNN_UPDATES_SORTED.  Without the latter the
+ *                                               update list may come in any order and is applied by a pass of its
+ *                                               own after the merge (workspace: dgnn_delta_rebuild_workspace).  With
+ *                                               it the list is sorted by (row, col) like the other two and the one
+ *                                               streaming merge consumes it as well (workspace:
+ *                                               dgnn_delta_rebuild_weighted_workspace with this n_upd); a list that
+ *                                               is not sorted then gives unspecified values, never an out-of-bounds
+ *                                               access, and DGNN_VALIDATE reports DGNN_BAD_DELTA_ORDER for it.
+ * No dinv is produced: the values are the matrix.  Everything else as dgnn_delta_rebuild.
  */
 int dgnn_delta_rebuild_weighted(int64_t n,
                                 const int32_t *rowptr_prev, const int32_t *colidx_prev, const float *val_prev,

@@ -32,8 +32,9 @@ constexpr int kMaxRange = kSub * 16;         // old entries streamed by one wave
 constexpr int kTargetWaves = 16384;          // ranges shrink on small inputs so that about this many wavefronts exist
 
 // The row in which a range of the merge begins: its extent in A_prev (rp, rp1) and in A_next (rn, rn1), and the stretch
-// of the added list that belongs to it (as, ae); the deleted list's stretch follows from these.
-struct RangeStart { int rp, rp1, rn, rn1, as, ae, row, pad; };
+// of the added list that belongs to it (as, ae); the deleted list's stretch follows from these.  us, ue: the row's
+// stretch of the sorted value-update list of a weighted rebuild (0, 0 without one).
+struct RangeStart { int rp, rp1, rn, rn1, as, ae, row, us, ue, pad; };
 
 __device__ __forceinline__ void report(int32_t *status, int code) {
     if (!status) return;
@@ -45,28 +46,65 @@ __device__ __forceinline__ void report(int32_t *status, int code) {
     }
 }
 
+constexpr int kListPerThread = 4;           // consecutive list entries per thread and round of the walk below
+
 // Per-row counts of a sorted row list restricted to [lo, hi), accumulated into LDS counters by
 // run boundaries: the last element of a run adds (j + 1), the first subtracts j.  On the way, where the row of
 // every entry lies in A_prev is written next to the list: ext[j] = (rowptr_prev[row_j], rowptr_prev[row_j + 1]).
 // The merge needs this pair for every entry it places; looked up there, it would be a load that depends on a
 // load in the middle of a stream.  COUNT = false: only the extents (the counts come from searches).
 // s_rp: the tile's row pointers of A_prev (rows r0 .. r0 + nr), staged in LDS.
+// A thread takes kListPerThread consecutive entries and their two neighbours, all loaded before any is looked at,
+// so that a tile's usual stretch of a list costs one trip to memory.
 template <bool COUNT>
 __device__ __forceinline__ void count_runs(const int32_t *__restrict__ rows, int lo, int hi, int r0, int nr,
                                            int *cnt, int tid, const int *s_rp, int2 *__restrict__ ext) {
-    for (int j = lo + tid; j < hi; j += kRowThreads) {
-        int r = rows[j];
-        unsigned k = (unsigned)(r - r0);
-        if (k < (unsigned)nr) {
-            if (COUNT) {
-                bool first = (j == lo) || rows[j - 1] != r;
-                bool last = (j == hi - 1) || rows[j + 1] != r;
-                if (last) atomicAdd(&cnt[k], j + 1);
-                if (first) atomicSub(&cnt[k], j);
+#pragma unroll 1
+    for (int base = lo; base < hi; base += kRowThreads * kListPerThread) {
+        const int j0 = base + tid * kListPerThread;
+        int r[kListPerThread + 2];        // rows[j0 - 1 .. j0 + kListPerThread]; -1 stands for "outside [lo, hi)"
+#pragma unroll
+        for (int k = 0; k < kListPerThread + 2; ++k) {
+            const int j = j0 - 1 + k;
+            r[k] = (j >= lo && j < hi) ? rows[j] : -1;
+        }
+#pragma unroll
+        for (int k = 0; k < kListPerThread; ++k) {
+            const int j = j0 + k;
+            const unsigned q = (unsigned)(r[k + 1] - r0);
+            if (j < hi && q < (unsigned)nr) {
+                if (COUNT) {
+                    if (r[k + 2] != r[k + 1]) atomicAdd(&cnt[q], j + 1);     // last of its run
+                    if (r[k] != r[k + 1]) atomicSub(&cnt[q], j);             // first of its run
+                }
+                ext[j] = make_int2(s_rp[q], s_rp[q + 1]);
             }
-            ext[j] = make_int2(s_rp[k], s_rp[k + 1]);
         }
     }
+}
+
+// wave_find_row for two lists at once: the two searches advance in lock step, so their loads travel together.
+// A list of length 0 (its pointer may be null) is not read and gives -1.
+__device__ __forceinline__ void wave_find_row_pair(const int32_t *__restrict__ a, int na, int key_a, const int32_t *__restrict__ b,
+                                                   int nb, int key_b, int lane, int &found_a, int &found_b) {
+    int lo_a = 0, hi_a = na, lo_b = 0, hi_b = nb;
+    while (hi_a > lo_a || hi_b > lo_b) {
+        const int step_a = (hi_a - lo_a + kWave - 1) / kWave, step_b = (hi_b - lo_b + kWave - 1) / kWave;
+        const int idx_a = lo_a + lane * step_a, idx_b = lo_b + lane * step_b;
+        const bool in_a = hi_a > lo_a && idx_a < hi_a, in_b = hi_b > lo_b && idx_b < hi_b;
+        const int v_a = in_a ? a[idx_a] : 0, v_b = in_b ? b[idx_b] : 0;
+        const int m_a = __popcll(__ballot(in_a && v_a <= key_a)), m_b = __popcll(__ballot(in_b && v_b <= key_b));
+        if (hi_a > lo_a) {
+            if (m_a == 0) hi_a = lo_a;
+            else { const int nlo = lo_a + (m_a - 1) * step_a + 1; hi_a = min(lo_a + m_a * step_a, hi_a); lo_a = nlo; }
+        }
+        if (hi_b > lo_b) {
+            if (m_b == 0) hi_b = lo_b;
+            else { const int nlo = lo_b + (m_b - 1) * step_b + 1; hi_b = min(lo_b + m_b * step_b, hi_b); lo_b = nlo; }
+        }
+    }
+    found_a = lo_a - 1;
+    found_b = lo_b - 1;
 }
 
 // The same counts from lower bounds: thread t finds where each of its rows begins inside [lo, hi),
@@ -91,11 +129,11 @@ __global__ __launch_bounds__(kRowThreads) void rowptr_kernel(
     const int32_t *__restrict__ add_row, int n_add, const int32_t *__restrict__ del_row, int n_del,
     int32_t *__restrict__ rowptr_next, float *__restrict__ dinv,
     int2 *__restrict__ add_ext, int2 *__restrict__ del_ext, int range_len, int n_ranges, RangeStart *__restrict__ range_start,
-    int32_t *status) {
+    const int32_t *__restrict__ upd_row, int n_upd, int2 *__restrict__ upd_ext, int32_t *status) {
     __shared__ int s_add[kRowTile];
     __shared__ int s_del[kRowTile];
     __shared__ int s_rp[kRowTile + 1];
-    __shared__ int s_bound[4];
+    __shared__ int s_bound[6];
     __shared__ int s_wsum[2][kRowThreads / kWave];
 
     const int tid = threadIdx.x;
@@ -105,14 +143,33 @@ __global__ __launch_bounds__(kRowThreads) void rowptr_kernel(
     const int nr = r1 - r0;
 
     if (blockIdx.x == 0 && tid == 0 && status) *status = 0;
-    {   // how many list entries have a row below r0 / below r1: one 64-ary search per wavefront
+    // the tile's row pointers (r0 + nr <= n), on their way while the searches run
+    int rp_own[kRowsPerThread];
+#pragma unroll
+    for (int k = 0; k < kRowsPerThread; ++k) {
+        const int i = tid + k * kRowThreads;
+        rp_own[k] = i <= nr ? rowptr_prev[r0 + i] : 0;
+    }
+    const int rp_last = (tid == 0 && nr == kRowTile) ? rowptr_prev[r0 + kRowTile] : 0;
+    {   // how many list entries have a row below r0 / below r1: one 64-ary search per wavefront and list; the
+        // wavefronts that search the added list take the value-update list of a weighted rebuild along
         const int32_t *list = wave < 2 ? add_row : del_row;
         const int len = wave < 2 ? n_add : n_del;
-        const int below = wave_find_row(list, len, ((wave & 1) ? r1 : r0) - 1, lane) + 1;
-        if (lane == 0) s_bound[wave] = below;
+        const int key = ((wave & 1) ? r1 : r0) - 1;
+        int found, found_upd;
+        wave_find_row_pair(list, len, key, upd_row, (wave < 2 && upd_row) ? n_upd : 0, key, lane, found, found_upd);
+        if (lane == 0) {
+            s_bound[wave] = found + 1;
+            if (wave < 2) s_bound[4 + wave] = found_upd + 1;
+        }
     }
     for (int i = tid; i < kRowTile; i += kRowThreads) { s_add[i] = 0; s_del[i] = 0; }
-    for (int i = tid; i <= nr; i += kRowThreads) s_rp[i] = rowptr_prev[r0 + i];      // r0 + nr <= n
+#pragma unroll
+    for (int k = 0; k < kRowsPerThread; ++k) {
+        const int i = tid + k * kRowThreads;
+        if (i <= nr) s_rp[i] = rp_own[k];
+    }
+    if (tid == 0 && nr == kRowTile) s_rp[kRowTile] = rp_last;
     __syncthreads();
     const int a0 = s_bound[0], a1 = s_bound[1], d0 = s_bound[2], d1 = s_bound[3];
     // A tile of hub rows can own a very long stretch of a list; walking it would leave the whole chip
@@ -121,6 +178,8 @@ __global__ __launch_bounds__(kRowThreads) void rowptr_kernel(
     else { count_by_search(add_row, a0, a1, r0, nr, s_add, tid); count_runs<false>(add_row, a0, a1, r0, nr, s_add, tid, s_rp, add_ext); }
     if (d1 - d0 <= kHeavyList) count_runs<true>(del_row, d0, d1, r0, nr, s_del, tid, s_rp, del_ext);
     else { count_by_search(del_row, d0, d1, r0, nr, s_del, tid); count_runs<false>(del_row, d0, d1, r0, nr, s_del, tid, s_rp, del_ext); }
+    const int u0 = upd_row ? s_bound[4] : 0, u1 = upd_row ? s_bound[5] : 0;
+    if (upd_row) count_runs<false>(upd_row, u0, u1, r0, nr, nullptr, tid, s_rp, upd_ext);     // extents only: nothing is counted
     __syncthreads();
 
     int ca[kRowsPerThread], cd[kRowsPerThread];
@@ -147,8 +206,14 @@ __global__ __launch_bounds__(kRowThreads) void rowptr_kernel(
             if (dinv) dinv[r] = 1.0f / sqrtf((float)(rq - rp + ca[k] - cd[k]));
             // ranges of the merge that begin inside this row (few rows hold a multiple of the range length; a hub
             // row several): what the merge needs to know about the row, so that it starts without a search
-            for (int g = max((rp + range_len - 1) / range_len, 0); g < n_ranges && (int64_t)g * range_len < rq; ++g)
-                range_start[g] = RangeStart{rp, rq, rp + oa - od, rq + oa + ca[k] - od - cd[k], oa, oa + ca[k], r, 0};
+            int us = -1, ue = 0;
+            for (int g = max((rp + range_len - 1) / range_len, 0); g < n_ranges && (int64_t)g * range_len < rq; ++g) {
+                if (upd_row && us < 0) {      // where the row's value updates lie: two searches inside the tile's stretch
+                    us = lower_bound(upd_row, u0, u1, r);
+                    ue = lower_bound(upd_row, us, u1, r + 1);
+                }
+                range_start[g] = RangeStart{rp, rq, rp + oa - od, rq + oa + ca[k] - od - cd[k], oa, oa + ca[k], r, max(us, 0), ue, 0};
+            }
         }
         oa += ca[k];
         od += cd[k];
@@ -184,18 +249,22 @@ __device__ __forceinline__ int lds_bound(const int *a, int lo, int hi, int key) 
 // Lane l owns entries l, l + 64, ... of the sub-tile, so loads and stores coalesce; the column
 // indices of the next sub-tile are fetched while this one is placed.
 // VALUES: every stored entry carries a value, which travels with its column index (same position); added
-// entries bring theirs.
-template <bool VALUES>
+// entries bring theirs.  UPDATES (with VALUES): a third list, sorted like the other two, names surviving entries
+// that get a new value; it is consumed through a cursor of its own, each entry finds its old entry in the staged
+// columns as a deleted entry does and leaves the new value there.  An entry that names nothing stored is passed over.
+template <bool VALUES, bool UPDATES>
 __global__ __launch_bounds__(kWave) void merge_kernel(
     const int32_t *__restrict__ colidx_prev, int nnz_prev, int range_len,
     const int32_t *__restrict__ add_col, const int2 *__restrict__ add_ext, int n_add,
     const int32_t *__restrict__ del_col, const int2 *__restrict__ del_ext, int n_del,
     const RangeStart *__restrict__ range_start,
     int32_t *__restrict__ colidx_next, int cap_next,
-    const float *__restrict__ val_prev, const float *__restrict__ add_val, float *__restrict__ val_next) {
+    const float *__restrict__ val_prev, const float *__restrict__ add_val, float *__restrict__ val_next,
+    const int32_t *__restrict__ upd_col, const int2 *__restrict__ upd_ext, const float *__restrict__ upd_val, int n_upd) {
     __shared__ int s_col[kSub];
-    __shared__ int s_mark[kSub + kWave];    // bit 0: deleted; bits 1..: added entries that go right before this slot
+    __shared__ int s_mark[kSub + kWave];    // bit 0: deleted; bit 1: new value in s_newval; bits 2..: added entries that go right before this slot
     __shared__ int s_start[kSub + kWave];   // outputs (kept + added) that precede the slot's block
+    __shared__ float s_newval[UPDATES ? kSub : 1];
 
     const int lane = threadIdx.x;
     const int e_begin = (int)((int64_t)blockIdx.x * range_len);
@@ -212,6 +281,7 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
 
     // ---- start of the range: its row, the list cursors, the first output position
     int a_cur, d_cur;   // first added / deleted entry not yet placed
+    int u_cur = 0;      // first value update not yet looked at
     int base;           // output position of the next entry to be written
     {
         const RangeStart st = range_start[blockIdx.x];                     // the row that holds entry e_begin
@@ -222,6 +292,11 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
         if (rp < e_begin) {   // the range begins inside row k0: skip what earlier ranges place
             if (as >= 0 && as < ae && ae <= n_add) a_cur = lower_bound(add_col, as, ae, colidx_prev[e_begin - 1]);
             if (ds >= 0 && ds < de && de <= n_del) d_cur = lower_bound(del_col, ds, de, colidx_prev[e_begin]);
+        }
+        if (UPDATES) {
+            u_cur = st.us;
+            if (rp < e_begin && st.us >= 0 && st.us < st.ue && st.ue <= n_upd) u_cur = lower_bound(upd_col, st.us, st.ue, colidx_prev[e_begin]);
+            u_cur = min(max(u_cur, 0), n_upd);
         }
         a_cur = min(max(a_cur, 0), n_add);
         d_cur = min(max(d_cur, 0), n_del);
@@ -257,6 +332,19 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
     };
     load_entry(add_col, add_ext, n_add, a_cur + lane, true, pa_col, pa_lo, pa_hi);
     load_entry(del_col, del_ext, n_del, d_cur + lane, true, pd_col, pd_lo, pd_hi);
+    // ... and the same for the value updates, each with its value
+    int pu_col = 0, pu_lo = kNone, pu_hi = kNone;
+    float pu_val = 0.0f;
+    auto load_update = [&](int j, bool want) {
+        if (want && j < n_upd) {
+            pu_col = upd_col[j];
+            const int2 x = upd_ext[j];
+            pu_lo = x.x;
+            pu_hi = x.y;
+            pu_val = upd_val[j];
+        }
+    };
+    if (UPDATES) load_update(u_cur + lane, true);
 
     for (int e = e_begin; e < e_end; e += kSub) {
         const int e_stop = min(e + kSub, e_end);
@@ -304,6 +392,48 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
             d_got = strike(d_cur + lane);
         }
         d_cur += d_got;
+        // ---- value updates: leave the new value at the old entry.  An entry is done with once its place in A_prev's
+        // order lies before the end of this sub-tile, whether something is stored there or not.
+        if (UPDATES) {
+            auto touch = [&](int j) {
+                bool done = false;
+                if (j < n_upd && pu_lo < e_stop) {
+                    const int lo = max(pu_lo - e, 0), hi = min(pu_hi - e, cnt);
+                    const int p = lo < hi ? lds_bound<false>(s_col, lo, hi, pu_col) : hi;
+                    if (p < hi) {
+                        done = true;
+                        if (s_col[p] == pu_col) {
+                            s_newval[p] = pu_val;
+                            atomicOr(&s_mark[p], 2);
+                        }
+                    } else {
+                        done = pu_hi <= e_stop;        // beyond the sub-tile's part of an unfinished row: later
+                    }
+                }
+                return __popcll(__ballot(done));
+            };
+            int u_got = touch(u_cur + lane);
+#pragma unroll 1
+            while (u_got == kWave) {
+                u_cur += kWave;
+                pu_lo = pu_hi = kNone;
+                load_update(u_cur + lane, true);
+                __builtin_amdgcn_s_waitcnt(kVmcntZero);
+                u_got = touch(u_cur + lane);
+            }
+            u_cur += u_got;
+            const int src = lane + u_got;       // the entries at the new cursor, for the next sub-tile
+            const int c2 = __shfl(pu_col, src & (kWave - 1), kWave);
+            const int lo2 = __shfl(pu_lo, src & (kWave - 1), kWave);
+            const int hi2 = __shfl(pu_hi, src & (kWave - 1), kWave);
+            const float v2 = __shfl(pu_val, src & (kWave - 1), kWave);
+            const bool fresh = src >= kWave;
+            pu_col = c2;
+            pu_val = v2;
+            pu_lo = fresh ? kNone : lo2;
+            pu_hi = fresh ? kNone : hi2;
+            load_update(u_cur + lane, fresh);
+        }
         // ---- added entries: count at the slot (old entry they precede; a row's end if none)
         const int a_tile = a_cur;
         auto slot = [&](int j, int &q) {
@@ -313,7 +443,7 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
                 const int lo = max(pa_lo - e, 0), hi = min(pa_hi - e, cnt);
                 q = lds_bound<true>(s_col, lo, hi, pa_col);
                 owned = q < hi || pa_hi <= e_stop;         // beyond the sub-tile's part of an unfinished row: later
-                if (owned) atomicAdd(&s_mark[q], 2);
+                if (owned) atomicAdd(&s_mark[q], 4);
             }
             if (!owned) q = -2 - lane;
             return __popcll(__ballot(owned));
@@ -346,7 +476,7 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
                 const int p = lane * kPerLane + j;
                 mk[j] = s_mark[p];
                 alive += (p < cnt && !(mk[j] & 1)) ? 1 : 0;
-                ins += mk[j] >> 1;
+                ins += mk[j] >> 2;
             }
             const int inc_alive = wave_scan_add(alive, lane), inc_ins = wave_scan_add(ins, lane);
             int run = (inc_alive - alive) + (inc_ins - ins);
@@ -354,10 +484,10 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
             for (int j = 0; j < kPerLane; ++j) {
                 const int p = lane * kPerLane + j;
                 s_start[p] = run;
-                run += ((p < cnt && !(mk[j] & 1)) ? 1 : 0) + (mk[j] >> 1);
+                run += ((p < cnt && !(mk[j] & 1)) ? 1 : 0) + (mk[j] >> 2);
             }
             if (lane == kWave - 1) s_start[kSub] = run;   // slot "after the last entry" of a full sub-tile
-            written = __shfl(run, kWave - 1, kWave) + (s_mark[kSub] >> 1);
+            written = __shfl(run, kWave - 1, kWave) + (s_mark[kSub] >> 2);
         }
         __syncthreads();
 
@@ -367,10 +497,10 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
             const int p = lane + j * kWave;
             if (p < cnt) {
                 const int mk = s_mark[p];
-                const unsigned pos = (unsigned)(base + s_start[p] + (mk >> 1));
+                const unsigned pos = (unsigned)(base + s_start[p] + (mk >> 2));
                 if (!(mk & 1) && pos < (unsigned)cap_next) {
                     colidx_next[pos] = c_[j];
-                    if (VALUES) val_next[pos] = v_[j];
+                    if (VALUES) val_next[pos] = (UPDATES && (mk & 2)) ? s_newval[p] : v_[j];
                 }
             }
         }
@@ -415,8 +545,8 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
     }
 }
 
-// Surviving entries whose value changes: one thread per listed entry finds it in its (new) row and overwrites
-// the value.  Entries that are not there are skipped.
+// Surviving entries whose value changes, for an update list in no particular order: one thread per listed entry
+// finds it in its (new) row and overwrites the value.  Entries that are not there are skipped.
 __global__ __launch_bounds__(256) void update_values_kernel(int n, const int32_t *__restrict__ rowptr,
                                                             const int32_t *__restrict__ colidx,
                                                             const int32_t *__restrict__ upd_row,
@@ -484,6 +614,19 @@ __global__ __launch_bounds__(256) void csr_validate_kernel(int n, const int32_t 
         prev = c;
     }
     if (require_diagonal && !diagonal) report(status, DGNN_BAD_NO_DIAGONAL);
+}
+
+// One thread per entry of a value-update list that is declared sorted: indices in range, strictly ascending by (row, col).
+__global__ __launch_bounds__(256) void validate_updates_kernel(int n, const int32_t *__restrict__ upd_row,
+                                                               const int32_t *__restrict__ upd_col, int n_upd, int32_t *status) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= n_upd) return;
+    const int r = upd_row[j], c = upd_col[j];
+    if (r < 0 || r >= n || c < 0 || c >= n) { report(status, DGNN_BAD_INDEX_RANGE); return; }
+    if (j > 0) {
+        const int pr = upd_row[j - 1], pc = upd_col[j - 1];
+        if (pr > r || (pr == r && pc >= c)) report(status, DGNN_BAD_DELTA_ORDER);
+    }
 }
 
 __global__ __launch_bounds__(64) void reset_status_kernel(int32_t *status) { *status = 0; }
@@ -567,14 +710,20 @@ int64_t max_ranges(int64_t nnz_prev) { return std::max<int64_t>(kTargetWaves + 1
 
 }  // namespace
 
-extern "C" int dgnn_delta_rebuild_workspace(int64_t n, int64_t nnz_prev, int64_t n_add, int64_t n_del, size_t *bytes) {
+extern "C" int dgnn_delta_rebuild_weighted_workspace(int64_t n, int64_t nnz_prev, int64_t n_add, int64_t n_del, int64_t n_upd,
+                                                     size_t *bytes) {
     if (!bytes) return DGNN_ERR_NULL;
-    if (n <= 0 || nnz_prev < 0 || n_add < 0 || n_del < 0) return DGNN_ERR_SHAPE;
-    if (!fits_index(n + 1) || !fits_index(nnz_prev + n_add)) return DGNN_ERR_OVERFLOW;
+    if (n <= 0 || nnz_prev < 0 || n_add < 0 || n_del < 0 || n_upd < 0) return DGNN_ERR_SHAPE;
+    if (!fits_index(n + 1) || !fits_index(nnz_prev + n_add) || !fits_index(n_upd)) return DGNN_ERR_OVERFLOW;
     *bytes = round_up((size_t)max_ranges(nnz_prev) * sizeof(RangeStart), 256)   // the row every range of the merge begins in
              + round_up((size_t)n_add * sizeof(int2), 256)         // row extents of the added entries
-             + round_up((size_t)n_del * sizeof(int2), 256);        // ... of the deleted entries
+             + round_up((size_t)n_del * sizeof(int2), 256)         // ... of the deleted entries
+             + round_up((size_t)n_upd * sizeof(int2), 256);        // ... of the value updates the merge consumes
     return DGNN_OK;
+}
+
+extern "C" int dgnn_delta_rebuild_workspace(int64_t n, int64_t nnz_prev, int64_t n_add, int64_t n_del, size_t *bytes) {
+    return dgnn_delta_rebuild_weighted_workspace(n, nnz_prev, n_add, n_del, 0, bytes);
 }
 
 namespace {
@@ -583,6 +732,11 @@ struct Values {
     const float *prev;
     const float *add;
     float *next;
+    // value updates the merge consumes (sorted by (row, col)); n_upd = 0: none
+    const int32_t *upd_row;
+    const int32_t *upd_col;
+    const float *upd_val;
+    int64_t n_upd;
 };
 
 int rebuild(int64_t n, const int32_t *rowptr_prev, const int32_t *colidx_prev, int64_t nnz_prev,
@@ -595,13 +749,14 @@ int rebuild(int64_t n, const int32_t *rowptr_prev, const int32_t *colidx_prev, i
     if (n_add > 0 && (!add_row || !add_col)) return DGNN_ERR_NULL;
     if (n_del > 0 && (!del_row || !del_col)) return DGNN_ERR_NULL;
     if (vals && (!vals->prev || !vals->next || (n_add > 0 && !vals->add))) return DGNN_ERR_NULL;
-    if (n <= 0 || nnz_prev <= 0 || (flags & ~DGNN_VALIDATE)) return DGNN_ERR_SHAPE;
+    if (n <= 0 || nnz_prev <= 0 || (flags & ~(vals ? DGNN_VALIDATE | DGNN_UPDATES_SORTED : DGNN_VALIDATE))) return DGNN_ERR_SHAPE;
     if (!fits_index(n + 1) || !fits_index(nnz_prev + n_add)) return DGNN_ERR_OVERFLOW;
     const int64_t nnz_new = nnz_prev + n_add - n_del;
     if (nnz_new < 0) return DGNN_ERR_SHAPE;
     if (cap_next < nnz_new) return DGNN_ERR_CAPACITY;
+    const int64_t n_upd = vals ? vals->n_upd : 0;
     size_t need = 0;
-    int rc = dgnn_delta_rebuild_workspace(n, nnz_prev, n_add, n_del, &need);
+    int rc = dgnn_delta_rebuild_weighted_workspace(n, nnz_prev, n_add, n_del, n_upd, &need);
     if (rc != DGNN_OK) return rc;
     if (ws_bytes < need) return DGNN_ERR_CAPACITY;
     if (rowptr_next == rowptr_prev || colidx_next == colidx_prev) return DGNN_ERR_ALIAS;
@@ -613,12 +768,14 @@ int rebuild(int64_t n, const int32_t *rowptr_prev, const int32_t *colidx_prev, i
     RangeStart *range_start = reinterpret_cast<RangeStart *>(wsb);
     int2 *add_ext = reinterpret_cast<int2 *>(wsb + round_up((size_t)max_ranges(nnz_prev) * sizeof(RangeStart), 256));
     int2 *del_ext = reinterpret_cast<int2 *>(reinterpret_cast<char *>(add_ext) + round_up((size_t)n_add * sizeof(int2), 256));
+    int2 *upd_ext = reinterpret_cast<int2 *>(reinterpret_cast<char *>(del_ext) + round_up((size_t)n_del * sizeof(int2), 256));
     const int cap = (int)min(cap_next, (int64_t)2147483647LL);
     const int64_t range_len = merge_range_length(nnz_prev);
 
     hipLaunchKernelGGL(rowptr_kernel, dim3((unsigned)((n + kRowTile - 1) / kRowTile)), dim3(kRowThreads), 0, s,
                        (int)n, rowptr_prev, add_row, (int)n_add, del_row, (int)n_del, rowptr_next,
-                       dinv_next, add_ext, del_ext, (int)range_len, (int)((nnz_prev + range_len - 1) / range_len), range_start, d_status);
+                       dinv_next, add_ext, del_ext, (int)range_len, (int)((nnz_prev + range_len - 1) / range_len), range_start,
+                       n_upd > 0 ? vals->upd_row : nullptr, (int)n_upd, upd_ext, d_status);
     DGNN_RETURN_IF_LAUNCH_FAILED();
     if ((flags & DGNN_VALIDATE) && d_status) {
         int64_t work = n_add + n_del + n;
@@ -626,16 +783,26 @@ int rebuild(int64_t n, const int32_t *rowptr_prev, const int32_t *colidx_prev, i
                            (int)n, rowptr_prev, colidx_prev, add_row, add_col, (int)n_add, del_row, del_col,
                            (int)n_del, d_status);
         DGNN_RETURN_IF_LAUNCH_FAILED();
+        if (n_upd > 0) {
+            hipLaunchKernelGGL(validate_updates_kernel, dim3((unsigned)((n_upd + 255) / 256)), dim3(256), 0, s, (int)n, vals->upd_row,
+                               vals->upd_col, (int)n_upd, d_status);
+            DGNN_RETURN_IF_LAUNCH_FAILED();
+        }
     }
     const dim3 grid((unsigned)((nnz_prev + range_len - 1) / range_len));
-    if (vals)
-        hipLaunchKernelGGL(merge_kernel<true>, grid, dim3(kWave), 0, s, colidx_prev, (int)nnz_prev,
+    if (vals && n_upd > 0)
+        hipLaunchKernelGGL((merge_kernel<true, true>), grid, dim3(kWave), 0, s, colidx_prev, (int)nnz_prev,
                            (int)range_len, add_col, add_ext, (int)n_add, del_col, del_ext, (int)n_del,
-                           range_start, colidx_next, cap, vals->prev, vals->add, vals->next);
+                           range_start, colidx_next, cap, vals->prev, vals->add, vals->next, vals->upd_col, upd_ext, vals->upd_val,
+                           (int)n_upd);
+    else if (vals)
+        hipLaunchKernelGGL((merge_kernel<true, false>), grid, dim3(kWave), 0, s, colidx_prev, (int)nnz_prev,
+                           (int)range_len, add_col, add_ext, (int)n_add, del_col, del_ext, (int)n_del,
+                           range_start, colidx_next, cap, vals->prev, vals->add, vals->next, nullptr, nullptr, nullptr, 0);
     else
-        hipLaunchKernelGGL(merge_kernel<false>, grid, dim3(kWave), 0, s, colidx_prev, (int)nnz_prev,
+        hipLaunchKernelGGL((merge_kernel<false, false>), grid, dim3(kWave), 0, s, colidx_prev, (int)nnz_prev,
                            (int)range_len, add_col, add_ext, (int)n_add, del_col, del_ext, (int)n_del,
-                           range_start, colidx_next, cap, nullptr, nullptr, nullptr);
+                           range_start, colidx_next, cap, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0);
     DGNN_RETURN_IF_LAUNCH_FAILED();
     return DGNN_OK;
 }
@@ -665,10 +832,11 @@ extern "C" int dgnn_delta_rebuild_weighted(int64_t n,
     if (n_upd < 0) return DGNN_ERR_SHAPE;
     if (n_upd > 0 && (!upd_row || !upd_col || !upd_val)) return DGNN_ERR_NULL;
     if (!fits_index(n_upd)) return DGNN_ERR_OVERFLOW;
-    const Values vals{val_prev, add_val, val_next};
+    const bool folded = (flags & DGNN_UPDATES_SORTED) && n_upd > 0;      // the merge takes the updates itself
+    const Values vals{val_prev, add_val, val_next, upd_row, upd_col, upd_val, folded ? n_upd : 0};
     const int rc = rebuild(n, rowptr_prev, colidx_prev, nnz_prev, add_row, add_col, n_add, del_row, del_col, n_del,
                            rowptr_next, colidx_next, cap_next, nnz_next, nullptr, &vals, ws, ws_bytes, flags, d_status, stream);
-    if (rc != DGNN_OK || n_upd == 0) return rc;
+    if (rc != DGNN_OK || n_upd == 0 || folded) return rc;
     hipLaunchKernelGGL(update_values_kernel, dim3((unsigned)((n_upd + 255) / 256)), dim3(256), 0, (hipStream_t)stream, (int)n,
                        rowptr_next, colidx_next, upd_row, upd_col, upd_val, (int)n_upd, val_next);
     DGNN_RETURN_IF_LAUNCH_FAILED();

@@ -18,24 +18,33 @@ def dev(a, dtype):
     return torch.as_tensor(np.ascontiguousarray(a), dtype=dtype).to(DEV)
 
 
-def gpu_rebuild_weighted(n, rp, ci, val, add, dele, upd):
-    """add/dele/upd as numpy tuples sorted by (row, col) (upd in any order); returns numpy (rowptr, colidx, val)."""
+def gpu_rebuild_weighted(n, rp, ci, val, add, dele, upd, merged=False, expect_status=0):
+    """add/dele as numpy tuples sorted by (row, col), upd in any order; returns numpy (rowptr, colidx, val).
+    merged: the update list is sorted here and handed over as sorted, so that the streaming merge consumes it."""
     nnz_prev = int(ci.size)
     n_add, n_del = int(add[0].size), int(dele[0].size)
     cap = nnz_prev + n_add - n_del + 5
     rpn = torch.full((n + 1,), -7, dtype=torch.int32, device=DEV)
     cin = torch.full((cap,), -7, dtype=torch.int32, device=DEV)
     vn = torch.full((cap,), float("nan"), dtype=torch.float32, device=DEV)
-    ws = torch.empty(dg.delta_rebuild_workspace(n, nnz_prev, n_add, n_del), dtype=torch.uint8, device=DEV)
+    flags = dg.DGNN_VALIDATE
+    if merged:
+        if expect_status == 0:
+            order = np.lexsort((upd[1], upd[0]))
+            upd = tuple(x[order] for x in upd)
+        flags |= dg.DGNN_UPDATES_SORTED
+        ws = torch.empty(dg.delta_rebuild_weighted_workspace(n, nnz_prev, n_add, n_del, int(upd[0].size)), dtype=torch.uint8, device=DEV)
+    else:
+        ws = torch.empty(dg.delta_rebuild_workspace(n, nnz_prev, n_add, n_del), dtype=torch.uint8, device=DEV)
     status = torch.zeros(1, dtype=torch.int32, device=DEV)
     nnz = dg.delta_rebuild_weighted(
         dev(rp, torch.int32), dev(ci, torch.int32), dev(val, torch.float32), nnz_prev,
         (dev(add[0], torch.int32), dev(add[1], torch.int32), dev(add[2], torch.float32)) if n_add else None,
         (dev(dele[0], torch.int32), dev(dele[1], torch.int32)) if n_del else None,
         (dev(upd[0], torch.int32), dev(upd[1], torch.int32), dev(upd[2], torch.float32)) if upd[0].size else None,
-        rpn, cin, vn, ws, flags=dg.DGNN_VALIDATE, d_status=status)
+        rpn, cin, vn, ws, flags=flags, d_status=status)
     torch.cuda.synchronize()
-    assert int(status.item()) == 0
+    assert int(status.item()) == expect_status
     assert torch.isnan(vn[nnz:]).all() and (cin[nnz:] == -7).all()      # nothing written beyond the result
     return rpn.cpu().numpy(), cin.cpu().numpy()[:nnz], vn.cpu().numpy()[:nnz]
 
@@ -57,8 +66,10 @@ def step_lists(wl_graph, rng, upd_frac):
     return ((ar, ac, f32(rng.uniform(1, 2, ar.size))), (dr, dc), (ur, uc, f32(rng.uniform(3, 4, ur.size))))
 
 
-@pytest.mark.parametrize("name,n,upd_frac", [("c1", 1000, 0.1), ("c3", 1 << 14, 0.05), ("c3", 1 << 14, 0.0), ("c2", 30_000, 0.3)])
-def test_weighted_rebuild_chain(name, n, upd_frac):
+@pytest.mark.parametrize("merged", [False, True])
+@pytest.mark.parametrize("name,n,upd_frac", [("c1", 1000, 0.1), ("c3", 1 << 14, 0.05), ("c3", 1 << 14, 0.0), ("c2", 30_000, 0.3),
+                                             ("c3", 1 << 14, 0.7), ("c2", 30_000, 1.0)])
+def test_weighted_rebuild_chain(name, n, upd_frac, merged):
     wl = WORKLOADS[name].scaled(n, T=5) if n != WORKLOADS[name].n else WORKLOADS[name]
     g = DynamicGraph(wl)
     rng = np.random.default_rng(n)
@@ -67,10 +78,60 @@ def test_weighted_rebuild_chain(name, n, upd_frac):
     for t in range(2, 6):
         add, dele, upd = step_lists(g, rng, upd_frac)
         want = oracle.delta_apply_weighted(wl.n, rp, ci, val, add=add, dele=dele, upd=upd)
-        got = gpu_rebuild_weighted(wl.n, rp, ci, val, add, dele, upd)
+        got = gpu_rebuild_weighted(wl.n, rp, ci, val, add, dele, upd, merged=merged)
         assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1]), (name, t)
         assert np.array_equal(got[2], f32(want[2])), (name, t)                 # values are carried, not computed
         rp, ci, val = got
+
+
+def test_weighted_rebuild_hub_rows_and_absent_updates():
+    """Rows longer than a range of the merge (its wavefronts then begin in the middle of a row and have to find their
+    place in the row's updates), with updates that name edges which are not stored (before, between and after a
+    row's entries) or which the same step deletes: they change nothing."""
+    n = 4096
+    rng = np.random.default_rng(77)
+    rows, cols = [np.arange(n)], [np.arange(n)]
+    for hub, deg in ((5, 3000), (6, 1200), (4000, 4000)):
+        rows.append(np.full(deg, hub)); cols.append(rng.choice(n, deg, replace=False))
+    rows.append(rng.integers(0, n, 20000)); cols.append(rng.integers(0, n, 20000))
+    rp, ci = oracle.csr_from_edges(n, np.concatenate(rows).astype(np.int32), np.concatenate(cols).astype(np.int32))
+    val = f32(rng.uniform(0.1, 1.0, ci.size))
+    r_of = np.repeat(np.arange(n, dtype=np.int32), np.diff(rp))
+    off = np.flatnonzero(r_of != ci)
+    dele_pos = np.sort(rng.choice(off, off.size // 10, replace=False))
+    dele = (r_of[dele_pos], ci[dele_pos])
+    stored = set(zip(r_of.tolist(), ci.tolist()))
+    add_pairs = sorted({(int(r), int(c)) for r, c in zip(rng.choice([5, 6, 4000, 17, 99], 3000), rng.integers(0, n, 3000))
+                        if (int(r), int(c)) not in stored and r != c})
+    add = (np.array([p[0] for p in add_pairs], np.int32), np.array([p[1] for p in add_pairs], np.int32), f32(rng.uniform(1, 2, len(add_pairs))))
+    # updates: 40 % of the stored entries (the deleted ones among them), and as many pairs drawn blindly
+    some = rng.choice(ci.size, int(0.4 * ci.size), replace=False)
+    blind_r = np.concatenate([rng.integers(0, n, 5000), np.full(5000, 5), np.full(5000, 4000)]).astype(np.int32)
+    blind_c = rng.integers(0, n, blind_r.size).astype(np.int32)
+    pairs = np.unique(np.concatenate([(r_of[some].astype(np.int64) << 32) | ci[some], (blind_r.astype(np.int64) << 32) | blind_c]))
+    added = (add[0].astype(np.int64) << 32) | add[1]
+    pairs = rng.permutation(pairs[~np.isin(pairs, added)])
+    upd = ((pairs >> 32).astype(np.int32), (pairs & 0xffffffff).astype(np.int32), f32(rng.uniform(3, 4, pairs.size)))
+    want = oracle.delta_apply_weighted(n, rp, ci, val, add=add, dele=dele, upd=upd)
+    for merged in (False, True):
+        got = gpu_rebuild_weighted(n, rp, ci, val, add, dele, upd, merged=merged)
+        assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1]), merged
+        assert np.array_equal(got[2], f32(want[2])), merged
+
+
+def test_weighted_rebuild_reports_an_unsorted_update_list():
+    """Declared sorted, but not: the check says so, and nothing is written outside the result."""
+    wl = WORKLOADS["c1"]
+    g = DynamicGraph(wl)
+    rng = np.random.default_rng(5)
+    rp, ci = (x.numpy() for x in g.csr())
+    val = f32(rng.uniform(0.1, 1.0, ci.size))
+    add, dele, upd = step_lists(g, rng, 0.3)
+    order = np.lexsort((upd[1], upd[0]))[::-1]
+    upd = tuple(np.ascontiguousarray(x[order]) for x in upd)
+    want = oracle.delta_apply_weighted(wl.n, rp, ci, val, add=add, dele=dele, upd=upd)
+    got = gpu_rebuild_weighted(wl.n, rp, ci, val, add, dele, upd, merged=True, expect_status=2)
+    assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1])      # the structure does not depend on the updates
 
 
 def test_weighted_rebuild_edge_cases():
@@ -91,9 +152,10 @@ def test_weighted_rebuild_edge_cases():
     }
     for name, (add, dele, upd) in cases.items():
         want = oracle.delta_apply_weighted(n, rp, ci, val, add=add, dele=dele, upd=upd)
-        got = gpu_rebuild_weighted(n, rp, ci, val, add, dele, upd)
-        assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1]), name
-        assert np.array_equal(got[2], f32(want[2])), name
+        for merged in (False, True):
+            got = gpu_rebuild_weighted(n, rp, ci, val, add, dele, upd, merged=merged)
+            assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1]), (name, merged)
+            assert np.array_equal(got[2], f32(want[2])), (name, merged)
 
 
 @pytest.mark.parametrize("dtype,f", [(torch.float32, 16), (torch.float32, 32), (torch.float32, 128), (torch.bfloat16, 64),
@@ -121,9 +183,10 @@ def test_weighted_spmm(dtype, f, relu):
         assert_close(to_f64(z), oracle.spmm(rp, ci, to_f64(h)), dtype, "Eqn (1) values shipped whole")
 
 
+@pytest.mark.parametrize("merged", [False, True])
 @pytest.mark.parametrize("name,n,life,mode", [("c1", 1000, 3, "edge_life"), ("c3", 1 << 13, 4, "edge_life"),
                                               ("c3", 1 << 13, 3, "mproduct"), ("c2", 20_000, 2, "mproduct")])
-def test_smoothed_series_through_the_weighted_path(name, n, life, mode):
+def test_smoothed_series_through_the_weighted_path(name, n, life, mode, merged):
     """The smoothed graphs the paper's models are trained on (sum of the raw snapshots of the last `life`
     timesteps), carried from step to step by weighted differences.  The expected snapshots are built here from
     the raw oracle snapshots with numpy, not from the lists."""
@@ -144,7 +207,7 @@ def test_smoothed_series_through_the_weighted_path(name, n, life, mode):
         want_val = f32(counts) / (np.float32(min(life, t)) if mode == "mproduct" else np.float32(1))
         add, dele, upd = sm.advance()
         add, dele, upd = tuple(x.numpy() for x in add), tuple(x.numpy() for x in dele), tuple(x.numpy() for x in upd)
-        g_rp, g_ci, g_val = gpu_rebuild_weighted(wl.n, g_rp, g_ci, g_val, add, dele, upd)
+        g_rp, g_ci, g_val = gpu_rebuild_weighted(wl.n, g_rp, g_ci, g_val, add, dele, upd, merged=merged)
         got_keys = (np.repeat(np.arange(wl.n, dtype=np.int64), np.diff(g_rp)) << 32) | g_ci.astype(np.int64)
         assert np.array_equal(got_keys, keys), (name, t)
         assert np.array_equal(g_val, want_val), (name, t)
