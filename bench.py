@@ -260,7 +260,7 @@ def weighted_step(args, wl, blk, dev):
     rpn = torch.empty(n + 1, dtype=torch.int32, device=dev)
     cin = torch.empty(cap, dtype=torch.int32, device=dev)
     vn = torch.empty(cap, dtype=torch.float32, device=dev)
-    ws_r = torch.empty(dg.delta_rebuild_weighted_workspace(n, nnz1, ar.numel(), dr.numel(), ur.numel()), dtype=torch.uint8, device=dev)
+    ws_r = torch.empty(dg.delta_rebuild_workspace(n, nnz1, ar.numel(), dr.numel()), dtype=torch.uint8, device=dev)
     ws_s = torch.empty(dg.spmm_workspace(n, cap, f), dtype=torch.uint8, device=dev)
     h, z = blk.x[1], torch.empty_like(blk.x[1])
 

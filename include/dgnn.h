@@ -96,12 +96,10 @@ int dgnn_delta_h2d(const int32_t *h_add_row, const int32_t *h_add_col, int64_t n
                    int32_t *d_add_row, int32_t *d_add_col, int32_t *d_del_row, int32_t *d_del_col,
                    void *stream);
 
-/* Workspace size of dgnn_delta_rebuild in bytes (HOST out-parameter): 8 (n_add + n_del) plus 40 per range of 8192
- * stored entries (never fewer than 16386 ranges), rounded up; it grows with each argument, so the size queried for
- * the largest snapshot and the longest lists of a block serves every step.  The second form adds 8 n_upd for a
- * weighted rebuild that is given a sorted value-update list (DGNN_UPDATES_SORTED). */
+/* Workspace size of dgnn_delta_rebuild and dgnn_delta_rebuild_weighted in bytes (HOST out-parameter): 40 per range of
+ * 8192 stored entries (never fewer than 16386 ranges), rounded up; it grows with nnz_prev only, so the size queried
+ * for the largest snapshot of a block serves every step. */
 int dgnn_delta_rebuild_workspace(int64_t n, int64_t nnz_prev, int64_t n_add, int64_t n_del, size_t *bytes);
-int dgnn_delta_rebuild_weighted_workspace(int64_t n, int64_t nnz_prev, int64_t n_add, int64_t n_del, int64_t n_upd, size_t *bytes);
 
 /*
  * On-GPU reconstruction of a snapshot (same section): with A_prev on the device,
@@ -215,12 +213,11 @@ int dgnn_mproduct(const void *z, void *y, int64_t T, int64_t n, int32_t f, int32
  *                                               are skipped)
  *   flags                                       DGNN_VALIDATE and/or DGNN_UPDATES_SORTED.  Without the latter the
  *                                               update list may come in any order and is applied by a pass of its
- *                                               own after the merge (workspace: dgnn_delta_rebuild_workspace).  With
+ *                                               own after the merge.  With
  *                                               it the list is sorted by (row, col) like the other two and the one
- *                                               streaming merge consumes it as well (workspace:
- *                                               dgnn_delta_rebuild_weighted_workspace with this n_upd); a list that
- *                                               is not sorted then gives unspecified values, never an out-of-bounds
- *                                               access, and DGNN_VALIDATE reports DGNN_BAD_DELTA_ORDER for it.
+ *                                               streaming merge consumes it as well; a list that is not sorted
+ *                                               then gives unspecified values, never an out-of-bounds access, and
+ *                                               DGNN_VALIDATE reports DGNN_BAD_DELTA_ORDER for it.
  * No dinv is produced: the values are the matrix.  Everything else as dgnn_delta_rebuild.
  */
 int dgnn_delta_rebuild_weighted(int64_t n,

@@ -14,7 +14,7 @@ from .binding import (  # noqa: F401
     mproduct_backward, mproduct_block, mproduct_backward_block, relu_backward, weight_grad, weight_grad_workspace,
     input_grad, csr_transpose, coo_transpose,
     # snapshots that carry values; smoothing on the device
-    delta_rebuild_weighted, delta_rebuild_weighted_workspace, spmm_weighted, csr_weighted_dinv, csr_weighted_dinv_workspace, csr_combine,
+    delta_rebuild_weighted, spmm_weighted, csr_weighted_dinv, csr_weighted_dinv_workspace, csr_combine,
     csr_combine_workspace,
     # CD-GCN layer and the LSTM over weights
     concat_relu, lstm_cell, lstm_step, lstm_step_supported, lstm_cell_backward, lstm_step_backward,

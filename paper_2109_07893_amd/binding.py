@@ -23,7 +23,7 @@ DGNN_RELU = 1
 DGNN_H_PRESCALED = 2
 
 EXPORTS = (
-    "dgnn_strerror", "dgnn_csr_validate", "dgnn_csr_dinv", "dgnn_delta_h2d", "dgnn_delta_rebuild_workspace", "dgnn_delta_rebuild_weighted_workspace",
+    "dgnn_strerror", "dgnn_csr_validate", "dgnn_csr_dinv", "dgnn_delta_h2d", "dgnn_delta_rebuild_workspace",
     "dgnn_delta_rebuild", "dgnn_feature_transform", "dgnn_spmm_workspace", "dgnn_spmm", "dgnn_spmm_static_limit",
     "dgnn_spmm_static", "dgnn_mproduct",
     "dgnn_delta_rebuild_weighted", "dgnn_spmm_weighted", "dgnn_csr_combine_workspace", "dgnn_csr_combine", "dgnn_csr_weighted_dinv_workspace", "dgnn_csr_weighted_dinv", "dgnn_concat_relu", "dgnn_lstm_cell", "dgnn_lstm_step", "dgnn_lstm_cell_backward", "dgnn_lstm_step_backward", "dgnn_concat_relu_backward", "dgnn_bias_grad_workspace", "dgnn_bias_grad", "dgnn_add",
@@ -94,7 +94,6 @@ def load_library():
     lib.dgnn_csr_dinv.argtypes = [_i64, _vp, _vp, _vp]
     lib.dgnn_delta_h2d.argtypes = [_vp, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _vp, _vp, _vp]
     lib.dgnn_delta_rebuild_workspace.argtypes = [_i64, _i64, _i64, _i64, ctypes.POINTER(_sz)]
-    lib.dgnn_delta_rebuild_weighted_workspace.argtypes = [_i64, _i64, _i64, _i64, _i64, ctypes.POINTER(_sz)]
     lib.dgnn_delta_rebuild.argtypes = [_i64, _vp, _vp, _i64, _vp, _vp, _i64, _vp, _vp, _i64,
                                        _vp, _vp, _i64, ctypes.POINTER(_i64), _vp, _vp, _sz, _u32, _vp, _vp]
     lib.dgnn_feature_transform.argtypes = [_vp, _i64, _i32, _vp, _i32, _vp, _vp, ctypes.c_int, _vp]
@@ -200,13 +199,6 @@ def delta_rebuild_workspace(n: int, nnz_prev: int, n_add: int, n_del: int) -> in
     return int(out.value)
 
 
-def delta_rebuild_weighted_workspace(n: int, nnz_prev: int, n_add: int, n_del: int, n_upd: int) -> int:
-    out = _sz(0)
-    _check(load_library().dgnn_delta_rebuild_weighted_workspace(n, nnz_prev, n_add, n_del, n_upd, ctypes.byref(out)),
-           "dgnn_delta_rebuild_weighted_workspace")
-    return int(out.value)
-
-
 def delta_rebuild(rowptr_prev, colidx_prev, nnz_prev: int, add_row, add_col, n_add: int, del_row, del_col, n_del: int,
                   rowptr_next, colidx_next, dinv_next, ws, flags: int = 0, d_status=None) -> int:
     """A_next = (A_prev minus deleted) plus added; returns nnz of A_next."""
@@ -293,8 +285,7 @@ def mproduct(z: torch.Tensor, y: torch.Tensor, w: int, m_band: Optional[torch.Te
 def delta_rebuild_weighted(rowptr_prev, colidx_prev, val_prev, nnz_prev: int, add, dele, upd,
                            rowptr_next, colidx_next, val_next, ws, flags: int = 0, d_status=None) -> int:
     """Snapshots with values: add = (row, col, val), dele = (row, col), upd = (row, col, val) device tensors
-    (or None); returns nnz of A_next.  flags may hold DGNN_UPDATES_SORTED (upd sorted by (row, col); ws then sized by
-    delta_rebuild_weighted_workspace)."""
+    (or None); returns nnz of A_next.  flags may hold DGNN_UPDATES_SORTED (upd sorted by (row, col): the merge consumes it)."""
     n = rowptr_prev.numel() - 1
     ar, ac, av = add if add is not None else (None, None, None)
     dr, dc = dele if dele is not None else (None, None)

@@ -5,10 +5,9 @@
 // Because both difference lists arrive sorted by (row, col), no global prefix scan is needed:
 //   rowptr_next[r] = rowptr_prev[r] + #added with row < r - #deleted with row < r
 // and "#entries with row < r" is a lower bound in a sorted list.  Every tile is independent:
-//   1. rowptr_kernel  (tiles of rows)         new row pointers, dinv = (row length)^(-1/2),
-//                                             the extent in A_prev of the row of every difference entry, and
-//                                             what the merge has to know about the row in which each of its
-//                                             ranges begins (both for the merge, in the workspace);
+//   1. rowptr_kernel  (tiles of rows)         new row pointers, dinv = (row length)^(-1/2), and what the merge
+//                                             has to know about the row in which each of its ranges begins
+//                                             (in the workspace);
 //   2. merge_kernel   (ranges of old entries) streams A_prev's column indices once: deleted entries
 //      are struck out, added entries slotted in, a prefix sum per sub-tile gives the positions.
 //      Ranges hold equal numbers of old entries, so hub rows of power-law graphs are spread over
@@ -22,7 +21,7 @@ namespace {
 using namespace dgnn;
 
 constexpr int kRowThreads = 256;
-constexpr int kRowsPerThread = 4;
+constexpr int kRowsPerThread = 4;          // rowptr_kernel moves a thread's rows as one 16-byte access: keep at 4
 constexpr int kRowTile = kRowThreads * kRowsPerThread;
 constexpr int kHeavyList = 16 * kRowTile;    // list entries per row tile beyond which counting walks no more
 
@@ -49,16 +48,10 @@ __device__ __forceinline__ void report(int32_t *status, int code) {
 constexpr int kListPerThread = 4;           // consecutive list entries per thread and round of the walk below
 
 // Per-row counts of a sorted row list restricted to [lo, hi), accumulated into LDS counters by
-// run boundaries: the last element of a run adds (j + 1), the first subtracts j.  On the way, where the row of
-// every entry lies in A_prev is written next to the list: ext[j] = (rowptr_prev[row_j], rowptr_prev[row_j + 1]).
-// The merge needs this pair for every entry it places; looked up there, it would be a load that depends on a
-// load in the middle of a stream.  COUNT = false: only the extents (the counts come from searches).
-// s_rp: the tile's row pointers of A_prev (rows r0 .. r0 + nr), staged in LDS.
+// run boundaries: the last element of a run adds (j + 1), the first subtracts j.
 // A thread takes kListPerThread consecutive entries and their two neighbours, all loaded before any is looked at,
 // so that a tile's usual stretch of a list costs one trip to memory.
-template <bool COUNT>
-__device__ __forceinline__ void count_runs(const int32_t *__restrict__ rows, int lo, int hi, int r0, int nr,
-                                           int *cnt, int tid, const int *s_rp, int2 *__restrict__ ext) {
+__device__ __forceinline__ void count_runs(const int32_t *__restrict__ rows, int lo, int hi, int r0, int nr, int *cnt, int tid) {
 #pragma unroll 1
     for (int base = lo; base < hi; base += kRowThreads * kListPerThread) {
         const int j0 = base + tid * kListPerThread;
@@ -73,11 +66,8 @@ __device__ __forceinline__ void count_runs(const int32_t *__restrict__ rows, int
             const int j = j0 + k;
             const unsigned q = (unsigned)(r[k + 1] - r0);
             if (j < hi && q < (unsigned)nr) {
-                if (COUNT) {
-                    if (r[k + 2] != r[k + 1]) atomicAdd(&cnt[q], j + 1);     // last of its run
-                    if (r[k] != r[k + 1]) atomicSub(&cnt[q], j);             // first of its run
-                }
-                ext[j] = make_int2(s_rp[q], s_rp[q + 1]);
+                if (r[k + 2] != r[k + 1]) atomicAdd(&cnt[q], j + 1);     // last of its run
+                if (r[k] != r[k + 1]) atomicSub(&cnt[q], j);             // first of its run
             }
         }
     }
@@ -124,15 +114,16 @@ __device__ __forceinline__ void count_by_search(const int32_t *__restrict__ rows
     }
 }
 
+// VEC: rowptr_prev, rowptr_next and dinv are 16-byte aligned, so a thread moves its four rows with one access each.
+template <bool VEC>
 __global__ __launch_bounds__(kRowThreads) void rowptr_kernel(
     int n, const int32_t *__restrict__ rowptr_prev,
     const int32_t *__restrict__ add_row, int n_add, const int32_t *__restrict__ del_row, int n_del,
     int32_t *__restrict__ rowptr_next, float *__restrict__ dinv,
-    int2 *__restrict__ add_ext, int2 *__restrict__ del_ext, int range_len, int n_ranges, RangeStart *__restrict__ range_start,
-    const int32_t *__restrict__ upd_row, int n_upd, int2 *__restrict__ upd_ext, int32_t *status) {
+    int range_len, int n_ranges, RangeStart *__restrict__ range_start,
+    const int32_t *__restrict__ upd_row, int n_upd, int32_t *status) {
     __shared__ int s_add[kRowTile];
     __shared__ int s_del[kRowTile];
-    __shared__ int s_rp[kRowTile + 1];
     __shared__ int s_bound[6];
     __shared__ int s_wsum[2][kRowThreads / kWave];
 
@@ -141,16 +132,20 @@ __global__ __launch_bounds__(kRowThreads) void rowptr_kernel(
     const int r0 = blockIdx.x * kRowTile;
     const int r1 = min(r0 + kRowTile, n);
     const int nr = r1 - r0;
+    const int r_own = r0 + tid * kRowsPerThread;          // this thread's rows: r_own .. r_own + 3
+    const bool whole = r_own + kRowsPerThread <= n;       // all four exist
 
     if (blockIdx.x == 0 && tid == 0 && status) *status = 0;
-    // the tile's row pointers (r0 + nr <= n), on their way while the searches run
-    int rp_own[kRowsPerThread];
+    // the pointers of the thread's rows and the one after, on their way while the searches run
+    int rp[kRowsPerThread + 1];
+    if (VEC && whole) {
+        const int4 v = *reinterpret_cast<const int4 *>(rowptr_prev + r_own);
+        rp[0] = v.x; rp[1] = v.y; rp[2] = v.z; rp[3] = v.w;
+        rp[4] = rowptr_prev[r_own + kRowsPerThread];
+    } else {
 #pragma unroll
-    for (int k = 0; k < kRowsPerThread; ++k) {
-        const int i = tid + k * kRowThreads;
-        rp_own[k] = i <= nr ? rowptr_prev[r0 + i] : 0;
+        for (int k = 0; k <= kRowsPerThread; ++k) rp[k] = r_own + k <= n ? rowptr_prev[r_own + k] : 0;
     }
-    const int rp_last = (tid == 0 && nr == kRowTile) ? rowptr_prev[r0 + kRowTile] : 0;
     {   // how many list entries have a row below r0 / below r1: one 64-ary search per wavefront and list; the
         // wavefronts that search the added list take the value-update list of a weighted rebuild along
         const int32_t *list = wave < 2 ? add_row : del_row;
@@ -164,22 +159,15 @@ __global__ __launch_bounds__(kRowThreads) void rowptr_kernel(
         }
     }
     for (int i = tid; i < kRowTile; i += kRowThreads) { s_add[i] = 0; s_del[i] = 0; }
-#pragma unroll
-    for (int k = 0; k < kRowsPerThread; ++k) {
-        const int i = tid + k * kRowThreads;
-        if (i <= nr) s_rp[i] = rp_own[k];
-    }
-    if (tid == 0 && nr == kRowTile) s_rp[kRowTile] = rp_last;
     __syncthreads();
     const int a0 = s_bound[0], a1 = s_bound[1], d0 = s_bound[2], d1 = s_bound[3];
+    const int u0 = upd_row ? s_bound[4] : 0, u1 = upd_row ? s_bound[5] : 0;
     // A tile of hub rows can own a very long stretch of a list; walking it would leave the whole chip
     // waiting for this workgroup, so there the counts come from one lower bound per row instead.
-    if (a1 - a0 <= kHeavyList) count_runs<true>(add_row, a0, a1, r0, nr, s_add, tid, s_rp, add_ext);
-    else { count_by_search(add_row, a0, a1, r0, nr, s_add, tid); count_runs<false>(add_row, a0, a1, r0, nr, s_add, tid, s_rp, add_ext); }
-    if (d1 - d0 <= kHeavyList) count_runs<true>(del_row, d0, d1, r0, nr, s_del, tid, s_rp, del_ext);
-    else { count_by_search(del_row, d0, d1, r0, nr, s_del, tid); count_runs<false>(del_row, d0, d1, r0, nr, s_del, tid, s_rp, del_ext); }
-    const int u0 = upd_row ? s_bound[4] : 0, u1 = upd_row ? s_bound[5] : 0;
-    if (upd_row) count_runs<false>(upd_row, u0, u1, r0, nr, nullptr, tid, s_rp, upd_ext);     // extents only: nothing is counted
+    if (a1 - a0 <= kHeavyList) count_runs(add_row, a0, a1, r0, nr, s_add, tid);
+    else count_by_search(add_row, a0, a1, r0, nr, s_add, tid);
+    if (d1 - d0 <= kHeavyList) count_runs(del_row, d0, d1, r0, nr, s_del, tid);
+    else count_by_search(del_row, d0, d1, r0, nr, s_del, tid);
     __syncthreads();
 
     int ca[kRowsPerThread], cd[kRowsPerThread];
@@ -197,26 +185,39 @@ __global__ __launch_bounds__(kRowThreads) void rowptr_kernel(
     int oa = a0 + ia - sa, od = d0 + id - sd;      // exclusive offsets of this thread's first row
     for (int w = 0; w < wave; ++w) { oa += s_wsum[0][w]; od += s_wsum[1][w]; }
 
+    int rn[kRowsPerThread];
+    float dv[kRowsPerThread];
 #pragma unroll
     for (int k = 0; k < kRowsPerThread; ++k) {
-        int r = r0 + tid * kRowsPerThread + k;
+        const int r = r_own + k;
+        const int p = rp[k], q = rp[k + 1];
+        rn[k] = p + oa - od;
+        dv[k] = 1.0f / sqrtf((float)(q - p + ca[k] - cd[k]));
         if (r < r1) {
-            const int rp = s_rp[tid * kRowsPerThread + k], rq = s_rp[tid * kRowsPerThread + k + 1];
-            rowptr_next[r] = rp + oa - od;
-            if (dinv) dinv[r] = 1.0f / sqrtf((float)(rq - rp + ca[k] - cd[k]));
             // ranges of the merge that begin inside this row (few rows hold a multiple of the range length; a hub
             // row several): what the merge needs to know about the row, so that it starts without a search
             int us = -1, ue = 0;
-            for (int g = max((rp + range_len - 1) / range_len, 0); g < n_ranges && (int64_t)g * range_len < rq; ++g) {
+            for (int g = max((p + range_len - 1) / range_len, 0); g < n_ranges && (int64_t)g * range_len < q; ++g) {
                 if (upd_row && us < 0) {      // where the row's value updates lie: two searches inside the tile's stretch
                     us = lower_bound(upd_row, u0, u1, r);
                     ue = lower_bound(upd_row, us, u1, r + 1);
                 }
-                range_start[g] = RangeStart{rp, rq, rp + oa - od, rq + oa + ca[k] - od - cd[k], oa, oa + ca[k], r, max(us, 0), ue, 0};
+                range_start[g] = RangeStart{p, q, p + oa - od, q + oa + ca[k] - od - cd[k], oa, oa + ca[k], r, max(us, 0), ue, 0};
             }
         }
         oa += ca[k];
         od += cd[k];
+    }
+    if (VEC && whole) {
+        *reinterpret_cast<int4 *>(rowptr_next + r_own) = make_int4(rn[0], rn[1], rn[2], rn[3]);
+        if (dinv) *reinterpret_cast<float4 *>(dinv + r_own) = make_float4(dv[0], dv[1], dv[2], dv[3]);
+    } else {
+#pragma unroll
+        for (int k = 0; k < kRowsPerThread; ++k)
+            if (r_own + k < r1) {
+                rowptr_next[r_own + k] = rn[k];
+                if (dinv) dinv[r_own + k] = dv[k];
+            }
     }
     if (r1 == n && tid == 0) rowptr_next[n] = rowptr_prev[n] + n_add - n_del;
 }
@@ -237,12 +238,14 @@ __device__ __forceinline__ int lds_bound(const int *a, int lo, int hi, int key) 
 // needs a search is done per DIFFERENCE entry, of which there are few:
 //   - the sub-tile's column indices are staged in LDS; each deleted entry that falls into the
 //     sub-tile finds its old entry there by binary search and marks it dead, each added entry
-//     finds the old entry it goes in front of (its slot) and counts itself there.  Where the row
-//     of a difference entry lies inside the sub-tile follows from its row's extent in A_prev,
-//     which rowptr_kernel has written next to the lists, so that no load here depends on another;
+//     finds the old entry it goes in front of (its slot) and counts itself there;
+//   - where the row of a difference entry lies inside the sub-tile comes from the row pointers of A_prev, which
+//     the wavefront streams beside the column indices: the pointers of the rows that meet the sub-tile (from the
+//     row that holds its first entry on) are staged in LDS as well, fetched one sub-tile ahead like the column
+//     indices, so a list entry (row, col) looks its row's extent up there and no load depends on another;
 //   - both lists are consumed in order through two cursors, so the lists are never searched
 //     (except once, where a range begins in the middle of a row); where a range's first row lies in A_prev,
-//     in A_next and in the lists comes from rowptr_kernel as well;
+//     in A_next and in the lists comes from rowptr_kernel;
 //   - one prefix sum over (alive, added-before) gives every old entry and every slot its place
 //     relative to the sub-tile's first output position; that position follows from rowptr_next
 //     at the start of the range and simply advances by what each sub-tile wrote.
@@ -254,21 +257,29 @@ __device__ __forceinline__ int lds_bound(const int *a, int lo, int hi, int key) 
 // columns as a deleted entry does and leaves the new value there.  An entry that names nothing stored is passed over.
 template <bool VALUES, bool UPDATES>
 __global__ __launch_bounds__(kWave) void merge_kernel(
-    const int32_t *__restrict__ colidx_prev, int nnz_prev, int range_len,
-    const int32_t *__restrict__ add_col, const int2 *__restrict__ add_ext, int n_add,
-    const int32_t *__restrict__ del_col, const int2 *__restrict__ del_ext, int n_del,
+    int n, const int32_t *__restrict__ rowptr_prev, const int32_t *__restrict__ colidx_prev, int nnz_prev, int range_len,
+    const int32_t *__restrict__ add_row, const int32_t *__restrict__ add_col, int n_add,
+    const int32_t *__restrict__ del_row, const int32_t *__restrict__ del_col, int n_del,
     const RangeStart *__restrict__ range_start,
     int32_t *__restrict__ colidx_next, int cap_next,
     const float *__restrict__ val_prev, const float *__restrict__ add_val, float *__restrict__ val_next,
-    const int32_t *__restrict__ upd_col, const int2 *__restrict__ upd_ext, const float *__restrict__ upd_val, int n_upd) {
+    const int32_t *__restrict__ upd_row, const int32_t *__restrict__ upd_col, const float *__restrict__ upd_val, int n_upd) {
+    constexpr int kWindow = 2 * kWave + 1;  // row pointers fetched ahead for every sub-tile; more are fetched when rows are short
+    constexpr int kMaxWindow = kSub + kWave;
     __shared__ int s_col[kSub];
     __shared__ int s_mark[kSub + kWave];    // bit 0: deleted; bit 1: new value in s_newval; bits 2..: added entries that go right before this slot
-    __shared__ int s_start[kSub + kWave];   // outputs (kept + added) that precede the slot's block
+    // Until the prefix sums are taken: s_rows[k] = rowptr_prev[first_row + k], the rows that meet the sub-tile.
+    // From then on: s_start[p] = outputs (kept + added) that precede slot p's block.
+    __shared__ int s_shared[kMaxWindow];
     __shared__ float s_newval[UPDATES ? kSub : 1];
+    int *const s_rows = s_shared;
+    int *const s_start = s_shared;
+    static_assert(kMaxWindow >= kWindow + kWave, "the window must be able to grow");
 
     const int lane = threadIdx.x;
     const int e_begin = (int)((int64_t)blockIdx.x * range_len);
     const int e_end = (int)min((int64_t)e_begin + range_len, (int64_t)nnz_prev);
+    constexpr int kNone = 0x7fffffff;    // a pointer "beyond everything"
 
     int c_next[kPerLane];
     float v_next[VALUES ? kPerLane : 1];
@@ -283,13 +294,23 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
     int a_cur, d_cur;   // first added / deleted entry not yet placed
     int u_cur = 0;      // first value update not yet looked at
     int base;           // output position of the next entry to be written
+    int first_row;      // the row that holds the sub-tile's first entry
+    // the pointers of rows first_row + lane, first_row + 64 + lane and (lane 0) first_row + 128, for the next sub-tile
+    int w0 = kNone, w1 = kNone, w2 = kNone;
+    auto fetch_window = [&](int row) {
+        w0 = row + lane <= n ? rowptr_prev[row + lane] : kNone;
+        w1 = row + kWave + lane <= n ? rowptr_prev[row + kWave + lane] : kNone;
+        w2 = (lane == 0 && row + 2 * kWave <= n) ? rowptr_prev[row + 2 * kWave] : kNone;
+    };
     {
         const RangeStart st = range_start[blockIdx.x];                     // the row that holds entry e_begin
         const int rp = st.rp, rp1 = st.rp1, rn = st.rn, rn1 = st.rn1, as = st.as, ae = st.ae;
         const int ds = rp + as - rn, de = rp1 + ae - rn1;
+        first_row = min(max(st.row, 0), n - 1);
+        fetch_window(first_row);
         a_cur = as;
         d_cur = ds;
-        if (rp < e_begin) {   // the range begins inside row k0: skip what earlier ranges place
+        if (rp < e_begin) {   // the range begins inside the row: skip what earlier ranges place
             if (as >= 0 && as < ae && ae <= n_add) a_cur = lower_bound(add_col, as, ae, colidx_prev[e_begin - 1]);
             if (ds >= 0 && ds < de && de <= n_del) d_cur = lower_bound(del_col, ds, de, colidx_prev[e_begin]);
         }
@@ -302,45 +323,36 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
         d_cur = min(max(d_cur, 0), n_del);
         base = rn + (e_begin - rp) - (d_cur - ds) + (a_cur - as);
     }
-    // The 64 list entries at each cursor (column, and where the entry's row lies in A_prev) are held in
-    // registers ahead of use.  A sub-tile consumes only some of them: the rest slide down to lane 0 and only
-    // the freed lanes load, without anyone waiting for those loads before the next sub-tile needs them.
-    constexpr int kNone = 0x7fffffff;    // "row begins beyond everything": the entry is not owned
+    // The 64 list entries at each cursor (row, column) are held in registers ahead of use.  A sub-tile consumes only
+    // some of them: the rest slide down to lane 0 and only the freed lanes load, without anyone waiting for those
+    // loads before the next sub-tile needs them.  An entry that does not exist has row kNone.
     constexpr int kVmcntZero = 0x0F70;   // s_waitcnt operand: every vector memory load has returned, other counters untouched
-    int pa_col = 0, pa_lo = kNone, pa_hi = kNone, pd_col = 0, pd_lo = kNone, pd_hi = kNone;
-    auto load_entry = [&](const int32_t *__restrict__ cols, const int2 *__restrict__ ext, int len, int j, bool want,
-                          int &c, int &lo, int &hi) {
+    int pa_row = kNone, pa_col = 0, pd_row = kNone, pd_col = 0;
+    auto load_entry = [&](const int32_t *__restrict__ rows, const int32_t *__restrict__ cols, int len, int j, bool want, int &r, int &c) {
         if (want && j < len) {
+            r = rows[j];
             c = cols[j];
-            const int2 x = ext[j];
-            lo = x.x;
-            hi = x.y;
         }
     };
     // registers hold the entries from (cur - got) on; afterwards from cur on
-    auto slide = [&](const int32_t *__restrict__ cols, const int2 *__restrict__ ext, int len, int cur, int got, int &c,
-                     int &lo, int &hi) {
+    auto slide = [&](const int32_t *__restrict__ rows, const int32_t *__restrict__ cols, int len, int cur, int got, int &r, int &c) {
         const int src = lane + got;
+        const int r2 = __shfl(r, src & (kWave - 1), kWave);
         const int c2 = __shfl(c, src & (kWave - 1), kWave);
-        const int lo2 = __shfl(lo, src & (kWave - 1), kWave);
-        const int hi2 = __shfl(hi, src & (kWave - 1), kWave);
         const bool fresh = src >= kWave;
         c = c2;
-        lo = fresh ? kNone : lo2;
-        hi = fresh ? kNone : hi2;
-        load_entry(cols, ext, len, cur + lane, fresh, c, lo, hi);
+        r = fresh ? kNone : r2;
+        load_entry(rows, cols, len, cur + lane, fresh, r, c);
     };
-    load_entry(add_col, add_ext, n_add, a_cur + lane, true, pa_col, pa_lo, pa_hi);
-    load_entry(del_col, del_ext, n_del, d_cur + lane, true, pd_col, pd_lo, pd_hi);
+    load_entry(add_row, add_col, n_add, a_cur + lane, true, pa_row, pa_col);
+    load_entry(del_row, del_col, n_del, d_cur + lane, true, pd_row, pd_col);
     // ... and the same for the value updates, each with its value
-    int pu_col = 0, pu_lo = kNone, pu_hi = kNone;
+    int pu_row = kNone, pu_col = 0;
     float pu_val = 0.0f;
     auto load_update = [&](int j, bool want) {
         if (want && j < n_upd) {
+            pu_row = upd_row[j];
             pu_col = upd_col[j];
-            const int2 x = upd_ext[j];
-            pu_lo = x.x;
-            pu_hi = x.y;
             pu_val = upd_val[j];
         }
     };
@@ -359,23 +371,54 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
             s_mark[lane + j * kWave] = 0;
         }
         s_mark[kSub + lane] = 0;
+        // ---- the rows that meet the sub-tile: their pointers go to LDS; `below` counts the staged pointers that are
+        // <= e_stop, so the row that holds entry e_stop (the next sub-tile's first) is first_row + below - 1
+        s_rows[lane] = w0;
+        s_rows[kWave + lane] = w1;
+        if (lane == 0) s_rows[2 * kWave] = w2;
+        int n_win = kWindow;
+        int last = __shfl(w2, 0, kWave);
+        int below = __popcll(__ballot(w0 <= e_stop)) + __popcll(__ballot(w1 <= e_stop)) + (last <= e_stop ? 1 : 0);
+#pragma unroll 1
+        while (last < e_stop && n_win + kWave <= kMaxWindow) {      // short rows: the sub-tile reaches beyond the window
+            const int idx = first_row + n_win + lane;
+            const int v = idx <= n ? rowptr_prev[idx] : kNone;
+            s_rows[n_win + lane] = v;
+            below += __popcll(__ballot(v <= e_stop));
+            last = __shfl(v, kWave - 1, kWave);
+            n_win += kWave;
+        }
+        const int row0 = first_row;                  // the window staged now starts here
+        first_row = min(first_row + max(below, 1) - 1, n - 1);
 #pragma unroll
         for (int j = 0; j < kPerLane; ++j) {      // fetched while this sub-tile is placed
             const int i = e_stop + lane + j * kWave;
             c_next[j] = i < e_end ? colidx_prev[i] : 0;
             if (VALUES) v_next[j] = i < e_end ? val_prev[i] : 0.0f;
         }
+        if (e_stop < e_end) fetch_window(first_row);
         // the values of the (at most 64) added entries placed first in this sub-tile, fetched ahead of their use
         float av_first = 0.0f;
         if (VALUES && n_add > 0) av_first = add_val[min(a_cur + lane, n_add - 1)];
         __syncthreads();
 
+        // where a list entry's row lies in A_prev, from the staged pointers: rows outside the window do not meet the sub-tile
+        auto extent = [&](int row, int &lo, int &hi) {
+            const unsigned k = (unsigned)(row - row0);
+            lo = hi = kNone;
+            if (k < (unsigned)(n_win - 1)) {
+                lo = s_rows[k];
+                hi = s_rows[k + 1];
+            }
+        };
         // ---- deleted entries: mark the old entry dead.  The first 64 are in registers already; a sub-tile
         // with more than that is rare and pays for its loads on the spot.
         auto strike = [&](int j) {
             bool owned = false;
-            if (j < n_del && pd_lo < e_stop && pd_hi > e) {      // its row has entries in this sub-tile
-                const int lo = max(pd_lo - e, 0), hi = min(pd_hi - e, cnt);
+            int r_lo, r_hi;
+            extent(pd_row, r_lo, r_hi);
+            if (j < n_del && r_lo < e_stop && r_hi > e) {      // its row has entries in this sub-tile
+                const int lo = max(r_lo - e, 0), hi = min(r_hi - e, cnt);
                 const int p = lds_bound<false>(s_col, lo, hi, pd_col);
                 owned = p < hi && s_col[p] == pd_col;
                 if (owned) atomicOr(&s_mark[p], 1);
@@ -386,8 +429,8 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
 #pragma unroll 1
         while (d_got == kWave) {
             d_cur += kWave;
-            pd_lo = pd_hi = kNone;
-            load_entry(del_col, del_ext, n_del, d_cur + lane, true, pd_col, pd_lo, pd_hi);
+            pd_row = kNone;
+            load_entry(del_row, del_col, n_del, d_cur + lane, true, pd_row, pd_col);
             __builtin_amdgcn_s_waitcnt(kVmcntZero);
             d_got = strike(d_cur + lane);
         }
@@ -397,8 +440,11 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
         if (UPDATES) {
             auto touch = [&](int j) {
                 bool done = false;
-                if (j < n_upd && pu_lo < e_stop) {
-                    const int lo = max(pu_lo - e, 0), hi = min(pu_hi - e, cnt);
+                int r_lo, r_hi;
+                extent(pu_row, r_lo, r_hi);
+                if (j < n_upd && pu_row < row0) done = true;      // a row before the sub-tile's first: nothing left to find
+                else if (j < n_upd && r_lo < e_stop) {
+                    const int lo = max(r_lo - e, 0), hi = min(r_hi - e, cnt);
                     const int p = lo < hi ? lds_bound<false>(s_col, lo, hi, pu_col) : hi;
                     if (p < hi) {
                         done = true;
@@ -407,7 +453,7 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
                             atomicOr(&s_mark[p], 2);
                         }
                     } else {
-                        done = pu_hi <= e_stop;        // beyond the sub-tile's part of an unfinished row: later
+                        done = r_hi <= e_stop;        // beyond the sub-tile's part of an unfinished row: later
                     }
                 }
                 return __popcll(__ballot(done));
@@ -416,33 +462,33 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
 #pragma unroll 1
             while (u_got == kWave) {
                 u_cur += kWave;
-                pu_lo = pu_hi = kNone;
+                pu_row = kNone;
                 load_update(u_cur + lane, true);
                 __builtin_amdgcn_s_waitcnt(kVmcntZero);
                 u_got = touch(u_cur + lane);
             }
             u_cur += u_got;
             const int src = lane + u_got;       // the entries at the new cursor, for the next sub-tile
+            const int r2 = __shfl(pu_row, src & (kWave - 1), kWave);
             const int c2 = __shfl(pu_col, src & (kWave - 1), kWave);
-            const int lo2 = __shfl(pu_lo, src & (kWave - 1), kWave);
-            const int hi2 = __shfl(pu_hi, src & (kWave - 1), kWave);
             const float v2 = __shfl(pu_val, src & (kWave - 1), kWave);
             const bool fresh = src >= kWave;
             pu_col = c2;
             pu_val = v2;
-            pu_lo = fresh ? kNone : lo2;
-            pu_hi = fresh ? kNone : hi2;
+            pu_row = fresh ? kNone : r2;
             load_update(u_cur + lane, fresh);
         }
         // ---- added entries: count at the slot (old entry they precede; a row's end if none)
         const int a_tile = a_cur;
         auto slot = [&](int j, int &q) {
             bool owned = false;
+            int r_lo, r_hi;
+            extent(pa_row, r_lo, r_hi);
             q = -2 - lane;
-            if (j < n_add && pa_lo < e_stop && pa_hi > e) {
-                const int lo = max(pa_lo - e, 0), hi = min(pa_hi - e, cnt);
+            if (j < n_add && r_lo < e_stop && r_hi > e) {
+                const int lo = max(r_lo - e, 0), hi = min(r_hi - e, cnt);
                 q = lds_bound<true>(s_col, lo, hi, pa_col);
-                owned = q < hi || pa_hi <= e_stop;         // beyond the sub-tile's part of an unfinished row: later
+                owned = q < hi || r_hi <= e_stop;         // beyond the sub-tile's part of an unfinished row: later
                 if (owned) atomicAdd(&s_mark[q], 4);
             }
             if (!owned) q = -2 - lane;
@@ -454,19 +500,20 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
 #pragma unroll 1
         while (a_got == kWave) {
             a_cur += kWave;
-            pa_lo = pa_hi = kNone;
-            load_entry(add_col, add_ext, n_add, a_cur + lane, true, pa_col, pa_lo, pa_hi);
+            pa_row = kNone;
+            load_entry(add_row, add_col, n_add, a_cur + lane, true, pa_row, pa_col);
             __builtin_amdgcn_s_waitcnt(kVmcntZero);
             int q_unused;
             a_got = slot(a_cur + lane, q_unused);
         }
         a_cur += a_got;
         // the list entries at the new cursors, for the next sub-tile
-        slide(del_col, del_ext, n_del, d_cur, d_got, pd_col, pd_lo, pd_hi);
-        slide(add_col, add_ext, n_add, a_cur, a_got, pa_col, pa_lo, pa_hi);
+        slide(del_row, del_col, n_del, d_cur, d_got, pd_row, pd_col);
+        slide(add_row, add_col, n_add, a_cur, a_got, pa_row, pa_col);
         __syncthreads();
 
-        // ---- prefix sums: s_start[p] = kept entries before p + added entries of slots before p
+        // ---- prefix sums: s_start[p] = kept entries before p + added entries of slots before p (the staged row
+        // pointers are not needed any more; their place is taken)
         int written;
         {
             int mk[kPerLane];
@@ -528,15 +575,19 @@ __global__ __launch_bounds__(kWave) void merge_kernel(
         if (a_tile < a_cur) place(a_tile + lane, q_first, c_first, av_first);
 #pragma unroll 1
         for (int j0 = a_tile + kWave; j0 < a_cur; j0 += kWave) {
+            // these search again; the extent of an entry's row comes from the row pointers themselves, two loads that
+            // depend on the entry's, which a sub-tile this full can afford
             const int j = j0 + lane;
             int q = -2 - lane, c = 0;
             float v = 0.0f;
             if (j < a_cur) {
-                const int2 x = add_ext[j];
+                const int r = add_row[j];
                 c = add_col[j];
                 if (VALUES) v = add_val[j];
-                const int lo = max(x.x - e, 0), hi = min(x.y - e, cnt);
-                q = lds_bound<true>(s_col, lo, hi, c);
+                if ((unsigned)r < (unsigned)n) {
+                    const int hi = min(rowptr_prev[r + 1] - e, cnt), lo = min(max(rowptr_prev[r] - e, 0), max(hi, 0));
+                    q = lds_bound<true>(s_col, lo, hi, c);
+                }
             }
             place(j, q, c, v);
         }
@@ -710,20 +761,12 @@ int64_t max_ranges(int64_t nnz_prev) { return std::max<int64_t>(kTargetWaves + 1
 
 }  // namespace
 
-extern "C" int dgnn_delta_rebuild_weighted_workspace(int64_t n, int64_t nnz_prev, int64_t n_add, int64_t n_del, int64_t n_upd,
-                                                     size_t *bytes) {
-    if (!bytes) return DGNN_ERR_NULL;
-    if (n <= 0 || nnz_prev < 0 || n_add < 0 || n_del < 0 || n_upd < 0) return DGNN_ERR_SHAPE;
-    if (!fits_index(n + 1) || !fits_index(nnz_prev + n_add) || !fits_index(n_upd)) return DGNN_ERR_OVERFLOW;
-    *bytes = round_up((size_t)max_ranges(nnz_prev) * sizeof(RangeStart), 256)   // the row every range of the merge begins in
-             + round_up((size_t)n_add * sizeof(int2), 256)         // row extents of the added entries
-             + round_up((size_t)n_del * sizeof(int2), 256)         // ... of the deleted entries
-             + round_up((size_t)n_upd * sizeof(int2), 256);        // ... of the value updates the merge consumes
-    return DGNN_OK;
-}
-
 extern "C" int dgnn_delta_rebuild_workspace(int64_t n, int64_t nnz_prev, int64_t n_add, int64_t n_del, size_t *bytes) {
-    return dgnn_delta_rebuild_weighted_workspace(n, nnz_prev, n_add, n_del, 0, bytes);
+    if (!bytes) return DGNN_ERR_NULL;
+    if (n <= 0 || nnz_prev < 0 || n_add < 0 || n_del < 0) return DGNN_ERR_SHAPE;
+    if (!fits_index(n + 1) || !fits_index(nnz_prev + n_add)) return DGNN_ERR_OVERFLOW;
+    *bytes = round_up((size_t)max_ranges(nnz_prev) * sizeof(RangeStart), 256);   // the row every range of the merge begins in
+    return DGNN_OK;
 }
 
 namespace {
@@ -756,7 +799,7 @@ int rebuild(int64_t n, const int32_t *rowptr_prev, const int32_t *colidx_prev, i
     if (cap_next < nnz_new) return DGNN_ERR_CAPACITY;
     const int64_t n_upd = vals ? vals->n_upd : 0;
     size_t need = 0;
-    int rc = dgnn_delta_rebuild_weighted_workspace(n, nnz_prev, n_add, n_del, n_upd, &need);
+    int rc = dgnn_delta_rebuild_workspace(n, nnz_prev, n_add, n_del, &need);
     if (rc != DGNN_OK) return rc;
     if (ws_bytes < need) return DGNN_ERR_CAPACITY;
     if (rowptr_next == rowptr_prev || colidx_next == colidx_prev) return DGNN_ERR_ALIAS;
@@ -766,16 +809,18 @@ int rebuild(int64_t n, const int32_t *rowptr_prev, const int32_t *colidx_prev, i
     hipStream_t s = (hipStream_t)stream;
     char *wsb = static_cast<char *>(ws);
     RangeStart *range_start = reinterpret_cast<RangeStart *>(wsb);
-    int2 *add_ext = reinterpret_cast<int2 *>(wsb + round_up((size_t)max_ranges(nnz_prev) * sizeof(RangeStart), 256));
-    int2 *del_ext = reinterpret_cast<int2 *>(reinterpret_cast<char *>(add_ext) + round_up((size_t)n_add * sizeof(int2), 256));
-    int2 *upd_ext = reinterpret_cast<int2 *>(reinterpret_cast<char *>(del_ext) + round_up((size_t)n_del * sizeof(int2), 256));
     const int cap = (int)min(cap_next, (int64_t)2147483647LL);
     const int64_t range_len = merge_range_length(nnz_prev);
+    const int n_ranges = (int)((nnz_prev + range_len - 1) / range_len);
+    const int32_t *upd_row = n_upd > 0 ? vals->upd_row : nullptr;
 
-    hipLaunchKernelGGL(rowptr_kernel, dim3((unsigned)((n + kRowTile - 1) / kRowTile)), dim3(kRowThreads), 0, s,
-                       (int)n, rowptr_prev, add_row, (int)n_add, del_row, (int)n_del, rowptr_next,
-                       dinv_next, add_ext, del_ext, (int)range_len, (int)((nnz_prev + range_len - 1) / range_len), range_start,
-                       n_upd > 0 ? vals->upd_row : nullptr, (int)n_upd, upd_ext, d_status);
+    const dim3 row_grid((unsigned)((n + kRowTile - 1) / kRowTile));
+    if (aligned16(rowptr_prev) && aligned16(rowptr_next) && aligned16(dinv_next))
+        hipLaunchKernelGGL(rowptr_kernel<true>, row_grid, dim3(kRowThreads), 0, s, (int)n, rowptr_prev, add_row, (int)n_add, del_row,
+                           (int)n_del, rowptr_next, dinv_next, (int)range_len, n_ranges, range_start, upd_row, (int)n_upd, d_status);
+    else
+        hipLaunchKernelGGL(rowptr_kernel<false>, row_grid, dim3(kRowThreads), 0, s, (int)n, rowptr_prev, add_row, (int)n_add, del_row,
+                           (int)n_del, rowptr_next, dinv_next, (int)range_len, n_ranges, range_start, upd_row, (int)n_upd, d_status);
     DGNN_RETURN_IF_LAUNCH_FAILED();
     if ((flags & DGNN_VALIDATE) && d_status) {
         int64_t work = n_add + n_del + n;
@@ -789,20 +834,19 @@ int rebuild(int64_t n, const int32_t *rowptr_prev, const int32_t *colidx_prev, i
             DGNN_RETURN_IF_LAUNCH_FAILED();
         }
     }
-    const dim3 grid((unsigned)((nnz_prev + range_len - 1) / range_len));
+    const dim3 grid((unsigned)n_ranges);
     if (vals && n_upd > 0)
-        hipLaunchKernelGGL((merge_kernel<true, true>), grid, dim3(kWave), 0, s, colidx_prev, (int)nnz_prev,
-                           (int)range_len, add_col, add_ext, (int)n_add, del_col, del_ext, (int)n_del,
-                           range_start, colidx_next, cap, vals->prev, vals->add, vals->next, vals->upd_col, upd_ext, vals->upd_val,
-                           (int)n_upd);
+        hipLaunchKernelGGL((merge_kernel<true, true>), grid, dim3(kWave), 0, s, (int)n, rowptr_prev, colidx_prev, (int)nnz_prev,
+                           (int)range_len, add_row, add_col, (int)n_add, del_row, del_col, (int)n_del, range_start, colidx_next, cap,
+                           vals->prev, vals->add, vals->next, vals->upd_row, vals->upd_col, vals->upd_val, (int)n_upd);
     else if (vals)
-        hipLaunchKernelGGL((merge_kernel<true, false>), grid, dim3(kWave), 0, s, colidx_prev, (int)nnz_prev,
-                           (int)range_len, add_col, add_ext, (int)n_add, del_col, del_ext, (int)n_del,
-                           range_start, colidx_next, cap, vals->prev, vals->add, vals->next, nullptr, nullptr, nullptr, 0);
+        hipLaunchKernelGGL((merge_kernel<true, false>), grid, dim3(kWave), 0, s, (int)n, rowptr_prev, colidx_prev, (int)nnz_prev,
+                           (int)range_len, add_row, add_col, (int)n_add, del_row, del_col, (int)n_del, range_start, colidx_next, cap,
+                           vals->prev, vals->add, vals->next, nullptr, nullptr, nullptr, 0);
     else
-        hipLaunchKernelGGL((merge_kernel<false, false>), grid, dim3(kWave), 0, s, colidx_prev, (int)nnz_prev,
-                           (int)range_len, add_col, add_ext, (int)n_add, del_col, del_ext, (int)n_del,
-                           range_start, colidx_next, cap, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0);
+        hipLaunchKernelGGL((merge_kernel<false, false>), grid, dim3(kWave), 0, s, (int)n, rowptr_prev, colidx_prev, (int)nnz_prev,
+                           (int)range_len, add_row, add_col, (int)n_add, del_row, del_col, (int)n_del, range_start, colidx_next, cap,
+                           nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0);
     DGNN_RETURN_IF_LAUNCH_FAILED();
     return DGNN_OK;
 }

@@ -17,14 +17,17 @@ def dev_i32(a):
     return torch.as_tensor(np.ascontiguousarray(a), dtype=torch.int32).to(DEV)
 
 
-def gpu_rebuild(n, rp, ci, ar, ac, dr, dc, validate=True, slack=0):
-    rp_d, ci_d = dev_i32(rp), dev_i32(ci)
+def gpu_rebuild(n, rp, ci, ar, ac, dr, dc, validate=True, slack=0, shift=0):
+    """shift: the row-pointer arrays and dinv begin `shift` elements into their allocations (1: not 16-byte aligned)."""
+    ci_d = dev_i32(ci)
+    rp_d = torch.empty(n + 1 + shift, dtype=torch.int32, device=DEV)[shift:]
+    rp_d.copy_(torch.as_tensor(rp))
     lists = [dev_i32(x) for x in (ar, ac, dr, dc)]
     nnz_prev, n_add, n_del = int(ci.size), int(ar.size), int(dr.size)
     cap = nnz_prev + n_add - n_del + slack
-    rpn = torch.full((n + 1,), -7, dtype=torch.int32, device=DEV)
+    rpn = torch.full((n + 1 + shift,), -7, dtype=torch.int32, device=DEV)[shift:]
     cin = torch.full((max(cap, 1),), -7, dtype=torch.int32, device=DEV)
-    dinv = torch.zeros(n, dtype=torch.float32, device=DEV)
+    dinv = torch.zeros(n + shift, dtype=torch.float32, device=DEV)[shift:]
     ws = torch.empty(dg.delta_rebuild_workspace(n, nnz_prev, n_add, n_del), dtype=torch.uint8, device=DEV)
     status = torch.full((1,), 99, dtype=torch.int32, device=DEV)
     nnz = dg.delta_rebuild(rp_d, ci_d, nnz_prev, lists[0], lists[1], n_add, lists[2], lists[3], n_del, rpn, cin, dinv,
@@ -108,6 +111,48 @@ def test_rebuild_heavy_rows_and_many_adds_between_neighbours():
     grp, gci, _, status, _ = gpu_rebuild(n, rp, ci, *a, *d)
     assert status == 0
     assert np.array_equal(grp, erp) and np.array_equal(gci, eci)
+
+
+@pytest.mark.parametrize("n", [1000, 1023, 4097, 70_001])
+def test_rebuild_with_row_pointers_that_are_not_16_byte_aligned(n):
+    """The row-pointer kernel moves four rows per access when its arrays allow it; here they do not, and n leaves a
+    ragged last group of rows either way."""
+    wl = WORKLOADS["c1"].scaled(n)
+    g = DynamicGraph(wl)
+    rp, ci = (x.numpy() for x in g.csr())
+    lists = [x.numpy() for x in g.advance()]
+    erp, eci = oracle.delta_apply(n, rp, ci, *lists)
+    for shift in (0, 1, 2):
+        grp, gci, dinv, status, _ = gpu_rebuild(n, rp, ci, *lists, shift=shift)
+        assert status == 0, shift
+        assert np.array_equal(grp, erp) and np.array_equal(gci, eci), shift
+        assert np.allclose(dinv, 1.0 / np.sqrt(np.diff(erp)), rtol=3e-7, atol=0), shift
+
+
+def test_rebuild_stretches_of_very_short_rows():
+    """Thousands of consecutive rows that hold their diagonal alone, or one more entry: a 512-entry piece of the
+    merge's stream then meets more rows than it fetches row pointers for ahead of time.  Hub rows in between."""
+    n = 30_000
+    rng = np.random.default_rng(21)
+    rows, cols = [np.arange(n)], [np.arange(n)]
+    second = np.arange(0, n, 3)                                  # every third row: one more entry
+    rows.append(second); cols.append((second + 7) % n)
+    for hub, deg in ((9000, 2000), (9001, 700), (20_000, 5000)):
+        rows.append(np.full(deg, hub)); cols.append(rng.choice(n, deg, replace=False))
+    rp, ci = oracle.csr_from_edges(n, np.concatenate(rows).astype(np.int32), np.concatenate(cols).astype(np.int32))
+    r_of = np.repeat(np.arange(n), np.diff(rp))
+    present = set(zip(r_of.tolist(), ci.tolist()))
+    off = np.flatnonzero(r_of != ci)
+    dele = np.sort(rng.choice(off, off.size // 3, replace=False))
+    adds = {(int(r), int(c)) for r, c in zip(rng.integers(0, n, 9000), rng.integers(0, n, 9000))}
+    adds |= {(9000, int(c)) for c in rng.integers(0, n, 800)} | {(12_345, int(c)) for c in rng.integers(0, n, 300)}
+    a = coo([p for p in adds if p not in present and p[0] != p[1]])
+    d = (r_of[dele].astype(np.int32), ci[dele].astype(np.int32))
+    erp, eci = oracle.delta_apply(n, rp, ci, *a, *d)
+    grp, gci, dinv, status, _ = gpu_rebuild(n, rp, ci, *a, *d)
+    assert status == 0
+    assert np.array_equal(grp, erp) and np.array_equal(gci, eci)
+    assert np.allclose(dinv, 1.0 / np.sqrt(np.diff(erp)), rtol=3e-7, atol=0)
 
 
 def test_rebuild_many_changes_in_one_row_tile():

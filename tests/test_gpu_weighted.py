@@ -33,9 +33,7 @@ def gpu_rebuild_weighted(n, rp, ci, val, add, dele, upd, merged=False, expect_st
             order = np.lexsort((upd[1], upd[0]))
             upd = tuple(x[order] for x in upd)
         flags |= dg.DGNN_UPDATES_SORTED
-        ws = torch.empty(dg.delta_rebuild_weighted_workspace(n, nnz_prev, n_add, n_del, int(upd[0].size)), dtype=torch.uint8, device=DEV)
-    else:
-        ws = torch.empty(dg.delta_rebuild_workspace(n, nnz_prev, n_add, n_del), dtype=torch.uint8, device=DEV)
+    ws = torch.empty(dg.delta_rebuild_workspace(n, nnz_prev, n_add, n_del), dtype=torch.uint8, device=DEV)
     status = torch.zeros(1, dtype=torch.int32, device=DEV)
     nnz = dg.delta_rebuild_weighted(
         dev(rp, torch.int32), dev(ci, torch.int32), dev(val, torch.float32), nnz_prev,
