@@ -473,6 +473,62 @@ def cdgcn_layer(args, wl, blk, dev):
     return out
 
 
+def lstm_step_shapes(args, wl, blk, dev):
+    """The fused LSTM step (gate pre-activations kept on chip) on every storage type and width it is built for,
+    beside the same step composed of two dense transforms and the cell kernel: an extra figure, n rows of the
+    workload, random inputs."""
+    import math
+    import torch
+    import paper_2109_07893_amd as dg
+    n = blk.n
+    gen = torch.Generator(device=dev).manual_seed(wl.seed)
+    rows = []
+    for dt, hidden, f_y in ((torch.float32, 32, 64), (torch.float32, 16, 32), (torch.bfloat16, 32, 64), (torch.bfloat16, 64, 64),
+                            (torch.bfloat16, 64, 128)):
+        y = torch.randn((n, f_y), generator=gen, device=dev).to(dt)
+        h = torch.randn((n, hidden), generator=gen, device=dev).to(dt)
+        c = torch.randn((n, hidden), generator=gen, device=dev).to(dt)
+        hn = torch.empty_like(h)
+        w_x = (torch.randn((f_y, 4 * hidden), generator=gen, device=dev) / math.sqrt(f_y)).to(dt)
+        w_h = (torch.randn((hidden, 4 * hidden), generator=gen, device=dev) / math.sqrt(hidden)).to(dt)
+        bias = torch.zeros(4 * hidden, device=dev)
+        gx = torch.empty((n, 4 * hidden), dtype=dt, device=dev)
+        gh = torch.empty_like(gx)
+
+        def fused():
+            dg.lstm_step(y, h, w_x, w_h, bias, c, hn)
+
+        def composed():
+            dg.feature_transform(y, w_x, gx)
+            dg.feature_transform(h, w_h, gh)
+            dg.lstm_cell(gx, gh, bias, c, c, hn)
+
+        ms = {"composed": None}
+        for name, fn in (("fused", fused), ("composed", composed)):
+            if name == "composed" and 4 * hidden > 128:      # the dense transform's widths end at 128
+                continue
+            for _ in range(2):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ms[name] = e0.elapsed_time(e1) / args.steps
+        s = y.element_size()
+        byts = s * n * (f_y + 4 * hidden)                  # Y, h, c in; c, h out
+        flops = 2 * n * (f_y + hidden) * 4 * hidden
+        rows.append({"dtype": "bf16" if dt == torch.bfloat16 else "f32", "hidden": hidden, "f_y": f_y,
+                     "fused_ms": round(ms["fused"], 3), "composed_ms": None if ms["composed"] is None else round(ms["composed"], 3),
+                     "fused_algorithmic_GBps": round(byts / (ms["fused"] * 1e-3) / 1e9, 1),
+                     "fused_TFLOPs": round(flops / (ms["fused"] * 1e-3) / 1e12, 1)})
+        del y, h, c, hn, gx, gh
+        torch.cuda.empty_cache()
+    return {"n": n, "shapes": rows}
+
+
 def training_step(args, wl, blk, dev):
     """Forward keeping activations plus backward over the same block (every snapshot t = 1..T); an extra
     figure next to the headline, which stays the forward pass."""
@@ -759,6 +815,7 @@ def main():
     extra("gather_working_sets", args.working_sets, gather_working_sets)
     extra("mproduct_explicit_band", args.mproduct_band, mproduct_band)
     extra("cdgcn_layer", args.cdgcn, cdgcn_layer)
+    extra("lstm_step_shapes", args.cdgcn, lstm_step_shapes)
     extra("weighted_step", args.weighted, weighted_step)
     extra("smoothing", args.smoothing, smoothing_steps)
     if not args.no_train:

@@ -439,8 +439,10 @@ int dgnn_lstm_cell(const void *gates_x, const void *gates_h, const float *bias, 
  * on the matrix cores and the cell of dgnn_lstm_cell is applied to the accumulators.
  *   y [n][f_y], h_prev [n][hidden], w_x [f_y][4 * hidden], w_h [hidden][4 * hidden], bias fp32 [4 * hidden] or NULL
  *   c [n][hidden]        cell state, updated IN PLACE;   h_next [n][hidden]   a buffer of its own
- * Supported: fp32 storage, hidden = 32, f_y = 32 or 64 (DGNN_ERR_SHAPE otherwise: use the two dense transforms and
- * dgnn_lstm_cell).  Same result as that composition up to the order of the fp32 sums.
+ * Supported: fp32 storage with hidden = 16 or 32, bf16 storage with hidden = 32 or 64, and f_y = hidden or
+ * 2 * hidden (DGNN_ERR_SHAPE otherwise: use the two dense transforms and dgnn_lstm_cell).  fp32: same result as that
+ * composition up to the order of the fp32 sums.  bf16: the pre-activations stay in fp32 here, where the composition
+ * rounds the two products to bf16 before it adds them; c and h are rounded once, when they are stored.
  */
 int dgnn_lstm_step(const void *y, int32_t f_y, const void *h_prev, const void *w_x, const void *w_h,
                    const float *bias, void *c, void *h_next, int64_t n, int32_t hidden, dgnn_dtype dt,

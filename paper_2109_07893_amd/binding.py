@@ -524,7 +524,8 @@ def add(a: torch.Tensor, b: torch.Tensor, out: torch.Tensor) -> None:
 
 
 def lstm_step_supported(y: torch.Tensor, hidden: int) -> bool:
-    return y.dtype == torch.float32 and hidden == 32 and y.shape[1] in (32, 64)
+    widths = (16, 32) if y.dtype == torch.float32 else (32, 64) if y.dtype == torch.bfloat16 else ()
+    return hidden in widths and y.shape[1] in (hidden, 2 * hidden)
 
 
 def lstm_step(y, h_prev, w_x, w_h, bias, c, h_next) -> None:

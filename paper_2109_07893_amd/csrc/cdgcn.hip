@@ -118,10 +118,12 @@ extern "C" int dgnn_lstm_cell(const void *gates_x, const void *gates_h, const fl
 // ---- One LSTM step with the gate pre-activations kept on chip -------------------------------------------
 // a = [Y | h_prev] [W_x ; W_h] + b is 4 * hidden wide and, written out, is two thirds of the traffic of an LSTM
 // step.  Here a wavefront takes 32 vertices, forms the TRANSPOSED gate tiles (W^T as the A operand, the rows
-// of [Y | h_prev] as the B operand) on the matrix cores, and applies the cell straight to the accumulators: with
-// hidden = 32 the four 32-column tiles ARE the four gates, and lane (i, h) holds, for vertex i and four consecutive
-// state elements per four registers, the input, forget, cell and output pre-activation in the same register slot of
-// the four tiles.  Traffic: Y, h_prev, c in; c, h out.  fp32 storage.
+// of [Y | h_prev] as the B operand) on the matrix cores, and applies the cell straight to the accumulators.  Column
+// C = g * hidden + k of the pre-activations is gate g of state element k; it lies in the 32-column tile C / 32, and
+// lane (i, h) holds, for vertex i, the columns c of a tile with (c / 4) % 2 == h, four consecutive ones per four
+// accumulator registers.  hidden is a multiple of 8, so the four gates of a state element sit in the same lane
+// (hidden = 32: the four tiles ARE the four gates, same register slot in each).  Traffic: Y, h_prev, c in; c, h out.
+// fp32 storage: hidden 16 or 32; bf16 storage (fp32 accumulation, the cell in fp32): hidden 32 or 64.
 namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
@@ -133,16 +135,16 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ float fast_sigmoid(float x) { return __frcp_rn(1.0f + __expf(-x)); }
 __device__ __forceinline__ float fast_tanh(float x) { return 2.0f * fast_sigmoid(2.0f * x) - 1.0f; }
 
-constexpr int kLstmHidden = 32;
+constexpr int kLstmHidden = 32;      // the adjoint kernel's only width
 constexpr int kLstmThreads = 512;   // eight wavefronts share W in LDS: two per SIMD, so one multiplies while the other moves data
 constexpr int kLstmWaves = kLstmThreads / kWave;
 
-template <int FY>
+template <int FY, int HID>
 __global__ __launch_bounds__(kLstmThreads) void lstm_step_f32_kernel(const float *__restrict__ y, const float *__restrict__ h_prev,
                                                                  const float *__restrict__ w_x, const float *__restrict__ w_h,
                                                                  const float *__restrict__ bias, float *c,
                                                                  float *__restrict__ h_next, int64_t n, int64_t n_tiles) {
-    constexpr int HID = kLstmHidden, G4 = 4 * HID;
+    constexpr int G4 = 4 * HID, NT = G4 / 32;
     constexpr int K = FY + HID, KH = K / 2;
     constexpr int LDT = K + 4;                          // padded tile row (floats)
     constexpr int Y_PIECES = 32 * FY / 4 / kWave;       // 16-byte pieces per lane of a tile of Y
@@ -199,34 +201,36 @@ __global__ __launch_bounds__(kLstmThreads) void lstm_step_f32_kernel(const float
             const int e = (q * kWave + lane) * 4;
             *reinterpret_cast<floatx4 *>(&tile_lds[(e / HID) * LDT + e % HID]) = c_cur[q];
         }
-        floatx16 acc[4];
+        floatx16 acc[NT];
 #pragma unroll
-        for (int g = 0; g < 4; ++g)
+        for (int g = 0; g < NT; ++g)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[g][v] = 0.0f;
 #pragma unroll
         for (int s = 0; s < KH; ++s) {
             const float xv = a[s / 4][s % 4];
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
+            for (int g = 0; g < NT; ++g) {
                 const float wv = s_w[(hh * KH + s) * G4 + g * 32 + i];
-                acc[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(wv, xv, acc[g], 0, 0, 0);     // transposed gate tile g
+                acc[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(wv, xv, acc[g], 0, 0, 0);     // transposed tile g of the pre-activations
             }
         }
         wave_lds_sync();                                                      // the old cell state is in LDS
-        // ---- the cell, on the accumulators: register 4 q + r of lane (i, h) is state element 8 q + 4 h + r of vertex i
+        // ---- the cell, on the accumulators: lane (i, h) owns state elements 8 m + 4 h + r of vertex i; gate g of
+        // them is column g * hidden + 8 m + 4 h + r: tile (g * hidden + 8 m) / 32, registers 4 q + r with q the
+        // 8-column group inside the tile
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int k0 = 8 * q + 4 * hh;
+        for (int m = 0; m < HID / 8; ++m) {
+            const int k0 = 8 * m + 4 * hh;
             const floatx4 c_old = *reinterpret_cast<const floatx4 *>(&tile_lds[i * LDT + k0]);
             floatx4 c_new, h_new;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int k = k0 + r;
-                const float ai = acc[0][4 * q + r] + (bias ? bias[k] : 0.0f);
-                const float af = acc[1][4 * q + r] + (bias ? bias[HID + k] : 0.0f);
-                const float ag = acc[2][4 * q + r] + (bias ? bias[2 * HID + k] : 0.0f);
-                const float ao = acc[3][4 * q + r] + (bias ? bias[3 * HID + k] : 0.0f);
+                const float ai = acc[(8 * m) / 32][4 * (((8 * m) % 32) / 8) + r] + (bias ? bias[k] : 0.0f);
+                const float af = acc[(HID + 8 * m) / 32][4 * (((HID + 8 * m) % 32) / 8) + r] + (bias ? bias[HID + k] : 0.0f);
+                const float ag = acc[(2 * HID + 8 * m) / 32][4 * (((2 * HID + 8 * m) % 32) / 8) + r] + (bias ? bias[2 * HID + k] : 0.0f);
+                const float ao = acc[(3 * HID + 8 * m) / 32][4 * (((3 * HID + 8 * m) % 32) / 8) + r] + (bias ? bias[3 * HID + k] : 0.0f);
                 c_new[r] = fast_sigmoid(af) * c_old[r] + fast_sigmoid(ai) * fast_tanh(ag);
                 h_new[r] = fast_sigmoid(ao) * fast_tanh(c_new[r]);
             }
@@ -244,6 +248,126 @@ __global__ __launch_bounds__(kLstmThreads) void lstm_step_f32_kernel(const float
                     reinterpret_cast<floatx4 *>(h_next)[piece] =
                         *reinterpret_cast<const floatx4 *>(&tile_lds[(e / HID) * LDT + HID + e % HID]);
                 }
+            }
+        }
+        wave_lds_sync();                                                      // the tile buffer is reused
+    }
+}
+
+// The same step for bf16 storage: 16 k-values per matrix instruction (eight from each lane half), W^T parked in LDS
+// with k contiguous, the tile buffer in bf16.  The cell runs in fp32 on the accumulators; c and h are rounded once,
+// on the way out.  WAVES: wavefronts per workgroup (the widest case leaves room for four tile buffers beside W).
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+template <int FY, int HID, int WAVES>
+__global__ __launch_bounds__(WAVES * kWave) void lstm_step_bf16_kernel(const uint16_t *__restrict__ y, const uint16_t *__restrict__ h_prev,
+                                                                      const uint16_t *__restrict__ w_x, const uint16_t *__restrict__ w_h,
+                                                                      const float *__restrict__ bias, uint16_t *c,
+                                                                      uint16_t *__restrict__ h_next, int64_t n, int64_t n_tiles) {
+    constexpr int G4 = 4 * HID, NT = G4 / 32;
+    constexpr int K = FY + HID, KH = K / 2, KS = KH / 8;
+    constexpr int LDW = K + 8;                          // padded row of W^T (bf16 values)
+    constexpr int LDT = K + 8;                          // padded tile row
+    constexpr int Y_PIECES = 32 * FY / 8 / kWave;       // 16-byte pieces per lane of a tile of Y
+    constexpr int S_PIECES = 32 * HID / 8 / kWave;      // ... of a tile of h or c
+    static_assert(K >= 2 * HID && KH % 8 == 0, "the tile buffer also carries c and h (2 * hidden columns)");
+    __shared__ __attribute__((aligned(16))) uint16_t s_wt[G4 * LDW];     // row j: column j of [W_x ; W_h]
+    __shared__ __attribute__((aligned(16))) uint16_t s_tile[WAVES][32 * LDT];
+
+    const int tid = threadIdx.x;
+    for (int idx = tid; idx < K * G4; idx += WAVES * kWave) {
+        const int k = idx / G4, j = idx % G4;
+        s_wt[j * LDW + k] = k < FY ? w_x[idx] : w_h[idx - FY * G4];
+    }
+    const int lane = tid & (kWave - 1), wave = tid / kWave;
+    const int i = lane & 31, hh = lane >> 5;
+    uint16_t *tile_lds = s_tile[wave];
+    const int64_t stride = (int64_t)gridDim.x * WAVES;
+    const int64_t first = (int64_t)blockIdx.x * WAVES + wave;
+    __syncthreads();                                   // W is in LDS; from here on every wavefront is on its own
+    for (int64_t tile = first; tile < n_tiles; tile += stride) {
+        const uintx4 zero = {0u, 0u, 0u, 0u};
+        uintx4 c_cur[S_PIECES];
+        {
+            uintx4 yv[Y_PIECES], hv[S_PIECES];
+#pragma unroll
+            for (int q = 0; q < Y_PIECES; ++q) {
+                const int64_t piece = tile * (32 * FY / 8) + q * kWave + lane;
+                yv[q] = piece * 8 < n * FY ? reinterpret_cast<const uintx4 *>(y)[piece] : zero;
+            }
+#pragma unroll
+            for (int q = 0; q < S_PIECES; ++q) {
+                const int64_t piece = tile * (32 * HID / 8) + q * kWave + lane;
+                const bool ok = piece * 8 < n * HID;
+                hv[q] = ok ? reinterpret_cast<const uintx4 *>(h_prev)[piece] : zero;
+                c_cur[q] = ok ? reinterpret_cast<const uintx4 *>(c)[piece] : zero;
+            }
+#pragma unroll
+            for (int q = 0; q < Y_PIECES; ++q) {
+                const int e = (q * kWave + lane) * 8;
+                *reinterpret_cast<uintx4 *>(&tile_lds[(e / FY) * LDT + e % FY]) = yv[q];
+            }
+#pragma unroll
+            for (int q = 0; q < S_PIECES; ++q) {
+                const int e = (q * kWave + lane) * 8;
+                *reinterpret_cast<uintx4 *>(&tile_lds[(e / HID) * LDT + FY + e % HID]) = hv[q];
+            }
+        }
+        wave_lds_sync();
+        bf16x8 a[KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) a[s] = *reinterpret_cast<const bf16x8 *>(&tile_lds[i * LDT + hh * KH + s * 8]);
+        wave_lds_sync();                                                      // every lane has its operands
+        // the tile buffer now takes the old cell state in columns [0, hidden)
+#pragma unroll
+        for (int q = 0; q < S_PIECES; ++q) {
+            const int e = (q * kWave + lane) * 8;
+            *reinterpret_cast<uintx4 *>(&tile_lds[(e / HID) * LDT + e % HID]) = c_cur[q];
+        }
+        floatx16 acc[NT];
+#pragma unroll
+        for (int g = 0; g < NT; ++g)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[g][v] = 0.0f;
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+#pragma unroll
+            for (int g = 0; g < NT; ++g) {
+                const bf16x8 wv = *reinterpret_cast<const bf16x8 *>(&s_wt[(g * 32 + i) * LDW + hh * KH + s * 8]);
+                acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, a[s], acc[g], 0, 0, 0);    // transposed tile g of the pre-activations
+            }
+        wave_lds_sync();                                                      // the old cell state is in LDS
+        // ---- the cell, on the accumulators (same ownership as in the fp32 kernel)
+#pragma unroll
+        for (int m = 0; m < HID / 8; ++m) {
+            const int k0 = 8 * m + 4 * hh;
+            const uint2 c_raw = *reinterpret_cast<const uint2 *>(&tile_lds[i * LDT + k0]);
+            const float c_old[4] = {bf16_to_f32(c_raw.x & 0xffffu), bf16_to_f32(c_raw.x >> 16), bf16_to_f32(c_raw.y & 0xffffu),
+                                    bf16_to_f32(c_raw.y >> 16)};
+            float c_new[4], h_new[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int k = k0 + r;
+                const float ai = acc[(8 * m) / 32][4 * (((8 * m) % 32) / 8) + r] + (bias ? bias[k] : 0.0f);
+                const float af = acc[(HID + 8 * m) / 32][4 * (((HID + 8 * m) % 32) / 8) + r] + (bias ? bias[HID + k] : 0.0f);
+                const float ag = acc[(2 * HID + 8 * m) / 32][4 * (((2 * HID + 8 * m) % 32) / 8) + r] + (bias ? bias[2 * HID + k] : 0.0f);
+                const float ao = acc[(3 * HID + 8 * m) / 32][4 * (((3 * HID + 8 * m) % 32) / 8) + r] + (bias ? bias[3 * HID + k] : 0.0f);
+                c_new[r] = fast_sigmoid(af) * c_old[r] + fast_sigmoid(ai) * fast_tanh(ag);
+                h_new[r] = fast_sigmoid(ao) * fast_tanh(c_new[r]);
+            }
+            *reinterpret_cast<uint2 *>(&tile_lds[i * LDT + k0]) =
+                make_uint2(f32_to_bf16(c_new[0]) | (f32_to_bf16(c_new[1]) << 16), f32_to_bf16(c_new[2]) | (f32_to_bf16(c_new[3]) << 16));
+            *reinterpret_cast<uint2 *>(&tile_lds[i * LDT + HID + k0]) =
+                make_uint2(f32_to_bf16(h_new[0]) | (f32_to_bf16(h_new[1]) << 16), f32_to_bf16(h_new[2]) | (f32_to_bf16(h_new[3]) << 16));
+        }
+        wave_lds_sync();
+#pragma unroll
+        for (int q = 0; q < S_PIECES; ++q) {
+            const int e = (q * kWave + lane) * 8;
+            const int64_t piece = tile * (32 * HID / 8) + q * kWave + lane;
+            if (piece * 8 < n * HID) {
+                reinterpret_cast<uintx4 *>(c)[piece] = *reinterpret_cast<const uintx4 *>(&tile_lds[(e / HID) * LDT + e % HID]);
+                reinterpret_cast<uintx4 *>(h_next)[piece] = *reinterpret_cast<const uintx4 *>(&tile_lds[(e / HID) * LDT + HID + e % HID]);
             }
         }
         wave_lds_sync();                                                      // the tile buffer is reused
@@ -401,18 +525,40 @@ __global__ __launch_bounds__(kLstmThreads) void lstm_step_backward_f32_kernel(
     }
 }
 
-template <int FY>
+template <int FY, int HID>
 int launch_lstm_step(const void *y, const void *h_prev, const void *w_x, const void *w_h, const float *bias, void *c,
                      void *h_next, int64_t n, hipStream_t s) {
     const int64_t n_tiles = (n + 31) / 32;
     const int64_t needed = (n_tiles + kLstmWaves - 1) / kLstmWaves;
-    const int64_t resident = resident_workgroups(lstm_step_f32_kernel<FY>, kLstmThreads, 256);
+    const int64_t resident = resident_workgroups(lstm_step_f32_kernel<FY, HID>, kLstmThreads, 256);
     const unsigned blocks = (unsigned)(needed < resident ? needed : resident);
-    hipLaunchKernelGGL(lstm_step_f32_kernel<FY>, dim3(blocks), dim3(kLstmThreads), 0, s, static_cast<const float *>(y),
+    hipLaunchKernelGGL((lstm_step_f32_kernel<FY, HID>), dim3(blocks), dim3(kLstmThreads), 0, s, static_cast<const float *>(y),
                        static_cast<const float *>(h_prev), static_cast<const float *>(w_x), static_cast<const float *>(w_h),
                        bias, static_cast<float *>(c), static_cast<float *>(h_next), n, n_tiles);
     DGNN_RETURN_IF_LAUNCH_FAILED();
     return DGNN_OK;
+}
+
+template <int FY, int HID, int WAVES>
+int launch_lstm_step_bf16(const void *y, const void *h_prev, const void *w_x, const void *w_h, const float *bias, void *c,
+                          void *h_next, int64_t n, hipStream_t s) {
+    const int64_t n_tiles = (n + 31) / 32;
+    const int64_t needed = (n_tiles + WAVES - 1) / WAVES;
+    const int64_t resident = resident_workgroups(lstm_step_bf16_kernel<FY, HID, WAVES>, WAVES * kWave, 256);
+    const unsigned blocks = (unsigned)(needed < resident ? needed : resident);
+    hipLaunchKernelGGL((lstm_step_bf16_kernel<FY, HID, WAVES>), dim3(blocks), dim3(WAVES * kWave), 0, s, static_cast<const uint16_t *>(y),
+                       static_cast<const uint16_t *>(h_prev), static_cast<const uint16_t *>(w_x), static_cast<const uint16_t *>(w_h),
+                       bias, static_cast<uint16_t *>(c), static_cast<uint16_t *>(h_next), n, n_tiles);
+    DGNN_RETURN_IF_LAUNCH_FAILED();
+    return DGNN_OK;
+}
+
+// The shapes the fused step is built for: hidden and, for each, the widths of Y (hidden and 2 * hidden: the layer's
+// input is the concatenation of two blocks of features).
+bool lstm_step_shape_ok(int32_t f_y, int32_t hidden, dgnn_dtype dt) {
+    if (dt == DGNN_F32) return (hidden == 16 || hidden == 32) && (f_y == hidden || f_y == 2 * hidden);
+    if (dt == DGNN_BF16) return (hidden == 32 || hidden == 64) && (f_y == hidden || f_y == 2 * hidden);
+    return false;
 }
 
 }  // namespace
@@ -421,13 +567,21 @@ extern "C" int dgnn_lstm_step(const void *y, int32_t f_y, const void *h_prev, co
                               const float *bias, void *c, void *h_next, int64_t n, int32_t hidden, dgnn_dtype dt,
                               void *stream) {
     if (!y || !h_prev || !w_x || !w_h || !c || !h_next) return DGNN_ERR_NULL;
-    if (n <= 0 || hidden != kLstmHidden || dt != DGNN_F32 || (f_y != 32 && f_y != 64)) return DGNN_ERR_SHAPE;
+    if (n <= 0 || !lstm_step_shape_ok(f_y, hidden, dt)) return DGNN_ERR_SHAPE;
     if (!fits_index(n)) return DGNN_ERR_OVERFLOW;
     if (!aligned16(y) || !aligned16(h_prev) || !aligned16(c) || !aligned16(h_next)) return DGNN_ERR_ALIGN;
     if (h_next == h_prev || h_next == c || h_next == y || c == y || c == h_prev) return DGNN_ERR_ALIAS;
     hipStream_t s = (hipStream_t)stream;
-    return f_y == 32 ? launch_lstm_step<32>(y, h_prev, w_x, w_h, bias, c, h_next, n, s)
-                     : launch_lstm_step<64>(y, h_prev, w_x, w_h, bias, c, h_next, n, s);
+    if (dt == DGNN_F32) {
+        if (hidden == 32) return f_y == 32 ? launch_lstm_step<32, 32>(y, h_prev, w_x, w_h, bias, c, h_next, n, s)
+                                           : launch_lstm_step<64, 32>(y, h_prev, w_x, w_h, bias, c, h_next, n, s);
+        return f_y == 16 ? launch_lstm_step<16, 16>(y, h_prev, w_x, w_h, bias, c, h_next, n, s)
+                         : launch_lstm_step<32, 16>(y, h_prev, w_x, w_h, bias, c, h_next, n, s);
+    }
+    if (hidden == 32) return f_y == 32 ? launch_lstm_step_bf16<32, 32, 8>(y, h_prev, w_x, w_h, bias, c, h_next, n, s)
+                                       : launch_lstm_step_bf16<64, 32, 8>(y, h_prev, w_x, w_h, bias, c, h_next, n, s);
+    return f_y == 64 ? launch_lstm_step_bf16<64, 64, 8>(y, h_prev, w_x, w_h, bias, c, h_next, n, s)
+                     : launch_lstm_step_bf16<128, 64, 4>(y, h_prev, w_x, w_h, bias, c, h_next, n, s);
 }
 
 extern "C" int dgnn_lstm_step_backward(const void *y, int32_t f_y, const void *h_prev, const void *w_x, const void *w_h,

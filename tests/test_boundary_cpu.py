@@ -228,7 +228,8 @@ def test_lstm_step_argument_errors(lib):
             a[{"y": 0, "f_y": 1, "h_prev": 2, "c": 6, "h_next": 7, "n": 8, "hidden": 9, "dt": 10}[k]] = v
         return f(*a)
     assert call(y=None) == -1 and call(c=None) == -1
-    assert call(f_y=128) == -2 and call(hidden=64) == -2 and call(dt=1) == -2 and call(n=0) == -2
+    assert call(f_y=128) == -2 and call(hidden=64) == -2 and call(dt=1, hidden=16, f_y=32) == -2 and call(dt=2) == -2 and call(n=0) == -2
+    assert call(f_y=16) == -2 and call(hidden=16, f_y=64) == -2
     assert call(h_next=FAKE + 0x4000) == -5 and call(h_next=FAKE + 0x1000) == -5
     assert call(y=FAKE + 8) == -7
 

@@ -82,23 +82,55 @@ def test_cdgcn_layer_over_a_block(case):
         assert_close(to_f64(got[t - 1]), h, dtype, f"{case}: h_{t}", stores=7 * t)
 
 
-@pytest.mark.parametrize("f_y", [32, 64])
+@pytest.mark.parametrize("dtype,hidden,f_y", [(torch.float32, 32, 32), (torch.float32, 32, 64), (torch.float32, 16, 16),
+                                              (torch.float32, 16, 32), (torch.bfloat16, 32, 32), (torch.bfloat16, 32, 64),
+                                              (torch.bfloat16, 64, 64), (torch.bfloat16, 64, 128)])
 @pytest.mark.parametrize("n", [1, 31, 32, 33, 4097, 20_011])
 @pytest.mark.parametrize("with_bias", [False, True])
-def test_fused_lstm_step(f_y, n, with_bias):
-    hidden = 32
-    y, h = randn((n, f_y), n + f_y), randn((n, hidden), n + 1)
-    c = randn((n, hidden), n + 2)
-    w_x = randn((f_y, 4 * hidden), 5) / np.sqrt(f_y)
-    w_h = randn((hidden, 4 * hidden), 6) / np.sqrt(hidden)
+def test_fused_lstm_step(dtype, hidden, f_y, n, with_bias):
+    assert dg.lstm_step_supported(torch.empty((1, f_y), dtype=dtype), hidden)
+    y, h = randn((n, f_y), n + f_y, dtype), randn((n, hidden), n + 1, dtype)
+    c = randn((n, hidden), n + 2, dtype)
+    w_x = (randn((f_y, 4 * hidden), 5) / np.sqrt(f_y)).to(dtype)
+    w_h = (randn((hidden, 4 * hidden), 6) / np.sqrt(hidden)).to(dtype)
     bias = randn((4 * hidden,), 7) if with_bias else None
     h_want, c_want = oracle.lstm_cell(to_f64(y), to_f64(h), to_f64(c), to_f64(w_x), to_f64(w_h),
                                       to_f64(bias) if with_bias else None)
     cd = c.to(DEV)
-    hn = torch.full((n, hidden), float("nan"), device=DEV)
+    hn = torch.full((n, hidden), float("nan"), dtype=dtype, device=DEV)
     dg.lstm_step(y.to(DEV), h.to(DEV), w_x.to(DEV), w_h.to(DEV), bias.to(DEV) if with_bias else None, cd, hn)
-    assert_close(to_f64(cd), c_want, torch.float32, f"fused step: c, n={n}")
-    assert_close(to_f64(hn), h_want, torch.float32, f"fused step: h, n={n}")
+    assert_close(to_f64(cd), c_want, dtype, f"fused step: c, n={n}")
+    assert_close(to_f64(hn), h_want, dtype, f"fused step: h, n={n}")
+
+
+@pytest.mark.parametrize("dtype,hidden", [(torch.float32, 16), (torch.float32, 32), (torch.bfloat16, 32)])
+def test_fused_lstm_step_against_the_composed_step(dtype, hidden):
+    """The same step from the two dense transforms and the cell kernel: both within the storage type's bound of
+    each other, over a few steps of carried state.  (hidden = 64 has no composed form: its gate pre-activations are
+    256 wide, beyond the dense transform's widths.)"""
+    n, f_y = 5000, 2 * hidden
+    w_x = (randn((f_y, 4 * hidden), 5) / np.sqrt(f_y)).to(dtype).to(DEV)
+    w_h = (randn((hidden, 4 * hidden), 6) / np.sqrt(hidden)).to(dtype).to(DEV)
+    bias = (randn((4 * hidden,), 7) * 0.1).to(DEV)
+    state = {}
+    for fused in (True, False):
+        h = torch.zeros((n, hidden), dtype=dtype, device=DEV)
+        c = torch.zeros((n, hidden), dtype=dtype, device=DEV)
+        for t in range(3):
+            y = randn((n, f_y), 100 + t, dtype).to(DEV)
+            hn = torch.empty_like(h)
+            if fused:
+                dg.lstm_step(y, h, w_x, w_h, bias, c, hn)
+            else:
+                gx = torch.empty((n, 4 * hidden), dtype=dtype, device=DEV)
+                gh = torch.empty_like(gx)
+                dg.feature_transform(y, w_x, gx)
+                dg.feature_transform(h, w_h, gh)
+                dg.lstm_cell(gx, gh, bias, c, c, hn)
+            h = hn
+        state[fused] = (to_f64(h), to_f64(c))
+    assert_close(state[True][0], state[False][0], dtype, "fused vs composed: h", stores=9)
+    assert_close(state[True][1], state[False][1], dtype, "fused vs composed: c", stores=9)
 
 
 def test_fused_and_composed_layers_agree():
