@@ -131,8 +131,9 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 // In the fused step the nonlinearities compete with the matrix cores for issue slots (they are as many cycles as
 // the products when taken from the math library), so they are built from the hardware exponential and reciprocal:
-// sig(x) = 1 / (1 + 2^(-x log2 e)), tanh(x) = 2 sig(2x) - 1; absolute error a few 1e-7.
-__device__ __forceinline__ float fast_sigmoid(float x) { return __frcp_rn(1.0f + __expf(-x)); }
+// sig(x) = 1 / (1 + 2^(-x log2 e)), tanh(x) = 2 sig(2x) - 1; absolute error a few 1e-7.  The reciprocal is the
+// hardware's approximation (1 ulp), one instruction where a correctly rounded one is a ten-instruction division.
+__device__ __forceinline__ float fast_sigmoid(float x) { return __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
 __device__ __forceinline__ float fast_tanh(float x) { return 2.0f * fast_sigmoid(2.0f * x) - 1.0f; }
 
 constexpr int kLstmHidden = 32;      // the adjoint kernel's only width
@@ -150,46 +151,65 @@ __global__ __launch_bounds__(kLstmThreads) void lstm_step_f32_kernel(const float
     constexpr int Y_PIECES = 32 * FY / 4 / kWave;       // 16-byte pieces per lane of a tile of Y
     constexpr int S_PIECES = 32 * HID / 4 / kWave;      // ... of a tile of h or c
     static_assert(K >= 2 * HID && KH % 4 == 0, "the tile buffer also carries c and h (2 * hidden columns)");
-    __shared__ float s_w[K * G4];                       // rows 0 .. FY-1: W_x, then W_h
+    // [W_x ; W_h] with the NT tiles' values of one (k, column-in-tile) side by side: s_w[(k * 32 + i) * NT + tile] is
+    // element (k, tile * 32 + i), so one LDS read brings a k-step's operand for every tile
+    __shared__ __attribute__((aligned(16))) float s_w[K * G4];
+    __shared__ __attribute__((aligned(16))) float s_bias[G4];
     __shared__ __attribute__((aligned(16))) float s_tile[kLstmWaves][32 * LDT];
 
     const int tid = threadIdx.x;
-    for (int idx = tid; idx < K * G4; idx += kLstmThreads) s_w[idx] = idx < FY * G4 ? w_x[idx] : w_h[idx - FY * G4];
+    for (int idx = tid; idx < K * G4; idx += kLstmThreads) {
+        const int k = idx / G4, col = idx % G4;
+        s_w[(k * 32 + col % 32) * NT + col / 32] = idx < FY * G4 ? w_x[idx] : w_h[idx - FY * G4];
+    }
+    for (int idx = tid; idx < G4; idx += kLstmThreads) s_bias[idx] = bias ? bias[idx] : 0.0f;
     const int lane = tid & (kWave - 1), wave = tid / kWave;
     const int i = lane & 31, hh = lane >> 5;
     float *tile_lds = s_tile[wave];
     const int64_t stride = (int64_t)gridDim.x * kLstmWaves;
     const int64_t first = (int64_t)blockIdx.x * kLstmWaves + wave;
     __syncthreads();                                   // W is in LDS; from here on every wavefront is on its own
-    for (int64_t tile = first; tile < n_tiles; tile += stride) {
-        // ---- [Y | h_prev] tile: global -> LDS in whole lines (the other wavefront of the SIMD multiplies meanwhile)
-        const floatx4 zero = {0.f, 0.f, 0.f, 0.f};
-        floatx4 c_cur[S_PIECES];
-        {
-            floatx4 yv[Y_PIECES], hv[S_PIECES];
+    // The two wavefronts of a SIMD do the same work in the same rhythm; started together they would both multiply,
+    // then both run the cell.  The second one starts about half a tile late, so that one's products run beside the
+    // other's nonlinearities.
+    if (wave >= kLstmWaves / 2) {
+        __builtin_amdgcn_s_sleep(127);
+        __builtin_amdgcn_s_sleep(127);
+    }
+    // The rows of the next tile travel while this one is multiplied: a wavefront shares its SIMD with one other
+    // only, which cannot hide a trip to memory per tile.
+    const floatx4 zero = {0.f, 0.f, 0.f, 0.f};
+    floatx4 yv[Y_PIECES], hv[S_PIECES], cv[S_PIECES];
+    auto fetch = [&](int64_t t) {
 #pragma unroll
-            for (int q = 0; q < Y_PIECES; ++q) {
-                const int64_t piece = tile * (32 * FY / 4) + q * kWave + lane;
-                yv[q] = (tile < n_tiles && piece * 4 < n * FY) ? reinterpret_cast<const floatx4 *>(y)[piece] : zero;
-            }
-#pragma unroll
-            for (int q = 0; q < S_PIECES; ++q) {
-                const int64_t piece = tile * (32 * HID / 4) + q * kWave + lane;
-                const bool ok = tile < n_tiles && piece * 4 < n * HID;
-                hv[q] = ok ? reinterpret_cast<const floatx4 *>(h_prev)[piece] : zero;
-                c_cur[q] = ok ? reinterpret_cast<const floatx4 *>(c)[piece] : zero;
-            }
-#pragma unroll
-            for (int q = 0; q < Y_PIECES; ++q) {
-                const int e = (q * kWave + lane) * 4;
-                *reinterpret_cast<floatx4 *>(&tile_lds[(e / FY) * LDT + e % FY]) = yv[q];
-            }
-#pragma unroll
-            for (int q = 0; q < S_PIECES; ++q) {
-                const int e = (q * kWave + lane) * 4;
-                *reinterpret_cast<floatx4 *>(&tile_lds[(e / HID) * LDT + FY + e % HID]) = hv[q];
-            }
+        for (int q = 0; q < Y_PIECES; ++q) {
+            const int64_t piece = t * (32 * FY / 4) + q * kWave + lane;
+            yv[q] = (t < n_tiles && piece * 4 < n * FY) ? reinterpret_cast<const floatx4 *>(y)[piece] : zero;
         }
+#pragma unroll
+        for (int q = 0; q < S_PIECES; ++q) {
+            const int64_t piece = t * (32 * HID / 4) + q * kWave + lane;
+            const bool ok = t < n_tiles && piece * 4 < n * HID;
+            hv[q] = ok ? reinterpret_cast<const floatx4 *>(h_prev)[piece] : zero;
+            cv[q] = ok ? reinterpret_cast<const floatx4 *>(c)[piece] : zero;
+        }
+    };
+    fetch(first);
+    for (int64_t tile = first; tile < n_tiles; tile += stride) {
+        // ---- [Y | h_prev] tile: registers -> LDS in whole lines
+        floatx4 c_cur[S_PIECES];
+#pragma unroll
+        for (int q = 0; q < Y_PIECES; ++q) {
+            const int e = (q * kWave + lane) * 4;
+            *reinterpret_cast<floatx4 *>(&tile_lds[(e / FY) * LDT + e % FY]) = yv[q];
+        }
+#pragma unroll
+        for (int q = 0; q < S_PIECES; ++q) {
+            const int e = (q * kWave + lane) * 4;
+            *reinterpret_cast<floatx4 *>(&tile_lds[(e / HID) * LDT + FY + e % HID]) = hv[q];
+            c_cur[q] = cv[q];
+        }
+        fetch(tile + stride);          // another wavefront's tile: c is updated in place, but never a tile that is in flight
         wave_lds_sync();
         floatx4 a[KH / 4];
 #pragma unroll
@@ -209,11 +229,12 @@ __global__ __launch_bounds__(kLstmThreads) void lstm_step_f32_kernel(const float
 #pragma unroll
         for (int s = 0; s < KH; ++s) {
             const float xv = a[s / 4][s % 4];
+            float wv[NT];
 #pragma unroll
-            for (int g = 0; g < NT; ++g) {
-                const float wv = s_w[(hh * KH + s) * G4 + g * 32 + i];
-                acc[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(wv, xv, acc[g], 0, 0, 0);     // transposed tile g of the pre-activations
-            }
+            for (int g = 0; g < NT; ++g) wv[g] = s_w[((hh * KH + s) * 32 + i) * NT + g];   // consecutive: one read
+#pragma unroll
+            for (int g = 0; g < NT; ++g)
+                acc[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(wv[g], xv, acc[g], 0, 0, 0);   // transposed tile g of the pre-activations
         }
         wave_lds_sync();                                                      // the old cell state is in LDS
         // ---- the cell, on the accumulators: lane (i, h) owns state elements 8 m + 4 h + r of vertex i; gate g of
@@ -227,10 +248,10 @@ __global__ __launch_bounds__(kLstmThreads) void lstm_step_f32_kernel(const float
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int k = k0 + r;
-                const float ai = acc[(8 * m) / 32][4 * (((8 * m) % 32) / 8) + r] + (bias ? bias[k] : 0.0f);
-                const float af = acc[(HID + 8 * m) / 32][4 * (((HID + 8 * m) % 32) / 8) + r] + (bias ? bias[HID + k] : 0.0f);
-                const float ag = acc[(2 * HID + 8 * m) / 32][4 * (((2 * HID + 8 * m) % 32) / 8) + r] + (bias ? bias[2 * HID + k] : 0.0f);
-                const float ao = acc[(3 * HID + 8 * m) / 32][4 * (((3 * HID + 8 * m) % 32) / 8) + r] + (bias ? bias[3 * HID + k] : 0.0f);
+                const float ai = acc[(8 * m) / 32][4 * (((8 * m) % 32) / 8) + r] + s_bias[k];
+                const float af = acc[(HID + 8 * m) / 32][4 * (((HID + 8 * m) % 32) / 8) + r] + s_bias[HID + k];
+                const float ag = acc[(2 * HID + 8 * m) / 32][4 * (((2 * HID + 8 * m) % 32) / 8) + r] + s_bias[2 * HID + k];
+                const float ao = acc[(3 * HID + 8 * m) / 32][4 * (((3 * HID + 8 * m) % 32) / 8) + r] + s_bias[3 * HID + k];
                 c_new[r] = fast_sigmoid(af) * c_old[r] + fast_sigmoid(ai) * fast_tanh(ag);
                 h_new[r] = fast_sigmoid(ao) * fast_tanh(c_new[r]);
             }
@@ -273,46 +294,51 @@ __global__ __launch_bounds__(WAVES * kWave) void lstm_step_bf16_kernel(const uin
     static_assert(K >= 2 * HID && KH % 8 == 0, "the tile buffer also carries c and h (2 * hidden columns)");
     __shared__ __attribute__((aligned(16))) uint16_t s_wt[G4 * LDW];     // row j: column j of [W_x ; W_h]
     __shared__ __attribute__((aligned(16))) uint16_t s_tile[WAVES][32 * LDT];
+    __shared__ __attribute__((aligned(16))) float s_bias[G4];
 
     const int tid = threadIdx.x;
     for (int idx = tid; idx < K * G4; idx += WAVES * kWave) {
         const int k = idx / G4, j = idx % G4;
         s_wt[j * LDW + k] = k < FY ? w_x[idx] : w_h[idx - FY * G4];
     }
+    for (int idx = tid; idx < G4; idx += WAVES * kWave) s_bias[idx] = bias ? bias[idx] : 0.0f;
     const int lane = tid & (kWave - 1), wave = tid / kWave;
     const int i = lane & 31, hh = lane >> 5;
     uint16_t *tile_lds = s_tile[wave];
     const int64_t stride = (int64_t)gridDim.x * WAVES;
     const int64_t first = (int64_t)blockIdx.x * WAVES + wave;
     __syncthreads();                                   // W is in LDS; from here on every wavefront is on its own
-    for (int64_t tile = first; tile < n_tiles; tile += stride) {
-        const uintx4 zero = {0u, 0u, 0u, 0u};
-        uintx4 c_cur[S_PIECES];
-        {
-            uintx4 yv[Y_PIECES], hv[S_PIECES];
+    const uintx4 zero = {0u, 0u, 0u, 0u};
+    uintx4 yv[Y_PIECES], hv[S_PIECES], cv[S_PIECES];        // the next tile's rows, fetched while this one is multiplied
+    auto fetch = [&](int64_t t) {
 #pragma unroll
-            for (int q = 0; q < Y_PIECES; ++q) {
-                const int64_t piece = tile * (32 * FY / 8) + q * kWave + lane;
-                yv[q] = piece * 8 < n * FY ? reinterpret_cast<const uintx4 *>(y)[piece] : zero;
-            }
-#pragma unroll
-            for (int q = 0; q < S_PIECES; ++q) {
-                const int64_t piece = tile * (32 * HID / 8) + q * kWave + lane;
-                const bool ok = piece * 8 < n * HID;
-                hv[q] = ok ? reinterpret_cast<const uintx4 *>(h_prev)[piece] : zero;
-                c_cur[q] = ok ? reinterpret_cast<const uintx4 *>(c)[piece] : zero;
-            }
-#pragma unroll
-            for (int q = 0; q < Y_PIECES; ++q) {
-                const int e = (q * kWave + lane) * 8;
-                *reinterpret_cast<uintx4 *>(&tile_lds[(e / FY) * LDT + e % FY]) = yv[q];
-            }
-#pragma unroll
-            for (int q = 0; q < S_PIECES; ++q) {
-                const int e = (q * kWave + lane) * 8;
-                *reinterpret_cast<uintx4 *>(&tile_lds[(e / HID) * LDT + FY + e % HID]) = hv[q];
-            }
+        for (int q = 0; q < Y_PIECES; ++q) {
+            const int64_t piece = t * (32 * FY / 8) + q * kWave + lane;
+            yv[q] = (t < n_tiles && piece * 8 < n * FY) ? reinterpret_cast<const uintx4 *>(y)[piece] : zero;
         }
+#pragma unroll
+        for (int q = 0; q < S_PIECES; ++q) {
+            const int64_t piece = t * (32 * HID / 8) + q * kWave + lane;
+            const bool ok = t < n_tiles && piece * 8 < n * HID;
+            hv[q] = ok ? reinterpret_cast<const uintx4 *>(h_prev)[piece] : zero;
+            cv[q] = ok ? reinterpret_cast<const uintx4 *>(c)[piece] : zero;
+        }
+    };
+    fetch(first);
+    for (int64_t tile = first; tile < n_tiles; tile += stride) {
+        uintx4 c_cur[S_PIECES];
+#pragma unroll
+        for (int q = 0; q < Y_PIECES; ++q) {
+            const int e = (q * kWave + lane) * 8;
+            *reinterpret_cast<uintx4 *>(&tile_lds[(e / FY) * LDT + e % FY]) = yv[q];
+        }
+#pragma unroll
+        for (int q = 0; q < S_PIECES; ++q) {
+            const int e = (q * kWave + lane) * 8;
+            *reinterpret_cast<uintx4 *>(&tile_lds[(e / HID) * LDT + FY + e % HID]) = hv[q];
+            c_cur[q] = cv[q];
+        }
+        fetch(tile + stride);
         wave_lds_sync();
         bf16x8 a[KS];
 #pragma unroll
@@ -348,10 +374,10 @@ __global__ __launch_bounds__(WAVES * kWave) void lstm_step_bf16_kernel(const uin
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int k = k0 + r;
-                const float ai = acc[(8 * m) / 32][4 * (((8 * m) % 32) / 8) + r] + (bias ? bias[k] : 0.0f);
-                const float af = acc[(HID + 8 * m) / 32][4 * (((HID + 8 * m) % 32) / 8) + r] + (bias ? bias[HID + k] : 0.0f);
-                const float ag = acc[(2 * HID + 8 * m) / 32][4 * (((2 * HID + 8 * m) % 32) / 8) + r] + (bias ? bias[2 * HID + k] : 0.0f);
-                const float ao = acc[(3 * HID + 8 * m) / 32][4 * (((3 * HID + 8 * m) % 32) / 8) + r] + (bias ? bias[3 * HID + k] : 0.0f);
+                const float ai = acc[(8 * m) / 32][4 * (((8 * m) % 32) / 8) + r] + s_bias[k];
+                const float af = acc[(HID + 8 * m) / 32][4 * (((HID + 8 * m) % 32) / 8) + r] + s_bias[HID + k];
+                const float ag = acc[(2 * HID + 8 * m) / 32][4 * (((2 * HID + 8 * m) % 32) / 8) + r] + s_bias[2 * HID + k];
+                const float ao = acc[(3 * HID + 8 * m) / 32][4 * (((3 * HID + 8 * m) % 32) / 8) + r] + s_bias[3 * HID + k];
                 c_new[r] = fast_sigmoid(af) * c_old[r] + fast_sigmoid(ai) * fast_tanh(ag);
                 h_new[r] = fast_sigmoid(ao) * fast_tanh(c_new[r]);
             }
@@ -392,11 +418,16 @@ __global__ __launch_bounds__(kLstmThreads) void lstm_step_backward_f32_kernel(
     constexpr int S_PIECES = 32 * HID / 4 / kWave;
     constexpr int HALF_PIECES = 32 * (2 * HID) / 4 / kWave;   // 16-byte pieces per lane of half a tile of da
     static_assert(KH % 4 == 0, "operand rows are read in 16-byte pieces");
-    __shared__ float s_w[K * G4];
+    __shared__ __attribute__((aligned(16))) float s_w[K * G4];      // laid out as in the forward kernel
+    __shared__ __attribute__((aligned(16))) float s_bias[G4];
     __shared__ __attribute__((aligned(16))) float s_tile[kLstmWaves][32 * LDT];
 
     const int tid = threadIdx.x;
-    for (int idx = tid; idx < K * G4; idx += kLstmThreads) s_w[idx] = idx < FY * G4 ? w_x[idx] : w_h[idx - FY * G4];
+    for (int idx = tid; idx < K * G4; idx += kLstmThreads) {
+        const int k = idx / G4, col = idx % G4;
+        s_w[(k * 32 + col % 32) * 4 + col / 32] = idx < FY * G4 ? w_x[idx] : w_h[idx - FY * G4];
+    }
+    for (int idx = tid; idx < G4; idx += kLstmThreads) s_bias[idx] = bias ? bias[idx] : 0.0f;
     const int lane = tid & (kWave - 1), wave = tid / kWave;
     const int i = lane & 31, hh = lane >> 5;
     float *tile_lds = s_tile[wave];
@@ -456,11 +487,9 @@ __global__ __launch_bounds__(kLstmThreads) void lstm_step_backward_f32_kernel(
 #pragma unroll
         for (int s = 0; s < KH; ++s) {
             const float xv = a[s / 4][s % 4];
+            const floatx4 wv = *reinterpret_cast<const floatx4 *>(&s_w[((hh * KH + s) * 32 + i) * 4]);
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const float wv = s_w[(hh * KH + s) * G4 + g * 32 + i];
-                acc[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(wv, xv, acc[g], 0, 0, 0);     // transposed gate tile g
-            }
+            for (int g = 0; g < 4; ++g) acc[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(wv[g], xv, acc[g], 0, 0, 0);   // transposed gate tile g
         }
         wave_lds_sync();                                                      // c_prev, dh, dc are in LDS
         // ---- the cell's adjoint, on the accumulators (register 4 q + r of lane (i, h): state element 8 q + 4 h + r);
@@ -475,10 +504,10 @@ __global__ __launch_bounds__(kLstmThreads) void lstm_step_backward_f32_kernel(
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int k = k0 + r;
-                const float gi = fast_sigmoid(acc[0][4 * q + r] + (bias ? bias[k] : 0.0f));
-                const float gf = fast_sigmoid(acc[1][4 * q + r] + (bias ? bias[HID + k] : 0.0f));
-                const float gg = fast_tanh(acc[2][4 * q + r] + (bias ? bias[2 * HID + k] : 0.0f));
-                const float go = fast_sigmoid(acc[3][4 * q + r] + (bias ? bias[3 * HID + k] : 0.0f));
+                const float gi = fast_sigmoid(acc[0][4 * q + r] + s_bias[k]);
+                const float gf = fast_sigmoid(acc[1][4 * q + r] + s_bias[HID + k]);
+                const float gg = fast_tanh(acc[2][4 * q + r] + s_bias[2 * HID + k]);
+                const float go = fast_sigmoid(acc[3][4 * q + r] + s_bias[3 * HID + k]);
                 const float tc = fast_tanh(gf * c_old[r] + gi * gg);
                 const float d = dh[r] * go * (1.0f - tc * tc) + dc_in[r];
                 acc[0][4 * q + r] = d * gg * gi * (1.0f - gi);
