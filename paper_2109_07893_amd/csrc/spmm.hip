@@ -670,7 +670,7 @@ namespace {
 // by the 64 lanes together).  A row cut by the range's ends leaves a piece in the workspace; a second small
 // kernel adds a cut row's pieces in entry order.  Every sum has an order fixed by the row structure alone:
 // results repeat bit for bit.
-constexpr int kSumRange = 4096;
+constexpr int kSumRange = 2048;
 constexpr int kCoop = 64;
 
 // p_cont: piece of the row that began in an earlier range; p_own/owner: first piece of the row that begins in
