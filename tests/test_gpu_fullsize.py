@@ -374,3 +374,73 @@ def test_fused_lstm_step_and_its_adjoint_full_size():
     back = oracle.lstm_cell_backward(*args, to_f64(g_h[idx]), to_f64(dc_n[idx]))
     assert_close(to_f64(da[idx]), back[0], torch.float32, "dL/d(pre-activations), sampled rows")
     assert_close(to_f64(dc[idx]), back[3], torch.float32, "dL/dc_prev, sampled rows")
+
+
+@pytest.mark.timeout(600)
+def test_weighted_rebuild_full_size():
+    """c5's first step with a value per stored entry, 7.9 M added and deleted edges and 13 M value updates, the way
+    bench.py times it.  The structure must be the unweighted rebuild's (which the tests above compare with the oracle
+    at this size); the values are checked on 2^14 sampled rows and the 256 longest rows against the oracle, which
+    applies the same step to those rows alone; and the two ways of handing over the update list (sorted: consumed by
+    the merge; any order: a pass of its own) must agree bit for bit."""
+    import paper_2109_07893_amd as dg
+    wl = WORKLOADS["c5"]
+    dev = torch.device(DEV)
+    blk = make_block(wl, dev, gen_device=dev, T=2)
+    n, nnz1 = blk.n, blk.nnz[0]
+    ar, ac, dr, dc = blk.deltas[0]
+    gen = torch.Generator(device=dev).manual_seed(wl.seed + 17)
+    val1 = torch.rand(nnz1, generator=gen, device=dev) + 0.5
+    add_val = torch.rand(ar.numel(), generator=gen, device=dev) + 0.5
+    pos = torch.randint(0, nnz1, (nnz1 // 20,), generator=gen, device=dev).unique()
+    rows = torch.searchsorted(blk.rowptr1.to(torch.int64), pos, right=True) - 1
+    keys = (rows << 32) | blk.colidx1[pos].to(torch.int64)
+    keys = keys[~torch.isin(keys, (dr.to(torch.int64) << 32) | dc.to(torch.int64))]
+    ur, uc = (keys >> 32).to(torch.int32), (keys & 0xffffffff).to(torch.int32)
+    uv = torch.rand(ur.numel(), generator=gen, device=dev) + 2.0
+    del pos, rows, keys
+    cap = blk.nnz[1]
+    ws = torch.empty(dg.delta_rebuild_workspace(n, nnz1, ar.numel(), dr.numel()), dtype=torch.uint8, device=dev)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    out = {}
+    for merged in (True, False):
+        rpn = torch.full((n + 1,), -7, dtype=torch.int32, device=dev)
+        cin = torch.full((cap + 3,), -7, dtype=torch.int32, device=dev)
+        vn = torch.full((cap + 3,), float("nan"), device=dev)
+        got = dg.delta_rebuild_weighted(blk.rowptr1, blk.colidx1, val1, nnz1, (ar, ac, add_val), (dr, dc), (ur, uc, uv), rpn, cin, vn,
+                                        ws, flags=dg.DGNN_VALIDATE | (dg.DGNN_UPDATES_SORTED if merged else 0), d_status=status)
+        torch.cuda.synchronize()
+        assert got == cap and int(status.item()) == 0
+        assert bool((cin[cap:] == -7).all()) and bool(torch.isnan(vn[cap:]).all())      # nothing written beyond the result
+        out[merged] = (rpn, cin[:cap], vn[:cap])
+    progress("weighted rebuild: both update paths done")
+    assert torch.equal(out[True][0], out[False][0]) and torch.equal(out[True][1], out[False][1])
+    assert torch.equal(out[True][2], out[False][2])
+    # the structure: the unweighted rebuild of the same step
+    rpu = torch.empty(n + 1, dtype=torch.int32, device=dev)
+    ciu = torch.empty(cap, dtype=torch.int32, device=dev)
+    dg.delta_rebuild(blk.rowptr1, blk.colidx1, nnz1, ar, ac, ar.numel(), dr, dc, dr.numel(), rpu, ciu, None, ws)
+    assert torch.equal(rpu, out[True][0]) and torch.equal(ciu, out[True][1])
+    # the values: the oracle applies the same step to the sampled rows alone (rows do not interact in this operation:
+    # A_1 restricted to the sample, the lists restricted to the sample), and the device's rows must equal its rows
+    rp1, rpn = blk.rowptr1.cpu().numpy(), out[True][0].cpu().numpy()
+    sample = sample_rows(rpn, 1 << 14, 256, 3)
+    in_sample = np.zeros(n, bool)
+    in_sample[sample] = True
+    len1 = np.where(in_sample, np.diff(rp1), 0)
+    sub_rp = np.concatenate([[0], np.cumsum(len1)]).astype(np.int32)
+    ent = np.flatnonzero(np.repeat(in_sample, np.diff(rp1)))                     # the sampled rows' entries of A_1
+    ent_d = torch.as_tensor(ent, device=dev)
+    sub_ci, sub_val = blk.colidx1[ent_d].cpu().numpy(), val1[ent_d].cpu().numpy()
+
+    def restricted(row_t, *others):
+        keep = torch.as_tensor(in_sample, device=dev)[row_t.long()]
+        return tuple(x[keep].cpu().numpy() for x in (row_t,) + others)
+
+    progress("weighted rebuild: oracle on the sampled rows")
+    want = oracle.delta_apply_weighted(n, sub_rp, sub_ci, sub_val, add=restricted(ar, ac, add_val), dele=restricted(dr, dc),
+                                       upd=restricted(ur, uc, uv))
+    assert np.array_equal(np.diff(want[0])[sample], np.diff(rpn)[sample])
+    ent_n = torch.as_tensor(np.flatnonzero(np.repeat(in_sample, np.diff(rpn))), device=dev)
+    assert np.array_equal(out[True][1][ent_n].cpu().numpy(), want[1])
+    assert np.array_equal(out[True][2][ent_n].cpu().numpy(), want[2].astype(np.float32))
