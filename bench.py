@@ -361,7 +361,7 @@ def smoothing_steps(args, wl, blk, dev, life=4):
     e1.record()
     torch.cuda.synchronize()
     out = {"edge_life": life, "steps": rows, "csr_weighted_dinv_ms": round(e0.elapsed_time(e1), 3),
-           "note": "each step: one pass over the operands (counts and a chained scan inside the kernel); the size of the result stays on the device"}
+           "note": "each step: a count launch, two small scans and a write launch, enqueue-only; the size of the result stays on the device"}
     del snaps, bufs, ws, s
     torch.cuda.empty_cache()
     # the whole forward pass on smoothed snapshots: rebuild, sliding-window sum, normalisation, X W, aggregation
