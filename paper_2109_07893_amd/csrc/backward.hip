@@ -177,7 +177,7 @@ __global__ __launch_bounds__(kThreads) void relu_backward_kernel(const uintx4 *_
                                                                  int64_t pieces, int pieces_per_row) {
     const int64_t p = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (p >= pieces) return;
-    const uintx4 gv = g[p], zv = z[p];
+    const uintx4 gv = __builtin_nontemporal_load(g + p), zv = __builtin_nontemporal_load(z + p);   // streams: read once
     const float sc = row_scale ? row_scale[p / pieces_per_row] : 1.0f;
     uintx4 o;
     if (BF16) {
@@ -195,7 +195,7 @@ __global__ __launch_bounds__(kThreads) void relu_backward_kernel(const uintx4 *_
         for (int e = 0; e < 4; ++e)
             o[e] = __float_as_uint(__uint_as_float(zv[e]) > 0.0f ? __uint_as_float(gv[e]) * sc : 0.0f);
     }
-    out[p] = o;
+    __builtin_nontemporal_store(o, out + p);
 }
 
 template <int FIN, int FOUT, bool BF16>

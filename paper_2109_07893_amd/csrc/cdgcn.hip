@@ -24,12 +24,12 @@ __global__ __launch_bounds__(kThreads) void concat_relu_kernel(const uintx4 *__r
     if (p >= pieces) return;
     const int64_t row = p / (p0 + p1);
     const int k = (int)(p - row * (p0 + p1));
-    const uintx4 raw = k < p0 ? y0[row * p0 + k] : y1[row * p1 + (k - p0)];
+    const uintx4 raw = __builtin_nontemporal_load(k < p0 ? y0 + row * p0 + k : y1 + row * p1 + (k - p0));   // streams
     float v[NV];
     Pack<BF16>::unpack(v, raw);
 #pragma unroll
     for (int e = 0; e < NV; ++e) v[e] = fmaxf(v[e], 0.0f);
-    out[p] = Pack<BF16>::pack(v);
+    __builtin_nontemporal_store(Pack<BF16>::pack(v), out + p);
 }
 
 // One 16-byte piece of the state per lane; the four gates of that piece lie `hp` pieces apart in a row of gates.

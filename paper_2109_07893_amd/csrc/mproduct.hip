@@ -44,7 +44,7 @@ template <> struct Vec<false> {
         for (int e = 0; e < 4; ++e) v[e] = t[e];
     }
     static __device__ __forceinline__ void store(char *p, const float (&v)[4]) {
-        *reinterpret_cast<floatx4 *>(p) = floatx4{v[0], v[1], v[2], v[3]};
+        __builtin_nontemporal_store(floatx4{v[0], v[1], v[2], v[3]}, reinterpret_cast<floatx4 *>(p));   // every frame is read once and written once: a stream
     }
     static __device__ __forceinline__ void unpack(float (&v)[4], uintx4 t) {
 #pragma unroll
@@ -65,7 +65,7 @@ template <> struct Vec<true> {
         uintx4 t;
 #pragma unroll
         for (int e = 0; e < 4; ++e) t[e] = f32_to_bf16(v[2 * e]) | (f32_to_bf16(v[2 * e + 1]) << 16);
-        *reinterpret_cast<uintx4 *>(p) = t;
+        __builtin_nontemporal_store(t, reinterpret_cast<uintx4 *>(p));
     }
     static __device__ __forceinline__ void unpack(float (&v)[8], uintx4 t) {
 #pragma unroll
@@ -153,14 +153,14 @@ __global__ __launch_bounds__(kThreads) void mproduct_shift_kernel(const char *z,
         const int h = REVERSE ? j - 1 : halo.count - j;
         if (h >= 0 && h < halo.count) ring[j - 1] = *reinterpret_cast<const uintx4 *>(halo.frames + (int64_t)h * frame_bytes + piece * 16);
     }
-    uintx4 next = *reinterpret_cast<const uintx4 *>(src + (int64_t)frame_of(0) * frame_bytes);
+    uintx4 next = __builtin_nontemporal_load(reinterpret_cast<const uintx4 *>(src + (int64_t)frame_of(0) * frame_bytes));
 #pragma unroll 1
     for (int i = 0; i < T; ++i) {
         const int t = frame_of(i);
 #pragma unroll
         for (int j = RING - 1; j > 0; --j) ring[j] = ring[j - 1];
         ring[0] = next;
-        next = *reinterpret_cast<const uintx4 *>(src + (int64_t)frame_of(min(i + 1, T - 1)) * frame_bytes);   // before the store: y may be z
+        next = __builtin_nontemporal_load(reinterpret_cast<const uintx4 *>(src + (int64_t)frame_of(min(i + 1, T - 1)) * frame_bytes));   // before the store: y may be z
         const int terms = REVERSE ? min(w, T - t + halo.count) : min(w, t + 1 + halo.count);
         float out[NV];
 #pragma unroll
@@ -218,13 +218,13 @@ __global__ __launch_bounds__(kThreads) void mproduct_uniform_kernel(const char *
 
     uintx4 ahead[D];
 #pragma unroll
-    for (int d = 0; d < D; ++d) ahead[d] = *reinterpret_cast<const uintx4 *>(src + (int64_t)frame_of(min(d, T - 1)) * frame_bytes);
+    for (int d = 0; d < D; ++d) ahead[d] = __builtin_nontemporal_load(reinterpret_cast<const uintx4 *>(src + (int64_t)frame_of(min(d, T - 1)) * frame_bytes));
 
     // one step i (0-based); `slot` holds the frame of step i - W, `queued` the frame of step i
     auto step = [&](int i, uintx4 &slot, uintx4 &queued) {
         const int t = frame_of(i);
         const uintx4 cur = queued;
-        queued = *reinterpret_cast<const uintx4 *>(src + (int64_t)frame_of(min(i + D, T - 1)) * frame_bytes);   // before the store: y may be z
+        queued = __builtin_nontemporal_load(reinterpret_cast<const uintx4 *>(src + (int64_t)frame_of(min(i + D, T - 1)) * frame_bytes));   // before the store: y may be z
         float in[NV], old[NV], out[NV];
         Vec<BF16>::unpack(in, cur);
         Vec<BF16>::unpack(old, slot);

@@ -53,7 +53,7 @@ template <> struct Piece<false> {
         for (int e = 0; e < 4; ++e) acc[e] = fmaf(s, v[e], acc[e]);
     }
     static __device__ __forceinline__ void store(void *p, const float (&acc)[4]) {
-        *static_cast<floatx4 *>(p) = floatx4{acc[0], acc[1], acc[2], acc[3]};
+        __builtin_nontemporal_store(floatx4{acc[0], acc[1], acc[2], acc[3]}, static_cast<floatx4 *>(p));   // written once, read by a later kernel
     }
 };
 template <> struct Piece<true> {
@@ -70,7 +70,7 @@ template <> struct Piece<true> {
         uintx4 v;
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = f32_to_bf16(acc[2 * e]) | (f32_to_bf16(acc[2 * e + 1]) << 16);
-        *static_cast<uintx4 *>(p) = v;
+        __builtin_nontemporal_store(v, static_cast<uintx4 *>(p));
     }
 };
 
@@ -157,7 +157,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(4, 8))) v
 #pragma unroll
         for (int i = 0; i < CPL; ++i) {
             const int idx = e0 + g * kPer + sub * CPL + i;
-            c_next[i] = idx < e_end ? colidx[idx] : 0;
+            c_next[i] = idx < e_end ? __builtin_nontemporal_load(colidx + idx) : 0;   // a stream: the caches are for rows of H
         }
         if (SCALE_V) {
 #pragma unroll
