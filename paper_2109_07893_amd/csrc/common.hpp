@@ -81,10 +81,9 @@ __device__ __forceinline__ int wave_find_row(const int32_t *__restrict__ rowptr,
 // Orders the LDS traffic of ONE wavefront: what its lanes have written to LDS before is visible to all of its
 // lanes after.  No s_barrier: other wavefronts of the workgroup are not waited for, so wavefronts that work on
 // private LDS tiles can drift apart (one loads while another multiplies).  The fences are of wavefront scope: the
-// LDS serves one wavefront's accesses in the order it issued them, so nothing has to be waited for -- in particular
-// not the wavefront's loads from global memory that are still in flight (a workgroup-scope fence waits for those as
-// well, which would undo every prefetch issued before it); the fences only keep the compiler from moving LDS accesses
-// across this point.
+// LDS serves one wavefront's accesses in the order it issued them, so nothing has to be waited for (a workgroup-scope
+// fence drains the wavefront's LDS queue first); the fences only keep the compiler from moving LDS accesses across
+// this point.  Loads from global memory that are in flight stay in flight either way.
 __device__ __forceinline__ void wave_lds_sync() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
