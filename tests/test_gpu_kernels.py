@@ -155,6 +155,32 @@ def test_rebuild_stretches_of_very_short_rows():
     assert np.allclose(dinv, 1.0 / np.sqrt(np.diff(erp)), rtol=3e-7, atol=0)
 
 
+def test_rebuild_rows_that_hold_their_diagonal_alone():
+    """Four thousand consecutive rows of one entry each: a 512-entry piece of the merge's stream meets 512 rows, the
+    most it can, and needs the pointer of a 513th.  Some of those rows gain entries, and lose them again in a second
+    step; rows with entries sit before and behind the stretch."""
+    n = 12_000
+    rng = np.random.default_rng(33)
+    rows, cols = [np.arange(n)], [np.arange(n)]
+    busy = np.concatenate([np.arange(0, 3000), np.arange(7000, n)])
+    rows.append(rng.choice(busy, 40_000)); cols.append(rng.integers(0, n, 40_000))
+    rp, ci = oracle.csr_from_edges(n, np.concatenate(rows).astype(np.int32), np.concatenate(cols).astype(np.int32))
+    assert np.all(np.diff(rp)[3000:7000] == 1)
+    lone = rng.choice(np.arange(3000, 7000), 900, replace=False)
+    adds = sorted({(int(r), int(c)) for r in lone for c in rng.integers(0, n, 3) if int(c) != int(r)})
+    a = coo(adds)
+    erp, eci = oracle.delta_apply(n, rp, ci, *a, *EMPTY)
+    grp, gci, dinv, status, _ = gpu_rebuild(n, rp, ci, *a, *EMPTY)
+    assert status == 0
+    assert np.array_equal(grp, erp) and np.array_equal(gci, eci)
+    assert np.allclose(dinv, 1.0 / np.sqrt(np.diff(erp)), rtol=3e-7, atol=0)
+    back_rp, back_ci = oracle.delta_apply(n, erp, eci, *EMPTY, *a)
+    grp, gci, _, status, _ = gpu_rebuild(n, erp, eci, *EMPTY, *a)
+    assert status == 0
+    assert np.array_equal(grp, back_rp) and np.array_equal(gci, back_ci)
+    assert np.array_equal(back_rp, rp) and np.array_equal(back_ci, ci)
+
+
 def test_rebuild_many_changes_in_one_row_tile():
     """More than 16 list entries per row over a whole tile of 1024 rows (the row-pointer kernel then counts
     by searching instead of walking the list), next to tiles that get nothing."""
