@@ -167,12 +167,14 @@ int dgnn_spmm(int64_t n, int64_t nnz, const int32_t *rowptr, const int32_t *coli
 
 /*
  * dgnn_spmm for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
- * harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-for-bit the same result as dgnn_spmm, but no
- * workspace argument: the carry records live in a device array of fixed size inside the library
- * (dgnn_spmm_static_limit() bytes, 32 MiB, held by every GPU the library runs on until the process ends).
- * DGNN_ERR_CAPACITY if the records of this call, (16 + 8 f) bytes per 8192 stored entries and never fewer than
- * 16385 of them, exceed that limit (f = 32: beyond 1.0e9 stored entries; f = 128: beyond 2.6e8); nothing is
- * enqueued then.  Neither this call nor anything it calls allocates or frees; the
+ * harnesses that forbid hipMalloc.  Same arguments and same kernels as dgnn_spmm, but no workspace argument: the carry
+ * records, (16 + 8 f) bytes per range of stored entries that one wavefront streams, live in a device array of fixed
+ * size inside the library (dgnn_spmm_static_limit() bytes, 32 MiB, held by every GPU the library runs on until the
+ * process ends).  Where dgnn_spmm's ranges (2048 entries, fewer on small snapshots) would need more records than
+ * the array holds, this call makes its ranges longer, up to 8192 entries: rows that a range's end cuts are then
+ * summed in other pieces, so the result equals dgnn_spmm's bit for bit when the ranges are the same and within the
+ * rounding of the fp32 sums otherwise.  DGNN_ERR_CAPACITY if ranges of 8192 entries are still too many
+ * (f = 32: beyond 1.0e9 stored entries; f = 128: beyond 2.6e8); nothing is enqueued then.  Neither this call nor anything it calls allocates or frees; the
  * first call on a device looks up the array's address on that device, once.  All calls on one GPU share the one array:
  * calls that overlap in time on the same GPU (two streams, two threads) race on it, and the caller must order them.
  */

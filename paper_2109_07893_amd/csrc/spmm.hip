@@ -34,8 +34,10 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBatch = 8;            // gathers issued together by a lane group
 constexpr int kPer = 32;             // entries a lane group walks per sub-tile (one mask word)
-constexpr int kMaxRange = 8192;      // entries streamed by one wavefront, at most
-constexpr int kTargetWaves = 16384;  // ranges shrink on small inputs so that about this many wavefronts exist
+constexpr int kMaxRange = 2048;      // entries streamed by one wavefront, at most: many short-lived wavefronts stream
+                                     // faster than few long-lived ones (8192: +2.5 % on the largest workloads)
+constexpr int kTargetWaves = 65536;  // ranges shrink on small inputs so that about this many wavefronts exist (16384: +4 %)
+constexpr int kLongestRange = 8192;  // what a caller with little room for records may stretch a range to
 constexpr int kXcds = 8;             // accelerator dies of an MI355X, each with its own L2
 constexpr int kXcdChunk = 16;        // consecutive ranges that go to the same XCD
 constexpr int kVmcntZero = 0x0F70;   // s_waitcnt operand: all vector memory loads returned, other counters untouched
@@ -495,10 +497,17 @@ struct Workspace {
 };
 
 // Entries per wavefront: a multiple of the sub-tile, at most kMaxRange, smaller when the input is small.
-int range_length(int64_t nnz, int sub_tile) {
+// max_ranges > 0: the caller has room for that many range records only; ranges are stretched to fit, up to
+// kLongestRange (0 is returned if even that does not do).
+int range_length(int64_t nnz, int sub_tile, int64_t max_ranges = 0) {
     int64_t len = (nnz + kTargetWaves - 1) / kTargetWaves;
     len = (len + sub_tile - 1) / sub_tile * sub_tile;
     if (len > kMaxRange) len = kMaxRange;
+    if (max_ranges > 0 && (nnz + len - 1) / len > max_ranges) {
+        len = (nnz + max_ranges - 1) / max_ranges;
+        len = (len + sub_tile - 1) / sub_tile * sub_tile;
+        if (len > kLongestRange) return 0;
+    }
     return (int)len;
 }
 
@@ -520,10 +529,9 @@ size_t workspace_layout(int64_t nnz, int32_t f, Workspace *ws, void *base, int64
 }
 
 template <int LPR, bool BF16>
-int launch(int64_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *dinv, bool scale_v,
+int launch(int64_t n, int64_t nnz, int range_len, const int32_t *rowptr, const int32_t *colidx, const float *dinv, bool scale_v,
            const void *h, void *z, int relu, const Workspace &ws, hipStream_t s, const float *vals = nullptr) {
     constexpr int G = 256 / LPR;
-    const int range_len = range_length(nnz, (kWave / LPR) * kPer);
     const int ranges = (int)((nnz + range_len - 1) / range_len);
     const int grid = (ranges + kXcds * kXcdChunk - 1) / (kXcds * kXcdChunk) * (kXcds * kXcdChunk);   // whole chunk rounds
     if (scale_v)
@@ -551,38 +559,40 @@ extern "C" int dgnn_spmm_workspace(int64_t n, int64_t nnz, int32_t f, size_t *by
 
 namespace {
 
-// Ranges of one call: what launch() below will use for this snapshot, width and storage type.
-int64_t ranges_of_call(int64_t nnz, int32_t f, dgnn_dtype dt) {
+// Entries per range of one call for this snapshot, width and storage type (max_ranges as in range_length).
+int range_length_of_call(int64_t nnz, int32_t f, dgnn_dtype dt, int64_t max_ranges = 0) {
     const int lpr = dt == DGNN_F32 ? f / 4 : f / 8;
-    const int range_len = range_length(nnz, (kWave / lpr) * kPer);
-    return (nnz + range_len - 1) / range_len;
+    return range_length(nnz, (kWave / lpr) * kPer, max_ranges);
 }
 
 int spmm(int64_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *dinv, const float *vals,
          const void *h, int32_t f, void *z, dgnn_dtype dt, uint32_t flags, uint32_t allowed, void *ws, size_t ws_bytes,
-         void *stream, bool exact_layout = false) {
+         void *stream, int64_t max_ranges = 0) {
     if (!rowptr || !colidx || !h || !z || !ws) return DGNN_ERR_NULL;
     if (n <= 0 || nnz <= 0 || !supported_width(f) || (flags & ~allowed)) return DGNN_ERR_SHAPE;
     if (dt != DGNN_F32 && dt != DGNN_BF16) return DGNN_ERR_SHAPE;
     if (!fits_index(n + 1) || !fits_index(nnz)) return DGNN_ERR_OVERFLOW;
     if (!aligned16(h) || !aligned16(z) || !aligned16(ws)) return DGNN_ERR_ALIGN;
     if (h == z) return DGNN_ERR_ALIAS;
+    // max_ranges > 0: the records of exactly this call, laid out for its own number of ranges
+    const int range_len = range_length_of_call(nnz, f, dt, max_ranges);
+    if (range_len <= 0) return DGNN_ERR_CAPACITY;
     Workspace w;
-    if (ws_bytes < workspace_layout(nnz, f, &w, ws, exact_layout ? ranges_of_call(nnz, f, dt) : 0)) return DGNN_ERR_CAPACITY;
+    if (ws_bytes < workspace_layout(nnz, f, &w, ws, max_ranges > 0 ? (nnz + range_len - 1) / range_len : 0)) return DGNN_ERR_CAPACITY;
     hipStream_t s = (hipStream_t)stream;
     const int relu = (flags & DGNN_RELU) ? 1 : 0;
     const bool scale_v = vals != nullptr || (dinv != nullptr && !(flags & DGNN_H_PRESCALED));
     const int lpr = dt == DGNN_F32 ? f / 4 : f / 8;   // lanes per feature row, 16 bytes each
     const bool bf = dt == DGNN_BF16;
     switch (lpr) {
-        case 2: return launch<2, true>(n, nnz, rowptr, colidx, dinv, scale_v, h, z, relu, w, s, vals);
-        case 4: return bf ? launch<4, true>(n, nnz, rowptr, colidx, dinv, scale_v, h, z, relu, w, s, vals)
-                          : launch<4, false>(n, nnz, rowptr, colidx, dinv, scale_v, h, z, relu, w, s, vals);
-        case 8: return bf ? launch<8, true>(n, nnz, rowptr, colidx, dinv, scale_v, h, z, relu, w, s, vals)
-                          : launch<8, false>(n, nnz, rowptr, colidx, dinv, scale_v, h, z, relu, w, s, vals);
-        case 16: return bf ? launch<16, true>(n, nnz, rowptr, colidx, dinv, scale_v, h, z, relu, w, s, vals)
-                           : launch<16, false>(n, nnz, rowptr, colidx, dinv, scale_v, h, z, relu, w, s, vals);
-        case 32: return launch<32, false>(n, nnz, rowptr, colidx, dinv, scale_v, h, z, relu, w, s, vals);
+        case 2: return launch<2, true>(n, nnz, range_len, rowptr, colidx, dinv, scale_v, h, z, relu, w, s, vals);
+        case 4: return bf ? launch<4, true>(n, nnz, range_len, rowptr, colidx, dinv, scale_v, h, z, relu, w, s, vals)
+                          : launch<4, false>(n, nnz, range_len, rowptr, colidx, dinv, scale_v, h, z, relu, w, s, vals);
+        case 8: return bf ? launch<8, true>(n, nnz, range_len, rowptr, colidx, dinv, scale_v, h, z, relu, w, s, vals)
+                          : launch<8, false>(n, nnz, range_len, rowptr, colidx, dinv, scale_v, h, z, relu, w, s, vals);
+        case 16: return bf ? launch<16, true>(n, nnz, range_len, rowptr, colidx, dinv, scale_v, h, z, relu, w, s, vals)
+                           : launch<16, false>(n, nnz, range_len, rowptr, colidx, dinv, scale_v, h, z, relu, w, s, vals);
+        case 32: return launch<32, false>(n, nnz, range_len, rowptr, colidx, dinv, scale_v, h, z, relu, w, s, vals);
         default: return DGNN_ERR_SHAPE;
     }
 }
@@ -640,14 +650,16 @@ extern "C" int dgnn_spmm_static(int64_t n, int64_t nnz, const int32_t *rowptr, c
     if (n <= 0 || nnz <= 0 || !supported_width(f) || (flags & ~(DGNN_RELU | DGNN_H_PRESCALED))) return DGNN_ERR_SHAPE;
     if (dt != DGNN_F32 && dt != DGNN_BF16) return DGNN_ERR_SHAPE;
     if (!fits_index(n + 1) || !fits_index(nnz)) return DGNN_ERR_OVERFLOW;
-    if (workspace_layout(nnz, f, nullptr, nullptr, ranges_of_call(nnz, f, dt)) > kStaticScratchBytes) return DGNN_ERR_CAPACITY;
+    // as many ranges as the array has room for records of: ranges grow longer where the usual ones would be too many
+    const int64_t max_ranges = (int64_t)((kStaticScratchBytes - 512) / (sizeof(RangeRec) + 2 * (size_t)f * sizeof(float)));
+    if (range_length_of_call(nnz, f, dt, max_ranges) <= 0) return DGNN_ERR_CAPACITY;
     void *ptr = nullptr;
     const int rc = static_scratch(&ptr);
     if (rc != DGNN_OK) return rc;
     // every range writes its record and the carries its flags announce before the second kernel reads them, so nothing
     // in the array has to start at zero; what the previous call left there is never read
     return spmm(n, nnz, rowptr, colidx, dinv, nullptr, h, f, z, dt, flags, DGNN_RELU | DGNN_H_PRESCALED, ptr,
-                kStaticScratchBytes, stream, /*exact_layout=*/true);
+                kStaticScratchBytes, stream, max_ranges);
 }
 
 extern "C" int dgnn_spmm_weighted(int64_t n, int64_t nnz, const int32_t *rowptr, const int32_t *colidx, const float *val,

@@ -62,6 +62,21 @@ def test_two_calls_in_a_row_second_one_smaller(dtype, f):
         assert_close(to_f64(z_static), expect, dtype, f"dgnn_spmm_static n={n} f={f}")
 
 
+def test_more_ranges_than_the_scratch_array_has_records_for():
+    """8.8 M stored entries at width 128 in fp32: the usual ranges (192 entries at this size and width) would need 46
+    thousand records of 1040 bytes, half as many again as the array holds, so this entry point makes its ranges longer.  Rows cut by a range's end are then summed in other pieces than in
+    dgnn_spmm: same result within the rounding of the sums, and within the bound against the oracle."""
+    n, f = 1 << 19, 128
+    rp, ci = power_law_snapshot(n, [(3, 50_000), (77_777, 9_000)], seed=9)
+    assert (16 + 8 * f) * (ci.size // 192) > dg.spmm_static_limit()
+    h = torch.randn((n, f), generator=torch.Generator().manual_seed(5))
+    z_ws, z_static = both_ways(rp, ci, h, dg.DGNN_RELU)
+    assert_close(to_f64(z_static), to_f64(z_ws), torch.float32, "dgnn_spmm_static against dgnn_spmm")
+    rows = np.unique(np.concatenate([np.random.default_rng(1).choice(n, 4096, replace=False), [3, 77_777]]))
+    expect = oracle.spmm(rp, ci, to_f64(h), relu=True, rows=rows)
+    assert_close(to_f64(z_static)[rows], expect, torch.float32, "dgnn_spmm_static, stretched ranges")
+
+
 def test_sizes_beyond_the_scratch_array_are_refused():
     limit = dg.spmm_static_limit()
     assert limit == 32 << 20
