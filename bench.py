@@ -179,8 +179,8 @@ def cpu_baseline(wl, blk, first, budget_s):
 
 def gather_working_sets(args, wl, blk, dev):
     """dgnn_spmm on the first snapshot's row structure with the column indices replaced, so that the gathered rows of H
-    come from working sets of known size: inside one L2 (1 MB), inside the Infinity Cache (32 MB), or spread uniformly
-    over the whole of H.  Tells what bounds the aggregation on the real columns: an extra figure."""
+    come from working sets of known size: inside one L2 (1 MB), inside the Infinity Cache (32 and 128 MB), beyond it
+    (512 MB), or spread uniformly over the whole of H.  Tells what bounds the aggregation on the real columns: an extra figure."""
     import torch
     import paper_2109_07893_amd as dg
     n, f, nnz = blk.n, blk.f, blk.nnz[0]
@@ -189,15 +189,15 @@ def gather_working_sets(args, wl, blk, dev):
     dinv = torch.empty(n, dtype=torch.float32, device=dev)
     dg.csr_dinv(blk.rowptr1, dinv)
     ws = torch.empty(dg.spmm_workspace(n, nnz, f), dtype=torch.uint8, device=dev)
-    idx = torch.arange(nnz, device=dev, dtype=torch.int64)
     row_bytes = f * h.element_size()
     patterns = [("the workload's columns", blk.colidx1)]
-    for size in (1 << 20, 32 << 20):
-        m = max(1, min(n, size // row_bytes))
-        patterns.append((f"columns inside {size >> 20} MB of H", ((idx * 2654435761) % m).to(torch.int32)))
     gen = torch.Generator(device=dev).manual_seed(wl.seed)
+    # uniformly random inside the working set: every wavefront, and so every L2, sees all of it (columns that follow
+    # the entry index would hand each L2 a share of its own)
+    for size in (1 << 20, 32 << 20, 128 << 20, 512 << 20):
+        m = max(1, min(n, size // row_bytes))
+        patterns.append((f"columns inside {size >> 20} MB of H", torch.randint(0, m, (nnz,), generator=gen, device=dev, dtype=torch.int32)))
     patterns.append((f"uniformly random columns ({n * row_bytes / 1e9:.2f} GB of H)", torch.randint(0, n, (nnz,), generator=gen, device=dev, dtype=torch.int32)))
-    del idx
     out = {"entries": nnz, "gathered_bytes": nnz * row_bytes, "cases": []}
     for label, cols in patterns:
         for _ in range(2):
