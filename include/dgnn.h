@@ -427,6 +427,17 @@ int dgnn_concat_relu(const void *y0, int32_t f0, const void *y1, int32_t f1, voi
                      dgnn_dtype dt, void *stream);
 
 /*
+ * The same Y formed in one pass, without materialising Y1: out [n][f_in + f_out] = relu([x | x W]) with
+ * x [n][f_in] = Y0 and w [f_in][f_out], the ReLU and the concatenation folded into the kernel that forms the product.
+ * Supported where both tiles and W fit on chip together: fp32 with f_in in {16, 32, 64} and f_out in {32, 64};
+ * bf16 with f_in, f_out in {32, 64} and f_in + f_out <= 128 (DGNN_ERR_SHAPE otherwise: use dgnn_feature_transform and
+ * dgnn_concat_relu).  Same values as that composition (bf16: the product is rounded to bf16 once either way).
+ * out must not be x.  Errors as dgnn_feature_transform.
+ */
+int dgnn_transform_concat_relu(const void *x, int64_t n, int32_t f_in, const void *w, int32_t f_out, void *out,
+                               dgnn_dtype dt, void *stream);
+
+/*
  * LSTM cell.  gates_x = X_t W_x and gates_h = h_{t-1} W_h, both [n][4 * hidden] with the gates in the order
  * (input, forget, cell, output); bias fp32 [4 * hidden] or NULL.  With a = gates_x + gates_h + bias:
  *     c_next = sig(a_f) * c_prev + sig(a_i) * tanh(a_g),     h_next = sig(a_o) * tanh(c_next).

@@ -17,7 +17,7 @@ from .binding import (  # noqa: F401
     delta_rebuild_weighted, spmm_weighted, csr_weighted_dinv, csr_weighted_dinv_workspace, csr_combine,
     csr_combine_workspace,
     # CD-GCN layer and the LSTM over weights
-    concat_relu, lstm_cell, lstm_step, lstm_step_supported, lstm_cell_backward, lstm_step_backward,
+    concat_relu, transform_concat_relu, transform_concat_relu_supported, lstm_cell, lstm_step, lstm_step_supported, lstm_cell_backward, lstm_step_backward,
     lstm_step_backward_supported, concat_relu_backward, bias_grad, bias_grad_workspace, add,
     DGNN_VALIDATE, DGNN_UPDATES_SORTED, DGNN_RELU, DGNN_H_PRESCALED, DGNN_F32, DGNN_BF16,
 )

@@ -26,7 +26,7 @@ EXPORTS = (
     "dgnn_strerror", "dgnn_csr_validate", "dgnn_csr_dinv", "dgnn_delta_h2d", "dgnn_delta_rebuild_workspace",
     "dgnn_delta_rebuild", "dgnn_feature_transform", "dgnn_spmm_workspace", "dgnn_spmm", "dgnn_spmm_static_limit",
     "dgnn_spmm_static", "dgnn_mproduct",
-    "dgnn_delta_rebuild_weighted", "dgnn_spmm_weighted", "dgnn_csr_combine_workspace", "dgnn_csr_combine", "dgnn_csr_weighted_dinv_workspace", "dgnn_csr_weighted_dinv", "dgnn_concat_relu", "dgnn_lstm_cell", "dgnn_lstm_step", "dgnn_lstm_cell_backward", "dgnn_lstm_step_backward", "dgnn_concat_relu_backward", "dgnn_bias_grad_workspace", "dgnn_bias_grad", "dgnn_add",
+    "dgnn_delta_rebuild_weighted", "dgnn_spmm_weighted", "dgnn_csr_combine_workspace", "dgnn_csr_combine", "dgnn_csr_weighted_dinv_workspace", "dgnn_csr_weighted_dinv", "dgnn_concat_relu", "dgnn_transform_concat_relu", "dgnn_lstm_cell", "dgnn_lstm_step", "dgnn_lstm_cell_backward", "dgnn_lstm_step_backward", "dgnn_concat_relu_backward", "dgnn_bias_grad_workspace", "dgnn_bias_grad", "dgnn_add",
     "dgnn_csr_transpose_workspace", "dgnn_csr_transpose", "dgnn_coo_transpose_workspace", "dgnn_coo_transpose",
     "dgnn_mproduct_backward", "dgnn_mproduct_block", "dgnn_mproduct_backward_block", "dgnn_relu_backward", "dgnn_weight_grad_workspace", "dgnn_weight_grad", "dgnn_input_grad",
 )
@@ -118,6 +118,7 @@ def load_library():
     lib.dgnn_coo_transpose_workspace.argtypes = [_i64, _i64, ctypes.POINTER(_sz)]
     lib.dgnn_coo_transpose.argtypes = [_i64, _i64, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     lib.dgnn_concat_relu.argtypes = [_vp, _i32, _vp, _i32, _vp, _i64, ctypes.c_int, _vp]
+    lib.dgnn_transform_concat_relu.argtypes = [_vp, _i64, _i32, _vp, _i32, _vp, ctypes.c_int, _vp]
     lib.dgnn_lstm_cell.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _i32, ctypes.c_int, _vp]
     lib.dgnn_lstm_cell_backward.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i32, ctypes.c_int, _vp]
     lib.dgnn_lstm_step_backward.argtypes = [_vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i32, ctypes.c_int, _vp]
@@ -428,6 +429,26 @@ def concat_relu(y0: torch.Tensor, y1: torch.Tensor, out: torch.Tensor) -> None:
     if y1.shape[0] != n or tuple(out.shape) != (n, f0 + f1) or y1.dtype != y0.dtype or out.dtype != y0.dtype:
         raise ValueError("shape mismatch in concat_relu")
     _check(load_library().dgnn_concat_relu(_ptr(y0), f0, _ptr(y1), f1, _ptr(out), n, dt, _stream(y0)), "dgnn_concat_relu")
+
+
+def transform_concat_relu_supported(x: torch.Tensor, f_out: int) -> bool:
+    f_in = x.shape[1]
+    if x.dtype == torch.float32:
+        return f_in in (16, 32, 64) and f_out in (32, 64)
+    return x.dtype == torch.bfloat16 and f_in in (32, 64) and f_out in (32, 64) and f_in + f_out <= 128
+
+
+def transform_concat_relu(x: torch.Tensor, w: torch.Tensor, out: torch.Tensor) -> None:
+    """out = relu([x | x W]) in one pass (the CD-GCN layer's Y from Y0)."""
+    dt = _dtype_code(x)
+    n, f_in = x.shape
+    f_out = w.shape[1]
+    if w.dtype != x.dtype or out.dtype != x.dtype or w.shape[0] != f_in or tuple(out.shape) != (n, f_in + f_out):
+        raise ValueError("shape or dtype mismatch in transform_concat_relu")
+    if not (x.is_contiguous() and w.is_contiguous() and out.is_contiguous()):
+        raise ValueError("transform_concat_relu needs contiguous tensors")
+    _check(load_library().dgnn_transform_concat_relu(_ptr(x), n, f_in, _ptr(w), f_out, _ptr(out), dt, _stream(x)),
+           "dgnn_transform_concat_relu")
 
 
 def lstm_cell(gates_x, gates_h, bias, c_prev, c_next, h_next) -> None:

@@ -2,7 +2,7 @@
 per snapshot the GCN operation with skip connection, then one LSTM step per vertex,
 
     Y0 = A~_t X_t           dgnn_spmm (no ReLU) on rows pre-scaled by dinv      Y1 = Y0 W      dgnn_feature_transform
-    Y  = relu(Y0 o Y1)      dgnn_concat_relu
+    Y  = relu(Y0 o Y1)      dgnn_concat_relu           (both in one pass where the widths allow: dgnn_transform_concat_relu)
     a  = Y W_x + h W_h + b  two dgnn_feature_transform     (h, c) <- LSTM cell      dgnn_lstm_cell
 
 Buffers and call order only; the arithmetic is in the HIP kernels."""
@@ -50,10 +50,7 @@ class CdgcnLayer(BlockRunner):
         with self._stage("spmm"):
             B.spmm(self.rowptr[slot], self.colidx[slot], blk.nnz[t - 1], self.dinv[slot], self.xs, self.y0, self.ws_spmm,
                    flags=B.DGNN_H_PRESCALED)
-        with self._stage("feature_transform"):
-            B.feature_transform(self.y0, self.w, self.y1)
-        with self._stage("concat_relu"):
-            B.concat_relu(self.y0, self.y1, self.y)
+        self.form_y()
         h_prev = self.h0 if t == 1 else self.h_all[t - 2]
         if self.fused and B.lstm_step_supported(self.y, self.hidden):
             with self._stage("lstm_step"):
@@ -64,6 +61,17 @@ class CdgcnLayer(BlockRunner):
             B.feature_transform(h_prev, self.w_h, self.gh)
         with self._stage("lstm_cell"):
             B.lstm_cell(self.gx, self.gh, self.bias, self.c, self.c, self.h_all[t - 1])
+
+    def form_y(self) -> None:
+        """Y = relu(Y0 o Y0 W) from self.y0: one kernel where the library has it, else the product and the concatenation."""
+        if self.fused and B.transform_concat_relu_supported(self.y0, self.w.shape[1]):
+            with self._stage("transform_concat_relu"):
+                B.transform_concat_relu(self.y0, self.w, self.y)
+            return
+        with self._stage("feature_transform"):
+            B.feature_transform(self.y0, self.w, self.y1)
+        with self._stage("concat_relu"):
+            B.concat_relu(self.y0, self.y1, self.y)
 
     def run(self) -> torch.Tensor:
         """The whole block from the initial state (h, c) = 0; returns h_t for t = 1..T."""
@@ -141,10 +149,7 @@ class CdgcnTrainer(CdgcnLayer):
         with self._stage("spmm"):
             B.spmm(self.rowptr[slot], self.colidx[slot], blk.nnz[t - 1], self.dinv[slot], self.xs, self.y0, self.ws_spmm,
                    flags=B.DGNN_H_PRESCALED)
-        with self._stage("feature_transform"):
-            B.feature_transform(self.y0, self.w, self.y1)
-        with self._stage("concat_relu"):
-            B.concat_relu(self.y0, self.y1, self.y)
+        self.form_y()
 
     def forward(self) -> torch.Tensor:
         blk = self.blk

@@ -117,16 +117,20 @@ __global__ __launch_bounds__(kThreads) void xw_f32_kernel(const float *__restric
 // in LDS with padded rows and picked up again in operand order; the result tile takes the same way back, so
 // the stores are whole lines too.  The product is computed transposed, (X W)^T = W^T X^T, which leaves lane
 // (i, h) with row i of the result and four consecutive columns in every four accumulator registers.
-template <int FIN, int FOUT>
+// CONCAT: the output row is relu([x | x W]), FIN + FOUT wide (the skip connection of the CD-GCN layer, Section
+// "CD-GCN"): the result tile is laid down behind the input tile, which is still in LDS, and both leave together.
+template <int FIN, int FOUT, bool CONCAT>
 __global__ __launch_bounds__(kThreads) void xw_f32_staged_kernel(const float *__restrict__ x, const float *__restrict__ w,
                                                                  const float *__restrict__ row_scale, float *__restrict__ h,
                                                                  int64_t n, int64_t n_tiles, int wt) {
     constexpr int NT = FOUT / 32;
     constexpr int KH = FIN / 2;
     constexpr int FMAX = FIN > FOUT ? FIN : FOUT;
-    constexpr int LDT = FMAX + 4;                    // padded tile row (floats): 16 bytes of padding
+    constexpr int ROFF = CONCAT ? FIN : 0;           // where the result begins in a staged row
+    constexpr int OUTW = CONCAT ? FIN + FOUT : FOUT; // width of an output row
+    constexpr int LDT = (CONCAT ? FIN + FOUT : FMAX) + 4;   // padded tile row (floats): 16 bytes of padding
     constexpr int IN_PIECES = 32 * FIN / 4 / kWave;  // 16-byte pieces per lane of an input tile
-    constexpr int OUT_PIECES = 32 * FOUT / 4 / kWave;
+    constexpr int OUT_PIECES = 32 * OUTW / 4 / kWave;
     static_assert(FOUT % 32 == 0 && FIN % 8 == 0, "staged kernel needs whole 32-column tiles");
     __shared__ float s_w[FIN * FOUT];
     __shared__ __attribute__((aligned(16))) float s_tile[kWavesPerBlock][32 * LDT];
@@ -186,7 +190,7 @@ __global__ __launch_bounds__(kThreads) void xw_f32_staged_kernel(const float *__
         for (int jt = 0; jt < NT; ++jt)
 #pragma unroll
             for (int g = 0; g < 4; ++g)
-                *reinterpret_cast<floatx4 *>(&tile_lds[i * LDT + jt * 32 + 8 * g + 4 * hh]) =
+                *reinterpret_cast<floatx4 *>(&tile_lds[i * LDT + ROFF + jt * 32 + 8 * g + 4 * hh]) =
                     floatx4{acc[jt][4 * g] * scale, acc[jt][4 * g + 1] * scale, acc[jt][4 * g + 2] * scale,
                             acc[jt][4 * g + 3] * scale};
         wave_lds_sync();
@@ -194,10 +198,12 @@ __global__ __launch_bounds__(kThreads) void xw_f32_staged_kernel(const float *__
 #pragma unroll
             for (int q = 0; q < OUT_PIECES; ++q) {
                 const int e = (q * kWave + lane) * 4;
-                const int64_t piece = tile * (32 * FOUT / 4) + q * kWave + lane;
-                if (piece * 4 < n * FOUT)
-                    __builtin_nontemporal_store(*reinterpret_cast<const floatx4 *>(&tile_lds[(e / FOUT) * LDT + e % FOUT]),
-                                                reinterpret_cast<floatx4 *>(h) + piece);   // whole lines, read by a later kernel: 4 % faster than plain stores
+                const int64_t piece = tile * (32 * OUTW / 4) + q * kWave + lane;
+                if (piece * 4 < n * OUTW) {
+                    floatx4 v = *reinterpret_cast<const floatx4 *>(&tile_lds[(e / OUTW) * LDT + e % OUTW]);
+                    if (CONCAT) v = floatx4{fmaxf(v[0], 0.0f), fmaxf(v[1], 0.0f), fmaxf(v[2], 0.0f), fmaxf(v[3], 0.0f)};
+                    __builtin_nontemporal_store(v, reinterpret_cast<floatx4 *>(h) + piece);   // whole lines, read by a later kernel: 4 % faster than plain stores
+                }
             }
         }
         wave_lds_sync();                                                      // the tile buffer is reused
@@ -286,7 +292,7 @@ __global__ __launch_bounds__(kThreads) void xw_bf16_kernel(const uint16_t *__res
 
 // bf16 with both widths at least 32: as the staged fp32 kernel, tiles pass through LDS so that every global
 // access is a run of whole lines, and the transposed product leaves four consecutive columns per lane.
-template <int FIN, int FOUT>
+template <int FIN, int FOUT, bool CONCAT>
 __global__ __launch_bounds__(kThreads) void xw_bf16_staged_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ w,
                                                                   const float *__restrict__ row_scale, uint16_t *__restrict__ h,
                                                                   int64_t n, int64_t n_tiles, int wt) {
@@ -296,9 +302,11 @@ __global__ __launch_bounds__(kThreads) void xw_bf16_staged_kernel(const uint16_t
     constexpr int KS = KH / 8;
     constexpr int LDW = FIN + 8;                     // padded row of W^T (bf16 values)
     constexpr int FMAX = FIN > FOUT ? FIN : FOUT;
-    constexpr int LDT = FMAX + 8;                    // padded tile row
+    constexpr int ROFF = CONCAT ? FIN : 0;           // as in the fp32 kernel
+    constexpr int OUTW = CONCAT ? FIN + FOUT : FOUT;
+    constexpr int LDT = (CONCAT ? FIN + FOUT : FMAX) + 8;   // padded tile row
     constexpr int IN_PIECES = 32 * FIN / 8 / kWave;  // 16-byte pieces per lane of an input tile
-    constexpr int OUT_PIECES = 32 * FOUT / 8 / kWave;
+    constexpr int OUT_PIECES = 32 * OUTW / 8 / kWave;
     static_assert(FOUT % 32 == 0 && FIN % 32 == 0, "staged kernel needs whole 32-column tiles");
     __shared__ __attribute__((aligned(16))) uint16_t s_wt[FOUT * LDW];
     __shared__ __attribute__((aligned(16))) uint16_t s_tile[kWavesPerBlock][32 * LDT];
@@ -361,7 +369,7 @@ __global__ __launch_bounds__(kThreads) void xw_bf16_staged_kernel(const uint16_t
                 for (int g = 0; g < 4; ++g) {
                     const uint32_t lo = f32_to_bf16(acc[jj][4 * g] * scale) | (f32_to_bf16(acc[jj][4 * g + 1] * scale) << 16);
                     const uint32_t hi = f32_to_bf16(acc[jj][4 * g + 2] * scale) | (f32_to_bf16(acc[jj][4 * g + 3] * scale) << 16);
-                    *reinterpret_cast<uint2 *>(&tile_lds[i * LDT + (j0 + jj) * 32 + 8 * g + 4 * hh]) = make_uint2(lo, hi);
+                    *reinterpret_cast<uint2 *>(&tile_lds[i * LDT + ROFF + (j0 + jj) * 32 + 8 * g + 4 * hh]) = make_uint2(lo, hi);
                 }
             __builtin_amdgcn_sched_barrier(0);   // keep the column groups apart: their accumulators share registers
         }
@@ -370,10 +378,15 @@ __global__ __launch_bounds__(kThreads) void xw_bf16_staged_kernel(const uint16_t
 #pragma unroll
             for (int q = 0; q < OUT_PIECES; ++q) {
                 const int e = (q * kWave + lane) * 8;
-                const int64_t piece = tile * (32 * FOUT / 8) + q * kWave + lane;
-                if (piece * 8 < n * FOUT)
-                    __builtin_nontemporal_store(*reinterpret_cast<const uintx4 *>(&tile_lds[(e / FOUT) * LDT + e % FOUT]),
-                                                reinterpret_cast<uintx4 *>(h) + piece);
+                const int64_t piece = tile * (32 * OUTW / 8) + q * kWave + lane;
+                if (piece * 8 < n * OUTW) {
+                    uintx4 v = *reinterpret_cast<const uintx4 *>(&tile_lds[(e / OUTW) * LDT + e % OUTW]);
+                    if (CONCAT) {      // a bf16 with its sign bit set becomes zero (a negative zero too)
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) v[c] = ((v[c] & 0x8000u) ? 0u : (v[c] & 0xffffu)) | ((v[c] & 0x80000000u) ? 0u : (v[c] & 0xffff0000u));
+                    }
+                    __builtin_nontemporal_store(v, reinterpret_cast<uintx4 *>(h) + piece);
+                }
             }
         }
         wave_lds_sync();                                                      // the tile buffer is reused
@@ -399,14 +412,14 @@ int launch(const void *x, const void *w, int wt, const float *row_scale, void *h
     };
     if (dt == DGNN_F32) {
         if constexpr (FIN <= 64 && FOUT <= 64 && FOUT % 32 == 0)   // both tiles and W fit in LDS
-            hipLaunchKernelGGL((xw_f32_staged_kernel<FIN, FOUT>), grid(xw_f32_staged_kernel<FIN, FOUT>), dim3(kThreads), 0, s,
+            hipLaunchKernelGGL((xw_f32_staged_kernel<FIN, FOUT, false>), grid(xw_f32_staged_kernel<FIN, FOUT, false>), dim3(kThreads), 0, s,
                                static_cast<const float *>(x), static_cast<const float *>(w), row_scale, static_cast<float *>(h), n, n_tiles, wt);
         else
             hipLaunchKernelGGL((xw_f32_kernel<FIN, FOUT>), grid(xw_f32_kernel<FIN, FOUT>), dim3(kThreads), 0, s,
                                static_cast<const float *>(x), static_cast<const float *>(w), row_scale, static_cast<float *>(h), n, n_tiles, wt);
     } else {
         if constexpr (FIN % 32 == 0 && FOUT % 32 == 0)
-            hipLaunchKernelGGL((xw_bf16_staged_kernel<FIN, FOUT>), grid(xw_bf16_staged_kernel<FIN, FOUT>), dim3(kThreads), 0, s,
+            hipLaunchKernelGGL((xw_bf16_staged_kernel<FIN, FOUT, false>), grid(xw_bf16_staged_kernel<FIN, FOUT, false>), dim3(kThreads), 0, s,
                                static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(w), row_scale,
                                static_cast<uint16_t *>(h), n, n_tiles, wt);
         else
@@ -416,6 +429,46 @@ int launch(const void *x, const void *w, int wt, const float *row_scale, void *h
     }
     DGNN_RETURN_IF_LAUNCH_FAILED();
     return DGNN_OK;
+}
+
+// out = relu([x | x W]) where both tiles of a wavefront and W fit in LDS together; other width pairs are refused.
+template <int FIN, int FOUT>
+int launch_concat(const void *x, const void *w, void *out, int64_t n, dgnn_dtype dt, hipStream_t s) {
+    const int64_t n_tiles = (n + 31) / 32;
+    const int64_t needed = (n_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
+    const int64_t elem = dt == DGNN_F32 ? 4 : 2;
+    const int64_t w_bytes = (int64_t)FIN * FOUT * elem, tile_bytes = 32 * (int64_t)(2 * FIN + FOUT) * elem;
+    const int64_t tiles_per_wave = w_bytes <= 4096 ? std::max<int64_t>(1, 8192 / tile_bytes) : w_bytes <= 8192 ? 4 : 0;
+    auto grid = [&](auto kernel) {      // as in launch(): short-lived workgroups when W is cheap to stage again
+        const int64_t resident = resident_workgroups(kernel, kThreads, 1024);
+        const int64_t many = tiles_per_wave > 0 ? (needed + tiles_per_wave - 1) / tiles_per_wave : 0;
+        return dim3((unsigned)(many >= 4 * resident ? many : std::min(needed, resident)));
+    };
+    if (dt == DGNN_F32) {
+        if constexpr (FIN <= 64 && FOUT <= 64 && FOUT % 32 == 0)
+            hipLaunchKernelGGL((xw_f32_staged_kernel<FIN, FOUT, true>), grid(xw_f32_staged_kernel<FIN, FOUT, true>), dim3(kThreads), 0, s,
+                               static_cast<const float *>(x), static_cast<const float *>(w), nullptr, static_cast<float *>(out), n, n_tiles, 0);
+        else
+            return DGNN_ERR_SHAPE;
+    } else {
+        if constexpr (FIN % 32 == 0 && FOUT % 32 == 0 && FIN + FOUT <= 128)
+            hipLaunchKernelGGL((xw_bf16_staged_kernel<FIN, FOUT, true>), grid(xw_bf16_staged_kernel<FIN, FOUT, true>), dim3(kThreads), 0, s,
+                               static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(w), nullptr, static_cast<uint16_t *>(out), n,
+                               n_tiles, 0);
+        else
+            return DGNN_ERR_SHAPE;
+    }
+    DGNN_RETURN_IF_LAUNCH_FAILED();
+    return DGNN_OK;
+}
+
+template <int FIN>
+int launch_concat_out(int32_t f_out, const void *x, const void *w, void *out, int64_t n, dgnn_dtype dt, hipStream_t s) {
+    switch (f_out) {
+        case 32: return launch_concat<FIN, 32>(x, w, out, n, dt, s);
+        case 64: return launch_concat<FIN, 64>(x, w, out, n, dt, s);
+        default: return DGNN_ERR_SHAPE;
+    }
 }
 
 template <int FIN>
@@ -464,4 +517,23 @@ extern "C" int dgnn_feature_transform(const void *x, int64_t n, int32_t f_in, co
 extern "C" int dgnn_input_grad(const void *g, int64_t n, int32_t f_out, const void *w, int32_t f_in,
                                const float *row_scale, void *dx, dgnn_dtype dt, void *stream) {
     return transform(g, n, f_out, w, 1, f_in, row_scale, dx, dt, stream);
+}
+
+// Y = relu([X | X W]): the dense transform with the skip connection of the CD-GCN layer's GCN operation (Section
+// "CD-GCN") and its ReLU folded into the kernel that forms X W, so that X W itself never travels.
+extern "C" int dgnn_transform_concat_relu(const void *x, int64_t n, int32_t f_in, const void *w, int32_t f_out, void *out,
+                                          dgnn_dtype dt, void *stream) {
+    if (!x || !w || !out) return DGNN_ERR_NULL;
+    if (n <= 0 || !supported_width(f_in) || !supported_width(f_out)) return DGNN_ERR_SHAPE;
+    if (dt != DGNN_F32 && dt != DGNN_BF16) return DGNN_ERR_SHAPE;
+    if (!fits_index(n)) return DGNN_ERR_OVERFLOW;
+    if (!aligned16(x) || !aligned16(out)) return DGNN_ERR_ALIGN;
+    if (x == out) return DGNN_ERR_ALIAS;
+    hipStream_t s = (hipStream_t)stream;
+    switch (f_in) {
+        case 16: return launch_concat_out<16>(f_out, x, w, out, n, dt, s);
+        case 32: return launch_concat_out<32>(f_out, x, w, out, n, dt, s);
+        case 64: return launch_concat_out<64>(f_out, x, w, out, n, dt, s);
+        default: return DGNN_ERR_SHAPE;
+    }
 }

@@ -212,6 +212,13 @@ def test_cdgcn_argument_errors(lib):
     assert f(FAKE, 24, FAKE, 32, FAKE + 4096, 10, 0, None) == -2
     assert f(FAKE, 32, FAKE, 32, FAKE, 10, 0, None) == -5
     assert f(FAKE, 32, FAKE + 4, 32, FAKE + 4096, 10, 0, None) == -7
+    f = lib.dgnn_transform_concat_relu
+    assert f(None, 10, 32, FAKE, 32, FAKE + 4096, 0, None) == -1 and f(FAKE, 10, 32, FAKE, 32, None, 0, None) == -1
+    assert f(FAKE, 0, 32, FAKE, 32, FAKE + 4096, 0, None) == -2 and f(FAKE, 10, 24, FAKE, 32, FAKE + 4096, 0, None) == -2
+    assert f(FAKE, 10, 128, FAKE, 32, FAKE + 4096, 0, None) == -2          # a width pair it has no kernel for
+    assert f(FAKE, 10, 32, FAKE, 16, FAKE + 4096, 0, None) == -2 and f(FAKE, 10, 64, FAKE, 128, FAKE + 4096, 1, None) == -2
+    assert f(FAKE, 10, 32, FAKE, 32, FAKE + 4096, 7, None) == -2
+    assert f(FAKE, 10, 32, FAKE, 32, FAKE, 0, None) == -5 and f(FAKE + 4, 10, 32, FAKE, 32, FAKE + 4096, 0, None) == -7
     f = lib.dgnn_lstm_cell
     assert f(FAKE, FAKE, None, None, FAKE, FAKE + 64, 10, 32, 0, None) == -1
     assert f(FAKE, FAKE + 64, None, FAKE + 128, FAKE + 128, FAKE + 256, 10, 20, 0, None) == -2

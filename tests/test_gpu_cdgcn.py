@@ -34,6 +34,37 @@ def test_concat_relu(dtype, f0, f1):
     assert np.array_equal(to_f64(out), want)          # nothing is computed: exact
 
 
+@pytest.mark.parametrize("dtype,f_in,f_out", [(torch.float32, 16, 32), (torch.float32, 32, 32), (torch.float32, 32, 64),
+                                              (torch.float32, 64, 64), (torch.float32, 64, 32), (torch.bfloat16, 32, 32),
+                                              (torch.bfloat16, 64, 64), (torch.bfloat16, 32, 64), (torch.bfloat16, 64, 32)])
+@pytest.mark.parametrize("n", [1, 33, 4097, 150_001])
+def test_transform_concat_relu(dtype, f_in, f_out, n):
+    """Y = relu([Y0 | Y0 W]) in one pass against the definition, and against the product followed by the concatenation:
+    the left part is a copy under the ReLU (exact), the right part the same product (fp32: same kernel arithmetic,
+    bit for bit; bf16: rounded to bf16 once either way, bit for bit as well)."""
+    assert dg.transform_concat_relu_supported(torch.empty((1, f_in), dtype=dtype), f_out)
+    x = randn((n, f_in), n + f_in, dtype)
+    w = (randn((f_in, f_out), 3) / np.sqrt(f_in)).to(dtype)
+    out = torch.full((n, f_in + f_out), float("nan"), dtype=dtype, device=DEV)
+    dg.transform_concat_relu(x.to(DEV), w.to(DEV), out)
+    want = np.maximum(np.concatenate([to_f64(x), oracle.xw(to_f64(x), to_f64(w))], axis=1), 0.0)
+    assert np.array_equal(to_f64(out)[:, :f_in], want[:, :f_in])
+    assert_close(to_f64(out), want, dtype, f"relu([x | x W]) {f_in}->{f_out} n={n}")
+    y1 = torch.empty((n, f_out), dtype=dtype, device=DEV)
+    two = torch.empty_like(out)
+    dg.feature_transform(x.to(DEV), w.to(DEV), y1)
+    dg.concat_relu(x.to(DEV), y1, two)
+    assert torch.equal(out.view(torch.uint8), two.view(torch.uint8))
+
+
+def test_transform_concat_relu_refuses_other_widths():
+    assert not dg.transform_concat_relu_supported(torch.empty((1, 128)), 32)
+    assert not dg.transform_concat_relu_supported(torch.empty((1, 64), dtype=torch.bfloat16), 128)
+    x = torch.zeros((8, 128), device=DEV)
+    with pytest.raises(dg.DgnnError):
+        dg.transform_concat_relu(x, torch.zeros((128, 32), device=DEV), torch.zeros((8, 160), device=DEV))
+
+
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("hidden", WIDTHS)
 @pytest.mark.parametrize("with_bias", [False, True])
