@@ -554,6 +554,165 @@ __global__ __launch_bounds__(kLstmThreads) void lstm_step_backward_f32_kernel(
     }
 }
 
+// The adjoint for bf16 storage, hidden = 32: products as in lstm_step_bf16_kernel, the cell's backward formulas in fp32
+// on the accumulators; the two summands of dL/dh stay apart until they are added in fp32.
+template <int FY>
+__global__ __launch_bounds__(kLstmThreads) void lstm_step_backward_bf16_kernel(
+    const uint16_t *__restrict__ y, const uint16_t *__restrict__ h_prev, const uint16_t *__restrict__ w_x,
+    const uint16_t *__restrict__ w_h, const float *__restrict__ bias, const uint16_t *__restrict__ c_prev,
+    const uint16_t *__restrict__ dh_a, const uint16_t *__restrict__ dh_b, const uint16_t *dc_next, uint16_t *__restrict__ da,
+    uint16_t *dc_prev, int64_t n, int64_t n_tiles) {
+    constexpr int HID = kLstmHidden, G4 = 4 * HID;
+    constexpr int K = FY + HID, KH = K / 2, KS = KH / 8;
+    constexpr int LDW = K + 8;
+    constexpr int LDT = (K > 4 * HID ? K : 4 * HID) + 8;      // the tile buffer also carries c_prev, the two dh and dc side by side
+    constexpr int Y_PIECES = 32 * FY / 8 / kWave;
+    constexpr int S_PIECES = 32 * HID / 8 / kWave;
+    constexpr int HALF_PIECES = 32 * (2 * HID) / 8 / kWave;   // 16-byte pieces per lane of half a tile of da
+    static_assert(KH % 8 == 0, "operand rows are read in 16-byte pieces");
+    __shared__ __attribute__((aligned(16))) uint16_t s_wt[G4 * LDW];
+    __shared__ __attribute__((aligned(16))) float s_bias[G4];
+    __shared__ __attribute__((aligned(16))) uint16_t s_tile[kLstmWaves][32 * LDT];
+
+    const int tid = threadIdx.x;
+    for (int idx = tid; idx < K * G4; idx += kLstmThreads) {
+        const int k = idx / G4, j = idx % G4;
+        s_wt[j * LDW + k] = k < FY ? w_x[idx] : w_h[idx - FY * G4];
+    }
+    for (int idx = tid; idx < G4; idx += kLstmThreads) s_bias[idx] = bias ? bias[idx] : 0.0f;
+    const int lane = tid & (kWave - 1), wave = tid / kWave;
+    const int i = lane & 31, hh = lane >> 5;
+    uint16_t *tile_lds = s_tile[wave];
+    const int64_t stride = (int64_t)gridDim.x * kLstmWaves;
+    const int64_t first = (int64_t)blockIdx.x * kLstmWaves + wave;
+    __syncthreads();
+    auto unpack4 = [](uint2 r, float (&v)[4]) {
+        v[0] = bf16_to_f32(r.x & 0xffffu); v[1] = bf16_to_f32(r.x >> 16);
+        v[2] = bf16_to_f32(r.y & 0xffffu); v[3] = bf16_to_f32(r.y >> 16);
+    };
+    auto pack4 = [](const float (&v)[4]) {
+        return make_uint2(f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16), f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16));
+    };
+    for (int64_t tile = first; tile < n_tiles; tile += stride) {
+        const uintx4 zero = {0u, 0u, 0u, 0u};
+        uintx4 c_cur[S_PIECES], dha_cur[S_PIECES], dhb_cur[S_PIECES], dc_cur[S_PIECES];
+        {
+            uintx4 yv[Y_PIECES], hv[S_PIECES];
+#pragma unroll
+            for (int q = 0; q < Y_PIECES; ++q) {
+                const int64_t piece = tile * (32 * FY / 8) + q * kWave + lane;
+                yv[q] = piece * 8 < n * FY ? reinterpret_cast<const uintx4 *>(y)[piece] : zero;
+            }
+#pragma unroll
+            for (int q = 0; q < S_PIECES; ++q) {
+                const int64_t piece = tile * (32 * HID / 8) + q * kWave + lane;
+                const bool ok = piece * 8 < n * HID;
+                hv[q] = ok ? reinterpret_cast<const uintx4 *>(h_prev)[piece] : zero;
+                c_cur[q] = ok ? reinterpret_cast<const uintx4 *>(c_prev)[piece] : zero;
+                dha_cur[q] = (ok && dh_a) ? reinterpret_cast<const uintx4 *>(dh_a)[piece] : zero;
+                dhb_cur[q] = (ok && dh_b) ? reinterpret_cast<const uintx4 *>(dh_b)[piece] : zero;
+                dc_cur[q] = (ok && dc_next) ? reinterpret_cast<const uintx4 *>(dc_next)[piece] : zero;
+            }
+#pragma unroll
+            for (int q = 0; q < Y_PIECES; ++q) {
+                const int e = (q * kWave + lane) * 8;
+                *reinterpret_cast<uintx4 *>(&tile_lds[(e / FY) * LDT + e % FY]) = yv[q];
+            }
+#pragma unroll
+            for (int q = 0; q < S_PIECES; ++q) {
+                const int e = (q * kWave + lane) * 8;
+                *reinterpret_cast<uintx4 *>(&tile_lds[(e / HID) * LDT + FY + e % HID]) = hv[q];
+            }
+        }
+        wave_lds_sync();
+        bf16x8 a[KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) a[s] = *reinterpret_cast<const bf16x8 *>(&tile_lds[i * LDT + hh * KH + s * 8]);
+        wave_lds_sync();                                                      // every lane has its operands
+        // the tile buffer now takes c_prev, dh (two summands) and dc in four stretches of `hidden` columns
+#pragma unroll
+        for (int q = 0; q < S_PIECES; ++q) {
+            const int e = (q * kWave + lane) * 8;
+            uint16_t *row = &tile_lds[(e / HID) * LDT + e % HID];
+            *reinterpret_cast<uintx4 *>(row) = c_cur[q];
+            *reinterpret_cast<uintx4 *>(row + HID) = dha_cur[q];
+            *reinterpret_cast<uintx4 *>(row + 2 * HID) = dhb_cur[q];
+            *reinterpret_cast<uintx4 *>(row + 3 * HID) = dc_cur[q];
+        }
+        floatx16 acc[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[g][v] = 0.0f;
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const bf16x8 wv = *reinterpret_cast<const bf16x8 *>(&s_wt[(g * 32 + i) * LDW + hh * KH + s * 8]);
+                acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, a[s], acc[g], 0, 0, 0);    // transposed gate tile g
+            }
+        wave_lds_sync();                                                      // c_prev, dh, dc are in LDS
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int k0 = 8 * q + 4 * hh;
+            float c_old[4], dha[4], dhb[4], dc_in[4], dc_out[4];
+            unpack4(*reinterpret_cast<const uint2 *>(&tile_lds[i * LDT + k0]), c_old);
+            unpack4(*reinterpret_cast<const uint2 *>(&tile_lds[i * LDT + HID + k0]), dha);
+            unpack4(*reinterpret_cast<const uint2 *>(&tile_lds[i * LDT + 2 * HID + k0]), dhb);
+            unpack4(*reinterpret_cast<const uint2 *>(&tile_lds[i * LDT + 3 * HID + k0]), dc_in);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int k = k0 + r;
+                const float dh = dha[r] + dhb[r];
+                const float gi = fast_sigmoid(acc[0][4 * q + r] + s_bias[k]);
+                const float gf = fast_sigmoid(acc[1][4 * q + r] + s_bias[HID + k]);
+                const float gg = fast_tanh(acc[2][4 * q + r] + s_bias[2 * HID + k]);
+                const float go = fast_sigmoid(acc[3][4 * q + r] + s_bias[3 * HID + k]);
+                const float tc = fast_tanh(gf * c_old[r] + gi * gg);
+                const float d = dh * go * (1.0f - tc * tc) + dc_in[r];
+                acc[0][4 * q + r] = d * gg * gi * (1.0f - gi);
+                acc[1][4 * q + r] = d * c_old[r] * gf * (1.0f - gf);
+                acc[2][4 * q + r] = d * gi * (1.0f - gg * gg);
+                acc[3][4 * q + r] = dh * tc * go * (1.0f - go);
+                dc_out[r] = d * gf;
+            }
+            *reinterpret_cast<uint2 *>(&tile_lds[i * LDT + k0]) = pack4(dc_out);         // over c_prev: this lane alone read it
+        }
+        wave_lds_sync();
+#pragma unroll
+        for (int q = 0; q < S_PIECES; ++q) {
+            const int e = (q * kWave + lane) * 8;
+            const int64_t piece = tile * (32 * HID / 8) + q * kWave + lane;
+            if (piece * 8 < n * HID)
+                reinterpret_cast<uintx4 *>(dc_prev)[piece] = *reinterpret_cast<const uintx4 *>(&tile_lds[(e / HID) * LDT + e % HID]);
+        }
+        // da leaves in two halves of two gates each, as in the fp32 kernel
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            wave_lds_sync();                                                  // the buffer's previous contents have been read
+#pragma unroll
+            for (int g = 0; g < 2; ++g)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const floatx16 &src = acc[2 * half + g];
+                    const float v[4] = {src[4 * q], src[4 * q + 1], src[4 * q + 2], src[4 * q + 3]};
+                    *reinterpret_cast<uint2 *>(&tile_lds[i * LDT + g * HID + 8 * q + 4 * hh]) = pack4(v);
+                }
+            wave_lds_sync();
+#pragma unroll
+            for (int q = 0; q < HALF_PIECES; ++q) {
+                const int e = (q * kWave + lane) * 8;                          // element of the 32 x 64 half tile
+                const int r = e / (2 * HID), col = e % (2 * HID);
+                const int64_t row = tile * 32 + r;
+                if (row < n)
+                    *reinterpret_cast<uintx4 *>(&da[row * G4 + half * 2 * HID + col]) =
+                        *reinterpret_cast<const uintx4 *>(&tile_lds[r * LDT + col]);
+            }
+        }
+        wave_lds_sync();                                                      // the tile buffer is reused
+    }
+}
+
 template <int FY, int HID>
 int launch_lstm_step(const void *y, const void *h_prev, const void *w_x, const void *w_h, const float *bias, void *c,
                      void *h_next, int64_t n, hipStream_t s) {
@@ -619,7 +778,7 @@ extern "C" int dgnn_lstm_step_backward(const void *y, int32_t f_y, const void *h
                                        void *stream) {
     if (!y || !h_prev || !w_x || !w_h || !c_prev || !da || !dc_prev) return DGNN_ERR_NULL;
     if (!dh_a && !dh_b && !dc_next) return DGNN_ERR_NULL;
-    if (n <= 0 || hidden != kLstmHidden || dt != DGNN_F32 || (f_y != 32 && f_y != 64)) return DGNN_ERR_SHAPE;
+    if (n <= 0 || hidden != kLstmHidden || (dt != DGNN_F32 && dt != DGNN_BF16) || (f_y != 32 && f_y != 64)) return DGNN_ERR_SHAPE;
     if (!fits_index(n)) return DGNN_ERR_OVERFLOW;
     for (const void *p : {y, h_prev, c_prev, dh_a, dh_b, dc_next, (const void *)da, (const void *)dc_prev})
         if (p && !aligned16(p)) return DGNN_ERR_ALIGN;
@@ -628,16 +787,21 @@ extern "C" int dgnn_lstm_step_backward(const void *y, int32_t f_y, const void *h
         return DGNN_ERR_ALIAS;                                     // dc_prev may be dc_next: a tile is read before it is written
     const int64_t n_tiles = (n + 31) / 32;
     const int64_t needed = (n_tiles + kLstmWaves - 1) / kLstmWaves;
-    auto launch = [&](auto kernel) {
+    auto launch = [&](auto kernel, auto elem) {
+        typedef decltype(elem) E;
         const int64_t resident = resident_workgroups(kernel, kLstmThreads, 256);
         const unsigned blocks = (unsigned)(needed < resident ? needed : resident);
-        hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kLstmThreads), 0, (hipStream_t)stream, static_cast<const float *>(y),
-                           static_cast<const float *>(h_prev), static_cast<const float *>(w_x), static_cast<const float *>(w_h),
-                           bias, static_cast<const float *>(c_prev), static_cast<const float *>(dh_a),
-                           static_cast<const float *>(dh_b), static_cast<const float *>(dc_next), static_cast<float *>(da),
-                           static_cast<float *>(dc_prev), n, n_tiles);
+        hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kLstmThreads), 0, (hipStream_t)stream, static_cast<const E *>(y),
+                           static_cast<const E *>(h_prev), static_cast<const E *>(w_x), static_cast<const E *>(w_h),
+                           bias, static_cast<const E *>(c_prev), static_cast<const E *>(dh_a),
+                           static_cast<const E *>(dh_b), static_cast<const E *>(dc_next), static_cast<E *>(da),
+                           static_cast<E *>(dc_prev), n, n_tiles);
     };
-    if (f_y == 64) launch(lstm_step_backward_f32_kernel<64>); else launch(lstm_step_backward_f32_kernel<32>);
+    if (dt == DGNN_F32) {
+        if (f_y == 64) launch(lstm_step_backward_f32_kernel<64>, float()); else launch(lstm_step_backward_f32_kernel<32>, float());
+    } else {
+        if (f_y == 64) launch(lstm_step_backward_bf16_kernel<64>, uint16_t()); else launch(lstm_step_backward_bf16_kernel<32>, uint16_t());
+    }
     DGNN_RETURN_IF_LAUNCH_FAILED();
     return DGNN_OK;
 }

@@ -321,7 +321,7 @@ def test_lstm_step_backward_argument_errors(lib):
                  p["dt"], None)
 
     assert call(y=None) == -1 and call(da=None) == -1 and call(dh=None) == -1
-    assert call(f_y=16) == -2 and call(hidden=64) == -2 and call(dt=1) == -2
+    assert call(f_y=16) == -2 and call(hidden=64) == -2 and call(dt=2) == -2 and call(dt=1, hidden=64) == -2
     assert call(da=a[0]) == -5 and call(dc=a[5]) == -5
     assert call(c=a[4] + 4) == -7
 

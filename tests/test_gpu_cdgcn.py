@@ -232,43 +232,47 @@ def test_bias_grad(dtype, f, n):
     assert torch.equal(db, first)                     # fixed order of summation
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("f_y", [32, 64])
 @pytest.mark.parametrize("n", [1, 31, 32, 33, 4097, 20_011])
 @pytest.mark.parametrize("carried", [False, True])
-def test_fused_lstm_step_backward(n, carried, f_y):
+def test_fused_lstm_step_backward(n, carried, f_y, dtype):
     hidden = 32
-    y, h_prev = randn((n, f_y), 1), randn((n, hidden), 2)
-    w_x, w_h = randn((f_y, 4 * hidden), 3) / 8, randn((hidden, 4 * hidden), 4) / 6
+    assert dg.lstm_step_backward_supported(torch.empty((1, f_y), dtype=dtype), hidden)
+    y, h_prev = randn((n, f_y), 1, dtype), randn((n, hidden), 2, dtype)
+    w_x, w_h = (randn((f_y, 4 * hidden), 3) / 8).to(dtype), (randn((hidden, 4 * hidden), 4) / 6).to(dtype)
     bias = randn((4 * hidden,), 5) * 0.1
-    c_prev, g_h = randn((n, hidden), 6), randn((n, hidden), 7)
-    dh_c, dc_n = (randn((n, hidden), 8), randn((n, hidden), 9)) if carried else (None, None)
-    da = torch.full((n, 4 * hidden), float("nan"), device=DEV)
-    dc = dc_n.to(DEV) if carried else torch.full((n, hidden), float("nan"), device=DEV)
+    c_prev, g_h = randn((n, hidden), 6, dtype), randn((n, hidden), 7, dtype)
+    dh_c, dc_n = (randn((n, hidden), 8, dtype), randn((n, hidden), 9, dtype)) if carried else (None, None)
+    da = torch.full((n, 4 * hidden), float("nan"), dtype=dtype, device=DEV)
+    dc = dc_n.to(DEV) if carried else torch.full((n, hidden), float("nan"), dtype=dtype, device=DEV)
     dg.lstm_step_backward(y.to(DEV), h_prev.to(DEV), w_x.to(DEV), w_h.to(DEV), bias.to(DEV), c_prev.to(DEV), g_h.to(DEV),
                           dh_c.to(DEV) if carried else None, dc if carried else None, da, dc)
     dh = to_f64(g_h) + (to_f64(dh_c) if carried else 0.0)
     want = oracle.lstm_cell_backward(to_f64(y), to_f64(h_prev), to_f64(c_prev), to_f64(w_x), to_f64(w_h), to_f64(bias), dh,
                                      to_f64(dc_n) if carried else None)
-    assert_close(to_f64(da), want[0], torch.float32, "dL/d(pre-activations), fused")
-    assert_close(to_f64(dc), want[3], torch.float32, "dL/dc_prev, fused")
+    assert_close(to_f64(da), want[0], dtype, "dL/d(pre-activations), fused")
+    assert_close(to_f64(dc), want[3], dtype, "dL/dc_prev, fused")
 
 
 @pytest.mark.parametrize("keep,fused", [(False, True), (True, True), (False, False)])
-@pytest.mark.parametrize("case", ["undirected_f32", "directed_f32"])
+@pytest.mark.parametrize("case", ["undirected_f32", "directed_f32", "undirected_bf16"])
 def test_cdgcn_training_step(case, keep, fused):
     """Gradients of sum_t <G_t, h_t> with respect to W, W_x, W_h and b over a block, against the oracle's backward
     pass (itself pinned by finite differences); the ReLU mask is taken on fp32 values on the device and fp64 in
     the oracle, which agree except for outputs within rounding of zero (none at these sizes would move a gradient
-    beyond the tolerance)."""
+    beyond the tolerance; the bf16 case has its own bound for dW, see below)."""
     from paper_2109_07893_amd.cdgcn import CdgcnTrainer
     wl = {"undirected_f32": replace(WORKLOADS["c1"], f=32, window=0, name="cd-c1"),
-          "directed_f32": replace(WORKLOADS["c3"].scaled(4096, T=5), name="cd-c3")}[case]
+          "directed_f32": replace(WORKLOADS["c3"].scaled(4096, T=5), name="cd-c3"),
+          "undirected_bf16": replace(WORKLOADS["c4"].scaled(3000, T=4), f=32, window=0, name="cd-c4")}[case]
+    dtype = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
     f, hidden, T = wl.f, 32, wl.T
     w = glorot_weight(wl, 0)
-    w_x = randn((2 * f, 4 * hidden), 11) / np.sqrt(2 * f)
-    w_h = randn((hidden, 4 * hidden), 12) / np.sqrt(hidden)
+    w_x = (randn((2 * f, 4 * hidden), 11) / np.sqrt(2 * f)).to(dtype)
+    w_h = (randn((hidden, 4 * hidden), 12) / np.sqrt(hidden)).to(dtype)
     bias = randn((4 * hidden,), 13) * 0.1
-    g_h = randn((T, wl.n, hidden), 14)
+    g_h = randn((T, wl.n, hidden), 14, dtype)
     blk = make_block(wl, DEV, gen_device="cpu")
     tr = CdgcnTrainer(blk, w.to(DEV), w_x.to(DEV), w_h.to(DEV), bias.to(DEV), hidden, fused=fused, keep_activations=keep)
     tr.load_first()
@@ -288,7 +292,7 @@ def test_cdgcn_training_step(case, keep, fused):
         ys.append(oracle.cdgcn_gcn(rp, ci, to_f64(features(wl, t)), W))
         h, c = oracle.lstm_cell(ys[-1], hs[-1], cs[-1], WX, WH, Bv)
         hs.append(h); cs.append(c)
-        assert_close(to_f64(tr.h_all[t - 1]), h, torch.float32, f"{case}: h_{t}")
+        assert_close(to_f64(tr.h_all[t - 1]), h, dtype, f"{case}: h_{t}", stores=7 * t)
     d_w, d_wx, d_wh, d_b = 0.0, 0.0, 0.0, 0.0
     dh, dc = 0.0, None
     for t in range(T, 0, -1):
@@ -296,10 +300,19 @@ def test_cdgcn_training_step(case, keep, fused):
                                                                 to_f64(g_h[t - 1]) + dh, dc)
         d_wx, d_wh, d_b = d_wx + a, d_wh + b, d_b + cgrad
         d_w = d_w + oracle.cdgcn_gcn_backward(*snaps[t - 1], to_f64(features(wl, t)), W, d_y)[0]
+    bad = []
     for name, got, want in (("dW", tr.dw, d_w), ("dW_x", tr.dw_x, d_wx), ("dW_h", tr.dw_h, d_wh), ("db", tr.db, d_b)):
         want = np.asarray(want)
         err = np.abs(to_f64(got) - want).max()
-        assert err <= 2e-4 * np.abs(want).max(), f"{case} {name}: max err {err:.3e} against max |.| {np.abs(want).max():.3e}"
+        # bf16: every gradient is a sum over thousands of vertices of products of values that were each rounded to 8 bits
+        # several times on the way; the roundings are independent, so the sums keep two to three digits (measured:
+        # 3e-3 of the largest entry).  dW is another matter: Y0 is stored in bf16, so Y1 = Y0 W has the other sign than
+        # the oracle's wherever |Y1| is below that rounding, about 3 in 1000 entries, and each such ReLU mask bit
+        # changes its term of Y0^T dY1 by 100 %: sqrt(0.003) = 5 % of a sum of terms with random signs
+        tol = 2e-4 if dtype == torch.float32 else (8e-2 if name == "dW" else 2e-2)
+        if err > tol * np.abs(want).max():
+            bad.append(f"{name}: max err {err:.3e} against max |.| {np.abs(want).max():.3e}")
+    assert not bad, f"{case}: " + "; ".join(bad)
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
