@@ -169,13 +169,6 @@ __global__ __launch_bounds__(kLstmThreads) void lstm_step_f32_kernel(const float
     const int64_t stride = (int64_t)gridDim.x * kLstmWaves;
     const int64_t first = (int64_t)blockIdx.x * kLstmWaves + wave;
     __syncthreads();                                   // W is in LDS; from here on every wavefront is on its own
-    // The two wavefronts of a SIMD do the same work in the same rhythm; started together they would both multiply,
-    // then both run the cell.  The second one starts about half a tile late, so that one's products run beside the
-    // other's nonlinearities.
-    if (wave >= kLstmWaves / 2) {
-        __builtin_amdgcn_s_sleep(127);
-        __builtin_amdgcn_s_sleep(127);
-    }
     // The rows of the next tile travel while this one is multiplied: a wavefront shares its SIMD with one other
     // only, which cannot hide a trip to memory per tile.
     const floatx4 zero = {0.f, 0.f, 0.f, 0.f};

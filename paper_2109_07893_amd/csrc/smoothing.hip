@@ -4,13 +4,15 @@
 // equal (row, column) are added up, entries whose result is exactly 0 leave the structure.  It is a three-way
 // merge in the order (row, column), made into work of equal size the way the other sparse kernels here are:
 // split by ENTRIES of S, not by rows, so that the hub rows of a power-law graph are spread over many lanes.
-//   - a wavefront owns kRange consecutive entries of S and stages them in LDS, a lane kPer of those.  A share
+//   - a wavefront owns kRange consecutive entries of S, a lane kPer consecutive ones of those, which it keeps in
+//     registers (one 16-byte load each of columns and values; the lanes' loads cover the range without a gap).  A share
 //     begins at a BOUNDARY: the (row, column) of its first S entry.  Every term of A_in and A_out belongs to the
 //     share whose boundary is the last one not behind it, found by one lower bound in the boundary's row; rows
 //     that begin between two boundaries (rows without S entries included) belong to the share in front;
-//   - the A_in and A_out terms of a range are consecutive in their arrays and are staged as well (a span longer
-//     than the staging area is read in place instead);
-//   - each lane merges its share out of LDS, row piece after row piece;
+//   - the A_in and A_out terms of a range are consecutive in their arrays and are staged in LDS, with the row
+//     pointers of the rows the range meets (a span longer than the staging area is read in place instead);
+//   - each lane merges its share, row piece after row piece.  The merge launches are bound by the rate at which
+//     the SIMDs issue vector instructions (about 600 per range and launch), not by memory;
 //   - the size of the result is not known beforehand, and the host never waits for it: a first launch only counts
 //     (per lane), a two-level scan turns the range totals into positions and leaves the grand total on the device,
 //     the second launch merges again and writes, rowptr included -- unless the total exceeds the capacity, which
@@ -28,20 +30,14 @@ namespace {
 
 using namespace dgnn;
 
-#ifndef DGNN_COMBINE_PER
-#define DGNN_COMBINE_PER 4
-#endif
-constexpr int kPer = DGNN_COMBINE_PER; // entries of S per lane (a multiple of 4: a lane fetches them 16 bytes at a time)
+constexpr int kPer = 4;                // entries of S per lane (a multiple of 4: a lane fetches them 16 bytes at a time)
 constexpr int kRange = kPer * kWave;   // entries of S per wavefront
 constexpr int kCapIn = 80 * kPer;      // staged terms of A_in per range
 constexpr int kCapOut = 64 * kPer;     // staged terms of A_out per range
 constexpr int kCapRows = 32 * kPer;    // staged row pointers per range and operand
 constexpr int kNoCol = 0x7fffffff;     // larger than any column index the library accepts
-#ifndef DGNN_COMBINE_XCD
-#define DGNN_COMBINE_XCD 16
-#endif
 constexpr int kXcds = 8;
-constexpr int kXcdChunk = DGNN_COMBINE_XCD;   // consecutive ranges that go to the same XCD
+constexpr int kXcdChunk = 16;          // consecutive ranges that go to the same XCD
 constexpr int kScanThreads = 1024;
 constexpr int kScanTile = 4 * kScanThreads;   // counts per workgroup of the first scan level
 
