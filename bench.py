@@ -56,6 +56,8 @@ def parse_args():
                     help="also time one step of the path for snapshots that carry a value per entry")
     ap.add_argument("--smoothing", action="store_true",
                     help="also time the sliding-window sum of the block's snapshots (edge life 4) computed on the device")
+    ap.add_argument("--smoothing-sum-only", action="store_true",
+                    help="with --smoothing: only the series of sliding-window sums and the normalisation (no smoothed pass, no training step)")
     ap.add_argument("--working-sets", action="store_true",
                     help="also time the aggregation with its gathers confined to working sets of known size")
     ap.add_argument("--mproduct-band", action="store_true",
@@ -364,6 +366,9 @@ def smoothing_steps(args, wl, blk, dev, life=4):
            "note": "each step: a count launch, two small scans and a write launch, enqueue-only; the size of the result stays on the device"}
     del snaps, bufs, ws, s
     torch.cuda.empty_cache()
+    progress("sliding-window sums timed")
+    if args.smoothing_sum_only:
+        return out
     # the whole forward pass on smoothed snapshots: rebuild, sliding-window sum, normalisation, X W, aggregation
     from paper_2109_07893_amd.pipeline import SmoothedRunner, StageTimer
     runner = SmoothedRunner(blk, life)
@@ -384,6 +389,7 @@ def smoothing_steps(args, wl, blk, dev, life=4):
                            "note": "every snapshot t = 1..T, including the copy of A_1 into the ring at the start of the pass"}
     del runner
     torch.cuda.empty_cache()
+    progress("pass on smoothed snapshots timed")
     # training step on the smoothed snapshots: every S_t (and S_t^T) stays resident, the backward pass does no graph work
     from dtdg_synth import gradient
     from paper_2109_07893_amd.training import make_smoothed_trainer
