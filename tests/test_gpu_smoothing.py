@@ -89,6 +89,39 @@ def test_combine_hub_rows_empty_rows_and_long_spans():
     check(n, a_in + (None,), s, 1.0, a_out, -1.0, "operands exchanged")
 
 
+def csr_with_row_lengths(n, lengths, rng):
+    """A CSR whose row u has lengths[u] entries at random columns."""
+    rows = np.repeat(np.arange(n), lengths)
+    cols = np.concatenate([np.sort(rng.choice(n, size=int(k), replace=False)) for k in lengths]) if rows.size else np.zeros(0, dtype=np.int64)
+    return oracle.csr_from_edges(n, rows, cols)
+
+
+@pytest.mark.parametrize("nnz_s", [256, 64 * 256, 64 * 256 + 1, 2 * 64 * 256 - 1, 2 * 64 * 256])
+def test_combine_entry_counts_on_the_edges_of_ranges_and_boundary_tiles(nnz_s):
+    """S with exactly as many entries as a whole number of wavefront ranges (256 entries each), and as a whole number
+    of the boundary kernel's groups of 64 ranges (then the end of everything is the first boundary of a group of
+    its own), and one more or less; rows of one entry (a boundary group meets more rows than it stages: 16384)
+    next to long rows."""
+    n = 40_000
+    rng = np.random.default_rng(nnz_s)
+    lengths = np.zeros(n, dtype=np.int64)
+    ones = min(n - 100, nnz_s // 2)
+    lengths[:ones] = 1                                       # a stretch of one-entry rows at the beginning
+    rest = nnz_s - ones
+    long_rows = rng.choice(np.arange(ones, n), size=40, replace=False)
+    cut = np.sort(rng.choice(rest + 1, size=39, replace=True))
+    lengths[long_rows] = np.diff(np.concatenate([[0], cut, [rest]]))
+    assert int(lengths.sum()) == nnz_s and int(lengths.max()) <= n
+    s = csr_with_row_lengths(n, lengths, rng)
+    assert s[1].size == nnz_s
+    a_in = random_csr(n, 0.0004, rng, hubs=((int(long_rows[0]), 3000), (5, 40)))
+    a_out = csr_with_row_lengths(n, np.minimum(lengths, 3), rng)
+    val = rng.integers(1, 3, s[1].size).astype(np.float64)
+    check(n, s + (val,), a_in, 1.0, a_out, -1.0, f"{nnz_s} entries")
+    check(n, s + (val,), a_in, 1.0, s, -1.0, f"{nnz_s} entries, S cancelled by itself where the value is 1")
+    check(n, s + (val,), a_in, 1.0, a_out, -1.0, f"{nnz_s} entries, given as an upper bound", s_bound=nnz_s + 64 * 256)
+
+
 def test_combine_empty_s_and_total_cancellation():
     n = 500
     rng = np.random.default_rng(5)
