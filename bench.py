@@ -58,6 +58,8 @@ def parse_args():
                     help="also time the sliding-window sum of the block's snapshots (edge life 4) computed on the device")
     ap.add_argument("--smoothing-sum-only", action="store_true",
                     help="with --smoothing: only the series of sliding-window sums and the normalisation (no smoothed pass, no training step)")
+    ap.add_argument("--two-streams", action="store_true",
+                    help="also time the step with the next snapshot's rebuild and X W on a second stream beside the aggregation")
     ap.add_argument("--working-sets", action="store_true",
                     help="also time the aggregation with its gathers confined to working sets of known size")
     ap.add_argument("--mproduct-band", action="store_true",
@@ -303,6 +305,44 @@ def weighted_step(args, wl, blk, dev):
         out[name] = {"avg_ms": round(ms, 4), "algorithmic_bytes_per_call": int(byts),
                      "algorithmic_GBps": round(byts / (ms * 1e-3) / 1e9, 1)}
     out["lists"] = {"added": int(ar.numel()), "deleted": int(dr.numel()), "value_updates": int(ur.numel())}
+    return out
+
+
+def two_stream_steps(args, wl, blk, dev):
+    """The timed step once more with the rebuild and X W of snapshot t+1 on a second stream while snapshot t is
+    aggregated (BlockRunner's overlap mode), beside the same step on one stream: an extra figure, the headline keeps
+    the one-stream pass that the per-stage figures and the profiles describe."""
+    import torch
+    from paper_2109_07893_amd.pipeline import BlockRunner
+    runner = BlockRunner(blk)
+    runner.load_first()
+    first = 1 if blk.window else 2
+    edges = sum(blk.nnz[first - 1:])
+
+    def timed(fn, finish=None):
+        for _ in range(max(args.warmup, 1)):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        el = (time.perf_counter() - t0) / args.steps
+        if finish:
+            finish()
+            torch.cuda.synchronize()
+        return {"ms_per_step": round(el * 1e3, 3), "value": edges / el, "unit": "edges/s"}
+
+    out = {"lists_resident": {"one_stream": timed(lambda: runner.run_resident(first=first)),
+                              "two_streams": timed(lambda: runner.run_resident(first=first, overlap=True))}}
+    if blk.pinned is not None:
+        out["lists_from_pinned_host"] = {
+            "one_stream": timed(lambda: runner.run_from_pinned(first=first, prefetch_next=True),
+                                lambda: runner.run_from_pinned(first=first)),
+            "two_streams": timed(lambda: runner.run_from_pinned(first=first, prefetch_next=True, overlap=True),
+                                 lambda: runner.run_from_pinned(first=first, overlap=True))}
+    out["note"] = ("two_streams: rebuild of A_t+1 and X_t+1 W enqueued on a second stream, at most one snapshot ahead of the "
+                   "aggregations; same kernels, same operands, bit-identical results; one more H buffer")
     return out
 
 
@@ -818,6 +858,7 @@ def main():
         torch.cuda.empty_cache()
         progress(f"{key} timed")
 
+    extra("two_streams", args.two_streams, two_stream_steps)
     extra("gather_working_sets", args.working_sets, gather_working_sets)
     extra("mproduct_explicit_band", args.mproduct_band, mproduct_band)
     extra("cdgcn_layer", args.cdgcn, cdgcn_layer)

@@ -142,19 +142,27 @@ class BlockRunner:
                                   flags=B.DGNN_VALIDATE if validate else 0, d_status=self.status[t:t + 1])
         assert nnz == blk.nnz[t - 1]
 
-    def gcn(self, t: int) -> torch.Tensor:
-        """All GCN layers on snapshot t; returns the frame Z_t."""
+    def transform_first(self, t: int, h: torch.Tensor) -> None:
+        """H = D^(-1/2) (X_t W) of the first layer into `h` (the right-hand D^(-1/2) of the normalised adjacency is
+        folded into the rows of H)."""
+        with self._stage("feature_transform"):
+            B.feature_transform(self.blk.x[t - 1], self.blk.weight(t, 0), h, row_scale=self.dinv[self.slot_of(t)])
+
+    def gcn(self, t: int, h_first: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """All GCN layers on snapshot t; returns the frame Z_t.  h_first: the first layer's H, already formed by
+        transform_first (the buffer then serves the later layers as well)."""
         blk = self.blk
         slot = self.slot_of(t)
         out = self.z[t - 1] if self.keep_all_z else self.z[0]
+        h = self.h if h_first is None else h_first
         cur = blk.x[t - 1]
         for layer in range(blk.layers):
-            # the right-hand D^(-1/2) of the normalised adjacency is folded into the rows of H
-            with self._stage("feature_transform"):
-                B.feature_transform(cur, blk.weight(t, layer), self.h, row_scale=self.dinv[slot])
+            if layer > 0 or h_first is None:
+                with self._stage("feature_transform"):
+                    B.feature_transform(cur, blk.weight(t, layer), h, row_scale=self.dinv[slot])
             dst = out if layer == blk.layers - 1 else self.z_mid
             with self._stage("spmm"):
-                B.spmm(self.rowptr[slot], self.colidx[slot], blk.nnz[t - 1], self.dinv[slot], self.h, dst,
+                B.spmm(self.rowptr[slot], self.colidx[slot], blk.nnz[t - 1], self.dinv[slot], h, dst,
                        self.ws_spmm, flags=B.DGNN_RELU | B.DGNN_H_PRESCALED)
             cur = dst
         return out
@@ -172,11 +180,14 @@ class BlockRunner:
                 B.mproduct(self.z, self.z, self.blk.window)
 
     # ------------------------------------------------------------------ whole passes
-    def run_resident(self, first: int = 1, validate: bool = False, on_snapshot=None) -> None:
+    def run_resident(self, first: int = 1, validate: bool = False, on_snapshot=None, overlap: bool = False) -> None:
         """Forward pass with the difference lists already on the device.  `first` = 2 skips the GCN
         on A_1 (timed regions that count only rebuilt snapshots).  on_snapshot(t, slot) is called
-        after the work of timestep t has been enqueued."""
+        after the work of timestep t has been enqueued.  overlap: see _run_overlapped."""
         blk = self.blk
+        if overlap:
+            self._run_overlapped(first, validate, on_snapshot, pinned=False, prefetch_next=False)
+            return
         self.begin_pass()
         for t in range(1, blk.T + 1):
             if t >= 2:
@@ -184,6 +195,72 @@ class BlockRunner:
             self.snapshot_ready(t)
             if t >= first:
                 self.gcn(t)
+            if on_snapshot is not None:
+                on_snapshot(t, self.slot_of(t))
+        self.mix()
+
+    def _run_overlapped(self, first: int, validate: bool, on_snapshot, pinned: bool, prefetch_next: bool) -> None:
+        """The same pass on two streams: the rebuild of A_t and the first layer's X_t W run on a second stream, up to
+        one snapshot ahead of the aggregations on the current one.  The aggregation is held back by the rate at which
+        L2 misses are served and leaves issue slots and HBM bandwidth unused, which the two streaming kernels of the
+        next snapshot take.  Two H buffers alternate; A_t's slot and an H buffer are written again only after the
+        aggregation that read them two snapshots earlier has finished (events both ways).  Results are those of the
+        one-stream pass bit for bit: the same kernels on the same operands."""
+        blk = self.blk
+        assert type(self).snapshot_ready is BlockRunner.snapshot_ready and type(self).begin_pass is BlockRunner.begin_pass, \
+            "subclasses that enqueue work of their own per snapshot run on one stream"
+        if pinned:
+            assert self.stage is not None
+        main = torch.cuda.current_stream(self.dev)
+        if getattr(self, "prep_stream", None) is None:
+            self.prep_stream = torch.cuda.Stream(device=self.dev)
+            self.h_pair = [self.h, torch.empty_like(self.h)]
+        prep = self.prep_stream
+        ready = [torch.cuda.Event() for _ in range(blk.T + 1)]     # A_t, dinv_t and the first H of t are there
+        done = [torch.cuda.Event() for _ in range(blk.T + 1)]      # everything that reads them has been enqueued and run
+
+        def issue_copy(t):
+            k = t % 2
+            with torch.cuda.stream(self.copy_stream):
+                self.copy_stream.wait_event(self.consumed[k])
+                with self._stage("delta_h2d"):
+                    B.delta_h2d(*blk.pinned[t - 2], *self.stage[k])
+                self.copied[k].record(self.copy_stream)
+
+        begun = torch.cuda.Event()
+        begun.record(main)                  # whatever the caller enqueued before the pass (an earlier pass, load_first)
+        prep.wait_event(begun)
+        if pinned:
+            if not getattr(self, "_first_lists_requested", False):
+                for k in range(2):
+                    self.consumed[k].record(main)
+                if blk.T >= 2:
+                    issue_copy(2)
+            self._first_lists_requested = False
+        for t in range(1, blk.T + 1):
+            with torch.cuda.stream(prep):
+                if t - 2 >= 1:
+                    prep.wait_event(done[t - 2])            # A_{t-2}'s slot and its H buffer are free again
+                if t >= 2:
+                    if pinned:
+                        k = t % 2
+                        prep.wait_event(self.copied[k])
+                        if t + 1 <= blk.T:
+                            issue_copy(t + 1)
+                        self.rebuild(t, self.stage[k], validate)
+                        self.consumed[k].record(prep)
+                        if t == blk.T and prefetch_next and blk.T >= 3:
+                            issue_copy(2)
+                            self._first_lists_requested = True
+                    else:
+                        self.rebuild(t, blk.deltas[t - 2], validate)
+                if t >= first:
+                    self.transform_first(t, self.h_pair[t % 2])
+                ready[t].record(prep)
+            main.wait_event(ready[t])
+            if t >= first:
+                self.gcn(t, h_first=self.h_pair[t % 2])
+            done[t].record(main)
             if on_snapshot is not None:
                 on_snapshot(t, self.slot_of(t))
         self.mix()
@@ -200,14 +277,18 @@ class BlockRunner:
             self.run_resident(first=first)
         return graph
 
-    def run_from_pinned(self, first: int = 1, prefetch_next: bool = False, validate: bool = False, on_snapshot=None) -> None:
+    def run_from_pinned(self, first: int = 1, prefetch_next: bool = False, validate: bool = False, on_snapshot=None,
+                        overlap: bool = False) -> None:
         """Same pass with the difference lists of step t+1 copied from pinned host memory on a second
         stream while step t computes (two staging sets, events both ways).  With prefetch_next the lists of
         the next pass's first step are already requested while this pass finishes (a stream of blocks: the
         next block's first lists travel during the current block's last steps).  on_snapshot(t, slot) as in
-        run_resident."""
+        run_resident; overlap: see _run_overlapped."""
         blk = self.blk
         assert self.stage is not None
+        if overlap:
+            self._run_overlapped(first, validate, on_snapshot, pinned=True, prefetch_next=prefetch_next)
+            return
         main = torch.cuda.current_stream(self.dev)
 
         def issue_copy(t):

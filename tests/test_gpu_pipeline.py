@@ -77,6 +77,45 @@ def test_pinned_host_pipeline_with_lists_requested_ahead():
     assert torch.equal(a.z, runner.z)
 
 
+@pytest.mark.parametrize("name,n,T", [("c1", 1000, 8), ("c2", 20_000, 7), ("c3", 1 << 14, 5), ("c4", 10_000, 20), ("c5", 1 << 15, 8)])
+def test_pass_on_two_streams_equals_the_pass_on_one(name, n, T):
+    """The rebuild and the first layer's X W of the next snapshot on a second stream (overlap=True): the same
+    kernels on the same operands, so every frame and every snapshot must come out bit for bit as from the pass on
+    one stream -- with the lists resident and from pinned host memory, in passes that follow one another (the
+    slots and H buffers of one pass are written again by the next), mixed with one-stream passes."""
+    wl = WORKLOADS[name] if WORKLOADS[name].n == n else WORKLOADS[name].scaled(n, T=T)
+    a, csr = run_gpu(wl, T=T)
+    blk = make_block(wl, DEV, gen_device="cpu", pinned=True, T=T)
+    runner = BlockRunner(blk, keep_all_z=True)
+    runner.load_first()
+
+    def same(what):
+        torch.cuda.synchronize()
+        assert int(runner.status.abs().sum()) == 0
+        assert torch.equal(a.z, runner.z), what
+        runner.z.fill_(float("nan"))
+
+    kept = []
+    runner.run_resident(validate=True, overlap=True, on_snapshot=lambda t, slot: kept.append(runner.snapshot_to_host(t)))
+    same("lists resident")
+    for t, ((rp, ci), (grp, gci)) in enumerate(zip(csr, kept), start=1):
+        assert np.array_equal(rp, grp) and np.array_equal(ci, gci), f"CSR differs at t={t}"
+    runner.run_resident(overlap=True)
+    runner.run_resident(overlap=True)                       # back to back, nothing waited for in between
+    same("two passes back to back")
+    runner.run_from_pinned(overlap=True)
+    same("lists from pinned host memory")
+    for k in range(3):
+        runner.run_from_pinned(prefetch_next=True, overlap=True)
+        same(f"lists requested ahead, pass {k}")
+    runner.run_from_pinned()                                # a one-stream pass takes up the outstanding request
+    same("one-stream pass after two-stream passes")
+    runner.run_from_pinned(overlap=True, first=2 if not wl.window else 1)
+    torch.cuda.synchronize()
+    lo = 0 if wl.window else 1
+    assert torch.equal(a.z[lo:], runner.z[lo:]), "first = 2"
+
+
 def test_block_forward_is_deterministic():
     wl = WORKLOADS["c3"].scaled(1 << 13, T=3)
     a, _ = run_gpu(wl)
