@@ -38,6 +38,10 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--settle-seconds", type=float, default=1.5,
+                    help="untimed passes of the same step before the warm-up steps, for this long: the device reaches its "
+                         "steady clocks and the pinned buffers have been read once (with 2 warm-up steps alone the timed "
+                         "steps of c5 come out 6 %% slower than after 20)")
     ap.add_argument("--workload", default="c5", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--n", type=int, default=0, help="run the workload's recipe at another vertex count (debugging)")
     ap.add_argument("--T", type=int, default=0, help="override the number of snapshots (debugging)")
@@ -687,10 +691,25 @@ def main():
     first = 1 if blk.window else 2
     edges_per_step = sum(blk.nnz[first - 1:])
 
+    settled = [0, 0]      # passes of the settle phase so far (-1 once it is over), and their final number
+
     def timed(step_fn, before=None, after=None):
         """Seconds per step of step_fn over args.steps back-to-back steps after args.warmup untimed ones."""
         if before:
             before()
+        if settled[0] >= 0 and args.settle_seconds > 0:
+            # preparation, like generating the inputs: one pass to learn how long it takes, then as many as fill the
+            # settle time, enqueued back to back (a wait after every pass lets the device fall idle in between)
+            t_settle = time.perf_counter()
+            step_fn()
+            torch.cuda.synchronize()
+            one = max(time.perf_counter() - t_settle, 1e-4)
+            more = min(int(args.settle_seconds / one), 1000)
+            for _ in range(more):
+                step_fn()
+            torch.cuda.synchronize()
+            settled[1] = 1 + more
+        settled[0] = -1                                               # once: the later figures find the device warm
         for _ in range(args.warmup):
             step_fn()
         torch.cuda.synchronize()
@@ -774,7 +793,7 @@ def main():
                    if pinned else "resident in HBM")
     out = {
         "metric": "snapshot-edges/sec (delta rebuild + SpMM)", "value": value, "unit": "edges/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "steps": args.steps, "warmup": args.warmup, "settle_steps_before_warmup": settled[1], "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32" if wl.dtype == "f32" else "bf16 storage, f32 accumulate",
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: N={blk.n}, T={T}, {wl.graph}, F={blk.f}, {wl.dtype}, layers={blk.layers}, "
