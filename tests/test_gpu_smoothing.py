@@ -214,7 +214,7 @@ def test_forward_pass_on_smoothed_snapshots(name, n, T, life, diag):
     assert_close(to_f64(runner.z), expect, runner.z.dtype, f"{wl.name} smoothed forward", stores=blk.layers + (1 if wl.window else 0))
 
 
-@pytest.mark.parametrize("seed", range(30))
+@pytest.mark.parametrize("seed", range(80))
 def test_combine_random_shapes(seed):
     """Seeded random operand shapes: sizes, densities, hub rows, empty stretches, weights, presence of A_in / A_out."""
     rng = np.random.default_rng(1000 + seed)
