@@ -483,7 +483,7 @@ int dgnn_lstm_cell_backward(const void *gates_x, const void *gates_h, const floa
 /*
  * The same with the gate pre-activations recomputed on chip (the adjoint of dgnn_lstm_step): takes Y, h_{t-1}, W_x,
  * W_h and the bias instead of the two halves of the pre-activations, everything else as dgnn_lstm_cell_backward.
- * fp32 or bf16 storage, hidden = 32, f_y = 32 or 64 (DGNN_ERR_SHAPE otherwise: use the two dense transforms and
+ * fp32 storage with hidden = 16 or 32, bf16 storage with hidden = 32; f_y = hidden or 2 * hidden (DGNN_ERR_SHAPE otherwise: use the two dense transforms and
  * dgnn_lstm_cell_backward).  bf16: the pre-activations and the cell's formulas in fp32, da and dc_prev rounded once.
  */
 int dgnn_lstm_step_backward(const void *y, int32_t f_y, const void *h_prev, const void *w_x, const void *w_h,

@@ -487,7 +487,8 @@ def lstm_cell_backward(gates_x, gates_h, bias, c_prev, dh_a, dh_b, dc_next, da, 
 
 
 def lstm_step_backward_supported(y: torch.Tensor, hidden: int) -> bool:
-    return y.dtype in (torch.float32, torch.bfloat16) and hidden == 32 and y.shape[1] in (32, 64)
+    widths = {torch.float32: (16, 32), torch.bfloat16: (32,)}.get(y.dtype, ())
+    return hidden in widths and y.shape[1] in (hidden, 2 * hidden)
 
 
 def lstm_step_backward(y, h_prev, w_x, w_h, bias, c_prev, dh_a, dh_b, dc_next, da, dc_prev) -> None:

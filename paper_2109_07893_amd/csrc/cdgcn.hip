@@ -136,7 +136,7 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ float fast_sigmoid(float x) { return __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
 __device__ __forceinline__ float fast_tanh(float x) { return 2.0f * fast_sigmoid(2.0f * x) - 1.0f; }
 
-constexpr int kLstmHidden = 32;      // the adjoint kernel's only width
+constexpr int kLstmHidden = 32;      // the bf16 adjoint kernel's only width
 constexpr int kLstmThreads = 512;   // eight wavefronts share W in LDS: two per SIMD, so one multiplies while the other moves data
 constexpr int kLstmWaves = kLstmThreads / kWave;
 
@@ -399,12 +399,12 @@ __global__ __launch_bounds__(WAVES * kWave) void lstm_step_bf16_kernel(const uin
 //     da_g = dc i (1 - g^2),  da_o = dh tanh(c_t) o (1 - o),   dc_{t-1} = dc f.
 // Traffic: Y, h_prev, c_prev, the incoming gradients in; da (4 * hidden wide) and dc_{t-1} out, instead of writing
 // and re-reading both halves of the pre-activations as well.
-template <int FY>
+template <int FY, int HID>
 __global__ __launch_bounds__(kLstmThreads) void lstm_step_backward_f32_kernel(
     const float *__restrict__ y, const float *__restrict__ h_prev, const float *__restrict__ w_x, const float *__restrict__ w_h,
     const float *__restrict__ bias, const float *__restrict__ c_prev, const float *__restrict__ dh_a,
     const float *__restrict__ dh_b, const float *dc_next, float *__restrict__ da, float *dc_prev, int64_t n, int64_t n_tiles) {
-    constexpr int HID = kLstmHidden, G4 = 4 * HID;
+    constexpr int G4 = 4 * HID, NT = G4 / 32;
     constexpr int K = FY + HID, KH = K / 2;
     constexpr int LDT = (K > 3 * HID ? K : 3 * HID) + 4;      // the tile buffer also carries c_prev, dh and dc side by side
     constexpr int Y_PIECES = 32 * FY / 4 / kWave;
@@ -418,7 +418,7 @@ __global__ __launch_bounds__(kLstmThreads) void lstm_step_backward_f32_kernel(
     const int tid = threadIdx.x;
     for (int idx = tid; idx < K * G4; idx += kLstmThreads) {
         const int k = idx / G4, col = idx % G4;
-        s_w[(k * 32 + col % 32) * 4 + col / 32] = idx < FY * G4 ? w_x[idx] : w_h[idx - FY * G4];
+        s_w[(k * 32 + col % 32) * NT + col / 32] = idx < FY * G4 ? w_x[idx] : w_h[idx - FY * G4];
     }
     for (int idx = tid; idx < G4; idx += kLstmThreads) s_bias[idx] = bias ? bias[idx] : 0.0f;
     const int lane = tid & (kWave - 1), wave = tid / kWave;
@@ -472,24 +472,33 @@ __global__ __launch_bounds__(kLstmThreads) void lstm_step_backward_f32_kernel(
             *reinterpret_cast<floatx4 *>(row + HID) = dh_cur[q];
             *reinterpret_cast<floatx4 *>(row + 2 * HID) = dc_cur[q];
         }
-        floatx16 acc[4];
+        floatx16 acc[NT];
 #pragma unroll
-        for (int g = 0; g < 4; ++g)
+        for (int g = 0; g < NT; ++g)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[g][v] = 0.0f;
 #pragma unroll
         for (int s = 0; s < KH; ++s) {
             const float xv = a[s / 4][s % 4];
-            const floatx4 wv = *reinterpret_cast<const floatx4 *>(&s_w[((hh * KH + s) * 32 + i) * 4]);
+            float wv[NT];
 #pragma unroll
-            for (int g = 0; g < 4; ++g) acc[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(wv[g], xv, acc[g], 0, 0, 0);   // transposed gate tile g
+            for (int g = 0; g < NT; ++g) wv[g] = s_w[((hh * KH + s) * 32 + i) * NT + g];   // consecutive: one read
+#pragma unroll
+            for (int g = 0; g < NT; ++g) acc[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(wv[g], xv, acc[g], 0, 0, 0);   // transposed tile g of the pre-activations
         }
         wave_lds_sync();                                                      // c_prev, dh, dc are in LDS
-        // ---- the cell's adjoint, on the accumulators (register 4 q + r of lane (i, h): state element 8 q + 4 h + r);
-        // the gradients replace the pre-activations in the accumulators, dc_{t-1} goes to the tile
+        // ---- the cell's adjoint, on the accumulators: lane (i, h) owns state elements 8 m + 4 h + r of vertex i; gate g
+        // of them is column g * hidden + 8 m + 4 h + r, in tile (g * hidden + 8 m) / 32, registers 4 q + r with q the
+        // 8-column group inside the tile.  The gradients replace the pre-activations in the accumulators, dc_{t-1}
+        // goes to the tile
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int k0 = 8 * q + 4 * hh;
+        for (int m = 0; m < HID / 8; ++m) {
+            const int k0 = 8 * m + 4 * hh;
+            constexpr int kGroup = 8;
+            const int ti = (0 * HID + kGroup * m) / 32, qi = ((0 * HID + kGroup * m) % 32) / 8;
+            const int tf = (1 * HID + kGroup * m) / 32, qf = ((1 * HID + kGroup * m) % 32) / 8;
+            const int tg = (2 * HID + kGroup * m) / 32, qg = ((2 * HID + kGroup * m) % 32) / 8;
+            const int to = (3 * HID + kGroup * m) / 32, qo = ((3 * HID + kGroup * m) % 32) / 8;
             const floatx4 c_old = *reinterpret_cast<const floatx4 *>(&tile_lds[i * LDT + k0]);
             const floatx4 dh = *reinterpret_cast<const floatx4 *>(&tile_lds[i * LDT + HID + k0]);
             const floatx4 dc_in = *reinterpret_cast<const floatx4 *>(&tile_lds[i * LDT + 2 * HID + k0]);
@@ -497,16 +506,16 @@ __global__ __launch_bounds__(kLstmThreads) void lstm_step_backward_f32_kernel(
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int k = k0 + r;
-                const float gi = fast_sigmoid(acc[0][4 * q + r] + s_bias[k]);
-                const float gf = fast_sigmoid(acc[1][4 * q + r] + s_bias[HID + k]);
-                const float gg = fast_tanh(acc[2][4 * q + r] + s_bias[2 * HID + k]);
-                const float go = fast_sigmoid(acc[3][4 * q + r] + s_bias[3 * HID + k]);
+                const float gi = fast_sigmoid(acc[ti][4 * qi + r] + s_bias[k]);
+                const float gf = fast_sigmoid(acc[tf][4 * qf + r] + s_bias[HID + k]);
+                const float gg = fast_tanh(acc[tg][4 * qg + r] + s_bias[2 * HID + k]);
+                const float go = fast_sigmoid(acc[to][4 * qo + r] + s_bias[3 * HID + k]);
                 const float tc = fast_tanh(gf * c_old[r] + gi * gg);
                 const float d = dh[r] * go * (1.0f - tc * tc) + dc_in[r];
-                acc[0][4 * q + r] = d * gg * gi * (1.0f - gi);
-                acc[1][4 * q + r] = d * c_old[r] * gf * (1.0f - gf);
-                acc[2][4 * q + r] = d * gi * (1.0f - gg * gg);
-                acc[3][4 * q + r] = dh[r] * tc * go * (1.0f - go);
+                acc[ti][4 * qi + r] = d * gg * gi * (1.0f - gi);
+                acc[tf][4 * qf + r] = d * c_old[r] * gf * (1.0f - gf);
+                acc[tg][4 * qg + r] = d * gi * (1.0f - gg * gg);
+                acc[to][4 * qo + r] = dh[r] * tc * go * (1.0f - go);
                 dc_out[r] = d * gf;
             }
             *reinterpret_cast<floatx4 *>(&tile_lds[i * LDT + k0]) = dc_out;          // over c_prev: this lane alone read it
@@ -520,16 +529,18 @@ __global__ __launch_bounds__(kLstmThreads) void lstm_step_backward_f32_kernel(
                 reinterpret_cast<floatx4 *>(dc_prev)[piece] = *reinterpret_cast<const floatx4 *>(&tile_lds[(e / HID) * LDT + e % HID]);
         }
         // da leaves in two halves of two gates each (a whole tile of it does not fit the buffer): columns
-        // [0, 2 hidden) of the tile rows, then whole 256-byte stretches of da's rows
+        // [0, 2 hidden) of the tile rows, then whole stretches of 2 hidden values of da's rows
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
             wave_lds_sync();                                                  // the buffer's previous contents have been read
 #pragma unroll
             for (int g = 0; g < 2; ++g)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const floatx16 &src = acc[2 * half + g];
-                    *reinterpret_cast<floatx4 *>(&tile_lds[i * LDT + g * HID + 8 * q + 4 * hh]) =
+                for (int m = 0; m < HID / 8; ++m) {
+                    const int col = (2 * half + g) * HID + 8 * m;             // first column of the group in da's row
+                    const floatx16 &src = acc[col / 32];
+                    const int q = (col % 32) / 8;
+                    *reinterpret_cast<floatx4 *>(&tile_lds[i * LDT + g * HID + 8 * m + 4 * hh]) =
                         floatx4{src[4 * q], src[4 * q + 1], src[4 * q + 2], src[4 * q + 3]};
                 }
             wave_lds_sync();
@@ -771,7 +782,9 @@ extern "C" int dgnn_lstm_step_backward(const void *y, int32_t f_y, const void *h
                                        void *stream) {
     if (!y || !h_prev || !w_x || !w_h || !c_prev || !da || !dc_prev) return DGNN_ERR_NULL;
     if (!dh_a && !dh_b && !dc_next) return DGNN_ERR_NULL;
-    if (n <= 0 || hidden != kLstmHidden || (dt != DGNN_F32 && dt != DGNN_BF16) || (f_y != 32 && f_y != 64)) return DGNN_ERR_SHAPE;
+    if (n <= 0 || (dt != DGNN_F32 && dt != DGNN_BF16)) return DGNN_ERR_SHAPE;
+    // fp32: hidden 16 or 32; bf16: hidden 32; Y as wide as the state or twice as wide
+    if (!(hidden == 32 || (hidden == 16 && dt == DGNN_F32)) || (f_y != hidden && f_y != 2 * hidden)) return DGNN_ERR_SHAPE;
     if (!fits_index(n)) return DGNN_ERR_OVERFLOW;
     for (const void *p : {y, h_prev, c_prev, dh_a, dh_b, dc_next, (const void *)da, (const void *)dc_prev})
         if (p && !aligned16(p)) return DGNN_ERR_ALIGN;
@@ -791,7 +804,11 @@ extern "C" int dgnn_lstm_step_backward(const void *y, int32_t f_y, const void *h
                            static_cast<E *>(dc_prev), n, n_tiles);
     };
     if (dt == DGNN_F32) {
-        if (f_y == 64) launch(lstm_step_backward_f32_kernel<64>, float()); else launch(lstm_step_backward_f32_kernel<32>, float());
+        if (hidden == 32) {
+            if (f_y == 64) launch(lstm_step_backward_f32_kernel<64, 32>, float()); else launch(lstm_step_backward_f32_kernel<32, 32>, float());
+        } else {
+            if (f_y == 32) launch(lstm_step_backward_f32_kernel<32, 16>, float()); else launch(lstm_step_backward_f32_kernel<16, 16>, float());
+        }
     } else {
         if (f_y == 64) launch(lstm_step_backward_bf16_kernel<64>, uint16_t()); else launch(lstm_step_backward_bf16_kernel<32>, uint16_t());
     }

@@ -232,12 +232,11 @@ def test_bias_grad(dtype, f, n):
     assert torch.equal(db, first)                     # fixed order of summation
 
 
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-@pytest.mark.parametrize("f_y", [32, 64])
+@pytest.mark.parametrize("dtype,hidden,f_y", [(torch.float32, 32, 32), (torch.float32, 32, 64), (torch.bfloat16, 32, 32),
+                                              (torch.bfloat16, 32, 64), (torch.float32, 16, 16), (torch.float32, 16, 32)])
 @pytest.mark.parametrize("n", [1, 31, 32, 33, 4097, 20_011])
 @pytest.mark.parametrize("carried", [False, True])
-def test_fused_lstm_step_backward(n, carried, f_y, dtype):
-    hidden = 32
+def test_fused_lstm_step_backward(n, carried, f_y, hidden, dtype):
     assert dg.lstm_step_backward_supported(torch.empty((1, f_y), dtype=dtype), hidden)
     y, h_prev = randn((n, f_y), 1, dtype), randn((n, hidden), 2, dtype)
     w_x, w_h = (randn((f_y, 4 * hidden), 3) / 8).to(dtype), (randn((hidden, 4 * hidden), 4) / 6).to(dtype)
@@ -256,7 +255,7 @@ def test_fused_lstm_step_backward(n, carried, f_y, dtype):
 
 
 @pytest.mark.parametrize("keep,fused", [(False, True), (True, True), (False, False)])
-@pytest.mark.parametrize("case", ["undirected_f32", "directed_f32", "undirected_bf16"])
+@pytest.mark.parametrize("case", ["undirected_f32", "directed_f32", "undirected_bf16", "undirected_f32_width16"])
 def test_cdgcn_training_step(case, keep, fused):
     """Gradients of sum_t <G_t, h_t> with respect to W, W_x, W_h and b over a block, against the oracle's backward
     pass (itself pinned by finite differences); the ReLU mask is taken on fp32 values on the device and fp64 in
@@ -265,9 +264,10 @@ def test_cdgcn_training_step(case, keep, fused):
     from paper_2109_07893_amd.cdgcn import CdgcnTrainer
     wl = {"undirected_f32": replace(WORKLOADS["c1"], f=32, window=0, name="cd-c1"),
           "directed_f32": replace(WORKLOADS["c3"].scaled(4096, T=5), name="cd-c3"),
-          "undirected_bf16": replace(WORKLOADS["c4"].scaled(3000, T=4), f=32, window=0, name="cd-c4")}[case]
+          "undirected_bf16": replace(WORKLOADS["c4"].scaled(3000, T=4), f=32, window=0, name="cd-c4"),
+          "undirected_f32_width16": replace(WORKLOADS["c1"], window=0, name="cd-c1-16")}[case]      # c1's own width
     dtype = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
-    f, hidden, T = wl.f, 32, wl.T
+    f, hidden, T = wl.f, (16 if case.endswith("width16") else 32), wl.T
     w = glorot_weight(wl, 0)
     w_x = (randn((2 * f, 4 * hidden), 11) / np.sqrt(2 * f)).to(dtype)
     w_h = (randn((hidden, 4 * hidden), 12) / np.sqrt(hidden)).to(dtype)
