@@ -185,8 +185,16 @@ __global__ __launch_bounds__(kThreads) void mproduct_shift_kernel(const char *z,
 // flight; whole rounds of W steps run without a bounds test, the remainder of the series with one.
 // REVERSE runs the adjoint, out_k = sum_{t=k}^{k+W-1} in_t / min(W, t): the time axis is walked from the end,
 // a frame enters the running sum already divided by its own min(W, t) and leaves it the same way.
+// Wavefronts per SIMD the compiler must leave room for.  Left to itself it spends 232 registers on the unrolled
+// round of a 16-frame window in bf16 (two wavefronts per SIMD: too few loads in flight for an in-place stream);
+// held to 168 (three per SIMD) it spills three values outside the loop and the in-place transform runs an eighth
+// faster.  Only where that is all it costs: the adjoint and windows beyond 23 frames would spill inside the loop,
+// fp32 and the shorter windows fit three wavefronts anyway.
+constexpr int uniform_waves_per_simd(int w, bool bf16, bool reverse) { return (bf16 && !reverse && w >= 12 && w <= 23) ? 3 : 1; }
+
 template <int W, bool BF16, bool REVERSE>
-__global__ __launch_bounds__(kThreads) void mproduct_uniform_kernel(const char *z, char *y, int T, int64_t pieces,
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(uniform_waves_per_simd(W, BF16, REVERSE))))
+void mproduct_uniform_kernel(const char *z, char *y, int T, int64_t pieces,
                                                                     int64_t frame_bytes, Halo halo) {
     constexpr int NV = Vec<BF16>::kVals;
     constexpr int D = W % 4 == 0 ? 4 : (W % 2 == 0 ? 2 : 1);     // divides W, so a frame's queue slot is i % D = jj % D
