@@ -423,11 +423,20 @@ def smoothing_steps(args, wl, blk, dev, life=4):
         runner.run_resident()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) / args.steps * 1e3
+    # the same pass with rebuild, sliding-window sum, normalisation and X W of the next snapshot on a second stream
+    runner.run_resident(overlap=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        runner.run_resident(overlap=True)
+    torch.cuda.synchronize()
+    ms_two = (time.perf_counter() - t0) / args.steps * 1e3
     runner.timer = StageTimer(dev)
     runner.run_resident()
     torch.cuda.synchronize()
     stored = runner.stored_entries()
-    out["forward_pass"] = {"ms_per_step": round(ms, 3), "snapshots_per_step": blk.T, "stored_entries_last": stored,
+    out["forward_pass"] = {"ms_per_step": round(ms, 3), "two_streams_ms_per_step": round(ms_two, 3),
+                           "snapshots_per_step": blk.T, "stored_entries_last": stored,
                            "stages": {k: {"calls_per_step": c, "avg_ms": round(t / c, 4)}
                                       for k, (c, t) in runner.timer.totals().items()},
                            "note": "every snapshot t = 1..T, including the copy of A_1 into the ring at the start of the pass"}

@@ -20,6 +20,8 @@ class CdgcnLayer(BlockRunner):
     """Reuses the runner's snapshot slots and rebuilds; `hidden` is the LSTM state width (4 * hidden and
     blk.f + f_out must be feature widths the dense transform takes)."""
 
+    two_stream_safe = False       # the layer's own pass is run(); its buffers do not alternate with t
+
     def __init__(self, blk: BlockInputs, w: torch.Tensor, w_x: torch.Tensor, w_h: torch.Tensor,
                  bias: Optional[torch.Tensor], hidden: int, fused: bool = True):
         super().__init__(blk, keep_all_z=False)

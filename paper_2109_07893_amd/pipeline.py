@@ -167,6 +167,10 @@ class BlockRunner:
             cur = dst
         return out
 
+    # A subclass whose snapshot_ready / transform_first / gcn keep to buffers that alternate with the parity of t (so
+    # that the work on snapshot t+1 on the second stream never touches what the aggregation of t reads) may say so.
+    two_stream_safe = True
+
     def begin_pass(self) -> None:
         """Called at the start of every pass (subclasses that overwrite A_1's slot reload it here)."""
 
@@ -200,15 +204,14 @@ class BlockRunner:
         self.mix()
 
     def _run_overlapped(self, first: int, validate: bool, on_snapshot, pinned: bool, prefetch_next: bool) -> None:
-        """The same pass on two streams: the rebuild of A_t and the first layer's X_t W run on a second stream, up to
-        one snapshot ahead of the aggregations on the current one.  The aggregation is held back by the rate at which
+        """The same pass on two streams: the rebuild of A_t, whatever a subclass does to A_t (snapshot_ready) and the
+        first layer's X_t W run on a second stream, up to one snapshot ahead of the aggregations on the current one.  The aggregation is held back by the rate at which
         L2 misses are served and leaves issue slots and HBM bandwidth unused, which the two streaming kernels of the
         next snapshot take.  Two H buffers alternate; A_t's slot and an H buffer are written again only after the
         aggregation that read them two snapshots earlier has finished (events both ways).  Results are those of the
         one-stream pass bit for bit: the same kernels on the same operands."""
         blk = self.blk
-        assert type(self).snapshot_ready is BlockRunner.snapshot_ready and type(self).begin_pass is BlockRunner.begin_pass, \
-            "subclasses that enqueue work of their own per snapshot run on one stream"
+        assert self.two_stream_safe, "this runner enqueues work per snapshot that the two-stream pass does not know about"
         if pinned:
             assert self.stage is not None
         main = torch.cuda.current_stream(self.dev)
@@ -216,6 +219,7 @@ class BlockRunner:
             self.prep_stream = torch.cuda.Stream(device=self.dev)
             self.h_pair = [self.h, torch.empty_like(self.h)]
         prep = self.prep_stream
+        self.begin_pass()                   # on the current stream, before the second one is let go
         ready = [torch.cuda.Event() for _ in range(blk.T + 1)]     # A_t, dinv_t and the first H of t are there
         done = [torch.cuda.Event() for _ in range(blk.T + 1)]      # everything that reads them has been enqueued and run
 
@@ -254,6 +258,7 @@ class BlockRunner:
                             self._first_lists_requested = True
                     else:
                         self.rebuild(t, blk.deltas[t - 2], validate)
+                self.snapshot_ready(t)      # a subclass's own work on A_t (it may use only what alternates with t)
                 if t >= first:
                     self.transform_first(t, self.h_pair[t % 2])
                 ready[t].record(prep)
@@ -355,7 +360,8 @@ class SmoothedRunner(BlockRunner):
                    torch.empty(self.cap_s, dtype=torch.float32, device=dev)) for _ in range(2)]
         self.s_nnz = 0
         self.cur = None                                 # (rowptr, colidx, val, nnz) of S_t
-        self.dinv_s = torch.empty(n, dtype=torch.float32, device=dev)
+        self.dinv_s_pair = [torch.empty(n, dtype=torch.float32, device=dev) for _ in range(2)]   # alternate with t, like S
+        self.dinv_s = self.dinv_s_pair[1]
         self.ws_combine = torch.empty(B.csr_combine_workspace(self.cap_s), dtype=torch.uint8, device=dev)
         self.ws_dinv = torch.empty(B.csr_weighted_dinv_workspace(self.cap_s), dtype=torch.uint8, device=dev)
         self.ws_spmm = torch.empty(B.spmm_workspace(n, self.cap_s, blk.f), dtype=torch.uint8, device=dev)
@@ -395,21 +401,29 @@ class SmoothedRunner(BlockRunner):
                               status=self.status_s[t:t + 1])
             # the number of stored entries stays on the device (out[0][n]); the capacity serves as the upper bound
             self.cur = (out[0], out[1], out[2], self.cap_s)
+        self.dinv_s = self.dinv_s_pair[t % 2]
         with self._stage("csr_weighted_dinv"):
             B.csr_weighted_dinv(self.cur[0], self.cur[2], self.cur[3], self.dinv_s, self.ws_dinv)
 
-    def gcn(self, t: int) -> torch.Tensor:
+    def transform_first(self, t: int, h: torch.Tensor) -> None:
+        with self._stage("feature_transform"):
+            B.feature_transform(self.blk.x[t - 1], self.blk.weight(t, 0), h, row_scale=self.dinv_s_pair[t % 2])
+
+    def gcn(self, t: int, h_first: Optional[torch.Tensor] = None) -> torch.Tensor:
         blk = self.blk
-        rp, ci, val, nnz = self.cur
+        rp, ci, val, nnz = self.cur                      # S_t as of now: the host enqueues snapshot by snapshot
+        dinv_s = self.dinv_s_pair[t % 2]
         out = self.z[t - 1] if self.keep_all_z else self.z[0]
+        h = self.h if h_first is None else h_first
         cur = blk.x[t - 1]
         for layer in range(blk.layers):
-            with self._stage("feature_transform"):
-                B.feature_transform(cur, blk.weight(t, layer), self.h, row_scale=self.dinv_s)
+            if layer > 0 or h_first is None:
+                with self._stage("feature_transform"):
+                    B.feature_transform(cur, blk.weight(t, layer), h, row_scale=dinv_s)
             dst = out if layer == blk.layers - 1 else self.z_mid
             with self._stage("spmm_weighted"):
-                B.spmm_weighted(rp, ci, val, nnz, self.h, dst, self.ws_spmm, flags=B.DGNN_RELU | B.DGNN_H_PRESCALED,
-                                dinv=self.dinv_s)
+                B.spmm_weighted(rp, ci, val, nnz, h, dst, self.ws_spmm, flags=B.DGNN_RELU | B.DGNN_H_PRESCALED,
+                                dinv=dinv_s)
             cur = dst
         return out
 

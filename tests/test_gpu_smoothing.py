@@ -356,6 +356,47 @@ def test_smoothed_forward_with_lists_from_pinned_host_memory():
         assert torch.equal(a.z, b.z)
 
 
+@pytest.mark.parametrize("name,n,T,life", [("c5", 1 << 13, 9, 3), ("c2", 20_000, 6, 2), ("c3", 1 << 13, 7, 4), ("c4", 10_000, 12, 4)])
+def test_smoothed_pass_on_two_streams_equals_the_pass_on_one(name, n, T, life):
+    """overlap=True: rebuild, sliding-window sum, normalisation and X W of snapshot t+1 on a second stream beside the
+    aggregation of snapshot t (S, its normalisation and H alternate with t).  Frames and the last smoothed snapshot
+    must be those of the one-stream pass bit for bit: resident lists and pinned ones, passes back to back, and a
+    one-stream pass in between."""
+    from dtdg_synth.blocks import make_block
+    from paper_2109_07893_amd.pipeline import SmoothedRunner
+    wl = WORKLOADS[name].scaled(n, T=T)
+    a = SmoothedRunner(make_block(wl, DEV, gen_device="cpu"), life=life, keep_all_z=True)
+    a.run_resident()
+    torch.cuda.synchronize()
+    nnz = a.stored_entries()
+    want_s = [x[:nnz].clone() if i else x.clone() for i, x in enumerate(a.cur[:3])]
+    b = SmoothedRunner(make_block(wl, DEV, gen_device="cpu", pinned=True), life=life, keep_all_z=True)
+
+    def same(what):
+        torch.cuda.synchronize()
+        assert int(b.status.abs().sum()) == 0 and int(b.status_s.abs().sum()) == 0
+        assert torch.equal(a.z, b.z), what
+        assert b.stored_entries() == nnz, what
+        for i, (w, g) in enumerate(zip(want_s, b.cur[:3])):
+            assert torch.equal(w, g[:nnz] if i else g), what
+        b.z.fill_(float("nan"))
+
+    b.run_resident(overlap=True)
+    same("resident lists")
+    b.run_resident(overlap=True)
+    b.run_resident(overlap=True)
+    same("two passes back to back")
+    b.run_from_pinned(overlap=True)
+    same("pinned lists")
+    b.run_from_pinned(prefetch_next=True, overlap=True)
+    b.run_from_pinned(prefetch_next=True, overlap=True)
+    same("pinned lists requested ahead")
+    b.run_from_pinned()
+    same("one-stream pass after two-stream passes")
+    b.run_resident(overlap=True)
+    same("and a two-stream pass again")
+
+
 def test_smoothed_pass_as_a_hip_graph_repeats_the_eager_result():
     """Every call of the smoothed pass only enqueues (the sliding-window sum leaves its size on the device), so the
     pass can be recorded as a HIP graph: replayed several times with eager passes and synchronisations in between,
